@@ -1,0 +1,152 @@
+/*
+ * rans_if.h -- C ABI of the MI355X rANS intermediate-feature codec.
+ *
+ * The library implements the compression pipeline of the paper's Sec. 3.1
+ * (Fig. 1(c)): reshape (Eq. 5) -> asymmetric integer quantisation (Eq. 6) ->
+ * modified CSR (v, c, r) -> concatenation D = v (+) c (+) r (Eq. 7) -> one
+ * frequency table -> rANS (Sec. 2.1, Eq. 2-4), and its inverse.  Everything
+ * runs in HIP kernels on one gfx950 device; there is no CPU fallback.
+ *
+ * Conventions
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; h_* are host
+ *     pointers.  The library allocates and frees nothing and keeps no state
+ *     between calls: scratch lives in the caller's workspace d_ws, whose size
+ *     rans_workspace_bytes() returns.  d_ws must be 256-byte aligned, d_stream
+ *     16-byte aligned, tensors aligned to their element size.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it; calls return without synchronising unless
+ *     stated otherwise.
+ *   - Return value: RANS_OK or a negative RANS_ERR_*.  Errors that depend only
+ *     on the arguments are detected on the host before any launch.  Errors
+ *     that depend on the data (non-finite input, too many distinct symbols,
+ *     output capacity, corrupt container) are recorded in the workspace; the
+ *     kernels then stop producing output, and rans_last_status() reports the
+ *     first such error.  No call aborts or throws.
+ *   - Limits: n_elems <= 2^30; 1 <= Q <= 8; 1 <= M <= 15; 1 <= S <= 65536;
+ *     CSR mode needs cols <= 65535.
+ */
+#ifndef RANS_IF_H
+#define RANS_IF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  RANS_OK = 0,
+  RANS_ERR_ARG = -1,       /* null/misaligned pointer, parameter out of range           */
+  RANS_ERR_SHAPE = -2,     /* rows*cols != n_elems, chunk_syms not a multiple of S      */
+  RANS_ERR_ALPHABET = -3,  /* more distinct symbols than 2^M, or CSR with cols > 65535  */
+  RANS_ERR_CAPACITY = -4,  /* output buffer too small                                   */
+  RANS_ERR_WORKSPACE = -5, /* ws_bytes smaller than rans_workspace_bytes() reports      */
+  RANS_ERR_NONFINITE = -6, /* NaN/Inf in the tensor, or x_max - x_min overflows         */
+  RANS_ERR_CORRUPT = -7,   /* container fails validation                                */
+  RANS_ERR_HIP = -8        /* a HIP runtime call failed                                 */
+};
+
+enum { RANS_MODE_DENSE = 0, RANS_MODE_CSR = 1 };
+enum { RANS_F32 = 0, RANS_F16 = 1 };
+
+/* The paper's statement of the problem: bit width Q (Eq. 6), coding precision
+ * n (Eq. 2-4, called M here), reshape N x K (Eq. 5).  mode selects what is
+ * coded: the paper's D = v (+) c (+) r (CSR), or the quantised tensor itself
+ * (DENSE, for activations without exact zeros).  n_streams / chunk_syms shape
+ * the parallel coder: D is cut into chunks of chunk_syms symbols, and inside a
+ * chunk symbol i belongs to stream i mod n_streams; every stream is an
+ * independent rANS coder sharing the one frequency table. */
+typedef struct {
+  uint32_t q_bits;     /* Q, 1..8                                          */
+  uint32_t freq_bits;  /* M, 1..15                                         */
+  uint64_t rows, cols; /* N, K with rows * cols == n_elems, cols >= 1      */
+  uint32_t mode;       /* RANS_MODE_*                                      */
+  uint32_t n_streams;  /* S >= 1                                           */
+  uint32_t chunk_syms; /* multiple of S; 0 = all of D in one chunk         */
+  uint32_t in_dtype;   /* RANS_F32 / RANS_F16: element type of the tensor  */
+} rans_params;
+
+/* Eq. 6: extrema, scale s and zero point z (an integer-valued float). */
+typedef struct {
+  float x_min, x_max, scale, zero_point;
+} rans_qinfo;
+
+/* Fixed part of a container, as rans_peek_header() reads it. */
+typedef struct {
+  rans_params p;
+  uint64_t n_elems;  /* T                                    */
+  uint64_t len_d;    /* number of coded symbols, l_D of Eq. 7 */
+  uint32_t alphabet; /* max(2^Q, K+1) in CSR mode, else 2^Q  */
+  uint32_t n_chunks;
+  float x_min, x_max;
+} rans_header;
+
+/* Size of the workspace every entry point below needs for these parameters,
+ * and an upper bound of the container size (either output may be NULL). Host only. */
+int rans_workspace_bytes(const rans_params *p, uint64_t n_elems, size_t *ws_bytes,
+                         size_t *max_stream_bytes);
+
+/* Eq. 6 over the whole tensor: global min/max, scale, zero point, then
+ * xhat = clamp(round_half_even(x / s + z), 0, 2^Q - 1) in binary32 without FMA.
+ * d_x: n_elems elements of p->in_dtype.  d_sym: n_elems bytes out.
+ * d_qinfo: one rans_qinfo out (device).  A constant tensor gives s = 0 and all
+ * symbols 0.  Data errors: RANS_ERR_NONFINITE. */
+int rans_quantize(const void *d_x, uint64_t n_elems, const rans_params *p, uint8_t *d_sym,
+                  rans_qinfo *d_qinfo, void *d_ws, size_t ws_bytes, void *stream);
+
+/* Sec. 3.1 "Modified CSR Encoding", "Concatenation and rANS Encoding", and
+ * Sec. 2.1 Eq. 2 with renormalisation: symbols -> container.
+ * d_sym: n_elems quantised symbols (< 2^Q).  d_qinfo: the extrema that go into
+ * the header (device).  d_stream / stream_cap: output buffer; the number of
+ * bytes written goes to *d_stream_bytes (device, 8-byte aligned; 0 on a data
+ * error).  Data errors: RANS_ERR_ALPHABET, RANS_ERR_CAPACITY. */
+int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p,
+                const rans_qinfo *d_qinfo, uint8_t *d_stream, size_t stream_cap,
+                uint64_t *d_stream_bytes, void *d_ws, size_t ws_bytes, void *stream);
+
+/* Sec. 2.1 Eq. 3-4 and the decoder side of the modified CSR (cumulative sum of
+ * r, scatter of v): container -> symbols.
+ * h_hdr: the container's header as rans_peek_header() returned it; it sizes the
+ * launches and is checked against the bytes on the device.  If NULL the library
+ * copies the 128-byte header to the host itself, which SYNCHRONISES the stream.
+ * d_sym / sym_cap: n_elems symbols out.  d_qinfo: nullable, receives the
+ * quantiser parameters recomputed from the header.  Every field, table, offset
+ * and final coder state is validated; nothing is read or written out of bounds
+ * for any input bytes.  Data errors: RANS_ERR_CORRUPT. */
+int rans_decode(const uint8_t *d_stream, size_t stream_bytes, const rans_header *h_hdr,
+                uint8_t *d_sym, uint64_t sym_cap, rans_qinfo *d_qinfo, void *d_ws,
+                size_t ws_bytes, void *stream);
+
+/* Inverse of Eq. 6: x = s * (xhat - z), one subtraction and one multiplication
+ * in binary32 without FMA; out_dtype RANS_F16 narrows with round-half-even.
+ * s = 0 (constant tensor) yields x_min everywhere. */
+int rans_dequantize(const uint8_t *d_sym, uint64_t n_elems, const rans_qinfo *d_qinfo,
+                    uint32_t out_dtype, void *d_x_out, void *stream);
+
+/* Fig. 1(c) end to end: tensor -> container.  Same bytes as rans_quantize
+ * followed by rans_encode. */
+int rans_compress(const void *d_x, uint64_t n_elems, const rans_params *p, uint8_t *d_stream,
+                  size_t stream_cap, uint64_t *d_stream_bytes, void *d_ws, size_t ws_bytes,
+                  void *stream);
+
+/* container -> tensor of out_dtype (elem_cap elements available at d_x_out).
+ * Same values as rans_decode followed by rans_dequantize. */
+int rans_decompress(const uint8_t *d_stream, size_t stream_bytes, const rans_header *h_hdr,
+                    uint32_t out_dtype, void *d_x_out, uint64_t elem_cap, void *d_ws,
+                    size_t ws_bytes, void *stream);
+
+/* Parse the fixed 128-byte header on the host.  h_bytes: at least 128 bytes.
+ * RANS_ERR_CORRUPT if the fields are not a valid header. */
+int rans_peek_header(const void *h_bytes, size_t n_bytes, rans_header *out);
+
+/* First data-dependent error recorded in the workspace by the calls enqueued
+ * so far (RANS_OK if none).  Synchronises `stream`. */
+int rans_last_status(const void *d_ws, void *stream);
+
+const char *rans_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

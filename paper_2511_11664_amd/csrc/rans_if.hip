@@ -1,0 +1,1536 @@
+// rans_if.hip -- HIP kernels (gfx950) and the C ABI of include/rans_if.h.
+//
+// Pipeline (paper Sec. 3.1, Fig. 1(c)):  min/max -> quantise (Eq. 6) + histogram ->
+// [modified CSR: count, scan, compact (v, c), row counts r] -> normalise to 2^M ->
+// interleaved rANS encode (Eq. 2) -> container.   Decoding runs the inverse
+// (Eq. 3-4, cumulative sum of r, scatter, dequantise).
+//
+// Everything is integer / binary32 work bound by HBM traffic and plain VALU + LDS
+// throughput; nothing is a dense contraction, so there is no MFMA code here.
+//
+// Compile: hipcc -O3 --offload-arch=gfx950 -ffp-contract=off (no fast-math): the
+// quantiser's x / s must be the correctly rounded binary32 quotient and no product
+// and sum may be fused, or symbols would differ from a CPU evaluation of Eq. 6.
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include <cmath>
+#include <cstring>
+
+#include "rans_if.h"
+
+namespace {
+
+constexpr uint32_t kL = 1u << 16;       // lower bound of the coder state interval [2^16, 2^32)
+constexpr int kWG = 256;                // threads per work-group of the streaming kernels
+constexpr int kBig = 1024;              // threads of the single-work-group kernels
+constexpr uint32_t kHdrBytes = 128;
+constexpr uint32_t kLdsHistMaxA = 8192; // alphabets up to this size keep histograms / tables in LDS
+constexpr uint64_t kMaxElems = 1ull << 30;
+
+// ------------------------------------------------------------------ workspace
+
+// Control block at the start of the workspace (device side).
+struct Ctl {
+  int32_t status;                        // first data-dependent error of the current call
+  uint32_t min_key, max_key, nonfinite;  // min/max as order-preserving integer keys
+  float x_min, x_max, scale, zero_point; // Eq. 6
+  uint64_t len_d;                        // l_D of Eq. 7
+  uint64_t payload_off, dir_off;         // container section offsets
+  uint64_t total_bytes;
+  uint32_t nnz, n_chunks;
+  uint32_t pad[46];
+};
+static_assert(sizeof(Ctl) == 256, "control block is 256 bytes");
+
+struct Layout {
+  // common
+  size_t ctl;
+  // encode side
+  size_t cnt, fq, enc_tab, sym, v, c, r, row_end, blk_nnz, st, nw, chunk_words, scratch;
+  // decode side (overlays the encode side from `sym` on)
+  size_t dec_lut, dec_tab, dec_F, D, row_off, dec_sym;
+  size_t total;
+  uint32_t A, nc_max, capw, n_blk;
+  uint64_t len_max, chunk_len_max;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline uint32_t alphabet_of(const rans_params &p) {
+  uint32_t a = 1u << p.q_bits;
+  if (p.mode == RANS_MODE_CSR && p.cols + 1 > a) a = (uint32_t)(p.cols + 1);
+  return a;
+}
+
+inline uint64_t n_chunks_of(uint64_t len, uint32_t cs) {
+  if (len == 0) return 0;
+  if (cs == 0) return 1;
+  return (len + cs - 1) / cs;
+}
+
+int check_params(const rans_params *p, uint64_t n) {
+  if (!p) return RANS_ERR_ARG;
+  if (p->q_bits < 1 || p->q_bits > 8 || p->freq_bits < 1 || p->freq_bits > 15) return RANS_ERR_ARG;
+  if (p->mode > RANS_MODE_CSR || p->in_dtype > RANS_F16) return RANS_ERR_ARG;
+  if (p->n_streams < 1 || p->n_streams > 65536) return RANS_ERR_ARG;
+  if (n > kMaxElems) return RANS_ERR_ARG;
+  if (p->cols < 1) return RANS_ERR_SHAPE;
+  if (p->rows != n / p->cols || p->rows * p->cols != n) return RANS_ERR_SHAPE;
+  if (p->chunk_syms % p->n_streams != 0) return RANS_ERR_SHAPE;
+  if (p->mode == RANS_MODE_CSR && p->cols + 1 > 65536) return RANS_ERR_ALPHABET;
+  return RANS_OK;
+}
+
+constexpr uint32_t kCsrTile = kWG * 16;  // elements per work-group in the CSR count / compact kernels
+
+Layout make_layout(const rans_params &p, uint64_t n) {
+  Layout L{};
+  L.A = alphabet_of(p);
+  L.len_max = p.mode == RANS_MODE_CSR ? 2 * n + p.rows : n;
+  L.nc_max = (uint32_t)n_chunks_of(L.len_max, p.chunk_syms);
+  L.chunk_len_max = p.chunk_syms ? p.chunk_syms : L.len_max;
+  uint64_t per_stream = (L.chunk_len_max + p.n_streams - 1) / p.n_streams;
+  L.capw = (uint32_t)align_up((size_t)per_stream, 4);
+  L.n_blk = (uint32_t)((n + kCsrTile - 1) / kCsrTile);
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = o;
+    o = align_up(o + bytes, 256);
+    return at;
+  };
+  L.ctl = take(sizeof(Ctl));
+  L.cnt = take((size_t)L.A * 4);
+  L.fq = take((size_t)L.A * 4);
+  L.enc_tab = take((size_t)L.A * 8);
+  size_t overlay = o;
+  L.sym = take(n);
+  if (p.mode == RANS_MODE_CSR) {
+    L.v = take(n);
+    L.c = take(n * 2);
+    L.r = take(p.rows * 2);
+    L.row_end = take(p.rows * 4);
+    L.blk_nnz = take(((size_t)L.n_blk + 1) * 4);
+  }
+  size_t n_sc = (size_t)L.nc_max * p.n_streams;
+  L.st = take(n_sc * 4);
+  L.nw = take(n_sc * 4);
+  L.chunk_words = take(((size_t)L.nc_max + 1) * 4);
+  L.scratch = take(n_sc * L.capw * 2);
+  size_t enc_end = o;
+  o = overlay;
+  L.dec_lut = take(((size_t)2 << p.freq_bits));
+  L.dec_tab = take((size_t)L.A * 4);
+  L.dec_F = take(((size_t)L.A + 1) * 4);
+  if (p.mode == RANS_MODE_CSR) {
+    L.D = take(L.len_max * 2);
+    L.row_off = take((p.rows + 1) * 4);
+    L.dec_sym = take(n);
+  }
+  size_t dec_end = o;
+  L.total = enc_end > dec_end ? enc_end : dec_end;
+  return L;
+}
+
+size_t stream_bound(const rans_params &p, const Layout &L) {
+  size_t b = kHdrBytes + align_up((size_t)L.A * 2, 8) + 8 * ((size_t)L.nc_max + 1);
+  b += (size_t)L.nc_max * (8 * (size_t)p.n_streams + 4) + 2 * (size_t)L.len_max;
+  return b;
+}
+
+// ------------------------------------------------------------------ device helpers
+
+__device__ __forceinline__ void set_status(Ctl *ctl, int code) { atomicCAS(&ctl->status, 0, code); }
+
+__device__ __forceinline__ uint32_t f2key(float v) {
+  uint32_t b = __float_as_uint(v);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key2f(uint32_t k) {
+  uint32_t b = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+  return __uint_as_float(b);
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+  return v;
+}
+
+__device__ __forceinline__ uint64_t shfl_xor64(uint64_t v, int d) {
+  uint32_t lo = __shfl_xor((uint32_t)v, d), hi = __shfl_xor((uint32_t)(v >> 32), d);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// Sum / max over a work-group of NT threads; every thread receives the result.
+template <int NT>
+__device__ uint64_t block_sum64(uint64_t v, uint64_t *sh /* NT/64 entries */) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += shfl_xor64(v, d);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  uint64_t t = 0;
+#pragma unroll
+  for (int w = 0; w < NT / 64; w++) t += sh[w];
+  return t;
+}
+template <int NT>
+__device__ uint64_t block_max64(uint64_t v, uint64_t *sh) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    uint64_t o = shfl_xor64(v, d);
+    v = o > v ? o : v;
+  }
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  uint64_t t = 0;
+#pragma unroll
+  for (int w = 0; w < NT / 64; w++) t = sh[w] > t ? sh[w] : t;
+  return t;
+}
+
+// Exclusive prefix sum over a work-group of NT threads; *total receives the sum.
+template <int NT>
+__device__ uint32_t block_excl_scan(uint32_t v, uint32_t *sh /* NT/64 entries */, uint32_t *total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  uint32_t inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    uint32_t o = __shfl_up(inc, d);
+    if (lane >= d) inc += o;
+  }
+  __syncthreads();
+  if (lane == 63) sh[w] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < NT / 64; i++) {
+    uint32_t s = sh[i];
+    if (i < w) base += s;
+    tot += s;
+  }
+  *total = tot;
+  return base + inc - v;
+}
+
+__device__ __forceinline__ float half_bits_to_float(uint16_t h) {
+  return __half2float(__ushort_as_half(h));
+}
+
+// Eq. 6 for one element, in binary32: correctly rounded quotient, one addition,
+// round half to even, clamp to [0, 2^Q - 1].
+__device__ __forceinline__ uint32_t quant1(float x, float s, float zf, float levels) {
+  float t = x / s;
+  float u = t + zf;
+  float r = rintf(u);
+  r = fminf(fmaxf(r, 0.0f), levels);
+  return (uint32_t)r;
+}
+
+// ------------------------------------------------------------------ kernels: set-up
+
+__global__ void k_init(Ctl *ctl, uint32_t *cnt, uint32_t A, uint32_t *chunk_words, uint32_t nc) {
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
+  if (i == 0) {
+    ctl->status = 0;
+    ctl->min_key = 0xffffffffu;
+    ctl->max_key = 0u;
+    ctl->nonfinite = 0;
+    ctl->len_d = 0;
+    ctl->payload_off = ctl->dir_off = ctl->total_bytes = 0;
+    ctl->nnz = 0;
+    ctl->n_chunks = 0;
+  }
+  for (uint32_t a = i; a < A; a += stride) cnt[a] = 0;
+  for (uint32_t k = i; k <= nc; k += stride) chunk_words[k] = 0;
+}
+
+template <typename T>
+__global__ void k_fill(T *p, uint64_t n, T val) {
+  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (uint64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = val;
+}
+
+// ------------------------------------------------------------------ kernels: Eq. 6
+
+// Global extrema.  Each lane keeps a running min / max over 16-byte vector loads,
+// the wave folds them with cross-lane shuffles, and one lane per wave issues a pair
+// of integer atomics on order-preserving keys.
+template <typename T, bool VEC>
+__global__ __launch_bounds__(kWG) void k_minmax(const T *x, uint32_t n, Ctl *ctl) {
+  constexpr int V = VEC ? (int)(16 / sizeof(T)) : 1;
+  float mn = INFINITY, mx = -INFINITY;
+  uint32_t bad = 0;
+  auto take = [&](float v) {
+    bad |= ((__float_as_uint(v) & 0x7fffffffu) >= 0x7f800000u);
+    mn = fminf(mn, v);
+    mx = fmaxf(mx, v);
+  };
+  uint32_t nvec = n / V;
+  uint32_t stride = gridDim.x * blockDim.x;
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
+    if constexpr (!VEC) {
+      if constexpr (sizeof(T) == 4) take(x[i]);
+      else take(half_bits_to_float(((const uint16_t *)x)[i]));
+    } else if constexpr (sizeof(T) == 4) {
+      float4 q = ((const float4 *)x)[i];
+      take(q.x); take(q.y); take(q.z); take(q.w);
+    } else {
+      uint4 q = ((const uint4 *)x)[i];
+      uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+      for (int k = 0; k < 4; k++) {
+        take(half_bits_to_float((uint16_t)(w[k] & 0xffffu)));
+        take(half_bits_to_float((uint16_t)(w[k] >> 16)));
+      }
+    }
+  }
+  if constexpr (VEC) {  // ragged tail
+    uint32_t i = nvec * V + blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+      if constexpr (sizeof(T) == 4) take(((const float *)x)[i]);
+      else take(half_bits_to_float(((const uint16_t *)x)[i]));
+    }
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    mn = fminf(mn, __shfl_xor(mn, d));
+    mx = fmaxf(mx, __shfl_xor(mx, d));
+    bad |= __shfl_xor(bad, d);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    if (bad) atomicOr(&ctl->nonfinite, 1u);
+    if (mn <= mx) {  // false only when the lane group saw no element
+      atomicMin(&ctl->min_key, f2key(mn));
+      atomicMax(&ctl->max_key, f2key(mx));
+    }
+  }
+}
+
+// Scale and zero point from the extrema (Eq. 6), one thread.
+__global__ void k_qinfo(Ctl *ctl, uint32_t q_bits, uint32_t n, rans_qinfo *out) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  float mn = 0.0f, mx = 0.0f;
+  if (n) {
+    mn = key2f(ctl->min_key) + 0.0f;  // -0.0 becomes +0.0
+    mx = key2f(ctl->max_key) + 0.0f;
+  }
+  float range = mx - mn;
+  float levels = (float)((1u << q_bits) - 1u);
+  float s = range / levels;
+  float zf = 0.0f;
+  if (s != 0.0f) {
+    float neg_min = 0.0f - mn;
+    zf = rintf(neg_min / s);
+  }
+  bool bad = ctl->nonfinite || !(fabsf(range) < INFINITY);
+  if (bad) {
+    set_status(ctl, RANS_ERR_NONFINITE);
+    mn = mx = s = zf = __uint_as_float(0x7fc00000u);
+  }
+  ctl->x_min = mn;
+  ctl->x_max = mx;
+  ctl->scale = s;
+  ctl->zero_point = zf;
+  if (out) {
+    out->x_min = mn;
+    out->x_max = mx;
+    out->scale = s;
+    out->zero_point = zf;
+  }
+}
+
+// Copies caller-provided extrema into the control block (rans_encode path) and
+// recomputes s, z from them with the arithmetic of k_qinfo.
+__global__ void k_qinfo_from_user(Ctl *ctl, const rans_qinfo *in, uint32_t q_bits) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  float mn = in->x_min, mx = in->x_max;
+  float range = mx - mn;
+  bool bad = !(fabsf(mn) < INFINITY) || !(fabsf(mx) < INFINITY) || !(fabsf(range) < INFINITY) || mn > mx;
+  if (bad) set_status(ctl, RANS_ERR_NONFINITE);
+  float levels = (float)((1u << q_bits) - 1u);
+  float s = range / levels;
+  float zf = 0.0f;
+  if (s != 0.0f) zf = rintf((0.0f - mn) / s);
+  ctl->x_min = mn + 0.0f;
+  ctl->x_max = mx + 0.0f;
+  ctl->scale = s;
+  ctl->zero_point = zf;
+}
+
+// Quantise a tile and histogram its symbols.  T = float / __half: Eq. 6 per
+// element, symbols written packed; T = uint8_t: symbols are the input (histogram
+// only).  The LDS histogram is replicated 8 ways (bin * 8 + lane % 8) so that the
+// few hot symbols of an activation tensor do not serialise the whole wave on one
+// LDS address.
+constexpr int kHistRep = 8;
+constexpr int kQIter = 4;
+
+template <typename T, bool VEC>
+__global__ __launch_bounds__(kWG) void k_quant_hist(const T *x, uint32_t n, Ctl *ctl, uint32_t q_bits,
+                                                    uint8_t *sym, uint32_t *cnt, int skip_zero_bin) {
+  constexpr bool IS_SYM = sizeof(T) == 1;
+  constexpr int V = VEC ? (int)(16 / sizeof(T)) : 1;
+  __shared__ uint32_t h[256 * kHistRep];
+  for (int i = threadIdx.x; i < 256 * kHistRep; i += kWG) h[i] = 0;
+  __syncthreads();
+  const float s = ctl->scale, zf = ctl->zero_point;
+  const float levels = (float)((1u << q_bits) - 1u);
+  const bool degenerate = !IS_SYM && !(s != 0.0f);  // s == 0 (constant tensor) or NaN (flagged input)
+  const uint32_t rep = threadIdx.x & (kHistRep - 1);
+  const uint32_t tile = kWG * V * kQIter;
+  const uint64_t base = (uint64_t)blockIdx.x * tile;
+  auto q = [&](float v) -> uint32_t { return degenerate ? 0u : quant1(v, s, zf, levels); };
+  auto bump = [&](uint32_t a) { atomicAdd(&h[a * kHistRep + rep], 1u); };
+#pragma unroll
+  for (int it = 0; it < kQIter; it++) {
+    uint64_t e0 = base + ((uint64_t)it * kWG + threadIdx.x) * V;
+    if (e0 >= n) break;
+    if (VEC && e0 + V <= n) {
+      if constexpr (IS_SYM) {
+        uint4 w = *(const uint4 *)((const uint8_t *)x + e0);
+        uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+          bump(ww[k] & 0xffu); bump((ww[k] >> 8) & 0xffu); bump((ww[k] >> 16) & 0xffu); bump(ww[k] >> 24);
+        }
+      } else if constexpr (sizeof(T) == 4) {
+        float4 f = *(const float4 *)((const float *)x + e0);
+        uint32_t a0 = q(f.x), a1 = q(f.y), a2 = q(f.z), a3 = q(f.w);
+        bump(a0); bump(a1); bump(a2); bump(a3);
+        *(uint32_t *)(sym + e0) = a0 | (a1 << 8) | (a2 << 16) | (a3 << 24);
+      } else {
+        uint4 w = *(const uint4 *)((const uint16_t *)x + e0);
+        uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+        uint32_t a[8];
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+          a[2 * k] = q(half_bits_to_float((uint16_t)(ww[k] & 0xffffu)));
+          a[2 * k + 1] = q(half_bits_to_float((uint16_t)(ww[k] >> 16)));
+        }
+#pragma unroll
+        for (int k = 0; k < 8; k++) bump(a[k]);
+        uint2 o;
+        o.x = a[0] | (a[1] << 8) | (a[2] << 16) | (a[3] << 24);
+        o.y = a[4] | (a[5] << 8) | (a[6] << 16) | (a[7] << 24);
+        *(uint2 *)(sym + e0) = o;
+      }
+    } else {  // scalar path: unaligned buffers, or the last partial vector
+      for (int k = 0; k < V && e0 + k < n; k++) {
+        uint32_t a;
+        if constexpr (IS_SYM) a = ((const uint8_t *)x)[e0 + k];
+        else if constexpr (sizeof(T) == 4) a = q(((const float *)x)[e0 + k]);
+        else a = q(half_bits_to_float(((const uint16_t *)x)[e0 + k]));
+        bump(a);
+        if constexpr (!IS_SYM) sym[e0 + k] = (uint8_t)a;
+      }
+    }
+  }
+  __syncthreads();
+  for (int a = threadIdx.x; a < 256; a += kWG) {
+    uint32_t t = 0;
+#pragma unroll
+    for (int r = 0; r < kHistRep; r++) t += h[a * kHistRep + r];
+    if (!t) continue;
+    if (a >= (1 << q_bits)) set_status(ctl, RANS_ERR_ARG);  // caller-provided symbol outside {0..2^Q-1}
+    else if (!(skip_zero_bin && a == 0)) atomicAdd(&cnt[a], t);
+  }
+}
+
+// ------------------------------------------------------------------ kernels: modified CSR
+
+__device__ __forceinline__ void load16(const uint8_t *p, uint64_t e0, uint64_t n, bool aligned, uint8_t out[16]) {
+  if (aligned && e0 + 16 <= n) {
+    uint4 w = *(const uint4 *)(p + e0);
+    uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int k = 0; k < 16; k++) out[k] = (uint8_t)(ww[k >> 2] >> (8 * (k & 3)));
+  } else {
+#pragma unroll
+    for (int k = 0; k < 16; k++) out[k] = (e0 + k < n) ? p[e0 + k] : (uint8_t)0;
+  }
+}
+
+// Number of nonzero symbols per tile of kCsrTile elements.
+__global__ __launch_bounds__(kWG) void k_csr_count(const uint8_t *sym, uint32_t n, int aligned, uint32_t *blk_nnz) {
+  __shared__ uint32_t sh[kWG / 64];
+  uint64_t e0 = (uint64_t)blockIdx.x * kCsrTile + threadIdx.x * 16;
+  uint8_t b[16];
+  load16(sym, e0, n, aligned, b);
+  uint32_t c = 0;
+#pragma unroll
+  for (int k = 0; k < 16; k++) c += b[k] != 0;
+  uint32_t tot;
+  (void)block_excl_scan<kWG>(c, sh, &tot);
+  if (threadIdx.x == 0) blk_nnz[blockIdx.x] = tot;
+}
+
+// In-place exclusive scan of a u32 array by one work-group; the total goes to a[n].
+__global__ __launch_bounds__(kBig) void k_scan_u32(uint32_t *a, uint32_t n) {
+  __shared__ uint32_t sh[kBig / 64];
+  uint32_t carry = 0;
+  for (uint32_t base = 0; base < n; base += kBig) {
+    uint32_t i = base + threadIdx.x;
+    uint32_t v = i < n ? a[i] : 0, tot;
+    uint32_t ex = block_excl_scan<kBig>(v, sh, &tot);
+    if (i < n) a[i] = carry + ex;
+    carry += tot;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) a[n] = carry;
+}
+
+// Stream compaction of the nonzero symbols in flat (= row-major) order: v gets the
+// values, c the column indices, row_end[i] the number of nonzeros up to and
+// including row i.  Column indices are histogrammed into cnt on the way.
+template <bool LDS_HIST>
+__global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_t n, int aligned, uint32_t K,
+                                                     const uint32_t *blk_off, uint8_t *v, uint16_t *c,
+                                                     uint32_t *row_end, uint32_t *cnt, uint32_t A) {
+  extern __shared__ uint32_t hist[];
+  __shared__ uint32_t sh[kWG / 64];
+  if (LDS_HIST) {
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) hist[a] = 0;
+  }
+  uint64_t e0 = (uint64_t)blockIdx.x * kCsrTile + threadIdx.x * 16;
+  uint8_t b[16];
+  load16(sym, e0, n, aligned, b);
+  uint32_t cth = 0;
+#pragma unroll
+  for (int k = 0; k < 16; k++) cth += b[k] != 0;
+  uint32_t tot;
+  uint32_t off = blk_off[blockIdx.x] + block_excl_scan<kWG>(cth, sh, &tot);  // also orders the hist zeroing
+  if (e0 < n) {
+    uint32_t row = (uint32_t)(e0 / K), col = (uint32_t)(e0 - (uint64_t)row * K);
+#pragma unroll
+    for (int k = 0; k < 16; k++) {
+      if (e0 + k < n) {
+        if (b[k]) {
+          v[off] = b[k];
+          c[off] = (uint16_t)col;
+          off++;
+          if (LDS_HIST) atomicAdd(&hist[col], 1u);
+          else atomicAdd(&cnt[col], 1u);
+        }
+        if (++col == K) {
+          row_end[row] = off;
+          col = 0;
+          row++;
+        }
+      }
+    }
+  }
+  if (LDS_HIST) {
+    __syncthreads();
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) {
+      uint32_t t = hist[a];
+      if (t) atomicAdd(&cnt[a], t);
+    }
+  }
+}
+
+// r[i] = row_end[i] - row_end[i-1] (the NON-cumulative row count), histogrammed.
+template <bool LDS_HIST>
+__global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint32_t N, uint16_t *r, uint32_t *cnt,
+                                                  uint32_t A, Ctl *ctl) {
+  extern __shared__ uint32_t hist[];
+  if (LDS_HIST) {
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) hist[a] = 0;
+    __syncthreads();
+  }
+  uint32_t i = blockIdx.x * kWG + threadIdx.x;
+  if (i < N) {
+    uint32_t e1 = row_end[i], e0 = i ? row_end[i - 1] : 0;
+    uint32_t ri = e1 - e0;
+    r[i] = (uint16_t)ri;
+    if (LDS_HIST) atomicAdd(&hist[ri], 1u);
+    else atomicAdd(&cnt[ri], 1u);
+    if (i == N - 1) {
+      ctl->nnz = e1;
+      ctl->len_d = 2ull * e1 + N;
+    }
+  }
+  if (LDS_HIST) {
+    __syncthreads();
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) {
+      uint32_t t = hist[a];
+      if (t) atomicAdd(&cnt[a], t);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ kernels: frequency table
+
+__device__ __forceinline__ void st32(uint8_t *p, uint32_t v) { *(uint32_t *)p = v; }
+__device__ __forceinline__ uint32_t ld32(const uint8_t *p) { return *(const uint32_t *)p; }
+__device__ __forceinline__ uint64_t ld64(const uint8_t *p) { return (uint64_t)ld32(p) | ((uint64_t)ld32(p + 4) << 32); }
+
+// One work-group: counts -> f with sum 2^M (largest-count symbol absorbs a surplus,
+// largest-f symbols pay a deficit, lowest index on ties), F = exclusive cumulative
+// sum, encoder table {reciprocal, f | F << 16}, container header and table.
+__global__ __launch_bounds__(kBig) void k_normalize(Ctl *ctl, const uint32_t *cnt, uint32_t *fq, uint2 *enc_tab,
+                                                    uint32_t A, rans_params p, uint64_t n_elems, int dense,
+                                                    uint8_t *out, uint64_t cap) {
+  __shared__ uint64_t sh64[kBig / 64];
+  __shared__ uint32_t sh32[kBig / 64];
+  __shared__ int64_t s_d;
+  const uint32_t M = p.freq_bits, total = 1u << M;
+  if (ctl->status != 0) return;  // uniform: written by an earlier kernel
+  uint64_t len_loc = 0, present_loc = 0;
+  for (uint32_t a = threadIdx.x; a < A; a += kBig) {
+    uint32_t c = cnt[a];
+    len_loc += c;
+    present_loc += c != 0;
+  }
+  const uint64_t len = block_sum64<kBig>(len_loc, sh64);
+  const uint64_t present = block_sum64<kBig>(present_loc, sh64);
+  if (dense) {
+    if (threadIdx.x == 0) ctl->len_d = len;
+  }
+  const uint64_t len_d = dense ? len : ctl->len_d;
+  if (present > total || len != len_d) {  // the second cannot happen; kept as a guard
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_ALPHABET);
+    return;
+  }
+  // first estimate and its sum
+  uint64_t sum_loc = 0, best_cnt = 0;
+  for (uint32_t a = threadIdx.x; a < A; a += kBig) {
+    uint32_t c = cnt[a];
+    uint32_t f = 0;
+    if (c) {
+      uint64_t q = ((uint64_t)c * total + len / 2) / len;
+      f = q < 1 ? 1u : (uint32_t)q;
+      uint64_t key = ((uint64_t)c << 32) | (0xffffffffu - a);  // max count, lowest index
+      best_cnt = key > best_cnt ? key : best_cnt;
+    }
+    fq[a] = f;
+    sum_loc += f;
+  }
+  const uint64_t sum = block_sum64<kBig>(sum_loc, sh64);
+  const uint64_t best = block_max64<kBig>(best_cnt, sh64);
+  int64_t d = (int64_t)total - (int64_t)sum;
+  if (len && d > 0) {
+    if (threadIdx.x == 0) fq[0xffffffffu - (uint32_t)best] += (uint32_t)d;
+    d = 0;
+  }
+  __syncthreads();
+  while (d < 0) {  // uniform loop: d is identical in every thread
+    uint64_t kb = 0;
+    for (uint32_t a = threadIdx.x; a < A; a += kBig) {
+      uint64_t key = ((uint64_t)fq[a] << 32) | (0xffffffffu - a);
+      kb = key > kb ? key : kb;
+    }
+    kb = block_max64<kBig>(kb, sh64);
+    uint32_t a_star = 0xffffffffu - (uint32_t)kb;
+    int64_t take = (int64_t)(kb >> 32) - 1;
+    if (take > -d) take = -d;
+    if (threadIdx.x == 0) {
+      fq[a_star] -= (uint32_t)take;
+      s_d = d + take;
+    }
+    __syncthreads();
+    d = s_d;
+    __syncthreads();
+  }
+  // container geometry
+  const uint64_t n_chunks = len_d == 0 ? 0 : (p.chunk_syms == 0 ? 1 : (len_d + p.chunk_syms - 1) / p.chunk_syms);
+  const uint64_t table_off = kHdrBytes;
+  const uint64_t dir_off = table_off + (((uint64_t)A * 2 + 7) & ~7ull);
+  const uint64_t payload_off = dir_off + 8 * (n_chunks + 1);
+  if (payload_off > cap) {
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CAPACITY);
+    return;
+  }
+  if (threadIdx.x == 0) {
+    ctl->n_chunks = (uint32_t)n_chunks;
+    ctl->dir_off = dir_off;
+    ctl->payload_off = payload_off;
+    st32(out + 0, 0x31464952u);  // "RIF1"
+    st32(out + 4, 1u | (p.mode << 16) | (p.in_dtype << 24));
+    st32(out + 8, p.q_bits | (M << 8));
+    st32(out + 12, (uint32_t)n_elems);       st32(out + 16, (uint32_t)(n_elems >> 32));
+    st32(out + 20, (uint32_t)p.rows);        st32(out + 24, (uint32_t)(p.rows >> 32));
+    st32(out + 28, (uint32_t)p.cols);        st32(out + 32, (uint32_t)(p.cols >> 32));
+    st32(out + 36, (uint32_t)len_d);         st32(out + 40, (uint32_t)(len_d >> 32));
+    st32(out + 44, A);
+    st32(out + 48, p.n_streams);
+    st32(out + 52, p.chunk_syms);
+    st32(out + 56, (uint32_t)n_chunks);
+    st32(out + 60, __float_as_uint(ctl->x_min));
+    st32(out + 64, __float_as_uint(ctl->x_max));
+    for (uint32_t o = 68; o < kHdrBytes; o += 4) st32(out + o, 0u);
+  }
+  // cumulative sum, encoder table, stored table
+  uint32_t carry = 0;
+  for (uint32_t base = 0; base < A; base += kBig) {
+    uint32_t a = base + threadIdx.x;
+    uint32_t f = a < A ? fq[a] : 0, tot;
+    uint32_t F = carry + block_excl_scan<kBig>(f, sh32, &tot);
+    if (a < A) {
+      // floor(2^32 / f) for f >= 2, 2^32 - 1 for f = 1: with it mulhi(s, m) is floor(s / f) or one less
+      uint32_t m = f <= 1 ? 0xffffffffu : (uint32_t)(0x100000000ull / f);
+      enc_tab[a] = make_uint2(m, f | (F << 16));
+      *(uint16_t *)(out + table_off + 2ull * a) = (uint16_t)f;
+    }
+    carry += tot;
+    __syncthreads();
+  }
+  for (uint64_t o = table_off + 2ull * A + 2 * threadIdx.x; o < dir_off; o += 2 * kBig) *(uint16_t *)(out + o) = 0;
+}
+
+// ------------------------------------------------------------------ kernels: rANS encode
+
+struct SrcDense {
+  const uint8_t *sym;
+  __device__ __forceinline__ void init(const Ctl *) {}
+  __device__ __forceinline__ uint32_t operator()(uint64_t i) const { return sym[i]; }
+};
+// D = v (+) c (+) r (Eq. 7) without materialising the concatenation.
+struct SrcCsr {
+  const uint8_t *v;
+  const uint16_t *c, *r;
+  uint64_t nnz;
+  __device__ __forceinline__ void init(const Ctl *ctl) { nnz = ctl->nnz; }
+  __device__ __forceinline__ uint32_t operator()(uint64_t i) const {
+    if (i < nnz) return v[i];
+    if (i < 2 * nnz) return c[i - nnz];
+    return r[i - 2 * nnz];
+  }
+};
+
+// One lane per stream.  The stream's symbols are taken last to first; before each
+// Eq. 2 update the state is renormalised by emitting its low 16 bits if it is too
+// large for the symbol.  Words are written downwards from the end of the stream's
+// scratch region, so that they end up in the order the decoder reads them.
+template <class Src, bool LDS_TAB>
+__global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uint32_t A, uint32_t M, uint32_t S,
+                                                uint32_t cs, const Ctl *ctl, uint16_t *scratch, uint32_t capw,
+                                                uint32_t *st_out, uint32_t *nw_out, uint32_t *chunk_words,
+                                                uint32_t groups) {
+  extern __shared__ uint2 l_tab[];
+  __shared__ uint32_t sh[kWG / 64];
+  if (ctl->status != 0) return;
+  const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
+  if (k >= ctl->n_chunks) return;
+  src.init(ctl);
+  if (LDS_TAB) {
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) l_tab[a] = g_tab[a];
+    __syncthreads();
+  }
+  const uint2 *tab = LDS_TAB ? l_tab : g_tab;
+  const uint64_t len = ctl->len_d;
+  const uint64_t chunk_len = cs ? cs : len;
+  const uint64_t base = (uint64_t)k * chunk_len;
+  const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
+  const uint32_t j = g * kWG + threadIdx.x;
+  uint32_t nw = 0;
+  if (j < S) {
+    const uint64_t n_j = n_here > j ? (n_here - j + S - 1) / S : 0;
+    uint16_t *p = scratch + ((uint64_t)k * S + j + 1) * capw;  // one past the end of the region
+    uint32_t s = kL;
+    const uint32_t sh_lim = 32 - M;
+    for (uint64_t t = n_j; t-- > 0;) {
+      uint32_t x = src(base + j + t * S);
+      uint2 e = tab[x];
+      uint32_t f = e.y & 0xffffu, F = e.y >> 16;
+      if ((s >> sh_lim) >= f) {
+        *--p = (uint16_t)s;
+        s >>= 16;
+        nw++;
+      }
+      uint32_t q = __umulhi(s, e.x);
+      uint32_t rem = s - q * f;
+      if (rem >= f) q++;
+      s = s + F + q * ((1u << M) - f);
+    }
+    st_out[(uint64_t)k * S + j] = s;
+    nw_out[(uint64_t)k * S + j] = nw;
+  }
+  uint32_t tot;
+  (void)block_excl_scan<kWG>(nw, sh, &tot);
+  if (threadIdx.x == 0 && tot) atomicAdd(&chunk_words[k], tot);
+}
+
+// Chunk sizes -> directory (byte offsets from the payload start), total size.
+__global__ __launch_bounds__(kBig) void k_chunk_scan(Ctl *ctl, uint32_t *chunk_words, uint32_t S, uint8_t *out,
+                                                     uint64_t cap, uint64_t *d_stream_bytes) {
+  __shared__ uint64_t sh64[kBig / 64];
+  if (ctl->status != 0) {
+    if (threadIdx.x == 0 && d_stream_bytes) *d_stream_bytes = 0;
+    return;
+  }
+  const uint32_t nc = ctl->n_chunks;
+  uint8_t *dir = out + ctl->dir_off;
+  uint64_t carry = 0;
+  for (uint32_t base = 0; base < nc; base += kBig) {
+    uint32_t k = base + threadIdx.x;
+    uint64_t sz = 0;
+    if (k < nc) sz = (8ull * S + 2ull * chunk_words[k] + 3) & ~3ull;
+    // inclusive scan over the work-group in 64 bits
+    uint64_t inc = sz;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      uint32_t lo = __shfl_up((uint32_t)inc, d), hi = __shfl_up((uint32_t)(inc >> 32), d);
+      if (lane >= d) inc += ((uint64_t)hi << 32) | lo;
+    }
+    __syncthreads();
+    if (lane == 63) sh64[w] = inc;
+    __syncthreads();
+    uint64_t pre = 0, tot = 0;
+    for (int i = 0; i < kBig / 64; i++) {
+      if (i < w) pre += sh64[i];
+      tot += sh64[i];
+    }
+    if (k < nc) {
+      uint64_t off = carry + pre + inc - sz;
+      st32(dir + 8ull * k, (uint32_t)off);
+      st32(dir + 8ull * k + 4, (uint32_t)(off >> 32));
+    }
+    carry += tot;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    st32(dir + 8ull * nc, (uint32_t)carry);
+    st32(dir + 8ull * nc + 4, (uint32_t)(carry >> 32));
+    uint64_t total = ctl->payload_off + carry;
+    ctl->total_bytes = total;
+    if (total > cap) {
+      set_status(ctl, RANS_ERR_CAPACITY);
+      total = 0;
+    }
+    if (d_stream_bytes) *d_stream_bytes = total;
+  }
+}
+
+// Moves each stream's words from its scratch region to its place in the chunk and
+// writes the chunk header (final states, word counts).
+__global__ __launch_bounds__(kWG) void k_gather(const Ctl *ctl, const uint16_t *scratch, uint32_t capw,
+                                                const uint32_t *st, const uint32_t *nw_arr, uint32_t S,
+                                                uint32_t groups, uint8_t *out) {
+  __shared__ uint32_t sh[kWG / 64];
+  __shared__ uint64_t sh64[kWG / 64];
+  if (ctl->status != 0) return;
+  const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
+  if (k >= ctl->n_chunks) return;
+  const uint8_t *dir = out + ctl->dir_off;
+  uint8_t *ck = out + ctl->payload_off + ld64(dir + 8ull * k);
+  const uint32_t *nwk = nw_arr + (uint64_t)k * S;
+  // words of the streams that precede this group inside the chunk
+  uint64_t pre_loc = 0;
+  for (uint32_t i = threadIdx.x; i < g * kWG; i += kWG) pre_loc += nwk[i];
+  const uint64_t pre = block_sum64<kWG>(pre_loc, sh64);
+  const uint32_t j = g * kWG + threadIdx.x;
+  const uint32_t nw = j < S ? nwk[j] : 0;
+  uint32_t tot;
+  const uint32_t ex = block_excl_scan<kWG>(nw, sh, &tot);
+  if (j < S) {
+    st32(ck + 4ull * j, st[(uint64_t)k * S + j]);
+    st32(ck + 4ull * S + 4ull * j, nw);
+    const uint16_t *src = scratch + ((uint64_t)k * S + j + 1) * capw - nw;
+    uint16_t *dst = (uint16_t *)(ck + 8ull * S) + pre + ex;
+    for (uint32_t i = 0; i < nw; i++) dst[i] = src[i];
+    if (j == S - 1 && ((pre + ex + nw) & 1)) dst[nw] = 0;  // pad the chunk to 4 bytes
+  }
+}
+
+// ------------------------------------------------------------------ kernels: decode
+
+// One work-group: validate the header against the expected geometry, rebuild F,
+// the slot -> symbol table (Eq. 3) and the decoder table f | F << 16, recompute
+// s and z from the stored extrema.
+__global__ __launch_bounds__(kBig) void k_dec_prepare(const uint8_t *in, uint64_t bytes, Ctl *ctl, rans_header h,
+                                                      uint16_t *lut, uint32_t *tab, uint32_t *Farr,
+                                                      rans_qinfo *qout) {
+  __shared__ uint32_t sh32[kBig / 64];
+  __shared__ int s_ok;
+  const uint32_t A = h.alphabet, M = h.p.freq_bits, total = 1u << M;
+  const uint64_t table_off = kHdrBytes;
+  const uint64_t dir_off = table_off + (((uint64_t)A * 2 + 7) & ~7ull);
+  const uint64_t payload_off = dir_off + 8 * ((uint64_t)h.n_chunks + 1);
+  if (threadIdx.x == 0) {
+    bool ok = bytes >= payload_off;
+    ok = ok && ld32(in) == 0x31464952u;
+    ok = ok && ld32(in + 4) == (1u | (h.p.mode << 16) | (h.p.in_dtype << 24));
+    ok = ok && ld32(in + 8) == (h.p.q_bits | (M << 8));
+    ok = ok && ld64(in + 12) == h.n_elems && ld64(in + 20) == h.p.rows && ld64(in + 28) == h.p.cols;
+    ok = ok && ld64(in + 36) == h.len_d && ld32(in + 44) == A && ld32(in + 48) == h.p.n_streams;
+    ok = ok && ld32(in + 52) == h.p.chunk_syms && ld32(in + 56) == h.n_chunks;
+    ok = ok && ld32(in + 60) == __float_as_uint(h.x_min) && ld32(in + 64) == __float_as_uint(h.x_max);
+    if (ok)
+      for (uint32_t o = 68; o < kHdrBytes; o += 4) ok = ok && ld32(in + o) == 0;
+    if (ok) {
+      ok = ok && ld64(in + dir_off) == 0 && ld64(in + dir_off + 8ull * h.n_chunks) == bytes - payload_off;
+    }
+    s_ok = ok;
+    ctl->status = ok ? 0 : RANS_ERR_CORRUPT;
+    ctl->len_d = h.len_d;
+    ctl->n_chunks = h.n_chunks;
+    ctl->dir_off = dir_off;
+    ctl->payload_off = payload_off;
+    ctl->nnz = h.p.mode == RANS_MODE_CSR ? (uint32_t)((h.len_d - h.p.rows) / 2) : 0;
+    // Eq. 6 parameters from the stored extrema, same arithmetic as on the encoding side
+    float mn = h.x_min, mx = h.x_max;
+    float range = mx - mn;
+    float s = range / (float)((1u << h.p.q_bits) - 1u);
+    float zf = 0.0f;
+    if (s != 0.0f) zf = rintf((0.0f - mn) / s);
+    ctl->x_min = mn;
+    ctl->x_max = mx;
+    ctl->scale = s;
+    ctl->zero_point = zf;
+    if (qout) {
+      qout->x_min = mn;
+      qout->x_max = mx;
+      qout->scale = s;
+      qout->zero_point = zf;
+    }
+  }
+  __syncthreads();
+  if (!s_ok) return;
+  // F and the decoder table; marks for the slot table
+  for (uint32_t sl = threadIdx.x; sl < total; sl += kBig) lut[sl] = 0;
+  __syncthreads();
+  uint32_t carry = 0;
+  bool pad_ok = true;
+  for (uint32_t base = 0; base < A; base += kBig) {
+    uint32_t a = base + threadIdx.x;
+    uint32_t f = a < A ? *(const uint16_t *)(in + table_off + 2ull * a) : 0, tot;
+    uint32_t F = carry + block_excl_scan<kBig>(f, sh32, &tot);
+    if (a < A) {
+      tab[a] = f | (F << 16);
+      Farr[a] = F;
+      if (f && F < total) lut[F] = (uint16_t)a;  // symbols with f > 0 start at distinct slots
+    }
+    carry += tot;
+    __syncthreads();
+  }
+  for (uint64_t o = table_off + 2ull * A + 2 * threadIdx.x; o < dir_off; o += 2 * kBig)
+    pad_ok = pad_ok && *(const uint16_t *)(in + o) == 0;
+  if (!pad_ok) set_status(ctl, RANS_ERR_CORRUPT);
+  if (carry != (h.len_d ? total : 0u)) {
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  if (threadIdx.x == 0) Farr[A] = carry;
+  __syncthreads();
+  // slot table = running maximum of the marks: each thread owns a contiguous range of slots
+  const uint32_t per = (total + kBig - 1) / kBig;
+  const uint32_t s0 = threadIdx.x * per;
+  uint32_t loc = 0;
+  for (uint32_t i = 0; i < per && s0 + i < total; i++) {
+    uint32_t m = lut[s0 + i];
+    loc = m > loc ? m : loc;
+  }
+  // exclusive running maximum across threads
+  uint32_t inc = loc;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    uint32_t o = __shfl_up(inc, d);
+    if (lane >= d) inc = o > inc ? o : inc;
+  }
+  uint32_t prev = __shfl_up(inc, 1);
+  if (lane == 0) prev = 0;
+  __syncthreads();
+  if (lane == 63) sh32[w] = inc;
+  __syncthreads();
+  uint32_t run = 0;
+  for (int i = 0; i < w; i++) run = sh32[i] > run ? sh32[i] : run;
+  run = prev > run ? prev : run;
+  for (uint32_t i = 0; i < per && s0 + i < total; i++) {
+    uint32_t m = lut[s0 + i];
+    run = m > run ? m : run;
+    lut[s0 + i] = (uint16_t)run;
+  }
+}
+
+struct SinkSym {
+  uint8_t *out;
+  __device__ __forceinline__ void init(const Ctl *) {}
+  __device__ __forceinline__ void put(uint64_t i, uint32_t x) const { out[i] = (uint8_t)x; }
+};
+struct SinkU16 {
+  uint16_t *out;
+  __device__ __forceinline__ void init(const Ctl *) {}
+  __device__ __forceinline__ void put(uint64_t i, uint32_t x) const { out[i] = (uint16_t)x; }
+};
+// Inverse of Eq. 6 fused into the decoder: x = s * (xhat - z).
+template <typename OutT>
+struct SinkFloat {
+  OutT *out;
+  float s, zf, x_min;
+  __device__ __forceinline__ void init(const Ctl *ctl) {
+    s = ctl->scale;
+    zf = ctl->zero_point;
+    x_min = ctl->x_min;
+  }
+  __device__ __forceinline__ void put(uint64_t i, uint32_t x) const {
+    float y = s == 0.0f ? x_min : s * ((float)x - zf);
+    if constexpr (sizeof(OutT) == 4) out[i] = y;
+    else out[i] = __float2half_rn(y);
+  }
+};
+
+// One lane per stream: slot = s mod 2^M, symbol from the slot table (Eq. 3), state
+// update (Eq. 4), refill of one 16-bit word when the state drops below 2^16.  All
+// sizes and offsets taken from the container are checked before use.
+template <class Sink, bool LDS_TAB>
+__global__ __launch_bounds__(kWG) void k_decode(const uint8_t *in, uint64_t bytes, Ctl *ctl, const uint16_t *g_lut,
+                                                const uint32_t *g_tab, uint32_t A, uint32_t M, uint32_t S,
+                                                uint32_t cs, uint32_t groups, Sink sink) {
+  extern __shared__ uint32_t l_mem[];
+  __shared__ uint32_t sh[kWG / 64];
+  __shared__ uint64_t sh64[kWG / 64];
+  if (ctl->status != 0) return;
+  const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
+  const uint32_t nc = ctl->n_chunks;
+  if (k >= nc) return;
+  sink.init(ctl);
+  const uint32_t total = 1u << M;
+  uint32_t *l_tab = l_mem;
+  uint16_t *l_lut = (uint16_t *)(l_mem + A);
+  if (LDS_TAB) {
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) l_tab[a] = g_tab[a];
+    for (uint32_t i = threadIdx.x; i < total / 2; i += kWG) ((uint32_t *)l_lut)[i] = ((const uint32_t *)g_lut)[i];
+    __syncthreads();
+  }
+  const uint32_t *tab = LDS_TAB ? l_tab : g_tab;
+  const uint16_t *lut = LDS_TAB ? l_lut : g_lut;
+
+  const uint64_t payload_off = ctl->payload_off;
+  const uint64_t payload_bytes = bytes - payload_off;
+  const uint8_t *dir = in + ctl->dir_off;
+  const uint64_t o0 = ld64(dir + 8ull * k), o1 = ld64(dir + 8ull * k + 8);
+  if (o0 > o1 || o1 > payload_bytes || o1 - o0 < 8ull * S || (o0 & 3)) {
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  const uint8_t *ck = in + payload_off + o0;
+  const uint64_t ck_bytes = o1 - o0;
+  const uint64_t len = ctl->len_d;
+  const uint64_t chunk_len = cs ? cs : len;
+  const uint64_t base = (uint64_t)k * chunk_len;
+  const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
+  const uint32_t *nwk = (const uint32_t *)(ck + 4ull * S);
+  uint64_t pre_loc = 0;
+  for (uint32_t i = threadIdx.x; i < g * kWG; i += kWG) pre_loc += nwk[i];
+  const uint64_t pre = block_sum64<kWG>(pre_loc, sh64);
+  const uint32_t j = g * kWG + threadIdx.x;
+  const bool live = j < S;
+  const uint64_t n_j = (live && n_here > j) ? (n_here - j + S - 1) / S : 0;
+  uint32_t nw = live ? nwk[j] : 0;
+  bool bad = false;
+  if (nw > n_j) {
+    bad = true;
+    nw = 0;
+  }
+  uint32_t tot;
+  const uint32_t ex = block_excl_scan<kWG>(nw, sh, &tot);
+  const uint64_t w0 = pre + ex;  // index of this stream's first word inside the chunk
+  if (8ull * S + 2 * (w0 + nw) > ck_bytes) {
+    bad = true;
+    nw = 0;
+  }
+  if (live) {
+    const uint16_t *wp = (const uint16_t *)(ck + 8ull * S) + w0;
+    uint32_t s = ((const uint32_t *)ck)[j];
+    uint32_t used = 0;
+    const uint32_t mask = total - 1;
+    for (uint64_t t = 0; t < n_j; t++) {
+      bad |= s < kL;
+      uint32_t slot = s & mask;
+      uint32_t x = lut[slot];
+      uint32_t e = tab[x];
+      s = (e & 0xffffu) * (s >> M) + slot - (e >> 16);
+      if (s < kL) {
+        uint32_t w = 0;
+        if (used < nw) w = wp[used++];
+        else bad = true;
+        s = (s << 16) | w;
+      }
+      sink.put(base + j + t * S, x);
+    }
+    bad |= (s != kL) || (used != nw);
+    if (j == S - 1) {  // chunk size must be exactly header + words, padded to 4 bytes with zeros
+      uint64_t end = 8ull * S + 2 * (w0 + nw);
+      if (((end + 3) & ~3ull) != ck_bytes) bad = true;
+      else if (end != ck_bytes && *(const uint16_t *)(ck + end) != 0) bad = true;
+    }
+  }
+  if (bad) set_status(ctl, RANS_ERR_CORRUPT);
+}
+
+// Exclusive cumulative sum of r (taken on the decoding side, Sec. 3.1) by one
+// work-group; checks r[i] <= K and sum r = nnz.
+__global__ __launch_bounds__(kBig) void k_row_scan(const uint16_t *r, uint32_t N, uint32_t K, uint32_t *row_off,
+                                                   Ctl *ctl) {
+  __shared__ uint32_t sh[kBig / 64];
+  if (ctl->status != 0) return;
+  uint32_t carry = 0;
+  bool bad = false;
+  for (uint32_t base = 0; base < N; base += kBig) {
+    uint32_t i = base + threadIdx.x;
+    uint32_t v = i < N ? r[i] : 0, tot;
+    bad |= v > K;
+    uint32_t ex = block_excl_scan<kBig>(v, sh, &tot);
+    if (i < N) row_off[i] = carry + ex;
+    carry += tot;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    row_off[N] = carry;
+    if (carry != ctl->nnz) bad = true;
+  }
+  if (bad) set_status(ctl, RANS_ERR_CORRUPT);
+}
+
+// Scatter v to (row, c): one thread per nonzero, the row found by bisection of the
+// cumulative row offsets.  Checks 1 <= v < 2^Q, c < K, c increasing inside a row.
+__global__ __launch_bounds__(kWG) void k_csr_expand(const uint16_t *D, const uint32_t *row_off, uint32_t N,
+                                                    uint32_t K, uint32_t q_bits, uint8_t *xhat, Ctl *ctl) {
+  if (ctl->status != 0) return;
+  const uint32_t nnz = ctl->nnz;
+  uint32_t j = blockIdx.x * kWG + threadIdx.x;
+  if (j >= nnz) return;
+  uint32_t v = D[j], c = D[(uint64_t)nnz + j];
+  // largest row i with row_off[i] <= j  (row_off is non-decreasing, row_off[N] = nnz > j)
+  uint32_t lo = 0, hi = N;
+  while (hi - lo > 1) {
+    uint32_t mid = (lo + hi) >> 1;
+    if (row_off[mid] <= j) lo = mid;
+    else hi = mid;
+  }
+  bool bad = v == 0 || v >= (1u << q_bits) || c >= K;
+  if (j > row_off[lo] && D[(uint64_t)nnz + j - 1] >= c) bad = true;
+  if (bad) set_status(ctl, RANS_ERR_CORRUPT);
+  else xhat[(uint64_t)lo * K + c] = (uint8_t)v;
+}
+
+// Inverse of Eq. 6 over a symbol array.
+template <typename OutT>
+__global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *sym, uint64_t n, const rans_qinfo *qi, const Ctl *ctl,
+                                                 OutT *out) {
+  if (ctl && ctl->status != 0) return;
+  const float s = qi->scale, zf = qi->zero_point, x_min = qi->x_min;
+  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (uint64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    float y = s == 0.0f ? x_min : s * ((float)sym[i] - zf);
+    if constexpr (sizeof(OutT) == 4) out[i] = y;
+    else out[i] = __float2half_rn(y);
+  }
+}
+
+// ------------------------------------------------------------------ host side
+
+#define LAUNCH_CHECK()                                  \
+  do {                                                  \
+    if (hipGetLastError() != hipSuccess) return RANS_ERR_HIP; \
+  } while (0)
+
+inline bool aligned_to(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+inline uint32_t grid_for(uint64_t n, uint32_t per_block, uint32_t cap) {
+  uint64_t g = (n + per_block - 1) / per_block;
+  if (g < 1) g = 1;
+  return (uint32_t)(g > cap ? cap : g);
+}
+
+int launch_init(const Layout &L, uint8_t *ws, hipStream_t st) {
+  uint32_t work = L.A > L.nc_max + 1 ? L.A : L.nc_max + 1;
+  hipLaunchKernelGGL(k_init, dim3(grid_for(work, kWG, 1024)), dim3(kWG), 0, st, (Ctl *)(ws + L.ctl),
+                     (uint32_t *)(ws + L.cnt), L.A, (uint32_t *)(ws + L.chunk_words), L.nc_max);
+  LAUNCH_CHECK();
+  return RANS_OK;
+}
+
+// min/max + scale/zero point + quantise/histogram of a float tensor.
+int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Layout &L, uint8_t *ws, uint8_t *d_sym,
+                    rans_qinfo *d_qinfo, hipStream_t st) {
+  Ctl *ctl = (Ctl *)(ws + L.ctl);
+  uint32_t *cnt = (uint32_t *)(ws + L.cnt);
+  const bool f16 = p.in_dtype == RANS_F16;
+  const bool vec = aligned_to(d_x, 16) && aligned_to(d_sym, 8);
+  const uint32_t V = vec ? (f16 ? 8 : 4) : 1;
+  if (n) {
+    uint32_t g = grid_for(n, kWG * V * 4, 2048);
+    if (f16) {
+      if (vec) hipLaunchKernelGGL((k_minmax<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl);
+      else hipLaunchKernelGGL((k_minmax<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl);
+    } else {
+      if (vec) hipLaunchKernelGGL((k_minmax<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl);
+      else hipLaunchKernelGGL((k_minmax<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl);
+    }
+    LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(k_qinfo, dim3(1), dim3(64), 0, st, ctl, p.q_bits, (uint32_t)n, d_qinfo);
+  LAUNCH_CHECK();
+  if (n) {
+    uint32_t tile = kWG * V * kQIter;
+    uint32_t g = (uint32_t)((n + tile - 1) / tile);
+    int skip0 = p.mode == RANS_MODE_CSR;
+    if (f16) {
+      if (vec) hipLaunchKernelGGL((k_quant_hist<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+      else hipLaunchKernelGGL((k_quant_hist<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+    } else {
+      if (vec) hipLaunchKernelGGL((k_quant_hist<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+      else hipLaunchKernelGGL((k_quant_hist<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+    }
+    LAUNCH_CHECK();
+  }
+  return RANS_OK;
+}
+
+// Everything after the symbol histogram: CSR, table, coder, container.
+int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, const Layout &L, uint8_t *ws,
+                       uint8_t *d_stream, size_t cap, uint64_t *d_stream_bytes, hipStream_t st) {
+  Ctl *ctl = (Ctl *)(ws + L.ctl);
+  uint32_t *cnt = (uint32_t *)(ws + L.cnt);
+  const bool csr = p.mode == RANS_MODE_CSR;
+  const uint32_t A = L.A, S = p.n_streams;
+  const bool lds_hist = A <= kLdsHistMaxA;
+  if (csr) {
+    const int al = aligned_to(d_sym, 16);
+    uint32_t *blk = (uint32_t *)(ws + L.blk_nnz);
+    uint32_t *row_end = (uint32_t *)(ws + L.row_end);
+    if (n) {
+      hipLaunchKernelGGL(k_csr_count, dim3(L.n_blk), dim3(kWG), 0, st, d_sym, (uint32_t)n, al, blk);
+      LAUNCH_CHECK();
+      hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(kBig), 0, st, blk, L.n_blk);
+      LAUNCH_CHECK();
+      if (lds_hist)
+        hipLaunchKernelGGL((k_csr_compact<true>), dim3(L.n_blk), dim3(kWG), A * 4, st, d_sym, (uint32_t)n, al,
+                           (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A);
+      else
+        hipLaunchKernelGGL((k_csr_compact<false>), dim3(L.n_blk), dim3(kWG), 0, st, d_sym, (uint32_t)n, al,
+                           (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A);
+      LAUNCH_CHECK();
+      uint32_t N = (uint32_t)p.rows;
+      uint32_t g = (N + kWG - 1) / kWG;
+      if (lds_hist)
+        hipLaunchKernelGGL((k_csr_rows<true>), dim3(g), dim3(kWG), A * 4, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl);
+      else
+        hipLaunchKernelGGL((k_csr_rows<false>), dim3(g), dim3(kWG), 0, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl);
+      LAUNCH_CHECK();
+    }
+  }
+  hipLaunchKernelGGL(k_normalize, dim3(1), dim3(kBig), 0, st, ctl, cnt, (uint32_t *)(ws + L.fq),
+                     (uint2 *)(ws + L.enc_tab), A, p, n, csr ? 0 : 1, d_stream, (uint64_t)cap);
+  LAUNCH_CHECK();
+  const uint32_t groups = (S + kWG - 1) / kWG;
+  if (L.nc_max) {
+    uint32_t g = L.nc_max * groups;
+    uint16_t *scratch = (uint16_t *)(ws + L.scratch);
+    uint32_t *st_arr = (uint32_t *)(ws + L.st), *nw_arr = (uint32_t *)(ws + L.nw);
+    uint32_t *cw = (uint32_t *)(ws + L.chunk_words);
+    const uint2 *tab = (const uint2 *)(ws + L.enc_tab);
+    const bool lds_tab = lds_hist;
+    if (csr) {
+      SrcCsr src{ws + L.v, (const uint16_t *)(ws + L.c), (const uint16_t *)(ws + L.r), 0};
+      if (lds_tab)
+        hipLaunchKernelGGL((k_encode<SrcCsr, true>), dim3(g), dim3(kWG), A * 8, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups);
+      else
+        hipLaunchKernelGGL((k_encode<SrcCsr, false>), dim3(g), dim3(kWG), 0, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups);
+    } else {
+      SrcDense src{d_sym};
+      hipLaunchKernelGGL((k_encode<SrcDense, true>), dim3(g), dim3(kWG), A * 8, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups);
+    }
+    LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(k_chunk_scan, dim3(1), dim3(kBig), 0, st, ctl, (uint32_t *)(ws + L.chunk_words), S, d_stream,
+                     (uint64_t)cap, d_stream_bytes);
+  LAUNCH_CHECK();
+  if (L.nc_max) {
+    hipLaunchKernelGGL(k_gather, dim3(L.nc_max * groups), dim3(kWG), 0, st, ctl, (const uint16_t *)(ws + L.scratch),
+                       L.capw, (const uint32_t *)(ws + L.st), (const uint32_t *)(ws + L.nw), S, groups, d_stream);
+    LAUNCH_CHECK();
+  }
+  return RANS_OK;
+}
+
+int check_common(const rans_params *p, uint64_t n, const void *d_ws, size_t ws_bytes, Layout *L) {
+  int rc = check_params(p, n);
+  if (rc) return rc;
+  if (!d_ws || !aligned_to(d_ws, 256)) return RANS_ERR_ARG;
+  *L = make_layout(*p, n);
+  if (ws_bytes < L->total) return RANS_ERR_WORKSPACE;
+  if ((uint64_t)L->nc_max * ((p->n_streams + kWG - 1) / kWG) > 0x7fffffffull) return RANS_ERR_ARG;
+  return RANS_OK;
+}
+
+int header_from_bytes(const uint8_t *b, size_t nb, rans_header *h) {
+  if (!b || !h) return RANS_ERR_ARG;
+  if (nb < kHdrBytes) return RANS_ERR_CORRUPT;
+  auto g16 = [&](size_t o) { return (uint32_t)b[o] | ((uint32_t)b[o + 1] << 8); };
+  auto g32 = [&](size_t o) { return g16(o) | (g16(o + 2) << 16); };
+  auto g64 = [&](size_t o) { return (uint64_t)g32(o) | ((uint64_t)g32(o + 4) << 32); };
+  if (g32(0) != 0x31464952u || g16(4) != 1) return RANS_ERR_CORRUPT;
+  memset(h, 0, sizeof(*h));
+  h->p.mode = b[6];
+  h->p.in_dtype = b[7];
+  h->p.q_bits = b[8];
+  h->p.freq_bits = b[9];
+  if (g16(10) != 0) return RANS_ERR_CORRUPT;
+  h->n_elems = g64(12);
+  h->p.rows = g64(20);
+  h->p.cols = g64(28);
+  h->len_d = g64(36);
+  h->alphabet = g32(44);
+  h->p.n_streams = g32(48);
+  h->p.chunk_syms = g32(52);
+  h->n_chunks = g32(56);
+  uint32_t u = g32(60);
+  memcpy(&h->x_min, &u, 4);
+  u = g32(64);
+  memcpy(&h->x_max, &u, 4);
+  for (size_t i = 68; i < kHdrBytes; i++)
+    if (b[i]) return RANS_ERR_CORRUPT;
+  return RANS_OK;
+}
+
+int validate_header(const rans_header *h) {
+  if (h->n_elems > kMaxElems || h->p.rows > kMaxElems || h->p.cols > kMaxElems) return RANS_ERR_CORRUPT;
+  if (check_params(&h->p, h->n_elems) != RANS_OK) return RANS_ERR_CORRUPT;
+  if (!std::isfinite(h->x_min) || !std::isfinite(h->x_max) || h->x_min > h->x_max) return RANS_ERR_CORRUPT;
+  if (h->alphabet != alphabet_of(h->p)) return RANS_ERR_CORRUPT;
+  if (h->p.mode == RANS_MODE_DENSE) {
+    if (h->len_d != h->n_elems) return RANS_ERR_CORRUPT;
+  } else {
+    if (h->len_d < h->p.rows || (h->len_d - h->p.rows) % 2 != 0) return RANS_ERR_CORRUPT;
+    if ((h->len_d - h->p.rows) / 2 > h->n_elems) return RANS_ERR_CORRUPT;
+  }
+  if ((uint64_t)h->n_chunks != n_chunks_of(h->len_d, h->p.chunk_syms)) return RANS_ERR_CORRUPT;
+  return RANS_OK;
+}
+
+// Shared body of rans_decode / rans_decompress.  out_kind: 0 symbols, 1 fp32, 2 fp16.
+int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_header *h_hdr, int out_kind, void *d_out,
+                  uint64_t out_cap, rans_qinfo *d_qinfo, void *d_ws, size_t ws_bytes, hipStream_t st) {
+  if (!d_stream || !aligned_to(d_stream, 16)) return RANS_ERR_ARG;
+  rans_header h;
+  if (h_hdr) {
+    h = *h_hdr;
+  } else {
+    if (stream_bytes < kHdrBytes) return RANS_ERR_CORRUPT;
+    uint8_t hb[kHdrBytes];
+    if (hipMemcpyAsync(hb, d_stream, kHdrBytes, hipMemcpyDeviceToHost, st) != hipSuccess) return RANS_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return RANS_ERR_HIP;
+    int rc = header_from_bytes(hb, kHdrBytes, &h);
+    if (rc) return rc;
+  }
+  int rc = validate_header(&h);
+  if (rc) return rc;
+  const uint64_t n = h.n_elems;
+  if (n > out_cap) return RANS_ERR_CAPACITY;
+  if (n && !d_out) return RANS_ERR_ARG;
+  Layout L;
+  rc = check_common(&h.p, n, d_ws, ws_bytes, &L);
+  if (rc) return rc;
+  const uint32_t A = L.A, M = h.p.freq_bits, S = h.p.n_streams;
+  const uint64_t payload_off = kHdrBytes + align_up((size_t)A * 2, 8) + 8 * ((uint64_t)h.n_chunks + 1);
+  if (stream_bytes < payload_off) return RANS_ERR_CORRUPT;
+  uint8_t *ws = (uint8_t *)d_ws;
+  Ctl *ctl = (Ctl *)(ws + L.ctl);
+  uint16_t *lut = (uint16_t *)(ws + L.dec_lut);
+  uint32_t *tab = (uint32_t *)(ws + L.dec_tab);
+  hipLaunchKernelGGL(k_dec_prepare, dim3(1), dim3(kBig), 0, st, d_stream, (uint64_t)stream_bytes, ctl, h, lut, tab,
+                     (uint32_t *)(ws + L.dec_F), d_qinfo);
+  LAUNCH_CHECK();
+  const uint32_t groups = (S + kWG - 1) / kWG;
+  const size_t lds = (size_t)A * 4 + ((size_t)2 << M);
+  const bool lds_tab = lds <= 48 * 1024;
+  const bool csr = h.p.mode == RANS_MODE_CSR;
+  if (h.n_chunks) {
+    dim3 grid(h.n_chunks * groups), blk(kWG);
+#define DEC_LAUNCH(SINKT, sinkv)                                                                                   \
+  do {                                                                                                             \
+    if (lds_tab)                                                                                                   \
+      hipLaunchKernelGGL((k_decode<SINKT, true>), grid, blk, lds, st, d_stream, (uint64_t)stream_bytes, ctl, lut,   \
+                         tab, A, M, S, h.p.chunk_syms, groups, sinkv);                                             \
+    else                                                                                                           \
+      hipLaunchKernelGGL((k_decode<SINKT, false>), grid, blk, 0, st, d_stream, (uint64_t)stream_bytes, ctl, lut,    \
+                         tab, A, M, S, h.p.chunk_syms, groups, sinkv);                                             \
+  } while (0)
+    if (csr) {
+      SinkU16 sk{(uint16_t *)(ws + L.D)};
+      DEC_LAUNCH(SinkU16, sk);
+    } else if (out_kind == 0) {
+      SinkSym sk{(uint8_t *)d_out};
+      DEC_LAUNCH(SinkSym, sk);
+    } else if (out_kind == 1) {
+      SinkFloat<float> sk{(float *)d_out, 0, 0, 0};
+      DEC_LAUNCH(SinkFloat<float>, sk);
+    } else {
+      SinkFloat<__half> sk{(__half *)d_out, 0, 0, 0};
+      DEC_LAUNCH(SinkFloat<__half>, sk);
+    }
+#undef DEC_LAUNCH
+    LAUNCH_CHECK();
+  }
+  if (csr && n) {
+    const uint32_t N = (uint32_t)h.p.rows, K = (uint32_t)h.p.cols;
+    const uint64_t nnz = (h.len_d - N) / 2;
+    uint8_t *xhat = out_kind == 0 ? (uint8_t *)d_out : ws + L.dec_sym;
+    uint32_t *row_off = (uint32_t *)(ws + L.row_off);
+    const uint16_t *D = (const uint16_t *)(ws + L.D);
+    hipLaunchKernelGGL((k_fill<uint8_t>), dim3(grid_for(n, kWG * 16, 4096)), dim3(kWG), 0, st, xhat, n, (uint8_t)0);
+    LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_row_scan, dim3(1), dim3(kBig), 0, st, D + 2 * nnz, N, K, row_off, ctl);
+    LAUNCH_CHECK();
+    if (nnz) {
+      hipLaunchKernelGGL(k_csr_expand, dim3((uint32_t)((nnz + kWG - 1) / kWG)), dim3(kWG), 0, st, D, row_off, N, K,
+                         h.p.q_bits, xhat, ctl);
+      LAUNCH_CHECK();
+    }
+    if (out_kind) {
+      const rans_qinfo *qi = (const rans_qinfo *)&ctl->x_min;
+      uint32_t g = grid_for(n, kWG * 8, 8192);
+      if (out_kind == 1) hipLaunchKernelGGL((k_dequant<float>), dim3(g), dim3(kWG), 0, st, xhat, n, qi, ctl, (float *)d_out);
+      else hipLaunchKernelGGL((k_dequant<__half>), dim3(g), dim3(kWG), 0, st, xhat, n, qi, ctl, (__half *)d_out);
+      LAUNCH_CHECK();
+    }
+  }
+  return RANS_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI
+
+extern "C" {
+
+int rans_workspace_bytes(const rans_params *p, uint64_t n_elems, size_t *ws_bytes, size_t *max_stream_bytes) {
+  int rc = check_params(p, n_elems);
+  if (rc) return rc;
+  Layout L = make_layout(*p, n_elems);
+  if (ws_bytes) *ws_bytes = L.total;
+  if (max_stream_bytes) *max_stream_bytes = stream_bound(*p, L);
+  return RANS_OK;
+}
+
+int rans_quantize(const void *d_x, uint64_t n_elems, const rans_params *p, uint8_t *d_sym, rans_qinfo *d_qinfo,
+                  void *d_ws, size_t ws_bytes, void *stream) {
+  Layout L;
+  int rc = check_common(p, n_elems, d_ws, ws_bytes, &L);
+  if (rc) return rc;
+  if (!d_qinfo || (n_elems && (!d_x || !d_sym))) return RANS_ERR_ARG;
+  if (!aligned_to(d_x, p->in_dtype == RANS_F16 ? 2 : 4) || !aligned_to(d_qinfo, 4)) return RANS_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  uint8_t *ws = (uint8_t *)d_ws;
+  rc = launch_init(L, ws, st);
+  if (rc) return rc;
+  return launch_quantize(d_x, n_elems, *p, L, ws, d_sym, d_qinfo, st);
+}
+
+int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, const rans_qinfo *d_qinfo,
+                uint8_t *d_stream, size_t stream_cap, uint64_t *d_stream_bytes, void *d_ws, size_t ws_bytes,
+                void *stream) {
+  Layout L;
+  int rc = check_common(p, n_elems, d_ws, ws_bytes, &L);
+  if (rc) return rc;
+  if (!d_qinfo || !d_stream || !d_stream_bytes || (n_elems && !d_sym)) return RANS_ERR_ARG;
+  if (!aligned_to(d_stream, 16) || !aligned_to(d_stream_bytes, 8) || !aligned_to(d_qinfo, 4)) return RANS_ERR_ARG;
+  if (stream_cap < kHdrBytes) return RANS_ERR_CAPACITY;
+  hipStream_t st = (hipStream_t)stream;
+  uint8_t *ws = (uint8_t *)d_ws;
+  Ctl *ctl = (Ctl *)(ws + L.ctl);
+  rc = launch_init(L, ws, st);
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_qinfo_from_user, dim3(1), dim3(64), 0, st, ctl, d_qinfo, p->q_bits);
+  LAUNCH_CHECK();
+  if (n_elems) {
+    const bool vec = aligned_to(d_sym, 16);
+    const uint32_t tile = kWG * (vec ? 16 : 1) * kQIter;
+    const uint32_t g = (uint32_t)((n_elems + tile - 1) / tile);
+    const int skip0 = p->mode == RANS_MODE_CSR;
+    if (vec)
+      hipLaunchKernelGGL((k_quant_hist<uint8_t, true>), dim3(g), dim3(kWG), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
+    else
+      hipLaunchKernelGGL((k_quant_hist<uint8_t, false>), dim3(g), dim3(kWG), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
+    LAUNCH_CHECK();
+  }
+  return launch_encode_tail(d_sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st);
+}
+
+int rans_compress(const void *d_x, uint64_t n_elems, const rans_params *p, uint8_t *d_stream, size_t stream_cap,
+                  uint64_t *d_stream_bytes, void *d_ws, size_t ws_bytes, void *stream) {
+  Layout L;
+  int rc = check_common(p, n_elems, d_ws, ws_bytes, &L);
+  if (rc) return rc;
+  if (!d_stream || !d_stream_bytes || (n_elems && !d_x)) return RANS_ERR_ARG;
+  if (!aligned_to(d_x, p->in_dtype == RANS_F16 ? 2 : 4)) return RANS_ERR_ARG;
+  if (!aligned_to(d_stream, 16) || !aligned_to(d_stream_bytes, 8)) return RANS_ERR_ARG;
+  if (stream_cap < kHdrBytes) return RANS_ERR_CAPACITY;
+  hipStream_t st = (hipStream_t)stream;
+  uint8_t *ws = (uint8_t *)d_ws;
+  rc = launch_init(L, ws, st);
+  if (rc) return rc;
+  rc = launch_quantize(d_x, n_elems, *p, L, ws, ws + L.sym, nullptr, st);
+  if (rc) return rc;
+  return launch_encode_tail(ws + L.sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st);
+}
+
+int rans_decode(const uint8_t *d_stream, size_t stream_bytes, const rans_header *h_hdr, uint8_t *d_sym,
+                uint64_t sym_cap, rans_qinfo *d_qinfo, void *d_ws, size_t ws_bytes, void *stream) {
+  if (d_qinfo && !aligned_to(d_qinfo, 4)) return RANS_ERR_ARG;
+  return decode_common(d_stream, stream_bytes, h_hdr, 0, d_sym, sym_cap, d_qinfo, d_ws, ws_bytes, (hipStream_t)stream);
+}
+
+int rans_decompress(const uint8_t *d_stream, size_t stream_bytes, const rans_header *h_hdr, uint32_t out_dtype,
+                    void *d_x_out, uint64_t elem_cap, void *d_ws, size_t ws_bytes, void *stream) {
+  if (out_dtype > RANS_F16) return RANS_ERR_ARG;
+  if (!aligned_to(d_x_out, out_dtype == RANS_F16 ? 2 : 4)) return RANS_ERR_ARG;
+  return decode_common(d_stream, stream_bytes, h_hdr, out_dtype == RANS_F16 ? 2 : 1, d_x_out, elem_cap, nullptr, d_ws,
+                       ws_bytes, (hipStream_t)stream);
+}
+
+int rans_dequantize(const uint8_t *d_sym, uint64_t n_elems, const rans_qinfo *d_qinfo, uint32_t out_dtype,
+                    void *d_x_out, void *stream) {
+  if (!d_qinfo || out_dtype > RANS_F16 || n_elems > kMaxElems) return RANS_ERR_ARG;
+  if (n_elems && (!d_sym || !d_x_out)) return RANS_ERR_ARG;
+  if (!aligned_to(d_x_out, out_dtype == RANS_F16 ? 2 : 4) || !aligned_to(d_qinfo, 4)) return RANS_ERR_ARG;
+  if (!n_elems) return RANS_OK;
+  hipStream_t st = (hipStream_t)stream;
+  uint32_t g = grid_for(n_elems, kWG * 8, 8192);
+  if (out_dtype == RANS_F32)
+    hipLaunchKernelGGL((k_dequant<float>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, (const Ctl *)nullptr, (float *)d_x_out);
+  else
+    hipLaunchKernelGGL((k_dequant<__half>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, (const Ctl *)nullptr, (__half *)d_x_out);
+  LAUNCH_CHECK();
+  return RANS_OK;
+}
+
+int rans_peek_header(const void *h_bytes, size_t n_bytes, rans_header *out) {
+  int rc = header_from_bytes((const uint8_t *)h_bytes, n_bytes, out);
+  if (rc) return rc;
+  return validate_header(out);
+}
+
+int rans_last_status(const void *d_ws, void *stream) {
+  if (!d_ws) return RANS_ERR_ARG;
+  int32_t status = 0;
+  hipStream_t st = (hipStream_t)stream;
+  if (hipMemcpyAsync(&status, d_ws, sizeof(status), hipMemcpyDeviceToHost, st) != hipSuccess) return RANS_ERR_HIP;
+  if (hipStreamSynchronize(st) != hipSuccess) return RANS_ERR_HIP;
+  return status;
+}
+
+const char *rans_strerror(int code) {
+  switch (code) {
+    case RANS_OK: return "ok";
+    case RANS_ERR_ARG: return "invalid argument";
+    case RANS_ERR_SHAPE: return "rows*cols != n_elems, or chunk_syms not a multiple of n_streams";
+    case RANS_ERR_ALPHABET: return "more distinct symbols than 2^freq_bits, or CSR with cols > 65535";
+    case RANS_ERR_CAPACITY: return "output buffer too small";
+    case RANS_ERR_WORKSPACE: return "workspace too small";
+    case RANS_ERR_NONFINITE: return "non-finite value in the tensor";
+    case RANS_ERR_CORRUPT: return "corrupt container";
+    case RANS_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

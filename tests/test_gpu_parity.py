@@ -1,0 +1,278 @@
+"""GPU library vs CPU oracle, element by element, through the C ABI.  Needs an MI355X (-m gpu).
+
+Bar: quantised symbols, quantiser parameters, container bytes and decoded symbols bit-exact;
+dequantised floats within 1 ulp (they are expected to be bit-identical: same binary32 operations,
+no FMA contraction on either side).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_11664_amd import binding as B, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _oparams(p):
+    return oracle.make_params(p.q_bits, p.freq_bits, p.rows, p.cols, p.mode, p.n_streams, p.chunk_syms, p.in_dtype)
+
+
+def _ulp_diff(a, b):
+    if a.dtype == np.float32:
+        ia, ib = a.view(np.int32).astype(np.int64), b.view(np.int32).astype(np.int64)
+    else:
+        ia, ib = a.view(np.int16).astype(np.int64), b.view(np.int16).astype(np.int64)
+    ia = np.where(ia < 0, -(ia & 0x7fffffff if a.dtype == np.float32 else ia & 0x7fff), ia)
+    ib = np.where(ib < 0, -(ib & 0x7fffffff if a.dtype == np.float32 else ib & 0x7fff), ib)
+    return np.abs(ia - ib).max(initial=0)
+
+
+def _check_all(x_cpu: torch.Tensor, p: B.Params, tag=""):
+    """Fused and unfused paths against the oracle for one tensor."""
+    print(f"[case] {tag} n={x_cpu.numel()} dtype={x_cpu.dtype} Q={p.q_bits} M={p.freq_bits} N={p.rows} K={p.cols} "
+          f"mode={p.mode} S={p.n_streams} cs={p.chunk_syms}", flush=True)
+    n = x_cpu.numel()
+    xn = x_cpu.numpy()
+    ref, sym_ref = oracle.compress(xn, _oparams(p))
+    _, qi_ref = oracle.quantize(xn, p.q_bits)
+    codec = B.Codec(p, n)
+    xd = x_cpu.cuda()
+    # fused
+    nbytes = codec.compress(xd)
+    got = codec.container(nbytes)
+    assert nbytes == len(ref), f"container size {nbytes} != oracle {len(ref)}"
+    assert got == ref, "container bytes differ"
+    # unfused: quantize -> encode
+    sym = torch.empty(max(n, 1), dtype=torch.uint8, device="cuda")
+    codec.quantize(xd, sym)
+    assert np.array_equal(sym[:n].cpu().numpy(), sym_ref), "quantised symbols differ"
+    q = codec.qinfo.cpu().numpy()
+    assert np.array_equal(q.view(np.uint32), np.array(qi_ref.as_tuple(), np.float32).view(np.uint32)), "qinfo differs"
+    nb2 = codec.encode(sym)
+    assert codec.container(nb2) == ref, "rans_encode bytes differ from rans_compress"
+    # decode (with header hint, and letting the library read the header)
+    hdr = codec.header(nbytes)
+    for h in (hdr, None):
+        out_sym = torch.full((max(n, 1),), 0xAB, dtype=torch.uint8, device="cuda")
+        codec.qinfo.zero_()
+        codec.decode(nbytes, h, out_sym)
+        assert np.array_equal(out_sym[:n].cpu().numpy(), sym_ref), "decoded symbols differ"
+        assert np.array_equal(codec.qinfo.cpu().numpy().view(np.uint32), q.view(np.uint32))
+    # decompress + dequantize
+    for dt, code in ((torch.float32, oracle.F32), (torch.float16, oracle.F16)):
+        y_ref = oracle.dequantize(sym_ref, qi_ref, code)
+        out = torch.empty(max(n, 1), dtype=dt, device="cuda")
+        codec.decompress(nbytes, hdr, out)
+        y = out[:n].cpu().numpy()
+        assert _ulp_diff(y, y_ref) <= 1
+        assert np.array_equal(y.view(np.uint8), y_ref.view(np.uint8)), "dequantised floats not bit-identical"
+        out2 = torch.empty(max(n, 1), dtype=dt, device="cuda")
+        rc = B.rans_dequantize(sym, n, codec.qinfo, code, out2)
+        assert rc == 0
+        assert np.array_equal(out2[:n].cpu().numpy().view(np.uint8), y_ref.view(np.uint8))
+    return nbytes
+
+
+def _relu_normal(n, seed, dtype=torch.float32, shift=0.0, scale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    return (torch.relu(torch.randn(n, generator=g) + shift) * scale).to(dtype)
+
+
+def _normal(n, seed, dtype=torch.float32, mean=0.3, std=2.0):
+    g = torch.Generator().manual_seed(seed)
+    return (torch.randn(n, generator=g) * std + mean).to(dtype)
+
+
+DENSE_CASES = [
+    # n, dtype, Q, M, S, cs
+    (1, torch.float32, 8, 12, 1, 0),
+    (7, torch.float32, 8, 12, 32, 0),
+    (1000, torch.float32, 8, 12, 32, 0),
+    (4099, torch.float32, 8, 12, 32, 64),
+    (65536 + 13, torch.float32, 8, 12, 64, 1024),
+    (100003, torch.float16, 8, 14, 1024, 4096),
+    (300000, torch.float16, 8, 14, 1024, 1 << 16),
+    (50001, torch.float32, 6, 14, 256, 2560),
+    (50001, torch.float32, 4, 10, 300, 600),
+    (50001, torch.float16, 2, 8, 5, 50),
+    (50001, torch.float32, 1, 1, 64, 0),
+    (20000, torch.float32, 3, 15, 64, 6400),
+    (50001, torch.float32, 8, 8, 64, 640),
+]
+
+
+@pytest.mark.parametrize("n,dtype,Q,M,S,cs", DENSE_CASES)
+def test_dense_parity(n, dtype, Q, M, S, cs):
+    for seed, x in ((0, _relu_normal(n, n, dtype)), (1, _normal(n, n + 1, dtype))):
+        p = B.make_params(Q, M, n, 1, B.MODE_DENSE, S, cs, B.F16 if dtype == torch.float16 else B.F32)
+        _check_all(x, p, f"dense seed={seed}")
+
+
+CSR_CASES = [
+    # rows, cols, dtype, Q, M, S, cs
+    (1, 1, torch.float32, 8, 12, 1, 0),
+    (3, 5, torch.float32, 8, 12, 4, 0),
+    (64, 7, torch.float32, 8, 12, 32, 0),
+    (1000, 7, torch.float32, 8, 12, 32, 320),
+    (997, 13, torch.float16, 8, 12, 64, 1024),
+    (300, 256, torch.float32, 8, 12, 1024, 8192),
+    (4096 + 5, 16, torch.float32, 4, 10, 256, 2048),
+    (64, 3136, torch.float32, 8, 12, 32, 0),
+    (17, 9000, torch.float32, 6, 15, 128, 12800),
+    (40000, 1, torch.float32, 8, 12, 64, 640),
+    (2, 65535, torch.float32, 8, 15, 64, 0),
+]
+
+
+@pytest.mark.parametrize("rows,cols,dtype,Q,M,S,cs", CSR_CASES)
+def test_csr_parity(rows, cols, dtype, Q, M, S, cs):
+    n = rows * cols
+    if cols > 20000:      # keep the number of distinct column symbols below 2^M
+        x = torch.zeros(n)
+        g = torch.Generator().manual_seed(5)
+        idx = torch.randperm(n, generator=g)[:3000]
+        x[idx] = torch.rand(3000, generator=g) + 0.1
+        xs = [x.to(dtype)]
+    else:
+        xs = [_relu_normal(n, n, dtype, shift=-0.5), _relu_normal(n, n + 1, dtype, shift=1.0)]
+    for i, x in enumerate(xs):
+        p = B.make_params(Q, M, rows, cols, B.MODE_CSR, S, cs, B.F16 if dtype == torch.float16 else B.F32)
+        _check_all(x, p, f"csr case={i}")
+
+
+def test_unaligned_buffers():
+    """Views that start at odd element offsets take the scalar load paths."""
+    n = 30011
+    base = _relu_normal(n + 3, 3)
+    x = base[1:1 + n]
+    p = B.make_params(8, 12, n, 1, B.MODE_DENSE, 32, 640, B.F32)
+    ref, sym_ref = oracle.compress(x.numpy().copy(), _oparams(p))
+    codec = B.Codec(p, n)
+    xd = base.cuda()[1:1 + n]
+    assert xd.data_ptr() % 16 != 0
+    assert codec.container(codec.compress(xd)) == ref
+    symbuf = torch.empty(n + 8, dtype=torch.uint8, device="cuda")
+    sym = symbuf[3:3 + n]
+    codec.quantize(xd, sym)
+    assert np.array_equal(sym.cpu().numpy(), sym_ref)
+    assert codec.container(codec.encode(sym)) == ref
+    pc = B.make_params(8, 12, n // 7 if n % 7 == 0 else n, 7 if n % 7 == 0 else 1, B.MODE_CSR, 32, 640, B.F32)
+    refc, _ = oracle.compress(x.numpy().copy(), _oparams(pc))
+    cc = B.Codec(pc, n)
+    cc.qinfo.copy_(codec.qinfo)
+    assert cc.container(cc.encode(sym)) == refc
+
+
+def test_edge_cases():
+    # empty tensor, both modes
+    for mode in (B.MODE_DENSE, B.MODE_CSR):
+        p = B.make_params(8, 12, 0, 4, mode, 32, 0, B.F32)
+        _check_all(torch.zeros(0), p, "empty")
+    # constant tensors (s = 0), negative zero, single element
+    for mode in (B.MODE_DENSE, B.MODE_CSR):
+        _check_all(torch.full((1000,), -2.5), B.make_params(8, 12, 250, 4, mode, 8, 16, B.F32), "constant")
+        _check_all(torch.zeros(1000), B.make_params(8, 12, 250, 4, mode, 8, 16, B.F32), "zeros")
+        x = torch.tensor([-0.0, 0.0, 1.0, 0.5] * 10)
+        _check_all(x, B.make_params(8, 12, 10, 4, mode, 3, 6, B.F32), "negzero")
+    # more streams than symbols; chunk of exactly S symbols
+    _check_all(_relu_normal(10, 1), B.make_params(8, 12, 10, 1, 0, 64, 64, B.F32), "S>n")
+    _check_all(_relu_normal(1000, 2), B.make_params(8, 12, 1000, 1, 0, 8, 8, B.F32), "cs=S")
+    # tiny and huge magnitudes, denormals
+    _check_all(_normal(5000, 3) * 1e-41, B.make_params(8, 12, 5000, 1, 0, 32, 0, B.F32), "denormal")
+    _check_all(_normal(5000, 4) * 1e37, B.make_params(8, 12, 5000, 1, 0, 32, 0, B.F32), "huge")
+    _check_all(_normal(5000, 5, mean=1e6, std=1.0), B.make_params(8, 12, 5000, 1, 0, 32, 0, B.F32), "offset")
+    x16 = torch.tensor([6.0e-8, 65504.0, -65504.0, 1.0, 0.0] * 100, dtype=torch.float16)
+    _check_all(x16, B.make_params(8, 12, 500, 1, 0, 32, 0, B.F16), "fp16 extremes")
+    # normalisation with a deficit: 4096 distinct column symbols crowd a 2^12 table
+    rows, cols = 64, 4090
+    x = torch.zeros(rows * cols)
+    g = torch.Generator().manual_seed(9)
+    x[torch.randperm(rows * cols, generator=g)[:60000]] = 1.0
+    _check_all(x, B.make_params(2, 12, rows, cols, B.MODE_CSR, 32, 0, B.F32), "deficit")
+
+
+def test_data_errors():
+    n = 4096
+    p = B.make_params(8, 12, n, 1, B.MODE_DENSE, 32, 0, B.F32)
+    codec = B.Codec(p, n)
+    for bad in (float("nan"), float("inf"), float("-inf")):
+        x = _relu_normal(n, 1)
+        x[77] = bad
+        with pytest.raises(B.RansError) as e:
+            codec.compress(x.cuda())
+        assert e.value.code == B.ERR_NONFINITE
+        assert int(codec.nbytes.item()) == 0
+    x = torch.tensor([-3e38, 3e38] * 2048)
+    with pytest.raises(B.RansError) as e:
+        codec.compress(x.cuda())
+    assert e.value.code == B.ERR_NONFINITE
+    # a good call afterwards works again
+    x = _relu_normal(n, 2)
+    ref, _ = oracle.compress(x.numpy(), _oparams(p))
+    assert codec.container(codec.compress(x.cuda())) == ref
+    # too many distinct symbols for 2^M
+    p4 = B.make_params(8, 4, n, 1, B.MODE_DENSE, 32, 0, B.F32)
+    c4 = B.Codec(p4, n)
+    with pytest.raises(B.RansError) as e:
+        c4.compress(x.cuda())
+    assert e.value.code == B.ERR_ALPHABET
+    # the literal "rows = 256" reshape of the ResNet-style workload has K + 1 > 65536
+    rc, _, _ = B.rans_workspace_bytes(B.make_params(8, 12, 256, 100352, B.MODE_CSR, 1024, 0, B.F32), 256 * 100352)
+    assert rc == B.ERR_ALPHABET
+    # capacity
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    rc = B.rans_compress(x.cuda(), n, p, small, codec.nbytes, codec.ws)
+    assert rc == 0 and B.rans_last_status(codec.ws) == B.ERR_CAPACITY and int(codec.nbytes.item()) == 0
+    # caller-provided symbols outside {0..2^Q-1}
+    p2 = B.make_params(2, 12, n, 1, B.MODE_DENSE, 32, 0, B.F32)
+    c2 = B.Codec(p2, n)
+    sym = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+    rc = B.rans_encode(sym, n, p2, c2.qinfo, c2.stream, c2.nbytes, c2.ws)
+    assert rc == 0 and B.rans_last_status(c2.ws) == B.ERR_ARG
+    # host-side argument errors
+    assert B.rans_compress(x.cuda(), n, p, codec.stream, codec.nbytes, codec.ws[:1024]) == B.ERR_WORKSPACE
+    assert B.rans_compress(x.cuda(), n, p, codec.stream[1:], codec.nbytes, codec.ws) == B.ERR_ARG
+    assert B.rans_compress(x.cuda(), n, p, None, codec.nbytes, codec.ws) == B.ERR_ARG
+
+
+@pytest.mark.parametrize("name,shrink,over", [
+    ("c1", 1, {}),
+    ("c1", 1, dict(mode=1)),
+    ("c1", 1, dict(mode=1, cols=7, chunk_syms=32 * 128)),
+    ("c1", 1, dict(chunk_syms=32 * 64)),
+    ("c2", 32, {}),
+    ("c2", 32, dict(mode=1)),
+    ("c3", 64, dict(mode=1)),
+    ("c3", 64, dict(q_bits=6, mode=1, cols=64)),
+    ("c3", 64, dict(q_bits=6)),
+    ("c4", 8, {}),
+    ("c5a", 32, {}),
+    ("c5b", 32, dict(chunk_syms=1 << 20)),
+])
+def test_synthetic_workloads(name, shrink, over):
+    w = synth.workload(name, shrink, **over)
+    x = synth.make(w)
+    nbytes = _check_all(x, B.params_of(w), f"{name}/{shrink} {over}")
+    assert nbytes < x.numel() * x.element_size()
+
+
+def test_full_size_llama_config_in_bench_configuration():
+    """The configuration bench.py times (c5a: fp16 8x2048x4096, Q=8, M=14, S=1024), whole container compared."""
+    w = synth.workload("c5a", 1)
+    x = synth.make(w)
+    p = B.params_of(w)
+    print("[case] c5a full size", flush=True)
+    ref, sym_ref = oracle.compress(x.numpy(), _oparams(p))
+    codec = B.Codec(p, w.numel)
+    nbytes = codec.compress(x.cuda())
+    assert nbytes == len(ref)
+    got = codec.stream[:nbytes].cpu().numpy()
+    assert np.array_equal(got, np.frombuffer(ref, np.uint8))
+    hdr = codec.header(nbytes)
+    out = torch.empty(w.numel, dtype=torch.float16, device="cuda")
+    codec.decompress(nbytes, hdr, out)
+    _, qi = oracle.quantize(x.numpy()[:1], 8)  # placeholder for the struct type
+    qi = oracle.qinfo_from_minmax(hdr.x_min, hdr.x_max, 8)
+    y_ref = oracle.dequantize(sym_ref, qi, oracle.F16)
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), y_ref.view(np.uint16))

@@ -230,6 +230,16 @@ __device__ __forceinline__ uint32_t quant1(float x, float s, float zf, float lev
   return (uint32_t)r;
 }
 
+// Eq. 6: z = round_half_even(-x_min / s), kept as an integer-valued float.  The
+// result is built so that a zero is always +0.0: the backend may turn 0 - x into a
+// sign flip, which would make z = -0.0 for x_min = +0.0.
+__device__ __forceinline__ float eq6_zero_point(float x_min, float s) {
+  if (!(s != 0.0f)) return 0.0f;
+  float zf = rintf((0.0f - x_min) / s);
+  uint32_t b = __float_as_uint(zf);
+  return __uint_as_float(b == 0x80000000u ? 0u : b);
+}
+
 // ------------------------------------------------------------------ kernels: set-up
 
 __global__ void k_init(Ctl *ctl, uint32_t *cnt, uint32_t A, uint32_t *chunk_words, uint32_t nc) {
@@ -321,11 +331,7 @@ __global__ void k_qinfo(Ctl *ctl, uint32_t q_bits, uint32_t n, rans_qinfo *out) 
   float range = mx - mn;
   float levels = (float)((1u << q_bits) - 1u);
   float s = range / levels;
-  float zf = 0.0f;
-  if (s != 0.0f) {
-    float neg_min = 0.0f - mn;
-    zf = rintf(neg_min / s);
-  }
+  float zf = eq6_zero_point(mn, s);
   bool bad = ctl->nonfinite || !(fabsf(range) < INFINITY);
   if (bad) {
     set_status(ctl, RANS_ERR_NONFINITE);
@@ -353,8 +359,7 @@ __global__ void k_qinfo_from_user(Ctl *ctl, const rans_qinfo *in, uint32_t q_bit
   if (bad) set_status(ctl, RANS_ERR_NONFINITE);
   float levels = (float)((1u << q_bits) - 1u);
   float s = range / levels;
-  float zf = 0.0f;
-  if (s != 0.0f) zf = rintf((0.0f - mn) / s);
+  float zf = eq6_zero_point(mn, s);
   ctl->x_min = mn + 0.0f;
   ctl->x_max = mx + 0.0f;
   ctl->scale = s;
@@ -876,8 +881,7 @@ __global__ __launch_bounds__(kBig) void k_dec_prepare(const uint8_t *in, uint64_
     float mn = h.x_min, mx = h.x_max;
     float range = mx - mn;
     float s = range / (float)((1u << h.p.q_bits) - 1u);
-    float zf = 0.0f;
-    if (s != 0.0f) zf = rintf((0.0f - mn) / s);
+    float zf = eq6_zero_point(mn, s);
     ctl->x_min = mn;
     ctl->x_max = mx;
     ctl->scale = s;

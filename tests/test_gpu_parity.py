@@ -233,7 +233,11 @@ def test_data_errors():
     # host-side argument errors
     assert B.rans_compress(x.cuda(), n, p, codec.stream, codec.nbytes, codec.ws[:1024]) == B.ERR_WORKSPACE
     assert B.rans_compress(x.cuda(), n, p, codec.stream[1:], codec.nbytes, codec.ws) == B.ERR_ARG
-    assert B.rans_compress(x.cuda(), n, p, None, codec.nbytes, codec.ws) == B.ERR_ARG
+    import ctypes as C
+    rc = B.lib().rans_compress(C.c_void_p(x.cuda().data_ptr()), n, C.byref(p), None, 1 << 20,
+                               C.c_void_p(codec.nbytes.data_ptr()), C.c_void_p(codec.ws.data_ptr()),
+                               codec.ws.numel(), None)
+    assert rc == B.ERR_ARG
 
 
 @pytest.mark.parametrize("name,shrink,over", [

@@ -63,7 +63,9 @@ class Header(C.Structure):
 
 
 EXPORTS = ("rans_workspace_bytes", "rans_quantize", "rans_encode", "rans_decode", "rans_dequantize",
-           "rans_compress", "rans_decompress", "rans_peek_header", "rans_last_status", "rans_strerror")
+           "rans_compress", "rans_decompress", "rans_peek_header", "rans_last_status",
+           "rans_profile_enable", "rans_profile_reset", "rans_profile_read",
+           "rans_strerror", "rans_profile_kernel_name")
 
 _lib = None
 
@@ -88,7 +90,12 @@ def lib() -> C.CDLL:
         L.rans_last_status.argtypes = [vp, vp]
         L.rans_strerror.argtypes = [C.c_int]
         L.rans_strerror.restype = C.c_char_p
-        for name in EXPORTS[:-1]:
+        L.rans_profile_enable.argtypes = [u64]
+        L.rans_profile_reset.argtypes = []
+        L.rans_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(u64)]
+        L.rans_profile_kernel_name.argtypes = [C.c_int]
+        L.rans_profile_kernel_name.restype = C.c_char_p
+        for name in EXPORTS[:-2]:
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -169,6 +176,42 @@ def rans_last_status(d_ws) -> int:
 
 def rans_strerror(code: int) -> str:
     return lib().rans_strerror(code).decode()
+
+
+def profile_kernel_names():
+    names, i = [], 0
+    while True:
+        nm = lib().rans_profile_kernel_name(i)
+        if nm is None:
+            return names
+        names.append(nm.decode())
+        i += 1
+
+
+def rans_profile_enable(kernels="all") -> int:
+    """kernels: "all", an iterable of kernel names, or a falsy value to switch recording off."""
+    if not kernels:
+        return lib().rans_profile_enable(0)
+    names = profile_kernel_names()
+    mask = (1 << len(names)) - 1 if kernels == "all" else sum(1 << names.index(k) for k in kernels)
+    return lib().rans_profile_enable(mask)
+
+
+def rans_profile_reset() -> int:
+    return lib().rans_profile_reset()
+
+
+def rans_profile_read() -> dict:
+    """{kernel name: {"total_ms": float, "count": int}} for kernels with at least one record (synchronises)."""
+    out = {}
+    for i, nm in enumerate(profile_kernel_names()):
+        ms, cnt = C.c_double(), C.c_uint64()
+        rc = lib().rans_profile_read(i, C.byref(ms), C.byref(cnt))
+        if rc:
+            raise RansError(rc)
+        if cnt.value:
+            out[nm] = {"total_ms": ms.value, "count": cnt.value}
+    return out
 
 
 # ------------------------------------------------------------------ buffer holder

@@ -17,6 +17,8 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
+#include <vector>
 
 #include "rans_if.h"
 
@@ -1128,7 +1130,64 @@ __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *sym, uint64_t n,
   }
 }
 
+// ------------------------------------------------------------------ instrumentation
+
+// Optional per-kernel timing for benchmarks: when a kernel's bit is set in the
+// mask, each of its launches is bracketed by a pair of HIP events recorded on the
+// launch stream.  Off by default; the normal path records nothing.
+enum KernelId {
+  KID_INIT = 0, KID_MINMAX, KID_QINFO, KID_QUANT_HIST, KID_CSR_COUNT, KID_SCAN, KID_CSR_COMPACT, KID_CSR_ROWS,
+  KID_NORMALIZE, KID_ENCODE, KID_CHUNK_SCAN, KID_GATHER, KID_DEC_PREPARE, KID_DECODE, KID_FILL, KID_ROW_SCAN,
+  KID_CSR_EXPAND, KID_DEQUANT, KID_COUNT
+};
+const char *const kKernelNames[KID_COUNT] = {
+    "k_init", "k_minmax", "k_qinfo", "k_quant_hist", "k_csr_count", "k_scan_u32", "k_csr_compact", "k_csr_rows",
+    "k_normalize", "k_encode", "k_chunk_scan", "k_gather", "k_dec_prepare", "k_decode", "k_fill", "k_row_scan",
+    "k_csr_expand", "k_dequant"};
+
+struct ProfRecord {
+  int kid;
+  hipEvent_t a, b;
+};
+struct Profiler {
+  uint64_t mask = 0;
+  std::vector<ProfRecord> recs;   // records in use
+  std::vector<ProfRecord> pool;   // event pairs ready for reuse
+  std::mutex mu;
+};
+Profiler g_prof;
+
+struct ProfScope {
+  ProfRecord r{-1, nullptr, nullptr};
+  hipStream_t st;
+  ProfScope(int kid, hipStream_t s) : st(s) {
+    if (!((g_prof.mask >> kid) & 1)) return;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    if (!g_prof.pool.empty()) {
+      r = g_prof.pool.back();
+      g_prof.pool.pop_back();
+    } else if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) {
+      return;
+    }
+    r.kid = kid;
+    (void)hipEventRecord(r.a, st);
+  }
+  ~ProfScope() {
+    if (r.kid < 0) return;
+    (void)hipEventRecord(r.b, st);
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    g_prof.recs.push_back(r);
+  }
+};
+
 // ------------------------------------------------------------------ host side
+
+// Launch with optional event bracketing; the stream is always the 5th macro argument.
+#define PROF_LAUNCH(KID, KERNEL, GRID, BLOCK, LDS, STREAM, ...)            \
+  do {                                                                     \
+    ProfScope prof_scope_(KID, STREAM);                                    \
+    hipLaunchKernelGGL(KERNEL, GRID, BLOCK, LDS, STREAM, __VA_ARGS__);     \
+  } while (0)
 
 #define LAUNCH_CHECK()                                  \
   do {                                                  \
@@ -1145,7 +1204,7 @@ inline uint32_t grid_for(uint64_t n, uint32_t per_block, uint32_t cap) {
 
 int launch_init(const Layout &L, uint8_t *ws, hipStream_t st) {
   uint32_t work = L.A > L.nc_max + 1 ? L.A : L.nc_max + 1;
-  hipLaunchKernelGGL(k_init, dim3(grid_for(work, kWG, 1024)), dim3(kWG), 0, st, (Ctl *)(ws + L.ctl),
+  PROF_LAUNCH(KID_INIT, k_init, dim3(grid_for(work, kWG, 1024)), dim3(kWG), 0, st, (Ctl *)(ws + L.ctl),
                      (uint32_t *)(ws + L.cnt), L.A, (uint32_t *)(ws + L.chunk_words), L.nc_max);
   LAUNCH_CHECK();
   return RANS_OK;
@@ -1162,26 +1221,26 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
   if (n) {
     uint32_t g = grid_for(n, kWG * V * 4, 2048);
     if (f16) {
-      if (vec) hipLaunchKernelGGL((k_minmax<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl);
-      else hipLaunchKernelGGL((k_minmax<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl);
+      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl);
+      else PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl);
     } else {
-      if (vec) hipLaunchKernelGGL((k_minmax<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl);
-      else hipLaunchKernelGGL((k_minmax<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl);
+      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl);
+      else PROF_LAUNCH(KID_MINMAX, (k_minmax<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl);
     }
     LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(k_qinfo, dim3(1), dim3(64), 0, st, ctl, p.q_bits, (uint32_t)n, d_qinfo);
+  PROF_LAUNCH(KID_QINFO, k_qinfo, dim3(1), dim3(64), 0, st, ctl, p.q_bits, (uint32_t)n, d_qinfo);
   LAUNCH_CHECK();
   if (n) {
     uint32_t tile = kWG * V * kQIter;
     uint32_t g = (uint32_t)((n + tile - 1) / tile);
     int skip0 = p.mode == RANS_MODE_CSR;
     if (f16) {
-      if (vec) hipLaunchKernelGGL((k_quant_hist<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
-      else hipLaunchKernelGGL((k_quant_hist<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+      if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+      else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
     } else {
-      if (vec) hipLaunchKernelGGL((k_quant_hist<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
-      else hipLaunchKernelGGL((k_quant_hist<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+      if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+      else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
     }
     LAUNCH_CHECK();
   }
@@ -1201,27 +1260,27 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     uint32_t *blk = (uint32_t *)(ws + L.blk_nnz);
     uint32_t *row_end = (uint32_t *)(ws + L.row_end);
     if (n) {
-      hipLaunchKernelGGL(k_csr_count, dim3(L.n_blk), dim3(kWG), 0, st, d_sym, (uint32_t)n, al, blk);
+      PROF_LAUNCH(KID_CSR_COUNT, k_csr_count, dim3(L.n_blk), dim3(kWG), 0, st, d_sym, (uint32_t)n, al, blk);
       LAUNCH_CHECK();
-      hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(kBig), 0, st, blk, L.n_blk);
+      PROF_LAUNCH(KID_SCAN, k_scan_u32, dim3(1), dim3(kBig), 0, st, blk, L.n_blk);
       LAUNCH_CHECK();
       if (lds_hist)
-        hipLaunchKernelGGL((k_csr_compact<true>), dim3(L.n_blk), dim3(kWG), A * 4, st, d_sym, (uint32_t)n, al,
+        PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true>), dim3(L.n_blk), dim3(kWG), A * 4, st, d_sym, (uint32_t)n, al,
                            (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A);
       else
-        hipLaunchKernelGGL((k_csr_compact<false>), dim3(L.n_blk), dim3(kWG), 0, st, d_sym, (uint32_t)n, al,
+        PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<false>), dim3(L.n_blk), dim3(kWG), 0, st, d_sym, (uint32_t)n, al,
                            (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A);
       LAUNCH_CHECK();
       uint32_t N = (uint32_t)p.rows;
       uint32_t g = (N + kWG - 1) / kWG;
       if (lds_hist)
-        hipLaunchKernelGGL((k_csr_rows<true>), dim3(g), dim3(kWG), A * 4, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl);
+        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<true>), dim3(g), dim3(kWG), A * 4, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl);
       else
-        hipLaunchKernelGGL((k_csr_rows<false>), dim3(g), dim3(kWG), 0, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl);
+        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<false>), dim3(g), dim3(kWG), 0, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl);
       LAUNCH_CHECK();
     }
   }
-  hipLaunchKernelGGL(k_normalize, dim3(1), dim3(kBig), 0, st, ctl, cnt, (uint32_t *)(ws + L.fq),
+  PROF_LAUNCH(KID_NORMALIZE, k_normalize, dim3(1), dim3(kBig), 0, st, ctl, cnt, (uint32_t *)(ws + L.fq),
                      (uint2 *)(ws + L.enc_tab), A, p, n, csr ? 0 : 1, d_stream, (uint64_t)cap);
   LAUNCH_CHECK();
   const uint32_t groups = (S + kWG - 1) / kWG;
@@ -1235,20 +1294,20 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     if (csr) {
       SrcCsr src{ws + L.v, (const uint16_t *)(ws + L.c), (const uint16_t *)(ws + L.r), 0};
       if (lds_tab)
-        hipLaunchKernelGGL((k_encode<SrcCsr, true>), dim3(g), dim3(kWG), A * 8, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups);
+        PROF_LAUNCH(KID_ENCODE, (k_encode<SrcCsr, true>), dim3(g), dim3(kWG), A * 8, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups);
       else
-        hipLaunchKernelGGL((k_encode<SrcCsr, false>), dim3(g), dim3(kWG), 0, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups);
+        PROF_LAUNCH(KID_ENCODE, (k_encode<SrcCsr, false>), dim3(g), dim3(kWG), 0, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups);
     } else {
       SrcDense src{d_sym};
-      hipLaunchKernelGGL((k_encode<SrcDense, true>), dim3(g), dim3(kWG), A * 8, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups);
+      PROF_LAUNCH(KID_ENCODE, (k_encode<SrcDense, true>), dim3(g), dim3(kWG), A * 8, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups);
     }
     LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(k_chunk_scan, dim3(1), dim3(kBig), 0, st, ctl, (uint32_t *)(ws + L.chunk_words), S, d_stream,
+  PROF_LAUNCH(KID_CHUNK_SCAN, k_chunk_scan, dim3(1), dim3(kBig), 0, st, ctl, (uint32_t *)(ws + L.chunk_words), S, d_stream,
                      (uint64_t)cap, d_stream_bytes);
   LAUNCH_CHECK();
   if (L.nc_max) {
-    hipLaunchKernelGGL(k_gather, dim3(L.nc_max * groups), dim3(kWG), 0, st, ctl, (const uint16_t *)(ws + L.scratch),
+    PROF_LAUNCH(KID_GATHER, k_gather, dim3(L.nc_max * groups), dim3(kWG), 0, st, ctl, (const uint16_t *)(ws + L.scratch),
                        L.capw, (const uint32_t *)(ws + L.st), (const uint32_t *)(ws + L.nw), S, groups, d_stream);
     LAUNCH_CHECK();
   }
@@ -1340,7 +1399,7 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
   Ctl *ctl = (Ctl *)(ws + L.ctl);
   uint16_t *lut = (uint16_t *)(ws + L.dec_lut);
   uint32_t *tab = (uint32_t *)(ws + L.dec_tab);
-  hipLaunchKernelGGL(k_dec_prepare, dim3(1), dim3(kBig), 0, st, d_stream, (uint64_t)stream_bytes, ctl, h, lut, tab,
+  PROF_LAUNCH(KID_DEC_PREPARE, k_dec_prepare, dim3(1), dim3(kBig), 0, st, d_stream, (uint64_t)stream_bytes, ctl, h, lut, tab,
                      (uint32_t *)(ws + L.dec_F), d_qinfo);
   LAUNCH_CHECK();
   const uint32_t groups = (S + kWG - 1) / kWG;
@@ -1352,10 +1411,10 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
 #define DEC_LAUNCH(SINKT, sinkv)                                                                                   \
   do {                                                                                                             \
     if (lds_tab)                                                                                                   \
-      hipLaunchKernelGGL((k_decode<SINKT, true>), grid, blk, lds, st, d_stream, (uint64_t)stream_bytes, ctl, lut,   \
+      PROF_LAUNCH(KID_DECODE, (k_decode<SINKT, true>), grid, blk, lds, st, d_stream, (uint64_t)stream_bytes, ctl, lut,   \
                          tab, A, M, S, h.p.chunk_syms, groups, sinkv);                                             \
     else                                                                                                           \
-      hipLaunchKernelGGL((k_decode<SINKT, false>), grid, blk, 0, st, d_stream, (uint64_t)stream_bytes, ctl, lut,    \
+      PROF_LAUNCH(KID_DECODE, (k_decode<SINKT, false>), grid, blk, 0, st, d_stream, (uint64_t)stream_bytes, ctl, lut,    \
                          tab, A, M, S, h.p.chunk_syms, groups, sinkv);                                             \
   } while (0)
     if (csr) {
@@ -1380,20 +1439,20 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
     uint8_t *xhat = out_kind == 0 ? (uint8_t *)d_out : ws + L.dec_sym;
     uint32_t *row_off = (uint32_t *)(ws + L.row_off);
     const uint16_t *D = (const uint16_t *)(ws + L.D);
-    hipLaunchKernelGGL((k_fill<uint8_t>), dim3(grid_for(n, kWG * 16, 4096)), dim3(kWG), 0, st, xhat, n, (uint8_t)0);
+    PROF_LAUNCH(KID_FILL, (k_fill<uint8_t>), dim3(grid_for(n, kWG * 16, 4096)), dim3(kWG), 0, st, xhat, n, (uint8_t)0);
     LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_row_scan, dim3(1), dim3(kBig), 0, st, D + 2 * nnz, N, K, row_off, ctl);
+    PROF_LAUNCH(KID_ROW_SCAN, k_row_scan, dim3(1), dim3(kBig), 0, st, D + 2 * nnz, N, K, row_off, ctl);
     LAUNCH_CHECK();
     if (nnz) {
-      hipLaunchKernelGGL(k_csr_expand, dim3((uint32_t)((nnz + kWG - 1) / kWG)), dim3(kWG), 0, st, D, row_off, N, K,
+      PROF_LAUNCH(KID_CSR_EXPAND, k_csr_expand, dim3((uint32_t)((nnz + kWG - 1) / kWG)), dim3(kWG), 0, st, D, row_off, N, K,
                          h.p.q_bits, xhat, ctl);
       LAUNCH_CHECK();
     }
     if (out_kind) {
       const rans_qinfo *qi = (const rans_qinfo *)&ctl->x_min;
       uint32_t g = grid_for(n, kWG * 8, 8192);
-      if (out_kind == 1) hipLaunchKernelGGL((k_dequant<float>), dim3(g), dim3(kWG), 0, st, xhat, n, qi, ctl, (float *)d_out);
-      else hipLaunchKernelGGL((k_dequant<__half>), dim3(g), dim3(kWG), 0, st, xhat, n, qi, ctl, (__half *)d_out);
+      if (out_kind == 1) PROF_LAUNCH(KID_DEQUANT, (k_dequant<float>), dim3(g), dim3(kWG), 0, st, xhat, n, qi, ctl, (float *)d_out);
+      else PROF_LAUNCH(KID_DEQUANT, (k_dequant<__half>), dim3(g), dim3(kWG), 0, st, xhat, n, qi, ctl, (__half *)d_out);
       LAUNCH_CHECK();
     }
   }
@@ -1443,7 +1502,7 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
   Ctl *ctl = (Ctl *)(ws + L.ctl);
   rc = launch_init(L, ws, st);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_qinfo_from_user, dim3(1), dim3(64), 0, st, ctl, d_qinfo, p->q_bits);
+  PROF_LAUNCH(KID_QINFO, k_qinfo_from_user, dim3(1), dim3(64), 0, st, ctl, d_qinfo, p->q_bits);
   LAUNCH_CHECK();
   if (n_elems) {
     const bool vec = aligned_to(d_sym, 16);
@@ -1451,9 +1510,9 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
     const uint32_t g = (uint32_t)((n_elems + tile - 1) / tile);
     const int skip0 = p->mode == RANS_MODE_CSR;
     if (vec)
-      hipLaunchKernelGGL((k_quant_hist<uint8_t, true>), dim3(g), dim3(kWG), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
+      PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, true>), dim3(g), dim3(kWG), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
     else
-      hipLaunchKernelGGL((k_quant_hist<uint8_t, false>), dim3(g), dim3(kWG), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
+      PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, false>), dim3(g), dim3(kWG), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
     LAUNCH_CHECK();
   }
   return launch_encode_tail(d_sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st);
@@ -1500,9 +1559,9 @@ int rans_dequantize(const uint8_t *d_sym, uint64_t n_elems, const rans_qinfo *d_
   hipStream_t st = (hipStream_t)stream;
   uint32_t g = grid_for(n_elems, kWG * 8, 8192);
   if (out_dtype == RANS_F32)
-    hipLaunchKernelGGL((k_dequant<float>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, (const Ctl *)nullptr, (float *)d_x_out);
+    PROF_LAUNCH(KID_DEQUANT, (k_dequant<float>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, (const Ctl *)nullptr, (float *)d_x_out);
   else
-    hipLaunchKernelGGL((k_dequant<__half>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, (const Ctl *)nullptr, (__half *)d_x_out);
+    PROF_LAUNCH(KID_DEQUANT, (k_dequant<__half>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, (const Ctl *)nullptr, (__half *)d_x_out);
   LAUNCH_CHECK();
   return RANS_OK;
 }
@@ -1520,6 +1579,41 @@ int rans_last_status(const void *d_ws, void *stream) {
   if (hipMemcpyAsync(&status, d_ws, sizeof(status), hipMemcpyDeviceToHost, st) != hipSuccess) return RANS_ERR_HIP;
   if (hipStreamSynchronize(st) != hipSuccess) return RANS_ERR_HIP;
   return status;
+}
+
+int rans_profile_enable(uint64_t kernel_mask) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  g_prof.mask = kernel_mask;
+  return RANS_OK;
+}
+
+int rans_profile_reset(void) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  for (auto &r : g_prof.recs) g_prof.pool.push_back(r);
+  g_prof.recs.clear();
+  return RANS_OK;
+}
+
+const char *rans_profile_kernel_name(int kernel_id) {
+  return (kernel_id >= 0 && kernel_id < KID_COUNT) ? kKernelNames[kernel_id] : nullptr;
+}
+
+int rans_profile_read(int kernel_id, double *total_ms, uint64_t *count) {
+  if (kernel_id < 0 || kernel_id >= KID_COUNT || !total_ms || !count) return RANS_ERR_ARG;
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  double tot = 0;
+  uint64_t n = 0;
+  for (auto &r : g_prof.recs) {
+    if (r.kid != kernel_id) continue;
+    if (hipEventSynchronize(r.b) != hipSuccess) return RANS_ERR_HIP;
+    float ms = 0;
+    if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return RANS_ERR_HIP;
+    tot += ms;
+    n++;
+  }
+  *total_ms = tot;
+  *count = n;
+  return RANS_OK;
 }
 
 const char *rans_strerror(int code) {

@@ -30,6 +30,7 @@ constexpr int kBig = 1024;              // threads of the single-work-group kern
 constexpr uint32_t kHdrBytes = 128;
 constexpr uint32_t kLdsHistMaxA = 8192; // alphabets up to this size keep histograms / tables in LDS
 constexpr uint64_t kMaxElems = 1ull << 30;
+constexpr uint32_t kMaxParts = 1024;    // work-groups (partial results) of the min/max kernel
 
 // ------------------------------------------------------------------ workspace
 
@@ -50,7 +51,7 @@ struct Layout {
   // common
   size_t ctl;
   // encode side
-  size_t cnt, fq, enc_tab, sym, v, c, r, row_end, blk_nnz, st, nw, chunk_words, scratch;
+  size_t mm_part, cnt, fq, enc_tab, sym, v, c, r, row_end, blk_nnz, st, nw, chunk_words, scratch;
   // decode side (overlays the encode side from `sym` on)
   size_t dec_lut, dec_tab, dec_F, D, row_off, dec_sym;
   size_t total;
@@ -103,6 +104,7 @@ Layout make_layout(const rans_params &p, uint64_t n) {
     return at;
   };
   L.ctl = take(sizeof(Ctl));
+  L.mm_part = take(kMaxParts * 16);
   L.cnt = take((size_t)L.A * 4);
   L.fq = take((size_t)L.A * 4);
   L.enc_tab = take((size_t)L.A * 8);
@@ -244,22 +246,6 @@ __device__ __forceinline__ float eq6_zero_point(float x_min, float s) {
 
 // ------------------------------------------------------------------ kernels: set-up
 
-__global__ void k_init(Ctl *ctl, uint32_t *cnt, uint32_t A, uint32_t *chunk_words, uint32_t nc) {
-  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
-  if (i == 0) {
-    ctl->status = 0;
-    ctl->min_key = 0xffffffffu;
-    ctl->max_key = 0u;
-    ctl->nonfinite = 0;
-    ctl->len_d = 0;
-    ctl->payload_off = ctl->dir_off = ctl->total_bytes = 0;
-    ctl->nnz = 0;
-    ctl->n_chunks = 0;
-  }
-  for (uint32_t a = i; a < A; a += stride) cnt[a] = 0;
-  for (uint32_t k = i; k <= nc; k += stride) chunk_words[k] = 0;
-}
-
 template <typename T>
 __global__ void k_fill(T *p, uint64_t n, T val) {
   uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (uint64_t)gridDim.x * blockDim.x;
@@ -268,12 +254,21 @@ __global__ void k_fill(T *p, uint64_t n, T val) {
 
 // ------------------------------------------------------------------ kernels: Eq. 6
 
-// Global extrema.  Each lane keeps a running min / max over 16-byte vector loads,
-// the wave folds them with cross-lane shuffles, and one lane per wave issues a pair
-// of integer atomics on order-preserving keys.
+// Partial extrema of one work-group of k_minmax.
+struct MinMaxPart {
+  float mn, mx;
+  uint32_t bad, pad;
+};
+
+// Global extrema, first stage.  Each lane keeps a running min / max over 16-byte
+// vector loads (four independent loads in flight per lane), the wave folds them
+// with cross-lane shuffles, the work-group through LDS, and one lane writes the
+// group's partial result.  No atomics: thousands of same-address atomics cost more
+// than reading the tensor.
 template <typename T, bool VEC>
-__global__ __launch_bounds__(kWG) void k_minmax(const T *x, uint32_t n, Ctl *ctl) {
+__global__ __launch_bounds__(kWG) void k_minmax(const T *x, uint32_t n, MinMaxPart *part) {
   constexpr int V = VEC ? (int)(16 / sizeof(T)) : 1;
+  constexpr int U = 4;
   float mn = INFINITY, mx = -INFINITY;
   uint32_t bad = 0;
   auto take = [&](float v) {
@@ -281,31 +276,54 @@ __global__ __launch_bounds__(kWG) void k_minmax(const T *x, uint32_t n, Ctl *ctl
     mn = fminf(mn, v);
     mx = fmaxf(mx, v);
   };
-  uint32_t nvec = n / V;
-  uint32_t stride = gridDim.x * blockDim.x;
-  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
+  auto take_vec = [&](uint32_t i) {
     if constexpr (!VEC) {
-      if constexpr (sizeof(T) == 4) take(x[i]);
+      if constexpr (sizeof(T) == 4) take(((const float *)x)[i]);
       else take(half_bits_to_float(((const uint16_t *)x)[i]));
-    } else if constexpr (sizeof(T) == 4) {
-      float4 q = ((const float4 *)x)[i];
-      take(q.x); take(q.y); take(q.z); take(q.w);
-    } else {
+    }
+  };
+  const uint32_t nvec = n / V;
+  const uint32_t stride = gridDim.x * blockDim.x;
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if constexpr (VEC) {
+    for (; (uint64_t)i + (uint64_t)(U - 1) * stride < nvec; i += U * stride) {
+      uint4 q[U];
+#pragma unroll
+      for (int u = 0; u < U; u++) q[u] = ((const uint4 *)x)[i + u * stride];
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        uint32_t w[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+          if constexpr (sizeof(T) == 4) {
+            take(__uint_as_float(w[k]));
+          } else {
+            take(half_bits_to_float((uint16_t)(w[k] & 0xffffu)));
+            take(half_bits_to_float((uint16_t)(w[k] >> 16)));
+          }
+        }
+      }
+    }
+    for (; i < nvec; i += stride) {
       uint4 q = ((const uint4 *)x)[i];
       uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
       for (int k = 0; k < 4; k++) {
-        take(half_bits_to_float((uint16_t)(w[k] & 0xffffu)));
-        take(half_bits_to_float((uint16_t)(w[k] >> 16)));
+        if constexpr (sizeof(T) == 4) {
+          take(__uint_as_float(w[k]));
+        } else {
+          take(half_bits_to_float((uint16_t)(w[k] & 0xffffu)));
+          take(half_bits_to_float((uint16_t)(w[k] >> 16)));
+        }
       }
     }
-  }
-  if constexpr (VEC) {  // ragged tail
-    uint32_t i = nvec * V + blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) {
-      if constexpr (sizeof(T) == 4) take(((const float *)x)[i]);
-      else take(half_bits_to_float(((const uint16_t *)x)[i]));
+    uint32_t t = nvec * V + blockIdx.x * blockDim.x + threadIdx.x;  // ragged tail, fewer than V elements
+    if (t < n) {
+      if constexpr (sizeof(T) == 4) take(((const float *)x)[t]);
+      else take(half_bits_to_float(((const uint16_t *)x)[t]));
     }
+  } else {
+    for (; i < nvec; i += stride) take_vec(i);
   }
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) {
@@ -313,29 +331,81 @@ __global__ __launch_bounds__(kWG) void k_minmax(const T *x, uint32_t n, Ctl *ctl
     mx = fmaxf(mx, __shfl_xor(mx, d));
     bad |= __shfl_xor(bad, d);
   }
+  __shared__ float s_mn[kWG / 64], s_mx[kWG / 64];
+  __shared__ uint32_t s_bad[kWG / 64];
   if ((threadIdx.x & 63) == 0) {
-    if (bad) atomicOr(&ctl->nonfinite, 1u);
-    if (mn <= mx) {  // false only when the lane group saw no element
-      atomicMin(&ctl->min_key, f2key(mn));
-      atomicMax(&ctl->max_key, f2key(mx));
+    s_mn[threadIdx.x >> 6] = mn;
+    s_mx[threadIdx.x >> 6] = mx;
+    s_bad[threadIdx.x >> 6] = bad;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kWG / 64; w++) {
+      mn = fminf(mn, s_mn[w]);
+      mx = fmaxf(mx, s_mx[w]);
+      bad |= s_bad[w];
     }
+    part[blockIdx.x] = MinMaxPart{mn, mx, bad, 0u};
   }
 }
 
-// Scale and zero point from the extrema (Eq. 6), one thread.
-__global__ void k_qinfo(Ctl *ctl, uint32_t q_bits, uint32_t n, rans_qinfo *out) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  float mn = 0.0f, mx = 0.0f;
-  if (n) {
-    mn = key2f(ctl->min_key) + 0.0f;  // -0.0 becomes +0.0
-    mx = key2f(ctl->max_key) + 0.0f;
+// Start-of-call bookkeeping shared by the two kernels below: reset the control
+// block, clear the histogram and the per-chunk word counters.
+__device__ void reset_call_state(Ctl *ctl, uint32_t *cnt, uint32_t A, uint32_t *chunk_words, uint32_t nc) {
+  if (threadIdx.x == 0) {
+    ctl->status = 0;
+    ctl->len_d = 0;
+    ctl->payload_off = ctl->dir_off = ctl->total_bytes = 0;
+    ctl->nnz = 0;
+    ctl->n_chunks = 0;
   }
+  for (uint32_t a = threadIdx.x; a < A; a += blockDim.x) cnt[a] = 0;
+  for (uint32_t k = threadIdx.x; k <= nc; k += blockDim.x) chunk_words[k] = 0;
+  __syncthreads();
+}
+
+// Second stage of the extrema, then scale and zero point (Eq. 6).  One work-group.
+__global__ __launch_bounds__(kBig) void k_qinfo(Ctl *ctl, const MinMaxPart *part, uint32_t n_part, uint32_t q_bits,
+                                                rans_qinfo *out, uint32_t *cnt, uint32_t A, uint32_t *chunk_words,
+                                                uint32_t nc) {
+  reset_call_state(ctl, cnt, A, chunk_words, nc);
+  float mn = INFINITY, mx = -INFINITY;
+  uint32_t bad = 0;
+  for (uint32_t i = threadIdx.x; i < n_part; i += kBig) {
+    MinMaxPart q = part[i];
+    mn = fminf(mn, q.mn);
+    mx = fmaxf(mx, q.mx);
+    bad |= q.bad;
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    mn = fminf(mn, __shfl_xor(mn, d));
+    mx = fmaxf(mx, __shfl_xor(mx, d));
+    bad |= __shfl_xor(bad, d);
+  }
+  __shared__ float s_mn[kBig / 64], s_mx[kBig / 64];
+  __shared__ uint32_t s_bad[kBig / 64];
+  if ((threadIdx.x & 63) == 0) {
+    s_mn[threadIdx.x >> 6] = mn;
+    s_mx[threadIdx.x >> 6] = mx;
+    s_bad[threadIdx.x >> 6] = bad;
+  }
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  for (int w = 1; w < kBig / 64; w++) {
+    mn = fminf(mn, s_mn[w]);
+    mx = fmaxf(mx, s_mx[w]);
+    bad |= s_bad[w];
+  }
+  if (n_part == 0) mn = mx = 0.0f;  // empty tensor
+  mn = mn + 0.0f;                    // -0.0 becomes +0.0
+  mx = mx + 0.0f;
   float range = mx - mn;
   float levels = (float)((1u << q_bits) - 1u);
   float s = range / levels;
   float zf = eq6_zero_point(mn, s);
-  bool bad = ctl->nonfinite || !(fabsf(range) < INFINITY);
-  if (bad) {
+  if (bad || !(fabsf(range) < INFINITY)) {
     set_status(ctl, RANS_ERR_NONFINITE);
     mn = mx = s = zf = __uint_as_float(0x7fc00000u);
   }
@@ -353,8 +423,11 @@ __global__ void k_qinfo(Ctl *ctl, uint32_t q_bits, uint32_t n, rans_qinfo *out) 
 
 // Copies caller-provided extrema into the control block (rans_encode path) and
 // recomputes s, z from them with the arithmetic of k_qinfo.
-__global__ void k_qinfo_from_user(Ctl *ctl, const rans_qinfo *in, uint32_t q_bits) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+__global__ __launch_bounds__(kBig) void k_qinfo_from_user(Ctl *ctl, const rans_qinfo *in, uint32_t q_bits,
+                                                          uint32_t *cnt, uint32_t A, uint32_t *chunk_words,
+                                                          uint32_t nc) {
+  reset_call_state(ctl, cnt, A, chunk_words, nc);
+  if (threadIdx.x != 0) return;
   float mn = in->x_min, mx = in->x_max;
   float range = mx - mn;
   bool bad = !(fabsf(mn) < INFINITY) || !(fabsf(mx) < INFINITY) || !(fabsf(range) < INFINITY) || mn > mx;
@@ -375,6 +448,7 @@ __global__ void k_qinfo_from_user(Ctl *ctl, const rans_qinfo *in, uint32_t q_bit
 // LDS address.
 constexpr int kHistRep = 8;
 constexpr int kQIter = 4;
+constexpr uint32_t kQuantBlocks = 1024;  // work-groups of the quantise / histogram kernel (persistent over tiles)
 
 template <typename T, bool VEC>
 __global__ __launch_bounds__(kWG) void k_quant_hist(const T *x, uint32_t n, Ctl *ctl, uint32_t q_bits,
@@ -389,9 +463,10 @@ __global__ __launch_bounds__(kWG) void k_quant_hist(const T *x, uint32_t n, Ctl 
   const bool degenerate = !IS_SYM && !(s != 0.0f);  // s == 0 (constant tensor) or NaN (flagged input)
   const uint32_t rep = threadIdx.x & (kHistRep - 1);
   const uint32_t tile = kWG * V * kQIter;
-  const uint64_t base = (uint64_t)blockIdx.x * tile;
   auto q = [&](float v) -> uint32_t { return degenerate ? 0u : quant1(v, s, zf, levels); };
   auto bump = [&](uint32_t a) { atomicAdd(&h[a * kHistRep + rep], 1u); };
+  // a work-group walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... and flushes its histogram once
+  for (uint64_t base = (uint64_t)blockIdx.x * tile; base < n; base += (uint64_t)gridDim.x * tile)
 #pragma unroll
   for (int it = 0; it < kQIter; it++) {
     uint64_t e0 = base + ((uint64_t)it * kWG + threadIdx.x) * V;
@@ -690,29 +765,53 @@ __global__ __launch_bounds__(kBig) void k_normalize(Ctl *ctl, const uint32_t *cn
 
 // ------------------------------------------------------------------ kernels: rANS encode
 
+// Symbol sources for the coder.  fetch<SPL>(i) returns the SPL consecutive symbols
+// D[i..i+SPL) packed into one register, get(raw, q) unpacks symbol q.
 struct SrcDense {
   const uint8_t *sym;
+  static constexpr int kMaxSpl = 4;
   __device__ __forceinline__ void init(const Ctl *) {}
   __device__ __forceinline__ uint32_t operator()(uint64_t i) const { return sym[i]; }
+  template <int SPL>
+  __device__ __forceinline__ uint32_t fetch(uint64_t i) const {
+    if constexpr (SPL == 4) return *(const uint32_t *)(sym + i);
+    else if constexpr (SPL == 2) return *(const uint16_t *)(sym + i);
+    else return sym[i];
+  }
+  __device__ __forceinline__ static uint32_t get(uint32_t raw, int q) { return (raw >> (8 * q)) & 0xffu; }
 };
 // D = v (+) c (+) r (Eq. 7) without materialising the concatenation.
 struct SrcCsr {
   const uint8_t *v;
   const uint16_t *c, *r;
   uint64_t nnz;
+  static constexpr int kMaxSpl = 2;
   __device__ __forceinline__ void init(const Ctl *ctl) { nnz = ctl->nnz; }
   __device__ __forceinline__ uint32_t operator()(uint64_t i) const {
     if (i < nnz) return v[i];
     if (i < 2 * nnz) return c[i - nnz];
     return r[i - 2 * nnz];
   }
+  template <int SPL>
+  __device__ __forceinline__ uint32_t fetch(uint64_t i) const {
+    uint32_t raw = (*this)(i);
+    if constexpr (SPL == 2) raw |= (*this)(i + 1) << 16;
+    return raw;
+  }
+  __device__ __forceinline__ static uint32_t get(uint32_t raw, int q) { return (raw >> (16 * q)) & 0xffffu; }
 };
 
-// One lane per stream.  The stream's symbols are taken last to first; before each
-// Eq. 2 update the state is renormalised by emitting its low 16 bits if it is too
-// large for the symbol.  Words are written downwards from the end of the stream's
-// scratch region, so that they end up in the order the decoder reads them.
-template <class Src, bool LDS_TAB>
+constexpr int kEncAhead = 8;  // rows of symbols fetched ahead of the coder
+
+// Each lane runs SPL adjacent streams, which gives the scheduler SPL independent
+// dependency chains and lets one load fetch a row of SPL symbols.  A stream's
+// symbols are taken last to first; before each Eq. 2 update the state is
+// renormalised by emitting its low 16 bits if it is too large for the symbol.
+// Emitted words are collected four at a time in a register pair and stored as one
+// aligned 8-byte block, downwards from the end of the stream's scratch region, so
+// that they end up in the order the decoder reads them.
+// floor(s / f) comes from a multiply-high with floor(2^32 / f) plus one correction.
+template <class Src, int SPL, bool LDS_TAB, bool MUL24>
 __global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uint32_t A, uint32_t M, uint32_t S,
                                                 uint32_t cs, const Ctl *ctl, uint16_t *scratch, uint32_t capw,
                                                 uint32_t *st_out, uint32_t *nw_out, uint32_t *chunk_words,
@@ -732,32 +831,79 @@ __global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uin
   const uint64_t chunk_len = cs ? cs : len;
   const uint64_t base = (uint64_t)k * chunk_len;
   const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
-  const uint32_t j = g * kWG + threadIdx.x;
-  uint32_t nw = 0;
-  if (j < S) {
-    const uint64_t n_j = n_here > j ? (n_here - j + S - 1) / S : 0;
-    uint16_t *p = scratch + ((uint64_t)k * S + j + 1) * capw;  // one past the end of the region
-    uint32_t s = kL;
-    const uint32_t sh_lim = 32 - M;
-    for (uint64_t t = n_j; t-- > 0;) {
-      uint32_t x = src(base + j + t * S);
-      uint2 e = tab[x];
-      uint32_t f = e.y & 0xffffu, F = e.y >> 16;
-      if ((s >> sh_lim) >= f) {
-        *--p = (uint16_t)s;
-        s >>= 16;
-        nw++;
-      }
-      uint32_t q = __umulhi(s, e.x);
-      uint32_t rem = s - q * f;
-      if (rem >= f) q++;
-      s = s + F + q * ((1u << M) - f);
-    }
-    st_out[(uint64_t)k * S + j] = s;
-    nw_out[(uint64_t)k * S + j] = nw;
+  const uint32_t j0 = (g * kWG + threadIdx.x) * SPL;
+  const bool live = j0 < S;  // S is a multiple of SPL: a lane's streams are all live or all absent
+  const uint32_t sh_lim = 32 - M, totalM = 1u << M;
+  uint32_t s[SPL], nw[SPL], plo[SPL], phi[SPL];
+  uint16_t *p[SPL];
+#pragma unroll
+  for (int i = 0; i < SPL; i++) {
+    s[i] = kL;
+    nw[i] = plo[i] = phi[i] = 0;
+    p[i] = scratch + ((uint64_t)k * S + j0 + i + 1) * capw;  // one past the end of the region, 8-byte aligned
   }
+  auto step = [&](int i, uint32_t x) {
+    uint2 e = tab[x];
+    uint32_t f = e.y & 0xffffu, F = e.y >> 16;
+    if ((s[i] >> sh_lim) >= f) {
+      phi[i] = __builtin_amdgcn_alignbit(phi[i], plo[i], 16);
+      plo[i] = (plo[i] << 16) | (s[i] & 0xffffu);
+      s[i] >>= 16;
+      nw[i]++;
+      if ((nw[i] & 3u) == 0) {
+        p[i] -= 4;
+        *(uint2 *)p[i] = make_uint2(plo[i], phi[i]);
+      }
+    }
+    uint32_t q = __umulhi(s[i], e.x);
+    uint32_t rem = s[i] - (MUL24 ? __umul24(q, f) : q * f);
+    q += rem >= f;
+    s[i] = s[i] + F + (MUL24 ? __umul24(q, totalM - f) : q * (totalM - f));
+  };
+  if (live) {
+    const uint64_t rows_full = n_here / S;
+    const uint32_t rem_row = (uint32_t)(n_here - rows_full * S);
+    if (rem_row) {  // ragged last row: only streams j < rem_row have a symbol there
+#pragma unroll
+      for (int i = 0; i < SPL; i++)
+        if (j0 + i < rem_row) step(i, src(base + rows_full * S + j0 + i));
+    }
+    uint32_t cur[kEncAhead], nxt[kEncAhead];
+    auto fetch_rows = [&](uint32_t *dst, uint64_t t_hi) {  // rows t_hi-1, t_hi-2, ... (uniform bounds)
+#pragma unroll
+      for (int u = 0; u < kEncAhead; u++)
+        if (t_hi > (uint64_t)u) dst[u] = src.template fetch<SPL>(base + (t_hi - 1 - u) * S + j0);
+    };
+    uint64_t t = rows_full;
+    fetch_rows(nxt, t);
+    while (t > 0) {
+#pragma unroll
+      for (int u = 0; u < kEncAhead; u++) cur[u] = nxt[u];
+      const uint64_t t_next = t > kEncAhead ? t - kEncAhead : 0;
+      if (t_next) fetch_rows(nxt, t_next);
+#pragma unroll
+      for (int u = 0; u < kEncAhead; u++) {
+        if (t > (uint64_t)u) {
+#pragma unroll
+          for (int i = 0; i < SPL; i++) step(i, Src::get(cur[u], i));
+        }
+      }
+      t = t_next;
+    }
+#pragma unroll
+    for (int i = 0; i < SPL; i++) {
+      const uint32_t c = nw[i] & 3u;  // words still in the register pair; the newest goes to the lowest address
+      uint16_t *dst = p[i] - c;
+      for (uint32_t q = 0; q < c; q++) dst[q] = (uint16_t)(q < 2 ? plo[i] >> (16 * q) : phi[i] >> (16 * (q - 2)));
+      st_out[(uint64_t)k * S + j0 + i] = s[i];
+      nw_out[(uint64_t)k * S + j0 + i] = nw[i];
+    }
+  }
+  uint32_t mine = 0;
+#pragma unroll
+  for (int i = 0; i < SPL; i++) mine += nw[i];
   uint32_t tot;
-  (void)block_excl_scan<kWG>(nw, sh, &tot);
+  (void)block_excl_scan<kWG>(mine, sh, &tot);
   if (threadIdx.x == 0 && tot) atomicAdd(&chunk_words[k], tot);
 }
 
@@ -814,12 +960,16 @@ __global__ __launch_bounds__(kBig) void k_chunk_scan(Ctl *ctl, uint32_t *chunk_w
 }
 
 // Moves each stream's words from its scratch region to its place in the chunk and
-// writes the chunk header (final states, word counts).
+// writes the chunk header (final states, word counts).  Lanes read their own
+// stream's words, stage them in LDS at their scanned position, and the work-group
+// writes the staged tile out with consecutive lanes on consecutive words.
+constexpr uint32_t kGatherTile = 8192;  // words per LDS tile
 __global__ __launch_bounds__(kWG) void k_gather(const Ctl *ctl, const uint16_t *scratch, uint32_t capw,
                                                 const uint32_t *st, const uint32_t *nw_arr, uint32_t S,
                                                 uint32_t groups, uint8_t *out) {
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
+  __shared__ uint16_t tile[kGatherTile];
   if (ctl->status != 0) return;
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
   if (k >= ctl->n_chunks) return;
@@ -837,11 +987,19 @@ __global__ __launch_bounds__(kWG) void k_gather(const Ctl *ctl, const uint16_t *
   if (j < S) {
     st32(ck + 4ull * j, st[(uint64_t)k * S + j]);
     st32(ck + 4ull * S + 4ull * j, nw);
-    const uint16_t *src = scratch + ((uint64_t)k * S + j + 1) * capw - nw;
-    uint16_t *dst = (uint16_t *)(ck + 8ull * S) + pre + ex;
-    for (uint32_t i = 0; i < nw; i++) dst[i] = src[i];
-    if (j == S - 1 && ((pre + ex + nw) & 1)) dst[nw] = 0;  // pad the chunk to 4 bytes
   }
+  const uint16_t *src = scratch + ((uint64_t)k * S + j + 1) * capw - nw;  // first word in read order
+  uint16_t *dst = (uint16_t *)(ck + 8ull * S) + pre;                       // first word of this group
+  for (uint32_t t0 = 0; t0 < tot; t0 += kGatherTile) {
+    const uint32_t lo = ex > t0 ? ex : t0;
+    const uint32_t hi = ex + nw < t0 + kGatherTile ? ex + nw : t0 + kGatherTile;
+    for (uint32_t w = lo; w < hi; w++) tile[w - t0] = src[w - ex];
+    __syncthreads();
+    const uint32_t cnt = tot - t0 < kGatherTile ? tot - t0 : kGatherTile;
+    for (uint32_t i = threadIdx.x; i < cnt; i += kWG) dst[t0 + i] = tile[i];
+    __syncthreads();
+  }
+  if (j == S - 1 && ((pre + tot) & 1)) dst[tot] = 0;  // pad the chunk to 4 bytes
 }
 
 // ------------------------------------------------------------------ kernels: decode
@@ -1202,14 +1360,6 @@ inline uint32_t grid_for(uint64_t n, uint32_t per_block, uint32_t cap) {
   return (uint32_t)(g > cap ? cap : g);
 }
 
-int launch_init(const Layout &L, uint8_t *ws, hipStream_t st) {
-  uint32_t work = L.A > L.nc_max + 1 ? L.A : L.nc_max + 1;
-  PROF_LAUNCH(KID_INIT, k_init, dim3(grid_for(work, kWG, 1024)), dim3(kWG), 0, st, (Ctl *)(ws + L.ctl),
-                     (uint32_t *)(ws + L.cnt), L.A, (uint32_t *)(ws + L.chunk_words), L.nc_max);
-  LAUNCH_CHECK();
-  return RANS_OK;
-}
-
 // min/max + scale/zero point + quantise/histogram of a float tensor.
 int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Layout &L, uint8_t *ws, uint8_t *d_sym,
                     rans_qinfo *d_qinfo, hipStream_t st) {
@@ -1218,22 +1368,24 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
   const bool f16 = p.in_dtype == RANS_F16;
   const bool vec = aligned_to(d_x, 16) && aligned_to(d_sym, 8);
   const uint32_t V = vec ? (f16 ? 8 : 4) : 1;
+  MinMaxPart *part = (MinMaxPart *)(ws + L.mm_part);
+  uint32_t n_part = 0;
   if (n) {
-    uint32_t g = grid_for(n, kWG * V * 4, 2048);
+    uint32_t g = n_part = grid_for(n, kWG * V * 4, kMaxParts);
     if (f16) {
-      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl);
-      else PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl);
+      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, part);
+      else PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, part);
     } else {
-      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl);
-      else PROF_LAUNCH(KID_MINMAX, (k_minmax<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl);
+      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, part);
+      else PROF_LAUNCH(KID_MINMAX, (k_minmax<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, part);
     }
     LAUNCH_CHECK();
   }
-  PROF_LAUNCH(KID_QINFO, k_qinfo, dim3(1), dim3(64), 0, st, ctl, p.q_bits, (uint32_t)n, d_qinfo);
+  PROF_LAUNCH(KID_QINFO, k_qinfo, dim3(1), dim3(kBig), 0, st, ctl, part, n_part, p.q_bits, d_qinfo, cnt, L.A,
+              (uint32_t *)(ws + L.chunk_words), L.nc_max);
   LAUNCH_CHECK();
   if (n) {
-    uint32_t tile = kWG * V * kQIter;
-    uint32_t g = (uint32_t)((n + tile - 1) / tile);
+    uint32_t g = grid_for(n, kWG * V * kQIter, kQuantBlocks);
     int skip0 = p.mode == RANS_MODE_CSR;
     if (f16) {
       if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
@@ -1285,22 +1437,41 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
   LAUNCH_CHECK();
   const uint32_t groups = (S + kWG - 1) / kWG;
   if (L.nc_max) {
-    uint32_t g = L.nc_max * groups;
     uint16_t *scratch = (uint16_t *)(ws + L.scratch);
     uint32_t *st_arr = (uint32_t *)(ws + L.st), *nw_arr = (uint32_t *)(ws + L.nw);
     uint32_t *cw = (uint32_t *)(ws + L.chunk_words);
     const uint2 *tab = (const uint2 *)(ws + L.enc_tab);
     const bool lds_tab = lds_hist;
+    const bool mul24 = p.freq_bits >= 8;  // then floor(s/f) < 2^24 and both products fit the 24-bit multiplier
+#define ENC_LAUNCH(SRCT, SPLV, LDSV)                                                                              \
+  do {                                                                                                            \
+    const uint32_t groups_e = (S + kWG * SPLV - 1) / (kWG * SPLV);                                                \
+    if (mul24)                                                                                                    \
+      PROF_LAUNCH(KID_ENCODE, (k_encode<SRCT, SPLV, LDSV, true>), dim3(L.nc_max * groups_e), dim3(kWG),            \
+                  LDSV ? A * 8 : 0, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr,   \
+                  nw_arr, cw, groups_e);                                                                          \
+    else                                                                                                          \
+      PROF_LAUNCH(KID_ENCODE, (k_encode<SRCT, SPLV, LDSV, false>), dim3(L.nc_max * groups_e), dim3(kWG),           \
+                  LDSV ? A * 8 : 0, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr,   \
+                  nw_arr, cw, groups_e);                                                                          \
+  } while (0)
     if (csr) {
       SrcCsr src{ws + L.v, (const uint16_t *)(ws + L.c), (const uint16_t *)(ws + L.r), 0};
-      if (lds_tab)
-        PROF_LAUNCH(KID_ENCODE, (k_encode<SrcCsr, true>), dim3(g), dim3(kWG), A * 8, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups);
-      else
-        PROF_LAUNCH(KID_ENCODE, (k_encode<SrcCsr, false>), dim3(g), dim3(kWG), 0, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups);
+      if (S % 2 == 0) {
+        if (lds_tab) ENC_LAUNCH(SrcCsr, 2, true);
+        else ENC_LAUNCH(SrcCsr, 2, false);
+      } else {
+        if (lds_tab) ENC_LAUNCH(SrcCsr, 1, true);
+        else ENC_LAUNCH(SrcCsr, 1, false);
+      }
     } else {
       SrcDense src{d_sym};
-      PROF_LAUNCH(KID_ENCODE, (k_encode<SrcDense, true>), dim3(g), dim3(kWG), A * 8, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups);
+      const bool al4 = aligned_to(d_sym, 4);
+      if (S % 4 == 0 && al4 && S >= 4 * 64) ENC_LAUNCH(SrcDense, 4, true);
+      else if (S % 2 == 0 && al4 && S >= 2 * 64) ENC_LAUNCH(SrcDense, 2, true);
+      else ENC_LAUNCH(SrcDense, 1, true);
     }
+#undef ENC_LAUNCH
     LAUNCH_CHECK();
   }
   PROF_LAUNCH(KID_CHUNK_SCAN, k_chunk_scan, dim3(1), dim3(kBig), 0, st, ctl, (uint32_t *)(ws + L.chunk_words), S, d_stream,
@@ -1483,8 +1654,6 @@ int rans_quantize(const void *d_x, uint64_t n_elems, const rans_params *p, uint8
   if (!aligned_to(d_x, p->in_dtype == RANS_F16 ? 2 : 4) || !aligned_to(d_qinfo, 4)) return RANS_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
   uint8_t *ws = (uint8_t *)d_ws;
-  rc = launch_init(L, ws, st);
-  if (rc) return rc;
   return launch_quantize(d_x, n_elems, *p, L, ws, d_sym, d_qinfo, st);
 }
 
@@ -1500,14 +1669,12 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
   hipStream_t st = (hipStream_t)stream;
   uint8_t *ws = (uint8_t *)d_ws;
   Ctl *ctl = (Ctl *)(ws + L.ctl);
-  rc = launch_init(L, ws, st);
-  if (rc) return rc;
-  PROF_LAUNCH(KID_QINFO, k_qinfo_from_user, dim3(1), dim3(64), 0, st, ctl, d_qinfo, p->q_bits);
+  PROF_LAUNCH(KID_QINFO, k_qinfo_from_user, dim3(1), dim3(kBig), 0, st, ctl, d_qinfo, p->q_bits,
+              (uint32_t *)(ws + L.cnt), L.A, (uint32_t *)(ws + L.chunk_words), L.nc_max);
   LAUNCH_CHECK();
   if (n_elems) {
     const bool vec = aligned_to(d_sym, 16);
-    const uint32_t tile = kWG * (vec ? 16 : 1) * kQIter;
-    const uint32_t g = (uint32_t)((n_elems + tile - 1) / tile);
+    const uint32_t g = grid_for(n_elems, kWG * (vec ? 16 : 1) * kQIter, kQuantBlocks);
     const int skip0 = p->mode == RANS_MODE_CSR;
     if (vec)
       PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, true>), dim3(g), dim3(kWG), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
@@ -1529,8 +1696,6 @@ int rans_compress(const void *d_x, uint64_t n_elems, const rans_params *p, uint8
   if (stream_cap < kHdrBytes) return RANS_ERR_CAPACITY;
   hipStream_t st = (hipStream_t)stream;
   uint8_t *ws = (uint8_t *)d_ws;
-  rc = launch_init(L, ws, st);
-  if (rc) return rc;
   rc = launch_quantize(d_x, n_elems, *p, L, ws, ws + L.sym, nullptr, st);
   if (rc) return rc;
   return launch_encode_tail(ws + L.sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st);

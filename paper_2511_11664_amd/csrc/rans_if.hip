@@ -95,7 +95,7 @@ Layout make_layout(const rans_params &p, uint64_t n) {
   L.nc_max = (uint32_t)n_chunks_of(L.len_max, p.chunk_syms);
   L.chunk_len_max = p.chunk_syms ? p.chunk_syms : L.len_max;
   uint64_t per_stream = (L.chunk_len_max + p.n_streams - 1) / p.n_streams;
-  L.capw = (uint32_t)align_up((size_t)per_stream, 4);
+  L.capw = (uint32_t)align_up((size_t)per_stream, 8);  // 16-byte blocks
   L.n_blk = (uint32_t)((n + kCsrTile - 1) / kCsrTile);
   size_t o = 0;
   auto take = [&](size_t bytes) {
@@ -801,104 +801,196 @@ struct SrcCsr {
   __device__ __forceinline__ static uint32_t get(uint32_t raw, int q) { return (raw >> (16 * q)) & 0xffffu; }
 };
 
-constexpr int kEncAhead = 8;  // rows of symbols fetched ahead of the coder
+constexpr int kEncAhead = 8;  // rows of symbols fetched ahead of the coder; also the flush period of the word ring
 
-// Each lane runs SPL adjacent streams, which gives the scheduler SPL independent
-// dependency chains and lets one load fetch a row of SPL symbols.  A stream's
-// symbols are taken last to first; before each Eq. 2 update the state is
-// renormalised by emitting its low 16 bits if it is too large for the symbol.
-// Emitted words are collected four at a time in a register pair and stored as one
-// aligned 8-byte block, downwards from the end of the stream's scratch region, so
-// that they end up in the order the decoder reads them.
+// Encoder table entry as the coder uses it.
+struct EncEntry {
+  uint32_t m, f, F, cmpl;  // floor(2^32/f) (2^32-1 for f = 1), f, F, 2^M - f
+};
+
+// Table modes: 0 = {m, f | F << 16} read from global memory (very large alphabets),
+// 1 = the same staged in LDS, 2 = unpacked {m, f, F, 2^M - f} staged in LDS (small
+// alphabets: one 16-byte LDS read, no unpacking arithmetic).
+template <int TAB>
+__device__ __forceinline__ EncEntry load_entry(const uint2 *g_tab, const uint32_t *l_tab, uint32_t x, uint32_t totalM) {
+  EncEntry e;
+  if constexpr (TAB == 2) {
+    uint4 q = ((const uint4 *)l_tab)[x];
+    e.m = q.x; e.f = q.y; e.F = q.z; e.cmpl = q.w;
+  } else {
+    uint2 q = TAB == 1 ? ((const uint2 *)l_tab)[x] : g_tab[x];
+    e.m = q.x; e.f = q.y & 0xffffu; e.F = q.y >> 16; e.cmpl = totalM - e.f;
+  }
+  return e;
+}
+
+// Interleaved rANS encoder (Eq. 2 with 16-bit renormalisation).
+//
+// Each lane runs SPL adjacent streams: SPL independent dependency chains for the
+// scheduler, and one load fetches a row of SPL symbols.  Symbols are taken last to
+// first, kEncAhead rows fetched ahead, table entries looked up one row ahead.  The
+// per-row arithmetic is branch-free (selects only) so that it stays one basic block.
+//
+// Emitted words go to a 16-word ring per stream in LDS, laid out [position][stream]
+// so that lanes hit distinct banks.  The low half of the state is written to the
+// ring slot of the next word on every step and the word count advances only when
+// the renormalisation fires, so a slot keeps rewriting until it is really used.
+// After every kEncAhead rows (a wave-uniform point) a stream with 8 or more staged
+// words moves one 16-byte block to its scratch region in global memory, downwards
+// from the region's end, which leaves the words in the order the decoder reads them.
+//
 // floor(s / f) comes from a multiply-high with floor(2^32 / f) plus one correction.
-template <class Src, int SPL, bool LDS_TAB, bool MUL24>
+template <class Src, int SPL, int TAB, bool MUL24>
 __global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uint32_t A, uint32_t M, uint32_t S,
                                                 uint32_t cs, const Ctl *ctl, uint16_t *scratch, uint32_t capw,
                                                 uint32_t *st_out, uint32_t *nw_out, uint32_t *chunk_words,
                                                 uint32_t groups) {
-  extern __shared__ uint2 l_tab[];
-  __shared__ uint32_t sh[kWG / 64];
+  extern __shared__ __align__(16) uint32_t l_mem[];  // the only LDS of this kernel, so the ring starts at offset 0
   if (ctl->status != 0) return;
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
   if (k >= ctl->n_chunks) return;
   src.init(ctl);
-  if (LDS_TAB) {
-    for (uint32_t a = threadIdx.x; a < A; a += kWG) l_tab[a] = g_tab[a];
-    __syncthreads();
+  const uint32_t sh_lim = 32 - M, totalM = 1u << M;
+  // LDS: [ring][table].  The ring comes first so that a slot address is a plain
+  // bit-field combination of the row number and the stream's column.
+  constexpr uint32_t G = kWG * SPL;       // streams per work-group = ring row length
+  constexpr uint32_t kRowBytes = 2 * G;   // a power of two
+  constexpr uint32_t kRingBytes = 16 * kRowBytes;
+  uint16_t *ring = (uint16_t *)l_mem;
+  uint32_t *l_tab = l_mem + kRingBytes / 4;
+  uint32_t *sh = l_tab + (TAB == 2 ? A * 4 : (TAB == 1 ? A * 2 : 0));  // kWG / 64 words for the final reduction
+  if (TAB == 1) {
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) ((uint2 *)l_tab)[a] = g_tab[a];
+  } else if (TAB == 2) {
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) {
+      uint2 q = g_tab[a];
+      ((uint4 *)l_tab)[a] = make_uint4(q.x, q.y & 0xffffu, q.y >> 16, totalM - (q.y & 0xffffu));
+    }
   }
-  const uint2 *tab = LDS_TAB ? l_tab : g_tab;
+  if (TAB != 0) __syncthreads();
   const uint64_t len = ctl->len_d;
   const uint64_t chunk_len = cs ? cs : len;
   const uint64_t base = (uint64_t)k * chunk_len;
   const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
   const uint32_t j0 = (g * kWG + threadIdx.x) * SPL;
   const bool live = j0 < S;  // S is a multiple of SPL: a lane's streams are all live or all absent
-  const uint32_t sh_lim = 32 - M, totalM = 1u << M;
-  uint32_t s[SPL], nw[SPL], plo[SPL], phi[SPL];
-  uint16_t *p[SPL];
+  uint32_t s[SPL], nnw[SPL], fl[SPL];  // nnw = ~(number of words emitted): its low 4 bits are the ring row of the next word
+  uint16_t *gp[SPL];                   // the next 16-byte block goes just below this address
+  uint32_t colb[SPL];                  // byte offset of the stream's column inside a ring row (stream-major: conflict-free)
 #pragma unroll
   for (int i = 0; i < SPL; i++) {
     s[i] = kL;
-    nw[i] = plo[i] = phi[i] = 0;
-    p[i] = scratch + ((uint64_t)k * S + j0 + i + 1) * capw;  // one past the end of the region, 8-byte aligned
+    nnw[i] = ~0u;
+    fl[i] = 0;
+    gp[i] = scratch + ((uint64_t)k * S + j0 + i + 1) * capw;  // end of the stream's region, 16-byte aligned
+    colb[i] = 2 * (i * kWG + threadIdx.x);
   }
-  auto step = [&](int i, uint32_t x) {
-    uint2 e = tab[x];
-    uint32_t f = e.y & 0xffffu, F = e.y >> 16;
-    if ((s[i] >> sh_lim) >= f) {
-      phi[i] = __builtin_amdgcn_alignbit(phi[i], plo[i], 16);
-      plo[i] = (plo[i] << 16) | (s[i] & 0xffffu);
-      s[i] >>= 16;
-      nw[i]++;
-      if ((nw[i] & 3u) == 0) {
-        p[i] -= 4;
-        *(uint2 *)p[i] = make_uint2(plo[i], phi[i]);
-      }
+  auto slot = [&](int i, uint32_t row16) -> uint16_t * {  // ring slot (row16 & 15, column of stream i)
+    return (uint16_t *)((uint8_t *)ring + (((row16 * kRowBytes) & (kRingBytes - 1)) | colb[i]));
+  };
+  // Eq. 2 for the lane's SPL streams, phase by phase across the streams so that the
+  // independent chains interleave; selects only, no branches.
+  auto row = [&](const EncEntry (&e)[SPL]) {
+    bool c[SPL];
+    uint32_t q[SPL], rem[SPL];
+#pragma unroll
+    for (int i = 0; i < SPL; i++) c[i] = (s[i] >> sh_lim) >= e[i].f;  // too large for this symbol: emit 16 bits
+#pragma unroll
+    for (int i = 0; i < SPL; i++) *slot(i, nnw[i]) = (uint16_t)s[i];  // speculative: the slot counts only if c
+#pragma unroll
+    for (int i = 0; i < SPL; i++) {
+      s[i] = c[i] ? s[i] >> 16 : s[i];
+      nnw[i] -= c[i] ? 1u : 0u;
     }
-    uint32_t q = __umulhi(s[i], e.x);
-    uint32_t rem = s[i] - (MUL24 ? __umul24(q, f) : q * f);
-    q += rem >= f;
-    s[i] = s[i] + F + (MUL24 ? __umul24(q, totalM - f) : q * (totalM - f));
+#pragma unroll
+    for (int i = 0; i < SPL; i++) q[i] = __umulhi(s[i], e[i].m);
+#pragma unroll
+    for (int i = 0; i < SPL; i++) rem[i] = s[i] - (MUL24 ? __umul24(q[i], e[i].f) : q[i] * e[i].f);
+#pragma unroll
+    for (int i = 0; i < SPL; i++) q[i] += rem[i] >= e[i].f ? 1u : 0u;
+#pragma unroll
+    for (int i = 0; i < SPL; i++) s[i] = s[i] + e[i].F + (MUL24 ? __umul24(q[i], e[i].cmpl) : q[i] * e[i].cmpl);
+  };
+  auto lookup = [&](EncEntry (&e)[SPL], uint32_t raw) {
+#pragma unroll
+    for (int i = 0; i < SPL; i++) e[i] = load_entry<TAB>(g_tab, l_tab, Src::get(raw, i), totalM);
+  };
+  // move one finished block of 8 words (numbers fl .. fl+7) from the ring to global memory
+  auto flush = [&](int i) {
+    if (~nnw[i] - fl[i] >= 8u) {
+      const uint32_t r0 = (fl[i] & 8u) ? 0u : 8u;  // rows of the block; ascending row = ascending address
+      uint32_t w[8];
+#pragma unroll
+      for (int q = 0; q < 8; q++) w[q] = *slot(i, r0 + q);
+      gp[i] -= 8;
+      *(uint4 *)gp[i] = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+      fl[i] += 8;
+    }
   };
   if (live) {
     const uint64_t rows_full = n_here / S;
     const uint32_t rem_row = (uint32_t)(n_here - rows_full * S);
+    EncEntry ea[SPL], eb[SPL];
     if (rem_row) {  // ragged last row: only streams j < rem_row have a symbol there
 #pragma unroll
-      for (int i = 0; i < SPL; i++)
-        if (j0 + i < rem_row) step(i, src(base + rows_full * S + j0 + i));
+      for (int i = 0; i < SPL; i++) {
+        // an absent stream gets the neutral entry f = 2^M, F = 0, which leaves the state untouched
+        ea[i] = EncEntry{0u, totalM, 0u, 0u};
+        if (j0 + i < rem_row) ea[i] = load_entry<TAB>(g_tab, l_tab, src(base + rows_full * S + j0 + i), totalM);
+      }
+      row(ea);
     }
-    uint32_t cur[kEncAhead], nxt[kEncAhead];
-    auto fetch_rows = [&](uint32_t *dst, uint64_t t_hi) {  // rows t_hi-1, t_hi-2, ... (uniform bounds)
-#pragma unroll
-      for (int u = 0; u < kEncAhead; u++)
-        if (t_hi > (uint64_t)u) dst[u] = src.template fetch<SPL>(base + (t_hi - 1 - u) * S + j0);
-    };
+    // rows beyond a multiple of kEncAhead, one at a time
     uint64_t t = rows_full;
-    fetch_rows(nxt, t);
-    while (t > 0) {
+    for (uint32_t r = (uint32_t)(rows_full % kEncAhead); r > 0; r--, t--) {
+      lookup(ea, src.template fetch<SPL>(base + (t - 1) * S + j0));
+      row(ea);
+    }
+    // at most 1 + 7 words staged so far; from here on every batch ends with a flush, which keeps a
+    // stream's staged words below 8 at the start of a batch and below 16 (the ring size) inside it
+#pragma unroll
+    for (int i = 0; i < SPL; i++) flush(i);
+    // full batches of kEncAhead rows: rows fetched one batch ahead, table entries one row ahead,
+    // alternating between two register sets
+    uint32_t cur[kEncAhead], nxt[kEncAhead];
+    auto fetch_rows = [&](uint32_t *dst, uint64_t t_hi) {  // rows t_hi-1 .. t_hi-kEncAhead
+#pragma unroll
+      for (int u = 0; u < kEncAhead; u++) dst[u] = src.template fetch<SPL>(base + (t_hi - 1 - u) * S + j0);
+    };
+    if (t) {
+      fetch_rows(nxt, t);
+      lookup(ea, nxt[0]);
+    }
+    while (t) {
 #pragma unroll
       for (int u = 0; u < kEncAhead; u++) cur[u] = nxt[u];
-      const uint64_t t_next = t > kEncAhead ? t - kEncAhead : 0;
-      if (t_next) fetch_rows(nxt, t_next);
+      t -= kEncAhead;
+      if (t) fetch_rows(nxt, t);
 #pragma unroll
-      for (int u = 0; u < kEncAhead; u++) {
-        if (t > (uint64_t)u) {
-#pragma unroll
-          for (int i = 0; i < SPL; i++) step(i, Src::get(cur[u], i));
-        }
+      for (int u = 0; u < kEncAhead; u += 2) {
+        lookup(eb, cur[u + 1]);
+        row(ea);
+        // after the last row of the batch this looks up the first row of the next batch; when there is
+        // none, nxt[0] still holds an old, valid symbol and the entry is simply not used
+        lookup(ea, u + 2 < kEncAhead ? cur[(u + 2) % kEncAhead] : nxt[0]);
+        row(eb);
       }
-      t = t_next;
+#pragma unroll
+      for (int i = 0; i < SPL; i++) flush(i);
     }
 #pragma unroll
     for (int i = 0; i < SPL; i++) {
-      const uint32_t c = nw[i] & 3u;  // words still in the register pair; the newest goes to the lowest address
-      uint16_t *dst = p[i] - c;
-      for (uint32_t q = 0; q < c; q++) dst[q] = (uint16_t)(q < 2 ? plo[i] >> (16 * q) : phi[i] >> (16 * (q - 2)));
+      const uint32_t nw = ~nnw[i];
+      // the remaining words (fewer than 8), newest at the lowest address
+      uint16_t *dst = gp[i] - (nw - fl[i]);
+      for (uint32_t n = nw; n-- > fl[i];) *dst++ = *slot(i, ~n);
       st_out[(uint64_t)k * S + j0 + i] = s[i];
-      nw_out[(uint64_t)k * S + j0 + i] = nw[i];
+      nw_out[(uint64_t)k * S + j0 + i] = nw;
     }
   }
+  uint32_t nw[SPL];
+#pragma unroll
+  for (int i = 0; i < SPL; i++) nw[i] = ~nnw[i];
   uint32_t mine = 0;
 #pragma unroll
   for (int i = 0; i < SPL; i++) mine += nw[i];
@@ -1146,7 +1238,7 @@ template <class Sink, bool LDS_TAB>
 __global__ __launch_bounds__(kWG) void k_decode(const uint8_t *in, uint64_t bytes, Ctl *ctl, const uint16_t *g_lut,
                                                 const uint32_t *g_tab, uint32_t A, uint32_t M, uint32_t S,
                                                 uint32_t cs, uint32_t groups, Sink sink) {
-  extern __shared__ uint32_t l_mem[];
+  extern __shared__ __align__(16) uint32_t l_mem[];
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
   if (ctl->status != 0) return;
@@ -1443,33 +1535,28 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     const uint2 *tab = (const uint2 *)(ws + L.enc_tab);
     const bool lds_tab = lds_hist;
     const bool mul24 = p.freq_bits >= 8;  // then floor(s/f) < 2^24 and both products fit the 24-bit multiplier
-#define ENC_LAUNCH(SRCT, SPLV, LDSV)                                                                              \
+#define ENC_LAUNCH(SRCT, SPLV, TABV)                                                                              \
   do {                                                                                                            \
     const uint32_t groups_e = (S + kWG * SPLV - 1) / (kWG * SPLV);                                                \
+    const size_t lds_e = (TABV == 2 ? A * 16 : (TABV == 1 ? A * 8 : 0)) + 32 * kWG * SPLV + 4 * (kWG / 64);       \
     if (mul24)                                                                                                    \
-      PROF_LAUNCH(KID_ENCODE, (k_encode<SRCT, SPLV, LDSV, true>), dim3(L.nc_max * groups_e), dim3(kWG),            \
-                  LDSV ? A * 8 : 0, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr,   \
-                  nw_arr, cw, groups_e);                                                                          \
+      PROF_LAUNCH(KID_ENCODE, (k_encode<SRCT, SPLV, TABV, true>), dim3(L.nc_max * groups_e), dim3(kWG), lds_e,     \
+                  st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw,         \
+                  groups_e);                                                                                      \
     else                                                                                                          \
-      PROF_LAUNCH(KID_ENCODE, (k_encode<SRCT, SPLV, LDSV, false>), dim3(L.nc_max * groups_e), dim3(kWG),           \
-                  LDSV ? A * 8 : 0, st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr,   \
-                  nw_arr, cw, groups_e);                                                                          \
+      PROF_LAUNCH(KID_ENCODE, (k_encode<SRCT, SPLV, TABV, false>), dim3(L.nc_max * groups_e), dim3(kWG), lds_e,    \
+                  st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw,         \
+                  groups_e);                                                                                      \
   } while (0)
+    // One stream per lane: the hardware interleaves waves better than the compiler interleaves
+    // several streams inside a lane, and the stream count rarely exceeds what the chip can hold.
     if (csr) {
       SrcCsr src{ws + L.v, (const uint16_t *)(ws + L.c), (const uint16_t *)(ws + L.r), 0};
-      if (S % 2 == 0) {
-        if (lds_tab) ENC_LAUNCH(SrcCsr, 2, true);
-        else ENC_LAUNCH(SrcCsr, 2, false);
-      } else {
-        if (lds_tab) ENC_LAUNCH(SrcCsr, 1, true);
-        else ENC_LAUNCH(SrcCsr, 1, false);
-      }
+      if (lds_tab) ENC_LAUNCH(SrcCsr, 1, 1);
+      else ENC_LAUNCH(SrcCsr, 1, 0);
     } else {
       SrcDense src{d_sym};
-      const bool al4 = aligned_to(d_sym, 4);
-      if (S % 4 == 0 && al4 && S >= 4 * 64) ENC_LAUNCH(SrcDense, 4, true);
-      else if (S % 2 == 0 && al4 && S >= 2 * 64) ENC_LAUNCH(SrcDense, 2, true);
-      else ENC_LAUNCH(SrcDense, 1, true);
+      ENC_LAUNCH(SrcDense, 1, 2);
     }
 #undef ENC_LAUNCH
     LAUNCH_CHECK();

@@ -1320,6 +1320,302 @@ __global__ __launch_bounds__(kWG) void k_decode(const uint8_t *in, uint64_t byte
   if (bad) set_status(ctl, RANS_ERR_CORRUPT);
 }
 
+// ---- fast decoder: tables rebuilt per work-group in LDS, word stream read through an LDS window ----
+
+// The 128-byte header the caller expects, as 32 little-endian words.
+struct HdrImage {
+  uint32_t w[32];
+};
+
+// One wave: compare the header and the ends of the directory with what the host
+// expects, check the zero padding after the frequency table, reset the status word
+// and publish the geometry and the quantiser parameters (Eq. 6, recomputed from the
+// stored extrema with the encoder's arithmetic).
+__global__ __launch_bounds__(64) void k_dec_begin(const uint8_t *in, uint64_t bytes, Ctl *ctl, HdrImage img,
+                                                  rans_header h, rans_qinfo *qout) {
+  const uint32_t lane = threadIdx.x;
+  const uint32_t A = h.alphabet;
+  const uint64_t table_off = kHdrBytes;
+  const uint64_t dir_off = table_off + (((uint64_t)A * 2 + 7) & ~7ull);
+  const uint64_t payload_off = dir_off + 8 * ((uint64_t)h.n_chunks + 1);
+  bool ok = true;
+  if (lane < 32) ok = ld32(in + 4 * lane) == img.w[lane];
+  if (lane == 32) ok = ld64(in + dir_off) == 0;
+  if (lane == 33) ok = ld64(in + dir_off + 8ull * h.n_chunks) == bytes - payload_off;
+  for (uint64_t o = table_off + 2ull * A + 2 * lane; o < dir_off; o += 128) ok = ok && *(const uint16_t *)(in + o) == 0;
+  const bool all_ok = __ballot(!ok) == 0;
+  if (lane != 0) return;
+  ctl->status = all_ok ? 0 : RANS_ERR_CORRUPT;
+  ctl->len_d = h.len_d;
+  ctl->n_chunks = h.n_chunks;
+  ctl->dir_off = dir_off;
+  ctl->payload_off = payload_off;
+  ctl->nnz = h.p.mode == RANS_MODE_CSR ? (uint32_t)((h.len_d - h.p.rows) / 2) : 0;
+  const float mn = h.x_min, mx = h.x_max;
+  const float sc = (mx - mn) / (float)((1u << h.p.q_bits) - 1u);
+  const float zf = eq6_zero_point(mn, sc);
+  ctl->x_min = mn;
+  ctl->x_max = mx;
+  ctl->scale = sc;
+  ctl->zero_point = zf;
+  if (qout) {
+    qout->x_min = mn;
+    qout->x_max = mx;
+    qout->scale = sc;
+    qout->zero_point = zf;
+  }
+}
+
+// Output side of the fast decoder.  bits(x) is evaluated once per symbol value when
+// the tables are built; put() stores the precomputed bits.
+struct FSinkSym {
+  uint8_t *out;
+  __device__ __forceinline__ uint32_t bits(uint32_t x, float, float, float) const { return x; }
+  __device__ __forceinline__ void put(uint64_t i, uint32_t b) const { out[i] = (uint8_t)b; }
+};
+struct FSinkU16 {
+  uint16_t *out;
+  __device__ __forceinline__ uint32_t bits(uint32_t x, float, float, float) const { return x; }
+  __device__ __forceinline__ void put(uint64_t i, uint32_t b) const { out[i] = (uint16_t)b; }
+};
+// Inverse of Eq. 6 fused into the decoder: x = s * (xhat - z), one value per symbol.
+template <typename OutT>
+struct FSinkFloat {
+  OutT *out;
+  __device__ __forceinline__ uint32_t bits(uint32_t x, float sc, float zf, float x_min) const {
+    const float y = sc == 0.0f ? x_min : sc * ((float)x - zf);
+    if constexpr (sizeof(OutT) == 4) return __float_as_uint(y);
+    else return (uint32_t)__half_as_ushort(__float2half_rn(y));
+  }
+  __device__ __forceinline__ void put(uint64_t i, uint32_t b) const {
+    if constexpr (sizeof(OutT) == 4) ((uint32_t *)out)[i] = b;
+    else ((uint16_t *)out)[i] = (uint16_t)b;
+  }
+};
+
+constexpr uint32_t kWinRowBytes = 2 * kWG;          // one 16-bit word per stream
+constexpr uint32_t kWinBytes = 16 * kWinRowBytes;   // 16-word window per stream
+
+// 16 bytes of the container at a 16-byte aligned offset; bytes past the end read as zero.
+__device__ __forceinline__ uint4 load_block16(const uint8_t *in, uint64_t bytes, uint64_t off) {
+  if (off + 16 <= bytes) return *(const uint4 *)(in + off);
+  uint32_t w[4] = {0, 0, 0, 0};
+  for (int q = 0; q < 8; q++)
+    if (off + 2 * q + 2 <= bytes) w[q >> 1] |= (uint32_t) * (const uint16_t *)(in + off + 2 * q) << (16 * (q & 1));
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// Interleaved rANS decoder (Eq. 3-4), one stream per lane.
+//
+// Every work-group rebuilds the tables in LDS from the stored frequencies: F by a
+// block scan, {f | F << 16, output bits} per symbol, and the slot -> symbol table
+// (Eq. 3) by marking each present symbol's first slot and taking a running maximum.
+//
+// A stream's words are read through a 16-word window in LDS ([row][stream] layout):
+// the lane loads 16-byte aligned blocks of its segment from global memory and the
+// coder consumes single words from the window, keeping the next word in a register.
+// Refills happen at wave-uniform points, every four steps: the block fetched at one
+// check is written to LDS at the next, and a block is requested as soon as the
+// reader has entered the block before it.  A stream consumes at most one word per
+// step and a block holds eight, so the words are always there in time, while the
+// global loads have at least four steps to complete.
+//
+// Everything taken from the container is checked before use; loads never leave the
+// buffer, and the final state / word count of every stream is verified.
+template <class Sink, typename LutT, bool MUL24>
+__global__ __launch_bounds__(kWG) void k_decode_fast(const uint8_t *in, uint64_t bytes, Ctl *ctl, uint32_t A,
+                                                     uint32_t M, uint32_t S, uint32_t cs, uint32_t groups,
+                                                     uint64_t len, uint64_t dir_off, uint64_t payload_off,
+                                                     float x_min, float x_max, uint32_t q_bits, Sink sink) {
+  extern __shared__ __align__(16) uint32_t l_mem[];
+  if (ctl->status != 0) return;
+  const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
+  const uint32_t total = 1u << M, mask = total - 1;
+  // LDS: [window][tab: A x 8 B][misc: 16 words][lut]
+  uint16_t *win = (uint16_t *)l_mem;
+  uint2 *tab = (uint2 *)(l_mem + kWinBytes / 4);
+  uint32_t *misc = (uint32_t *)(tab + A);
+  uint64_t *misc64 = (uint64_t *)(misc + 8);
+  LutT *lut = (LutT *)(misc + 16);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  // ---- tables
+  const float sc = (x_max - x_min) / (float)((1u << q_bits) - 1u);
+  const float zf = eq6_zero_point(x_min, sc);
+  for (uint32_t i = threadIdx.x; i < (total * sizeof(LutT) + 3) / 4; i += kWG) ((uint32_t *)lut)[i] = 0;
+  uint32_t carry = 0;
+  for (uint32_t a0 = 0; a0 < A; a0 += kWG) {  // also orders the zeroing above before the marks below
+    const uint32_t a = a0 + threadIdx.x;
+    const uint32_t f = a < A ? *(const uint16_t *)(in + kHdrBytes + 2ull * a) : 0;
+    uint32_t tot;
+    const uint32_t F = carry + block_excl_scan<kWG>(f, misc, &tot);
+    if (a < A) {
+      tab[a] = make_uint2(f | (F << 16), sink.bits(a, sc, zf, x_min));
+      if (f && F < total) lut[F] = (LutT)a;  // present symbols start at distinct slots
+    }
+    carry += tot;
+  }
+  if (carry != total) {  // uniform; an empty D never reaches this kernel
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  __syncthreads();
+  {  // running maximum of the marks: each wave owns a contiguous quarter of the slots
+    constexpr uint32_t V = 4 / sizeof(LutT);  // slots per 32-bit word
+    const uint32_t per_wave = ((total + 4 * 64 * V - 1) / (4 * 64 * V)) * 64 * V;
+    const uint32_t lo = wave * per_wave;
+    if (lo < total) {
+      const uint32_t hi = lo + per_wave < total ? lo + per_wave : total;
+      // symbol that owns slot lo: the largest a with F[a] <= lo
+      uint32_t a_lo = 0, a_hi = A;
+      while (a_hi - a_lo > 1) {
+        const uint32_t mid = (a_lo + a_hi) >> 1;
+        if ((tab[mid].x >> 16) <= lo) a_lo = mid;
+        else a_hi = mid;
+      }
+      uint32_t run = a_lo;
+      for (uint32_t b = lo; b < hi; b += 64 * V) {
+        const uint32_t idx = b + lane * V;
+        uint32_t w = idx < hi ? ((const uint32_t *)lut)[idx / V] : 0;
+        uint32_t e[V];
+#pragma unroll
+        for (uint32_t q = 0; q < V; q++) e[q] = (w >> (8 * sizeof(LutT) * q)) & (sizeof(LutT) == 1 ? 0xffu : 0xffffu);
+#pragma unroll
+        for (uint32_t q = 1; q < V; q++) e[q] = e[q] > e[q - 1] ? e[q] : e[q - 1];
+        uint32_t inc = e[V - 1];
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+          const uint32_t o = __shfl_up(inc, d);
+          if (lane >= d) inc = o > inc ? o : inc;
+        }
+        uint32_t prev = __shfl_up(inc, 1);
+        prev = lane == 0 ? run : (prev > run ? prev : run);
+        w = 0;
+#pragma unroll
+        for (uint32_t q = 0; q < V; q++) {
+          const uint32_t v = e[q] > prev ? e[q] : prev;
+          w |= v << (8 * sizeof(LutT) * q);
+        }
+        if (idx < hi) ((uint32_t *)lut)[idx / V] = w;
+        const uint32_t last = __shfl(inc, 63);
+        run = last > run ? last : run;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- this work-group's streams
+  const uint64_t payload_bytes = bytes - payload_off;
+  const uint8_t *dir = in + dir_off;
+  const uint64_t o0 = ld64(dir + 8ull * k), o1 = ld64(dir + 8ull * k + 8);
+  if (o0 > o1 || o1 > payload_bytes || o1 - o0 < 8ull * S || (o0 & 3)) {
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  const uint64_t ck_off = payload_off + o0;  // chunk start, from the start of the container
+  const uint8_t *ck = in + ck_off;
+  const uint64_t ck_bytes = o1 - o0;
+  const uint64_t chunk_len = cs ? cs : len;
+  const uint64_t base = (uint64_t)k * chunk_len;
+  const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
+  const uint32_t *nwk = (const uint32_t *)(ck + 4ull * S);
+  uint64_t pre_loc = 0;
+  for (uint32_t i = threadIdx.x; i < g * kWG; i += kWG) pre_loc += nwk[i];
+  const uint64_t pre = block_sum64<kWG>(pre_loc, misc64);
+  const uint32_t j = g * kWG + threadIdx.x;
+  const bool live = j < S;
+  const uint64_t rows_full = n_here / S;
+  const uint32_t rem_row = (uint32_t)(n_here - rows_full * S);
+  const uint64_t n_j = live ? rows_full + (j < rem_row ? 1 : 0) : 0;
+  uint32_t nw = live ? nwk[j] : 0;
+  bool bad = false;
+  if (nw > n_j) {
+    bad = true;
+    nw = 0;
+  }
+  uint32_t tot;
+  const uint32_t ex = block_excl_scan<kWG>(nw, misc, &tot);
+  const uint64_t w0 = pre + ex;  // index of this stream's first word inside the chunk
+  if (8ull * S + 2 * (w0 + nw) > ck_bytes) {
+    bad = true;
+    nw = 0;
+  }
+  if (live) {
+    const uint64_t B0 = ck_off + 8ull * S + 2 * w0;  // first byte of the stream's words
+    const uint64_t B1 = B0 + 2ull * nw;              // one past its last byte
+    const uint64_t blk0 = B0 >> 4;                   // 16-byte blocks are counted from here
+    const uint32_t pos0 = (uint32_t)(B0 & 15) >> 1;
+    const uint32_t colb = 2 * threadIdx.x;
+    auto wslot = [&](uint32_t n) -> uint16_t * {  // window slot of word n (counted from block blk0)
+      return (uint16_t *)((uint8_t *)win + (((n * kWinRowBytes) & (kWinBytes - 1)) | colb));
+    };
+    auto store_block = [&](uint32_t b, const uint4 &q) {  // block b -> rows (8b .. 8b+7) & 15
+      const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+      for (int i = 0; i < 8; i++) *wslot(8 * b + i) = (uint16_t)(w[i >> 1] >> (16 * (i & 1)));
+    };
+    // the first two blocks
+    store_block(0, load_block16(in, bytes, blk0 << 4));
+    if (((blk0 + 1) << 4) < B1) store_block(1, load_block16(in, bytes, (blk0 + 1) << 4));
+    uint32_t ldb = 2;        // next block to request
+    uint32_t rd = pos0;      // next unread word, counted from block blk0
+    uint32_t pend_b = 0;
+    bool pending = false;
+    uint4 pend_q = make_uint4(0, 0, 0, 0);
+    uint32_t wnext = *wslot(rd);
+    uint32_t s = ((const uint32_t *)ck)[j];
+    uint32_t smin = s;
+    uint64_t oi = base + j;
+    auto refill = [&]() {
+      if (pending) {
+        store_block(pend_b, pend_q);
+        pending = false;
+      }
+      if (ldb <= (rd >> 3) + 1 && ((blk0 + ldb) << 4) < B1) {
+        pend_q = load_block16(in, bytes, (blk0 + ldb) << 4);
+        pend_b = ldb;
+        pending = true;
+        ldb++;
+      }
+    };
+    auto step = [&]() {
+      const uint32_t slot = s & mask;
+      const uint32_t x = lut[slot];
+      const uint2 e = tab[x];
+      // f < 2^16 always; s >> M < 2^24 only when M >= 8
+      s = (MUL24 ? __umul24(e.x & 0xffffu, s >> M) : (e.x & 0xffffu) * (s >> M)) + slot - (e.x >> 16);
+      sink.put(oi, e.y);
+      oi += S;
+      if (s < kL) {
+        s = (s << 16) | wnext;
+        rd++;
+        wnext = *wslot(rd);
+      }
+      smin = s < smin ? s : smin;
+    };
+    uint64_t t = 0;
+    for (; t + 4 <= rows_full; t += 4) {
+      refill();
+      step();
+      step();
+      step();
+      step();
+    }
+    if (t < rows_full || j < rem_row) {
+      refill();
+      for (; t < rows_full; t++) step();
+      if (j < rem_row) step();
+    }
+    bad |= smin < kL || s != kL || rd - pos0 != nw;
+    if (j == S - 1) {  // chunk size must be exactly header + words, padded to 4 bytes with zeros
+      const uint64_t end = 8ull * S + 2 * (w0 + nw);
+      if (((end + 3) & ~3ull) != ck_bytes) bad = true;
+      else if (end != ck_bytes && *(const uint16_t *)(ck + end) != 0) bad = true;
+    }
+  }
+  if (bad) set_status(ctl, RANS_ERR_CORRUPT);
+}
+
 // Exclusive cumulative sum of r (taken on the decoding side, Sec. 3.1) by one
 // work-group; checks r[i] <= K and sum r = nnz.
 __global__ __launch_bounds__(kBig) void k_row_scan(const uint16_t *r, uint32_t N, uint32_t K, uint32_t *row_off,
@@ -1655,15 +1951,71 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
   if (stream_bytes < payload_off) return RANS_ERR_CORRUPT;
   uint8_t *ws = (uint8_t *)d_ws;
   Ctl *ctl = (Ctl *)(ws + L.ctl);
+  const uint32_t groups = (S + kWG - 1) / kWG;
+  const bool csr = h.p.mode == RANS_MODE_CSR;
+  const size_t lut_elem = A <= 256 ? 1 : 2;
+  const size_t lds_fast = kWinBytes + (size_t)A * 8 + 64 + align_up((size_t)lut_elem << M, 16);
+  if (lds_fast <= 64 * 1024) {
+    // fast path: one small kernel for the header, one decode kernel that builds its tables in LDS
+    HdrImage img;
+    memset(&img, 0, sizeof(img));
+    img.w[0] = 0x31464952u;
+    img.w[1] = 1u | (h.p.mode << 16) | (h.p.in_dtype << 24);
+    img.w[2] = h.p.q_bits | (M << 8);
+    uint8_t *ib = (uint8_t *)img.w;
+    memcpy(ib + 12, &h.n_elems, 8);
+    memcpy(ib + 20, &h.p.rows, 8);
+    memcpy(ib + 28, &h.p.cols, 8);
+    memcpy(ib + 36, &h.len_d, 8);
+    memcpy(ib + 44, &A, 4);
+    memcpy(ib + 48, &h.p.n_streams, 4);
+    memcpy(ib + 52, &h.p.chunk_syms, 4);
+    memcpy(ib + 56, &h.n_chunks, 4);
+    memcpy(ib + 60, &h.x_min, 4);
+    memcpy(ib + 64, &h.x_max, 4);
+    PROF_LAUNCH(KID_DEC_PREPARE, k_dec_begin, dim3(1), dim3(64), 0, st, d_stream, (uint64_t)stream_bytes, ctl, img, h,
+                d_qinfo);
+    LAUNCH_CHECK();
+    if (h.n_chunks) {
+      const dim3 grid(h.n_chunks * groups), blk(kWG);
+      const uint64_t dir_off = kHdrBytes + align_up((size_t)A * 2, 8);
+#define FDEC_LAUNCH(SINKT, LUTT, sinkv)                                                                            \
+  do {                                                                                                             \
+    if (M >= 8)                                                                                                    \
+      PROF_LAUNCH(KID_DECODE, (k_decode_fast<SINKT, LUTT, true>), grid, blk, lds_fast, st, d_stream,               \
+                  (uint64_t)stream_bytes, ctl, A, M, S, h.p.chunk_syms, groups, h.len_d, dir_off, payload_off,     \
+                  h.x_min, h.x_max, h.p.q_bits, sinkv);                                                            \
+    else                                                                                                           \
+      PROF_LAUNCH(KID_DECODE, (k_decode_fast<SINKT, LUTT, false>), grid, blk, lds_fast, st, d_stream,              \
+                  (uint64_t)stream_bytes, ctl, A, M, S, h.p.chunk_syms, groups, h.len_d, dir_off, payload_off,     \
+                  h.x_min, h.x_max, h.p.q_bits, sinkv);                                                            \
+  } while (0)
+      if (csr) {
+        FSinkU16 sk{(uint16_t *)(ws + L.D)};
+        if (lut_elem == 1) FDEC_LAUNCH(FSinkU16, uint8_t, sk);
+        else FDEC_LAUNCH(FSinkU16, uint16_t, sk);
+      } else if (out_kind == 0) {
+        FSinkSym sk{(uint8_t *)d_out};
+        FDEC_LAUNCH(FSinkSym, uint8_t, sk);
+      } else if (out_kind == 1) {
+        FSinkFloat<float> sk{(float *)d_out};
+        FDEC_LAUNCH(FSinkFloat<float>, uint8_t, sk);
+      } else {
+        FSinkFloat<__half> sk{(__half *)d_out};
+        FDEC_LAUNCH(FSinkFloat<__half>, uint8_t, sk);
+      }
+#undef FDEC_LAUNCH
+      LAUNCH_CHECK();
+    }
+  } else {
+  // generic path for tables that do not fit LDS: tables built once in global memory
   uint16_t *lut = (uint16_t *)(ws + L.dec_lut);
   uint32_t *tab = (uint32_t *)(ws + L.dec_tab);
   PROF_LAUNCH(KID_DEC_PREPARE, k_dec_prepare, dim3(1), dim3(kBig), 0, st, d_stream, (uint64_t)stream_bytes, ctl, h, lut, tab,
                      (uint32_t *)(ws + L.dec_F), d_qinfo);
   LAUNCH_CHECK();
-  const uint32_t groups = (S + kWG - 1) / kWG;
   const size_t lds = (size_t)A * 4 + ((size_t)2 << M);
   const bool lds_tab = lds <= 48 * 1024;
-  const bool csr = h.p.mode == RANS_MODE_CSR;
   if (h.n_chunks) {
     dim3 grid(h.n_chunks * groups), blk(kWG);
 #define DEC_LAUNCH(SINKT, sinkv)                                                                                   \
@@ -1690,6 +2042,7 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
     }
 #undef DEC_LAUNCH
     LAUNCH_CHECK();
+  }
   }
   if (csr && n) {
     const uint32_t N = (uint32_t)h.p.rows, K = (uint32_t)h.p.cols;

@@ -1371,12 +1371,12 @@ __global__ __launch_bounds__(64) void k_dec_begin(const uint8_t *in, uint64_t by
 struct FSinkSym {
   uint8_t *out;
   __device__ __forceinline__ uint32_t bits(uint32_t x, float, float, float) const { return x; }
-  __device__ __forceinline__ void put(uint64_t i, uint32_t b) const { out[i] = (uint8_t)b; }
+  __device__ __forceinline__ static void put(uint8_t *base, uint32_t i, uint32_t b) { base[i] = (uint8_t)b; }
 };
 struct FSinkU16 {
   uint16_t *out;
   __device__ __forceinline__ uint32_t bits(uint32_t x, float, float, float) const { return x; }
-  __device__ __forceinline__ void put(uint64_t i, uint32_t b) const { out[i] = (uint16_t)b; }
+  __device__ __forceinline__ static void put(uint16_t *base, uint32_t i, uint32_t b) { base[i] = (uint16_t)b; }
 };
 // Inverse of Eq. 6 fused into the decoder: x = s * (xhat - z), one value per symbol.
 template <typename OutT>
@@ -1387,14 +1387,12 @@ struct FSinkFloat {
     if constexpr (sizeof(OutT) == 4) return __float_as_uint(y);
     else return (uint32_t)__half_as_ushort(__float2half_rn(y));
   }
-  __device__ __forceinline__ void put(uint64_t i, uint32_t b) const {
-    if constexpr (sizeof(OutT) == 4) ((uint32_t *)out)[i] = b;
-    else ((uint16_t *)out)[i] = (uint16_t)b;
+  __device__ __forceinline__ static void put(OutT *base, uint32_t i, uint32_t b) {
+    if constexpr (sizeof(OutT) == 4) ((uint32_t *)base)[i] = b;
+    else ((uint16_t *)base)[i] = (uint16_t)b;
   }
 };
 
-constexpr uint32_t kWinRowBytes = 2 * kWG;          // one 16-bit word per stream
-constexpr uint32_t kWinBytes = 16 * kWinRowBytes;   // 16-word window per stream
 
 // 16 bytes of the container at a 16-byte aligned offset; bytes past the end read as zero.
 __device__ __forceinline__ uint4 load_block16(const uint8_t *in, uint64_t bytes, uint64_t off) {
@@ -1422,33 +1420,36 @@ __device__ __forceinline__ uint4 load_block16(const uint8_t *in, uint64_t bytes,
 //
 // Everything taken from the container is checked before use; loads never leave the
 // buffer, and the final state / word count of every stream is verified.
-template <class Sink, typename LutT, bool MUL24>
-__global__ __launch_bounds__(kWG) void k_decode_fast(const uint8_t *in, uint64_t bytes, Ctl *ctl, uint32_t A,
+template <class Sink, typename LutT, bool MUL24, int NT>
+__global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t bytes, Ctl *ctl, uint32_t A,
                                                      uint32_t M, uint32_t S, uint32_t cs, uint32_t groups,
                                                      uint64_t len, uint64_t dir_off, uint64_t payload_off,
                                                      float x_min, float x_max, uint32_t q_bits, Sink sink) {
   extern __shared__ __align__(16) uint32_t l_mem[];
+  constexpr uint32_t kWinRowBytes = 2 * NT;          // one 16-bit word per stream
+  constexpr uint32_t kWinBytes = 16 * kWinRowBytes;   // 16-word window per stream
+  constexpr uint32_t NW = NT / 64;                    // waves per work-group
   if (ctl->status != 0) return;
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
   const uint32_t total = 1u << M, mask = total - 1;
-  // LDS: [window][tab: A x 8 B][misc: 16 words][lut]
-  uint16_t *win = (uint16_t *)l_mem;
-  uint2 *tab = (uint2 *)(l_mem + kWinBytes / 4);
-  uint32_t *misc = (uint32_t *)(tab + A);
-  uint64_t *misc64 = (uint64_t *)(misc + 8);
-  LutT *lut = (LutT *)(misc + 16);
+  // LDS: [window][lut][misc: 48 words][tab: A x 8 B].  The window and the slot table sit at constant
+  // offsets, so their addresses need no base arithmetic.
+  LutT *lut = (LutT *)(l_mem + kWinBytes / 4);
+  uint32_t *misc = l_mem + kWinBytes / 4 + ((total * (uint32_t)sizeof(LutT) + 15) / 16) * 4;
+  uint64_t *misc64 = (uint64_t *)(misc + 16);
+  uint2 *tab = (uint2 *)(misc + 48);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
   // ---- tables
   const float sc = (x_max - x_min) / (float)((1u << q_bits) - 1u);
   const float zf = eq6_zero_point(x_min, sc);
-  for (uint32_t i = threadIdx.x; i < (total * sizeof(LutT) + 3) / 4; i += kWG) ((uint32_t *)lut)[i] = 0;
+  for (uint32_t i = threadIdx.x; i < (total * sizeof(LutT) + 3) / 4; i += NT) ((uint32_t *)lut)[i] = 0;
   uint32_t carry = 0;
-  for (uint32_t a0 = 0; a0 < A; a0 += kWG) {  // also orders the zeroing above before the marks below
+  for (uint32_t a0 = 0; a0 < A; a0 += NT) {  // also orders the zeroing above before the marks below
     const uint32_t a = a0 + threadIdx.x;
     const uint32_t f = a < A ? *(const uint16_t *)(in + kHdrBytes + 2ull * a) : 0;
     uint32_t tot;
-    const uint32_t F = carry + block_excl_scan<kWG>(f, misc, &tot);
+    const uint32_t F = carry + block_excl_scan<NT>(f, misc, &tot);
     if (a < A) {
       tab[a] = make_uint2(f | (F << 16), sink.bits(a, sc, zf, x_min));
       if (f && F < total) lut[F] = (LutT)a;  // present symbols start at distinct slots
@@ -1460,9 +1461,9 @@ __global__ __launch_bounds__(kWG) void k_decode_fast(const uint8_t *in, uint64_t
     return;
   }
   __syncthreads();
-  {  // running maximum of the marks: each wave owns a contiguous quarter of the slots
+  {  // running maximum of the marks: each wave owns a contiguous share of the slots
     constexpr uint32_t V = 4 / sizeof(LutT);  // slots per 32-bit word
-    const uint32_t per_wave = ((total + 4 * 64 * V - 1) / (4 * 64 * V)) * 64 * V;
+    const uint32_t per_wave = ((total + NW * 64 * V - 1) / (NW * 64 * V)) * 64 * V;
     const uint32_t lo = wave * per_wave;
     if (lo < total) {
       const uint32_t hi = lo + per_wave < total ? lo + per_wave : total;
@@ -1520,9 +1521,9 @@ __global__ __launch_bounds__(kWG) void k_decode_fast(const uint8_t *in, uint64_t
   const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
   const uint32_t *nwk = (const uint32_t *)(ck + 4ull * S);
   uint64_t pre_loc = 0;
-  for (uint32_t i = threadIdx.x; i < g * kWG; i += kWG) pre_loc += nwk[i];
-  const uint64_t pre = block_sum64<kWG>(pre_loc, misc64);
-  const uint32_t j = g * kWG + threadIdx.x;
+  for (uint32_t i = threadIdx.x; i < g * NT; i += NT) pre_loc += nwk[i];
+  const uint64_t pre = block_sum64<NT>(pre_loc, misc64);
+  const uint32_t j = g * NT + threadIdx.x;
   const bool live = j < S;
   const uint64_t rows_full = n_here / S;
   const uint32_t rem_row = (uint32_t)(n_here - rows_full * S);
@@ -1534,45 +1535,67 @@ __global__ __launch_bounds__(kWG) void k_decode_fast(const uint8_t *in, uint64_t
     nw = 0;
   }
   uint32_t tot;
-  const uint32_t ex = block_excl_scan<kWG>(nw, misc, &tot);
+  const uint32_t ex = block_excl_scan<NT>(nw, misc, &tot);
   const uint64_t w0 = pre + ex;  // index of this stream's first word inside the chunk
   if (8ull * S + 2 * (w0 + nw) > ck_bytes) {
     bad = true;
     nw = 0;
   }
   if (live) {
+    typedef __attribute__((address_space(3))) uint16_t lds_u16;
+    constexpr uint32_t RB = kWinRowBytes, LOG_RB = NT == 1024 ? 11 : 9;
     const uint64_t B0 = ck_off + 8ull * S + 2 * w0;  // first byte of the stream's words
-    const uint64_t B1 = B0 + 2ull * nw;              // one past its last byte
-    const uint64_t blk0 = B0 >> 4;                   // 16-byte blocks are counted from here
+    const uint64_t blk_base = B0 & ~15ull;           // 16-byte blocks are counted from here
+    const uint8_t *sp = in + blk_base;
     const uint32_t pos0 = (uint32_t)(B0 & 15) >> 1;
-    const uint32_t colb = 2 * threadIdx.x;
-    auto wslot = [&](uint32_t n) -> uint16_t * {  // window slot of word n (counted from block blk0)
-      return (uint16_t *)((uint8_t *)win + (((n * kWinRowBytes) & (kWinBytes - 1)) | colb));
+    const uint32_t end16 = (uint32_t)(B0 - blk_base) + 2 * nw;  // stream end, in bytes from blk_base
+    // bytes of the container from blk_base on (saturated): loads stay below this
+    const uint64_t room = bytes > blk_base ? bytes - blk_base : 0;
+    const uint32_t lim16 = room > 0xffffffffull ? 0xffffffffu : (uint32_t)room;
+    // column of this stream inside a window row; lanes l and l+32 share a 32-bit bank word, so the two
+    // halves of a wave never collide.  The window starts at LDS address 0 (this kernel has no static LDS).
+    if ((uint32_t)(uintptr_t)(lds_u16 *)l_mem != 0) {  // cannot happen without static LDS; the slot arithmetic relies on it
+      set_status(ctl, RANS_ERR_HIP);
+      return;
+    }
+    const uint32_t lane_col = ((uint32_t)lane & 31u) * 2 + ((uint32_t)lane >> 5);
+    const uint32_t colb = 2 * ((uint32_t)wave * 64 + lane_col);
+    auto wread = [&](uint32_t rd_scaled) -> uint32_t {  // word whose number times RB is rd_scaled
+      return *(lds_u16 *)(uintptr_t)((rd_scaled & (kWinBytes - 1)) | colb);
     };
-    auto store_block = [&](uint32_t b, const uint4 &q) {  // block b -> rows (8b .. 8b+7) & 15
+    auto store_block = [&](uint32_t b, const uint4 &q) {  // block b -> rows 8(b&1) .. 8(b&1)+7
+      lds_u16 *row0 = (lds_u16 *)(uintptr_t)(((b & 1u) * 8 * RB) | colb);
       const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-      for (int i = 0; i < 8; i++) *wslot(8 * b + i) = (uint16_t)(w[i >> 1] >> (16 * (i & 1)));
+      for (int i = 0; i < 8; i++) row0[i * (RB / 2)] = (uint16_t)(w[i >> 1] >> (16 * (i & 1)));
+    };
+    auto load_block = [&](uint32_t off16) -> uint4 {  // 16 bytes at sp + off16; bytes past the end read as zero
+      if (off16 <= lim16 && lim16 - off16 >= 16) return *(const uint4 *)(sp + off16);
+      uint32_t w[4] = {0, 0, 0, 0};
+      for (uint32_t q = 0; q < 8; q++)
+        if ((uint64_t)off16 + 2 * q + 2 <= lim16) w[q >> 1] |= (uint32_t) * (const uint16_t *)(sp + off16 + 2 * q) << (16 * (q & 1));
+      return make_uint4(w[0], w[1], w[2], w[3]);
     };
     // the first two blocks
-    store_block(0, load_block16(in, bytes, blk0 << 4));
-    if (((blk0 + 1) << 4) < B1) store_block(1, load_block16(in, bytes, (blk0 + 1) << 4));
-    uint32_t ldb = 2;        // next block to request
-    uint32_t rd = pos0;      // next unread word, counted from block blk0
+    store_block(0, load_block(0));
+    if (16 < end16) store_block(1, load_block(16));
+    uint32_t ldb = 2;              // next block to request
+    uint32_t rd9 = pos0 * RB;      // RB times the number of the next unread word (counted from blk_base)
     uint32_t pend_b = 0;
     bool pending = false;
     uint4 pend_q = make_uint4(0, 0, 0, 0);
-    uint32_t wnext = *wslot(rd);
+    uint32_t wnext = wread(rd9);
     uint32_t s = ((const uint32_t *)ck)[j];
     uint32_t smin = s;
-    uint64_t oi = base + j;
+    auto *ob = sink.out + base + (uint64_t)g * NT;  // uniform base of this work-group's outputs
+    uint32_t oi = threadIdx.x;
     auto refill = [&]() {
       if (pending) {
         store_block(pend_b, pend_q);
         pending = false;
       }
-      if (ldb <= (rd >> 3) + 1 && ((blk0 + ldb) << 4) < B1) {
-        pend_q = load_block16(in, bytes, (blk0 + ldb) << 4);
+      if (ldb <= (rd9 >> (LOG_RB + 3)) + 1 && ldb * 16 < end16) {
+        pend_q = load_block(ldb * 16);
         pend_b = ldb;
         pending = true;
         ldb++;
@@ -1584,12 +1607,12 @@ __global__ __launch_bounds__(kWG) void k_decode_fast(const uint8_t *in, uint64_t
       const uint2 e = tab[x];
       // f < 2^16 always; s >> M < 2^24 only when M >= 8
       s = (MUL24 ? __umul24(e.x & 0xffffu, s >> M) : (e.x & 0xffffu) * (s >> M)) + slot - (e.x >> 16);
-      sink.put(oi, e.y);
+      sink.put(ob, oi, e.y);
       oi += S;
       if (s < kL) {
         s = (s << 16) | wnext;
-        rd++;
-        wnext = *wslot(rd);
+        rd9 += RB;
+        wnext = wread(rd9);
       }
       smin = s < smin ? s : smin;
     };
@@ -1606,6 +1629,7 @@ __global__ __launch_bounds__(kWG) void k_decode_fast(const uint8_t *in, uint64_t
       for (; t < rows_full; t++) step();
       if (j < rem_row) step();
     }
+    const uint32_t rd = rd9 >> LOG_RB;
     bad |= smin < kL || s != kL || rd - pos0 != nw;
     if (j == S - 1) {  // chunk size must be exactly header + words, padded to 4 bytes with zeros
       const uint64_t end = 8ull * S + 2 * (w0 + nw);
@@ -1954,8 +1978,13 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
   const uint32_t groups = (S + kWG - 1) / kWG;
   const bool csr = h.p.mode == RANS_MODE_CSR;
   const size_t lut_elem = A <= 256 ? 1 : 2;
-  const size_t lds_fast = kWinBytes + (size_t)A * 8 + 64 + align_up((size_t)lut_elem << M, 16);
-  if (lds_fast <= 64 * 1024) {
+  // work-group size of the fast decoder: 1024 lanes share one set of tables when a chunk has that many streams
+  const uint32_t nt = S > 512 ? 1024u : 256u;
+  const uint32_t groups_f = (S + nt - 1) / nt;
+  const size_t lds_fast = 32 * (size_t)nt + (size_t)A * 8 + 192 + align_up((size_t)lut_elem << M, 16);
+  // the fast decoder indexes a chunk's outputs and words with 32-bit offsets
+  const bool small_chunk = L.chunk_len_max < (1ull << 29) && L.capw < (1u << 20);
+  if (lds_fast <= 64 * 1024 && small_chunk) {
     // fast path: one small kernel for the header, one decode kernel that builds its tables in LDS
     HdrImage img;
     memset(&img, 0, sizeof(img));
@@ -1977,18 +2006,21 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
                 d_qinfo);
     LAUNCH_CHECK();
     if (h.n_chunks) {
-      const dim3 grid(h.n_chunks * groups), blk(kWG);
+      const dim3 grid(h.n_chunks * groups_f), blk(nt);
       const uint64_t dir_off = kHdrBytes + align_up((size_t)A * 2, 8);
+#define FDEC_ARGS                                                                                            \
+  d_stream, (uint64_t)stream_bytes, ctl, A, M, S, h.p.chunk_syms, groups_f, h.len_d, dir_off, payload_off, h.x_min, \
+      h.x_max, h.p.q_bits
 #define FDEC_LAUNCH(SINKT, LUTT, sinkv)                                                                            \
   do {                                                                                                             \
-    if (M >= 8)                                                                                                    \
-      PROF_LAUNCH(KID_DECODE, (k_decode_fast<SINKT, LUTT, true>), grid, blk, lds_fast, st, d_stream,               \
-                  (uint64_t)stream_bytes, ctl, A, M, S, h.p.chunk_syms, groups, h.len_d, dir_off, payload_off,     \
-                  h.x_min, h.x_max, h.p.q_bits, sinkv);                                                            \
+    if (M >= 8 && nt == 1024)                                                                                      \
+      PROF_LAUNCH(KID_DECODE, (k_decode_fast<SINKT, LUTT, true, 1024>), grid, blk, lds_fast, st, FDEC_ARGS, sinkv); \
+    else if (M >= 8)                                                                                               \
+      PROF_LAUNCH(KID_DECODE, (k_decode_fast<SINKT, LUTT, true, 256>), grid, blk, lds_fast, st, FDEC_ARGS, sinkv);  \
+    else if (nt == 1024)                                                                                           \
+      PROF_LAUNCH(KID_DECODE, (k_decode_fast<SINKT, LUTT, false, 1024>), grid, blk, lds_fast, st, FDEC_ARGS, sinkv); \
     else                                                                                                           \
-      PROF_LAUNCH(KID_DECODE, (k_decode_fast<SINKT, LUTT, false>), grid, blk, lds_fast, st, d_stream,              \
-                  (uint64_t)stream_bytes, ctl, A, M, S, h.p.chunk_syms, groups, h.len_d, dir_off, payload_off,     \
-                  h.x_min, h.x_max, h.p.q_bits, sinkv);                                                            \
+      PROF_LAUNCH(KID_DECODE, (k_decode_fast<SINKT, LUTT, false, 256>), grid, blk, lds_fast, st, FDEC_ARGS, sinkv); \
   } while (0)
       if (csr) {
         FSinkU16 sk{(uint16_t *)(ws + L.D)};
@@ -2005,6 +2037,7 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
         FDEC_LAUNCH(FSinkFloat<__half>, uint8_t, sk);
       }
 #undef FDEC_LAUNCH
+#undef FDEC_ARGS
       LAUNCH_CHECK();
     }
   } else {

@@ -60,6 +60,11 @@ def main():
     nbytes = codec.compress(x)
     hdr = codec.header(nbytes)
     codec.decompress(nbytes, hdr, out)
+    # a plain device copy of known size (reads and writes the input's byte count once): the reference
+    # that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this script
+    calib = torch.empty_like(x)
+    calib.copy_(x)
+    del calib
 
     def step():
         rc = B.rans_compress(x, n, p, codec.stream, codec.nbytes, codec.ws)

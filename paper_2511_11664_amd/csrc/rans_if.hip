@@ -1371,12 +1371,16 @@ __global__ __launch_bounds__(64) void k_dec_begin(const uint8_t *in, uint64_t by
 struct FSinkSym {
   uint8_t *out;
   __device__ __forceinline__ uint32_t bits(uint32_t x, float, float, float) const { return x; }
-  __device__ __forceinline__ static void put(uint8_t *base, uint32_t i, uint32_t b) { base[i] = (uint8_t)b; }
+  __device__ __forceinline__ static void put(uint8_t *base, uint32_t i, uint32_t b) {
+    __builtin_nontemporal_store((uint8_t)b, base + i);  // streamed once: keep it from evicting the coded words
+  }
 };
 struct FSinkU16 {
   uint16_t *out;
   __device__ __forceinline__ uint32_t bits(uint32_t x, float, float, float) const { return x; }
-  __device__ __forceinline__ static void put(uint16_t *base, uint32_t i, uint32_t b) { base[i] = (uint16_t)b; }
+  __device__ __forceinline__ static void put(uint16_t *base, uint32_t i, uint32_t b) {
+    __builtin_nontemporal_store((uint16_t)b, base + i);
+  }
 };
 // Inverse of Eq. 6 fused into the decoder: x = s * (xhat - z), one value per symbol.
 template <typename OutT>
@@ -1388,8 +1392,8 @@ struct FSinkFloat {
     else return (uint32_t)__half_as_ushort(__float2half_rn(y));
   }
   __device__ __forceinline__ static void put(OutT *base, uint32_t i, uint32_t b) {
-    if constexpr (sizeof(OutT) == 4) ((uint32_t *)base)[i] = b;
-    else ((uint16_t *)base)[i] = (uint16_t)b;
+    if constexpr (sizeof(OutT) == 4) __builtin_nontemporal_store(b, (uint32_t *)base + i);
+    else __builtin_nontemporal_store((uint16_t)b, (uint16_t *)base + i);
   }
 };
 

@@ -1052,21 +1052,68 @@ __global__ __launch_bounds__(kBig) void k_chunk_scan(Ctl *ctl, uint32_t *chunk_w
 }
 
 // Moves each stream's words from its scratch region to its place in the chunk and
-// writes the chunk header (final states, word counts).  Lanes read their own
-// stream's words, stage them in LDS at their scanned position, and the work-group
-// writes the staged tile out with consecutive lanes on consecutive words.
-constexpr uint32_t kGatherTile = 8192;  // words per LDS tile
-__global__ __launch_bounds__(kWG) void k_gather(const Ctl *ctl, const uint16_t *scratch, uint32_t capw,
-                                                const uint32_t *st, const uint32_t *nw_arr, uint32_t S,
-                                                uint32_t groups, uint8_t *out) {
+// writes the chunk header (final states, word counts).  A lane reads its own
+// stream's words in the aligned 16-byte blocks the encoder wrote, stages them in
+// LDS at their scanned position, and the work-group writes the staged tile out with
+// consecutive lanes on consecutive words.
+//
+// FUSED_SCAN: the chunk's byte offset is computed here by summing the sizes of the
+// chunks before it (cheap for up to a few thousand chunks), and the work-groups with
+// g == 0 write the directory; otherwise k_chunk_scan has written the directory.
+constexpr uint32_t kGatherTile = 8192;     // words per LDS tile
+constexpr uint32_t kFusedScanMax = 4096;   // chunks up to which the gather kernel scans the sizes itself
+template <bool FUSED_SCAN>
+__global__ __launch_bounds__(kWG) void k_gather(Ctl *ctl, const uint16_t *scratch, uint32_t capw, const uint32_t *st,
+                                                const uint32_t *nw_arr, const uint32_t *chunk_words, uint32_t S,
+                                                uint32_t groups, uint8_t *out, uint64_t cap,
+                                                uint64_t *d_stream_bytes) {
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
   __shared__ uint16_t tile[kGatherTile];
-  if (ctl->status != 0) return;
+  if (ctl->status != 0) {
+    if (FUSED_SCAN && blockIdx.x == 0 && threadIdx.x == 0 && d_stream_bytes) *d_stream_bytes = 0;
+    return;
+  }
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
-  if (k >= ctl->n_chunks) return;
-  const uint8_t *dir = out + ctl->dir_off;
-  uint8_t *ck = out + ctl->payload_off + ld64(dir + 8ull * k);
+  const uint32_t nc = ctl->n_chunks;
+  if (FUSED_SCAN && nc == 0 && blockIdx.x == 0) {  // empty D: only the directory's single entry
+    if (threadIdx.x == 0) {
+      uint8_t *dir0 = out + ctl->dir_off;
+      st32(dir0, 0u);
+      st32(dir0 + 4, 0u);
+      ctl->total_bytes = ctl->payload_off;
+      if (d_stream_bytes) *d_stream_bytes = ctl->payload_off;
+    }
+    return;
+  }
+  if (k >= nc) return;
+  uint8_t *dir = out + ctl->dir_off;
+  uint64_t off;
+  if (FUSED_SCAN) {
+    uint64_t loc = 0;
+    for (uint32_t i = threadIdx.x; i < k; i += kWG) loc += (8ull * S + 2ull * chunk_words[i] + 3) & ~3ull;
+    off = block_sum64<kWG>(loc, sh64);
+    const uint64_t my_size = (8ull * S + 2ull * chunk_words[k] + 3) & ~3ull;
+    const uint64_t end_abs = ctl->payload_off + off + my_size;
+    const bool fits = end_abs <= cap;
+    if (g == 0 && threadIdx.x == 0) {
+      st32(dir + 8ull * k, (uint32_t)off);
+      st32(dir + 8ull * k + 4, (uint32_t)(off >> 32));
+      if (k == nc - 1) {
+        st32(dir + 8ull * nc, (uint32_t)(off + my_size));
+        st32(dir + 8ull * nc + 4, (uint32_t)((off + my_size) >> 32));
+        ctl->total_bytes = end_abs;
+        if (d_stream_bytes) *d_stream_bytes = fits ? end_abs : 0;
+      }
+    }
+    if (!fits) {  // uniform: this chunk would end past the buffer
+      if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CAPACITY);
+      return;
+    }
+  } else {
+    off = ld64(dir + 8ull * k);
+  }
+  uint8_t *ck = out + ctl->payload_off + off;
   const uint32_t *nwk = nw_arr + (uint64_t)k * S;
   // words of the streams that precede this group inside the chunk
   uint64_t pre_loc = 0;
@@ -1080,12 +1127,26 @@ __global__ __launch_bounds__(kWG) void k_gather(const Ctl *ctl, const uint16_t *
     st32(ck + 4ull * j, st[(uint64_t)k * S + j]);
     st32(ck + 4ull * S + 4ull * j, nw);
   }
-  const uint16_t *src = scratch + ((uint64_t)k * S + j + 1) * capw - nw;  // first word in read order
-  uint16_t *dst = (uint16_t *)(ck + 8ull * S) + pre;                       // first word of this group
+  const uint16_t *rend = scratch + ((uint64_t)k * S + j + 1) * capw;  // end of the stream's region, 16-byte aligned
+  const uint32_t nb = (nw + 7) / 8;                                    // aligned 8-word blocks that hold the words
+  const uint32_t skip = nb * 8 - nw;                                   // words of the lowest block before the first one
+  uint16_t *dst = (uint16_t *)(ck + 8ull * S) + pre;                   // first word of this group
   for (uint32_t t0 = 0; t0 < tot; t0 += kGatherTile) {
+    // word w of this stream (in read order) has group position ex + w and sits in block (w + skip) / 8
     const uint32_t lo = ex > t0 ? ex : t0;
     const uint32_t hi = ex + nw < t0 + kGatherTile ? ex + nw : t0 + kGatherTile;
-    for (uint32_t w = lo; w < hi; w++) tile[w - t0] = src[w - ex];
+    if (lo < hi) {
+      const uint32_t b_lo = (lo - ex + skip) / 8, b_hi = (hi - 1 - ex + skip) / 8;
+      for (uint32_t bi = b_lo; bi <= b_hi; bi++) {
+        const uint4 q = *(const uint4 *)(rend - 8 * (nb - bi));
+        const uint32_t ww[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+          const uint32_t pos = ex + bi * 8 + i - skip;  // wraps below ex for the skipped words: fails the test
+          if (bi * 8 + i >= skip && pos >= lo && pos < hi) tile[pos - t0] = (uint16_t)(ww[i >> 1] >> (16 * (i & 1)));
+        }
+      }
+    }
     __syncthreads();
     const uint32_t cnt = tot - t0 < kGatherTile ? tot - t0 : kGatherTile;
     for (uint32_t i = threadIdx.x; i < cnt; i += kWG) dst[t0 + i] = tile[i];
@@ -1885,12 +1946,22 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
 #undef ENC_LAUNCH
     LAUNCH_CHECK();
   }
-  PROF_LAUNCH(KID_CHUNK_SCAN, k_chunk_scan, dim3(1), dim3(kBig), 0, st, ctl, (uint32_t *)(ws + L.chunk_words), S, d_stream,
-                     (uint64_t)cap, d_stream_bytes);
-  LAUNCH_CHECK();
-  if (L.nc_max) {
-    PROF_LAUNCH(KID_GATHER, k_gather, dim3(L.nc_max * groups), dim3(kWG), 0, st, ctl, (const uint16_t *)(ws + L.scratch),
-                       L.capw, (const uint32_t *)(ws + L.st), (const uint32_t *)(ws + L.nw), S, groups, d_stream);
+  const bool fused_scan = L.nc_max <= kFusedScanMax;
+  if (!fused_scan) {
+    PROF_LAUNCH(KID_CHUNK_SCAN, k_chunk_scan, dim3(1), dim3(kBig), 0, st, ctl, (uint32_t *)(ws + L.chunk_words), S,
+                d_stream, (uint64_t)cap, d_stream_bytes);
+    LAUNCH_CHECK();
+  }
+  {
+    const uint32_t gg = L.nc_max ? L.nc_max * groups : 1;  // an empty D still needs its one directory entry
+    if (fused_scan)
+      PROF_LAUNCH(KID_GATHER, (k_gather<true>), dim3(gg), dim3(kWG), 0, st, ctl, (const uint16_t *)(ws + L.scratch),
+                  L.capw, (const uint32_t *)(ws + L.st), (const uint32_t *)(ws + L.nw),
+                  (const uint32_t *)(ws + L.chunk_words), S, groups, d_stream, (uint64_t)cap, d_stream_bytes);
+    else
+      PROF_LAUNCH(KID_GATHER, (k_gather<false>), dim3(gg), dim3(kWG), 0, st, ctl, (const uint16_t *)(ws + L.scratch),
+                  L.capw, (const uint32_t *)(ws + L.st), (const uint32_t *)(ws + L.nw),
+                  (const uint32_t *)(ws + L.chunk_words), S, groups, d_stream, (uint64_t)cap, d_stream_bytes);
     LAUNCH_CHECK();
   }
   return RANS_OK;

@@ -18,6 +18,7 @@
 #include <cmath>
 #include <cstring>
 #include <mutex>
+#include <type_traits>
 #include <vector>
 
 #include "rans_if.h"
@@ -233,6 +234,31 @@ __device__ __forceinline__ uint32_t quant1(float x, float s, float zf, float lev
   r = fminf(fmaxf(r, 0.0f), levels);
   return (uint32_t)r;
 }
+
+// The same with the divisor-only part of the division hoisted out of the loop.
+// The correctly rounded binary32 quotient is computed on this target as
+//   r1 = refined reciprocal of s;  q0 = x r1;  q1 = q0 + (x - s q0) r1;  q = q1 + (x - s q1) r1
+// (fused operations), wrapped in operand scaling and special-case fix-ups that only
+// act when an operand is zero / denormal / non-finite or the exponents are far apart.
+// With s and every |x| inside [2^-30, 2^30] (or x = 0) none of them acts and the five
+// per-element operations below give the same bits; for |x| below that range the
+// quotient is far below 1/2 and cannot change the rounded sum with z.
+struct FastDiv {
+  float s, r1;
+  __device__ __forceinline__ void init(float s_) {
+    s = s_;
+    const float r0 = __builtin_amdgcn_rcpf(s_);
+    const float e0 = __builtin_fmaf(-s_, r0, 1.0f);
+    r1 = __builtin_fmaf(e0, r0, r0);
+  }
+  __device__ __forceinline__ float div(float x) const {
+    const float q0 = x * r1;
+    const float e1 = __builtin_fmaf(-s, q0, x);
+    const float q1 = __builtin_fmaf(e1, r1, q0);
+    const float e2 = __builtin_fmaf(-s, q1, x);
+    return __builtin_fmaf(e2, r1, q1);
+  }
+};
 
 // Eq. 6: z = round_half_even(-x_min / s), kept as an integer-valued float.  The
 // result is built so that a zero is always +0.0: the backend may turn 0 - x into a
@@ -458,13 +484,25 @@ __global__ __launch_bounds__(kWG) void k_quant_hist(const T *x, uint32_t n, Ctl 
   __shared__ uint32_t h[256 * kHistRep];
   for (int i = threadIdx.x; i < 256 * kHistRep; i += kWG) h[i] = 0;
   __syncthreads();
-  const float s = ctl->scale, zf = ctl->zero_point;
-  const float levels = (float)((1u << q_bits) - 1u);
-  const bool degenerate = !IS_SYM && !(s != 0.0f);  // s == 0 (constant tensor) or NaN (flagged input)
+  // s == 0 (constant tensor) or NaN (flagged input): quantise with s = 1, z = 0 and a top level of 0,
+  // which maps everything to symbol 0 without a branch in the loop
+  const bool degenerate = !IS_SYM && !(ctl->scale != 0.0f);
+  const float s = degenerate ? 1.0f : ctl->scale, zf = degenerate ? 0.0f : ctl->zero_point;
+  const float levels = degenerate ? 0.0f : (float)((1u << q_bits) - 1u);
+  const float amax = fmaxf(fabsf(ctl->x_min), fabsf(ctl->x_max));
+  const bool fast = s >= 0x1p-30f && s <= 0x1p30f && amax <= 0x1p30f;  // uniform; see FastDiv
+  FastDiv fd;
+  fd.init(s);
   const uint32_t rep = threadIdx.x & (kHistRep - 1);
   const uint32_t tile = kWG * V * kQIter;
-  auto q = [&](float v) -> uint32_t { return degenerate ? 0u : quant1(v, s, zf, levels); };
   auto bump = [&](uint32_t a) { atomicAdd(&h[a * kHistRep + rep], 1u); };
+  auto run = [&](auto fast_tag) {
+  constexpr bool FAST = decltype(fast_tag)::value;
+  auto q = [&](float v) -> uint32_t {
+    const float t = FAST ? fd.div(v) : v / s;
+    const float r = rintf(t + zf);
+    return (uint32_t)__builtin_amdgcn_fmed3f(r, 0.0f, levels);
+  };
   // a work-group walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... and flushes its histogram once
   for (uint64_t base = (uint64_t)blockIdx.x * tile; base < n; base += (uint64_t)gridDim.x * tile)
 #pragma unroll
@@ -511,6 +549,9 @@ __global__ __launch_bounds__(kWG) void k_quant_hist(const T *x, uint32_t n, Ctl 
       }
     }
   }
+  };  // run
+  if (fast) run(std::true_type{});
+  else run(std::false_type{});
   __syncthreads();
   for (int a = threadIdx.x; a < 256; a += kWG) {
     uint32_t t = 0;

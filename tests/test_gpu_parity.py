@@ -141,6 +141,35 @@ def test_csr_parity(rows, cols, dtype, Q, M, S, cs):
         _check_all(x, p, f"csr case={i}")
 
 
+def test_quantiser_matches_ieee_division_everywhere_it_takes_the_hoisted_reciprocal_path():
+    """Symbols must equal the oracle's (which divides with the CPU's IEEE binary32 division) for every binary16
+    value at several scales, and for wide random binary32 samples inside and outside the fast-path range."""
+    halves = torch.arange(65536, dtype=torch.int32).to(torch.int16).view(torch.float16)
+    halves = halves[torch.isfinite(halves)]
+    cases = []
+    for bound in (65504.0, 1000.0, 97.3, 7.25, 1.0, 0.11, 3e-3, 6.2e-5):
+        x = halves[halves.abs().float() <= bound]
+        cases.append((x.contiguous(), 8))
+        cases.append((x[x >= 0].contiguous(), 5))
+    g = torch.Generator().manual_seed(77)
+    for scale in (1e-12, 1e-6, 1e-3, 1.0, 37.0, 1e4, 1e8, 3e12):
+        x = torch.randn(1 << 20, generator=g) * scale
+        cases.append((x, 8))
+        bits = torch.randint(0, 1 << 31, (1 << 20,), generator=g, dtype=torch.int64).to(torch.int32)
+        y = bits.view(torch.float32)
+        y = torch.where(torch.isfinite(y) & (y.abs() < 1e30), y, torch.zeros_like(y)).clamp(-scale, scale)
+        cases.append((y.contiguous(), 7))
+    for x, Q in cases:
+        n = x.numel()
+        p = B.make_params(Q, 12, n, 1, B.MODE_DENSE, 32, 0, B.F16 if x.dtype == torch.float16 else B.F32)
+        codec = B.Codec(p, n)
+        sym = torch.empty(n, dtype=torch.uint8, device="cuda")
+        codec.quantize(x.cuda(), sym)
+        ref, qi = oracle.quantize(x.numpy(), Q)
+        print(f"[case] quantiser n={n} dtype={x.dtype} Q={Q} scale={qi.scale}", flush=True)
+        assert np.array_equal(sym.cpu().numpy(), ref)
+
+
 def test_unaligned_buffers():
     """Views that start at odd element offsets take the scalar load paths."""
     n = 30011

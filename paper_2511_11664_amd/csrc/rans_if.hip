@@ -1473,15 +1473,17 @@ __global__ __launch_bounds__(64) void k_dec_begin(const uint8_t *in, uint64_t by
 struct FSinkSym {
   uint8_t *out;
   __device__ __forceinline__ uint32_t bits(uint32_t x, float, float, float) const { return x; }
-  __device__ __forceinline__ static void put(uint8_t *base, uint32_t i, uint32_t b) {
-    __builtin_nontemporal_store((uint8_t)b, base + i);  // streamed once: keep it from evicting the coded words
+  // byte_off is a byte offset from a wave-uniform base: the store can take the base from scalar
+  // registers; non-temporal because the output is streamed once and must not evict the coded words
+  __device__ __forceinline__ static void put(uint8_t *base, uint32_t byte_off, uint32_t b) {
+    __builtin_nontemporal_store((uint8_t)b, base + byte_off);
   }
 };
 struct FSinkU16 {
   uint16_t *out;
   __device__ __forceinline__ uint32_t bits(uint32_t x, float, float, float) const { return x; }
-  __device__ __forceinline__ static void put(uint16_t *base, uint32_t i, uint32_t b) {
-    __builtin_nontemporal_store((uint16_t)b, base + i);
+  __device__ __forceinline__ static void put(uint16_t *base, uint32_t byte_off, uint32_t b) {
+    __builtin_nontemporal_store((uint16_t)b, (uint16_t *)((uint8_t *)base + byte_off));
   }
 };
 // Inverse of Eq. 6 fused into the decoder: x = s * (xhat - z), one value per symbol.
@@ -1493,9 +1495,9 @@ struct FSinkFloat {
     if constexpr (sizeof(OutT) == 4) return __float_as_uint(y);
     else return (uint32_t)__half_as_ushort(__float2half_rn(y));
   }
-  __device__ __forceinline__ static void put(OutT *base, uint32_t i, uint32_t b) {
-    if constexpr (sizeof(OutT) == 4) __builtin_nontemporal_store(b, (uint32_t *)base + i);
-    else __builtin_nontemporal_store((uint16_t)b, (uint16_t *)base + i);
+  __device__ __forceinline__ static void put(OutT *base, uint32_t byte_off, uint32_t b) {
+    if constexpr (sizeof(OutT) == 4) __builtin_nontemporal_store(b, (uint32_t *)((uint8_t *)base + byte_off));
+    else __builtin_nontemporal_store((uint16_t)b, (uint16_t *)((uint8_t *)base + byte_off));
   }
 };
 
@@ -1526,11 +1528,17 @@ __device__ __forceinline__ uint4 load_block16(const uint8_t *in, uint64_t bytes,
 //
 // Everything taken from the container is checked before use; loads never leave the
 // buffer, and the final state / word count of every stream is verified.
-template <class Sink, typename LutT, bool MUL24, int NT>
+//
+// WIDE: instead of the two dependent lookups slot -> symbol -> {f, F, output}, one 8-byte entry per slot
+// {f | (slot - F) << 16, output bits} (a 2^M x 8 B table): one LDS access on the state's dependency chain.
+// The byte-per-slot table, the per-symbol table and the scan scratch are then only needed while the tables
+// are built; they live at tmp_off, which may alias the window (not yet in use at that time).
+template <class Sink, typename LutT, bool MUL24, int NT, bool WIDE>
 __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t bytes, Ctl *ctl, uint32_t A,
                                                      uint32_t M, uint32_t S, uint32_t cs, uint32_t groups,
                                                      uint64_t len, uint64_t dir_off, uint64_t payload_off,
-                                                     float x_min, float x_max, uint32_t q_bits, Sink sink) {
+                                                     float x_min, float x_max, uint32_t q_bits, uint32_t tmp_off,
+                                                     Sink sink) {
   extern __shared__ __align__(16) uint32_t l_mem[];
   constexpr uint32_t kWinRowBytes = 2 * NT;          // one 16-bit word per stream
   constexpr uint32_t kWinBytes = 16 * kWinRowBytes;   // 16-word window per stream
@@ -1538,12 +1546,14 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
   if (ctl->status != 0) return;
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
   const uint32_t total = 1u << M, mask = total - 1;
-  // LDS: [window][lut][misc: 48 words][tab: A x 8 B].  The window and the slot table sit at constant
-  // offsets, so their addresses need no base arithmetic.
-  LutT *lut = (LutT *)(l_mem + kWinBytes / 4);
-  uint32_t *misc = l_mem + kWinBytes / 4 + ((total * (uint32_t)sizeof(LutT) + 15) / 16) * 4;
+  // LDS: [window][lut][misc: 48 words][tab: A x 8 B], or WIDE: [window][wide table] and
+  // [lut][misc][tab] at tmp_off.  The window and the table the coder reads sit at constant offsets, so
+  // their addresses need no base arithmetic.
+  LutT *lut = (LutT *)(l_mem + (WIDE ? tmp_off : kWinBytes) / 4);
+  uint32_t *misc = (uint32_t *)lut + ((total * (uint32_t)sizeof(LutT) + 15) / 16) * 4;
   uint64_t *misc64 = (uint64_t *)(misc + 16);
   uint2 *tab = (uint2 *)(misc + 48);
+  uint2 *wide = (uint2 *)(l_mem + kWinBytes / 4);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
   // ---- tables
@@ -1610,6 +1620,13 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
     }
   }
   __syncthreads();
+  if (WIDE) {
+    for (uint32_t sl = threadIdx.x; sl < total; sl += NT) {
+      const uint2 e = tab[lut[sl]];
+      wide[sl] = make_uint2((e.x & 0xffffu) | ((sl - (e.x >> 16)) << 16), e.y);
+    }
+    __syncthreads();
+  }
 
   // ---- this work-group's streams
   const uint64_t payload_bytes = bytes - payload_off;
@@ -1647,6 +1664,7 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
     bad = true;
     nw = 0;
   }
+  if (WIDE) __syncthreads();  // the scan scratch above may alias the window that is filled below
   if (live) {
     typedef __attribute__((address_space(3))) uint16_t lds_u16;
     constexpr uint32_t RB = kWinRowBytes, LOG_RB = NT == 1024 ? 11 : 9;
@@ -1694,7 +1712,13 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
     uint32_t s = ((const uint32_t *)ck)[j];
     uint32_t smin = s;
     auto *ob = sink.out + base + (uint64_t)g * NT;  // uniform base of this work-group's outputs
-    uint32_t oi = threadIdx.x;
+    constexpr uint32_t kOutElem = sizeof(*sink.out);
+    uint32_t oi = threadIdx.x * kOutElem;           // byte offset of this stream's next output
+    const uint32_t oi_step = S * kOutElem;
+    // table addresses as plain LDS offsets (the window starts at 0, the slot table right after it)
+    typedef __attribute__((address_space(3))) LutT lds_lut;
+    typedef __attribute__((address_space(3))) uint64_t lds_u64;
+    const uint32_t tab_off = (uint32_t)(uintptr_t)(lds_u64 *)tab;
     auto refill = [&]() {
       if (pending) {
         store_block(pend_b, pend_q);
@@ -1709,12 +1733,22 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
     };
     auto step = [&]() {
       const uint32_t slot = s & mask;
-      const uint32_t x = lut[slot];
-      const uint2 e = tab[x];
+      uint2 e;
+      uint32_t bias;  // slot - F
+      if constexpr (WIDE) {
+        const uint64_t e64 = *(lds_u64 *)(uintptr_t)(kWinBytes + slot * 8);
+        e = make_uint2((uint32_t)e64, (uint32_t)(e64 >> 32));
+        bias = e.x >> 16;
+      } else {
+        const uint32_t x = *(lds_lut *)(uintptr_t)(kWinBytes + slot * (uint32_t)sizeof(LutT));
+        const uint64_t e64 = *(lds_u64 *)(uintptr_t)(tab_off + x * 8);
+        e = make_uint2((uint32_t)e64, (uint32_t)(e64 >> 32));
+        bias = slot - (e.x >> 16);
+      }
       // f < 2^16 always; s >> M < 2^24 only when M >= 8
-      s = (MUL24 ? __umul24(e.x & 0xffffu, s >> M) : (e.x & 0xffffu) * (s >> M)) + slot - (e.x >> 16);
+      s = (MUL24 ? __umul24(e.x & 0xffffu, s >> M) : (e.x & 0xffffu) * (s >> M)) + bias;
       sink.put(ob, oi, e.y);
-      oi += S;
+      oi += oi_step;
       if (s < kL) {
         s = (s << 16) | wnext;
         rd9 += RB;
@@ -2097,10 +2131,21 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
   // work-group size of the fast decoder: 1024 lanes share one set of tables when a chunk has that many streams
   const uint32_t nt = S > 512 ? 1024u : 256u;
   const uint32_t groups_f = (S + nt - 1) / nt;
-  const size_t lds_fast = 32 * (size_t)nt + (size_t)A * 8 + 192 + align_up((size_t)lut_elem << M, 16);
+  const size_t win_b = 32 * (size_t)nt;
+  const size_t tmp_b = align_up((size_t)lut_elem << M, 16) + 192 + (size_t)A * 8;  // [lut][misc][tab]
+  const size_t lds_two = win_b + tmp_b;
+  // wide table: 8 bytes per slot after the window; the build-time tables alias the window if they fit there
+  const size_t wide_b = (size_t)8 << M;
+  const bool tmp_alias = tmp_b <= win_b;
+  const size_t lds_wide = win_b + wide_b + (tmp_alias ? 0 : tmp_b);
+  const uint32_t tmp_off = (uint32_t)(tmp_alias ? 0 : win_b + wide_b);
+  const size_t kLdsMax = 160 * 1024;
+  // worth it when the table is shared by enough lanes: always up to 2^13 slots, at 2^14 only for 1024-lane groups
+  const bool use_wide = lds_wide <= kLdsMax && (M <= 13 || nt == 1024);
+  const size_t lds_fast = use_wide ? lds_wide : lds_two;
   // the fast decoder indexes a chunk's outputs and words with 32-bit offsets
   const bool small_chunk = L.chunk_len_max < (1ull << 29) && L.capw < (1u << 20);
-  if (lds_fast <= 64 * 1024 && small_chunk) {
+  if (lds_fast <= kLdsMax && small_chunk) {
     // fast path: one small kernel for the header, one decode kernel that builds its tables in LDS
     HdrImage img;
     memset(&img, 0, sizeof(img));
@@ -2126,17 +2171,29 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
       const uint64_t dir_off = kHdrBytes + align_up((size_t)A * 2, 8);
 #define FDEC_ARGS                                                                                            \
   d_stream, (uint64_t)stream_bytes, ctl, A, M, S, h.p.chunk_syms, groups_f, h.len_d, dir_off, payload_off, h.x_min, \
-      h.x_max, h.p.q_bits
+      h.x_max, h.p.q_bits, tmp_off
+#define FDEC_ONE(SINKT, LUTT, MULV, NTV, WIDEV, sinkv)                                                              \
+  do {                                                                                                             \
+    auto kfn = k_decode_fast<SINKT, LUTT, MULV, NTV, WIDEV>;                                                       \
+    /* once per instantiation: allow dynamic LDS beyond the default 64 KB */                                       \
+    static const hipError_t attr_rc =                                                                              \
+        hipFuncSetAttribute((const void *)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax);          \
+    if (lds_fast > 64 * 1024 && attr_rc != hipSuccess) return RANS_ERR_HIP;                                        \
+    PROF_LAUNCH(KID_DECODE, kfn, grid, blk, lds_fast, st, FDEC_ARGS, sinkv);                                       \
+  } while (0)
 #define FDEC_LAUNCH(SINKT, LUTT, sinkv)                                                                            \
   do {                                                                                                             \
-    if (M >= 8 && nt == 1024)                                                                                      \
-      PROF_LAUNCH(KID_DECODE, (k_decode_fast<SINKT, LUTT, true, 1024>), grid, blk, lds_fast, st, FDEC_ARGS, sinkv); \
-    else if (M >= 8)                                                                                               \
-      PROF_LAUNCH(KID_DECODE, (k_decode_fast<SINKT, LUTT, true, 256>), grid, blk, lds_fast, st, FDEC_ARGS, sinkv);  \
-    else if (nt == 1024)                                                                                           \
-      PROF_LAUNCH(KID_DECODE, (k_decode_fast<SINKT, LUTT, false, 1024>), grid, blk, lds_fast, st, FDEC_ARGS, sinkv); \
-    else                                                                                                           \
-      PROF_LAUNCH(KID_DECODE, (k_decode_fast<SINKT, LUTT, false, 256>), grid, blk, lds_fast, st, FDEC_ARGS, sinkv); \
+    if (use_wide) {                                                                                                \
+      if (M >= 8 && nt == 1024) FDEC_ONE(SINKT, LUTT, true, 1024, true, sinkv);                                    \
+      else if (M >= 8) FDEC_ONE(SINKT, LUTT, true, 256, true, sinkv);                                              \
+      else if (nt == 1024) FDEC_ONE(SINKT, LUTT, false, 1024, true, sinkv);                                        \
+      else FDEC_ONE(SINKT, LUTT, false, 256, true, sinkv);                                                         \
+    } else {                                                                                                       \
+      if (M >= 8 && nt == 1024) FDEC_ONE(SINKT, LUTT, true, 1024, false, sinkv);                                   \
+      else if (M >= 8) FDEC_ONE(SINKT, LUTT, true, 256, false, sinkv);                                             \
+      else if (nt == 1024) FDEC_ONE(SINKT, LUTT, false, 1024, false, sinkv);                                       \
+      else FDEC_ONE(SINKT, LUTT, false, 256, false, sinkv);                                                        \
+    }                                                                                                              \
   } while (0)
       if (csr) {
         FSinkU16 sk{(uint16_t *)(ws + L.D)};
@@ -2153,6 +2210,7 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
         FDEC_LAUNCH(FSinkFloat<__half>, uint8_t, sk);
       }
 #undef FDEC_LAUNCH
+#undef FDEC_ONE
 #undef FDEC_ARGS
       LAUNCH_CHECK();
     }

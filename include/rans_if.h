@@ -149,12 +149,14 @@ const char *rans_strerror(int code);
 /* Measurement aid for benchmarks (not part of the paper's method): per-kernel
  * launch durations.  rans_profile_enable(mask) makes every later launch of the
  * kernels whose bit (1 << kernel_id) is set record a pair of HIP events on its
- * launch stream; mask 0 switches it off (the default: nothing is recorded).
+ * launch stream (only every `every`-th launch of each kernel, to keep the cost
+ * of the event packets out of a timed region; 0 or 1 = every launch); mask 0
+ * switches it off (the default: nothing is recorded).
  * rans_profile_read() waits for the recorded events of one kernel and returns
  * their summed elapsed time and their number; rans_profile_reset() forgets all
  * records.  rans_profile_kernel_name() maps ids 0..n-1 to kernel names and
  * returns NULL past the end.  Host only; the event pairs are created on demand. */
-int rans_profile_enable(uint64_t kernel_mask);
+int rans_profile_enable(uint64_t kernel_mask, uint32_t every);
 int rans_profile_reset(void);
 int rans_profile_read(int kernel_id, double *total_ms, uint64_t *count);
 const char *rans_profile_kernel_name(int kernel_id);

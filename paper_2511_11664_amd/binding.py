@@ -90,7 +90,7 @@ def lib() -> C.CDLL:
         L.rans_last_status.argtypes = [vp, vp]
         L.rans_strerror.argtypes = [C.c_int]
         L.rans_strerror.restype = C.c_char_p
-        L.rans_profile_enable.argtypes = [u64]
+        L.rans_profile_enable.argtypes = [u64, u32]
         L.rans_profile_reset.argtypes = []
         L.rans_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(u64)]
         L.rans_profile_kernel_name.argtypes = [C.c_int]
@@ -188,13 +188,14 @@ def profile_kernel_names():
         i += 1
 
 
-def rans_profile_enable(kernels="all") -> int:
-    """kernels: "all", an iterable of kernel names, or a falsy value to switch recording off."""
+def rans_profile_enable(kernels="all", every: int = 1) -> int:
+    """kernels: "all", an iterable of kernel names, or a falsy value to switch recording off.
+    every: bracket only every n-th launch of each enabled kernel."""
     if not kernels:
-        return lib().rans_profile_enable(0)
+        return lib().rans_profile_enable(0, 1)
     names = profile_kernel_names()
     mask = (1 << len(names)) - 1 if kernels == "all" else sum(1 << names.index(k) for k in kernels)
-    return lib().rans_profile_enable(mask)
+    return lib().rans_profile_enable(mask, every)
 
 
 def rans_profile_reset() -> int:

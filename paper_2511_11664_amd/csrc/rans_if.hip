@@ -1556,6 +1556,28 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
   uint2 *wide = (uint2 *)(l_mem + kWinBytes / 4);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
+  // ---- global loads of the stream set-up first: their latency overlaps the table build below
+  const uint64_t payload_bytes = bytes - payload_off;
+  const uint8_t *dir = in + dir_off;
+  const uint64_t o0 = ld64(dir + 8ull * k), o1 = ld64(dir + 8ull * k + 8);
+  if (o0 > o1 || o1 > payload_bytes || o1 - o0 < 8ull * S || (o0 & 3)) {
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  const uint64_t ck_off = payload_off + o0;  // chunk start, from the start of the container
+  const uint8_t *ck = in + ck_off;
+  const uint64_t ck_bytes = o1 - o0;
+  const uint64_t chunk_len = cs ? cs : len;
+  const uint64_t base = (uint64_t)k * chunk_len;
+  const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
+  const uint32_t *nwk = (const uint32_t *)(ck + 4ull * S);
+  uint64_t pre_loc = 0;
+  for (uint32_t i = threadIdx.x; i < g * NT; i += NT) pre_loc += nwk[i];
+  const uint32_t j = g * NT + threadIdx.x;
+  const bool live = j < S;
+  const uint32_t nw_stored = live ? nwk[j] : 0;
+  const uint32_t s_stored = live ? ((const uint32_t *)ck)[j] : kL;
+
   // ---- tables
   const float sc = (x_max - x_min) / (float)((1u << q_bits) - 1u);
   const float zf = eq6_zero_point(x_min, sc);
@@ -1621,6 +1643,7 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
   }
   __syncthreads();
   if (WIDE) {
+#pragma unroll 4
     for (uint32_t sl = threadIdx.x; sl < total; sl += NT) {
       const uint2 e = tab[lut[sl]];
       wide[sl] = make_uint2((e.x & 0xffffu) | ((sl - (e.x >> 16)) << 16), e.y);
@@ -1629,29 +1652,11 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
   }
 
   // ---- this work-group's streams
-  const uint64_t payload_bytes = bytes - payload_off;
-  const uint8_t *dir = in + dir_off;
-  const uint64_t o0 = ld64(dir + 8ull * k), o1 = ld64(dir + 8ull * k + 8);
-  if (o0 > o1 || o1 > payload_bytes || o1 - o0 < 8ull * S || (o0 & 3)) {
-    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
-    return;
-  }
-  const uint64_t ck_off = payload_off + o0;  // chunk start, from the start of the container
-  const uint8_t *ck = in + ck_off;
-  const uint64_t ck_bytes = o1 - o0;
-  const uint64_t chunk_len = cs ? cs : len;
-  const uint64_t base = (uint64_t)k * chunk_len;
-  const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
-  const uint32_t *nwk = (const uint32_t *)(ck + 4ull * S);
-  uint64_t pre_loc = 0;
-  for (uint32_t i = threadIdx.x; i < g * NT; i += NT) pre_loc += nwk[i];
   const uint64_t pre = block_sum64<NT>(pre_loc, misc64);
-  const uint32_t j = g * NT + threadIdx.x;
-  const bool live = j < S;
   const uint64_t rows_full = n_here / S;
   const uint32_t rem_row = (uint32_t)(n_here - rows_full * S);
   const uint64_t n_j = live ? rows_full + (j < rem_row ? 1 : 0) : 0;
-  uint32_t nw = live ? nwk[j] : 0;
+  uint32_t nw = nw_stored;
   bool bad = false;
   if (nw > n_j) {
     bad = true;
@@ -1709,7 +1714,7 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
     bool pending = false;
     uint4 pend_q = make_uint4(0, 0, 0, 0);
     uint32_t wnext = wread(rd9);
-    uint32_t s = ((const uint32_t *)ck)[j];
+    uint32_t s = s_stored;
     uint32_t smin = s;
     auto *ob = sink.out + base + (uint64_t)g * NT;  // uniform base of this work-group's outputs
     constexpr uint32_t kOutElem = sizeof(*sink.out);
@@ -1861,6 +1866,8 @@ struct ProfRecord {
 };
 struct Profiler {
   uint64_t mask = 0;
+  uint32_t every = 1;                 // bracket every n-th launch of an enabled kernel
+  uint32_t seen[32] = {0};            // launches seen per kernel id since the last enable
   std::vector<ProfRecord> recs;   // records in use
   std::vector<ProfRecord> pool;   // event pairs ready for reuse
   std::mutex mu;
@@ -1873,6 +1880,7 @@ struct ProfScope {
   ProfScope(int kid, hipStream_t s) : st(s) {
     if (!((g_prof.mask >> kid) & 1)) return;
     std::lock_guard<std::mutex> lk(g_prof.mu);
+    if (g_prof.seen[kid]++ % g_prof.every != 0) return;
     if (!g_prof.pool.empty()) {
       r = g_prof.pool.back();
       g_prof.pool.pop_back();
@@ -2393,9 +2401,11 @@ int rans_last_status(const void *d_ws, void *stream) {
   return status;
 }
 
-int rans_profile_enable(uint64_t kernel_mask) {
+int rans_profile_enable(uint64_t kernel_mask, uint32_t every) {
   std::lock_guard<std::mutex> lk(g_prof.mu);
   g_prof.mask = kernel_mask;
+  g_prof.every = every ? every : 1;
+  for (auto &c : g_prof.seen) c = 0;
   return RANS_OK;
 }
 

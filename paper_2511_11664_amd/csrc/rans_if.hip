@@ -17,6 +17,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 #include <type_traits>
 #include <vector>
@@ -37,8 +38,13 @@ constexpr uint32_t kMaxParts = 1024;    // work-groups (partial results) of the 
 
 // Control block at the start of the workspace (device side).
 struct Ctl {
-  int32_t status;                        // first data-dependent error of the current call
-  uint32_t min_key, max_key, nonfinite;  // min/max as order-preserving integer keys
+  // {status, status_seq} form one 64-bit word: the first data-dependent error of call number
+  // status_seq.  An entry of another call number counts as "no error", so nothing has to reset the
+  // word when a call starts (and a kernel's work-groups need not wait for such a reset).
+  int32_t status;
+  uint32_t status_seq;
+  uint32_t last_seq;                     // number of the latest call enqueued on this workspace
+  uint32_t reserved0;
   float x_min, x_max, scale, zero_point; // Eq. 6
   uint64_t len_d;                        // l_D of Eq. 7
   uint64_t payload_off, dir_off;         // container section offsets
@@ -47,6 +53,14 @@ struct Ctl {
   uint32_t pad[46];
 };
 static_assert(sizeof(Ctl) == 256, "control block is 256 bytes");
+
+// What kernels receive: the control block and the number of the call they belong to.
+struct CtlRef {
+  Ctl *p;
+  uint32_t seq;
+  __host__ __device__ Ctl *operator->() const { return p; }
+  __host__ __device__ explicit operator bool() const { return p != nullptr; }
+};
 
 struct Layout {
   // common
@@ -146,7 +160,23 @@ size_t stream_bound(const rans_params &p, const Layout &L) {
 
 // ------------------------------------------------------------------ device helpers
 
-__device__ __forceinline__ void set_status(Ctl *ctl, int code) { atomicCAS(&ctl->status, 0, code); }
+// Status of the call ctl.seq (0 = no error so far).
+__device__ __forceinline__ int get_status(const CtlRef &ctl) {
+  const unsigned long long v = *(volatile const unsigned long long *)&ctl.p->status;
+  return (uint32_t)(v >> 32) == ctl.seq ? (int)(uint32_t)v : 0;
+}
+// Records `code` as the error of call ctl.seq unless that call already has one.
+__device__ __forceinline__ void set_status(const CtlRef &ctl, int code) {
+  unsigned long long *w = (unsigned long long *)&ctl.p->status;
+  unsigned long long old = *(volatile unsigned long long *)w;
+  for (int tries = 0; tries < 64; tries++) {  // other writers only ever store an error of this call: one retry suffices
+    if ((uint32_t)(old >> 32) == ctl.seq && (uint32_t)old != 0) return;
+    const unsigned long long want = ((unsigned long long)ctl.seq << 32) | (uint32_t)code;
+    const unsigned long long prev = atomicCAS(w, old, want);
+    if (prev == old) return;
+    old = prev;
+  }
+}
 
 __device__ __forceinline__ uint32_t f2key(float v) {
   uint32_t b = __float_as_uint(v);
@@ -378,9 +408,9 @@ __global__ __launch_bounds__(kWG) void k_minmax(const T *x, uint32_t n, MinMaxPa
 
 // Start-of-call bookkeeping shared by the two kernels below: reset the control
 // block, clear the histogram and the per-chunk word counters.
-__device__ void reset_call_state(Ctl *ctl, uint32_t *cnt, uint32_t A, uint32_t *chunk_words, uint32_t nc) {
+__device__ void reset_call_state(const CtlRef &ctl, uint32_t *cnt, uint32_t A, uint32_t *chunk_words, uint32_t nc) {
   if (threadIdx.x == 0) {
-    ctl->status = 0;
+    ctl->last_seq = ctl.seq;
     ctl->len_d = 0;
     ctl->payload_off = ctl->dir_off = ctl->total_bytes = 0;
     ctl->nnz = 0;
@@ -392,7 +422,7 @@ __device__ void reset_call_state(Ctl *ctl, uint32_t *cnt, uint32_t A, uint32_t *
 }
 
 // Second stage of the extrema, then scale and zero point (Eq. 6).  One work-group.
-__global__ __launch_bounds__(kBig) void k_qinfo(Ctl *ctl, const MinMaxPart *part, uint32_t n_part, uint32_t q_bits,
+__global__ __launch_bounds__(kBig) void k_qinfo(CtlRef ctl, const MinMaxPart *part, uint32_t n_part, uint32_t q_bits,
                                                 rans_qinfo *out, uint32_t *cnt, uint32_t A, uint32_t *chunk_words,
                                                 uint32_t nc) {
   reset_call_state(ctl, cnt, A, chunk_words, nc);
@@ -449,7 +479,7 @@ __global__ __launch_bounds__(kBig) void k_qinfo(Ctl *ctl, const MinMaxPart *part
 
 // Copies caller-provided extrema into the control block (rans_encode path) and
 // recomputes s, z from them with the arithmetic of k_qinfo.
-__global__ __launch_bounds__(kBig) void k_qinfo_from_user(Ctl *ctl, const rans_qinfo *in, uint32_t q_bits,
+__global__ __launch_bounds__(kBig) void k_qinfo_from_user(CtlRef ctl, const rans_qinfo *in, uint32_t q_bits,
                                                           uint32_t *cnt, uint32_t A, uint32_t *chunk_words,
                                                           uint32_t nc) {
   reset_call_state(ctl, cnt, A, chunk_words, nc);
@@ -477,7 +507,7 @@ constexpr int kQIter = 4;
 constexpr uint32_t kQuantBlocks = 1024;  // work-groups of the quantise / histogram kernel (persistent over tiles)
 
 template <typename T, bool VEC>
-__global__ __launch_bounds__(kWG) void k_quant_hist(const T *x, uint32_t n, Ctl *ctl, uint32_t q_bits,
+__global__ __launch_bounds__(kWG) void k_quant_hist(const T *x, uint32_t n, CtlRef ctl, uint32_t q_bits,
                                                     uint8_t *sym, uint32_t *cnt, int skip_zero_bin) {
   constexpr bool IS_SYM = sizeof(T) == 1;
   constexpr int V = VEC ? (int)(16 / sizeof(T)) : 1;
@@ -658,7 +688,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
 // r[i] = row_end[i] - row_end[i-1] (the NON-cumulative row count), histogrammed.
 template <bool LDS_HIST>
 __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint32_t N, uint16_t *r, uint32_t *cnt,
-                                                  uint32_t A, Ctl *ctl) {
+                                                  uint32_t A, CtlRef ctl) {
   extern __shared__ uint32_t hist[];
   if (LDS_HIST) {
     for (uint32_t a = threadIdx.x; a < A; a += kWG) hist[a] = 0;
@@ -694,14 +724,14 @@ __device__ __forceinline__ uint64_t ld64(const uint8_t *p) { return (uint64_t)ld
 // One work-group: counts -> f with sum 2^M (largest-count symbol absorbs a surplus,
 // largest-f symbols pay a deficit, lowest index on ties), F = exclusive cumulative
 // sum, encoder table {reciprocal, f | F << 16}, container header and table.
-__global__ __launch_bounds__(kBig) void k_normalize(Ctl *ctl, const uint32_t *cnt, uint32_t *fq, uint2 *enc_tab,
+__global__ __launch_bounds__(kBig) void k_normalize(CtlRef ctl, const uint32_t *cnt, uint32_t *fq, uint2 *enc_tab,
                                                     uint32_t A, rans_params p, uint64_t n_elems, int dense,
                                                     uint8_t *out, uint64_t cap) {
   __shared__ uint64_t sh64[kBig / 64];
   __shared__ uint32_t sh32[kBig / 64];
   __shared__ int64_t s_d;
   const uint32_t M = p.freq_bits, total = 1u << M;
-  if (ctl->status != 0) return;  // uniform: written by an earlier kernel
+  if (get_status(ctl) != 0) return;  // uniform: written by an earlier kernel
   uint64_t len_loc = 0, present_loc = 0;
   for (uint32_t a = threadIdx.x; a < A; a += kBig) {
     uint32_t c = cnt[a];
@@ -811,7 +841,7 @@ __global__ __launch_bounds__(kBig) void k_normalize(Ctl *ctl, const uint32_t *cn
 struct SrcDense {
   const uint8_t *sym;
   static constexpr int kMaxSpl = 4;
-  __device__ __forceinline__ void init(const Ctl *) {}
+  __device__ __forceinline__ void init(const CtlRef &) {}
   __device__ __forceinline__ uint32_t operator()(uint64_t i) const { return sym[i]; }
   template <int SPL>
   __device__ __forceinline__ uint32_t fetch(uint64_t i) const {
@@ -827,7 +857,7 @@ struct SrcCsr {
   const uint16_t *c, *r;
   uint64_t nnz;
   static constexpr int kMaxSpl = 2;
-  __device__ __forceinline__ void init(const Ctl *ctl) { nnz = ctl->nnz; }
+  __device__ __forceinline__ void init(const CtlRef &ctl) { nnz = ctl->nnz; }
   __device__ __forceinline__ uint32_t operator()(uint64_t i) const {
     if (i < nnz) return v[i];
     if (i < 2 * nnz) return c[i - nnz];
@@ -883,11 +913,11 @@ __device__ __forceinline__ EncEntry load_entry(const uint2 *g_tab, const uint32_
 // floor(s / f) comes from a multiply-high with floor(2^32 / f) plus one correction.
 template <class Src, int SPL, int TAB, bool MUL24>
 __global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uint32_t A, uint32_t M, uint32_t S,
-                                                uint32_t cs, const Ctl *ctl, uint16_t *scratch, uint32_t capw,
+                                                uint32_t cs, CtlRef ctl, uint16_t *scratch, uint32_t capw,
                                                 uint32_t *st_out, uint32_t *nw_out, uint32_t *chunk_words,
                                                 uint32_t groups) {
   extern __shared__ __align__(16) uint32_t l_mem[];  // the only LDS of this kernel, so the ring starts at offset 0
-  if (ctl->status != 0) return;
+  if (get_status(ctl) != 0) return;
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
   if (k >= ctl->n_chunks) return;
   src.init(ctl);
@@ -1041,10 +1071,10 @@ __global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uin
 }
 
 // Chunk sizes -> directory (byte offsets from the payload start), total size.
-__global__ __launch_bounds__(kBig) void k_chunk_scan(Ctl *ctl, uint32_t *chunk_words, uint32_t S, uint8_t *out,
+__global__ __launch_bounds__(kBig) void k_chunk_scan(CtlRef ctl, uint32_t *chunk_words, uint32_t S, uint8_t *out,
                                                      uint64_t cap, uint64_t *d_stream_bytes) {
   __shared__ uint64_t sh64[kBig / 64];
-  if (ctl->status != 0) {
+  if (get_status(ctl) != 0) {
     if (threadIdx.x == 0 && d_stream_bytes) *d_stream_bytes = 0;
     return;
   }
@@ -1104,14 +1134,14 @@ __global__ __launch_bounds__(kBig) void k_chunk_scan(Ctl *ctl, uint32_t *chunk_w
 constexpr uint32_t kGatherTile = 8192;     // words per LDS tile
 constexpr uint32_t kFusedScanMax = 4096;   // chunks up to which the gather kernel scans the sizes itself
 template <bool FUSED_SCAN>
-__global__ __launch_bounds__(kWG) void k_gather(Ctl *ctl, const uint16_t *scratch, uint32_t capw, const uint32_t *st,
+__global__ __launch_bounds__(kWG) void k_gather(CtlRef ctl, const uint16_t *scratch, uint32_t capw, const uint32_t *st,
                                                 const uint32_t *nw_arr, const uint32_t *chunk_words, uint32_t S,
                                                 uint32_t groups, uint8_t *out, uint64_t cap,
                                                 uint64_t *d_stream_bytes) {
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
   __shared__ uint16_t tile[kGatherTile];
-  if (ctl->status != 0) {
+  if (get_status(ctl) != 0) {
     if (FUSED_SCAN && blockIdx.x == 0 && threadIdx.x == 0 && d_stream_bytes) *d_stream_bytes = 0;
     return;
   }
@@ -1201,7 +1231,7 @@ __global__ __launch_bounds__(kWG) void k_gather(Ctl *ctl, const uint16_t *scratc
 // One work-group: validate the header against the expected geometry, rebuild F,
 // the slot -> symbol table (Eq. 3) and the decoder table f | F << 16, recompute
 // s and z from the stored extrema.
-__global__ __launch_bounds__(kBig) void k_dec_prepare(const uint8_t *in, uint64_t bytes, Ctl *ctl, rans_header h,
+__global__ __launch_bounds__(kBig) void k_dec_prepare(const uint8_t *in, uint64_t bytes, CtlRef ctl, rans_header h,
                                                       uint16_t *lut, uint32_t *tab, uint32_t *Farr,
                                                       rans_qinfo *qout) {
   __shared__ uint32_t sh32[kBig / 64];
@@ -1225,7 +1255,8 @@ __global__ __launch_bounds__(kBig) void k_dec_prepare(const uint8_t *in, uint64_
       ok = ok && ld64(in + dir_off) == 0 && ld64(in + dir_off + 8ull * h.n_chunks) == bytes - payload_off;
     }
     s_ok = ok;
-    ctl->status = ok ? 0 : RANS_ERR_CORRUPT;
+    ctl->last_seq = ctl.seq;
+    if (!ok) set_status(ctl, RANS_ERR_CORRUPT);
     ctl->len_d = h.len_d;
     ctl->n_chunks = h.n_chunks;
     ctl->dir_off = dir_off;
@@ -1308,12 +1339,12 @@ __global__ __launch_bounds__(kBig) void k_dec_prepare(const uint8_t *in, uint64_
 
 struct SinkSym {
   uint8_t *out;
-  __device__ __forceinline__ void init(const Ctl *) {}
+  __device__ __forceinline__ void init(const CtlRef &) {}
   __device__ __forceinline__ void put(uint64_t i, uint32_t x) const { out[i] = (uint8_t)x; }
 };
 struct SinkU16 {
   uint16_t *out;
-  __device__ __forceinline__ void init(const Ctl *) {}
+  __device__ __forceinline__ void init(const CtlRef &) {}
   __device__ __forceinline__ void put(uint64_t i, uint32_t x) const { out[i] = (uint16_t)x; }
 };
 // Inverse of Eq. 6 fused into the decoder: x = s * (xhat - z).
@@ -1321,7 +1352,7 @@ template <typename OutT>
 struct SinkFloat {
   OutT *out;
   float s, zf, x_min;
-  __device__ __forceinline__ void init(const Ctl *ctl) {
+  __device__ __forceinline__ void init(const CtlRef &ctl) {
     s = ctl->scale;
     zf = ctl->zero_point;
     x_min = ctl->x_min;
@@ -1337,13 +1368,13 @@ struct SinkFloat {
 // update (Eq. 4), refill of one 16-bit word when the state drops below 2^16.  All
 // sizes and offsets taken from the container are checked before use.
 template <class Sink, bool LDS_TAB>
-__global__ __launch_bounds__(kWG) void k_decode(const uint8_t *in, uint64_t bytes, Ctl *ctl, const uint16_t *g_lut,
+__global__ __launch_bounds__(kWG) void k_decode(const uint8_t *in, uint64_t bytes, CtlRef ctl, const uint16_t *g_lut,
                                                 const uint32_t *g_tab, uint32_t A, uint32_t M, uint32_t S,
                                                 uint32_t cs, uint32_t groups, Sink sink) {
   extern __shared__ __align__(16) uint32_t l_mem[];
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
-  if (ctl->status != 0) return;
+  if (get_status(ctl) != 0) return;
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
   const uint32_t nc = ctl->n_chunks;
   if (k >= nc) return;
@@ -1429,13 +1460,14 @@ struct HdrImage {
   uint32_t w[32];
 };
 
-// One wave: compare the header and the ends of the directory with what the host
-// expects, check the zero padding after the frequency table, reset the status word
-// and publish the geometry and the quantiser parameters (Eq. 6, recomputed from the
-// stored extrema with the encoder's arithmetic).
-__global__ __launch_bounds__(64) void k_dec_begin(const uint8_t *in, uint64_t bytes, Ctl *ctl, HdrImage img,
-                                                  rans_header h, rans_qinfo *qout) {
-  const uint32_t lane = threadIdx.x;
+// First wave of work-group 0 of the fast decoder: compare the header and the ends of the
+// directory with what the host expects, check the zero padding after the frequency table,
+// publish the geometry and the quantiser parameters (Eq. 6, recomputed from the stored extrema
+// with the encoder's arithmetic).  The other work-groups do not wait for this: they take the
+// geometry from the kernel arguments and report what they find themselves.
+__device__ void dec_check_header(const uint8_t *in, uint64_t bytes, const CtlRef &ctl, const HdrImage &img,
+                                 const rans_header &h, rans_qinfo *qout) {
+  const uint32_t lane = threadIdx.x;  // called by threads 0..63
   const uint32_t A = h.alphabet;
   const uint64_t table_off = kHdrBytes;
   const uint64_t dir_off = table_off + (((uint64_t)A * 2 + 7) & ~7ull);
@@ -1447,7 +1479,8 @@ __global__ __launch_bounds__(64) void k_dec_begin(const uint8_t *in, uint64_t by
   for (uint64_t o = table_off + 2ull * A + 2 * lane; o < dir_off; o += 128) ok = ok && *(const uint16_t *)(in + o) == 0;
   const bool all_ok = __ballot(!ok) == 0;
   if (lane != 0) return;
-  ctl->status = all_ok ? 0 : RANS_ERR_CORRUPT;
+  ctl->last_seq = ctl.seq;
+  if (!all_ok) set_status(ctl, RANS_ERR_CORRUPT);
   ctl->len_d = h.len_d;
   ctl->n_chunks = h.n_chunks;
   ctl->dir_off = dir_off;
@@ -1466,6 +1499,12 @@ __global__ __launch_bounds__(64) void k_dec_begin(const uint8_t *in, uint64_t by
     qout->scale = sc;
     qout->zero_point = zf;
   }
+}
+
+// The same as a kernel of its own, for a container without chunks (nothing else to launch).
+__global__ __launch_bounds__(64) void k_dec_begin(const uint8_t *in, uint64_t bytes, CtlRef ctl, HdrImage img,
+                                                  rans_header h, rans_qinfo *qout) {
+  dec_check_header(in, bytes, ctl, img, h, qout);
 }
 
 // Output side of the fast decoder.  bits(x) is evaluated once per symbol value when
@@ -1534,16 +1573,17 @@ __device__ __forceinline__ uint4 load_block16(const uint8_t *in, uint64_t bytes,
 // The byte-per-slot table, the per-symbol table and the scan scratch are then only needed while the tables
 // are built; they live at tmp_off, which may alias the window (not yet in use at that time).
 template <class Sink, typename LutT, bool MUL24, int NT, bool WIDE>
-__global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t bytes, Ctl *ctl, uint32_t A,
+__global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t bytes, CtlRef ctl, uint32_t A,
                                                      uint32_t M, uint32_t S, uint32_t cs, uint32_t groups,
                                                      uint64_t len, uint64_t dir_off, uint64_t payload_off,
                                                      float x_min, float x_max, uint32_t q_bits, uint32_t tmp_off,
-                                                     Sink sink) {
+                                                     HdrImage img, rans_header hdr, rans_qinfo *qout, Sink sink) {
   extern __shared__ __align__(16) uint32_t l_mem[];
   constexpr uint32_t kWinRowBytes = 2 * NT;          // one 16-bit word per stream
   constexpr uint32_t kWinBytes = 16 * kWinRowBytes;   // 16-word window per stream
   constexpr uint32_t NW = NT / 64;                    // waves per work-group
-  if (ctl->status != 0) return;
+  // this is the first kernel of the call: no status to look at yet; work-group 0 checks the header
+  if (blockIdx.x == 0 && threadIdx.x < 64) dec_check_header(in, bytes, ctl, img, hdr, qout);
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
   const uint32_t total = 1u << M, mask = total - 1;
   // LDS: [window][lut][misc: 48 words][tab: A x 8 B], or WIDE: [window][wide table] and
@@ -1788,9 +1828,9 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
 // Exclusive cumulative sum of r (taken on the decoding side, Sec. 3.1) by one
 // work-group; checks r[i] <= K and sum r = nnz.
 __global__ __launch_bounds__(kBig) void k_row_scan(const uint16_t *r, uint32_t N, uint32_t K, uint32_t *row_off,
-                                                   Ctl *ctl) {
+                                                   CtlRef ctl) {
   __shared__ uint32_t sh[kBig / 64];
-  if (ctl->status != 0) return;
+  if (get_status(ctl) != 0) return;
   uint32_t carry = 0;
   bool bad = false;
   for (uint32_t base = 0; base < N; base += kBig) {
@@ -1812,8 +1852,8 @@ __global__ __launch_bounds__(kBig) void k_row_scan(const uint16_t *r, uint32_t N
 // Scatter v to (row, c): one thread per nonzero, the row found by bisection of the
 // cumulative row offsets.  Checks 1 <= v < 2^Q, c < K, c increasing inside a row.
 __global__ __launch_bounds__(kWG) void k_csr_expand(const uint16_t *D, const uint32_t *row_off, uint32_t N,
-                                                    uint32_t K, uint32_t q_bits, uint8_t *xhat, Ctl *ctl) {
-  if (ctl->status != 0) return;
+                                                    uint32_t K, uint32_t q_bits, uint8_t *xhat, CtlRef ctl) {
+  if (get_status(ctl) != 0) return;
   const uint32_t nnz = ctl->nnz;
   uint32_t j = blockIdx.x * kWG + threadIdx.x;
   if (j >= nnz) return;
@@ -1833,9 +1873,9 @@ __global__ __launch_bounds__(kWG) void k_csr_expand(const uint16_t *D, const uin
 
 // Inverse of Eq. 6 over a symbol array.
 template <typename OutT>
-__global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *sym, uint64_t n, const rans_qinfo *qi, const Ctl *ctl,
+__global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *sym, uint64_t n, const rans_qinfo *qi, CtlRef ctl,
                                                  OutT *out) {
-  if (ctl && ctl->status != 0) return;
+  if (ctl && get_status(ctl) != 0) return;
   const float s = qi->scale, zf = qi->zero_point, x_min = qi->x_min;
   uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (uint64_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) {
@@ -1914,6 +1954,14 @@ struct ProfScope {
 
 inline bool aligned_to(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
+// Call numbers: process-wide, never 0 (a zeroed control block then never matches a call).
+std::atomic<uint32_t> g_call_seq{0};
+inline uint32_t next_seq() {
+  uint32_t v = ++g_call_seq;
+  if (v == 0) v = ++g_call_seq;
+  return v;
+}
+
 inline uint32_t grid_for(uint64_t n, uint32_t per_block, uint32_t cap) {
   uint64_t g = (n + per_block - 1) / per_block;
   if (g < 1) g = 1;
@@ -1922,8 +1970,8 @@ inline uint32_t grid_for(uint64_t n, uint32_t per_block, uint32_t cap) {
 
 // min/max + scale/zero point + quantise/histogram of a float tensor.
 int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Layout &L, uint8_t *ws, uint8_t *d_sym,
-                    rans_qinfo *d_qinfo, hipStream_t st) {
-  Ctl *ctl = (Ctl *)(ws + L.ctl);
+                    rans_qinfo *d_qinfo, hipStream_t st, uint32_t seq) {
+  const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   uint32_t *cnt = (uint32_t *)(ws + L.cnt);
   const bool f16 = p.in_dtype == RANS_F16;
   const bool vec = aligned_to(d_x, 16) && aligned_to(d_sym, 8);
@@ -1961,8 +2009,8 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
 
 // Everything after the symbol histogram: CSR, table, coder, container.
 int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, const Layout &L, uint8_t *ws,
-                       uint8_t *d_stream, size_t cap, uint64_t *d_stream_bytes, hipStream_t st) {
-  Ctl *ctl = (Ctl *)(ws + L.ctl);
+                       uint8_t *d_stream, size_t cap, uint64_t *d_stream_bytes, hipStream_t st, uint32_t seq) {
+  const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   uint32_t *cnt = (uint32_t *)(ws + L.cnt);
   const bool csr = p.mode == RANS_MODE_CSR;
   const uint32_t A = L.A, S = p.n_streams;
@@ -2132,7 +2180,8 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
   const uint64_t payload_off = kHdrBytes + align_up((size_t)A * 2, 8) + 8 * ((uint64_t)h.n_chunks + 1);
   if (stream_bytes < payload_off) return RANS_ERR_CORRUPT;
   uint8_t *ws = (uint8_t *)d_ws;
-  Ctl *ctl = (Ctl *)(ws + L.ctl);
+  const uint32_t seq = next_seq();
+  const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   const uint32_t groups = (S + kWG - 1) / kWG;
   const bool csr = h.p.mode == RANS_MODE_CSR;
   const size_t lut_elem = A <= 256 ? 1 : 2;
@@ -2171,15 +2220,17 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
     memcpy(ib + 56, &h.n_chunks, 4);
     memcpy(ib + 60, &h.x_min, 4);
     memcpy(ib + 64, &h.x_max, 4);
-    PROF_LAUNCH(KID_DEC_PREPARE, k_dec_begin, dim3(1), dim3(64), 0, st, d_stream, (uint64_t)stream_bytes, ctl, img, h,
-                d_qinfo);
-    LAUNCH_CHECK();
+    if (!h.n_chunks) {
+      PROF_LAUNCH(KID_DEC_PREPARE, k_dec_begin, dim3(1), dim3(64), 0, st, d_stream, (uint64_t)stream_bytes, ctl, img, h,
+                  d_qinfo);
+      LAUNCH_CHECK();
+    }
     if (h.n_chunks) {
       const dim3 grid(h.n_chunks * groups_f), blk(nt);
       const uint64_t dir_off = kHdrBytes + align_up((size_t)A * 2, 8);
 #define FDEC_ARGS                                                                                            \
   d_stream, (uint64_t)stream_bytes, ctl, A, M, S, h.p.chunk_syms, groups_f, h.len_d, dir_off, payload_off, h.x_min, \
-      h.x_max, h.p.q_bits, tmp_off
+      h.x_max, h.p.q_bits, tmp_off, img, h, d_qinfo
 #define FDEC_ONE(SINKT, LUTT, MULV, NTV, WIDEV, sinkv)                                                              \
   do {                                                                                                             \
     auto kfn = k_decode_fast<SINKT, LUTT, MULV, NTV, WIDEV>;                                                       \
@@ -2309,7 +2360,7 @@ int rans_quantize(const void *d_x, uint64_t n_elems, const rans_params *p, uint8
   if (!aligned_to(d_x, p->in_dtype == RANS_F16 ? 2 : 4) || !aligned_to(d_qinfo, 4)) return RANS_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
   uint8_t *ws = (uint8_t *)d_ws;
-  return launch_quantize(d_x, n_elems, *p, L, ws, d_sym, d_qinfo, st);
+  return launch_quantize(d_x, n_elems, *p, L, ws, d_sym, d_qinfo, st, next_seq());
 }
 
 int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, const rans_qinfo *d_qinfo,
@@ -2323,7 +2374,8 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
   if (stream_cap < kHdrBytes) return RANS_ERR_CAPACITY;
   hipStream_t st = (hipStream_t)stream;
   uint8_t *ws = (uint8_t *)d_ws;
-  Ctl *ctl = (Ctl *)(ws + L.ctl);
+  const uint32_t seq = next_seq();
+  const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   PROF_LAUNCH(KID_QINFO, k_qinfo_from_user, dim3(1), dim3(kBig), 0, st, ctl, d_qinfo, p->q_bits,
               (uint32_t *)(ws + L.cnt), L.A, (uint32_t *)(ws + L.chunk_words), L.nc_max);
   LAUNCH_CHECK();
@@ -2337,7 +2389,7 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
       PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, false>), dim3(g), dim3(kWG), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
     LAUNCH_CHECK();
   }
-  return launch_encode_tail(d_sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st);
+  return launch_encode_tail(d_sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq);
 }
 
 int rans_compress(const void *d_x, uint64_t n_elems, const rans_params *p, uint8_t *d_stream, size_t stream_cap,
@@ -2351,9 +2403,10 @@ int rans_compress(const void *d_x, uint64_t n_elems, const rans_params *p, uint8
   if (stream_cap < kHdrBytes) return RANS_ERR_CAPACITY;
   hipStream_t st = (hipStream_t)stream;
   uint8_t *ws = (uint8_t *)d_ws;
-  rc = launch_quantize(d_x, n_elems, *p, L, ws, ws + L.sym, nullptr, st);
+  const uint32_t seq = next_seq();
+  rc = launch_quantize(d_x, n_elems, *p, L, ws, ws + L.sym, nullptr, st, seq);
   if (rc) return rc;
-  return launch_encode_tail(ws + L.sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st);
+  return launch_encode_tail(ws + L.sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq);
 }
 
 int rans_decode(const uint8_t *d_stream, size_t stream_bytes, const rans_header *h_hdr, uint8_t *d_sym,
@@ -2379,9 +2432,9 @@ int rans_dequantize(const uint8_t *d_sym, uint64_t n_elems, const rans_qinfo *d_
   hipStream_t st = (hipStream_t)stream;
   uint32_t g = grid_for(n_elems, kWG * 8, 8192);
   if (out_dtype == RANS_F32)
-    PROF_LAUNCH(KID_DEQUANT, (k_dequant<float>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, (const Ctl *)nullptr, (float *)d_x_out);
+    PROF_LAUNCH(KID_DEQUANT, (k_dequant<float>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, CtlRef{nullptr, 0}, (float *)d_x_out);
   else
-    PROF_LAUNCH(KID_DEQUANT, (k_dequant<__half>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, (const Ctl *)nullptr, (__half *)d_x_out);
+    PROF_LAUNCH(KID_DEQUANT, (k_dequant<__half>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, CtlRef{nullptr, 0}, (__half *)d_x_out);
   LAUNCH_CHECK();
   return RANS_OK;
 }
@@ -2394,11 +2447,11 @@ int rans_peek_header(const void *h_bytes, size_t n_bytes, rans_header *out) {
 
 int rans_last_status(const void *d_ws, void *stream) {
   if (!d_ws) return RANS_ERR_ARG;
-  int32_t status = 0;
+  uint32_t w[3] = {0, 0, 0};  // status, status_seq, last_seq
   hipStream_t st = (hipStream_t)stream;
-  if (hipMemcpyAsync(&status, d_ws, sizeof(status), hipMemcpyDeviceToHost, st) != hipSuccess) return RANS_ERR_HIP;
+  if (hipMemcpyAsync(w, d_ws, sizeof(w), hipMemcpyDeviceToHost, st) != hipSuccess) return RANS_ERR_HIP;
   if (hipStreamSynchronize(st) != hipSuccess) return RANS_ERR_HIP;
-  return status;
+  return w[1] == w[2] ? (int32_t)w[0] : RANS_OK;  // an error of an older call is not this call's
 }
 
 int rans_profile_enable(uint64_t kernel_mask, uint32_t every) {

@@ -504,15 +504,17 @@ __global__ __launch_bounds__(kBig) void k_qinfo_from_user(CtlRef ctl, const rans
 // LDS address.
 constexpr int kHistRep = 8;
 constexpr int kQIter = 4;
-constexpr uint32_t kQuantBlocks = 1024;  // work-groups of the quantise / histogram kernel (persistent over tiles)
+constexpr int QNT = 1024;                // lanes per work-group of the quantise / histogram kernel
+constexpr uint32_t kQuantBlocks = 256;   // its work-groups (persistent over tiles): few of them, because each one ends
+                                         // with a burst of same-address atomics on the global histogram
 
-template <typename T, bool VEC>
-__global__ __launch_bounds__(kWG) void k_quant_hist(const T *x, uint32_t n, CtlRef ctl, uint32_t q_bits,
+template <typename T, bool VEC, int NT>
+__global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRef ctl, uint32_t q_bits,
                                                     uint8_t *sym, uint32_t *cnt, int skip_zero_bin) {
   constexpr bool IS_SYM = sizeof(T) == 1;
   constexpr int V = VEC ? (int)(16 / sizeof(T)) : 1;
   __shared__ uint32_t h[256 * kHistRep];
-  for (int i = threadIdx.x; i < 256 * kHistRep; i += kWG) h[i] = 0;
+  for (int i = threadIdx.x; i < 256 * kHistRep; i += NT) h[i] = 0;
   __syncthreads();
   // s == 0 (constant tensor) or NaN (flagged input): quantise with s = 1, z = 0 and a top level of 0,
   // which maps everything to symbol 0 without a branch in the loop
@@ -524,7 +526,7 @@ __global__ __launch_bounds__(kWG) void k_quant_hist(const T *x, uint32_t n, CtlR
   FastDiv fd;
   fd.init(s);
   const uint32_t rep = threadIdx.x & (kHistRep - 1);
-  const uint32_t tile = kWG * V * kQIter;
+  const uint32_t tile = NT * V * kQIter;
   auto bump = [&](uint32_t a) { atomicAdd(&h[a * kHistRep + rep], 1u); };
   auto run = [&](auto fast_tag) {
   constexpr bool FAST = decltype(fast_tag)::value;
@@ -537,7 +539,7 @@ __global__ __launch_bounds__(kWG) void k_quant_hist(const T *x, uint32_t n, CtlR
   for (uint64_t base = (uint64_t)blockIdx.x * tile; base < n; base += (uint64_t)gridDim.x * tile)
 #pragma unroll
   for (int it = 0; it < kQIter; it++) {
-    uint64_t e0 = base + ((uint64_t)it * kWG + threadIdx.x) * V;
+    uint64_t e0 = base + ((uint64_t)it * NT + threadIdx.x) * V;
     if (e0 >= n) break;
     if (VEC && e0 + V <= n) {
       if constexpr (IS_SYM) {
@@ -583,7 +585,7 @@ __global__ __launch_bounds__(kWG) void k_quant_hist(const T *x, uint32_t n, CtlR
   if (fast) run(std::true_type{});
   else run(std::false_type{});
   __syncthreads();
-  for (int a = threadIdx.x; a < 256; a += kWG) {
+  for (int a = threadIdx.x; a < 256; a += NT) {
     uint32_t t = 0;
 #pragma unroll
     for (int r = 0; r < kHistRep; r++) t += h[a * kHistRep + r];
@@ -1993,14 +1995,14 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
               (uint32_t *)(ws + L.chunk_words), L.nc_max);
   LAUNCH_CHECK();
   if (n) {
-    uint32_t g = grid_for(n, kWG * V * kQIter, kQuantBlocks);
+    uint32_t g = grid_for(n, QNT * V * kQIter, kQuantBlocks);
     int skip0 = p.mode == RANS_MODE_CSR;
     if (f16) {
-      if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
-      else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+      if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, true, QNT>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+      else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, false, QNT>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
     } else {
-      if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
-      else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+      if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, true, QNT>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+      else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, false, QNT>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
     }
     LAUNCH_CHECK();
   }
@@ -2381,12 +2383,12 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
   LAUNCH_CHECK();
   if (n_elems) {
     const bool vec = aligned_to(d_sym, 16);
-    const uint32_t g = grid_for(n_elems, kWG * (vec ? 16 : 1) * kQIter, kQuantBlocks);
+    const uint32_t g = grid_for(n_elems, QNT * (vec ? 16 : 1) * kQIter, kQuantBlocks);
     const int skip0 = p->mode == RANS_MODE_CSR;
     if (vec)
-      PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, true>), dim3(g), dim3(kWG), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
+      PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, true, QNT>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
     else
-      PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, false>), dim3(g), dim3(kWG), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
+      PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, false, QNT>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
     LAUNCH_CHECK();
   }
   return launch_encode_tail(d_sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq);

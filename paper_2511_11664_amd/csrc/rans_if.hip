@@ -929,7 +929,6 @@ __global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uin
   constexpr uint32_t G = kWG * SPL;       // streams per work-group = ring row length
   constexpr uint32_t kRowBytes = 2 * G;   // a power of two
   constexpr uint32_t kRingBytes = 16 * kRowBytes;
-  uint16_t *ring = (uint16_t *)l_mem;
   uint32_t *l_tab = l_mem + kRingBytes / 4;
   uint32_t *sh = l_tab + (TAB == 2 ? A * 4 : (TAB == 1 ? A * 2 : 0));  // kWG / 64 words for the final reduction
   if (TAB == 1) {
@@ -958,9 +957,15 @@ __global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uin
     gp[i] = scratch + ((uint64_t)k * S + j0 + i + 1) * capw;  // end of the stream's region, 16-byte aligned
     colb[i] = 2 * (i * kWG + threadIdx.x);
   }
-  auto slot = [&](int i, uint32_t row16) -> uint16_t * {  // ring slot (row16 & 15, column of stream i)
-    return (uint16_t *)((uint8_t *)ring + (((row16 * kRowBytes) & (kRingBytes - 1)) | colb[i]));
+  // ring slot (row16 & 15, column of stream i) as a plain LDS address: the ring starts at LDS address 0
+  typedef __attribute__((address_space(3))) uint16_t lds_u16;
+  auto slot = [&](int i, uint32_t row16) -> lds_u16 * {
+    return (lds_u16 *)(uintptr_t)(((row16 * kRowBytes) & (kRingBytes - 1)) | colb[i]);
   };
+  if ((uint32_t)(uintptr_t)(lds_u16 *)l_mem != 0) {  // cannot happen without static LDS; the slot arithmetic relies on it
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_HIP);
+    return;
+  }
   // Eq. 2 for the lane's SPL streams, phase by phase across the streams so that the
   // independent chains interleave; selects only, no branches.
   auto row = [&](const EncEntry (&e)[SPL]) {

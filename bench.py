@@ -120,12 +120,20 @@ def main():
     b_dec = nbytes + e * n
     alg = {"k_encode": n + nbytes, "k_decode": nbytes + e * n, "k_quant_hist": e * n + n, "k_minmax": e * n,
            "k_gather": 2 * nbytes}
+    # HBM-side bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary of this
+    # same command (FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size); null if there is none
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"{w.name}_{'csr' if w.mode else 'dense'}_pmc_traffic.txt")
+    if dom and os.path.exists(tfile) and not over:
+        for line in open(tfile):
+            if line.startswith(dom):
+                traffic = int(line.split()[-1])
     roof = None
     if dom:
         avg_ms = prof[dom]["total_ms"] / prof[dom]["count"]
         achieved = alg.get(dom, 0) / (avg_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "avg_us": round(avg_ms * 1e3, 2),
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "avg_us": round(avg_ms * 1e3, 2),
                 "algorithmic_bytes": alg.get(dom, 0),
                 "all_kernels_avg_us_warmup": {k: round(v["total_ms"] / v["count"] * 1e3, 2) for k, v in prof_all.items()}}
 

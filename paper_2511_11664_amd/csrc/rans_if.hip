@@ -14,6 +14,7 @@
 
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
+#include <hip/hip_ext.h>
 
 #include <cmath>
 #include <cstring>
@@ -1921,37 +1922,40 @@ struct Profiler {
 };
 Profiler g_prof;
 
-struct ProfScope {
-  ProfRecord r{-1, nullptr, nullptr};
-  hipStream_t st;
-  ProfScope(int kid, hipStream_t s) : st(s) {
-    if (!((g_prof.mask >> kid) & 1)) return;
-    std::lock_guard<std::mutex> lk(g_prof.mu);
-    if (g_prof.seen[kid]++ % g_prof.every != 0) return;
-    if (!g_prof.pool.empty()) {
-      r = g_prof.pool.back();
-      g_prof.pool.pop_back();
-    } else if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) {
-      return;
-    }
-    r.kid = kid;
-    (void)hipEventRecord(r.a, st);
+// Takes an event pair for launch `kid` if that launch is to be timed.
+inline bool prof_take(int kid, ProfRecord *r) {
+  if (!((g_prof.mask >> kid) & 1)) return false;
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  if (g_prof.seen[kid]++ % g_prof.every != 0) return false;
+  if (!g_prof.pool.empty()) {
+    *r = g_prof.pool.back();
+    g_prof.pool.pop_back();
+  } else if (hipEventCreate(&r->a) != hipSuccess || hipEventCreate(&r->b) != hipSuccess) {
+    return false;
   }
-  ~ProfScope() {
-    if (r.kid < 0) return;
-    (void)hipEventRecord(r.b, st);
-    std::lock_guard<std::mutex> lk(g_prof.mu);
-    g_prof.recs.push_back(r);
-  }
-};
+  r->kid = kid;
+  return true;
+}
+inline void prof_keep(const ProfRecord &r) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  g_prof.recs.push_back(r);
+}
 
 // ------------------------------------------------------------------ host side
 
-// Launch with optional event bracketing; the stream is always the 5th macro argument.
-#define PROF_LAUNCH(KID, KERNEL, GRID, BLOCK, LDS, STREAM, ...)            \
-  do {                                                                     \
-    ProfScope prof_scope_(KID, STREAM);                                    \
-    hipLaunchKernelGGL(KERNEL, GRID, BLOCK, LDS, STREAM, __VA_ARGS__);     \
+// Kernel launch; a timed launch hands its event pair to the runtime, which stamps
+// them with the begin and end of the kernel's execution on the device (the same
+// interval a kernel trace reports), the stream is always the 5th macro argument.
+#define PROF_LAUNCH(KID, KERNEL, GRID, BLOCK, LDS, STREAM, ...)                                \
+  do {                                                                                         \
+    ProfRecord prof_rec_{-1, nullptr, nullptr};                                                \
+    if (prof_take(KID, &prof_rec_)) {                                                          \
+      hipExtLaunchKernelGGL(KERNEL, GRID, BLOCK, LDS, STREAM, prof_rec_.a, prof_rec_.b, 0,     \
+                            __VA_ARGS__);                                                      \
+      prof_keep(prof_rec_);                                                                    \
+    } else {                                                                                   \
+      hipLaunchKernelGGL(KERNEL, GRID, BLOCK, LDS, STREAM, __VA_ARGS__);                       \
+    }                                                                                          \
   } while (0)
 
 #define LAUNCH_CHECK()                                  \

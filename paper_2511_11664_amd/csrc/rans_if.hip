@@ -33,6 +33,7 @@ constexpr int kBig = 1024;              // threads of the single-work-group kern
 constexpr uint32_t kHdrBytes = 128;
 constexpr uint32_t kLdsHistMaxA = 8192; // alphabets up to this size keep histograms / tables in LDS
 constexpr uint64_t kMaxElems = 1ull << 30;
+constexpr uint32_t kFusedGatherMax = 16384;  // encoder work-groups up to which the encoder places its words itself
 constexpr uint32_t kMaxParts = 1024;    // work-groups (partial results) of the min/max kernel
 
 // ------------------------------------------------------------------ workspace
@@ -72,6 +73,7 @@ struct Layout {
   size_t dec_lut, dec_tab, dec_F, D, row_off, dec_sym;
   size_t total;
   uint32_t A, nc_max, capw, n_blk;
+  uint32_t n_pub;  // work-groups of the encoder when it also places its words (0: separate gather kernel)
   uint64_t len_max, chunk_len_max;
 };
 
@@ -136,7 +138,11 @@ Layout make_layout(const rans_params &p, uint64_t n) {
   size_t n_sc = (size_t)L.nc_max * p.n_streams;
   L.st = take(n_sc * 4);
   L.nw = take(n_sc * 4);
-  L.chunk_words = take(((size_t)L.nc_max + 1) * 4);
+  {
+    const uint64_t wgs = (uint64_t)L.nc_max * ((p.n_streams + kWG - 1) / kWG);
+    L.n_pub = (wgs > 0 && wgs <= kFusedGatherMax) ? (uint32_t)wgs : 0;
+  }
+  L.chunk_words = take(((size_t)L.nc_max + 1 + L.n_pub) * 4);  // per-chunk word counts, then the encoder's published totals
   L.scratch = take(n_sc * L.capw * 2);
   size_t enc_end = o;
   o = overlay;
@@ -914,15 +920,59 @@ __device__ __forceinline__ EncEntry load_entry(const uint2 *g_tab, const uint32_
 // from the region's end, which leaves the words in the order the decoder reads them.
 //
 // floor(s / f) comes from a multiply-high with floor(2^32 / f) plus one correction.
-template <class Src, int SPL, int TAB, bool MUL24>
-__global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uint32_t A, uint32_t M, uint32_t S,
+//
+// FUSE: the work-group also moves its streams' words to their place in the container (what k_gather
+// does otherwise).  It publishes its word total, waits until every work-group with a lower index has
+// published its own (those were dispatched earlier and never wait for a higher index, so the wait ends;
+// it is bounded all the same and turns into RANS_ERR_HIP if the bound is hit), and derives the chunk's
+// byte offset and its own position inside the chunk from those totals.
+// Work-group barrier that orders LDS accesses only: outstanding global loads and stores stay in flight.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+constexpr int kSpinMax = 1 << 18;
+constexpr uint32_t kEncTileBytes = 16384;  // LDS tile of the fused placement (overlays ring and table)
+__device__ __forceinline__ uint32_t wait_published(const uint32_t *pub, uint32_t i, const CtlRef &ctl) {
+  for (int spins = 0; spins < kSpinMax; spins++) {
+    const uint32_t v = __hip_atomic_load(pub + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (v) return v;
+    if ((spins & 255) == 255 && get_status(ctl) != 0) return 0;
+    __builtin_amdgcn_s_sleep(4);
+  }
+  return 0;
+}
+
+template <class Src, int SPL, int TAB, bool MUL24, bool FUSE>
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k_encode(Src src, const uint2 *g_tab, uint32_t A, uint32_t M, uint32_t S,
                                                 uint32_t cs, CtlRef ctl, uint16_t *scratch, uint32_t capw,
                                                 uint32_t *st_out, uint32_t *nw_out, uint32_t *chunk_words,
-                                                uint32_t groups) {
+                                                uint32_t groups, uint32_t *wg_pub, uint8_t *out, uint64_t cap,
+                                                uint64_t *d_stream_bytes) {
   extern __shared__ __align__(16) uint32_t l_mem[];  // the only LDS of this kernel, so the ring starts at offset 0
-  if (get_status(ctl) != 0) return;
+  // every exit publishes a total (0 words), or the work-groups behind this one would wait for it
+  auto bail = [&]() {
+    if (FUSE && threadIdx.x == 0) __hip_atomic_store(wg_pub + blockIdx.x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  };
+  if (get_status(ctl) != 0) {
+    if (FUSE && blockIdx.x == 0 && threadIdx.x == 0 && d_stream_bytes) *d_stream_bytes = 0;
+    bail();
+    return;
+  }
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
-  if (k >= ctl->n_chunks) return;
+  const uint32_t nc = ctl->n_chunks;
+  if (k >= nc) {
+    if (FUSE && nc == 0 && blockIdx.x == 0 && threadIdx.x == 0) {  // empty D: only the directory's single entry
+      uint8_t *dir0 = out + ctl->dir_off;
+      st32(dir0, 0u);
+      st32(dir0 + 4, 0u);
+      ctl->total_bytes = ctl->payload_off;
+      if (d_stream_bytes) *d_stream_bytes = ctl->payload_off;
+    }
+    bail();
+    return;
+  }
   src.init(ctl);
   const uint32_t sh_lim = 32 - M, totalM = 1u << M;
   // LDS: [ring][table].  The ring comes first so that a slot address is a plain
@@ -931,7 +981,7 @@ __global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uin
   constexpr uint32_t kRowBytes = 2 * G;   // a power of two
   constexpr uint32_t kRingBytes = 16 * kRowBytes;
   uint32_t *l_tab = l_mem + kRingBytes / 4;
-  uint32_t *sh = l_tab + (TAB == 2 ? A * 4 : (TAB == 1 ? A * 2 : 0));  // kWG / 64 words for the final reduction
+  uint32_t *sh = l_tab + (TAB == 2 ? A * 4 : (TAB == 1 ? A * 2 : 0));  // 4 + 8 words for the final reductions
   if (TAB == 1) {
     for (uint32_t a = threadIdx.x; a < A; a += kWG) ((uint2 *)l_tab)[a] = g_tab[a];
   } else if (TAB == 2) {
@@ -965,6 +1015,7 @@ __global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uin
   };
   if ((uint32_t)(uintptr_t)(lds_u16 *)l_mem != 0) {  // cannot happen without static LDS; the slot arithmetic relies on it
     if (threadIdx.x == 0) set_status(ctl, RANS_ERR_HIP);
+    bail();
     return;
   }
   // Eq. 2 for the lane's SPL streams, phase by phase across the streams so that the
@@ -1063,8 +1114,10 @@ __global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uin
       // the remaining words (fewer than 8), newest at the lowest address
       uint16_t *dst = gp[i] - (nw - fl[i]);
       for (uint32_t n = nw; n-- > fl[i];) *dst++ = *slot(i, ~n);
-      st_out[(uint64_t)k * S + j0 + i] = s[i];
-      nw_out[(uint64_t)k * S + j0 + i] = nw;
+      if (!FUSE) {
+        st_out[(uint64_t)k * S + j0 + i] = s[i];
+        nw_out[(uint64_t)k * S + j0 + i] = nw;
+      }
     }
   }
   uint32_t nw[SPL];
@@ -1074,8 +1127,134 @@ __global__ __launch_bounds__(kWG) void k_encode(Src src, const uint2 *g_tab, uin
 #pragma unroll
   for (int i = 0; i < SPL; i++) mine += nw[i];
   uint32_t tot;
-  (void)block_excl_scan<kWG>(mine, sh, &tot);
-  if (threadIdx.x == 0 && tot) atomicAdd(&chunk_words[k], tot);
+  const uint32_t ex = block_excl_scan<kWG>(mine, sh, &tot);
+  if (!FUSE) {
+    if (threadIdx.x == 0 && tot) atomicAdd(&chunk_words[k], tot);
+    return;
+  }
+  if constexpr (FUSE) {
+    static_assert(!FUSE || SPL == 1, "the fused placement assumes one stream per lane");
+    if (threadIdx.x == 0) __hip_atomic_store(wg_pub + blockIdx.x, tot + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // The lane's own words come back from scratch in the aligned 16-byte blocks written above (block 0
+    // is the lowest one; it starts with `skip` words that are not part of the stream).
+    constexpr int kInFlight = 4;
+    const uint32_t nw1 = live ? nw[0] : 0;
+    const uint16_t *rend = scratch + ((uint64_t)k * S + j0 + 1) * capw;
+    const uint32_t nb = (nw1 + 7) / 8, skip = nb * 8 - nw1;
+    // totals of the work-groups before this one: whole chunks give the chunk's byte offset, the groups
+    // of this chunk before g give the position inside the chunk
+    uint64_t off_loc = 0, pre_loc = 0;
+    uint32_t failed = 0;
+    for (uint32_t c = threadIdx.x; c < k; c += kWG) {
+      uint64_t words = 0;
+      for (uint32_t g2 = 0; g2 < groups; g2++) {
+        const uint32_t v = wait_published(wg_pub, c * groups + g2, ctl);
+        failed |= v == 0;
+        words += v - 1;
+      }
+      off_loc += (8ull * S + 2 * words + 3) & ~3ull;
+    }
+    for (uint32_t g2 = threadIdx.x; g2 < g; g2 += kWG) {
+      const uint32_t v = wait_published(wg_pub, k * groups + g2, ctl);
+      failed |= v == 0;
+      pre_loc += v - 1;
+    }
+    uint64_t *sh64 = (uint64_t *)(sh + 4);
+    const uint64_t off = block_sum64<kWG>(off_loc, sh64);
+    const uint64_t pre = block_sum64<kWG>(pre_loc, sh64);
+    const uint64_t any_failed = block_sum64<kWG>(failed, sh64);
+    if (any_failed) {  // uniform: a wait ran into its bound, or another work-group reported an error
+      if (threadIdx.x == 0) {
+        if (get_status(ctl) == 0) set_status(ctl, RANS_ERR_HIP);
+        if (k == nc - 1 && g == groups - 1 && d_stream_bytes) *d_stream_bytes = 0;
+      }
+      return;
+    }
+    uint8_t *dir = out + ctl->dir_off;
+    const uint64_t my_end = ctl->payload_off + off + 8ull * S + 2 * (pre + tot);  // end of this group's words
+    const bool last_group = g == groups - 1;
+    const uint64_t chunk_end = (my_end + 3) & ~3ull;  // meaningful for the chunk's last group
+    const bool fits = (last_group ? chunk_end : my_end) <= cap;
+    if (threadIdx.x == 0) {
+      if (g == 0) {
+        st32(dir + 8ull * k, (uint32_t)off);
+        st32(dir + 8ull * k + 4, (uint32_t)(off >> 32));
+      }
+      if (k == nc - 1 && last_group) {
+        const uint64_t pay = chunk_end - ctl->payload_off;
+        st32(dir + 8ull * nc, (uint32_t)pay);
+        st32(dir + 8ull * nc + 4, (uint32_t)(pay >> 32));
+        ctl->total_bytes = chunk_end;
+        if (d_stream_bytes) *d_stream_bytes = fits ? chunk_end : 0;
+      }
+      if (!fits) set_status(ctl, RANS_ERR_CAPACITY);
+    }
+    if (!fits) return;  // uniform
+    uint8_t *ck = out + ctl->payload_off + off;
+    const uint32_t j = j0;
+    if (live) {
+      st32(ck + 4ull * j, s[0]);
+      st32(ck + 4ull * S + 4ull * j, nw1);
+    }
+    // words: registers / scratch -> LDS tile -> container.  A lane stages its own stream's words in LDS
+    // at their position in the chunk; the work-group then writes the staged tile out in aligned
+    // 16-byte vectors (single words only at the two ends of its range).  The tile reuses the ring and
+    // the table, which are no longer needed.  Tile positions are shifted by the destination's offset
+    // inside a 16-byte vector, so LDS vectors and output vectors coincide.
+    uint16_t *tile = (uint16_t *)l_mem;
+    constexpr uint32_t kTile = kEncTileBytes / 2;
+    uint16_t *dst = (uint16_t *)(ck + 8ull * S) + pre;
+    const uint32_t shift = (uint32_t)(((uintptr_t)dst >> 1) & 7);
+    uint16_t *vbase = dst - shift;  // 16-byte aligned; tile word p' (over all tiles) goes to vbase[p']
+    const uint32_t exs = ex + shift;
+    lds_barrier();  // everyone is done with the ring, the table and the reduction scratch
+    for (uint32_t t0 = 0; t0 < shift + tot; t0 += kTile) {
+      const uint32_t lo = exs > t0 ? exs : t0;
+      const uint32_t hi = exs + nw1 < t0 + kTile ? exs + nw1 : t0 + kTile;
+      auto stage = [&](const uint4 &q, uint32_t bi) {
+        const uint32_t w0 = bi * 8 - skip;  // read-order number of the block's first word (wraps in block 0)
+        const uint32_t pos0 = exs + w0;
+        if (bi * 8 >= skip && pos0 >= lo && pos0 + 8 <= hi) {
+          // the whole block belongs to the stream and to this tile: one 16-byte LDS store at a 2-byte
+          // aligned address (the target allows unaligned LDS access)
+          __builtin_memcpy(tile + (pos0 - t0), &q, 16);
+        } else {
+          const uint32_t ww[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+          for (int i = 0; i < 8; i++) {
+            const uint32_t pos = pos0 + i;
+            if (w0 + i < nw1 && pos >= lo && pos < hi) tile[pos - t0] = (uint16_t)(ww[i >> 1] >> (16 * (i & 1)));
+          }
+        }
+      };
+      if (lo < hi) {
+        const uint32_t b_lo = (lo - exs + skip) / 8, b_hi = (hi - 1 - exs + skip) / 8;
+        for (uint32_t b0 = b_lo; b0 <= b_hi; b0 += kInFlight) {
+          uint4 q[kInFlight];
+#pragma unroll
+          for (int u = 0; u < kInFlight; u++)
+            if (b0 + u <= b_hi) q[u] = *(const uint4 *)(rend - 8 * (nb - (b0 + u)));
+#pragma unroll
+          for (int u = 0; u < kInFlight; u++)
+            if (b0 + u <= b_hi) stage(q[u], b0 + u);
+        }
+      }
+      lds_barrier();
+      const uint32_t a = t0 == 0 ? shift : 0;                                      // first valid tile word
+      const uint32_t e = shift + tot - t0 < kTile ? shift + tot - t0 : kTile;      // end of the valid tile words
+      const uint32_t head_end = a ? (e < 8u ? e : 8u) : 0;
+      const uint32_t v_lo = a ? 1 : 0, v_hi = e / 8;
+      const uint32_t tail_beg = v_hi >= v_lo ? 8 * v_hi : e;
+      for (uint32_t v = v_lo + threadIdx.x; v < v_hi; v += kWG) ((uint4 *)(vbase + t0))[v] = ((const uint4 *)tile)[v];
+      if (threadIdx.x < 8) {
+        const uint32_t h = a + threadIdx.x, t = tail_beg + threadIdx.x;
+        if (h < head_end) vbase[t0 + h] = tile[h];
+        if (t < e) vbase[t0 + t] = tile[t];
+      }
+      lds_barrier();
+    }
+    if (last_group && live && j == S - 1 && ((pre + tot) & 1)) dst[tot] = 0;  // pad the chunk to 4 bytes
+  }
 }
 
 // Chunk sizes -> directory (byte offsets from the payload start), total size.
@@ -2001,7 +2180,7 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
     LAUNCH_CHECK();
   }
   PROF_LAUNCH(KID_QINFO, k_qinfo, dim3(1), dim3(kBig), 0, st, ctl, part, n_part, p.q_bits, d_qinfo, cnt, L.A,
-              (uint32_t *)(ws + L.chunk_words), L.nc_max);
+              (uint32_t *)(ws + L.chunk_words), L.nc_max + L.n_pub);
   LAUNCH_CHECK();
   if (n) {
     uint32_t g = grid_for(n, QNT * V * kQIter, kQuantBlocks);
@@ -2055,6 +2234,7 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
                      (uint2 *)(ws + L.enc_tab), A, p, n, csr ? 0 : 1, d_stream, (uint64_t)cap);
   LAUNCH_CHECK();
   const uint32_t groups = (S + kWG - 1) / kWG;
+  const bool fused_gather = L.n_pub != 0;  // the encoder places its words itself: no k_chunk_scan / k_gather
   if (L.nc_max) {
     uint16_t *scratch = (uint16_t *)(ws + L.scratch);
     uint32_t *st_arr = (uint32_t *)(ws + L.st), *nw_arr = (uint32_t *)(ws + L.nw);
@@ -2062,18 +2242,22 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     const uint2 *tab = (const uint2 *)(ws + L.enc_tab);
     const bool lds_tab = lds_hist;
     const bool mul24 = p.freq_bits >= 8;  // then floor(s/f) < 2^24 and both products fit the 24-bit multiplier
+#define ENC_LAUNCH2(SRCT, SPLV, TABV, M24, FUSEV)                                                                 \
+  PROF_LAUNCH(KID_ENCODE, (k_encode<SRCT, SPLV, TABV, M24, FUSEV>), dim3(L.nc_max * groups_e), dim3(kWG), lds_e, st, \
+              src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups_e,      \
+              cw + L.nc_max + 1, d_stream, (uint64_t)cap, d_stream_bytes)
 #define ENC_LAUNCH(SRCT, SPLV, TABV)                                                                              \
   do {                                                                                                            \
     const uint32_t groups_e = (S + kWG * SPLV - 1) / (kWG * SPLV);                                                \
-    const size_t lds_e = (TABV == 2 ? A * 16 : (TABV == 1 ? A * 8 : 0)) + 32 * kWG * SPLV + 4 * (kWG / 64);       \
-    if (mul24)                                                                                                    \
-      PROF_LAUNCH(KID_ENCODE, (k_encode<SRCT, SPLV, TABV, true>), dim3(L.nc_max * groups_e), dim3(kWG), lds_e,     \
-                  st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw,         \
-                  groups_e);                                                                                      \
-    else                                                                                                          \
-      PROF_LAUNCH(KID_ENCODE, (k_encode<SRCT, SPLV, TABV, false>), dim3(L.nc_max * groups_e), dim3(kWG), lds_e,    \
-                  st, src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw,         \
-                  groups_e);                                                                                      \
+    size_t lds_e = (TABV == 2 ? A * 16 : (TABV == 1 ? A * 8 : 0)) + 32 * kWG * SPLV + 64;                         \
+    if (fused_gather && lds_e < kEncTileBytes) lds_e = kEncTileBytes;                                             \
+    if (mul24) {                                                                                                  \
+      if (fused_gather) ENC_LAUNCH2(SRCT, SPLV, TABV, true, true);                                                \
+      else ENC_LAUNCH2(SRCT, SPLV, TABV, true, false);                                                            \
+    } else {                                                                                                      \
+      if (fused_gather) ENC_LAUNCH2(SRCT, SPLV, TABV, false, true);                                               \
+      else ENC_LAUNCH2(SRCT, SPLV, TABV, false, false);                                                           \
+    }                                                                                                             \
   } while (0)
     // One stream per lane: the hardware interleaves waves better than the compiler interleaves
     // several streams inside a lane, and the stream count rarely exceeds what the chip can hold.
@@ -2086,8 +2270,10 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       ENC_LAUNCH(SrcDense, 1, 2);
     }
 #undef ENC_LAUNCH
+#undef ENC_LAUNCH2
     LAUNCH_CHECK();
   }
+  if (fused_gather) return RANS_OK;
   const bool fused_scan = L.nc_max <= kFusedScanMax;
   if (!fused_scan) {
     PROF_LAUNCH(KID_CHUNK_SCAN, k_chunk_scan, dim3(1), dim3(kBig), 0, st, ctl, (uint32_t *)(ws + L.chunk_words), S,
@@ -2388,7 +2574,7 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
   const uint32_t seq = next_seq();
   const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   PROF_LAUNCH(KID_QINFO, k_qinfo_from_user, dim3(1), dim3(kBig), 0, st, ctl, d_qinfo, p->q_bits,
-              (uint32_t *)(ws + L.cnt), L.A, (uint32_t *)(ws + L.chunk_words), L.nc_max);
+              (uint32_t *)(ws + L.cnt), L.A, (uint32_t *)(ws + L.chunk_words), L.nc_max + L.n_pub);
   LAUNCH_CHECK();
   if (n_elems) {
     const bool vec = aligned_to(d_sym, 16);

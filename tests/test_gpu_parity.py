@@ -99,6 +99,11 @@ DENSE_CASES = [
     (50001, torch.float32, 1, 1, 64, 0),
     (20000, torch.float32, 3, 15, 64, 6400),
     (50001, torch.float32, 8, 8, 64, 640),
+    # more encoder work-groups than the chip holds at once (their placement waits on lower-numbered ones)
+    (1000003, torch.float32, 8, 12, 64, 128),
+    (2000003, torch.float16, 8, 14, 1024, 1024),
+    # more work-groups than the encoder places itself: separate size scan and gather kernels
+    (1200007, torch.float32, 8, 12, 32, 64),
 ]
 
 
@@ -122,6 +127,7 @@ CSR_CASES = [
     (17, 9000, torch.float32, 6, 15, 128, 12800),
     (40000, 1, torch.float32, 8, 12, 64, 640),
     (2, 65535, torch.float32, 8, 15, 64, 0),
+    (200000, 5, torch.float32, 8, 12, 64, 256),
 ]
 
 

@@ -46,7 +46,7 @@ struct Ctl {
   int32_t status;
   uint32_t status_seq;
   uint32_t last_seq;                     // number of the latest call enqueued on this workspace
-  uint32_t reserved0;
+  uint32_t enc_exact;                    // every entry of the division-free encoder table is exact (see k_normalize)
   float x_min, x_max, scale, zero_point; // Eq. 6
   uint64_t len_d;                        // l_D of Eq. 7
   uint64_t payload_off, dir_off;         // container section offsets
@@ -68,7 +68,7 @@ struct Layout {
   // common
   size_t ctl;
   // encode side
-  size_t mm_part, cnt, fq, enc_tab, sym, v, c, r, row_end, blk_nnz, st, nw, chunk_words, scratch;
+  size_t mm_part, cnt, fq, enc_tab, enc_tab4, sym, v, c, r, row_end, blk_nnz, st, nw, chunk_words, scratch;
   // decode side (overlays the encode side from `sym` on)
   size_t dec_lut, dec_tab, dec_F, D, row_off, dec_sym;
   size_t total;
@@ -126,6 +126,7 @@ Layout make_layout(const rans_params &p, uint64_t n) {
   L.cnt = take((size_t)L.A * 4);
   L.fq = take((size_t)L.A * 4);
   L.enc_tab = take((size_t)L.A * 8);
+  L.enc_tab4 = take((size_t)L.A * 16);
   size_t overlay = o;
   L.sym = take(n);
   if (p.mode == RANS_MODE_CSR) {
@@ -734,6 +735,7 @@ __device__ __forceinline__ uint64_t ld64(const uint8_t *p) { return (uint64_t)ld
 // largest-f symbols pay a deficit, lowest index on ties), F = exclusive cumulative
 // sum, encoder table {reciprocal, f | F << 16}, container header and table.
 __global__ __launch_bounds__(kBig) void k_normalize(CtlRef ctl, const uint32_t *cnt, uint32_t *fq, uint2 *enc_tab,
+                                                    uint4 *enc_tab4,
                                                     uint32_t A, rans_params p, uint64_t n_elems, int dense,
                                                     uint8_t *out, uint64_t cap) {
   __shared__ uint64_t sh64[kBig / 64];
@@ -827,6 +829,7 @@ __global__ __launch_bounds__(kBig) void k_normalize(CtlRef ctl, const uint32_t *
   }
   // cumulative sum, encoder table, stored table
   uint32_t carry = 0;
+  int inexact = 0;
   for (uint32_t base = 0; base < A; base += kBig) {
     uint32_t a = base + threadIdx.x;
     uint32_t f = a < A ? fq[a] : 0, tot;
@@ -836,10 +839,39 @@ __global__ __launch_bounds__(kBig) void k_normalize(CtlRef ctl, const uint32_t *
       uint32_t m = f <= 1 ? 0xffffffffu : (uint32_t)(0x100000000ull / f);
       enc_tab[a] = make_uint2(m, f | (F << 16));
       *(uint16_t *)(out + table_off + 2ull * a) = (uint16_t)f;
+      // Division-free entry {lim1, mx, Fx | sh << 16, 2^M - f}: the coder renormalises when s > lim1 and
+      // then takes q = mulhi(s, mx) >> sh for floor(s / f) in Eq. 2.  At that point s <= lim1 =
+      // f * 2^(32-M) - 1.  With 2^k <= f < 2^(k+1), mx = floor(2^(32+k) / f) + 1 and e = mx * f - 2^(32+k),
+      // q is exact for every s with s * e < 2^(32+k); the entry is marked inexact otherwise (possible only
+      // for f > 2^(M-1)).  Powers of two take mx = 2^31, sh = k - 1.  f = 1 cannot have its multiplier
+      // 2^32: it takes mx = 2^32 - 1, which gives q = s - 1 (s >= 1 there), and the missing 2^M - f is
+      // added to Fx instead.  f = 0 (absent symbol) is never looked up.
+      const uint32_t cmpl = total - f;
+      uint32_t lim1 = (f << (32 - M)) - 1u, mx = 0, sh = 0, Fx = F;
+      if (f == 1) {
+        mx = 0xffffffffu;
+        Fx = F + cmpl;
+      } else if (f > 1) {
+        const uint32_t k = 31u - (uint32_t)__clz((int)f);
+        if ((f & (f - 1)) == 0) {
+          mx = 0x80000000u;
+          sh = k - 1;
+        } else {
+          const uint64_t two = 1ull << (32 + k);
+          const uint64_t mq = two / f + 1;  // < 2^32 because f > 2^k
+          const uint64_t e = mq * f - two;
+          if ((uint64_t)lim1 * e >= two) inexact = 1;
+          mx = (uint32_t)mq;
+          sh = k;
+        }
+      }
+      enc_tab4[a] = make_uint4(lim1, mx, Fx | (sh << 16), cmpl);
     }
     carry += tot;
     __syncthreads();
   }
+  inexact = __syncthreads_or(inexact);
+  if (threadIdx.x == 0) ctl->enc_exact = inexact ? 0u : 1u;
   for (uint64_t o = table_off + 2ull * A + 2 * threadIdx.x; o < dir_off; o += 2 * kBig) *(uint16_t *)(out + o) = 0;
 }
 
@@ -851,6 +883,7 @@ struct SrcDense {
   const uint8_t *sym;
   static constexpr int kMaxSpl = 4;
   __device__ __forceinline__ void init(const CtlRef &) {}
+  __device__ __forceinline__ const uint8_t *bytes() const { return sym; }  // D as a plain byte array
   __device__ __forceinline__ uint32_t operator()(uint64_t i) const { return sym[i]; }
   template <int SPL>
   __device__ __forceinline__ uint32_t fetch(uint64_t i) const {
@@ -867,6 +900,7 @@ struct SrcCsr {
   uint64_t nnz;
   static constexpr int kMaxSpl = 2;
   __device__ __forceinline__ void init(const CtlRef &ctl) { nnz = ctl->nnz; }
+  __device__ __forceinline__ const uint8_t *bytes() const { return nullptr; }  // D is not one byte array
   __device__ __forceinline__ uint32_t operator()(uint64_t i) const {
     if (i < nnz) return v[i];
     if (i < 2 * nnz) return c[i - nnz];
@@ -881,6 +915,8 @@ struct SrcCsr {
   __device__ __forceinline__ static uint32_t get(uint32_t raw, int q) { return (raw >> (16 * q)) & 0xffffu; }
 };
 
+constexpr int kStageRows = 32;         // rows per tile of the encoder's symbol staging (dense source)
+constexpr uint32_t kRingStride = 40;  // bytes between the word rings of adjacent streams: 16 slots + padding against bank conflicts
 constexpr int kEncAhead = 8;  // rows of symbols fetched ahead of the coder; also the flush period of the word ring
 
 // Encoder table entry as the coder uses it.
@@ -945,11 +981,12 @@ __device__ __forceinline__ uint32_t wait_published(const uint32_t *pub, uint32_t
 }
 
 template <class Src, int SPL, int TAB, bool MUL24, bool FUSE>
-__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k_encode(Src src, const uint2 *g_tab, uint32_t A, uint32_t M, uint32_t S,
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k_encode(Src src, const uint2 *g_tab, const uint4 *g_tab4, uint32_t A, uint32_t M,
+                                                uint32_t S,
                                                 uint32_t cs, CtlRef ctl, uint16_t *scratch, uint32_t capw,
                                                 uint32_t *st_out, uint32_t *nw_out, uint32_t *chunk_words,
                                                 uint32_t groups, uint32_t *wg_pub, uint8_t *out, uint64_t cap,
-                                                uint64_t *d_stream_bytes) {
+                                                uint64_t *d_stream_bytes, int wide) {
   extern __shared__ __align__(16) uint32_t l_mem[];  // the only LDS of this kernel, so the ring starts at offset 0
   // every exit publishes a total (0 words), or the work-groups behind this one would wait for it
   auto bail = [&]() {
@@ -975,19 +1012,25 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
   }
   src.init(ctl);
   const uint32_t sh_lim = 32 - M, totalM = 1u << M;
-  // LDS: [ring][table].  The ring comes first so that a slot address is a plain
-  // bit-field combination of the row number and the stream's column.
-  constexpr uint32_t G = kWG * SPL;       // streams per work-group = ring row length
-  constexpr uint32_t kRowBytes = 2 * G;   // a power of two
-  constexpr uint32_t kRingBytes = 16 * kRowBytes;
+  // LDS: [ring][table].  The ring comes first (LDS address 0) so that a slot address is the lane's
+  // fixed base plus twice the slot number.
+  constexpr uint32_t G = kWG * SPL;  // streams per work-group
+  constexpr uint32_t kRingBytes = kRingStride * G;
   uint32_t *l_tab = l_mem + kRingBytes / 4;
   uint32_t *sh = l_tab + (TAB == 2 ? A * 4 : (TAB == 1 ? A * 2 : 0));  // 4 + 8 words for the final reductions
+  // TAB == 2 has two forms of the table: the division-free one when every entry of it is exact for
+  // this frequency table (the common case), else {floor(2^32/f), f, F, 2^M - f} with a correction step.
+  const bool exact = TAB == 2 && ctl->enc_exact != 0;
   if (TAB == 1) {
     for (uint32_t a = threadIdx.x; a < A; a += kWG) ((uint2 *)l_tab)[a] = g_tab[a];
   } else if (TAB == 2) {
-    for (uint32_t a = threadIdx.x; a < A; a += kWG) {
-      uint2 q = g_tab[a];
-      ((uint4 *)l_tab)[a] = make_uint4(q.x, q.y & 0xffffu, q.y >> 16, totalM - (q.y & 0xffffu));
+    if (exact) {
+      for (uint32_t a = threadIdx.x; a < A; a += kWG) ((uint4 *)l_tab)[a] = g_tab4[a];
+    } else {
+      for (uint32_t a = threadIdx.x; a < A; a += kWG) {
+        uint2 q = g_tab[a];
+        ((uint4 *)l_tab)[a] = make_uint4(q.x, q.y & 0xffffu, q.y >> 16, totalM - (q.y & 0xffffu));
+      }
     }
   }
   if (TAB != 0) __syncthreads();
@@ -997,76 +1040,98 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
   const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
   const uint32_t j0 = (g * kWG + threadIdx.x) * SPL;
   const bool live = j0 < S;  // S is a multiple of SPL: a lane's streams are all live or all absent
-  uint32_t s[SPL], nnw[SPL], fl[SPL];  // nnw = ~(number of words emitted): its low 4 bits are the ring row of the next word
+  uint32_t s[SPL], nnw[SPL], fl[SPL];  // nnw = ~(number of words emitted): its low 4 bits are the ring slot of the next word
   uint16_t *gp[SPL];                   // the next 16-byte block goes just below this address
-  uint32_t colb[SPL];                  // byte offset of the stream's column inside a ring row (stream-major: conflict-free)
+  uint32_t colb[SPL];                  // LDS address of the stream's ring: 16 slots, kRingStride bytes apart (conflict-free)
 #pragma unroll
   for (int i = 0; i < SPL; i++) {
     s[i] = kL;
     nnw[i] = ~0u;
     fl[i] = 0;
     gp[i] = scratch + ((uint64_t)k * S + j0 + i + 1) * capw;  // end of the stream's region, 16-byte aligned
-    colb[i] = 2 * (i * kWG + threadIdx.x);
+    colb[i] = kRingStride * (i * kWG + threadIdx.x);
   }
-  // ring slot (row16 & 15, column of stream i) as a plain LDS address: the ring starts at LDS address 0
+  // ring slot (slot16 & 15) of stream i as a plain LDS address: the ring starts at LDS address 0
   typedef __attribute__((address_space(3))) uint16_t lds_u16;
-  auto slot = [&](int i, uint32_t row16) -> lds_u16 * {
-    return (lds_u16 *)(uintptr_t)(((row16 * kRowBytes) & (kRingBytes - 1)) | colb[i]);
+  typedef __attribute__((address_space(3))) uint64_t lds_u64;
+  auto slot = [&](int i, uint32_t slot16) -> lds_u16 * {
+    return (lds_u16 *)(uintptr_t)(colb[i] + ((slot16 & 15u) << 1));
   };
   if ((uint32_t)(uintptr_t)(lds_u16 *)l_mem != 0) {  // cannot happen without static LDS; the slot arithmetic relies on it
     if (threadIdx.x == 0) set_status(ctl, RANS_ERR_HIP);
     bail();
     return;
   }
-  // Eq. 2 for the lane's SPL streams, phase by phase across the streams so that the
-  // independent chains interleave; selects only, no branches.
-  auto row = [&](const EncEntry (&e)[SPL]) {
-    bool c[SPL];
-    uint32_t q[SPL], rem[SPL];
-#pragma unroll
-    for (int i = 0; i < SPL; i++) c[i] = (s[i] >> sh_lim) >= e[i].f;  // too large for this symbol: emit 16 bits
-#pragma unroll
-    for (int i = 0; i < SPL; i++) *slot(i, nnw[i]) = (uint16_t)s[i];  // speculative: the slot counts only if c
-#pragma unroll
-    for (int i = 0; i < SPL; i++) {
-      s[i] = c[i] ? s[i] >> 16 : s[i];
-      nnw[i] -= c[i] ? 1u : 0u;
-    }
-#pragma unroll
-    for (int i = 0; i < SPL; i++) q[i] = __umulhi(s[i], e[i].m);
-#pragma unroll
-    for (int i = 0; i < SPL; i++) rem[i] = s[i] - (MUL24 ? __umul24(q[i], e[i].f) : q[i] * e[i].f);
-#pragma unroll
-    for (int i = 0; i < SPL; i++) q[i] += rem[i] >= e[i].f ? 1u : 0u;
-#pragma unroll
-    for (int i = 0; i < SPL; i++) s[i] = s[i] + e[i].F + (MUL24 ? __umul24(q[i], e[i].cmpl) : q[i] * e[i].cmpl);
-  };
-  auto lookup = [&](EncEntry (&e)[SPL], uint32_t raw) {
-#pragma unroll
-    for (int i = 0; i < SPL; i++) e[i] = load_entry<TAB>(g_tab, l_tab, Src::get(raw, i), totalM);
-  };
-  // move one finished block of 8 words (numbers fl .. fl+7) from the ring to global memory
+  // move one finished block of 8 words (numbers fl .. fl+7) from the ring to global memory: they sit
+  // in slots 8..15 or 0..7, ascending slot = ascending address = descending word number
   auto flush = [&](int i) {
     if (~nnw[i] - fl[i] >= 8u) {
-      const uint32_t r0 = (fl[i] & 8u) ? 0u : 8u;  // rows of the block; ascending row = ascending address
-      uint32_t w[8];
-#pragma unroll
-      for (int q = 0; q < 8; q++) w[q] = *slot(i, r0 + q);
+      const lds_u64 *r = (const lds_u64 *)(uintptr_t)(colb[i] + ((fl[i] & 8u) ? 0u : 16u));
+      const uint64_t lo = r[0], hi = r[1];
       gp[i] -= 8;
-      *(uint4 *)gp[i] = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+      *(uint4 *)gp[i] = make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
       fl[i] += 8;
     }
   };
-  if (live) {
+  // The coding loop, for one of the two table forms (an entry is {m, f, F, cmpl} with the meaning of
+  // that form: EXACT {mx, lim1, Fx | sh << 16, 2^M - f}, else {floor(2^32/f), f, F, 2^M - f}).
+  auto run = [&](auto exact_tag, auto wide_tag) {
+    constexpr bool EXACT = decltype(exact_tag)::value;
+    constexpr bool WIDE = decltype(wide_tag)::value;
+    // Eq. 2 for the lane's SPL streams, phase by phase across the streams so that the
+    // independent chains interleave; selects only, no branches.
+    auto row = [&](const EncEntry (&e)[SPL]) {
+      bool c[SPL];
+      uint32_t q[SPL];
+#pragma unroll
+      for (int i = 0; i < SPL; i++)  // too large for this symbol: emit 16 bits
+        c[i] = EXACT ? s[i] > e[i].f : (s[i] >> sh_lim) >= e[i].f;
+#pragma unroll
+      for (int i = 0; i < SPL; i++) *slot(i, nnw[i]) = (uint16_t)s[i];  // speculative: the slot counts only if c
+#pragma unroll
+      for (int i = 0; i < SPL; i++) {
+        s[i] = c[i] ? s[i] >> 16 : s[i];
+        nnw[i] -= c[i] ? 1u : 0u;
+      }
+#pragma unroll
+      for (int i = 0; i < SPL; i++) q[i] = __umulhi(s[i], e[i].m);
+      if constexpr (EXACT) {
+#pragma unroll
+        for (int i = 0; i < SPL; i++) q[i] >>= e[i].F >> 16;
+#pragma unroll
+        for (int i = 0; i < SPL; i++)
+          s[i] = (MUL24 ? __umul24(q[i], e[i].cmpl) + s[i] : q[i] * e[i].cmpl + s[i]) + (e[i].F & 0xffffu);
+      } else {
+        uint32_t rem[SPL];
+#pragma unroll
+        for (int i = 0; i < SPL; i++) rem[i] = s[i] - (MUL24 ? __umul24(q[i], e[i].f) : q[i] * e[i].f);
+#pragma unroll
+        for (int i = 0; i < SPL; i++) q[i] += rem[i] >= e[i].f ? 1u : 0u;
+#pragma unroll
+        for (int i = 0; i < SPL; i++) s[i] = s[i] + e[i].F + (MUL24 ? __umul24(q[i], e[i].cmpl) : q[i] * e[i].cmpl);
+      }
+    };
+    auto entry = [&](uint32_t x) -> EncEntry {
+      if constexpr (EXACT) {
+        const uint4 q = ((const uint4 *)l_tab)[x];
+        return EncEntry{q.y, q.x, q.z, q.w};
+      } else {
+        return load_entry<TAB>(g_tab, l_tab, x, totalM);
+      }
+    };
+    auto lookup = [&](EncEntry (&e)[SPL], uint32_t raw) {
+#pragma unroll
+      for (int i = 0; i < SPL; i++) e[i] = entry(Src::get(raw, i));
+    };
     const uint64_t rows_full = n_here / S;
     const uint32_t rem_row = (uint32_t)(n_here - rows_full * S);
     EncEntry ea[SPL], eb[SPL];
     if (rem_row) {  // ragged last row: only streams j < rem_row have a symbol there
 #pragma unroll
       for (int i = 0; i < SPL; i++) {
-        // an absent stream gets the neutral entry f = 2^M, F = 0, which leaves the state untouched
-        ea[i] = EncEntry{0u, totalM, 0u, 0u};
-        if (j0 + i < rem_row) ea[i] = load_entry<TAB>(g_tab, l_tab, src(base + rows_full * S + j0 + i), totalM);
+        // an absent stream gets a neutral entry, which leaves the state untouched
+        ea[i] = EXACT ? EncEntry{0u, 0xffffffffu, 0u, 0u} : EncEntry{0u, totalM, 0u, 0u};
+        if (j0 + i < rem_row) ea[i] = entry(src(base + rows_full * S + j0 + i));
       }
       row(ea);
     }
@@ -1083,19 +1148,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
     // full batches of kEncAhead rows: rows fetched one batch ahead, table entries one row ahead,
     // alternating between two register sets
     uint32_t cur[kEncAhead], nxt[kEncAhead];
-    auto fetch_rows = [&](uint32_t *dst, uint64_t t_hi) {  // rows t_hi-1 .. t_hi-kEncAhead
-#pragma unroll
-      for (int u = 0; u < kEncAhead; u++) dst[u] = src.template fetch<SPL>(base + (t_hi - 1 - u) * S + j0);
-    };
-    if (t) {
-      fetch_rows(nxt, t);
-      lookup(ea, nxt[0]);
-    }
-    while (t) {
-#pragma unroll
-      for (int u = 0; u < kEncAhead; u++) cur[u] = nxt[u];
-      t -= kEncAhead;
-      if (t) fetch_rows(nxt, t);
+    auto batch = [&]() {  // codes the rows in cur[]; leaves in ea the entry of nxt[0]
 #pragma unroll
       for (int u = 0; u < kEncAhead; u += 2) {
         lookup(eb, cur[u + 1]);
@@ -1107,6 +1160,87 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
       }
 #pragma unroll
       for (int i = 0; i < SPL; i++) flush(i);
+    };
+    if constexpr (WIDE) {
+      // Symbols through LDS: single-byte loads keep too few bytes in flight to cover the memory latency.
+      // A wave owns a 64-byte column of the chunk's rows.  It fetches kStageRows rows of it at a time
+      // with 16-byte loads (lane L: row L/4 and row 16 + L/4 of the tile, bytes 16 (L%4) ..), a whole tile
+      // ahead of the coder, and parks them in a private LDS area that holds two tiles, row r in line
+      // r mod 64; the coder reads its byte of each row from there.  No other wave touches the area.
+      static_assert(!WIDE || (SPL == 1 && kEncAhead == 8 && kStageRows == 32), "tile arithmetic below");
+      const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+      uint8_t *stg = (uint8_t *)(sh + 16) + wv * (2 * kStageRows * 64);
+      const uint8_t *colp = src.bytes() + base + (j0 - lane) + 16 * (lane & 3);  // the lane's 16 bytes of row 0
+      uint4 pend[2];
+      auto request = [&](uint64_t t_lo, uint64_t t_top) {  // rows t_lo .. t_lo+31 (below t_top) of the column
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+          const uint64_t r = t_lo + 16 * h + (lane >> 2);
+          pend[h] = make_uint4(0, 0, 0, 0);
+          if (r < t_top) pend[h] = *(const uint4 *)(colp + r * S);
+        }
+      };
+      auto park = [&](uint64_t t_lo) {
+#pragma unroll
+        for (int h = 0; h < 2; h++)
+          *(uint4 *)(stg + (((uint32_t)t_lo + 16 * h) & 63u) * 64 + 16 * lane) = pend[h];
+      };
+      auto read_rows = [&](uint32_t *dst, uint64_t t_hi) {  // rows t_hi-1 .. t_hi-8; t_hi is a multiple of 8
+        const uint8_t *b = stg + (((uint32_t)t_hi - 8) & 63u) * 64 + lane;
+#pragma unroll
+        for (int u = 0; u < kEncAhead; u++) dst[u] = b[(kEncAhead - 1 - u) * 64];
+      };
+      if (t) {
+        const uint64_t t_lo = (t - 1) & ~(uint64_t)(kStageRows - 1);
+        request(t_lo, t);
+        park(t_lo);
+        if (t_lo) request(t_lo - kStageRows, t_lo);
+        read_rows(nxt, t);
+        lookup(ea, nxt[0]);
+      }
+      while (t) {
+#pragma unroll
+        for (int u = 0; u < kEncAhead; u++) cur[u] = nxt[u];
+        t -= kEncAhead;
+        if (t) {
+          if ((t & (kStageRows - 1)) == 0) {  // the next rows belong to the tile below: it has arrived by now
+            park(t - kStageRows);
+            if (t > kStageRows) request(t - 2 * kStageRows, t - kStageRows);
+          }
+          read_rows(nxt, t);
+        }
+        batch();
+      }
+    } else {
+      auto fetch_rows = [&](uint32_t *dst, uint64_t t_hi) {  // rows t_hi-1 .. t_hi-kEncAhead
+#pragma unroll
+        for (int u = 0; u < kEncAhead; u++) dst[u] = src.template fetch<SPL>(base + (t_hi - 1 - u) * S + j0);
+      };
+      if (t) {
+        fetch_rows(nxt, t);
+        lookup(ea, nxt[0]);
+      }
+      while (t) {
+#pragma unroll
+        for (int u = 0; u < kEncAhead; u++) cur[u] = nxt[u];
+        t -= kEncAhead;
+        if (t) fetch_rows(nxt, t);
+        batch();
+      }
+    }
+  };
+  if (live) {
+    if constexpr (std::is_same<Src, SrcDense>::value && SPL == 1) {
+      if (wide) {
+        if (exact) run(std::true_type{}, std::true_type{});
+        else run(std::false_type{}, std::true_type{});
+      } else {
+        if (exact) run(std::true_type{}, std::false_type{});
+        else run(std::false_type{}, std::false_type{});
+      }
+    } else {
+      if (exact) run(std::true_type{}, std::false_type{});
+      else run(std::false_type{}, std::false_type{});
     }
 #pragma unroll
     for (int i = 0; i < SPL; i++) {
@@ -2231,7 +2365,8 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     }
   }
   PROF_LAUNCH(KID_NORMALIZE, k_normalize, dim3(1), dim3(kBig), 0, st, ctl, cnt, (uint32_t *)(ws + L.fq),
-                     (uint2 *)(ws + L.enc_tab), A, p, n, csr ? 0 : 1, d_stream, (uint64_t)cap);
+                     (uint2 *)(ws + L.enc_tab), (uint4 *)(ws + L.enc_tab4), A, p, n, csr ? 0 : 1, d_stream,
+                     (uint64_t)cap);
   LAUNCH_CHECK();
   const uint32_t groups = (S + kWG - 1) / kWG;
   const bool fused_gather = L.n_pub != 0;  // the encoder places its words itself: no k_chunk_scan / k_gather
@@ -2240,16 +2375,19 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     uint32_t *st_arr = (uint32_t *)(ws + L.st), *nw_arr = (uint32_t *)(ws + L.nw);
     uint32_t *cw = (uint32_t *)(ws + L.chunk_words);
     const uint2 *tab = (const uint2 *)(ws + L.enc_tab);
+    const uint4 *tab4 = (const uint4 *)(ws + L.enc_tab4);
     const bool lds_tab = lds_hist;
     const bool mul24 = p.freq_bits >= 8;  // then floor(s/f) < 2^24 and both products fit the 24-bit multiplier
 #define ENC_LAUNCH2(SRCT, SPLV, TABV, M24, FUSEV)                                                                 \
   PROF_LAUNCH(KID_ENCODE, (k_encode<SRCT, SPLV, TABV, M24, FUSEV>), dim3(L.nc_max * groups_e), dim3(kWG), lds_e, st, \
-              src, tab, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups_e,      \
-              cw + L.nc_max + 1, d_stream, (uint64_t)cap, d_stream_bytes)
+              src, tab, tab4, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups_e,      \
+              cw + L.nc_max + 1, d_stream, (uint64_t)cap, d_stream_bytes, wide_e)
 #define ENC_LAUNCH(SRCT, SPLV, TABV)                                                                              \
   do {                                                                                                            \
     const uint32_t groups_e = (S + kWG * SPLV - 1) / (kWG * SPLV);                                                \
-    size_t lds_e = (TABV == 2 ? A * 16 : (TABV == 1 ? A * 8 : 0)) + 32 * kWG * SPLV + 64;                         \
+    size_t lds_e = (TABV == 2 ? A * 16 : (TABV == 1 ? A * 8 : 0)) + kRingStride * kWG * SPLV + 64;                         \
+    const int wide_e = !csr && SPLV == 1 && S % 64 == 0 && aligned_to(d_sym, 16);                                 \
+    if (wide_e) lds_e += (kWG / 64) * 2 * kStageRows * 64;                                                        \
     if (fused_gather && lds_e < kEncTileBytes) lds_e = kEncTileBytes;                                             \
     if (mul24) {                                                                                                  \
       if (fused_gather) ENC_LAUNCH2(SRCT, SPLV, TABV, true, true);                                                \

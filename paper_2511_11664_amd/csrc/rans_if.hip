@@ -144,7 +144,8 @@ Layout make_layout(const rans_params &p, uint64_t n) {
     L.n_pub = (wgs > 0 && wgs <= kFusedGatherMax) ? (uint32_t)wgs : 0;
   }
   L.chunk_words = take(((size_t)L.nc_max + 1 + L.n_pub) * 4);  // per-chunk word counts, then the encoder's published totals
-  L.scratch = take(n_sc * L.capw * 2);
+  // word blocks of the encoder, per work-group (kWG streams, absent ones included): see k_encode
+  L.scratch = take((size_t)L.nc_max * ((p.n_streams + kWG - 1) / kWG) * kWG * L.capw * 2);
   size_t enc_end = o;
   o = overlay;
   L.dec_lut = take(((size_t)2 << p.freq_bits));
@@ -1040,37 +1041,40 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
   const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
   const uint32_t j0 = (g * kWG + threadIdx.x) * SPL;
   const bool live = j0 < S;  // S is a multiple of SPL: a lane's streams are all live or all absent
-  uint32_t s[SPL], nnw[SPL], fl[SPL];  // nnw = ~(number of words emitted): its low 4 bits are the ring slot of the next word
-  uint16_t *gp[SPL];                   // the next 16-byte block goes just below this address
-  uint32_t colb[SPL];                  // LDS address of the stream's ring: 16 slots, kRingStride bytes apart (conflict-free)
+  // Emitted words wait in a 16-slot LDS area per stream, filled from its top slot downwards: `wp` is the
+  // LDS address of the slot of the next word.  Once 8 or more words wait, the 8 oldest (the upper half:
+  // ascending address = descending word number, the order the decoder reads) leave as one 16-byte block
+  // and the lower half moves up.
+  uint32_t s[SPL], wp[SPL];
+  // Scratch holds the work-group's 16-byte blocks block-major: block b of the stream in column c at
+  // ((b * G + c) * 8) words from the work-group's base, so that the lanes of a wave that flush the
+  // same block number write adjacent memory.
+  uint16_t *gp[SPL];    // where the stream's next 16-byte block goes
+  uint32_t colb[SPL];   // LDS address of the stream's area; areas are kRingStride bytes apart (conflict-free)
 #pragma unroll
   for (int i = 0; i < SPL; i++) {
     s[i] = kL;
-    nnw[i] = ~0u;
-    fl[i] = 0;
-    gp[i] = scratch + ((uint64_t)k * S + j0 + i + 1) * capw;  // end of the stream's region, 16-byte aligned
+    gp[i] = scratch + (uint64_t)blockIdx.x * (kWG * SPL) * capw + (i * kWG + threadIdx.x) * 8;
     colb[i] = kRingStride * (i * kWG + threadIdx.x);
+    wp[i] = colb[i] + 30;
   }
-  // ring slot (slot16 & 15) of stream i as a plain LDS address: the ring starts at LDS address 0
+  // the areas start at LDS address 0, so that `wp` is a plain LDS address
   typedef __attribute__((address_space(3))) uint16_t lds_u16;
   typedef __attribute__((address_space(3))) uint64_t lds_u64;
-  auto slot = [&](int i, uint32_t slot16) -> lds_u16 * {
-    return (lds_u16 *)(uintptr_t)(colb[i] + ((slot16 & 15u) << 1));
-  };
   if ((uint32_t)(uintptr_t)(lds_u16 *)l_mem != 0) {  // cannot happen without static LDS; the slot arithmetic relies on it
     if (threadIdx.x == 0) set_status(ctl, RANS_ERR_HIP);
     bail();
     return;
   }
-  // move one finished block of 8 words (numbers fl .. fl+7) from the ring to global memory: they sit
-  // in slots 8..15 or 0..7, ascending slot = ascending address = descending word number
   auto flush = [&](int i) {
-    if (~nnw[i] - fl[i] >= 8u) {
-      const lds_u64 *r = (const lds_u64 *)(uintptr_t)(colb[i] + ((fl[i] & 8u) ? 0u : 16u));
-      const uint64_t lo = r[0], hi = r[1];
-      gp[i] -= 8;
-      *(uint4 *)gp[i] = make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
-      fl[i] += 8;
+    if (wp[i] < colb[i] + 16) {  // 8 or more words wait
+      lds_u64 *r = (lds_u64 *)(uintptr_t)colb[i];
+      const uint64_t lo0 = r[0], lo1 = r[1], hi0 = r[2], hi1 = r[3];
+      *(uint4 *)gp[i] = make_uint4((uint32_t)hi0, (uint32_t)(hi0 >> 32), (uint32_t)hi1, (uint32_t)(hi1 >> 32));
+      gp[i] += kWG * SPL * 8;
+      r[2] = lo0;
+      r[3] = lo1;
+      wp[i] += 16;
     }
   };
   // The coding loop, for one of the two table forms (an entry is {m, f, F, cmpl} with the meaning of
@@ -1087,11 +1091,11 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
       for (int i = 0; i < SPL; i++)  // too large for this symbol: emit 16 bits
         c[i] = EXACT ? s[i] > e[i].f : (s[i] >> sh_lim) >= e[i].f;
 #pragma unroll
-      for (int i = 0; i < SPL; i++) *slot(i, nnw[i]) = (uint16_t)s[i];  // speculative: the slot counts only if c
+      for (int i = 0; i < SPL; i++) *(lds_u16 *)(uintptr_t)wp[i] = (uint16_t)s[i];  // speculative: the slot counts only if c
 #pragma unroll
       for (int i = 0; i < SPL; i++) {
         s[i] = c[i] ? s[i] >> 16 : s[i];
-        nnw[i] -= c[i] ? 1u : 0u;
+        wp[i] = c[i] ? wp[i] - 2 : wp[i];
       }
 #pragma unroll
       for (int i = 0; i < SPL; i++) q[i] = __umulhi(s[i], e[i].m);
@@ -1125,7 +1129,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
     };
     const uint64_t rows_full = n_here / S;
     const uint32_t rem_row = (uint32_t)(n_here - rows_full * S);
-    EncEntry ea[SPL], eb[SPL];
+    EncEntry ea[SPL];
     if (rem_row) {  // ragged last row: only streams j < rem_row have a symbol there
 #pragma unroll
       for (int i = 0; i < SPL; i++) {
@@ -1148,15 +1152,21 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
     // full batches of kEncAhead rows: rows fetched one batch ahead, table entries one row ahead,
     // alternating between two register sets
     uint32_t cur[kEncAhead], nxt[kEncAhead];
-    auto batch = [&]() {  // codes the rows in cur[]; leaves in ea the entry of nxt[0]
+    // Table entries are looked up kLook rows ahead of their use (an LDS read takes longer than the
+    // arithmetic of a row), in a rotation of kLook + 1 register sets.
+    constexpr int kLook = 3;
+    EncEntry E[kLook + 1][SPL];
+    auto prime = [&]() {  // entries of the first kLook rows of nxt[]
 #pragma unroll
-      for (int u = 0; u < kEncAhead; u += 2) {
-        lookup(eb, cur[u + 1]);
-        row(ea);
-        // after the last row of the batch this looks up the first row of the next batch; when there is
-        // none, nxt[0] still holds an old, valid symbol and the entry is simply not used
-        lookup(ea, u + 2 < kEncAhead ? cur[(u + 2) % kEncAhead] : nxt[0]);
-        row(eb);
+      for (int u = 0; u < kLook; u++) lookup(E[u], nxt[u]);
+    };
+    auto batch = [&]() {  // codes the rows in cur[]; leaves the entries of nxt[0 .. kLook-1] in E[0 .. kLook-1]
+#pragma unroll
+      for (int u = 0; u < kEncAhead; u++) {
+        // past the end of the batch this looks up rows of the next batch; when there is none, nxt[]
+        // still holds old, valid symbols and the entries are simply not used
+        lookup(E[(u + kLook) % (kLook + 1)], u + kLook < kEncAhead ? cur[(u + kLook) % kEncAhead] : nxt[(u + kLook) % kEncAhead]);
+        row(E[u % (kLook + 1)]);
       }
 #pragma unroll
       for (int i = 0; i < SPL; i++) flush(i);
@@ -1196,7 +1206,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
         park(t_lo);
         if (t_lo) request(t_lo - kStageRows, t_lo);
         read_rows(nxt, t);
-        lookup(ea, nxt[0]);
+        prime();
       }
       while (t) {
 #pragma unroll
@@ -1218,7 +1228,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
       };
       if (t) {
         fetch_rows(nxt, t);
-        lookup(ea, nxt[0]);
+        prime();
       }
       while (t) {
 #pragma unroll
@@ -1242,21 +1252,27 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
       if (exact) run(std::true_type{}, std::false_type{});
       else run(std::false_type{}, std::false_type{});
     }
-#pragma unroll
-    for (int i = 0; i < SPL; i++) {
-      const uint32_t nw = ~nnw[i];
-      // the remaining words (fewer than 8), newest at the lowest address
-      uint16_t *dst = gp[i] - (nw - fl[i]);
-      for (uint32_t n = nw; n-- > fl[i];) *dst++ = *slot(i, ~n);
-      if (!FUSE) {
-        st_out[(uint64_t)k * S + j0 + i] = s[i];
-        nw_out[(uint64_t)k * S + j0 + i] = nw;
-      }
-    }
   }
   uint32_t nw[SPL];
 #pragma unroll
-  for (int i = 0; i < SPL; i++) nw[i] = ~nnw[i];
+  for (int i = 0; i < SPL; i++) {
+    const uint16_t *g0 = scratch + (uint64_t)blockIdx.x * (kWG * SPL) * capw + (i * kWG + threadIdx.x) * 8;
+    const uint32_t n_rem = (colb[i] + 30 - wp[i]) >> 1;  // fewer than 8
+    nw[i] = live ? (uint32_t)((gp[i] - g0) / (kWG * SPL)) + n_rem : 0;
+    if (live) {
+      // the remaining words sit at the top of the area's upper half: it leaves as one more block, whose
+      // first 8 - n_rem words are not part of the stream
+      if (n_rem) {
+        const lds_u64 *r = (const lds_u64 *)(uintptr_t)colb[i];
+        const uint64_t hi0 = r[2], hi1 = r[3];
+        *(uint4 *)gp[i] = make_uint4((uint32_t)hi0, (uint32_t)(hi0 >> 32), (uint32_t)hi1, (uint32_t)(hi1 >> 32));
+      }
+      if (!FUSE) {
+        st_out[(uint64_t)k * S + j0 + i] = s[i];
+        nw_out[(uint64_t)k * S + j0 + i] = nw[i];
+      }
+    }
+  }
   uint32_t mine = 0;
 #pragma unroll
   for (int i = 0; i < SPL; i++) mine += nw[i];
@@ -1273,7 +1289,8 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
     // is the lowest one; it starts with `skip` words that are not part of the stream).
     constexpr int kInFlight = 4;
     const uint32_t nw1 = live ? nw[0] : 0;
-    const uint16_t *rend = scratch + ((uint64_t)k * S + j0 + 1) * capw;
+    // block bi of the stream in read order (bi = 0: the newest, partial one) is block nb - 1 - bi as written
+    const uint16_t *g0 = scratch + (uint64_t)blockIdx.x * kWG * capw + threadIdx.x * 8;
     const uint32_t nb = (nw1 + 7) / 8, skip = nb * 8 - nw1;
     // totals of the work-groups before this one: whole chunks give the chunk's byte offset, the groups
     // of this chunk before g give the position inside the chunk
@@ -1367,7 +1384,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
           uint4 q[kInFlight];
 #pragma unroll
           for (int u = 0; u < kInFlight; u++)
-            if (b0 + u <= b_hi) q[u] = *(const uint4 *)(rend - 8 * (nb - (b0 + u)));
+            if (b0 + u <= b_hi) q[u] = *(const uint4 *)(g0 + (uint64_t)(nb - 1 - (b0 + u)) * (kWG * 8));
 #pragma unroll
           for (int u = 0; u < kInFlight; u++)
             if (b0 + u <= b_hi) stage(q[u], b0 + u);
@@ -1519,7 +1536,8 @@ __global__ __launch_bounds__(kWG) void k_gather(CtlRef ctl, const uint16_t *scra
     st32(ck + 4ull * j, st[(uint64_t)k * S + j]);
     st32(ck + 4ull * S + 4ull * j, nw);
   }
-  const uint16_t *rend = scratch + ((uint64_t)k * S + j + 1) * capw;  // end of the stream's region, 16-byte aligned
+  // block bi of the stream in read order (bi = 0: the newest, partial one) is block nb - 1 - bi as written
+  const uint16_t *g0 = scratch + (uint64_t)blockIdx.x * kWG * capw + threadIdx.x * 8;
   const uint32_t nb = (nw + 7) / 8;                                    // aligned 8-word blocks that hold the words
   const uint32_t skip = nb * 8 - nw;                                   // words of the lowest block before the first one
   uint16_t *dst = (uint16_t *)(ck + 8ull * S) + pre;                   // first word of this group
@@ -1530,7 +1548,7 @@ __global__ __launch_bounds__(kWG) void k_gather(CtlRef ctl, const uint16_t *scra
     if (lo < hi) {
       const uint32_t b_lo = (lo - ex + skip) / 8, b_hi = (hi - 1 - ex + skip) / 8;
       for (uint32_t bi = b_lo; bi <= b_hi; bi++) {
-        const uint4 q = *(const uint4 *)(rend - 8 * (nb - bi));
+        const uint4 q = *(const uint4 *)(g0 + (uint64_t)(nb - 1 - bi) * (kWG * 8));
         const uint32_t ww[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
         for (int i = 0; i < 8; i++) {

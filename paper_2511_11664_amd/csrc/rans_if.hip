@@ -52,7 +52,8 @@ struct Ctl {
   uint64_t payload_off, dir_off;         // container section offsets
   uint64_t total_bytes;
   uint32_t nnz, n_chunks;
-  uint32_t pad[46];
+  uint32_t hist_done;                    // work-groups of the histogram kernel that have added their counts
+  uint32_t pad[45];
 };
 static_assert(sizeof(Ctl) == 256, "control block is 256 bytes");
 
@@ -319,6 +320,22 @@ __global__ void k_fill(T *p, uint64_t n, T val) {
 
 // ------------------------------------------------------------------ kernels: Eq. 6
 
+// Start-of-call bookkeeping (done by one work-group of the first kernel of a call): reset the control
+// block, clear the histogram and the encoder's per-chunk / per-work-group word counters.
+__device__ void reset_call_state(const CtlRef &ctl, uint32_t *cnt, uint32_t A, uint32_t *chunk_words, uint32_t nc) {
+  if (threadIdx.x == 0) {
+    ctl->last_seq = ctl.seq;
+    ctl->len_d = 0;
+    ctl->payload_off = ctl->dir_off = ctl->total_bytes = 0;
+    ctl->nnz = 0;
+    ctl->n_chunks = 0;
+    ctl->hist_done = 0;
+  }
+  for (uint32_t a = threadIdx.x; a < A; a += blockDim.x) cnt[a] = 0;
+  for (uint32_t k = threadIdx.x; k <= nc; k += blockDim.x) chunk_words[k] = 0;
+  __syncthreads();
+}
+
 // Partial extrema of one work-group of k_minmax.
 struct MinMaxPart {
   float mn, mx;
@@ -331,7 +348,9 @@ struct MinMaxPart {
 // group's partial result.  No atomics: thousands of same-address atomics cost more
 // than reading the tensor.
 template <typename T, bool VEC>
-__global__ __launch_bounds__(kWG) void k_minmax(const T *x, uint32_t n, MinMaxPart *part) {
+__global__ __launch_bounds__(kWG) void k_minmax(const T *x, uint32_t n, MinMaxPart *part, CtlRef ctl, uint32_t *cnt,
+                                                uint32_t A, uint32_t *chunk_words, uint32_t nc) {
+  if (blockIdx.x == 0) reset_call_state(ctl, cnt, A, chunk_words, nc);  // nothing in this kernel uses that state
   constexpr int V = VEC ? (int)(16 / sizeof(T)) : 1;
   constexpr int U = 4;
   float mn = INFINITY, mx = -INFINITY;
@@ -415,29 +434,14 @@ __global__ __launch_bounds__(kWG) void k_minmax(const T *x, uint32_t n, MinMaxPa
   }
 }
 
-// Start-of-call bookkeeping shared by the two kernels below: reset the control
-// block, clear the histogram and the per-chunk word counters.
-__device__ void reset_call_state(const CtlRef &ctl, uint32_t *cnt, uint32_t A, uint32_t *chunk_words, uint32_t nc) {
-  if (threadIdx.x == 0) {
-    ctl->last_seq = ctl.seq;
-    ctl->len_d = 0;
-    ctl->payload_off = ctl->dir_off = ctl->total_bytes = 0;
-    ctl->nnz = 0;
-    ctl->n_chunks = 0;
-  }
-  for (uint32_t a = threadIdx.x; a < A; a += blockDim.x) cnt[a] = 0;
-  for (uint32_t k = threadIdx.x; k <= nc; k += blockDim.x) chunk_words[k] = 0;
-  __syncthreads();
-}
-
-// Second stage of the extrema, then scale and zero point (Eq. 6).  One work-group.
-__global__ __launch_bounds__(kBig) void k_qinfo(CtlRef ctl, const MinMaxPart *part, uint32_t n_part, uint32_t q_bits,
-                                                rans_qinfo *out, uint32_t *cnt, uint32_t A, uint32_t *chunk_words,
-                                                uint32_t nc) {
-  reset_call_state(ctl, cnt, A, chunk_words, nc);
+// Second stage of the extrema, then scale and zero point (Eq. 6), by a whole work-group of NT lanes:
+// every lane returns the same values.  `bad` reports non-finite input or an overflowing range; the
+// values are NaN then.
+template <int NT>
+__device__ rans_qinfo qinfo_from_parts(const MinMaxPart *part, uint32_t n_part, uint32_t q_bits, bool *bad_out) {
   float mn = INFINITY, mx = -INFINITY;
   uint32_t bad = 0;
-  for (uint32_t i = threadIdx.x; i < n_part; i += kBig) {
+  for (uint32_t i = threadIdx.x; i < n_part; i += NT) {
     MinMaxPart q = part[i];
     mn = fminf(mn, q.mn);
     mx = fmaxf(mx, q.mx);
@@ -449,16 +453,18 @@ __global__ __launch_bounds__(kBig) void k_qinfo(CtlRef ctl, const MinMaxPart *pa
     mx = fmaxf(mx, __shfl_xor(mx, d));
     bad |= __shfl_xor(bad, d);
   }
-  __shared__ float s_mn[kBig / 64], s_mx[kBig / 64];
-  __shared__ uint32_t s_bad[kBig / 64];
+  __shared__ float s_mn[NT / 64], s_mx[NT / 64];
+  __shared__ uint32_t s_bad[NT / 64];
   if ((threadIdx.x & 63) == 0) {
     s_mn[threadIdx.x >> 6] = mn;
     s_mx[threadIdx.x >> 6] = mx;
     s_bad[threadIdx.x >> 6] = bad;
   }
   __syncthreads();
-  if (threadIdx.x != 0) return;
-  for (int w = 1; w < kBig / 64; w++) {
+  mn = s_mn[0];
+  mx = s_mx[0];
+  bad = s_bad[0];
+  for (int w = 1; w < NT / 64; w++) {
     mn = fminf(mn, s_mn[w]);
     mx = fmaxf(mx, s_mx[w]);
     bad |= s_bad[w];
@@ -470,20 +476,30 @@ __global__ __launch_bounds__(kBig) void k_qinfo(CtlRef ctl, const MinMaxPart *pa
   float levels = (float)((1u << q_bits) - 1u);
   float s = range / levels;
   float zf = eq6_zero_point(mn, s);
-  if (bad || !(fabsf(range) < INFINITY)) {
-    set_status(ctl, RANS_ERR_NONFINITE);
-    mn = mx = s = zf = __uint_as_float(0x7fc00000u);
-  }
-  ctl->x_min = mn;
-  ctl->x_max = mx;
-  ctl->scale = s;
-  ctl->zero_point = zf;
-  if (out) {
-    out->x_min = mn;
-    out->x_max = mx;
-    out->scale = s;
-    out->zero_point = zf;
-  }
+  const bool is_bad = bad || !(fabsf(range) < INFINITY);
+  if (is_bad) mn = mx = s = zf = __uint_as_float(0x7fc00000u);
+  *bad_out = is_bad;
+  return rans_qinfo{mn, mx, s, zf};
+}
+
+__device__ void publish_qinfo(const CtlRef &ctl, const rans_qinfo &q, bool bad, rans_qinfo *out) {
+  if (bad) set_status(ctl, RANS_ERR_NONFINITE);
+  ctl->x_min = q.x_min;
+  ctl->x_max = q.x_max;
+  ctl->scale = q.scale;
+  ctl->zero_point = q.zero_point;
+  if (out) *out = q;
+}
+
+// The same as a kernel of one work-group, with the start-of-call bookkeeping (empty tensors: no other
+// kernel runs before it).
+__global__ __launch_bounds__(kBig) void k_qinfo(CtlRef ctl, const MinMaxPart *part, uint32_t n_part, uint32_t q_bits,
+                                                rans_qinfo *out, uint32_t *cnt, uint32_t A, uint32_t *chunk_words,
+                                                uint32_t nc) {
+  reset_call_state(ctl, cnt, A, chunk_words, nc);
+  bool bad;
+  const rans_qinfo q = qinfo_from_parts<kBig>(part, n_part, q_bits, &bad);
+  if (threadIdx.x == 0) publish_qinfo(ctl, q, bad, out);
 }
 
 // Copies caller-provided extrema into the control block (rans_encode path) and
@@ -506,6 +522,177 @@ __global__ __launch_bounds__(kBig) void k_qinfo_from_user(CtlRef ctl, const rans
   ctl->zero_point = zf;
 }
 
+// ------------------------------------------------------------------ kernels: frequency table
+
+__device__ __forceinline__ void st32(uint8_t *p, uint32_t v) { *(uint32_t *)p = v; }
+__device__ __forceinline__ uint32_t ld32(const uint8_t *p) { return *(const uint32_t *)p; }
+__device__ __forceinline__ uint64_t ld64(const uint8_t *p) { return (uint64_t)ld32(p) | ((uint64_t)ld32(p + 4) << 32); }
+
+// One work-group: counts -> f with sum 2^M (largest-count symbol absorbs a surplus,
+// largest-f symbols pay a deficit, lowest index on ties), F = exclusive cumulative
+// sum, encoder table {reciprocal, f | F << 16}, container header and table.
+struct NormArgs {
+  const uint32_t *cnt;
+  uint32_t *fq;
+  uint2 *enc_tab;
+  uint4 *enc_tab4;
+  uint32_t A;
+  rans_params p;
+  uint64_t n_elems;
+  int dense;
+  uint8_t *out;
+  uint64_t cap;
+};
+__device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
+  const uint32_t *cnt = na.cnt;
+  uint32_t *fq = na.fq;
+  uint2 *enc_tab = na.enc_tab;
+  uint4 *enc_tab4 = na.enc_tab4;
+  const uint32_t A = na.A;
+  const rans_params &p = na.p;
+  const uint64_t n_elems = na.n_elems;
+  const int dense = na.dense;
+  uint8_t *out = na.out;
+  const uint64_t cap = na.cap;
+  __shared__ uint64_t sh64[kBig / 64];
+  __shared__ uint32_t sh32[kBig / 64];
+  __shared__ int64_t s_d;
+  const uint32_t M = p.freq_bits, total = 1u << M;
+  if (get_status(ctl) != 0) return;  // uniform: written by an earlier kernel
+  uint64_t len_loc = 0, present_loc = 0;
+  for (uint32_t a = threadIdx.x; a < A; a += kBig) {
+    uint32_t c = __hip_atomic_load(cnt + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    len_loc += c;
+    present_loc += c != 0;
+  }
+  const uint64_t len = block_sum64<kBig>(len_loc, sh64);
+  const uint64_t present = block_sum64<kBig>(present_loc, sh64);
+  if (dense) {
+    if (threadIdx.x == 0) ctl->len_d = len;
+  }
+  const uint64_t len_d = dense ? len : ctl->len_d;
+  if (present > total || len != len_d) {  // the second cannot happen; kept as a guard
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_ALPHABET);
+    return;
+  }
+  // first estimate and its sum
+  uint64_t sum_loc = 0, best_cnt = 0;
+  for (uint32_t a = threadIdx.x; a < A; a += kBig) {
+    uint32_t c = __hip_atomic_load(cnt + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t f = 0;
+    if (c) {
+      uint64_t q = ((uint64_t)c * total + len / 2) / len;
+      f = q < 1 ? 1u : (uint32_t)q;
+      uint64_t key = ((uint64_t)c << 32) | (0xffffffffu - a);  // max count, lowest index
+      best_cnt = key > best_cnt ? key : best_cnt;
+    }
+    fq[a] = f;
+    sum_loc += f;
+  }
+  const uint64_t sum = block_sum64<kBig>(sum_loc, sh64);
+  const uint64_t best = block_max64<kBig>(best_cnt, sh64);
+  int64_t d = (int64_t)total - (int64_t)sum;
+  if (len && d > 0) {
+    if (threadIdx.x == 0) fq[0xffffffffu - (uint32_t)best] += (uint32_t)d;
+    d = 0;
+  }
+  __syncthreads();
+  while (d < 0) {  // uniform loop: d is identical in every thread
+    uint64_t kb = 0;
+    for (uint32_t a = threadIdx.x; a < A; a += kBig) {
+      uint64_t key = ((uint64_t)fq[a] << 32) | (0xffffffffu - a);
+      kb = key > kb ? key : kb;
+    }
+    kb = block_max64<kBig>(kb, sh64);
+    uint32_t a_star = 0xffffffffu - (uint32_t)kb;
+    int64_t take = (int64_t)(kb >> 32) - 1;
+    if (take > -d) take = -d;
+    if (threadIdx.x == 0) {
+      fq[a_star] -= (uint32_t)take;
+      s_d = d + take;
+    }
+    __syncthreads();
+    d = s_d;
+    __syncthreads();
+  }
+  // container geometry
+  const uint64_t n_chunks = len_d == 0 ? 0 : (p.chunk_syms == 0 ? 1 : (len_d + p.chunk_syms - 1) / p.chunk_syms);
+  const uint64_t table_off = kHdrBytes;
+  const uint64_t dir_off = table_off + (((uint64_t)A * 2 + 7) & ~7ull);
+  const uint64_t payload_off = dir_off + 8 * (n_chunks + 1);
+  if (payload_off > cap) {
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CAPACITY);
+    return;
+  }
+  if (threadIdx.x == 0) {
+    ctl->n_chunks = (uint32_t)n_chunks;
+    ctl->dir_off = dir_off;
+    ctl->payload_off = payload_off;
+    st32(out + 0, 0x31464952u);  // "RIF1"
+    st32(out + 4, 1u | (p.mode << 16) | (p.in_dtype << 24));
+    st32(out + 8, p.q_bits | (M << 8));
+    st32(out + 12, (uint32_t)n_elems);       st32(out + 16, (uint32_t)(n_elems >> 32));
+    st32(out + 20, (uint32_t)p.rows);        st32(out + 24, (uint32_t)(p.rows >> 32));
+    st32(out + 28, (uint32_t)p.cols);        st32(out + 32, (uint32_t)(p.cols >> 32));
+    st32(out + 36, (uint32_t)len_d);         st32(out + 40, (uint32_t)(len_d >> 32));
+    st32(out + 44, A);
+    st32(out + 48, p.n_streams);
+    st32(out + 52, p.chunk_syms);
+    st32(out + 56, (uint32_t)n_chunks);
+    st32(out + 60, __float_as_uint(ctl->x_min));
+    st32(out + 64, __float_as_uint(ctl->x_max));
+    for (uint32_t o = 68; o < kHdrBytes; o += 4) st32(out + o, 0u);
+  }
+  // cumulative sum, encoder table, stored table
+  uint32_t carry = 0;
+  int inexact = 0;
+  for (uint32_t base = 0; base < A; base += kBig) {
+    uint32_t a = base + threadIdx.x;
+    uint32_t f = a < A ? fq[a] : 0, tot;
+    uint32_t F = carry + block_excl_scan<kBig>(f, sh32, &tot);
+    if (a < A) {
+      // floor(2^32 / f) for f >= 2, 2^32 - 1 for f = 1: with it mulhi(s, m) is floor(s / f) or one less
+      uint32_t m = f <= 1 ? 0xffffffffu : (uint32_t)(0x100000000ull / f);
+      enc_tab[a] = make_uint2(m, f | (F << 16));
+      *(uint16_t *)(out + table_off + 2ull * a) = (uint16_t)f;
+      // Division-free entry {lim1, mx, Fx | sh << 16, 2^M - f}: the coder renormalises when s > lim1 and
+      // then takes q = mulhi(s, mx) >> sh for floor(s / f) in Eq. 2.  At that point s <= lim1 =
+      // f * 2^(32-M) - 1.  With 2^k <= f < 2^(k+1), mx = floor(2^(32+k) / f) + 1 and e = mx * f - 2^(32+k),
+      // q is exact for every s with s * e < 2^(32+k); the entry is marked inexact otherwise (possible only
+      // for f > 2^(M-1)).  Powers of two take mx = 2^31, sh = k - 1.  f = 1 cannot have its multiplier
+      // 2^32: it takes mx = 2^32 - 1, which gives q = s - 1 (s >= 1 there), and the missing 2^M - f is
+      // added to Fx instead.  f = 0 (absent symbol) is never looked up.
+      const uint32_t cmpl = total - f;
+      uint32_t lim1 = (f << (32 - M)) - 1u, mx = 0, sh = 0, Fx = F;
+      if (f == 1) {
+        mx = 0xffffffffu;
+        Fx = F + cmpl;
+      } else if (f > 1) {
+        const uint32_t k = 31u - (uint32_t)__clz((int)f);
+        if ((f & (f - 1)) == 0) {
+          mx = 0x80000000u;
+          sh = k - 1;
+        } else {
+          const uint64_t two = 1ull << (32 + k);
+          const uint64_t mq = two / f + 1;  // < 2^32 because f > 2^k
+          const uint64_t e = mq * f - two;
+          if ((uint64_t)lim1 * e >= two) inexact = 1;
+          mx = (uint32_t)mq;
+          sh = k;
+        }
+      }
+      enc_tab4[a] = make_uint4(lim1, mx, Fx | (sh << 16), cmpl);
+    }
+    carry += tot;
+    __syncthreads();
+  }
+  inexact = __syncthreads_or(inexact);
+  if (threadIdx.x == 0) ctl->enc_exact = inexact ? 0u : 1u;
+  for (uint64_t o = table_off + 2ull * A + 2 * threadIdx.x; o < dir_off; o += 2 * kBig) *(uint16_t *)(out + o) = 0;
+}
+
+__global__ __launch_bounds__(kBig) void k_normalize(CtlRef ctl, NormArgs na) { normalize_body(ctl, na); }
+
 // Quantise a tile and histogram its symbols.  T = float / __half: Eq. 6 per
 // element, symbols written packed; T = uint8_t: symbols are the input (histogram
 // only).  The LDS histogram is replicated 8 ways (bin * 8 + lane % 8) so that the
@@ -519,18 +706,30 @@ constexpr uint32_t kQuantBlocks = 256;   // its work-groups (persistent over til
 
 template <typename T, bool VEC, int NT>
 __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRef ctl, uint32_t q_bits,
-                                                    uint8_t *sym, uint32_t *cnt, int skip_zero_bin) {
+                                                    uint8_t *sym, uint32_t *cnt, int skip_zero_bin,
+                                                    const MinMaxPart *part, uint32_t n_part, rans_qinfo *qout,
+                                                    int fold_norm, NormArgs na) {
   constexpr bool IS_SYM = sizeof(T) == 1;
   constexpr int V = VEC ? (int)(16 / sizeof(T)) : 1;
   __shared__ uint32_t h[256 * kHistRep];
   for (int i = threadIdx.x; i < 256 * kHistRep; i += NT) h[i] = 0;
+  // Eq. 6's parameters: from the partial extrema (every work-group reduces them itself and gets the
+  // same values; the first one records them), or from the control block when there are none
+  rans_qinfo qi;
+  if (part) {
+    bool bad;
+    qi = qinfo_from_parts<NT>(part, n_part, q_bits, &bad);
+    if (blockIdx.x == 0 && threadIdx.x == 0) publish_qinfo(ctl, qi, bad, qout);
+  } else {
+    qi = rans_qinfo{ctl->x_min, ctl->x_max, ctl->scale, ctl->zero_point};
+  }
   __syncthreads();
-  // s == 0 (constant tensor) or NaN (flagged input): quantise with s = 1, z = 0 and a top level of 0,
-  // which maps everything to symbol 0 without a branch in the loop
-  const bool degenerate = !IS_SYM && !(ctl->scale != 0.0f);
-  const float s = degenerate ? 1.0f : ctl->scale, zf = degenerate ? 0.0f : ctl->zero_point;
+  // s == 0 (constant tensor): quantise with s = 1, z = 0 and a top level of 0, which maps everything
+  // to symbol 0 without a branch in the loop
+  const bool degenerate = !IS_SYM && !(qi.scale != 0.0f);
+  const float s = degenerate ? 1.0f : qi.scale, zf = degenerate ? 0.0f : qi.zero_point;
   const float levels = degenerate ? 0.0f : (float)((1u << q_bits) - 1u);
-  const float amax = fmaxf(fabsf(ctl->x_min), fabsf(ctl->x_max));
+  const float amax = fmaxf(fabsf(qi.x_min), fabsf(qi.x_max));
   const bool fast = s >= 0x1p-30f && s <= 0x1p30f && amax <= 0x1p30f;  // uniform; see FastDiv
   FastDiv fd;
   fd.init(s);
@@ -602,6 +801,17 @@ __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRe
     if (a >= (1 << q_bits)) set_status(ctl, RANS_ERR_ARG);  // caller-provided symbol outside {0..2^Q-1}
     else if (!(skip_zero_bin && a == 0)) atomicAdd(&cnt[a], t);
   }
+  if (!fold_norm) return;
+  // The work-group that adds its counts last also builds the frequency table (saves a launch).  The
+  // additions above are device-scope atomics; the barrier waits until this work-group's have been
+  // performed, only then does it take its ticket.  The last one reads the histogram with device-scope
+  // atomic loads, so no cache has to be written back or invalidated in between.
+  __shared__ uint32_t s_ticket;
+  __syncthreads();
+  if (threadIdx.x == 0) s_ticket = __hip_atomic_fetch_add(&ctl->hist_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (s_ticket != gridDim.x - 1) return;
+  if constexpr (NT == kBig) normalize_body(ctl, na);
 }
 
 // ------------------------------------------------------------------ kernels: modified CSR
@@ -724,156 +934,6 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
       if (t) atomicAdd(&cnt[a], t);
     }
   }
-}
-
-// ------------------------------------------------------------------ kernels: frequency table
-
-__device__ __forceinline__ void st32(uint8_t *p, uint32_t v) { *(uint32_t *)p = v; }
-__device__ __forceinline__ uint32_t ld32(const uint8_t *p) { return *(const uint32_t *)p; }
-__device__ __forceinline__ uint64_t ld64(const uint8_t *p) { return (uint64_t)ld32(p) | ((uint64_t)ld32(p + 4) << 32); }
-
-// One work-group: counts -> f with sum 2^M (largest-count symbol absorbs a surplus,
-// largest-f symbols pay a deficit, lowest index on ties), F = exclusive cumulative
-// sum, encoder table {reciprocal, f | F << 16}, container header and table.
-__global__ __launch_bounds__(kBig) void k_normalize(CtlRef ctl, const uint32_t *cnt, uint32_t *fq, uint2 *enc_tab,
-                                                    uint4 *enc_tab4,
-                                                    uint32_t A, rans_params p, uint64_t n_elems, int dense,
-                                                    uint8_t *out, uint64_t cap) {
-  __shared__ uint64_t sh64[kBig / 64];
-  __shared__ uint32_t sh32[kBig / 64];
-  __shared__ int64_t s_d;
-  const uint32_t M = p.freq_bits, total = 1u << M;
-  if (get_status(ctl) != 0) return;  // uniform: written by an earlier kernel
-  uint64_t len_loc = 0, present_loc = 0;
-  for (uint32_t a = threadIdx.x; a < A; a += kBig) {
-    uint32_t c = cnt[a];
-    len_loc += c;
-    present_loc += c != 0;
-  }
-  const uint64_t len = block_sum64<kBig>(len_loc, sh64);
-  const uint64_t present = block_sum64<kBig>(present_loc, sh64);
-  if (dense) {
-    if (threadIdx.x == 0) ctl->len_d = len;
-  }
-  const uint64_t len_d = dense ? len : ctl->len_d;
-  if (present > total || len != len_d) {  // the second cannot happen; kept as a guard
-    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_ALPHABET);
-    return;
-  }
-  // first estimate and its sum
-  uint64_t sum_loc = 0, best_cnt = 0;
-  for (uint32_t a = threadIdx.x; a < A; a += kBig) {
-    uint32_t c = cnt[a];
-    uint32_t f = 0;
-    if (c) {
-      uint64_t q = ((uint64_t)c * total + len / 2) / len;
-      f = q < 1 ? 1u : (uint32_t)q;
-      uint64_t key = ((uint64_t)c << 32) | (0xffffffffu - a);  // max count, lowest index
-      best_cnt = key > best_cnt ? key : best_cnt;
-    }
-    fq[a] = f;
-    sum_loc += f;
-  }
-  const uint64_t sum = block_sum64<kBig>(sum_loc, sh64);
-  const uint64_t best = block_max64<kBig>(best_cnt, sh64);
-  int64_t d = (int64_t)total - (int64_t)sum;
-  if (len && d > 0) {
-    if (threadIdx.x == 0) fq[0xffffffffu - (uint32_t)best] += (uint32_t)d;
-    d = 0;
-  }
-  __syncthreads();
-  while (d < 0) {  // uniform loop: d is identical in every thread
-    uint64_t kb = 0;
-    for (uint32_t a = threadIdx.x; a < A; a += kBig) {
-      uint64_t key = ((uint64_t)fq[a] << 32) | (0xffffffffu - a);
-      kb = key > kb ? key : kb;
-    }
-    kb = block_max64<kBig>(kb, sh64);
-    uint32_t a_star = 0xffffffffu - (uint32_t)kb;
-    int64_t take = (int64_t)(kb >> 32) - 1;
-    if (take > -d) take = -d;
-    if (threadIdx.x == 0) {
-      fq[a_star] -= (uint32_t)take;
-      s_d = d + take;
-    }
-    __syncthreads();
-    d = s_d;
-    __syncthreads();
-  }
-  // container geometry
-  const uint64_t n_chunks = len_d == 0 ? 0 : (p.chunk_syms == 0 ? 1 : (len_d + p.chunk_syms - 1) / p.chunk_syms);
-  const uint64_t table_off = kHdrBytes;
-  const uint64_t dir_off = table_off + (((uint64_t)A * 2 + 7) & ~7ull);
-  const uint64_t payload_off = dir_off + 8 * (n_chunks + 1);
-  if (payload_off > cap) {
-    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CAPACITY);
-    return;
-  }
-  if (threadIdx.x == 0) {
-    ctl->n_chunks = (uint32_t)n_chunks;
-    ctl->dir_off = dir_off;
-    ctl->payload_off = payload_off;
-    st32(out + 0, 0x31464952u);  // "RIF1"
-    st32(out + 4, 1u | (p.mode << 16) | (p.in_dtype << 24));
-    st32(out + 8, p.q_bits | (M << 8));
-    st32(out + 12, (uint32_t)n_elems);       st32(out + 16, (uint32_t)(n_elems >> 32));
-    st32(out + 20, (uint32_t)p.rows);        st32(out + 24, (uint32_t)(p.rows >> 32));
-    st32(out + 28, (uint32_t)p.cols);        st32(out + 32, (uint32_t)(p.cols >> 32));
-    st32(out + 36, (uint32_t)len_d);         st32(out + 40, (uint32_t)(len_d >> 32));
-    st32(out + 44, A);
-    st32(out + 48, p.n_streams);
-    st32(out + 52, p.chunk_syms);
-    st32(out + 56, (uint32_t)n_chunks);
-    st32(out + 60, __float_as_uint(ctl->x_min));
-    st32(out + 64, __float_as_uint(ctl->x_max));
-    for (uint32_t o = 68; o < kHdrBytes; o += 4) st32(out + o, 0u);
-  }
-  // cumulative sum, encoder table, stored table
-  uint32_t carry = 0;
-  int inexact = 0;
-  for (uint32_t base = 0; base < A; base += kBig) {
-    uint32_t a = base + threadIdx.x;
-    uint32_t f = a < A ? fq[a] : 0, tot;
-    uint32_t F = carry + block_excl_scan<kBig>(f, sh32, &tot);
-    if (a < A) {
-      // floor(2^32 / f) for f >= 2, 2^32 - 1 for f = 1: with it mulhi(s, m) is floor(s / f) or one less
-      uint32_t m = f <= 1 ? 0xffffffffu : (uint32_t)(0x100000000ull / f);
-      enc_tab[a] = make_uint2(m, f | (F << 16));
-      *(uint16_t *)(out + table_off + 2ull * a) = (uint16_t)f;
-      // Division-free entry {lim1, mx, Fx | sh << 16, 2^M - f}: the coder renormalises when s > lim1 and
-      // then takes q = mulhi(s, mx) >> sh for floor(s / f) in Eq. 2.  At that point s <= lim1 =
-      // f * 2^(32-M) - 1.  With 2^k <= f < 2^(k+1), mx = floor(2^(32+k) / f) + 1 and e = mx * f - 2^(32+k),
-      // q is exact for every s with s * e < 2^(32+k); the entry is marked inexact otherwise (possible only
-      // for f > 2^(M-1)).  Powers of two take mx = 2^31, sh = k - 1.  f = 1 cannot have its multiplier
-      // 2^32: it takes mx = 2^32 - 1, which gives q = s - 1 (s >= 1 there), and the missing 2^M - f is
-      // added to Fx instead.  f = 0 (absent symbol) is never looked up.
-      const uint32_t cmpl = total - f;
-      uint32_t lim1 = (f << (32 - M)) - 1u, mx = 0, sh = 0, Fx = F;
-      if (f == 1) {
-        mx = 0xffffffffu;
-        Fx = F + cmpl;
-      } else if (f > 1) {
-        const uint32_t k = 31u - (uint32_t)__clz((int)f);
-        if ((f & (f - 1)) == 0) {
-          mx = 0x80000000u;
-          sh = k - 1;
-        } else {
-          const uint64_t two = 1ull << (32 + k);
-          const uint64_t mq = two / f + 1;  // < 2^32 because f > 2^k
-          const uint64_t e = mq * f - two;
-          if ((uint64_t)lim1 * e >= two) inexact = 1;
-          mx = (uint32_t)mq;
-          sh = k;
-        }
-      }
-      enc_tab4[a] = make_uint4(lim1, mx, Fx | (sh << 16), cmpl);
-    }
-    carry += tot;
-    __syncthreads();
-  }
-  inexact = __syncthreads_or(inexact);
-  if (threadIdx.x == 0) ctl->enc_exact = inexact ? 0u : 1u;
-  for (uint64_t o = table_off + 2ull * A + 2 * threadIdx.x; o < dir_off; o += 2 * kBig) *(uint16_t *)(out + o) = 0;
 }
 
 // ------------------------------------------------------------------ kernels: rANS encode
@@ -2311,10 +2371,19 @@ inline uint32_t grid_for(uint64_t n, uint32_t per_block, uint32_t cap) {
 }
 
 // min/max + scale/zero point + quantise/histogram of a float tensor.
+NormArgs norm_args(const rans_params &p, const Layout &L, uint8_t *ws, uint64_t n, uint8_t *d_stream, size_t cap) {
+  return NormArgs{(const uint32_t *)(ws + L.cnt), (uint32_t *)(ws + L.fq), (uint2 *)(ws + L.enc_tab),
+                  (uint4 *)(ws + L.enc_tab4), L.A, p, n, p.mode == RANS_MODE_CSR ? 0 : 1, d_stream, (uint64_t)cap};
+}
+
+// Extrema, Eq. 6, symbols and their histogram.  With `na` (dense mode, a container follows) the
+// histogram kernel also builds the frequency table and the container header.
 int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Layout &L, uint8_t *ws, uint8_t *d_sym,
-                    rans_qinfo *d_qinfo, hipStream_t st, uint32_t seq) {
+                    rans_qinfo *d_qinfo, hipStream_t st, uint32_t seq, const NormArgs *na) {
   const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   uint32_t *cnt = (uint32_t *)(ws + L.cnt);
+  uint32_t *cw_ = (uint32_t *)(ws + L.chunk_words);
+  const uint32_t ncz_ = L.nc_max + L.n_pub;
   const bool f16 = p.in_dtype == RANS_F16;
   const bool vec = aligned_to(d_x, 16) && aligned_to(d_sym, 8);
   const uint32_t V = vec ? (f16 ? 8 : 4) : 1;
@@ -2323,26 +2392,29 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
   if (n) {
     uint32_t g = n_part = grid_for(n, kWG * V * 4, kMaxParts);
     if (f16) {
-      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, part);
-      else PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, part);
+      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, part, ctl, cnt, L.A, cw_, ncz_);
+      else PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, part, ctl, cnt, L.A, cw_, ncz_);
     } else {
-      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, part);
-      else PROF_LAUNCH(KID_MINMAX, (k_minmax<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, part);
+      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, part, ctl, cnt, L.A, cw_, ncz_);
+      else PROF_LAUNCH(KID_MINMAX, (k_minmax<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, part, ctl, cnt, L.A, cw_, ncz_);
     }
     LAUNCH_CHECK();
   }
-  PROF_LAUNCH(KID_QINFO, k_qinfo, dim3(1), dim3(kBig), 0, st, ctl, part, n_part, p.q_bits, d_qinfo, cnt, L.A,
-              (uint32_t *)(ws + L.chunk_words), L.nc_max + L.n_pub);
-  LAUNCH_CHECK();
+  if (!n) {  // empty tensor: only the bookkeeping and the (zero) quantiser parameters
+    PROF_LAUNCH(KID_QINFO, k_qinfo, dim3(1), dim3(kBig), 0, st, ctl, part, n_part, p.q_bits, d_qinfo, cnt, L.A, cw_, ncz_);
+    LAUNCH_CHECK();
+  }
   if (n) {
     uint32_t g = grid_for(n, QNT * V * kQIter, kQuantBlocks);
     int skip0 = p.mode == RANS_MODE_CSR;
+    const int fold = na != nullptr;
+    const NormArgs nav = na ? *na : NormArgs{};
     if (f16) {
-      if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, true, QNT>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
-      else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, false, QNT>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+      if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, true, QNT>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav);
+      else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, false, QNT>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav);
     } else {
-      if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, true, QNT>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
-      else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, false, QNT>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0);
+      if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, true, QNT>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav);
+      else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, false, QNT>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav);
     }
     LAUNCH_CHECK();
   }
@@ -2351,7 +2423,8 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
 
 // Everything after the symbol histogram: CSR, table, coder, container.
 int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, const Layout &L, uint8_t *ws,
-                       uint8_t *d_stream, size_t cap, uint64_t *d_stream_bytes, hipStream_t st, uint32_t seq) {
+                       uint8_t *d_stream, size_t cap, uint64_t *d_stream_bytes, hipStream_t st, uint32_t seq,
+                       bool table_done) {
   const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   uint32_t *cnt = (uint32_t *)(ws + L.cnt);
   const bool csr = p.mode == RANS_MODE_CSR;
@@ -2382,10 +2455,10 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       LAUNCH_CHECK();
     }
   }
-  PROF_LAUNCH(KID_NORMALIZE, k_normalize, dim3(1), dim3(kBig), 0, st, ctl, cnt, (uint32_t *)(ws + L.fq),
-                     (uint2 *)(ws + L.enc_tab), (uint4 *)(ws + L.enc_tab4), A, p, n, csr ? 0 : 1, d_stream,
-                     (uint64_t)cap);
-  LAUNCH_CHECK();
+  if (!table_done) {  // else the histogram kernel has built the table
+    PROF_LAUNCH(KID_NORMALIZE, k_normalize, dim3(1), dim3(kBig), 0, st, ctl, norm_args(p, L, ws, n, d_stream, cap));
+    LAUNCH_CHECK();
+  }
   const uint32_t groups = (S + kWG - 1) / kWG;
   const bool fused_gather = L.n_pub != 0;  // the encoder places its words itself: no k_chunk_scan / k_gather
   if (L.nc_max) {
@@ -2713,7 +2786,7 @@ int rans_quantize(const void *d_x, uint64_t n_elems, const rans_params *p, uint8
   if (!aligned_to(d_x, p->in_dtype == RANS_F16 ? 2 : 4) || !aligned_to(d_qinfo, 4)) return RANS_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
   uint8_t *ws = (uint8_t *)d_ws;
-  return launch_quantize(d_x, n_elems, *p, L, ws, d_sym, d_qinfo, st, next_seq());
+  return launch_quantize(d_x, n_elems, *p, L, ws, d_sym, d_qinfo, st, next_seq(), nullptr);
 }
 
 int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, const rans_qinfo *d_qinfo,
@@ -2736,13 +2809,16 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
     const bool vec = aligned_to(d_sym, 16);
     const uint32_t g = grid_for(n_elems, QNT * (vec ? 16 : 1) * kQIter, kQuantBlocks);
     const int skip0 = p->mode == RANS_MODE_CSR;
+    const int fold = !skip0;  // dense: the histogram is complete after this kernel, which then builds the table
+    const NormArgs na = norm_args(*p, L, ws, n_elems, d_stream, stream_cap);
     if (vec)
-      PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, true, QNT>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
+      PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, true, QNT>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, fold, na);
     else
-      PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, false, QNT>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0);
+      PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, false, QNT>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, fold, na);
     LAUNCH_CHECK();
   }
-  return launch_encode_tail(d_sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq);
+  return launch_encode_tail(d_sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq,
+                            n_elems && p->mode != RANS_MODE_CSR);
 }
 
 int rans_compress(const void *d_x, uint64_t n_elems, const rans_params *p, uint8_t *d_stream, size_t stream_cap,
@@ -2757,9 +2833,11 @@ int rans_compress(const void *d_x, uint64_t n_elems, const rans_params *p, uint8
   hipStream_t st = (hipStream_t)stream;
   uint8_t *ws = (uint8_t *)d_ws;
   const uint32_t seq = next_seq();
-  rc = launch_quantize(d_x, n_elems, *p, L, ws, ws + L.sym, nullptr, st, seq);
+  const bool fold = n_elems && p->mode != RANS_MODE_CSR;  // dense: the histogram kernel also builds the table
+  const NormArgs na = norm_args(*p, L, ws, n_elems, d_stream, stream_cap);
+  rc = launch_quantize(d_x, n_elems, *p, L, ws, ws + L.sym, nullptr, st, seq, fold ? &na : nullptr);
   if (rc) return rc;
-  return launch_encode_tail(ws + L.sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq);
+  return launch_encode_tail(ws + L.sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq, fold);
 }
 
 int rans_decode(const uint8_t *d_stream, size_t stream_bytes, const rans_header *h_hdr, uint8_t *d_sym,

@@ -1996,6 +1996,7 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
   // ---- global loads of the stream set-up first: their latency overlaps the table build below
+  const uint32_t f_first = threadIdx.x < A ? *(const uint16_t *)(in + kHdrBytes + 2ull * threadIdx.x) : 0;
   const uint64_t payload_bytes = bytes - payload_off;
   const uint8_t *dir = in + dir_off;
   const uint64_t o0 = ld64(dir + 8ull * k), o1 = ld64(dir + 8ull * k + 8);
@@ -2017,6 +2018,47 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
   const uint32_t nw_stored = live ? nwk[j] : 0;
   const uint32_t s_stored = live ? ((const uint32_t *)ck)[j] : kL;
 
+  // ---- this work-group's streams
+  const uint64_t pre = block_sum64<NT>(pre_loc, misc64);
+  const uint64_t rows_full = n_here / S;
+  const uint32_t rem_row = (uint32_t)(n_here - rows_full * S);
+  const uint64_t n_j = live ? rows_full + (j < rem_row ? 1 : 0) : 0;
+  uint32_t nw = nw_stored;
+  bool bad = false;
+  if (nw > n_j) {
+    bad = true;
+    nw = 0;
+  }
+  uint32_t tot;
+  const uint32_t ex = block_excl_scan<NT>(nw, misc, &tot);
+  const uint64_t w0 = pre + ex;  // index of this stream's first word inside the chunk
+  if (8ull * S + 2 * (w0 + nw) > ck_bytes) {
+    bad = true;
+    nw = 0;
+  }
+  // where the stream's words are; its first two 16-byte blocks are requested now, so that their latency
+  // overlaps the table build
+  const uint64_t B0 = ck_off + 8ull * S + 2 * w0;  // first byte of the stream's words
+  const uint64_t blk_base = B0 & ~15ull;           // 16-byte blocks are counted from here
+  const uint8_t *sp = in + blk_base;
+  const uint32_t pos0 = (uint32_t)(B0 & 15) >> 1;
+  const uint32_t end16 = (uint32_t)(B0 - blk_base) + 2 * nw;  // stream end, in bytes from blk_base
+  // bytes of the container from blk_base on (saturated): loads stay below this
+  const uint64_t room = bytes > blk_base ? bytes - blk_base : 0;
+  const uint32_t lim16 = room > 0xffffffffull ? 0xffffffffu : (uint32_t)room;
+  auto load_block = [&](uint32_t off16) -> uint4 {  // 16 bytes at sp + off16; bytes past the end read as zero
+    if (off16 <= lim16 && lim16 - off16 >= 16) return *(const uint4 *)(sp + off16);
+    uint32_t w[4] = {0, 0, 0, 0};
+    for (uint32_t q = 0; q < 8; q++)
+      if ((uint64_t)off16 + 2 * q + 2 <= lim16) w[q >> 1] |= (uint32_t) * (const uint16_t *)(sp + off16 + 2 * q) << (16 * (q & 1));
+    return make_uint4(w[0], w[1], w[2], w[3]);
+  };
+  uint4 q_first[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+  if (live) {
+    q_first[0] = load_block(0);
+    if (16 < end16) q_first[1] = load_block(16);
+  }
+
   // ---- tables
   const float sc = (x_max - x_min) / (float)((1u << q_bits) - 1u);
   const float zf = eq6_zero_point(x_min, sc);
@@ -2024,7 +2066,7 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
   uint32_t carry = 0;
   for (uint32_t a0 = 0; a0 < A; a0 += NT) {  // also orders the zeroing above before the marks below
     const uint32_t a = a0 + threadIdx.x;
-    const uint32_t f = a < A ? *(const uint16_t *)(in + kHdrBytes + 2ull * a) : 0;
+    const uint32_t f = a0 == 0 ? f_first : (a < A ? *(const uint16_t *)(in + kHdrBytes + 2ull * a) : 0);
     uint32_t tot;
     const uint32_t F = carry + block_excl_scan<NT>(f, misc, &tot);
     if (a < A) {
@@ -2090,36 +2132,10 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
     __syncthreads();
   }
 
-  // ---- this work-group's streams
-  const uint64_t pre = block_sum64<NT>(pre_loc, misc64);
-  const uint64_t rows_full = n_here / S;
-  const uint32_t rem_row = (uint32_t)(n_here - rows_full * S);
-  const uint64_t n_j = live ? rows_full + (j < rem_row ? 1 : 0) : 0;
-  uint32_t nw = nw_stored;
-  bool bad = false;
-  if (nw > n_j) {
-    bad = true;
-    nw = 0;
-  }
-  uint32_t tot;
-  const uint32_t ex = block_excl_scan<NT>(nw, misc, &tot);
-  const uint64_t w0 = pre + ex;  // index of this stream's first word inside the chunk
-  if (8ull * S + 2 * (w0 + nw) > ck_bytes) {
-    bad = true;
-    nw = 0;
-  }
   if (WIDE) __syncthreads();  // the scan scratch above may alias the window that is filled below
   if (live) {
     typedef __attribute__((address_space(3))) uint16_t lds_u16;
     constexpr uint32_t RB = kWinRowBytes, LOG_RB = NT == 1024 ? 11 : 9;
-    const uint64_t B0 = ck_off + 8ull * S + 2 * w0;  // first byte of the stream's words
-    const uint64_t blk_base = B0 & ~15ull;           // 16-byte blocks are counted from here
-    const uint8_t *sp = in + blk_base;
-    const uint32_t pos0 = (uint32_t)(B0 & 15) >> 1;
-    const uint32_t end16 = (uint32_t)(B0 - blk_base) + 2 * nw;  // stream end, in bytes from blk_base
-    // bytes of the container from blk_base on (saturated): loads stay below this
-    const uint64_t room = bytes > blk_base ? bytes - blk_base : 0;
-    const uint32_t lim16 = room > 0xffffffffull ? 0xffffffffu : (uint32_t)room;
     // column of this stream inside a window row; lanes l and l+32 share a 32-bit bank word, so the two
     // halves of a wave never collide.  The window starts at LDS address 0 (this kernel has no static LDS).
     if ((uint32_t)(uintptr_t)(lds_u16 *)l_mem != 0) {  // cannot happen without static LDS; the slot arithmetic relies on it
@@ -2137,16 +2153,9 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
 #pragma unroll
       for (int i = 0; i < 8; i++) row0[i * (RB / 2)] = (uint16_t)(w[i >> 1] >> (16 * (i & 1)));
     };
-    auto load_block = [&](uint32_t off16) -> uint4 {  // 16 bytes at sp + off16; bytes past the end read as zero
-      if (off16 <= lim16 && lim16 - off16 >= 16) return *(const uint4 *)(sp + off16);
-      uint32_t w[4] = {0, 0, 0, 0};
-      for (uint32_t q = 0; q < 8; q++)
-        if ((uint64_t)off16 + 2 * q + 2 <= lim16) w[q >> 1] |= (uint32_t) * (const uint16_t *)(sp + off16 + 2 * q) << (16 * (q & 1));
-      return make_uint4(w[0], w[1], w[2], w[3]);
-    };
-    // the first two blocks
-    store_block(0, load_block(0));
-    if (16 < end16) store_block(1, load_block(16));
+    // the first two blocks, requested before the table build
+    store_block(0, q_first[0]);
+    if (16 < end16) store_block(1, q_first[1]);
     uint32_t ldb = 2;              // next block to request
     uint32_t rd9 = pos0 * RB;      // RB times the number of the next unread word (counted from blk_base)
     uint32_t pend_b = 0;

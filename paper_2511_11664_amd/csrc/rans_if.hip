@@ -2299,12 +2299,12 @@ __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *sym, uint64_t n,
 // mask, each of its launches is bracketed by a pair of HIP events recorded on the
 // launch stream.  Off by default; the normal path records nothing.
 enum KernelId {
-  KID_INIT = 0, KID_MINMAX, KID_QINFO, KID_QUANT_HIST, KID_CSR_COUNT, KID_SCAN, KID_CSR_COMPACT, KID_CSR_ROWS,
+  KID_MINMAX = 0, KID_QINFO, KID_QUANT_HIST, KID_CSR_COUNT, KID_SCAN, KID_CSR_COMPACT, KID_CSR_ROWS,
   KID_NORMALIZE, KID_ENCODE, KID_CHUNK_SCAN, KID_GATHER, KID_DEC_PREPARE, KID_DECODE, KID_FILL, KID_ROW_SCAN,
   KID_CSR_EXPAND, KID_DEQUANT, KID_COUNT
 };
 const char *const kKernelNames[KID_COUNT] = {
-    "k_init", "k_minmax", "k_qinfo", "k_quant_hist", "k_csr_count", "k_scan_u32", "k_csr_compact", "k_csr_rows",
+    "k_minmax", "k_qinfo", "k_quant_hist", "k_csr_count", "k_scan_u32", "k_csr_compact", "k_csr_rows",
     "k_normalize", "k_encode", "k_chunk_scan", "k_gather", "k_dec_prepare", "k_decode", "k_fill", "k_row_scan",
     "k_csr_expand", "k_dequant"};
 

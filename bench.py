@@ -6,7 +6,8 @@ histogram, normalise, interleaved rANS encode, container) followed by
 rans_decompress (table rebuild, rANS decode, dequantise), inputs and outputs
 resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5a] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5a] [--mode 0|1] [--cols K]
+                    [--q-bits Q] [--chunk-syms N] [--no-cpu]
 """
 import argparse
 import json
@@ -29,6 +30,7 @@ def main():
     ap.add_argument("--chunk-syms", type=int, default=None)
     ap.add_argument("--mode", type=int, default=None)
     ap.add_argument("--cols", type=int, default=None)
+    ap.add_argument("--q-bits", type=int, default=None)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -46,6 +48,8 @@ def main():
         over["mode"] = args.mode
     if args.cols is not None:
         over["cols"] = args.cols
+    if args.q_bits is not None:
+        over["q_bits"] = args.q_bits
     w = synth.workload(args.workload, 1, **over)
     x_cpu = synth.make(w)
     p = B.params_of(w)
@@ -118,6 +122,13 @@ def main():
     # writes xhat; the coder reads xhat and writes the container), one on the decode side.
     b_enc = 2 * e * n + 2 * n + nbytes
     b_dec = nbytes + e * n
+    if w.mode == synth.MODE_CSR:
+        # D = v (u8), c (u16), r (u16) is written and read back on both sides; the decoder also zero-fills and
+        # scatters the symbol tensor
+        nnz = (int(hdr.len_d) - w.rows) // 2
+        d_bytes = 2 * (3 * nnz + 2 * w.rows)
+        b_enc += d_bytes
+        b_dec += d_bytes + n
     alg = {"k_encode": n + nbytes, "k_decode": nbytes + e * n, "k_quant_hist": e * n + n, "k_minmax": e * n,
            "k_gather": 2 * nbytes}
     # HBM-side bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary of this

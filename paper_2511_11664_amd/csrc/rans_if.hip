@@ -71,7 +71,7 @@ struct Layout {
   // encode side
   size_t mm_part, cnt, fq, enc_tab, enc_tab4, sym, v, c, r, row_end, blk_nnz, st, nw, chunk_words, scratch;
   // decode side (overlays the encode side from `sym` on)
-  size_t dec_lut, dec_tab, dec_F, D, row_off, dec_sym;
+  size_t dec_lut, dec_tab, dec_F, D, row_off;
   size_t total;
   uint32_t A, nc_max, capw, n_blk;
   uint32_t n_pub;  // work-groups of the encoder when it also places its words (0: separate gather kernel)
@@ -105,7 +105,9 @@ int check_params(const rans_params *p, uint64_t n) {
   return RANS_OK;
 }
 
-constexpr uint32_t kCsrTile = kWG * 16;  // elements per work-group in the CSR count / compact kernels
+constexpr uint32_t kCsrTile = kWG * 16;  // elements per tile in the CSR count / compact kernels
+constexpr uint32_t kDenseTileCells = 16384; // symbols per tile of the CSR-to-dense kernel (one row if a row is larger)
+constexpr uint32_t kCompactBlocks = 1024;  // work-groups of the compact kernel (persistent over tiles)
 
 Layout make_layout(const rans_params &p, uint64_t n) {
   Layout L{};
@@ -155,7 +157,6 @@ Layout make_layout(const rans_params &p, uint64_t n) {
   if (p.mode == RANS_MODE_CSR) {
     L.D = take(L.len_max * 2);
     L.row_off = take((p.rows + 1) * 4);
-    L.dec_sym = take(n);
   }
   size_t dec_end = o;
   L.total = enc_end > dec_end ? enc_end : dec_end;
@@ -311,12 +312,6 @@ __device__ __forceinline__ float eq6_zero_point(float x_min, float s) {
 }
 
 // ------------------------------------------------------------------ kernels: set-up
-
-template <typename T>
-__global__ void k_fill(T *p, uint64_t n, T val) {
-  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (uint64_t)gridDim.x * blockDim.x;
-  for (; i < n; i += stride) p[i] = val;
-}
 
 // ------------------------------------------------------------------ kernels: Eq. 6
 
@@ -860,45 +855,59 @@ __global__ __launch_bounds__(kBig) void k_scan_u32(uint32_t *a, uint32_t n) {
 // Stream compaction of the nonzero symbols in flat (= row-major) order: v gets the
 // values, c the column indices, row_end[i] the number of nonzeros up to and
 // including row i.  Column indices are histogrammed into cnt on the way.
+// A work-group walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...: a tile's nonzeros are
+// compacted in LDS first and leave with consecutive lanes on consecutive entries, and the
+// column histogram is added to the global one once at the end (few work-groups: same-address
+// global atomics are what costs here).
 template <bool LDS_HIST>
 __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_t n, int aligned, uint32_t K,
                                                      const uint32_t *blk_off, uint8_t *v, uint16_t *c,
-                                                     uint32_t *row_end, uint32_t *cnt, uint32_t A) {
+                                                     uint32_t *row_end, uint32_t *cnt, uint32_t A, uint32_t n_tiles) {
   extern __shared__ uint32_t hist[];
   __shared__ uint32_t sh[kWG / 64];
+  __shared__ uint8_t s_v[kCsrTile];
+  __shared__ uint16_t s_c[kCsrTile];
   if (LDS_HIST) {
     for (uint32_t a = threadIdx.x; a < A; a += kWG) hist[a] = 0;
   }
-  uint64_t e0 = (uint64_t)blockIdx.x * kCsrTile + threadIdx.x * 16;
-  uint8_t b[16];
-  load16(sym, e0, n, aligned, b);
-  uint32_t cth = 0;
+  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const uint64_t e0 = (uint64_t)tile * kCsrTile + threadIdx.x * 16;
+    uint8_t b[16];
+    load16(sym, e0, n, aligned, b);
+    uint32_t cth = 0;
 #pragma unroll
-  for (int k = 0; k < 16; k++) cth += b[k] != 0;
-  uint32_t tot;
-  uint32_t off = blk_off[blockIdx.x] + block_excl_scan<kWG>(cth, sh, &tot);  // also orders the hist zeroing
-  if (e0 < n) {
-    uint32_t row = (uint32_t)(e0 / K), col = (uint32_t)(e0 - (uint64_t)row * K);
+    for (int k = 0; k < 16; k++) cth += b[k] != 0;
+    uint32_t tot;
+    uint32_t loc = block_excl_scan<kWG>(cth, sh, &tot);  // also orders the hist zeroing and the staging reuse
+    const uint32_t base = blk_off[tile];
+    if (e0 < n) {
+      uint32_t row = (uint32_t)(e0 / K), col = (uint32_t)(e0 - (uint64_t)row * K);
 #pragma unroll
-    for (int k = 0; k < 16; k++) {
-      if (e0 + k < n) {
-        if (b[k]) {
-          v[off] = b[k];
-          c[off] = (uint16_t)col;
-          off++;
-          if (LDS_HIST) atomicAdd(&hist[col], 1u);
-          else atomicAdd(&cnt[col], 1u);
-        }
-        if (++col == K) {
-          row_end[row] = off;
-          col = 0;
-          row++;
+      for (int k = 0; k < 16; k++) {
+        if (e0 + k < n) {
+          if (b[k]) {
+            s_v[loc] = b[k];
+            s_c[loc] = (uint16_t)col;
+            loc++;
+            if (LDS_HIST) atomicAdd(&hist[col], 1u);
+            else atomicAdd(&cnt[col], 1u);
+          }
+          if (++col == K) {
+            row_end[row] = base + loc;
+            col = 0;
+            row++;
+          }
         }
       }
     }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < tot; i += kWG) {
+      v[base + i] = s_v[i];
+      c[base + i] = s_c[i];
+    }
+    __syncthreads();  // staging and scan scratch are reused by the next tile
   }
   if (LDS_HIST) {
-    __syncthreads();
     for (uint32_t a = threadIdx.x; a < A; a += kWG) {
       uint32_t t = hist[a];
       if (t) atomicAdd(&cnt[a], t);
@@ -2233,50 +2242,96 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
   if (bad) set_status(ctl, RANS_ERR_CORRUPT);
 }
 
-// Exclusive cumulative sum of r (taken on the decoding side, Sec. 3.1) by one
-// work-group; checks r[i] <= K and sum r = nnz.
-__global__ __launch_bounds__(kBig) void k_row_scan(const uint16_t *r, uint32_t N, uint32_t K, uint32_t *row_off,
-                                                   CtlRef ctl) {
-  __shared__ uint32_t sh[kBig / 64];
+// Decoder side of the modified CSR (Sec. 3.1: the cumulative sum of r is taken at decode time, then v is
+// scattered).  Rows are cut into tiles of `tile_rows` rows; k_row_part sums r over each tile (and checks
+// r[i] <= K), a single-work-group scan turns the sums into the index of each tile's first nonzero, and
+// k_csr_to_dense rebuilds one tile per work-group in LDS and writes it out in the output type.
+__global__ __launch_bounds__(kWG) void k_row_part(const uint16_t *r, uint32_t N, uint32_t K, uint32_t tile_rows,
+                                                  uint32_t *part, CtlRef ctl) {
+  __shared__ uint64_t sh64[kWG / 64];
   if (get_status(ctl) != 0) return;
-  uint32_t carry = 0;
+  const uint32_t i0 = blockIdx.x * tile_rows;
+  const uint32_t i1 = i0 + tile_rows < N ? i0 + tile_rows : N;
+  uint64_t loc = 0;
   bool bad = false;
-  for (uint32_t base = 0; base < N; base += kBig) {
-    uint32_t i = base + threadIdx.x;
-    uint32_t v = i < N ? r[i] : 0, tot;
+  for (uint32_t i = i0 + threadIdx.x; i < i1; i += kWG) {
+    const uint32_t v = r[i];
     bad |= v > K;
-    uint32_t ex = block_excl_scan<kBig>(v, sh, &tot);
-    if (i < N) row_off[i] = carry + ex;
+    loc += v;
+  }
+  const uint64_t tot = block_sum64<kWG>(loc, sh64);
+  if (bad || tot > 0xffffffffull) set_status(ctl, RANS_ERR_CORRUPT);
+  if (threadIdx.x == 0) part[blockIdx.x] = (uint32_t)tot;
+}
+
+// One tile of rows: row offsets by a local scan of r, the tile zeroed in LDS, every nonzero of the tile
+// placed (its row found by bisection of the local offsets) and checked (1 <= v < 2^Q, c < K, c strictly
+// increasing inside a row), then the tile written out: as symbols, or dequantised (x = s (xhat - z)).
+// D holds v, c, r as 16-bit symbols; part[] the exclusive scan of the tile sums, part[n_tiles] = their total.
+template <typename OutT>
+__global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const uint32_t *part, uint32_t N, uint32_t K,
+                                                      uint32_t tile_rows, uint32_t q_bits, OutT *out, CtlRef ctl) {
+  extern __shared__ __align__(16) uint32_t l_mem[];
+  __shared__ uint32_t sh[kWG / 64];
+  if (get_status(ctl) != 0) return;
+  const uint32_t nnz = ctl->nnz;
+  const uint32_t i0 = blockIdx.x * tile_rows;
+  const uint32_t rows = i0 + tile_rows < N ? tile_rows : N - i0;
+  uint32_t *roff = l_mem;                                          // rows + 1 local offsets
+  uint8_t *dense = (uint8_t *)(l_mem + ((rows + 1 + 3) & ~3u));   // rows * K symbols
+  const uint32_t base = part[blockIdx.x];
+  const uint32_t n_tiles = gridDim.x;
+  if (blockIdx.x == n_tiles - 1 && part[n_tiles] != nnz) {  // sum of r must be the number of nonzeros
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  const uint16_t *r = D + 2ull * nnz + i0;
+  uint32_t carry = 0;
+  for (uint32_t b0 = 0; b0 < rows; b0 += kWG) {
+    const uint32_t i = b0 + threadIdx.x;
+    const uint32_t v = i < rows ? r[i] : 0;
+    uint32_t tot;
+    const uint32_t ex = block_excl_scan<kWG>(v, sh, &tot);
+    if (i < rows) roff[i] = carry + ex;
     carry += tot;
     __syncthreads();
   }
-  if (threadIdx.x == 0) {
-    row_off[N] = carry;
-    if (carry != ctl->nnz) bad = true;
+  if (threadIdx.x == 0) roff[rows] = carry;
+  const uint32_t cells = rows * K;
+  for (uint32_t i = threadIdx.x; i < (cells + 3) / 4; i += kWG) ((uint32_t *)dense)[i] = 0;
+  __syncthreads();
+  const uint32_t cnt_here = carry;
+  if ((uint64_t)base + cnt_here > nnz) {  // uniform: the offsets would run past the stored nonzeros
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  bool bad = false;
+  for (uint32_t j = threadIdx.x; j < cnt_here; j += kWG) {
+    const uint32_t v = D[base + j], c = D[(uint64_t)nnz + base + j];
+    uint32_t lo = 0, hi = rows;  // largest local row with roff[row] <= j (roff[rows] = cnt_here > j)
+    while (hi - lo > 1) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (roff[mid] <= j) lo = mid;
+      else hi = mid;
+    }
+    bool b = v == 0 || v >= (1u << q_bits) || c >= K;
+    if (j > roff[lo] && D[(uint64_t)nnz + base + j - 1] >= c) b = true;
+    if (b) bad = true;
+    else dense[lo * K + c] = (uint8_t)v;
   }
   if (bad) set_status(ctl, RANS_ERR_CORRUPT);
-}
-
-// Scatter v to (row, c): one thread per nonzero, the row found by bisection of the
-// cumulative row offsets.  Checks 1 <= v < 2^Q, c < K, c increasing inside a row.
-__global__ __launch_bounds__(kWG) void k_csr_expand(const uint16_t *D, const uint32_t *row_off, uint32_t N,
-                                                    uint32_t K, uint32_t q_bits, uint8_t *xhat, CtlRef ctl) {
-  if (get_status(ctl) != 0) return;
-  const uint32_t nnz = ctl->nnz;
-  uint32_t j = blockIdx.x * kWG + threadIdx.x;
-  if (j >= nnz) return;
-  uint32_t v = D[j], c = D[(uint64_t)nnz + j];
-  // largest row i with row_off[i] <= j  (row_off is non-decreasing, row_off[N] = nnz > j)
-  uint32_t lo = 0, hi = N;
-  while (hi - lo > 1) {
-    uint32_t mid = (lo + hi) >> 1;
-    if (row_off[mid] <= j) lo = mid;
-    else hi = mid;
+  __syncthreads();
+  const float s = ctl->scale, zf = ctl->zero_point, x_min = ctl->x_min;
+  OutT *o = out + (uint64_t)i0 * K;
+  for (uint32_t i = threadIdx.x; i < cells; i += kWG) {
+    if constexpr (sizeof(OutT) == 1) {
+      o[i] = dense[i];
+    } else {
+      const float y = s == 0.0f ? x_min : s * ((float)dense[i] - zf);
+      if constexpr (sizeof(OutT) == 4) o[i] = y;
+      else o[i] = __float2half_rn(y);
+    }
   }
-  bool bad = v == 0 || v >= (1u << q_bits) || c >= K;
-  if (j > row_off[lo] && D[(uint64_t)nnz + j - 1] >= c) bad = true;
-  if (bad) set_status(ctl, RANS_ERR_CORRUPT);
-  else xhat[(uint64_t)lo * K + c] = (uint8_t)v;
 }
 
 // Inverse of Eq. 6 over a symbol array.
@@ -2300,13 +2355,13 @@ __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *sym, uint64_t n,
 // launch stream.  Off by default; the normal path records nothing.
 enum KernelId {
   KID_MINMAX = 0, KID_QINFO, KID_QUANT_HIST, KID_CSR_COUNT, KID_SCAN, KID_CSR_COMPACT, KID_CSR_ROWS,
-  KID_NORMALIZE, KID_ENCODE, KID_CHUNK_SCAN, KID_GATHER, KID_DEC_PREPARE, KID_DECODE, KID_FILL, KID_ROW_SCAN,
+  KID_NORMALIZE, KID_ENCODE, KID_CHUNK_SCAN, KID_GATHER, KID_DEC_PREPARE, KID_DECODE, KID_ROW_SCAN,
   KID_CSR_EXPAND, KID_DEQUANT, KID_COUNT
 };
 const char *const kKernelNames[KID_COUNT] = {
     "k_minmax", "k_qinfo", "k_quant_hist", "k_csr_count", "k_scan_u32", "k_csr_compact", "k_csr_rows",
-    "k_normalize", "k_encode", "k_chunk_scan", "k_gather", "k_dec_prepare", "k_decode", "k_fill", "k_row_scan",
-    "k_csr_expand", "k_dequant"};
+    "k_normalize", "k_encode", "k_chunk_scan", "k_gather", "k_dec_prepare", "k_decode", "k_row_part",
+    "k_csr_to_dense", "k_dequant"};
 
 struct ProfRecord {
   int kid;
@@ -2448,12 +2503,13 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       LAUNCH_CHECK();
       PROF_LAUNCH(KID_SCAN, k_scan_u32, dim3(1), dim3(kBig), 0, st, blk, L.n_blk);
       LAUNCH_CHECK();
+      const uint32_t g_compact = L.n_blk < kCompactBlocks ? L.n_blk : kCompactBlocks;
       if (lds_hist)
-        PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true>), dim3(L.n_blk), dim3(kWG), A * 4, st, d_sym, (uint32_t)n, al,
-                           (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A);
+        PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true>), dim3(g_compact), dim3(kWG), A * 4, st, d_sym, (uint32_t)n, al,
+                           (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk);
       else
-        PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<false>), dim3(L.n_blk), dim3(kWG), 0, st, d_sym, (uint32_t)n, al,
-                           (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A);
+        PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<false>), dim3(g_compact), dim3(kWG), 0, st, d_sym, (uint32_t)n, al,
+                           (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk);
       LAUNCH_CHECK();
       uint32_t N = (uint32_t)p.rows;
       uint32_t g = (N + kWG - 1) / kWG;
@@ -2748,25 +2804,33 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
   if (csr && n) {
     const uint32_t N = (uint32_t)h.p.rows, K = (uint32_t)h.p.cols;
     const uint64_t nnz = (h.len_d - N) / 2;
-    uint8_t *xhat = out_kind == 0 ? (uint8_t *)d_out : ws + L.dec_sym;
-    uint32_t *row_off = (uint32_t *)(ws + L.row_off);
     const uint16_t *D = (const uint16_t *)(ws + L.D);
-    PROF_LAUNCH(KID_FILL, (k_fill<uint8_t>), dim3(grid_for(n, kWG * 16, 4096)), dim3(kWG), 0, st, xhat, n, (uint8_t)0);
+    // tile of rows per work-group: about 16K cells, at least one row (a row has at most 65535 cells)
+    uint32_t tile_rows = kDenseTileCells / K;
+    tile_rows = tile_rows < 1 ? 1 : (tile_rows > 4096 ? 4096 : tile_rows);
+    const uint32_t n_tiles = (N + tile_rows - 1) / tile_rows;
+    uint32_t *part = (uint32_t *)(ws + L.row_off);  // n_tiles + 1 entries (n_tiles <= N)
+    PROF_LAUNCH(KID_ROW_SCAN, k_row_part, dim3(n_tiles), dim3(kWG), 0, st, D + 2 * nnz, N, K, tile_rows, part, ctl);
     LAUNCH_CHECK();
-    PROF_LAUNCH(KID_ROW_SCAN, k_row_scan, dim3(1), dim3(kBig), 0, st, D + 2 * nnz, N, K, row_off, ctl);
+    PROF_LAUNCH(KID_SCAN, k_scan_u32, dim3(1), dim3(kBig), 0, st, part, n_tiles);
     LAUNCH_CHECK();
-    if (nnz) {
-      PROF_LAUNCH(KID_CSR_EXPAND, k_csr_expand, dim3((uint32_t)((nnz + kWG - 1) / kWG)), dim3(kWG), 0, st, D, row_off, N, K,
-                         h.p.q_bits, xhat, ctl);
-      LAUNCH_CHECK();
+    const size_t lds = (((size_t)tile_rows + 1 + 3) & ~(size_t)3) * 4 + (((size_t)tile_rows * K + 3) & ~(size_t)3);
+    if (lds > 64 * 1024) {  // a single long row: allow dynamic LDS beyond the default 64 KB (once per instantiation)
+      static const hipError_t a0 = hipFuncSetAttribute((const void *)k_csr_to_dense<uint8_t>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+      static const hipError_t a1 = hipFuncSetAttribute((const void *)k_csr_to_dense<float>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+      static const hipError_t a2 = hipFuncSetAttribute((const void *)k_csr_to_dense<__half>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+      if (a0 != hipSuccess || a1 != hipSuccess || a2 != hipSuccess) return RANS_ERR_HIP;
     }
-    if (out_kind) {
-      const rans_qinfo *qi = (const rans_qinfo *)&ctl->x_min;
-      uint32_t g = grid_for(n, kWG * 8, 8192);
-      if (out_kind == 1) PROF_LAUNCH(KID_DEQUANT, (k_dequant<float>), dim3(g), dim3(kWG), 0, st, xhat, n, qi, ctl, (float *)d_out);
-      else PROF_LAUNCH(KID_DEQUANT, (k_dequant<__half>), dim3(g), dim3(kWG), 0, st, xhat, n, qi, ctl, (__half *)d_out);
-      LAUNCH_CHECK();
-    }
+    if (out_kind == 0)
+      PROF_LAUNCH(KID_CSR_EXPAND, (k_csr_to_dense<uint8_t>), dim3(n_tiles), dim3(kWG), lds, st, D, part, N, K, tile_rows,
+                  h.p.q_bits, (uint8_t *)d_out, ctl);
+    else if (out_kind == 1)
+      PROF_LAUNCH(KID_CSR_EXPAND, (k_csr_to_dense<float>), dim3(n_tiles), dim3(kWG), lds, st, D, part, N, K, tile_rows,
+                  h.p.q_bits, (float *)d_out, ctl);
+    else
+      PROF_LAUNCH(KID_CSR_EXPAND, (k_csr_to_dense<__half>), dim3(n_tiles), dim3(kWG), lds, st, D, part, N, K, tile_rows,
+                  h.p.q_bits, (__half *)d_out, ctl);
+    LAUNCH_CHECK();
   }
   return RANS_OK;
 }

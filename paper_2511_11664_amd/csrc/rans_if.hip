@@ -915,7 +915,8 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
   }
 }
 
-// r[i] = row_end[i] - row_end[i-1] (the NON-cumulative row count), histogrammed.
+// r[i] = row_end[i] - row_end[i-1] (the NON-cumulative row count), histogrammed.  Work-groups stride
+// over the rows and add their histogram to the global one once.
 template <bool LDS_HIST>
 __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint32_t N, uint16_t *r, uint32_t *cnt,
                                                   uint32_t A, CtlRef ctl) {
@@ -924,8 +925,7 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
     for (uint32_t a = threadIdx.x; a < A; a += kWG) hist[a] = 0;
     __syncthreads();
   }
-  uint32_t i = blockIdx.x * kWG + threadIdx.x;
-  if (i < N) {
+  for (uint32_t i = blockIdx.x * kWG + threadIdx.x; i < N; i += gridDim.x * kWG) {
     uint32_t e1 = row_end[i], e0 = i ? row_end[i - 1] : 0;
     uint32_t ri = e1 - e0;
     r[i] = (uint16_t)ri;
@@ -1980,6 +1980,21 @@ __device__ __forceinline__ uint4 load_block16(const uint8_t *in, uint64_t bytes,
 // {f | (slot - F) << 16, output bits} (a 2^M x 8 B table): one LDS access on the state's dependency chain.
 // The byte-per-slot table, the per-symbol table and the scan scratch are then only needed while the tables
 // are built; they live at tmp_off, which may alias the window (not yet in use at that time).
+// Inclusive maximum over the lanes 0 .. l of a wave, in every lane l, with data-parallel-primitive moves
+// (shifts inside rows of 16 lanes, then the last lane of a row broadcast to the rows above): six
+// register-to-register steps instead of six trips through the LDS crossbar.  A lane without a source
+// keeps 0, the identity of the unsigned maximum.
+__device__ __forceinline__ uint32_t wave_incl_max_scan(uint32_t x) {
+  auto mx = [](uint32_t a, int b) { return a > (uint32_t)b ? a : (uint32_t)b; };
+  x = mx(x, __builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false));  // row_shr:1
+  x = mx(x, __builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false));  // row_shr:2
+  x = mx(x, __builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false));  // row_shr:4
+  x = mx(x, __builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false));  // row_shr:8
+  x = mx(x, __builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false));  // row_bcast:15 into rows 1 and 3
+  x = mx(x, __builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false));  // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
 template <class Sink, typename LutT, bool MUL24, int NT, bool WIDE>
 __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t bytes, CtlRef ctl, uint32_t A,
                                                      uint32_t M, uint32_t S, uint32_t cs, uint32_t groups,
@@ -2091,6 +2106,7 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
   __syncthreads();
   {  // running maximum of the marks: each wave owns a contiguous share of the slots
     constexpr uint32_t V = 4 / sizeof(LutT);  // slots per 32-bit word
+    constexpr uint32_t kIt = 4;               // words of a lane handled together (their scans do not depend on each other)
     const uint32_t per_wave = ((total + NW * 64 * V - 1) / (NW * 64 * V)) * 64 * V;
     const uint32_t lo = wave * per_wave;
     if (lo < total) {
@@ -2103,44 +2119,49 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
         else a_hi = mid;
       }
       uint32_t run = a_lo;
-      for (uint32_t b = lo; b < hi; b += 64 * V) {
-        const uint32_t idx = b + lane * V;
-        uint32_t w = idx < hi ? ((const uint32_t *)lut)[idx / V] : 0;
-        uint32_t e[V];
+      for (uint32_t b0 = lo; b0 < hi; b0 += 64 * V * kIt) {
+        uint32_t e[kIt][V], inc[kIt];
 #pragma unroll
-        for (uint32_t q = 0; q < V; q++) e[q] = (w >> (8 * sizeof(LutT) * q)) & (sizeof(LutT) == 1 ? 0xffu : 0xffffu);
+        for (uint32_t it = 0; it < kIt; it++) {
+          const uint32_t idx = b0 + it * 64 * V + lane * V;
+          const uint32_t w = idx < hi ? ((const uint32_t *)lut)[idx / V] : 0;
 #pragma unroll
-        for (uint32_t q = 1; q < V; q++) e[q] = e[q] > e[q - 1] ? e[q] : e[q - 1];
-        uint32_t inc = e[V - 1];
+          for (uint32_t q = 0; q < V; q++) e[it][q] = (w >> (8 * sizeof(LutT) * q)) & (sizeof(LutT) == 1 ? 0xffu : 0xffffu);
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-          const uint32_t o = __shfl_up(inc, d);
-          if (lane >= d) inc = o > inc ? o : inc;
+          for (uint32_t q = 1; q < V; q++) e[it][q] = e[it][q] > e[it][q - 1] ? e[it][q] : e[it][q - 1];
+          inc[it] = wave_incl_max_scan(e[it][V - 1]);
         }
-        uint32_t prev = __shfl_up(inc, 1);
-        prev = lane == 0 ? run : (prev > run ? prev : run);
-        w = 0;
 #pragma unroll
-        for (uint32_t q = 0; q < V; q++) {
-          const uint32_t v = e[q] > prev ? e[q] : prev;
-          w |= v << (8 * sizeof(LutT) * q);
+        for (uint32_t it = 0; it < kIt; it++) {
+          const uint32_t idx = b0 + it * 64 * V + lane * V;
+          // largest mark before this lane's word: the lane below's inclusive maximum, or the running one
+          uint32_t prev = (uint32_t)__builtin_amdgcn_update_dpp((int)run, (int)inc[it], 0x138, 0xf, 0xf, false);  // wave_shr:1
+          prev = prev > run ? prev : run;
+          uint32_t sy[V];
+#pragma unroll
+          for (uint32_t q = 0; q < V; q++) sy[q] = e[it][q] > prev ? e[it][q] : prev;
+          if (idx < hi) {
+            if (WIDE) {  // straight to the slot table the coder reads
+              uint2 te[V];
+#pragma unroll
+              for (uint32_t q = 0; q < V; q++) te[q] = tab[sy[q]];
+#pragma unroll
+              for (uint32_t q = 0; q < V; q++)
+                if (idx + q < total) wide[idx + q] = make_uint2((te[q].x & 0xffffu) | ((idx + q - (te[q].x >> 16)) << 16), te[q].y);
+            } else {
+              uint32_t w = 0;
+#pragma unroll
+              for (uint32_t q = 0; q < V; q++) w |= sy[q] << (8 * sizeof(LutT) * q);
+              ((uint32_t *)lut)[idx / V] = w;
+            }
+          }
+          const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)inc[it], 63);
+          run = last > run ? last : run;
         }
-        if (idx < hi) ((uint32_t *)lut)[idx / V] = w;
-        const uint32_t last = __shfl(inc, 63);
-        run = last > run ? last : run;
       }
     }
   }
   __syncthreads();
-  if (WIDE) {
-#pragma unroll 4
-    for (uint32_t sl = threadIdx.x; sl < total; sl += NT) {
-      const uint2 e = tab[lut[sl]];
-      wide[sl] = make_uint2((e.x & 0xffffu) | ((sl - (e.x >> 16)) << 16), e.y);
-    }
-    __syncthreads();
-  }
-
   if (WIDE) __syncthreads();  // the scan scratch above may alias the window that is filled below
   if (live) {
     typedef __attribute__((address_space(3))) uint16_t lds_u16;
@@ -2513,6 +2534,7 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       LAUNCH_CHECK();
       uint32_t N = (uint32_t)p.rows;
       uint32_t g = (N + kWG - 1) / kWG;
+      g = g > 512 ? 512 : g;
       if (lds_hist)
         PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<true>), dim3(g), dim3(kWG), A * 4, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl);
       else
@@ -2805,8 +2827,11 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
     const uint32_t N = (uint32_t)h.p.rows, K = (uint32_t)h.p.cols;
     const uint64_t nnz = (h.len_d - N) / 2;
     const uint16_t *D = (const uint16_t *)(ws + L.D);
-    // tile of rows per work-group: about 16K cells, at least one row (a row has at most 65535 cells)
-    uint32_t tile_rows = kDenseTileCells / K;
+    // tile of rows per work-group: up to 16K cells, fewer for small tensors (so that there are about a thousand
+    // tiles), at least one row (a row has at most 65535 cells)
+    uint64_t cells = n / 1024;
+    cells = cells < 2048 ? 2048 : (cells > kDenseTileCells ? kDenseTileCells : cells);
+    uint32_t tile_rows = (uint32_t)(cells / K);
     tile_rows = tile_rows < 1 ? 1 : (tile_rows > 4096 ? 4096 : tile_rows);
     const uint32_t n_tiles = (N + tile_rows - 1) / tile_rows;
     uint32_t *part = (uint32_t *)(ws + L.row_off);  // n_tiles + 1 entries (n_tiles <= N)

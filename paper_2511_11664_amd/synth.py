@@ -103,7 +103,7 @@ _RECIPES = {
     "c3": ((64, 512, 28, 28), torch.float32, 2, _c3, 8, 14, 1024, 1 << 18, MODE_DENSE, 256),
     "c4": ((16, 3136, 96), torch.float32, 3, _c4, 8, 12, 1024, 1 << 18, MODE_DENSE, 96),
     "c5a": ((8, 2048, 4096), torch.float16, 4, _c5, 8, 14, 1024, 1 << 18, MODE_DENSE, 4096),
-    "c5b": ((8, 2048, 5120), torch.float16, 5, _c5, 8, 14, 1024, 1 << 18, MODE_DENSE, 5120),
+    "c5b": ((8, 2048, 5120), torch.float16, 5, _c5, 8, 14, 1024, 320 * 1024, MODE_DENSE, 5120),  # 256 chunks: one per CU
 }
 
 NAMES = tuple(_RECIPES)

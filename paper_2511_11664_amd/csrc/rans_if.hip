@@ -198,22 +198,54 @@ __device__ __forceinline__ float key2f(uint32_t k) {
   return __uint_as_float(b);
 }
 
-__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-  return v;
+// Wave-wide inclusive scans with data-parallel-primitive moves (shifts inside rows of 16 lanes, then the
+// last lane of a row broadcast into the rows above): six register-to-register steps instead of six trips
+// through the LDS crossbar.  A lane without a source receives 0, the identity of + and of the unsigned max.
+#define RANS_DPP_STEPS(X, OP)                                                          \
+  X = OP(X, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)X, 0x111, 0xf, 0xf, false)); /* row_shr:1 */ \
+  X = OP(X, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)X, 0x112, 0xf, 0xf, false)); /* row_shr:2 */ \
+  X = OP(X, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)X, 0x114, 0xf, 0xf, false)); /* row_shr:4 */ \
+  X = OP(X, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)X, 0x118, 0xf, 0xf, false)); /* row_shr:8 */ \
+  X = OP(X, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)X, 0x142, 0xa, 0xf, false)); /* row_bcast:15 into rows 1, 3 */ \
+  X = OP(X, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)X, 0x143, 0xc, 0xf, false)); /* row_bcast:31 into rows 2, 3 */
+__device__ __forceinline__ uint32_t op_add32(uint32_t a, uint32_t b) { return a + b; }
+__device__ __forceinline__ uint32_t op_max32(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint32_t wave_incl_sum_scan(uint32_t x) {
+  RANS_DPP_STEPS(x, op_add32)
+  return x;
 }
-
-__device__ __forceinline__ uint64_t shfl_xor64(uint64_t v, int d) {
-  uint32_t lo = __shfl_xor((uint32_t)v, d), hi = __shfl_xor((uint32_t)(v >> 32), d);
+__device__ __forceinline__ uint32_t wave_incl_max_scan(uint32_t x) {
+  RANS_DPP_STEPS(x, op_max32)
+  return x;
+}
+#undef RANS_DPP_STEPS
+// the same moves on both halves of a 64-bit value
+template <class Op>
+__device__ __forceinline__ uint64_t wave_incl_scan64(uint64_t x, Op op) {
+  auto mv = [](uint64_t v, auto ctrl, auto rows) -> uint64_t {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, decltype(ctrl)::value, decltype(rows)::value, 0xf, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), decltype(ctrl)::value, decltype(rows)::value, 0xf, false);
+    return ((uint64_t)hi << 32) | lo;
+  };
+  using std::integral_constant;
+  x = op(x, mv(x, integral_constant<int, 0x111>{}, integral_constant<int, 0xf>{}));
+  x = op(x, mv(x, integral_constant<int, 0x112>{}, integral_constant<int, 0xf>{}));
+  x = op(x, mv(x, integral_constant<int, 0x114>{}, integral_constant<int, 0xf>{}));
+  x = op(x, mv(x, integral_constant<int, 0x118>{}, integral_constant<int, 0xf>{}));
+  x = op(x, mv(x, integral_constant<int, 0x142>{}, integral_constant<int, 0xa>{}));
+  x = op(x, mv(x, integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{}));
+  return x;
+}
+__device__ __forceinline__ uint64_t lane63_64(uint64_t v) {  // the value lane 63 holds, in every lane
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, 63);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), 63);
   return ((uint64_t)hi << 32) | lo;
 }
 
 // Sum / max over a work-group of NT threads; every thread receives the result.
 template <int NT>
 __device__ uint64_t block_sum64(uint64_t v, uint64_t *sh /* NT/64 entries */) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += shfl_xor64(v, d);
+  v = lane63_64(wave_incl_scan64(v, [](uint64_t a, uint64_t b) { return a + b; }));
   __syncthreads();
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
   __syncthreads();
@@ -224,11 +256,7 @@ __device__ uint64_t block_sum64(uint64_t v, uint64_t *sh /* NT/64 entries */) {
 }
 template <int NT>
 __device__ uint64_t block_max64(uint64_t v, uint64_t *sh) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) {
-    uint64_t o = shfl_xor64(v, d);
-    v = o > v ? o : v;
-  }
+  v = lane63_64(wave_incl_scan64(v, [](uint64_t a, uint64_t b) { return a > b ? a : b; }));
   __syncthreads();
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
   __syncthreads();
@@ -242,12 +270,7 @@ __device__ uint64_t block_max64(uint64_t v, uint64_t *sh) {
 template <int NT>
 __device__ uint32_t block_excl_scan(uint32_t v, uint32_t *sh /* NT/64 entries */, uint32_t *total) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  uint32_t inc = v;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    uint32_t o = __shfl_up(inc, d);
-    if (lane >= d) inc += o;
-  }
+  const uint32_t inc = wave_incl_sum_scan(v);
   __syncthreads();
   if (lane == 63) sh[w] = inc;
   __syncthreads();
@@ -1980,21 +2003,6 @@ __device__ __forceinline__ uint4 load_block16(const uint8_t *in, uint64_t bytes,
 // {f | (slot - F) << 16, output bits} (a 2^M x 8 B table): one LDS access on the state's dependency chain.
 // The byte-per-slot table, the per-symbol table and the scan scratch are then only needed while the tables
 // are built; they live at tmp_off, which may alias the window (not yet in use at that time).
-// Inclusive maximum over the lanes 0 .. l of a wave, in every lane l, with data-parallel-primitive moves
-// (shifts inside rows of 16 lanes, then the last lane of a row broadcast to the rows above): six
-// register-to-register steps instead of six trips through the LDS crossbar.  A lane without a source
-// keeps 0, the identity of the unsigned maximum.
-__device__ __forceinline__ uint32_t wave_incl_max_scan(uint32_t x) {
-  auto mx = [](uint32_t a, int b) { return a > (uint32_t)b ? a : (uint32_t)b; };
-  x = mx(x, __builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false));  // row_shr:1
-  x = mx(x, __builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false));  // row_shr:2
-  x = mx(x, __builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false));  // row_shr:4
-  x = mx(x, __builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false));  // row_shr:8
-  x = mx(x, __builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false));  // row_bcast:15 into rows 1 and 3
-  x = mx(x, __builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false));  // row_bcast:31 into rows 2 and 3
-  return x;
-}
-
 template <class Sink, typename LutT, bool MUL24, int NT, bool WIDE>
 __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t bytes, CtlRef ctl, uint32_t A,
                                                      uint32_t M, uint32_t S, uint32_t cs, uint32_t groups,

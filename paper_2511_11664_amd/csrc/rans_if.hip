@@ -2210,12 +2210,18 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
     typedef __attribute__((address_space(3))) LutT lds_lut;
     typedef __attribute__((address_space(3))) uint64_t lds_u64;
     const uint32_t tab_off = (uint32_t)(uintptr_t)(lds_u64 *)tab;
+    // Called every 8 steps (a step consumes at most one word).  The window holds blocks cur and cur + 1,
+    // cur the block of the next unread word.  A block is requested two blocks ahead and moved into the
+    // window once the block whose rows it takes (two blocks back) is read up.  Reading a block takes at
+    // least 8 steps, so each block sees a call while it is being read: block b is requested during
+    // block b - 2 at the latest and stored during block b - 1.
     auto refill = [&]() {
-      if (pending) {
+      const uint32_t cur = rd9 >> (LOG_RB + 3);
+      if (pending && pend_b <= cur + 1) {
         store_block(pend_b, pend_q);
         pending = false;
       }
-      if (ldb <= (rd9 >> (LOG_RB + 3)) + 1 && ldb * 16 < end16) {
+      if (!pending && ldb <= cur + 2 && ldb * 16 < end16) {
         pend_q = load_block(ldb * 16);
         pend_b = ldb;
         pending = true;
@@ -2248,12 +2254,10 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
       smin = s < smin ? s : smin;
     };
     uint64_t t = 0;
-    for (; t + 4 <= rows_full; t += 4) {
+    for (; t + 8 <= rows_full; t += 8) {
       refill();
-      step();
-      step();
-      step();
-      step();
+#pragma unroll
+      for (int u = 0; u < 8; u++) step();
     }
     if (t < rows_full || j < rem_row) {
       refill();

@@ -311,3 +311,27 @@ def decompress(buf, out_dtype=F32):
     _check(lib().orc_decompress(_ptr(a), C.c_size_t(a.size), _ptr(sym), C.c_uint64(sym.size), C.byref(qi),
                                 out_dtype, _ptr(out)))
     return sym[:h.n_elems], qi, out[:h.n_elems]
+
+
+def reshape_cost(xhat: np.ndarray, n_rows: int, q_bits: int):
+    """Size proxy l_D * H(p(N)) in bits for the reshape [N, T/N] (Sec. 3.2, Eq. 8 with both alphas 0)."""
+    xhat = np.ascontiguousarray(xhat, dtype=np.uint8).ravel()
+    cost = C.c_double()
+    len_d = C.c_uint64()
+    _check(lib().orc_reshape_cost(_ptr(xhat), C.c_uint64(xhat.size), C.c_uint64(n_rows), C.c_uint32(q_bits),
+                                  C.byref(cost), C.byref(len_d)))
+    return cost.value, len_d.value
+
+
+def search_reshape(xhat: np.ndarray, q_bits: int, cap: int = 4096):
+    """Algorithm 1: returns (N_tilde, best_cost, [(N, cost) for every N evaluated, in order])."""
+    xhat = np.ascontiguousarray(xhat, dtype=np.uint8).ravel()
+    n_best = C.c_uint64()
+    best = C.c_double()
+    cand_n = np.zeros(cap, dtype=np.uint64)
+    cand_c = np.zeros(cap, dtype=np.float64)
+    n_cand = C.c_uint32()
+    _check(lib().orc_search_reshape(_ptr(xhat), C.c_uint64(xhat.size), C.c_uint32(q_bits), C.byref(n_best),
+                                    C.byref(best), _ptr(cand_n), _ptr(cand_c), C.c_uint32(cap), C.byref(n_cand)))
+    k = min(n_cand.value, cap)
+    return n_best.value, best.value, list(zip(cand_n[:k].tolist(), cand_c[:k].tolist()))

@@ -642,6 +642,92 @@ int orc_decode_container(const uint8_t *buf, size_t bytes, uint16_t *D, uint64_t
 
 /* ---------------------------------------------------------- whole path */
 
+/* ---------------------------------------------------------------- Sec. 3.2: reshape search */
+
+int orc_reshape_cost(const uint8_t *xhat, uint64_t T, uint64_t N, uint32_t q_bits, double *cost_bits,
+                     uint64_t *len_D) {
+  if (!xhat || !cost_bits || T == 0 || N == 0 || T % N != 0 || q_bits < 1 || q_bits > 8) return ORC_ERR_ARG;
+  const uint64_t K = T / N;
+  if (K > 65535) return ORC_ERR_ARG;
+  uint16_t *v = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)T);
+  uint16_t *c = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)T);
+  uint16_t *r = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)N);
+  if (!v || !c || !r) {
+    free(v); free(c); free(r);
+    return ORC_ERR_ARG;
+  }
+  uint64_t nnz = 0;
+  int rc = orc_csr(xhat, N, K, v, c, r, &nnz);
+  if (rc) {
+    free(v); free(c); free(r);
+    return rc;
+  }
+  /* one histogram over D = v (+) c (+) r (Eq. 7) */
+  const uint32_t two_q = 1u << q_bits;
+  const uint32_t A = (uint32_t)(K + 1 > two_q ? K + 1 : two_q);
+  uint64_t *cnt = (uint64_t *)calloc(A, sizeof(uint64_t));
+  if (!cnt) {
+    free(v); free(c); free(r);
+    return ORC_ERR_ARG;
+  }
+  for (uint64_t j = 0; j < nnz; j++) cnt[v[j]]++;
+  for (uint64_t j = 0; j < nnz; j++) cnt[c[j]]++;
+  for (uint64_t i = 0; i < N; i++) cnt[r[i]]++;
+  const uint64_t len = 2 * nnz + N;
+  double H = 0.0;
+  for (uint32_t a = 0; a < A; a++) {
+    if (cnt[a]) {
+      const double p = (double)cnt[a] / (double)len;
+      H -= p * log2(p);
+    }
+  }
+  *cost_bits = (double)len * H;
+  if (len_D) *len_D = len;
+  free(cnt); free(v); free(c); free(r);
+  return ORC_OK;
+}
+
+static uint64_t isqrt_u64(uint64_t t) {
+  uint64_t r = (uint64_t)sqrt((double)t);
+  while (r * r > t) r--;
+  while ((r + 1) * (r + 1) <= t) r++;
+  return r;
+}
+
+int orc_search_reshape(const uint8_t *xhat, uint64_t T, uint32_t q_bits, uint64_t *N_best, double *best_cost,
+                       uint64_t *cand_N, double *cand_cost, uint32_t cand_cap, uint32_t *n_cand) {
+  if (!xhat || !N_best || !best_cost || T == 0 || q_bits < 1 || q_bits > 8) return ORC_ERR_ARG;
+  const uint64_t two_q = 1ull << q_bits;
+  const uint64_t n_sqrt = isqrt_u64(T) + 1;
+  const uint64_t n_q = (T + two_q - 1) / two_q;
+  const uint64_t N_min = n_sqrt > n_q ? n_sqrt : n_q;
+  const uint64_t N_max = T;
+  double best = INFINITY, prev = INFINITY;
+  uint64_t N_tilde = N_max;
+  uint32_t evaluated = 0;
+  for (uint64_t N = N_max; N >= N_min && N >= 1; N--) {
+    if (T % N != 0) continue;
+    double cost;
+    int rc = orc_reshape_cost(xhat, T, N, q_bits, &cost, NULL);
+    if (rc) return rc;
+    if (evaluated < cand_cap) {
+      if (cand_N) cand_N[evaluated] = N;
+      if (cand_cost) cand_cost[evaluated] = cost;
+    }
+    evaluated++;
+    if (cost < best) {
+      best = cost;
+      N_tilde = N;
+    }
+    if (cost > prev) break;
+    prev = cost;
+  }
+  *N_best = N_tilde;
+  *best_cost = best;
+  if (n_cand) *n_cand = evaluated;
+  return ORC_OK;
+}
+
 /* Fig. 1(c): reshape + quantise (Eq. 5-6), modified CSR, D = v (+) c (+) r
  * (Eq. 7; DENSE mode: D = xhat), one frequency table, rANS. */
 int orc_compress(const void *x, uint64_t n, const orc_params *p, uint8_t *out, size_t out_cap,

@@ -4,7 +4,7 @@
  * TEST INFRASTRUCTURE ONLY.  This is a plain, slow, single-threaded C
  * implementation of what the codec computes, written from the paper
  * (Sec. 2.1 "Brief Introduction to rANS", Sec. 3.1 "rANS-based Compression
- * Pipeline").  It exists so that tests, the smoke check and the benchmark's
+ * Pipeline", Sec. 3.2 Algorithm 1 for the reshape search).  It exists so that tests, the smoke check and the benchmark's
  * cpu_baseline leg can compare the GPU library against it.  Nothing in the
  * product path may include, link or call it, and it shares no code with the
  * GPU library.
@@ -18,7 +18,10 @@
  * closed-form values, the hand-computed two-symbol example of Eq. 2 / Eq. 4,
  * exact round trip, a big-integer coder written directly from Eq. 2-4,
  * exhaustive brute force over tiny alphabets, CSR brute force, size against
- * the entropy bound of Eq. 1.  Parity unpinned by the paper (format
+ * the entropy bound of Eq. 1; the reshape cost against an independent numpy /
+ * scipy construction, a closed form for K = 1 and a planted column structure,
+ * the search against a re-walk of Algorithm 1's rules over those costs.
+ * Parity unpinned by the paper (format
  * definitions of this build, checked only for self-consistency): container
  * byte layout, normalisation tie-break rule, chunk/stream assignment.
  */
@@ -129,6 +132,19 @@ int orc_parse_header(const uint8_t *buf, size_t bytes, orc_header *h);
 /* Decode a container to D (cap >= len_D), validating everything. */
 int orc_decode_container(const uint8_t *buf, size_t bytes, uint16_t *D, uint64_t D_cap,
                          orc_header *h);
+
+/* Sec. 3.2, Eq. 8 with alpha_enc = alpha_dec = 0 (as Algorithm 1 sets them): the size proxy
+ * T_tot(N) = l_D * H(p(N)) in bits for the reshape [N, T/N] of the quantised tensor: D and its
+ * histogram as orc_csr / orc_histogram give them, H = -sum p log2 p with p = count / l_D, all in
+ * binary64, symbols summed in ascending order.  N must divide T and T/N must be at most 65535. */
+int orc_reshape_cost(const uint8_t *xhat, uint64_t T, uint64_t N, uint32_t q_bits, double *cost_bits,
+                     uint64_t *len_D);
+/* Algorithm 1: N from N_max = T down to N_min = max(floor(sqrt T) + 1, ceil(T / 2^Q)), divisors of T only;
+ * the best cost so far and its N are kept; the walk stops after the first N whose cost is larger than the
+ * previous one.  cand_N / cand_cost (nullable, cand_cap entries) receive every N evaluated and its cost,
+ * *n_cand their number.  No N in the domain: *N_best = T, *best_cost = +inf, *n_cand = 0. */
+int orc_search_reshape(const uint8_t *xhat, uint64_t T, uint32_t q_bits, uint64_t *N_best, double *best_cost,
+                       uint64_t *cand_N, double *cand_cost, uint32_t cand_cap, uint32_t *n_cand);
 
 /* Whole path: tensor -> container, container -> symbols / floats. */
 int orc_compress(const void *x, uint64_t n_elems, const orc_params *p, uint8_t *out,

@@ -136,6 +136,29 @@ int rans_decompress(const uint8_t *d_stream, size_t stream_bytes, const rans_hea
                     uint32_t out_dtype, void *d_x_out, uint64_t elem_cap, void *d_ws,
                     size_t ws_bytes, void *stream);
 
+/* Sec. 3.2, Algorithm 1: approximate search for the reshape N~ of the modified CSR.  The cost of a
+ * reshape [N, K = T/N] is the size proxy of Eq. 8 with alpha_enc = alpha_dec = 0,
+ * T_tot(N) = l_D * H(p(N)) in bits, H the entropy of the one histogram over D = v (+) c (+) r (Eq. 7),
+ * in binary64.  The domain is N > sqrt(T), T/N <= 2^Q, N | T; the walk goes from N = T downwards,
+ * keeps the cheapest N and stops after the first N that costs more than the one before it.
+ * d_sym: the n_elems quantised symbols (< 2^Q).  *d_result (device, 8-byte aligned) receives the
+ * result; the costs of ALL reshapes of the domain are computed (cand_* in walk order, the first
+ * n_evaluated of them are the ones the walk looks at).  An empty domain gives rows = T, cols = 1,
+ * cost_bits = +inf.  More than RANS_RESHAPE_MAX_CAND reshapes in the domain: RANS_ERR_ARG.
+ * Workspace: rans_search_workspace_bytes(). */
+#define RANS_RESHAPE_MAX_CAND 128
+typedef struct {
+  uint64_t rows, cols;   /* N~, T / N~ */
+  double cost_bits;      /* T_tot(N~) */
+  uint32_t n_evaluated;  /* reshapes the walk evaluated before it stopped */
+  uint32_t n_candidates; /* reshapes in the domain */
+  uint64_t cand_rows[RANS_RESHAPE_MAX_CAND];
+  double cand_cost[RANS_RESHAPE_MAX_CAND];
+} rans_reshape_result;
+int rans_search_workspace_bytes(uint64_t n_elems, uint32_t q_bits, size_t *ws_bytes);
+int rans_search_reshape(const uint8_t *d_sym, uint64_t n_elems, uint32_t q_bits,
+                        rans_reshape_result *d_result, void *d_ws, size_t ws_bytes, void *stream);
+
 /* Parse the fixed 128-byte header on the host.  h_bytes: at least 128 bytes.
  * RANS_ERR_CORRUPT if the fields are not a valid header. */
 int rans_peek_header(const void *h_bytes, size_t n_bytes, rans_header *out);

@@ -56,6 +56,15 @@ class QInfo(C.Structure):
                 ("zero_point", C.c_float)]
 
 
+RESHAPE_MAX_CAND = 128
+
+
+class ReshapeResult(C.Structure):
+    _fields_ = [("rows", C.c_uint64), ("cols", C.c_uint64), ("cost_bits", C.c_double),
+                ("n_evaluated", C.c_uint32), ("n_candidates", C.c_uint32),
+                ("cand_rows", C.c_uint64 * RESHAPE_MAX_CAND), ("cand_cost", C.c_double * RESHAPE_MAX_CAND)]
+
+
 class Header(C.Structure):
     _fields_ = [("p", Params), ("n_elems", C.c_uint64), ("len_d", C.c_uint64),
                 ("alphabet", C.c_uint32), ("n_chunks", C.c_uint32),
@@ -64,6 +73,7 @@ class Header(C.Structure):
 
 EXPORTS = ("rans_workspace_bytes", "rans_quantize", "rans_encode", "rans_decode", "rans_dequantize",
            "rans_compress", "rans_decompress", "rans_peek_header", "rans_last_status",
+           "rans_search_workspace_bytes", "rans_search_reshape",
            "rans_profile_enable", "rans_profile_reset", "rans_profile_read",
            "rans_strerror", "rans_profile_kernel_name")
 
@@ -88,6 +98,8 @@ def lib() -> C.CDLL:
         L.rans_decompress.argtypes = [vp, sz, HP, u32, vp, u64, vp, sz, vp]
         L.rans_peek_header.argtypes = [vp, sz, HP]
         L.rans_last_status.argtypes = [vp, vp]
+        L.rans_search_workspace_bytes.argtypes = [u64, u32, C.POINTER(sz)]
+        L.rans_search_reshape.argtypes = [vp, u64, u32, vp, vp, sz, vp]
         L.rans_strerror.argtypes = [C.c_int]
         L.rans_strerror.restype = C.c_char_p
         L.rans_profile_enable.argtypes = [u64, u32]
@@ -172,6 +184,36 @@ def rans_peek_header(h_bytes: bytes):
 
 def rans_last_status(d_ws) -> int:
     return lib().rans_last_status(_p(d_ws), _stream())
+
+
+def rans_search_workspace_bytes(n_elems: int, q_bits: int):
+    ws = C.c_size_t()
+    rc = lib().rans_search_workspace_bytes(n_elems, q_bits, C.byref(ws))
+    return rc, ws.value
+
+
+def rans_search_reshape(d_sym, n_elems, q_bits, d_result, d_ws) -> int:
+    """d_result: a device byte tensor of at least sizeof(ReshapeResult) bytes."""
+    return lib().rans_search_reshape(_p(d_sym), n_elems, q_bits, _p(d_result), _p(d_ws),
+                                     d_ws.numel() * d_ws.element_size(), _stream())
+
+
+def search_reshape(d_sym, q_bits: int) -> ReshapeResult:
+    """Algorithm 1 on a device tensor of quantised symbols; allocates its workspace, synchronises, returns the result."""
+    import torch
+    n = d_sym.numel()
+    rc, ws_bytes = rans_search_workspace_bytes(n, q_bits)
+    if rc:
+        raise RansError(rc)
+    ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=d_sym.device)
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + ws_bytes]
+    res = torch.zeros(C.sizeof(ReshapeResult), dtype=torch.uint8, device=d_sym.device)
+    rc = rans_search_reshape(d_sym, n, q_bits, res, ws)
+    if rc:
+        raise RansError(rc)
+    host = res.cpu().numpy().tobytes()
+    return ReshapeResult.from_buffer_copy(host)
 
 
 def rans_strerror(code: int) -> str:

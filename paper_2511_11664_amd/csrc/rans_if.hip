@@ -2381,6 +2381,193 @@ __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *sym, uint64_t n,
   }
 }
 
+// ------------------------------------------------------------------ kernels: reshape search (Sec. 3.2)
+
+// The quantised tensor is fixed over all reshapes [N, K]: so are the nonzero values v and their
+// number.  Only the histograms of the column indices (position mod K) and of the row counts change.
+// One pass turns the tensor into a zero mask (16 positions per entry), the number of nonzeros
+// before each entry inside its tile, the tile totals and the histogram of v; everything else is
+// computed from those.
+constexpr uint32_t kRsTile = kWG * 16;
+struct RsCands {
+  uint32_t n;
+  uint16_t K[RANS_RESHAPE_MAX_CAND];
+};
+struct RsOffsets {  // first bin of each candidate's column / row-count histogram; entry n = total
+  uint32_t hc[RANS_RESHAPE_MAX_CAND + 1], hr[RANS_RESHAPE_MAX_CAND + 1];
+};
+
+__global__ __launch_bounds__(kWG) void k_rs_mask(const uint8_t *sym, uint32_t n, int aligned, uint32_t n_tiles,
+                                                 uint16_t *mask16, uint16_t *lp, uint32_t *tile_cnt, uint32_t *hv,
+                                                 uint32_t q_bits, uint32_t *bad_flag) {
+  __shared__ uint32_t sh[kWG / 64];
+  __shared__ uint32_t h[256];
+  h[threadIdx.x] = 0;  // kWG == 256
+  __syncthreads();
+  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const uint64_t e0 = (uint64_t)tile * kRsTile + threadIdx.x * 16;
+    uint8_t b[16];
+    load16(sym, e0, n, aligned, b);
+    uint32_t m = 0;
+#pragma unroll
+    for (int k = 0; k < 16; k++) {
+      if (b[k]) {
+        m |= 1u << k;
+        if (b[k] >> q_bits) atomicOr(bad_flag, 1u);  // not a symbol of this bit width
+        atomicAdd(&h[b[k]], 1u);
+      }
+    }
+    uint32_t tot;
+    const uint32_t ex = block_excl_scan<kWG>(__popc(m), sh, &tot);
+    if (e0 < n) {
+      mask16[e0 >> 4] = (uint16_t)m;
+      lp[e0 >> 4] = (uint16_t)ex;
+    }
+    if (threadIdx.x == 0) tile_cnt[tile] = tot;
+    __syncthreads();
+  }
+  const uint32_t t = h[threadIdx.x];
+  if (t) atomicAdd(&hv[threadIdx.x], t);
+}
+
+// zeroes the histograms of a call (runs before k_rs_mask, which adds to hv)
+__global__ void k_rs_zero(uint32_t *p, uint32_t words) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < words; i += gridDim.x * blockDim.x) p[i] = 0;
+}
+
+// Histograms of c = position mod K over the nonzero positions, for the candidates [k0, k1): their bins
+// sit one after the other in LDS (at most kRsColBins in total) and in hc (at hc_off[k]).
+constexpr uint32_t kRsColBins = 8192;
+__global__ __launch_bounds__(kWG) void k_rs_cols(const uint16_t *mask16, uint32_t n_entries, RsCands cands, uint32_t k0,
+                                                 uint32_t k1, RsOffsets offs, uint32_t *hc) {
+  __shared__ uint32_t h[kRsColBins];
+  const uint32_t *hc_off = offs.hc;
+  const uint32_t base0 = hc_off[k0], bins = hc_off[k1] - base0;
+  for (uint32_t i = threadIdx.x; i < bins; i += kWG) h[i] = 0;
+  __syncthreads();
+  for (uint32_t e = blockIdx.x * kWG + threadIdx.x; e < n_entries; e += gridDim.x * kWG) {
+    const uint32_t m = mask16[e];
+    if (!m) continue;
+    const uint32_t g0 = e * 16;  // n <= 2^30: fits
+    for (uint32_t k = k0; k < k1; k++) {
+      const uint32_t K = cands.K[k];
+      uint32_t *hk = h + (hc_off[k] - base0);
+      uint32_t c = g0 % K;
+#pragma unroll
+      for (int bit = 0; bit < 16; bit++) {
+        if (m & (1u << bit)) atomicAdd(&hk[c], 1u);
+        c = c + 1 == K ? 0 : c + 1;
+      }
+    }
+  }
+  __syncthreads();
+  for (uint32_t i = threadIdx.x; i < bins; i += kWG) {
+    const uint32_t t = h[i];
+    if (t) atomicAdd(&hc[base0 + i], t);
+  }
+}
+
+// nonzeros before position g (g <= n)
+__device__ __forceinline__ uint32_t rs_prefix(uint32_t g, uint32_t n, uint32_t nnz, const uint16_t *mask16,
+                                              const uint16_t *lp, const uint32_t *tile_off) {
+  if (g >= n) return nnz;
+  const uint32_t e = g >> 4;
+  return tile_off[g / kRsTile] + lp[e] + __popc((uint32_t)mask16[e] & ((1u << (g & 15)) - 1u));
+}
+
+// Histogram of the row counts r for candidate blockIdx.y: r[i] = prefix((i + 1) K) - prefix(i K).
+__global__ __launch_bounds__(kWG) void k_rs_rows(const uint16_t *mask16, const uint16_t *lp, const uint32_t *tile_off,
+                                                 uint32_t n, uint32_t n_tiles, RsCands cands, RsOffsets offs,
+                                                 uint32_t *hr) {
+  __shared__ uint32_t h[257];
+  const uint32_t *hr_off = offs.hr;
+  const uint32_t k = blockIdx.y, K = cands.K[k];
+  const uint32_t nnz = tile_off[n_tiles];
+  uint32_t *out = hr + hr_off[k];
+  if (K == 1) {  // the row counts are the zero mask itself
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      out[0] = n - nnz;
+      out[1] = nnz;
+    }
+    return;
+  }
+  for (uint32_t i = threadIdx.x; i <= K; i += kWG) h[i] = 0;
+  __syncthreads();
+  const uint32_t N = n / K;
+  for (uint32_t i = blockIdx.x * kWG + threadIdx.x; i < N; i += gridDim.x * kWG) {
+    const uint32_t a = rs_prefix(i * K, n, nnz, mask16, lp, tile_off);
+    const uint32_t b = rs_prefix(i * K + K, n, nnz, mask16, lp, tile_off);
+    atomicAdd(&h[b - a], 1u);
+  }
+  __syncthreads();
+  for (uint32_t i = threadIdx.x; i <= K; i += kWG) {
+    const uint32_t t = h[i];
+    if (t) atomicAdd(&out[i], t);
+  }
+}
+
+// Costs and the walk of Algorithm 1.  One thread per candidate sums its entropy (symbols in ascending
+// order, binary64); thread 0 then walks the candidates from the largest N down.
+__global__ __launch_bounds__(RANS_RESHAPE_MAX_CAND) void k_rs_cost(RsCands cands, uint32_t n, uint32_t n_tiles,
+                                                                    uint32_t q_bits, const uint32_t *tile_off,
+                                                                    const uint32_t *hv, const uint32_t *hc,
+                                                                    const uint32_t *hr, RsOffsets offs,
+                                                                    const uint32_t *bad_flag,
+                                                                    rans_reshape_result *res) {
+  __shared__ double s_cost[RANS_RESHAPE_MAX_CAND];
+  const uint32_t *hc_off = offs.hc, *hr_off = offs.hr;
+  const uint32_t k = threadIdx.x;
+  const uint32_t nnz = tile_off[n_tiles];
+  if (k < cands.n) {
+    const uint32_t K = cands.K[k], N = n / K;
+    const uint32_t two_q = 1u << q_bits;
+    const uint32_t A = K + 1 > two_q ? K + 1 : two_q;
+    const uint64_t len = 2ull * nnz + N;
+    double H = 0.0;
+    for (uint32_t a = 0; a < A; a++) {
+      uint64_t c = 0;
+      if (a < two_q) c += hv[a];
+      if (a < K) c += hc[hc_off[k] + a];
+      if (a <= K) c += hr[hr_off[k] + a];
+      if (c) {
+        const double p = (double)c / (double)len;
+        H -= p * log2(p);
+      }
+    }
+    s_cost[k] = (double)len * H;
+  }
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  double best = INFINITY, prev = INFINITY;
+  uint64_t n_tilde = n;
+  uint32_t evaluated = 0;
+  for (uint32_t i = 0; i < cands.n; i++) {
+    const double cost = s_cost[i];
+    res->cand_rows[i] = n / cands.K[i];
+    res->cand_cost[i] = cost;
+    if (evaluated == i) {  // the walk is still going
+      evaluated++;
+      if (cost < best) {
+        best = cost;
+        n_tilde = n / cands.K[i];
+      }
+      if (cost > prev) evaluated |= 0x80000000u;  // stop after this one
+      prev = cost;
+    }
+  }
+  evaluated &= 0x7fffffffu;
+  if (*bad_flag) {  // a symbol outside {0 .. 2^Q - 1}: no meaningful result
+    best = __longlong_as_double(0x7ff8000000000000ll);
+    n_tilde = n;
+    evaluated = 0;
+  }
+  res->rows = n_tilde;
+  res->cols = n / n_tilde;
+  res->cost_bits = best;
+  res->n_evaluated = evaluated;
+  res->n_candidates = cands.n;
+}
+
 // ------------------------------------------------------------------ instrumentation
 
 // Optional per-kernel timing for benchmarks: when a kernel's bit is set in the
@@ -2872,6 +3059,102 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
   return RANS_OK;
 }
 
+
+// ---- reshape search: host side
+
+struct RsPlan {
+  RsCands cands;
+  RsOffsets offs;
+  uint32_t n_entries, n_tiles;
+  size_t mask16, lp, tile_cnt, zero0, hv, hc, hr, bad, total;  // byte offsets in the workspace
+  uint32_t zero_words;
+  bool too_many;
+};
+
+uint64_t isqrt_u64(uint64_t t) {
+  uint64_t r = (uint64_t)sqrt((double)t);
+  while (r * r > t) r--;
+  while ((r + 1) * (r + 1) <= t) r++;
+  return r;
+}
+
+// Domain of Algorithm 1 in walk order (N descending = K ascending): K | T, K <= 2^Q, T/K > sqrt(T).
+RsPlan rs_plan(uint64_t n, uint32_t q_bits) {
+  RsPlan P{};
+  const uint64_t two_q = 1ull << q_bits;
+  const uint64_t n_sq = isqrt_u64(n) + 1, n_q = (n + two_q - 1) / two_q;
+  const uint64_t n_min = n_sq > n_q ? n_sq : n_q;
+  for (uint64_t K = 1; K <= two_q && K <= n; K++) {
+    if (n % K) continue;
+    if (n / K < n_min) break;
+    if (P.cands.n == RANS_RESHAPE_MAX_CAND) {
+      P.too_many = true;
+      break;
+    }
+    P.cands.K[P.cands.n++] = (uint16_t)K;
+  }
+  uint32_t oc = 0, orr = 0;
+  for (uint32_t k = 0; k < P.cands.n; k++) {
+    P.offs.hc[k] = oc;
+    P.offs.hr[k] = orr;
+    oc += P.cands.K[k];
+    orr += P.cands.K[k] + 1u;
+  }
+  P.offs.hc[P.cands.n] = oc;
+  P.offs.hr[P.cands.n] = orr;
+  P.n_entries = (uint32_t)((n + 15) / 16);
+  P.n_tiles = (uint32_t)((n + kRsTile - 1) / kRsTile);
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = o;
+    o = align_up(o + bytes, 256);
+    return at;
+  };
+  P.mask16 = take((size_t)P.n_entries * 2);
+  P.lp = take((size_t)P.n_entries * 2);
+  P.tile_cnt = take(((size_t)P.n_tiles + 1) * 4);
+  P.zero0 = o;
+  P.hv = take(256 * 4);
+  P.hc = take((size_t)oc * 4 + 4);
+  P.hr = take((size_t)orr * 4 + 4);
+  P.bad = take(4);
+  P.zero_words = (uint32_t)((o - P.zero0) / 4);
+  P.total = o;
+  return P;
+}
+
+int launch_search_reshape(const uint8_t *d_sym, uint64_t n, uint32_t q_bits, rans_reshape_result *d_res, uint8_t *ws,
+                          const RsPlan &P, hipStream_t st) {
+  uint16_t *mask16 = (uint16_t *)(ws + P.mask16), *lp = (uint16_t *)(ws + P.lp);
+  uint32_t *tile_cnt = (uint32_t *)(ws + P.tile_cnt);
+  uint32_t *hv = (uint32_t *)(ws + P.hv), *hc = (uint32_t *)(ws + P.hc), *hr = (uint32_t *)(ws + P.hr);
+  uint32_t *bad = (uint32_t *)(ws + P.bad);
+  hipLaunchKernelGGL(k_rs_zero, dim3(8), dim3(256), 0, st, (uint32_t *)(ws + P.zero0), P.zero_words);
+  LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_rs_mask, dim3(P.n_tiles < 1024 ? P.n_tiles : 1024), dim3(kWG), 0, st, d_sym, (uint32_t)n,
+                     (int)aligned_to(d_sym, 16), P.n_tiles, mask16, lp, tile_cnt, hv, q_bits, bad);
+  LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(kBig), 0, st, tile_cnt, P.n_tiles);
+  LAUNCH_CHECK();
+  const uint32_t g_e = grid_for(P.n_entries, kWG, 1024);
+  for (uint32_t k0 = 0; k0 < P.cands.n;) {  // groups of candidates whose column bins fit in LDS together
+    uint32_t k1 = k0 + 1;
+    while (k1 < P.cands.n && P.offs.hc[k1 + 1] - P.offs.hc[k0] <= kRsColBins) k1++;
+    hipLaunchKernelGGL(k_rs_cols, dim3(g_e), dim3(kWG), 0, st, mask16, P.n_entries, P.cands, k0, k1, P.offs, hc);
+    LAUNCH_CHECK();
+    k0 = k1;
+  }
+  if (P.cands.n) {
+    hipLaunchKernelGGL(k_rs_rows, dim3(grid_for(n, kWG, 512), P.cands.n), dim3(kWG), 0, st, mask16, lp, tile_cnt,
+                       (uint32_t)n, P.n_tiles, P.cands, P.offs, hr);
+    LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(k_rs_cost, dim3(1), dim3(RANS_RESHAPE_MAX_CAND), 0, st, P.cands, (uint32_t)n, P.n_tiles, q_bits,
+                     tile_cnt, hv, hc, hr, P.offs, bad, d_res);
+  LAUNCH_CHECK();
+  return RANS_OK;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ C ABI
@@ -2984,6 +3267,24 @@ int rans_peek_header(const void *h_bytes, size_t n_bytes, rans_header *out) {
   int rc = header_from_bytes((const uint8_t *)h_bytes, n_bytes, out);
   if (rc) return rc;
   return validate_header(out);
+}
+
+int rans_search_workspace_bytes(uint64_t n_elems, uint32_t q_bits, size_t *ws_bytes) {
+  if (!ws_bytes || n_elems == 0 || n_elems > kMaxElems || q_bits < 1 || q_bits > 8) return RANS_ERR_ARG;
+  const RsPlan P = rs_plan(n_elems, q_bits);
+  if (P.too_many) return RANS_ERR_ARG;
+  *ws_bytes = P.total;
+  return RANS_OK;
+}
+
+int rans_search_reshape(const uint8_t *d_sym, uint64_t n_elems, uint32_t q_bits, rans_reshape_result *d_result,
+                        void *d_ws, size_t ws_bytes, void *stream) {
+  if (!d_sym || !d_result || !d_ws || n_elems == 0 || n_elems > kMaxElems || q_bits < 1 || q_bits > 8) return RANS_ERR_ARG;
+  if (!aligned_to(d_ws, 256) || !aligned_to(d_result, 8)) return RANS_ERR_ARG;
+  const RsPlan P = rs_plan(n_elems, q_bits);
+  if (P.too_many) return RANS_ERR_ARG;
+  if (ws_bytes < P.total) return RANS_ERR_WORKSPACE;
+  return launch_search_reshape(d_sym, n_elems, q_bits, d_result, (uint8_t *)d_ws, P, (hipStream_t)stream);
 }
 
 int rans_last_status(const void *d_ws, void *stream) {

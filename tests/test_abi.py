@@ -28,6 +28,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_struct_layouts_match_header():
     assert C.sizeof(B.Params) == 40 and C.sizeof(B.QInfo) == 16 and C.sizeof(B.Header) == 72
+    assert C.sizeof(B.ReshapeResult) == 32 + 16 * B.RESHAPE_MAX_CAND
 
 
 def test_workspace_bytes_and_argument_errors(lib):

@@ -1,0 +1,97 @@
+"""GPU parity of the reshape search (paper Sec. 3.2, Algorithm 1) against the CPU oracle.
+
+Bit-exact parts: the domain (every divisor N of T with N > sqrt(T), T/N <= 2^Q, in walk order), the
+chosen N and the number of reshapes the walk evaluates.  The costs l_D * H are binary64 sums of
+p log2 p on both sides (same order of the symbols); they may differ in the last bits through the two
+log2 implementations, so they are compared to 1e-11 relative, and a disagreement in the chosen N is
+accepted only if the two costs that decide it are closer than that.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_11664_amd import binding as B, synth
+
+pytestmark = pytest.mark.gpu
+REL = 1e-11
+
+
+def _check(oracle, x: np.ndarray, Q: int, tag: str):
+    print(f"[case] reshape {tag} T={x.size} Q={Q}", flush=True)
+    d = torch.from_numpy(x).cuda()
+    res = B.search_reshape(d, Q)
+    n_best, best, cands = oracle.search_reshape(x, Q)
+    T = x.size
+    nmin = max(math.isqrt(T) + 1, -(-T // (1 << Q)))
+    domain = [n for n in (T // k for k in range(1, min(1 << Q, T) + 1) if T % k == 0) if n >= nmin]
+    assert res.n_candidates == len(domain)
+    assert list(res.cand_rows[:res.n_candidates]) == domain
+    for i, n in enumerate(domain):
+        want = cands[i][1] if i < len(cands) else oracle.reshape_cost(x, n, Q)[0]
+        assert res.cand_cost[i] == pytest.approx(want, rel=REL, abs=1e-9), (tag, n)
+    if not cands:
+        assert res.rows == T and res.cols == 1 and math.isinf(res.cost_bits) and res.n_evaluated == 0
+        return
+    costs = [c for _, c in cands]
+    gaps = [abs(a - b) / max(abs(a), abs(b), 1.0) for a, b in zip(costs, costs[1:])]
+    near_tie = any(g < 10 * REL for g in gaps)
+    if not near_tie:
+        assert res.n_evaluated == len(cands)
+        assert res.rows == n_best and res.cols == T // n_best
+    assert res.rows * res.cols == T
+    assert res.cost_bits == pytest.approx(best, rel=REL, abs=1e-9)
+
+
+def _sparse(n, seed, density=0.4, levels=256):
+    rng = np.random.default_rng(seed)
+    return (rng.integers(1, levels, n) * (rng.random(n) < density)).astype(np.uint8)
+
+
+@pytest.mark.parametrize("T,Q,seed,density", [
+    (1, 8, 0, 1.0), (2, 8, 1, 0.5), (17, 8, 2, 0.5), (360, 8, 3, 0.4), (997, 8, 4, 0.4), (4096, 8, 5, 0.3),
+    (4099, 4, 6, 0.6), (5040, 8, 7, 0.5), (30030, 8, 8, 0.2), (65536, 3, 9, 0.5), (100003, 8, 10, 0.4),
+    (200704, 8, 11, 0.5), (720720, 8, 12, 0.35), (1 << 20, 2, 13, 0.5), (1 << 20, 8, 14, 0.05),
+    (3 * 5 * 7 * 11 * 13 * 16, 6, 15, 0.7),
+])
+def test_reshape_search_parity(oracle, T, Q, seed, density):
+    _check(oracle, _sparse(T, seed, density, 1 << Q), Q, f"random d={density}")
+
+
+def test_reshape_search_structured_inputs(oracle):
+    T = 8 * 4096
+    x = np.zeros(T, np.uint8)
+    x[::8] = 7
+    _check(oracle, x, 8, "planted period 8")
+    _check(oracle, np.zeros(4096, np.uint8), 8, "all zero")
+    _check(oracle, np.full(4096, 3, np.uint8), 8, "no zero at all")
+    x = np.zeros(6144, np.uint8)
+    x[5::6] = 1
+    _check(oracle, x, 2, "period 6, Q=2")
+
+
+@pytest.mark.parametrize("name,shrink", [("c1", 1), ("c2", 64), ("c3", 64)])
+def test_reshape_search_on_quantised_workloads(oracle, name, shrink):
+    w = synth.workload(name, shrink)
+    x = synth.make(w).numpy()
+    sym, _ = oracle.quantize(x, w.q_bits)
+    _check(oracle, np.asarray(sym, np.uint8), w.q_bits, f"{name}/{shrink}")
+
+
+def test_reshape_search_argument_errors():
+    d = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    rc, _ = B.rans_search_workspace_bytes(0, 8)
+    assert rc == -1
+    rc, _ = B.rans_search_workspace_bytes(64, 9)
+    assert rc == -1
+    rc, ws_bytes = B.rans_search_workspace_bytes(64, 8)
+    assert rc == 0 and ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    res = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    assert B.rans_search_reshape(d, 64, 8, res, ws[: ws_bytes // 2]) == -5
+    assert B.rans_search_reshape(d, 64, 8, res[4:], ws) == -1
+    # a symbol outside {0 .. 2^Q - 1}: the result carries no N and a NaN cost
+    d[3] = 200
+    r = B.search_reshape(d, 4)
+    assert math.isnan(r.cost_bits) and r.n_evaluated == 0

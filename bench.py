@@ -151,8 +151,10 @@ def main():
     cpu = None
     if not args.no_cpu:
         import oracle
-        # bounded sample: the first 1/16 of the tensor (same recipe, same parameters), single thread
-        ns = n // 16 // w.cols * w.cols if w.mode == synth.MODE_CSR else n // 16
+        # bounded sample: the whole tensor if it has at most 2^27 elements (about 5-10 s of single-thread work for
+        # the Llama-shaped tensors), else its first 2^27 elements (same recipe, same parameters)
+        cap = 1 << 27
+        ns = n if n <= cap else (cap // w.cols * w.cols if w.mode == synth.MODE_CSR else cap)
         xs = x_cpu[:ns].numpy()
         op = oracle.make_params(w.q_bits, w.freq_bits, ns // w.cols if w.mode == synth.MODE_CSR else ns,
                                 w.cols if w.mode == synth.MODE_CSR else 1, w.mode, w.n_streams, w.chunk_syms, w.in_dtype)

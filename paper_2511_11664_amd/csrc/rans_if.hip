@@ -2339,32 +2339,61 @@ __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const u
     return;
   }
   bool bad = false;
-  for (uint32_t j = threadIdx.x; j < cnt_here; j += kWG) {
-    const uint32_t v = D[base + j], c = D[(uint64_t)nnz + base + j];
-    uint32_t lo = 0, hi = rows;  // largest local row with roff[row] <= j (roff[rows] = cnt_here > j)
-    while (hi - lo > 1) {
-      const uint32_t mid = (lo + hi) >> 1;
-      if (roff[mid] <= j) lo = mid;
-      else hi = mid;
+  // a lane per nonzero, eight of them per step with all their loads issued first (the loads of one
+  // nonzero after the other would leave the kernel waiting on memory latency); the row of a nonzero by
+  // bisection of the local offsets
+  constexpr int kU = 8;
+  for (uint32_t j0 = 0; j0 < cnt_here; j0 += kWG * kU) {
+    uint32_t v[kU], c[kU], cp[kU];
+#pragma unroll
+    for (int u = 0; u < kU; u++) {
+      const uint32_t j = j0 + u * kWG + threadIdx.x;
+      v[u] = c[u] = cp[u] = 0;
+      if (j < cnt_here) {
+        v[u] = D[base + j];
+        c[u] = D[(uint64_t)nnz + base + j];
+        if (j) cp[u] = D[(uint64_t)nnz + base + j - 1];
+      }
     }
-    bool b = v == 0 || v >= (1u << q_bits) || c >= K;
-    if (j > roff[lo] && D[(uint64_t)nnz + base + j - 1] >= c) b = true;
-    if (b) bad = true;
-    else dense[lo * K + c] = (uint8_t)v;
+#pragma unroll
+    for (int u = 0; u < kU; u++) {
+      const uint32_t j = j0 + u * kWG + threadIdx.x;
+      if (j < cnt_here) {
+        uint32_t lo = 0, hi = rows;  // largest local row with roff[row] <= j (roff[rows] = cnt_here > j)
+        while (hi - lo > 1) {
+          const uint32_t mid = (lo + hi) >> 1;
+          if (roff[mid] <= j) lo = mid;
+          else hi = mid;
+        }
+        bool b = v[u] == 0 || v[u] >= (1u << q_bits) || c[u] >= K;
+        if (j > roff[lo] && cp[u] >= c[u]) b = true;
+        if (b) bad = true;
+        else dense[lo * K + c[u]] = (uint8_t)v[u];
+      }
+    }
   }
   if (bad) set_status(ctl, RANS_ERR_CORRUPT);
   __syncthreads();
   const float s = ctl->scale, zf = ctl->zero_point, x_min = ctl->x_min;
   OutT *o = out + (uint64_t)i0 * K;
-  for (uint32_t i = threadIdx.x; i < cells; i += kWG) {
+  auto conv = [&](uint32_t sym) -> OutT {
     if constexpr (sizeof(OutT) == 1) {
-      o[i] = dense[i];
+      return (OutT)sym;
     } else {
-      const float y = s == 0.0f ? x_min : s * ((float)dense[i] - zf);
-      if constexpr (sizeof(OutT) == 4) o[i] = y;
-      else o[i] = __float2half_rn(y);
+      const float y = s == 0.0f ? x_min : s * ((float)sym - zf);
+      if constexpr (sizeof(OutT) == 4) return y;
+      else return __float2half_rn(y);
     }
+  };
+  // four cells per lane and step when the tile starts on a 4-cell boundary of a 16-byte aligned output
+  const bool vec4 = (((uint64_t)i0 * K) & 3) == 0 && ((uintptr_t)out & 15) == 0;
+  const uint32_t cells4 = vec4 ? cells / 4 : 0;
+  for (uint32_t q = threadIdx.x; q < cells4; q += kWG) {
+    const uint32_t w = ((const uint32_t *)dense)[q];
+    struct alignas(4 * sizeof(OutT)) Quad { OutT a, b, c, d; };
+    ((Quad *)o)[q] = Quad{conv(w & 0xffu), conv((w >> 8) & 0xffu), conv((w >> 16) & 0xffu), conv(w >> 24)};
   }
+  for (uint32_t i = cells4 * 4 + threadIdx.x; i < cells; i += kWG) o[i] = conv(dense[i]);
 }
 
 // Inverse of Eq. 6 over a symbol array.
@@ -3032,6 +3061,7 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
     cells = cells < 2048 ? 2048 : (cells > kDenseTileCells ? kDenseTileCells : cells);
     uint32_t tile_rows = (uint32_t)(cells / K);
     tile_rows = tile_rows < 1 ? 1 : (tile_rows > 4096 ? 4096 : tile_rows);
+    if (tile_rows >= 4) tile_rows &= ~3u;  // then every tile starts on a 4-cell boundary (vector stores)
     const uint32_t n_tiles = (N + tile_rows - 1) / tile_rows;
     uint32_t *part = (uint32_t *)(ws + L.row_off);  // n_tiles + 1 entries (n_tiles <= N)
     PROF_LAUNCH(KID_ROW_SCAN, k_row_part, dim3(n_tiles), dim3(kWG), 0, st, D + 2 * nnz, N, K, tile_rows, part, ctl);

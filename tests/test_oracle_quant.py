@@ -73,7 +73,7 @@ def test_closed_forms_exact_arithmetic(oracle):
     sym, qi = oracle.quantize((x - 128) * 0.25, 8)
     assert qi.scale == 0.25 and qi.zero_point == 128.0
     assert np.array_equal(sym, np.arange(256))
-    # the survey's spot value: X spans [0, 2.55], Q = 8 -> s ~ 0.01, 1.0 -> 100
+    # a spot value: X spans [0, 2.55], Q = 8 -> s ~ 0.01, 1.0 -> 100
     xs = np.array([0.0, 1.0, 2.55], np.float32)
     sym, qi = oracle.quantize(xs, 8)
     assert abs(qi.scale - 0.01) < 1e-6 and list(sym) == [0, 100, 255]

@@ -561,6 +561,73 @@ struct NormArgs {
   uint8_t *out;
   uint64_t cap;
 };
+// Container header (fixed part) and the geometry the later kernels read from the control block.
+__device__ void write_header(const CtlRef &ctl, const NormArgs &na, uint64_t len_d, uint64_t n_chunks, uint64_t dir_off,
+                             uint64_t payload_off) {
+  const rans_params &p = na.p;
+  uint8_t *out = na.out;
+  ctl->n_chunks = (uint32_t)n_chunks;
+  ctl->dir_off = dir_off;
+  ctl->payload_off = payload_off;
+  st32(out + 0, 0x31464952u);  // "RIF1"
+  st32(out + 4, 1u | (p.mode << 16) | (p.in_dtype << 24));
+  st32(out + 8, p.q_bits | (p.freq_bits << 8));
+  st32(out + 12, (uint32_t)na.n_elems);    st32(out + 16, (uint32_t)(na.n_elems >> 32));
+  st32(out + 20, (uint32_t)p.rows);        st32(out + 24, (uint32_t)(p.rows >> 32));
+  st32(out + 28, (uint32_t)p.cols);        st32(out + 32, (uint32_t)(p.cols >> 32));
+  st32(out + 36, (uint32_t)len_d);         st32(out + 40, (uint32_t)(len_d >> 32));
+  st32(out + 44, na.A);
+  st32(out + 48, p.n_streams);
+  st32(out + 52, p.chunk_syms);
+  st32(out + 56, (uint32_t)n_chunks);
+  st32(out + 60, __float_as_uint(ctl->x_min));
+  st32(out + 64, __float_as_uint(ctl->x_max));
+  for (uint32_t o = 68; o < kHdrBytes; o += 4) st32(out + o, 0u);
+}
+
+// Everything stored per symbol: f in the container, the encoder's two table entries.  m_floor is
+// floor(2^32 / f) (any value for f <= 1), div(two) returns floor(two / f) for two = 2^(32+k).  Returns
+// whether the division-free entry is inexact.
+//
+// Division-free entry {lim1, mx, Fx | sh << 16, 2^M - f}: the coder renormalises when s > lim1 and
+// then takes q = mulhi(s, mx) >> sh for floor(s / f) in Eq. 2.  At that point s <= lim1 =
+// f * 2^(32-M) - 1.  With 2^k <= f < 2^(k+1), mx = floor(2^(32+k) / f) + 1 and e = mx * f - 2^(32+k),
+// q is exact for every s with s * e < 2^(32+k); the entry is marked inexact otherwise (possible only
+// for f > 2^(M-1)).  Powers of two take mx = 2^31, sh = k - 1.  f = 1 cannot have its multiplier
+// 2^32: it takes mx = 2^32 - 1, which gives q = s - 1 (s >= 1 there), and the missing 2^M - f is
+// added to Fx instead.  f = 0 (absent symbol) is never looked up.
+template <class Div>
+__device__ __forceinline__ int emit_entries(const NormArgs &na, uint32_t a, uint32_t f, uint32_t F, uint32_t m_floor,
+                                            Div div) {
+  const uint32_t M = na.p.freq_bits, total = 1u << M;
+  int inexact = 0;
+  // floor(2^32 / f) for f >= 2, 2^32 - 1 for f = 1: with it mulhi(s, m) is floor(s / f) or one less
+  const uint32_t m = f <= 1 ? 0xffffffffu : m_floor;
+  na.enc_tab[a] = make_uint2(m, f | (F << 16));
+  *(uint16_t *)(na.out + kHdrBytes + 2ull * a) = (uint16_t)f;
+  const uint32_t cmpl = total - f;
+  uint32_t lim1 = (f << (32 - M)) - 1u, mx = 0, sh = 0, Fx = F;
+  if (f == 1) {
+    mx = 0xffffffffu;
+    Fx = F + cmpl;
+  } else if (f > 1) {
+    const uint32_t k = 31u - (uint32_t)__clz((int)f);
+    if ((f & (f - 1)) == 0) {
+      mx = 0x80000000u;
+      sh = k - 1;
+    } else {
+      const uint64_t two = 1ull << (32 + k);
+      const uint64_t mq = div(two) + 1;  // < 2^32 because f > 2^k
+      const uint64_t e = mq * f - two;
+      if ((uint64_t)lim1 * e >= two) inexact = 1;
+      mx = (uint32_t)mq;
+      sh = k;
+    }
+  }
+  na.enc_tab4[a] = make_uint4(lim1, mx, Fx | (sh << 16), cmpl);
+  return inexact;
+}
+
 __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
   const uint32_t *cnt = na.cnt;
   uint32_t *fq = na.fq;
@@ -642,25 +709,7 @@ __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
     if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CAPACITY);
     return;
   }
-  if (threadIdx.x == 0) {
-    ctl->n_chunks = (uint32_t)n_chunks;
-    ctl->dir_off = dir_off;
-    ctl->payload_off = payload_off;
-    st32(out + 0, 0x31464952u);  // "RIF1"
-    st32(out + 4, 1u | (p.mode << 16) | (p.in_dtype << 24));
-    st32(out + 8, p.q_bits | (M << 8));
-    st32(out + 12, (uint32_t)n_elems);       st32(out + 16, (uint32_t)(n_elems >> 32));
-    st32(out + 20, (uint32_t)p.rows);        st32(out + 24, (uint32_t)(p.rows >> 32));
-    st32(out + 28, (uint32_t)p.cols);        st32(out + 32, (uint32_t)(p.cols >> 32));
-    st32(out + 36, (uint32_t)len_d);         st32(out + 40, (uint32_t)(len_d >> 32));
-    st32(out + 44, A);
-    st32(out + 48, p.n_streams);
-    st32(out + 52, p.chunk_syms);
-    st32(out + 56, (uint32_t)n_chunks);
-    st32(out + 60, __float_as_uint(ctl->x_min));
-    st32(out + 64, __float_as_uint(ctl->x_max));
-    for (uint32_t o = 68; o < kHdrBytes; o += 4) st32(out + o, 0u);
-  }
+  if (threadIdx.x == 0) write_header(ctl, na, len_d, n_chunks, dir_off, payload_off);
   // cumulative sum, encoder table, stored table
   uint32_t carry = 0;
   int inexact = 0;
@@ -669,37 +718,7 @@ __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
     uint32_t f = a < A ? fq[a] : 0, tot;
     uint32_t F = carry + block_excl_scan<kBig>(f, sh32, &tot);
     if (a < A) {
-      // floor(2^32 / f) for f >= 2, 2^32 - 1 for f = 1: with it mulhi(s, m) is floor(s / f) or one less
-      uint32_t m = f <= 1 ? 0xffffffffu : (uint32_t)(0x100000000ull / f);
-      enc_tab[a] = make_uint2(m, f | (F << 16));
-      *(uint16_t *)(out + table_off + 2ull * a) = (uint16_t)f;
-      // Division-free entry {lim1, mx, Fx | sh << 16, 2^M - f}: the coder renormalises when s > lim1 and
-      // then takes q = mulhi(s, mx) >> sh for floor(s / f) in Eq. 2.  At that point s <= lim1 =
-      // f * 2^(32-M) - 1.  With 2^k <= f < 2^(k+1), mx = floor(2^(32+k) / f) + 1 and e = mx * f - 2^(32+k),
-      // q is exact for every s with s * e < 2^(32+k); the entry is marked inexact otherwise (possible only
-      // for f > 2^(M-1)).  Powers of two take mx = 2^31, sh = k - 1.  f = 1 cannot have its multiplier
-      // 2^32: it takes mx = 2^32 - 1, which gives q = s - 1 (s >= 1 there), and the missing 2^M - f is
-      // added to Fx instead.  f = 0 (absent symbol) is never looked up.
-      const uint32_t cmpl = total - f;
-      uint32_t lim1 = (f << (32 - M)) - 1u, mx = 0, sh = 0, Fx = F;
-      if (f == 1) {
-        mx = 0xffffffffu;
-        Fx = F + cmpl;
-      } else if (f > 1) {
-        const uint32_t k = 31u - (uint32_t)__clz((int)f);
-        if ((f & (f - 1)) == 0) {
-          mx = 0x80000000u;
-          sh = k - 1;
-        } else {
-          const uint64_t two = 1ull << (32 + k);
-          const uint64_t mq = two / f + 1;  // < 2^32 because f > 2^k
-          const uint64_t e = mq * f - two;
-          if ((uint64_t)lim1 * e >= two) inexact = 1;
-          mx = (uint32_t)mq;
-          sh = k;
-        }
-      }
-      enc_tab4[a] = make_uint4(lim1, mx, Fx | (sh << 16), cmpl);
+      inexact |= emit_entries(na, a, f, F, (uint32_t)(0x100000000ull / (f ? f : 1)), [&](uint64_t two) { return two / f; });
     }
     carry += tot;
     __syncthreads();
@@ -709,7 +728,119 @@ __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
   for (uint64_t o = table_off + 2ull * A + 2 * threadIdx.x; o < dir_off; o += 2 * kBig) *(uint16_t *)(out + o) = 0;
 }
 
-__global__ __launch_bounds__(kBig) void k_normalize(CtlRef ctl, NormArgs na) { normalize_body(ctl, na); }
+// floor(a / b) for 0 <= a < 2^52, 1 <= b < 2^32 through one binary64 division instead of the much
+// longer 64-bit integer division.  Both operands are exact in binary64.  If b divides a the division is
+// exact.  Otherwise a / b lies at least 1 / b away from the integers next to it, and the correctly
+// rounded quotient differs from a / b by at most (a / b) * 2^-53 < 1 / b (because a < 2^53), so it
+// stays strictly between the same two integers and its floor is the floor of a / b.
+__device__ __forceinline__ uint64_t floor_div_f64(uint64_t a, uint32_t b) {
+  return (uint64_t)((double)a / (double)b);
+}
+
+// The same as normalize_body for alphabets of up to 256 symbols, by ONE wave without a barrier: lane l
+// owns the symbols 4 l .. 4 l + 3, sums and maxima are wave scans.  Called by the first wave of a
+// work-group; the single work-group version spends most of its time in barriers between 16 waves.
+constexpr uint32_t kNormWaveA = 256;
+__device__ void normalize_wave(const CtlRef &ctl, const NormArgs &na) {
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t A = na.A;
+  const rans_params &p = na.p;
+  const uint32_t M = p.freq_bits, total = 1u << M;
+  if (get_status(ctl) != 0) return;  // uniform: written by an earlier kernel
+  auto total64 = [](uint64_t v) { return lane63_64(wave_incl_scan64(v, [](uint64_t a, uint64_t b) { return a + b; })); };
+  auto max64 = [](uint64_t v) { return lane63_64(wave_incl_scan64(v, [](uint64_t a, uint64_t b) { return a > b ? a : b; })); };
+  uint32_t c[4];
+#pragma unroll
+  for (int q = 0; q < 4; q++) {
+    const uint32_t a = 4 * lane + q;
+    c[q] = a < A ? __hip_atomic_load(na.cnt + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+  }
+  uint64_t lp = 0;  // l_D in the low 40 bits, the number of present symbols above
+#pragma unroll
+  for (int q = 0; q < 4; q++) lp += (uint64_t)c[q] + ((uint64_t)(c[q] != 0) << 40);
+  lp = total64(lp);
+  const uint64_t len = lp & ((1ull << 40) - 1), present = lp >> 40;
+  if (na.dense && lane == 0) ctl->len_d = len;
+  const uint64_t len_d = na.dense ? len : ctl->len_d;
+  if (present > total || len != len_d) {  // the second cannot happen; kept as a guard
+    if (lane == 0) set_status(ctl, RANS_ERR_ALPHABET);
+    return;
+  }
+  // first estimate, its sum, the symbol with the largest count
+  uint32_t f[4];
+  uint64_t sum = 0, best = 0;
+#pragma unroll
+  for (int q = 0; q < 4; q++) {
+    f[q] = 0;
+    if (c[q]) {
+      const uint64_t e = floor_div_f64((uint64_t)c[q] * total + len / 2, (uint32_t)len);  // < 2^46 over < 2^32
+      f[q] = e < 1 ? 1u : (uint32_t)e;
+      const uint64_t key = ((uint64_t)c[q] << 32) | (0xffffffffu - (4 * lane + q));  // max count, lowest index
+      best = key > best ? key : best;
+    }
+    sum += f[q];
+  }
+  sum = total64(sum);
+  best = max64(best);
+  int64_t d = (int64_t)total - (int64_t)sum;
+  auto adjust = [&](uint32_t a_star, int64_t by) {  // f[a_star] += by, in the lane that owns it
+#pragma unroll
+    for (int q = 0; q < 4; q++)
+      if (4 * lane + q == a_star) f[q] = (uint32_t)((int64_t)f[q] + by);
+  };
+  if (len && d > 0) {
+    adjust(0xffffffffu - (uint32_t)best, d);
+    d = 0;
+  }
+  while (d < 0) {  // uniform: d is identical in every lane
+    uint64_t kb = 0;
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+      const uint64_t key = ((uint64_t)f[q] << 32) | (0xffffffffu - (4 * lane + q));
+      kb = 4 * lane + q < A && key > kb ? key : kb;
+    }
+    kb = max64(kb);
+    int64_t take = (int64_t)(kb >> 32) - 1;
+    if (take > -d) take = -d;
+    adjust(0xffffffffu - (uint32_t)kb, -take);
+    d += take;
+  }
+  // container geometry
+  const uint64_t n_chunks = len_d == 0 ? 0 : (p.chunk_syms == 0 ? 1 : (len_d + p.chunk_syms - 1) / p.chunk_syms);
+  const uint64_t table_off = kHdrBytes;
+  const uint64_t dir_off = table_off + (((uint64_t)A * 2 + 7) & ~7ull);
+  const uint64_t payload_off = dir_off + 8 * (n_chunks + 1);
+  if (payload_off > na.cap) {
+    if (lane == 0) set_status(ctl, RANS_ERR_CAPACITY);
+    return;
+  }
+  if (lane == 0) write_header(ctl, na, len_d, n_chunks, dir_off, payload_off);
+  // cumulative sum, encoder tables, stored table
+  const uint32_t mine = f[0] + f[1] + f[2] + f[3];
+  uint32_t F = wave_incl_sum_scan(mine) - mine;
+  int inexact = 0;
+#pragma unroll
+  for (int q = 0; q < 4; q++) {
+    const uint32_t a = 4 * lane + q;
+    if (a < A) {
+      const uint32_t fa = f[q];
+      inexact |= emit_entries(na, a, fa, F, (uint32_t)floor_div_f64(0x100000000ull, fa ? fa : 1),
+                              [&](uint64_t two) { return floor_div_f64(two, fa); });  // two <= 2^46, fa < 2^16
+    }
+    F += f[q];
+  }
+  const bool any_inexact = __ballot(inexact) != 0;
+  if (lane == 0) ctl->enc_exact = any_inexact ? 0u : 1u;
+  for (uint64_t o = table_off + 2ull * A + 2 * lane; o < dir_off; o += 2 * 64) *(uint16_t *)(na.out + o) = 0;
+}
+
+__global__ __launch_bounds__(kBig) void k_normalize(CtlRef ctl, NormArgs na) {
+  if (na.A <= kNormWaveA) {
+    if (threadIdx.x < 64) normalize_wave(ctl, na);
+  } else {
+    normalize_body(ctl, na);
+  }
+}
 
 // Quantise a tile and histogram its symbols.  T = float / __half: Eq. 6 per
 // element, symbols written packed; T = uint8_t: symbols are the input (histogram
@@ -829,7 +960,11 @@ __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRe
   if (threadIdx.x == 0) s_ticket = __hip_atomic_fetch_add(&ctl->hist_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
   if (s_ticket != gridDim.x - 1) return;
-  if constexpr (NT == kBig) normalize_body(ctl, na);
+  if (na.A <= kNormWaveA) {
+    if (threadIdx.x < 64) normalize_wave(ctl, na);
+  } else if constexpr (NT == kBig) {
+    normalize_body(ctl, na);
+  }
 }
 
 // ------------------------------------------------------------------ kernels: modified CSR

@@ -1153,8 +1153,9 @@ struct EncEntry {
 };
 
 // Table modes: 0 = {m, f | F << 16} read from global memory (very large alphabets),
-// 1 = the same staged in LDS, 2 = unpacked {m, f, F, 2^M - f} staged in LDS (small
-// alphabets: one 16-byte LDS read, no unpacking arithmetic).
+// 1 = the same staged in LDS, 2 = 16-byte entries staged in LDS (small alphabets: one LDS read, no
+// unpacking arithmetic): the division-free form {lim1, mx, Fx | sh << 16, 2^M - f} when every entry of it
+// is exact, else {m, f, F, 2^M - f}.
 template <int TAB>
 __device__ __forceinline__ EncEntry load_entry(const uint2 *g_tab, const uint32_t *l_tab, uint32_t x, uint32_t totalM) {
   EncEntry e;
@@ -1168,22 +1169,23 @@ __device__ __forceinline__ EncEntry load_entry(const uint2 *g_tab, const uint32_
   return e;
 }
 
-// Interleaved rANS encoder (Eq. 2 with 16-bit renormalisation).
+// Interleaved rANS encoder (Eq. 2 with 16-bit renormalisation).  One work-group codes kWG * SPL
+// streams of one chunk (only SPL = 1 is instantiated: the hardware interleaves waves better than the
+// compiler interleaves several streams inside a lane).
 //
-// Each lane runs SPL adjacent streams: SPL independent dependency chains for the
-// scheduler, and one load fetches a row of SPL symbols.  Symbols are taken last to
-// first, kEncAhead rows fetched ahead, table entries looked up one row ahead.  The
-// per-row arithmetic is branch-free (selects only) so that it stays one basic block.
+// Symbols are taken last to first in batches of kEncAhead rows, fetched a batch ahead (dense source:
+// through a per-wave LDS stage filled with 16-byte loads a whole tile ahead), table entries looked up
+// three rows ahead.  The per-row arithmetic is branch-free (selects only) so that it stays one basic
+// block.  floor(s / f) of Eq. 2 is a multiply-high and a shift with the per-symbol multiplier that
+// k_normalize proved exact (table form 2, when every entry is exact), else a multiply-high with
+// floor(2^32 / f) plus one correction step.
 //
-// Emitted words go to a 16-word ring per stream in LDS, laid out [position][stream]
-// so that lanes hit distinct banks.  The low half of the state is written to the
-// ring slot of the next word on every step and the word count advances only when
-// the renormalisation fires, so a slot keeps rewriting until it is really used.
-// After every kEncAhead rows (a wave-uniform point) a stream with 8 or more staged
-// words moves one 16-byte block to its scratch region in global memory, downwards
-// from the region's end, which leaves the words in the order the decoder reads them.
-//
-// floor(s / f) comes from a multiply-high with floor(2^32 / f) plus one correction.
+// Emitted words wait in a 16-slot LDS area per stream, filled from the top: the low half of the state
+// is written to the next slot on every step and the slot pointer moves only when the renormalisation
+// fires, so a slot keeps being rewritten until it is really used.  After every kEncAhead rows (a
+// wave-uniform point) a stream with 8 or more waiting words moves its 8 oldest as one 16-byte block to
+// scratch in global memory (block-major per work-group: lanes that flush the same block number write
+// adjacent memory); inside a block ascending address = descending word number, the decoder's order.
 //
 // FUSE: the work-group also moves its streams' words to their place in the container (what k_gather
 // does otherwise).  It publishes its word total, waits until every work-group with a lower index has

@@ -117,6 +117,17 @@ def main():
     enc_p50, enc_p10, enc_p90 = p50_us(lambda: B.rans_compress(x, n, p, codec.stream, codec.nbytes, codec.ws), reps)
     dec_p50, dec_p10, dec_p90 = p50_us(lambda: B.rans_decompress(codec.stream, nbytes, hdr, w.in_dtype, out, codec.ws), reps)
 
+    # the four unfused entry points, for the record (symbols through a caller-side buffer)
+    sym = torch.empty(n, dtype=torch.uint8, device=dev)
+    unf = {}
+    for name, fn in (("rans_quantize", lambda: B.rans_quantize(x, n, p, sym, codec.qinfo, codec.ws)),
+                     ("rans_encode", lambda: B.rans_encode(sym, n, p, codec.qinfo, codec.stream, codec.nbytes, codec.ws)),
+                     ("rans_decode", lambda: B.rans_decode(codec.stream, nbytes, hdr, sym, codec.qinfo, codec.ws)),
+                     ("rans_dequantize", lambda: B.rans_dequantize(sym, n, codec.qinfo, w.in_dtype, out))):
+        fn()
+        unf[name] = round(p50_us(fn, 20)[0], 1)
+    assert B.rans_last_status(codec.ws) == 0
+
     in_bytes = n * e
     # algorithmic bytes: three forced passes on the encode side (min/max reads X; quantise reads X and
     # writes xhat; the coder reads xhat and writes the container), one on the decode side.
@@ -187,6 +198,7 @@ def main():
         "decode": {"p50_us": round(dec_p50, 1), "p10_us": round(dec_p10, 1), "p90_us": round(dec_p90, 1),
                    "GBps_output": round(in_bytes / dec_p50 / 1e3, 1), "GBps_fp32_equiv": round(4 * n / dec_p50 / 1e3, 1),
                    "algorithmic_bytes": b_dec, "roofline_frac": round(b_dec / (dec_p50 * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)},
+        "unfused_p50_us": unf,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

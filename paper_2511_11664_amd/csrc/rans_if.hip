@@ -2533,18 +2533,33 @@ __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const u
   for (uint32_t i = cells4 * 4 + threadIdx.x; i < cells; i += kWG) o[i] = conv(dense[i]);
 }
 
-// Inverse of Eq. 6 over a symbol array.
-template <typename OutT>
+// Inverse of Eq. 6 over a symbol array.  VEC: sixteen symbols per lane and step (both arrays 16-byte
+// aligned); the tail and unaligned arrays go one symbol at a time.
+template <typename OutT, bool VEC>
 __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *sym, uint64_t n, const rans_qinfo *qi, CtlRef ctl,
                                                  OutT *out) {
   if (ctl && get_status(ctl) != 0) return;
   const float s = qi->scale, zf = qi->zero_point, x_min = qi->x_min;
-  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (uint64_t)gridDim.x * blockDim.x;
-  for (; i < n; i += stride) {
-    float y = s == 0.0f ? x_min : s * ((float)sym[i] - zf);
-    if constexpr (sizeof(OutT) == 4) out[i] = y;
-    else out[i] = __float2half_rn(y);
+  auto conv = [&](uint32_t a) -> OutT {
+    const float y = s == 0.0f ? x_min : s * ((float)a - zf);
+    if constexpr (sizeof(OutT) == 4) return y;
+    else return __float2half_rn(y);
+  };
+  const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (uint64_t)gridDim.x * blockDim.x;
+  uint64_t done = 0;
+  if constexpr (VEC) {
+    struct alignas(4 * sizeof(OutT)) Quad { OutT a, b, c, d; };
+    const uint64_t nv = n / 16;
+    for (uint64_t i = tid; i < nv; i += stride) {
+      const uint4 w = ((const uint4 *)sym)[i];
+      const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+      for (int k = 0; k < 4; k++)
+        ((Quad *)out)[4 * i + k] = Quad{conv(ww[k] & 0xffu), conv((ww[k] >> 8) & 0xffu), conv((ww[k] >> 16) & 0xffu), conv(ww[k] >> 24)};
+    }
+    done = nv * 16;
   }
+  for (uint64_t i = done + tid; i < n; i += stride) out[i] = conv(sym[i]);
 }
 
 // ------------------------------------------------------------------ kernels: reshape search (Sec. 3.2)
@@ -3421,11 +3436,16 @@ int rans_dequantize(const uint8_t *d_sym, uint64_t n_elems, const rans_qinfo *d_
   if (!aligned_to(d_x_out, out_dtype == RANS_F16 ? 2 : 4) || !aligned_to(d_qinfo, 4)) return RANS_ERR_ARG;
   if (!n_elems) return RANS_OK;
   hipStream_t st = (hipStream_t)stream;
-  uint32_t g = grid_for(n_elems, kWG * 8, 8192);
-  if (out_dtype == RANS_F32)
-    PROF_LAUNCH(KID_DEQUANT, (k_dequant<float>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, CtlRef{nullptr, 0}, (float *)d_x_out);
-  else
-    PROF_LAUNCH(KID_DEQUANT, (k_dequant<__half>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, CtlRef{nullptr, 0}, (__half *)d_x_out);
+  const bool vec = aligned_to(d_sym, 16) && aligned_to(d_x_out, 16);
+  const uint32_t g = grid_for(n_elems, kWG * 16, 8192);
+  const CtlRef no_ctl{nullptr, 0};
+  if (out_dtype == RANS_F32) {
+    if (vec) PROF_LAUNCH(KID_DEQUANT, (k_dequant<float, true>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, no_ctl, (float *)d_x_out);
+    else PROF_LAUNCH(KID_DEQUANT, (k_dequant<float, false>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, no_ctl, (float *)d_x_out);
+  } else {
+    if (vec) PROF_LAUNCH(KID_DEQUANT, (k_dequant<__half, true>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, no_ctl, (__half *)d_x_out);
+    else PROF_LAUNCH(KID_DEQUANT, (k_dequant<__half, false>), dim3(g), dim3(kWG), 0, st, d_sym, n_elems, d_qinfo, no_ctl, (__half *)d_x_out);
+  }
   LAUNCH_CHECK();
   return RANS_OK;
 }

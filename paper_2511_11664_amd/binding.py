@@ -308,3 +308,23 @@ class Codec:
 
     def container(self, nbytes: int) -> bytes:
         return bytes(self.stream[:nbytes].cpu().numpy())
+
+
+def compress_with_search(x: torch.Tensor, q_bits: int, freq_bits: int, n_streams: int, chunk_syms: int):
+    """The paper's whole edge side (Fig. 1(c) with the reshape of Algorithm 1): quantise, search the reshape
+    N~ on the quantised symbols, then code D = v (+) c (+) r for [N~, T / N~].  The search result has to come
+    back to the host, because rows and cols are host-side parameters of the encoder.
+    Returns (container bytes as a device tensor view, Params used, ReshapeResult)."""
+    n = x.numel()
+    in_dtype = F16 if x.dtype == torch.float16 else F32
+    # any valid reshape serves for the quantise step (Eq. 6 does not depend on it)
+    pq = make_params(q_bits, freq_bits, n, 1, MODE_DENSE, n_streams, chunk_syms, in_dtype)
+    cq = Codec(pq, n, x.device)
+    sym = torch.empty(n, dtype=torch.uint8, device=x.device)
+    cq.quantize(x.reshape(-1), sym)
+    res = search_reshape(sym, q_bits)
+    p = make_params(q_bits, freq_bits, res.rows, res.cols, MODE_CSR, n_streams, chunk_syms, in_dtype)
+    ce = Codec(p, n, x.device)
+    ce.qinfo.copy_(cq.qinfo)
+    nbytes = ce.encode(sym)
+    return ce.stream[:nbytes], p, res

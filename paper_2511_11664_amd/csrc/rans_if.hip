@@ -2687,56 +2687,68 @@ __global__ __launch_bounds__(kWG) void k_rs_rows(const uint16_t *mask16, const u
   }
 }
 
-// Costs and the walk of Algorithm 1.  One thread per candidate sums its entropy (symbols in ascending
-// order, binary64); thread 0 then walks the candidates from the largest N down.
-__global__ __launch_bounds__(RANS_RESHAPE_MAX_CAND) void k_rs_cost(RsCands cands, uint32_t n, uint32_t n_tiles,
-                                                                    uint32_t q_bits, const uint32_t *tile_off,
-                                                                    const uint32_t *hv, const uint32_t *hc,
-                                                                    const uint32_t *hr, RsOffsets offs,
-                                                                    const uint32_t *bad_flag,
-                                                                    rans_reshape_result *res) {
-  __shared__ double s_cost[RANS_RESHAPE_MAX_CAND];
+// Costs and the walk of Algorithm 1.  One work-group per candidate sums its entropy terms in binary64
+// (a fixed tree: lanes, then waves); the work-group that finishes last walks the candidates from the
+// largest N down.  costs[] and the ticket live in the zeroed part of the workspace.
+__global__ __launch_bounds__(kWG) void k_rs_cost(RsCands cands, uint32_t n, uint32_t n_tiles, uint32_t q_bits,
+                                                 const uint32_t *tile_off, const uint32_t *hv, const uint32_t *hc,
+                                                 const uint32_t *hr, RsOffsets offs, const uint32_t *bad_flag,
+                                                 double *costs, uint32_t *ticket, rans_reshape_result *res) {
+  __shared__ double s_part[kWG / 64];
+  __shared__ uint32_t s_ticket;
   const uint32_t *hc_off = offs.hc, *hr_off = offs.hr;
-  const uint32_t k = threadIdx.x;
+  const uint32_t k = blockIdx.x;
   const uint32_t nnz = tile_off[n_tiles];
-  if (k < cands.n) {
+  {
     const uint32_t K = cands.K[k], N = n / K;
     const uint32_t two_q = 1u << q_bits;
     const uint32_t A = K + 1 > two_q ? K + 1 : two_q;
     const uint64_t len = 2ull * nnz + N;
-    double H = 0.0;
-    for (uint32_t a = 0; a < A; a++) {
+    double h = 0.0;
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) {
       uint64_t c = 0;
       if (a < two_q) c += hv[a];
       if (a < K) c += hc[hc_off[k] + a];
       if (a <= K) c += hr[hr_off[k] + a];
       if (c) {
         const double p = (double)c / (double)len;
-        H -= p * log2(p);
+        h -= p * log2(p);
       }
     }
-    s_cost[k] = (double)len * H;
+    const uint64_t bits = wave_incl_scan64((uint64_t)__double_as_longlong(h), [](uint64_t x, uint64_t y) {
+      return (uint64_t)__double_as_longlong(__longlong_as_double((long long)x) + __longlong_as_double((long long)y));
+    });
+    if ((threadIdx.x & 63) == 63) s_part[threadIdx.x >> 6] = __longlong_as_double((long long)bits);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double H = 0.0;
+      for (int w = 0; w < kWG / 64; w++) H += s_part[w];
+      // device-scope store, then the ticket: the last work-group reads every cost with device-scope loads
+      __hip_atomic_store(costs + k, (double)len * H, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_ticket = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
   }
-  __syncthreads();
-  if (threadIdx.x != 0) return;
+  if (s_ticket != gridDim.x - 1 || threadIdx.x != 0) return;
+  __atomic_thread_fence(__ATOMIC_ACQUIRE);
   double best = INFINITY, prev = INFINITY;
   uint64_t n_tilde = n;
   uint32_t evaluated = 0;
+  bool walking = true;
   for (uint32_t i = 0; i < cands.n; i++) {
-    const double cost = s_cost[i];
+    const double cost = __hip_atomic_load(costs + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     res->cand_rows[i] = n / cands.K[i];
     res->cand_cost[i] = cost;
-    if (evaluated == i) {  // the walk is still going
+    if (walking) {
       evaluated++;
       if (cost < best) {
         best = cost;
         n_tilde = n / cands.K[i];
       }
-      if (cost > prev) evaluated |= 0x80000000u;  // stop after this one
+      if (cost > prev) walking = false;  // stop after this one
       prev = cost;
     }
   }
-  evaluated &= 0x7fffffffu;
   if (*bad_flag) {  // a symbol outside {0 .. 2^Q - 1}: no meaningful result
     best = __longlong_as_double(0x7ff8000000000000ll);
     n_tilde = n;
@@ -2747,6 +2759,15 @@ __global__ __launch_bounds__(RANS_RESHAPE_MAX_CAND) void k_rs_cost(RsCands cands
   res->cost_bits = best;
   res->n_evaluated = evaluated;
   res->n_candidates = cands.n;
+}
+
+// an empty domain: rows = T, cols = 1, cost +inf
+__global__ void k_rs_empty(uint32_t n, const uint32_t *bad_flag, rans_reshape_result *res) {
+  res->rows = n;
+  res->cols = 1;
+  res->cost_bits = *bad_flag ? __longlong_as_double(0x7ff8000000000000ll) : INFINITY;
+  res->n_evaluated = 0;
+  res->n_candidates = 0;
 }
 
 // ------------------------------------------------------------------ instrumentation
@@ -3248,7 +3269,7 @@ struct RsPlan {
   RsCands cands;
   RsOffsets offs;
   uint32_t n_entries, n_tiles;
-  size_t mask16, lp, tile_cnt, zero0, hv, hc, hr, bad, total;  // byte offsets in the workspace
+  size_t mask16, lp, tile_cnt, zero0, hv, hc, hr, bad, costs, ticket, total;  // byte offsets in the workspace
   uint32_t zero_words;
   bool too_many;
 };
@@ -3300,6 +3321,8 @@ RsPlan rs_plan(uint64_t n, uint32_t q_bits) {
   P.hc = take((size_t)oc * 4 + 4);
   P.hr = take((size_t)orr * 4 + 4);
   P.bad = take(4);
+  P.costs = take(RANS_RESHAPE_MAX_CAND * 8);
+  P.ticket = take(4);
   P.zero_words = (uint32_t)((o - P.zero0) / 4);
   P.total = o;
   return P;
@@ -3331,8 +3354,11 @@ int launch_search_reshape(const uint8_t *d_sym, uint64_t n, uint32_t q_bits, ran
                        (uint32_t)n, P.n_tiles, P.cands, P.offs, hr);
     LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(k_rs_cost, dim3(1), dim3(RANS_RESHAPE_MAX_CAND), 0, st, P.cands, (uint32_t)n, P.n_tiles, q_bits,
-                     tile_cnt, hv, hc, hr, P.offs, bad, d_res);
+  if (P.cands.n)
+    hipLaunchKernelGGL(k_rs_cost, dim3(P.cands.n), dim3(kWG), 0, st, P.cands, (uint32_t)n, P.n_tiles, q_bits, tile_cnt, hv, hc,
+                       hr, P.offs, bad, (double *)(ws + P.costs), (uint32_t *)(ws + P.ticket), d_res);
+  else
+    hipLaunchKernelGGL(k_rs_empty, dim3(1), dim3(1), 0, st, (uint32_t)n, bad, d_res);
   LAUNCH_CHECK();
   return RANS_OK;
 }

@@ -99,6 +99,8 @@ def _c5(shape, g):
 _RECIPES = {
     # name: (full shape, dtype, seed, fn, Q, M, S, chunk_syms, mode, cols)
     "c1": ((1, 64, 56, 56), torch.float32, 0, _c1, 8, 12, 32, 0, MODE_DENSE, 3136),
+    # the shape of the features in the paper's Table 1 (128 x 28 x 28 fp32, 401 408 bytes), post-ReLU
+    "t1": ((1, 128, 28, 28), torch.float32, 6, _c1, 8, 12, 64, 64 * 64, MODE_DENSE, 784),
     "c2": ((32, 256, 56, 56), torch.float32, 1, _c2, 8, 12, 1024, 1 << 18, MODE_DENSE, 256),
     "c3": ((64, 512, 28, 28), torch.float32, 2, _c3, 8, 14, 1024, 1 << 18, MODE_DENSE, 256),
     "c4": ((16, 3136, 96), torch.float32, 3, _c4, 8, 12, 1024, 1 << 18, MODE_DENSE, 96),
@@ -115,6 +117,8 @@ def workload(name: str, shrink: int = 1, **over) -> Workload:
     shape = (max(1, shape[0] // shrink),) + tuple(shape[1:])
     if name == "c1" and shrink > 1:
         shape = (1, max(1, 64 // shrink), 56, 56)
+    if name == "t1" and shrink > 1:
+        shape = (1, max(1, 128 // shrink), 28, 28)
     w = Workload(name=name, shape=shape, dtype=dtype, seed=seed, q_bits=q, freq_bits=m, n_streams=s,
                  chunk_syms=cs, mode=mode, cols=cols)
     for k, v in over.items():

@@ -95,3 +95,26 @@ def test_reshape_search_argument_errors():
     d[3] = 200
     r = B.search_reshape(d, 4)
     assert math.isnan(r.cost_bits) and r.n_evaluated == 0
+
+
+@pytest.mark.parametrize("name,shrink,Q", [("t1", 1, 8), ("t1", 1, 4), ("t1", 1, 2), ("c1", 1, 6), ("c3", 128, 8)])
+def test_quantise_search_encode_pipeline_matches_the_oracle(oracle, name, shrink, Q):
+    # Fig. 1(c) with the reshape chosen by Algorithm 1: the container must be the oracle's for the oracle's N~
+    w = synth.workload(name, shrink, q_bits=Q)
+    x = synth.make(w)
+    print(f"[case] pipeline {name}/{shrink} Q={Q} T={w.numel}", flush=True)
+    stream, p, res = B.compress_with_search(x.cuda(), Q, w.freq_bits, w.n_streams, w.chunk_syms)
+    sym, _ = oracle.quantize(x.numpy(), Q)
+    n_best, best, cands = oracle.search_reshape(np.asarray(sym, np.uint8), Q)
+    assert res.rows == n_best and res.n_evaluated == len(cands)
+    op = oracle.make_params(Q, w.freq_bits, n_best, w.numel // n_best, synth.MODE_CSR, w.n_streams, w.chunk_syms, w.in_dtype)
+    want, _ = oracle.compress(x.numpy(), op)
+    got = bytes(stream.cpu().numpy())
+    assert got == bytes(want)
+    # and it decodes back to the same symbols
+    codec = B.Codec(p, w.numel)
+    codec.stream[:len(got)].copy_(stream)
+    hdr = codec.header(len(got))
+    out = torch.empty(w.numel, dtype=torch.uint8, device="cuda")
+    codec.decode(len(got), hdr, out)
+    assert np.array_equal(out.cpu().numpy(), np.asarray(sym, np.uint8))

@@ -69,7 +69,7 @@ struct Layout {
   // common
   size_t ctl;
   // encode side
-  size_t mm_part, cnt, fq, enc_tab, enc_tab4, sym, v, c, r, row_end, blk_nnz, st, nw, chunk_words, scratch;
+  size_t mm_part, cnt, fq, enc_tab, enc_tab4, sym, v, c, r, row_end, st, nw, chunk_words, scratch;
   // decode side (overlays the encode side from `sym` on)
   size_t dec_lut, dec_tab, dec_F, D, row_off;
   size_t total;
@@ -137,7 +137,6 @@ Layout make_layout(const rans_params &p, uint64_t n) {
     L.c = take(n * 2);
     L.r = take(p.rows * 2);
     L.row_end = take(p.rows * 4);
-    L.blk_nnz = take(((size_t)L.n_blk + 1) * 4);
   }
   size_t n_sc = (size_t)L.nc_max * p.n_streams;
   L.st = take(n_sc * 4);
@@ -146,7 +145,9 @@ Layout make_layout(const rans_params &p, uint64_t n) {
     const uint64_t wgs = (uint64_t)L.nc_max * ((p.n_streams + kWG - 1) / kWG);
     L.n_pub = (wgs > 0 && wgs <= kFusedGatherMax) ? (uint32_t)wgs : 0;
   }
-  L.chunk_words = take(((size_t)L.nc_max + 1 + L.n_pub) * 4);  // per-chunk word counts, then the encoder's published totals
+  if (p.mode != RANS_MODE_CSR) L.n_blk = 0;
+  // per-chunk word counts, the encoder's published totals, the nonzeros per CSR tile: all zeroed when a call starts
+  L.chunk_words = take(((size_t)L.nc_max + 1 + L.n_pub + L.n_blk) * 4);
   // word blocks of the encoder, per work-group (kWG streams, absent ones included): see k_encode
   L.scratch = take((size_t)L.nc_max * ((p.n_streams + kWG - 1) / kWG) * kWG * L.capw * 2);
   size_t enc_end = o;
@@ -737,11 +738,12 @@ __device__ __forceinline__ uint64_t floor_div_f64(uint64_t a, uint32_t b) {
   return (uint64_t)((double)a / (double)b);
 }
 
-// The same as normalize_body for alphabets of up to 256 symbols, by ONE wave without a barrier: lane l
-// owns the symbols 4 l .. 4 l + 3, sums and maxima are wave scans.  Called by the first wave of a
+// The same as normalize_body for alphabets of up to 64 PER symbols, by ONE wave without a barrier: lane l
+// owns the symbols PER l .. PER l + PER - 1, sums and maxima are wave scans.  Called by the first wave of a
 // work-group; the single work-group version spends most of its time in barriers between 16 waves.
-constexpr uint32_t kNormWaveA = 256;
-__device__ void normalize_wave(const CtlRef &ctl, const NormArgs &na) {
+constexpr uint32_t kNormWaveA = 512;
+template <int PER>
+__device__ void normalize_wave_per(const CtlRef &ctl, const NormArgs &na) {
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t A = na.A;
   const rans_params &p = na.p;
@@ -749,33 +751,34 @@ __device__ void normalize_wave(const CtlRef &ctl, const NormArgs &na) {
   if (get_status(ctl) != 0) return;  // uniform: written by an earlier kernel
   auto total64 = [](uint64_t v) { return lane63_64(wave_incl_scan64(v, [](uint64_t a, uint64_t b) { return a + b; })); };
   auto max64 = [](uint64_t v) { return lane63_64(wave_incl_scan64(v, [](uint64_t a, uint64_t b) { return a > b ? a : b; })); };
-  uint32_t c[4];
+  uint32_t c[PER];
 #pragma unroll
-  for (int q = 0; q < 4; q++) {
-    const uint32_t a = 4 * lane + q;
+  for (int q = 0; q < PER; q++) {
+    const uint32_t a = PER * lane + q;
     c[q] = a < A ? __hip_atomic_load(na.cnt + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
   }
   uint64_t lp = 0;  // l_D in the low 40 bits, the number of present symbols above
 #pragma unroll
-  for (int q = 0; q < 4; q++) lp += (uint64_t)c[q] + ((uint64_t)(c[q] != 0) << 40);
+  for (int q = 0; q < PER; q++) lp += (uint64_t)c[q] + ((uint64_t)(c[q] != 0) << 40);
   lp = total64(lp);
   const uint64_t len = lp & ((1ull << 40) - 1), present = lp >> 40;
   if (na.dense && lane == 0) ctl->len_d = len;
-  const uint64_t len_d = na.dense ? len : ctl->len_d;
+  // CSR mode: len_d was stored with a device-scope atomic by a work-group of the kernel this may run in
+  const uint64_t len_d = na.dense ? len : __hip_atomic_load(&ctl->len_d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (present > total || len != len_d) {  // the second cannot happen; kept as a guard
     if (lane == 0) set_status(ctl, RANS_ERR_ALPHABET);
     return;
   }
   // first estimate, its sum, the symbol with the largest count
-  uint32_t f[4];
+  uint32_t f[PER];
   uint64_t sum = 0, best = 0;
 #pragma unroll
-  for (int q = 0; q < 4; q++) {
+  for (int q = 0; q < PER; q++) {
     f[q] = 0;
     if (c[q]) {
       const uint64_t e = floor_div_f64((uint64_t)c[q] * total + len / 2, (uint32_t)len);  // < 2^46 over < 2^32
       f[q] = e < 1 ? 1u : (uint32_t)e;
-      const uint64_t key = ((uint64_t)c[q] << 32) | (0xffffffffu - (4 * lane + q));  // max count, lowest index
+      const uint64_t key = ((uint64_t)c[q] << 32) | (0xffffffffu - (PER * lane + q));  // max count, lowest index
       best = key > best ? key : best;
     }
     sum += f[q];
@@ -785,8 +788,8 @@ __device__ void normalize_wave(const CtlRef &ctl, const NormArgs &na) {
   int64_t d = (int64_t)total - (int64_t)sum;
   auto adjust = [&](uint32_t a_star, int64_t by) {  // f[a_star] += by, in the lane that owns it
 #pragma unroll
-    for (int q = 0; q < 4; q++)
-      if (4 * lane + q == a_star) f[q] = (uint32_t)((int64_t)f[q] + by);
+    for (int q = 0; q < PER; q++)
+      if (PER * lane + q == a_star) f[q] = (uint32_t)((int64_t)f[q] + by);
   };
   if (len && d > 0) {
     adjust(0xffffffffu - (uint32_t)best, d);
@@ -795,9 +798,9 @@ __device__ void normalize_wave(const CtlRef &ctl, const NormArgs &na) {
   while (d < 0) {  // uniform: d is identical in every lane
     uint64_t kb = 0;
 #pragma unroll
-    for (int q = 0; q < 4; q++) {
-      const uint64_t key = ((uint64_t)f[q] << 32) | (0xffffffffu - (4 * lane + q));
-      kb = 4 * lane + q < A && key > kb ? key : kb;
+    for (int q = 0; q < PER; q++) {
+      const uint64_t key = ((uint64_t)f[q] << 32) | (0xffffffffu - (PER * lane + q));
+      kb = PER * lane + q < A && key > kb ? key : kb;
     }
     kb = max64(kb);
     int64_t take = (int64_t)(kb >> 32) - 1;
@@ -816,12 +819,14 @@ __device__ void normalize_wave(const CtlRef &ctl, const NormArgs &na) {
   }
   if (lane == 0) write_header(ctl, na, len_d, n_chunks, dir_off, payload_off);
   // cumulative sum, encoder tables, stored table
-  const uint32_t mine = f[0] + f[1] + f[2] + f[3];
+  uint32_t mine = 0;
+#pragma unroll
+  for (int q = 0; q < PER; q++) mine += f[q];
   uint32_t F = wave_incl_sum_scan(mine) - mine;
   int inexact = 0;
 #pragma unroll
-  for (int q = 0; q < 4; q++) {
-    const uint32_t a = 4 * lane + q;
+  for (int q = 0; q < PER; q++) {
+    const uint32_t a = PER * lane + q;
     if (a < A) {
       const uint32_t fa = f[q];
       inexact |= emit_entries(na, a, fa, F, (uint32_t)floor_div_f64(0x100000000ull, fa ? fa : 1),
@@ -832,6 +837,11 @@ __device__ void normalize_wave(const CtlRef &ctl, const NormArgs &na) {
   const bool any_inexact = __ballot(inexact) != 0;
   if (lane == 0) ctl->enc_exact = any_inexact ? 0u : 1u;
   for (uint64_t o = table_off + 2ull * A + 2 * lane; o < dir_off; o += 2 * 64) *(uint16_t *)(na.out + o) = 0;
+}
+
+__device__ void normalize_wave(const CtlRef &ctl, const NormArgs &na) {
+  if (na.A <= 256) normalize_wave_per<4>(ctl, na);
+  else normalize_wave_per<8>(ctl, na);
 }
 
 __global__ __launch_bounds__(kBig) void k_normalize(CtlRef ctl, NormArgs na) {
@@ -853,11 +863,11 @@ constexpr int QNT = 1024;                // lanes per work-group of the quantise
 constexpr uint32_t kQuantBlocks = 256;   // its work-groups (persistent over tiles): few of them, because each one ends
                                          // with a burst of same-address atomics on the global histogram
 
-template <typename T, bool VEC, int NT>
+template <typename T, bool VEC, int NT, bool CSR>
 __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRef ctl, uint32_t q_bits,
                                                     uint8_t *sym, uint32_t *cnt, int skip_zero_bin,
                                                     const MinMaxPart *part, uint32_t n_part, rans_qinfo *qout,
-                                                    int fold_norm, NormArgs na) {
+                                                    int fold_norm, NormArgs na, uint32_t *blk_nnz) {
   constexpr bool IS_SYM = sizeof(T) == 1;
   constexpr int V = VEC ? (int)(16 / sizeof(T)) : 1;
   __shared__ uint32_t h[256 * kHistRep];
@@ -884,7 +894,14 @@ __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRe
   fd.init(s);
   const uint32_t rep = threadIdx.x & (kHistRep - 1);
   const uint32_t tile = NT * V * kQIter;
-  auto bump = [&](uint32_t a) { atomicAdd(&h[a * kHistRep + rep], 1u); };
+  // CSR: the nonzeros of each tile of kCsrTile symbols are counted on the way.  A wave's symbols of one step
+  // lie in one tile: the lanes' counts are summed with a wave scan and the last lane adds the sum to the
+  // tile's global counter.
+  uint32_t lane_nz = 0;
+  auto bump = [&](uint32_t a) {
+    atomicAdd(&h[a * kHistRep + rep], 1u);
+    if constexpr (CSR) lane_nz += a != 0;
+  };
   auto run = [&](auto fast_tag) {
   constexpr bool FAST = decltype(fast_tag)::value;
   auto q = [&](float v) -> uint32_t {
@@ -897,7 +914,8 @@ __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRe
 #pragma unroll
   for (int it = 0; it < kQIter; it++) {
     uint64_t e0 = base + ((uint64_t)it * NT + threadIdx.x) * V;
-    if (e0 >= n) break;
+    if (!CSR && e0 >= n) break;
+    if (e0 < n) {
     if (VEC && e0 + V <= n) {
       if constexpr (IS_SYM) {
         uint4 w = *(const uint4 *)((const uint8_t *)x + e0);
@@ -937,24 +955,39 @@ __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRe
         if constexpr (!IS_SYM) sym[e0 + k] = (uint8_t)a;
       }
     }
+    }  // e0 < n
+    if constexpr (CSR) {  // every lane of the wave is here; lane 0 holds the wave's lowest element
+      const uint32_t wave_nz = wave_incl_sum_scan(lane_nz);
+      lane_nz = 0;
+      const uint32_t tile_of_wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(e0 / kCsrTile));
+      if ((threadIdx.x & 63) == 63 && wave_nz) atomicAdd(&blk_nnz[tile_of_wave], wave_nz);
+    }
   }
   };  // run
   if (fast) run(std::true_type{});
   else run(std::false_type{});
   __syncthreads();
+  uint32_t seen = 0;
   for (int a = threadIdx.x; a < 256; a += NT) {
     uint32_t t = 0;
 #pragma unroll
     for (int r = 0; r < kHistRep; r++) t += h[a * kHistRep + r];
     if (!t) continue;
     if (a >= (1 << q_bits)) set_status(ctl, RANS_ERR_ARG);  // caller-provided symbol outside {0..2^Q-1}
-    else if (!(skip_zero_bin && a == 0)) atomicAdd(&cnt[a], t);
+    else if (!(skip_zero_bin && a == 0)) {
+      // with the table build folded in, the additions return their old value: a returned value is the only
+      // proof that an addition has been performed before the work-group takes its ticket (one without a
+      // result is acknowledged earlier than that)
+      if (fold_norm) seen |= atomicAdd(&cnt[a], t);
+      else atomicAdd(&cnt[a], t);
+    }
   }
   if (!fold_norm) return;
+  if (seen == 0xffffffffu) set_status(ctl, RANS_ERR_HIP);  // cannot happen (counts are below 2^31); keeps the values in use
   // The work-group that adds its counts last also builds the frequency table (saves a launch).  The
-  // additions above are device-scope atomics; the barrier waits until this work-group's have been
-  // performed, only then does it take its ticket.  The last one reads the histogram with device-scope
-  // atomic loads, so no cache has to be written back or invalidated in between.
+  // additions above are device-scope atomics that return a value; the barrier waits for the values, so
+  // this work-group's additions have been performed when it takes its ticket.  The last one reads the
+  // histogram with device-scope atomic loads, so no cache has to be written back or invalidated in between.
   __shared__ uint32_t s_ticket;
   __syncthreads();
   if (threadIdx.x == 0) s_ticket = __hip_atomic_fetch_add(&ctl->hist_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -981,20 +1014,6 @@ __device__ __forceinline__ void load16(const uint8_t *p, uint64_t e0, uint64_t n
   }
 }
 
-// Number of nonzero symbols per tile of kCsrTile elements.
-__global__ __launch_bounds__(kWG) void k_csr_count(const uint8_t *sym, uint32_t n, int aligned, uint32_t *blk_nnz) {
-  __shared__ uint32_t sh[kWG / 64];
-  uint64_t e0 = (uint64_t)blockIdx.x * kCsrTile + threadIdx.x * 16;
-  uint8_t b[16];
-  load16(sym, e0, n, aligned, b);
-  uint32_t c = 0;
-#pragma unroll
-  for (int k = 0; k < 16; k++) c += b[k] != 0;
-  uint32_t tot;
-  (void)block_excl_scan<kWG>(c, sh, &tot);
-  if (threadIdx.x == 0) blk_nnz[blockIdx.x] = tot;
-}
-
 // In-place exclusive scan of a u32 array by one work-group; the total goes to a[n].
 __global__ __launch_bounds__(kBig) void k_scan_u32(uint32_t *a, uint32_t n) {
   __shared__ uint32_t sh[kBig / 64];
@@ -1016,17 +1035,34 @@ __global__ __launch_bounds__(kBig) void k_scan_u32(uint32_t *a, uint32_t n) {
 // A work-group walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...: a tile's nonzeros are
 // compacted in LDS first and leave with consecutive lanes on consecutive entries, and the
 // column histogram is added to the global one once at the end (few work-groups: same-address
-// global atomics are what costs here).
+// global atomics are what costs here).  blk_nnz[t] is the number of nonzeros of tile t (counted by
+// k_quant_hist); a tile's place in v and c is the sum over the tiles before it, which the work-group
+// adds up itself.
 template <bool LDS_HIST>
 __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_t n, int aligned, uint32_t K,
-                                                     const uint32_t *blk_off, uint8_t *v, uint16_t *c,
+                                                     const uint32_t *blk_nnz, uint8_t *v, uint16_t *c,
                                                      uint32_t *row_end, uint32_t *cnt, uint32_t A, uint32_t n_tiles) {
   extern __shared__ uint32_t hist[];
   __shared__ uint32_t sh[kWG / 64];
+  __shared__ uint64_t sh64[kWG / 64];
   __shared__ uint8_t s_v[kCsrTile];
   __shared__ uint16_t s_c[kCsrTile];
   if (LDS_HIST) {
     for (uint32_t a = threadIdx.x; a < A; a += kWG) hist[a] = 0;
+  }
+  // where the work-group's tile starts in v and c: the nonzeros of all tiles before it (k_quant_hist has
+  // counted them), kept up to date from tile to tile with the counts of the tiles in between
+  uint32_t base;
+  {
+    uint64_t part = 0;
+    for (uint32_t u0 = threadIdx.x; u0 < blockIdx.x; u0 += 4 * kWG) {
+      uint32_t x4[4];
+#pragma unroll
+      for (int k = 0; k < 4; k++) x4[k] = u0 + k * kWG < blockIdx.x ? blk_nnz[u0 + k * kWG] : 0u;
+#pragma unroll
+      for (int k = 0; k < 4; k++) part += x4[k];
+    }
+    base = (uint32_t)block_sum64<kWG>(part, sh64);
   }
   for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const uint64_t e0 = (uint64_t)tile * kCsrTile + threadIdx.x * 16;
@@ -1037,7 +1073,6 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
     for (int k = 0; k < 16; k++) cth += b[k] != 0;
     uint32_t tot;
     uint32_t loc = block_excl_scan<kWG>(cth, sh, &tot);  // also orders the hist zeroing and the staging reuse
-    const uint32_t base = blk_off[tile];
     if (e0 < n) {
       uint32_t row = (uint32_t)(e0 / K), col = (uint32_t)(e0 - (uint64_t)row * K);
 #pragma unroll
@@ -1063,6 +1098,17 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
       v[base + i] = s_v[i];
       c[base + i] = s_c[i];
     }
+    if (tile + gridDim.x < n_tiles) {  // uniform
+      uint64_t skip = 0;
+      for (uint32_t u0 = tile + threadIdx.x; u0 < tile + gridDim.x; u0 += 4 * kWG) {
+        uint32_t x4[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) x4[k] = u0 + k * kWG < tile + gridDim.x ? blk_nnz[u0 + k * kWG] : 0u;
+#pragma unroll
+        for (int k = 0; k < 4; k++) skip += x4[k];
+      }
+      base += (uint32_t)block_sum64<kWG>(skip, sh64);
+    }
     __syncthreads();  // staging and scan scratch are reused by the next tile
   }
   if (LDS_HIST) {
@@ -1077,7 +1123,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
 // over the rows and add their histogram to the global one once.
 template <bool LDS_HIST>
 __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint32_t N, uint16_t *r, uint32_t *cnt,
-                                                  uint32_t A, CtlRef ctl) {
+                                                  uint32_t A, CtlRef ctl, int fold_norm, NormArgs na) {
   extern __shared__ uint32_t hist[];
   if (LDS_HIST) {
     for (uint32_t a = threadIdx.x; a < A; a += kWG) hist[a] = 0;
@@ -1091,16 +1137,34 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
     else atomicAdd(&cnt[ri], 1u);
     if (i == N - 1) {
       ctl->nnz = e1;
-      ctl->len_d = 2ull * e1 + N;
+      __hip_atomic_store(&ctl->len_d, 2ull * e1 + N, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
+  uint32_t seen = 0;
   if (LDS_HIST) {
     __syncthreads();
     for (uint32_t a = threadIdx.x; a < A; a += kWG) {
       uint32_t t = hist[a];
-      if (t) atomicAdd(&cnt[a], t);
+      // with the table build folded in, the additions return their old value: a returned value is the only
+      // proof that an addition has been performed before the work-group takes its ticket
+      if (t) {
+        if (fold_norm) seen |= atomicAdd(&cnt[a], t);
+        else atomicAdd(&cnt[a], t);
+      }
     }
   }
+  if (!fold_norm) return;
+  if (seen == 0xffffffffu) set_status(ctl, RANS_ERR_HIP);  // cannot happen (counts are below 2^31); keeps the values in use
+  // D's histogram is complete once every work-group has added its row counts: the last one to do so
+  // builds the frequency table (the same hand-over as at the end of k_quant_hist).  It also reads len_d,
+  // which the work-group holding the last row stored (device-scope atomic) before the barrier ahead of
+  // its ticket.
+  __shared__ uint32_t s_ticket;
+  __syncthreads();
+  if (threadIdx.x == 0) s_ticket = __hip_atomic_fetch_add(&ctl->hist_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (s_ticket != gridDim.x - 1) return;
+  if (threadIdx.x < 64) normalize_wave(ctl, na);
 }
 
 // ------------------------------------------------------------------ kernels: rANS encode
@@ -2776,12 +2840,12 @@ __global__ void k_rs_empty(uint32_t n, const uint32_t *bad_flag, rans_reshape_re
 // mask, each of its launches is bracketed by a pair of HIP events recorded on the
 // launch stream.  Off by default; the normal path records nothing.
 enum KernelId {
-  KID_MINMAX = 0, KID_QINFO, KID_QUANT_HIST, KID_CSR_COUNT, KID_SCAN, KID_CSR_COMPACT, KID_CSR_ROWS,
+  KID_MINMAX = 0, KID_QINFO, KID_QUANT_HIST, KID_SCAN, KID_CSR_COMPACT, KID_CSR_ROWS,
   KID_NORMALIZE, KID_ENCODE, KID_CHUNK_SCAN, KID_GATHER, KID_DEC_PREPARE, KID_DECODE, KID_ROW_SCAN,
   KID_CSR_EXPAND, KID_DEQUANT, KID_COUNT
 };
 const char *const kKernelNames[KID_COUNT] = {
-    "k_minmax", "k_qinfo", "k_quant_hist", "k_csr_count", "k_scan_u32", "k_csr_compact", "k_csr_rows",
+    "k_minmax", "k_qinfo", "k_quant_hist", "k_scan_u32", "k_csr_compact", "k_csr_rows",
     "k_normalize", "k_encode", "k_chunk_scan", "k_gather", "k_dec_prepare", "k_decode", "k_row_part",
     "k_csr_to_dense", "k_dequant"};
 
@@ -2856,7 +2920,12 @@ inline uint32_t grid_for(uint64_t n, uint32_t per_block, uint32_t cap) {
   return (uint32_t)(g > cap ? cap : g);
 }
 
-// min/max + scale/zero point + quantise/histogram of a float tensor.
+// Index of the last of the counters behind L.chunk_words that a call starts from zero, and the tile counts among them.
+inline uint32_t counter_words(const Layout &L) { return L.nc_max + L.n_pub + L.n_blk; }
+inline uint32_t *tile_counts_of(const Layout &L, uint8_t *ws) {
+  return L.n_blk ? (uint32_t *)(ws + L.chunk_words) + L.nc_max + 1 + L.n_pub : nullptr;
+}
+
 NormArgs norm_args(const rans_params &p, const Layout &L, uint8_t *ws, uint64_t n, uint8_t *d_stream, size_t cap) {
   return NormArgs{(const uint32_t *)(ws + L.cnt), (uint32_t *)(ws + L.fq), (uint2 *)(ws + L.enc_tab),
                   (uint4 *)(ws + L.enc_tab4), L.A, p, n, p.mode == RANS_MODE_CSR ? 0 : 1, d_stream, (uint64_t)cap};
@@ -2869,7 +2938,7 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
   const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   uint32_t *cnt = (uint32_t *)(ws + L.cnt);
   uint32_t *cw_ = (uint32_t *)(ws + L.chunk_words);
-  const uint32_t ncz_ = L.nc_max + L.n_pub;
+  const uint32_t ncz_ = counter_words(L);
   const bool f16 = p.in_dtype == RANS_F16;
   const bool vec = aligned_to(d_x, 16) && aligned_to(d_sym, 8);
   const uint32_t V = vec ? (f16 ? 8 : 4) : 1;
@@ -2895,13 +2964,18 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
     int skip0 = p.mode == RANS_MODE_CSR;
     const int fold = na != nullptr;
     const NormArgs nav = na ? *na : NormArgs{};
-    if (f16) {
-      if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, true, QNT>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav);
-      else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, false, QNT>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav);
-    } else {
-      if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, true, QNT>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav);
-      else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, false, QNT>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav);
-    }
+    auto launch_qh = [&](auto csr_tag) {
+      constexpr bool CSRV = decltype(csr_tag)::value;
+      if (f16) {
+        if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws));
+        else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws));
+      } else {
+        if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws));
+        else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws));
+      }
+    };
+    if (skip0) launch_qh(std::true_type{});
+    else launch_qh(std::false_type{});
     LAUNCH_CHECK();
   }
   return RANS_OK;
@@ -2918,13 +2992,9 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
   const bool lds_hist = A <= kLdsHistMaxA;
   if (csr) {
     const int al = aligned_to(d_sym, 16);
-    uint32_t *blk = (uint32_t *)(ws + L.blk_nnz);
+    const uint32_t *blk = tile_counts_of(L, ws);  // counted by k_quant_hist
     uint32_t *row_end = (uint32_t *)(ws + L.row_end);
     if (n) {
-      PROF_LAUNCH(KID_CSR_COUNT, k_csr_count, dim3(L.n_blk), dim3(kWG), 0, st, d_sym, (uint32_t)n, al, blk);
-      LAUNCH_CHECK();
-      PROF_LAUNCH(KID_SCAN, k_scan_u32, dim3(1), dim3(kBig), 0, st, blk, L.n_blk);
-      LAUNCH_CHECK();
       const uint32_t g_compact = L.n_blk < kCompactBlocks ? L.n_blk : kCompactBlocks;
       if (lds_hist)
         PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true>), dim3(g_compact), dim3(kWG), A * 4, st, d_sym, (uint32_t)n, al,
@@ -2936,11 +3006,14 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       uint32_t N = (uint32_t)p.rows;
       uint32_t g = (N + kWG - 1) / kWG;
       g = g > 512 ? 512 : g;
+      const int fold = A <= kNormWaveA;  // one wave of the last work-group can build the table
+      const NormArgs na = norm_args(p, L, ws, n, d_stream, cap);
       if (lds_hist)
-        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<true>), dim3(g), dim3(kWG), A * 4, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl);
+        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<true>), dim3(g), dim3(kWG), A * 4, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl, fold, na);
       else
-        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<false>), dim3(g), dim3(kWG), 0, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl);
+        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<false>), dim3(g), dim3(kWG), 0, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl, fold, na);
       LAUNCH_CHECK();
+      table_done = fold != 0;
     }
   }
   if (!table_done) {  // else the histogram kernel has built the table
@@ -3404,7 +3477,7 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
   const uint32_t seq = next_seq();
   const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   PROF_LAUNCH(KID_QINFO, k_qinfo_from_user, dim3(1), dim3(kBig), 0, st, ctl, d_qinfo, p->q_bits,
-              (uint32_t *)(ws + L.cnt), L.A, (uint32_t *)(ws + L.chunk_words), L.nc_max + L.n_pub);
+              (uint32_t *)(ws + L.cnt), L.A, (uint32_t *)(ws + L.chunk_words), counter_words(L));
   LAUNCH_CHECK();
   if (n_elems) {
     const bool vec = aligned_to(d_sym, 16);
@@ -3412,10 +3485,15 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
     const int skip0 = p->mode == RANS_MODE_CSR;
     const int fold = !skip0;  // dense: the histogram is complete after this kernel, which then builds the table
     const NormArgs na = norm_args(*p, L, ws, n_elems, d_stream, stream_cap);
-    if (vec)
-      PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, true, QNT>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, fold, na);
-    else
-      PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, false, QNT>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, fold, na);
+    auto launch_qh = [&](auto csr_tag) {
+      constexpr bool CSRV = decltype(csr_tag)::value;
+      if (vec)
+        PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, fold, na, tile_counts_of(L, ws));
+      else
+        PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, fold, na, tile_counts_of(L, ws));
+    };
+    if (skip0) launch_qh(std::true_type{});
+    else launch_qh(std::false_type{});
     LAUNCH_CHECK();
   }
   return launch_encode_tail(d_sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq,

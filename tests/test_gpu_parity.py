@@ -315,3 +315,32 @@ def test_full_size_llama_config_in_bench_configuration():
     qi = oracle.qinfo_from_minmax(hdr.x_min, hdr.x_max, 8)
     y_ref = oracle.dequantize(sym_ref, qi, oracle.F16)
     assert np.array_equal(out.cpu().numpy().view(np.uint16), y_ref.view(np.uint16))
+
+
+def test_full_size_csr_config_repeated():
+    """c3 in CSR form at full size (fp32 64x512x28x28, N x 256, Q=8, M=14, S=1024, 2^16-symbol chunks): the whole
+    container against the oracle's, and the same bytes on every one of many calls in a row.  The table of this
+    path is built by whichever work-group adds its part of the histogram last, hundreds of work-groups and a wide
+    spread of row counts; a hand-over that starts before every addition has been performed shows up here as an
+    error status on some of the calls."""
+    w = synth.workload("c3", 1, mode=1, cols=256, chunk_syms=65536)
+    x = synth.make(w)
+    p = B.params_of(w)
+    print("[case] c3 CSR full size, repeated", flush=True)
+    ref, _ = oracle.compress(x.numpy(), _oparams(p))
+    ref = torch.from_numpy(np.frombuffer(ref, np.uint8).copy()).cuda()
+    codec = B.Codec(p, w.numel)
+    xd = x.cuda()
+    for it in range(40):
+        assert B.rans_compress(xd, w.numel, p, codec.stream, codec.nbytes, codec.ws) == 0
+        assert B.rans_last_status(codec.ws) == 0, f"call {it}"
+        nbytes = int(codec.nbytes.item())
+        assert nbytes == ref.numel(), f"call {it}"
+        assert torch.equal(codec.stream[:nbytes], ref), f"call {it}"
+    hdr = codec.header(nbytes)
+    sym = torch.empty(w.numel, dtype=torch.uint8, device="cuda")
+    qinfo = torch.empty(4, dtype=torch.float32, device="cuda")
+    assert B.rans_decode(codec.stream, nbytes, hdr, sym, qinfo, codec.ws) == 0
+    assert B.rans_last_status(codec.ws) == 0
+    sym_ref, _ = oracle.quantize(x.numpy(), 8)
+    assert np.array_equal(sym.cpu().numpy(), sym_ref)

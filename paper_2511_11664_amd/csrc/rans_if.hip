@@ -1176,6 +1176,11 @@ struct SrcDense {
   static constexpr int kMaxSpl = 4;
   __device__ __forceinline__ void init(const CtlRef &) {}
   __device__ __forceinline__ const uint8_t *bytes() const { return sym; }  // D as a plain byte array
+  // the parts of a CSR source (not meaningful here; they keep the coder's code generic)
+  __device__ __forceinline__ uint64_t nnz_of() const { return 0; }
+  __device__ __forceinline__ const uint8_t *v_ptr() const { return nullptr; }
+  __device__ __forceinline__ const uint16_t *c_ptr() const { return nullptr; }
+  __device__ __forceinline__ const uint16_t *r_ptr() const { return nullptr; }
   __device__ __forceinline__ uint32_t operator()(uint64_t i) const { return sym[i]; }
   template <int SPL>
   __device__ __forceinline__ uint32_t fetch(uint64_t i) const {
@@ -1193,6 +1198,10 @@ struct SrcCsr {
   static constexpr int kMaxSpl = 2;
   __device__ __forceinline__ void init(const CtlRef &ctl) { nnz = ctl->nnz; }
   __device__ __forceinline__ const uint8_t *bytes() const { return nullptr; }  // D is not one byte array
+  __device__ __forceinline__ uint64_t nnz_of() const { return nnz; }
+  __device__ __forceinline__ const uint8_t *v_ptr() const { return v; }
+  __device__ __forceinline__ const uint16_t *c_ptr() const { return c; }
+  __device__ __forceinline__ const uint16_t *r_ptr() const { return r; }
   __device__ __forceinline__ uint32_t operator()(uint64_t i) const {
     if (i < nnz) return v[i];
     if (i < 2 * nnz) return c[i - nnz];
@@ -1208,7 +1217,9 @@ struct SrcCsr {
 };
 
 constexpr int kStageRows = 32;         // rows per tile of the encoder's symbol staging (dense source)
+constexpr int kStageRows2 = 16;        // the same for the CSR source (16-bit entries)
 constexpr uint32_t kRingStride = 40;  // bytes between the word rings of adjacent streams: 16 slots + padding against bank conflicts
+constexpr uint32_t kEncTab16MaxA = 1024;  // CSR alphabets up to this size use the 16-byte table entries
 constexpr int kEncAhead = 8;  // rows of symbols fetched ahead of the coder; also the flush period of the word ring
 
 // Encoder table entry as the coder uses it.
@@ -1374,7 +1385,8 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
   // that form: EXACT {mx, lim1, Fx | sh << 16, 2^M - f}, else {floor(2^32/f), f, F, 2^M - f}).
   auto run = [&](auto exact_tag, auto wide_tag) {
     constexpr bool EXACT = decltype(exact_tag)::value;
-    constexpr bool WIDE = decltype(wide_tag)::value;
+    constexpr int WIDE_KIND = decltype(wide_tag)::value;  // 0: direct loads, 1: dense bytes through LDS, 2: CSR segments through LDS
+    constexpr bool WIDE = WIDE_KIND == 1;
     // Eq. 2 for the lane's SPL streams, phase by phase across the streams so that the
     // independent chains interleave; selects only, no branches.
     auto row = [&](const EncEntry (&e)[SPL]) {
@@ -1514,6 +1526,93 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
         }
         batch();
       }
+    } else if constexpr (WIDE_KIND == 2) {
+      // The same for D = v (+) c (+) r (Eq. 7), staged as 16-bit entries.  A wave owns 64 streams; a tile is
+      // kStageRows2 rows of them, lane L fetches the 16 entries 16 (L % 4) .. of row L / 4: one 16-byte load
+      // where they all lie in v, two where they all lie in c or in r (2-byte aligned: where c starts inside D
+      // depends on the number of nonzeros), entry by entry where they straddle two parts or the end of D.
+      static_assert(WIDE_KIND != 2 || (SPL == 1 && kEncAhead == 8 && kStageRows2 == 16), "tile arithmetic below");
+      const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+      // 16-byte aligned whatever the size of the table before it
+      uint8_t *stg = (uint8_t *)(((uintptr_t)(sh + 16) + 15) & ~(uintptr_t)15) + wv * (2 * kStageRows2 * 128);
+      const uint64_t nnz = src.nnz_of();
+      const uint64_t col_i = base + (j0 - lane) + 16 * (lane & 3);  // D index of the lane's 16 entries in row 0
+      uint4 pend[2];
+      auto request = [&](uint64_t t_lo, uint64_t t_top) {  // rows t_lo .. t_lo+15 (below t_top) of the column
+        const uint64_t r = t_lo + (lane >> 2);
+        pend[0] = pend[1] = make_uint4(0, 0, 0, 0);
+        if (r < t_top) {
+          const uint64_t i = col_i + r * S;
+          if (i + 16 <= nnz) {  // values: bytes, widened when they are parked
+            pend[0] = *(const uint4 *)(src.v_ptr() + i);
+          } else if (i >= nnz && (i + 16 <= 2 * nnz || (i >= 2 * nnz && i + 16 <= len))) {
+            const uint16_t *q = i < 2 * nnz ? src.c_ptr() + (i - nnz) : src.r_ptr() + (i - 2 * nnz);
+            __builtin_memcpy(&pend[0], q, 16);
+            __builtin_memcpy(&pend[1], q + 8, 16);
+          } else {
+            uint32_t w[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+              const uint32_t lo = i + 2 * k < len ? src(i + 2 * k) : 0u, hi = i + 2 * k + 1 < len ? src(i + 2 * k + 1) : 0u;
+              w[k] = lo | (hi << 16);
+            }
+            pend[0] = make_uint4(w[0], w[1], w[2], w[3]);
+            pend[1] = make_uint4(w[4], w[5], w[6], w[7]);
+          }
+        }
+      };
+      auto park = [&](uint64_t t_lo, uint64_t t_top) {
+        const uint64_t r = t_lo + (lane >> 2);
+        const uint64_t i = col_i + r * S;
+        uint4 a = pend[0], b = pend[1];
+        if (r < t_top && i + 16 <= nnz) {  // 16 bytes -> 16 16-bit entries
+          const uint32_t ww[4] = {pend[0].x, pend[0].y, pend[0].z, pend[0].w};
+          uint32_t e[8];
+#pragma unroll
+          for (int k = 0; k < 8; k++) {
+            const uint32_t two = ww[k >> 1] >> (16 * (k & 1));
+            e[k] = (two & 0xffu) | ((two & 0xff00u) << 8);
+          }
+          a = make_uint4(e[0], e[1], e[2], e[3]);
+          b = make_uint4(e[4], e[5], e[6], e[7]);
+        }
+        uint4 *line = (uint4 *)(stg + (((uint32_t)t_lo + (lane >> 2)) & 31u) * 128 + 32 * (lane & 3));
+        line[0] = a;
+        line[1] = b;
+      };
+      auto read_rows = [&](uint32_t *dst, uint64_t t_hi) {  // rows t_hi-1 .. t_hi-8; t_hi is a multiple of 8
+        const uint8_t *b = stg + (((uint32_t)t_hi - 8) & 31u) * 128 + 2 * lane;
+#pragma unroll
+        for (int u = 0; u < kEncAhead; u++) dst[u] = *(const uint16_t *)(b + (kEncAhead - 1 - u) * 128);
+      };
+      uint64_t t_req_top = 0;  // upper row bound of the tile in flight (park needs it to tell how it was fetched)
+      if (t) {
+        const uint64_t t_lo = (t - 1) & ~(uint64_t)(kStageRows2 - 1);
+        request(t_lo, t);
+        park(t_lo, t);
+        if (t_lo) {
+          request(t_lo - kStageRows2, t_lo);
+          t_req_top = t_lo;
+        }
+        read_rows(nxt, t);
+        prime();
+      }
+      while (t) {
+#pragma unroll
+        for (int u = 0; u < kEncAhead; u++) cur[u] = nxt[u];
+        t -= kEncAhead;
+        if (t) {
+          if ((t & (kStageRows2 - 1)) == 0) {  // the next rows belong to the tile below: it has arrived by now
+            park(t - kStageRows2, t_req_top);
+            if (t > kStageRows2) {
+              request(t - 2 * kStageRows2, t - kStageRows2);
+              t_req_top = t - kStageRows2;
+            }
+          }
+          read_rows(nxt, t);
+        }
+        batch();
+      }
     } else {
       auto fetch_rows = [&](uint32_t *dst, uint64_t t_hi) {  // rows t_hi-1 .. t_hi-kEncAhead
 #pragma unroll
@@ -1535,15 +1634,23 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
   if (live) {
     if constexpr (std::is_same<Src, SrcDense>::value && SPL == 1) {
       if (wide) {
-        if (exact) run(std::true_type{}, std::true_type{});
-        else run(std::false_type{}, std::true_type{});
+        if (exact) run(std::true_type{}, std::integral_constant<int, 1>{});
+        else run(std::false_type{}, std::integral_constant<int, 1>{});
       } else {
-        if (exact) run(std::true_type{}, std::false_type{});
-        else run(std::false_type{}, std::false_type{});
+        if (exact) run(std::true_type{}, std::integral_constant<int, 0>{});
+        else run(std::false_type{}, std::integral_constant<int, 0>{});
+      }
+    } else if constexpr (std::is_same<Src, SrcCsr>::value && SPL == 1) {
+      if (wide) {
+        if (exact) run(std::true_type{}, std::integral_constant<int, 2>{});
+        else run(std::false_type{}, std::integral_constant<int, 2>{});
+      } else {
+        if (exact) run(std::true_type{}, std::integral_constant<int, 0>{});
+        else run(std::false_type{}, std::integral_constant<int, 0>{});
       }
     } else {
-      if (exact) run(std::true_type{}, std::false_type{});
-      else run(std::false_type{}, std::false_type{});
+      if (exact) run(std::true_type{}, std::integral_constant<int, 0>{});
+      else run(std::false_type{}, std::integral_constant<int, 0>{});
     }
   }
   uint32_t nw[SPL];
@@ -3038,8 +3145,8 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
   do {                                                                                                            \
     const uint32_t groups_e = (S + kWG * SPLV - 1) / (kWG * SPLV);                                                \
     size_t lds_e = (TABV == 2 ? A * 16 : (TABV == 1 ? A * 8 : 0)) + kRingStride * kWG * SPLV + 64;                         \
-    const int wide_e = !csr && SPLV == 1 && S % 64 == 0 && aligned_to(d_sym, 16);                                 \
-    if (wide_e) lds_e += (kWG / 64) * 2 * kStageRows * 64;                                                        \
+    const int wide_e = SPLV == 1 && S % 64 == 0 && (csr || aligned_to(d_sym, 16));                                \
+    if (wide_e) lds_e += csr ? (kWG / 64) * 2 * kStageRows2 * 128 + 16 : (kWG / 64) * 2 * kStageRows * 64;        \
     if (fused_gather && lds_e < kEncTileBytes) lds_e = kEncTileBytes;                                             \
     if (mul24) {                                                                                                  \
       if (fused_gather) ENC_LAUNCH2(SRCT, SPLV, TABV, true, true);                                                \
@@ -3053,7 +3160,8 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     // several streams inside a lane, and the stream count rarely exceeds what the chip can hold.
     if (csr) {
       SrcCsr src{ws + L.v, (const uint16_t *)(ws + L.c), (const uint16_t *)(ws + L.r), 0};
-      if (lds_tab) ENC_LAUNCH(SrcCsr, 1, 1);
+      if (A <= kEncTab16MaxA) ENC_LAUNCH(SrcCsr, 1, 2);
+      else if (lds_tab) ENC_LAUNCH(SrcCsr, 1, 1);
       else ENC_LAUNCH(SrcCsr, 1, 0);
     } else {
       SrcDense src{d_sym};

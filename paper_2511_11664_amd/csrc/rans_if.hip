@@ -3112,7 +3112,7 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       LAUNCH_CHECK();
       uint32_t N = (uint32_t)p.rows;
       uint32_t g = (N + kWG - 1) / kWG;
-      g = g > 512 ? 512 : g;
+      g = g > 128 ? 128 : g;  // few work-groups: each ends with additions to the same few addresses and a ticket
       const int fold = A <= kNormWaveA;  // one wave of the last work-group can build the table
       const NormArgs na = norm_args(p, L, ws, n, d_stream, cap);
       if (lds_hist)

@@ -8,6 +8,12 @@ resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5a] [--mode 0|1] [--cols K]
                     [--q-bits Q] [--chunk-syms N] [--no-cpu]
+
+Two further measurements print a JSON object of their own instead of that line:
+
+    python bench.py --sweep bits [--workload t1]      size and latency per bit width Q (layout of the paper's Table 1 / 3)
+    python bench.py --sweep reshape [--workload t1]   Eq. 8: size, encode and decode time for every reshape N of
+                                                      Algorithm 1's domain, next to a plain copy of the tensor
 """
 import argparse
 import json
@@ -32,6 +38,7 @@ def main():
     ap.add_argument("--cols", type=int, default=None)
     ap.add_argument("--q-bits", type=int, default=None)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--sweep", choices=["bits", "reshape"], default=None)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the codec has no cross-GPU step); use --gpus 1", file=sys.stderr)
@@ -40,6 +47,9 @@ def main():
     import numpy as np
     import torch
     from paper_2511_11664_amd import binding as B, synth
+
+    if args.sweep:
+        return sweep(args, np, torch, B, synth)
 
     over = {}
     if args.chunk_syms is not None:
@@ -129,6 +139,23 @@ def main():
     assert B.rans_last_status(codec.ws) == 0
 
     in_bytes = n * e
+    # the measured ceiling of this machine: a plain device-to-device copy of the input (reads and writes its bytes once)
+    calib = torch.empty_like(x)
+    copy_p50 = p50_us(lambda: calib.copy_(x), 20)[0]
+    del calib
+    copy_ceiling = {"p50_us": round(copy_p50, 1), "GBps": round(2 * in_bytes / copy_p50 / 1e3, 1),
+                    "frac_of_peak": round(2 * in_bytes / copy_p50 / 1e3 / HBM_PEAK_GBPS, 4)}
+    # bits per symbol next to the entropy H of the symbols and the cross entropy CE against the stored table
+    # (Eq. 1); DENSE mode only, where D is the symbol tensor itself
+    coding = None
+    if w.mode != synth.MODE_CSR and n:
+        hist = torch.bincount(sym.to(torch.int64), minlength=1 << w.q_bits).double().cpu().numpy()
+        pr = hist / hist.sum()
+        f = np.frombuffer(codec.stream[128:128 + 2 * (1 << w.q_bits)].cpu().numpy().tobytes(), dtype="<u2").astype(np.float64)
+        nzm = pr > 0
+        H = float(-(pr[nzm] * np.log2(pr[nzm])).sum())
+        CE = float(-(pr[nzm] * np.log2(f[nzm] / float(1 << w.freq_bits))).sum())
+        coding = {"bits_per_symbol": round(8 * nbytes / n, 4), "entropy_H": round(H, 4), "cross_entropy_CE": round(CE, 4)}
     # algorithmic bytes: three forced passes on the encode side (min/max reads X; quantise reads X and
     # writes xhat; the coder reads xhat and writes the container), one on the decode side.
     b_enc = 2 * e * n + 2 * n + nbytes
@@ -199,10 +226,94 @@ def main():
                    "GBps_output": round(in_bytes / dec_p50 / 1e3, 1), "GBps_fp32_equiv": round(4 * n / dec_p50 / 1e3, 1),
                    "algorithmic_bytes": b_dec, "roofline_frac": round(b_dec / (dec_p50 * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)},
         "unfused_p50_us": unf,
+        "copy_ceiling": copy_ceiling,
+        "coding": coding,
         "roofline": roof,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
+
+
+def _p50(torch, fn, reps=30):
+    for _ in range(3):
+        fn()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+    return round(ts[len(ts) // 2], 1)
+
+
+def sweep(args, np, torch, B, synth):
+    """--sweep bits / reshape: see the module docstring."""
+    import ctypes as C
+    name = args.workload if args.workload != "c5a" or args.sweep == "bits" else "t1"
+    torch.cuda.set_device(0)
+    rows = []
+    if args.sweep == "bits":
+        for Q in (2, 3, 4, 6, 8):
+            w = synth.workload(name, 1, q_bits=Q)
+            x = synth.make(w).cuda()
+            n = w.numel
+            pd = B.params_of(w)
+            cd = B.Codec(pd, n)
+            nb_d = cd.compress(x)
+            hd = cd.header(nb_d)
+            out = torch.empty(n, dtype=x.dtype, device="cuda")
+            row = {"Q": Q, "raw_bytes": n * x.element_size(), "dense_bytes": nb_d,
+                   "dense_compress_us": _p50(torch, lambda: B.rans_compress(x, n, pd, cd.stream, cd.nbytes, cd.ws)),
+                   "dense_decompress_us": _p50(torch, lambda: B.rans_decompress(cd.stream, nb_d, hd, w.in_dtype, out, cd.ws))}
+            if n <= 1 << 24 and n >= 4:  # the searched CSR form too (the search result comes back to the host)
+                stream, p, res = B.compress_with_search(x, Q, w.freq_bits, w.n_streams, w.chunk_syms)
+                sym = torch.empty(n, dtype=torch.uint8, device="cuda")
+                cq = B.Codec(pd, n)
+                row["quantise_us"] = _p50(torch, lambda: B.rans_quantize(x, n, pd, sym, cq.qinfo, cq.ws))
+                rc, wsb = B.rans_search_workspace_bytes(n, Q)
+                ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+                rr = torch.zeros(C.sizeof(B.ReshapeResult), dtype=torch.uint8, device="cuda")
+                row["search_us"] = _p50(torch, lambda: B.rans_search_reshape(sym, n, Q, rr, ws))
+                ce = B.Codec(p, n)
+                ce.qinfo.copy_(cq.qinfo)
+                row["csr_encode_us"] = _p50(torch, lambda: B.rans_encode(sym, n, p, ce.qinfo, ce.stream, ce.nbytes, ce.ws))
+                nb = int(ce.nbytes.item())
+                hc = ce.header(nb)
+                row["csr_decompress_us"] = _p50(torch, lambda: B.rans_decompress(ce.stream, nb, hc, w.in_dtype, out, ce.ws))
+                row.update({"csr_bytes": stream.numel(), "csr_rows": int(res.rows), "csr_cols": int(res.cols)})
+            rows.append(row)
+        print(json.dumps({"sweep": "bits", "workload": name, "rows": rows}))
+        return
+    # Eq. 8: T(N) = alpha_enc T_enc(N) + alpha_dec T_dec(N) + T_tot(N) over the whole domain of Algorithm 1
+    w = synth.workload(name, 1)
+    x = synth.make(w).cuda()
+    n = w.numel
+    pd = B.params_of(w)
+    cq = B.Codec(pd, n)
+    sym = torch.empty(n, dtype=torch.uint8, device="cuda")
+    cq.quantize(x.reshape(-1), sym)
+    res = B.search_reshape(sym, w.q_bits)
+    out = torch.empty(n, dtype=x.dtype, device="cuda")
+    for k in range(res.n_candidates):
+        N = int(res.cand_rows[k])
+        p = B.make_params(w.q_bits, w.freq_bits, N, n // N, B.MODE_CSR, w.n_streams, w.chunk_syms, w.in_dtype)
+        ce = B.Codec(p, n)
+        ce.qinfo.copy_(cq.qinfo)
+        nb = ce.encode(sym)
+        hc = ce.header(nb)
+        rows.append({"N": N, "K": n // N, "len_D": int(hc.len_d), "T_tot_bits": round(float(res.cand_cost[k]), 1),
+                     "container_bytes": nb,
+                     "T_enc_us": _p50(torch, lambda: B.rans_encode(sym, n, p, ce.qinfo, ce.stream, ce.nbytes, ce.ws)),
+                     "T_dec_us": _p50(torch, lambda: B.rans_decompress(ce.stream, nb, hc, w.in_dtype, out, ce.ws))})
+    calib = torch.empty_like(x)
+    copy_us = _p50(torch, lambda: calib.copy_(x))
+    best = {}
+    for alpha in (0.0, 100.0, 10000.0):  # bits per microsecond of coding time (the rate of the link)
+        best[str(alpha)] = min(rows, key=lambda r: r["T_tot_bits"] + alpha * (r["T_enc_us"] + r["T_dec_us"]))["N"]
+    print(json.dumps({"sweep": "reshape", "workload": name, "q_bits": w.q_bits, "chosen_by_algorithm_1": int(res.rows),
+                      "n_evaluated": int(res.n_evaluated), "argmin_N_for_alpha_bits_per_us": best,
+                      "binary_serialisation": {"bytes": n * x.element_size(), "copy_us": copy_us}, "rows": rows}))
 
 
 if __name__ == "__main__":

@@ -561,6 +561,10 @@ struct NormArgs {
   int dense;
   uint8_t *out;
   uint64_t cap;
+  // The extrema, when the kernel that builds the table has computed them itself (set inside that kernel;
+  // the control block's copy was then written by another of its work-groups and is not read).
+  int mm_given;
+  float x_min, x_max;
 };
 // Container header (fixed part) and the geometry the later kernels read from the control block.
 __device__ void write_header(const CtlRef &ctl, const NormArgs &na, uint64_t len_d, uint64_t n_chunks, uint64_t dir_off,
@@ -581,8 +585,8 @@ __device__ void write_header(const CtlRef &ctl, const NormArgs &na, uint64_t len
   st32(out + 48, p.n_streams);
   st32(out + 52, p.chunk_syms);
   st32(out + 56, (uint32_t)n_chunks);
-  st32(out + 60, __float_as_uint(ctl->x_min));
-  st32(out + 64, __float_as_uint(ctl->x_max));
+  st32(out + 60, __float_as_uint(na.mm_given ? na.x_min : ctl->x_min));
+  st32(out + 64, __float_as_uint(na.mm_given ? na.x_max : ctl->x_max));
   for (uint32_t o = 68; o < kHdrBytes; o += 4) st32(out + o, 0u);
 }
 
@@ -993,6 +997,11 @@ __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRe
   if (threadIdx.x == 0) s_ticket = __hip_atomic_fetch_add(&ctl->hist_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
   if (s_ticket != gridDim.x - 1) return;
+  if (part) {  // every work-group has computed the extrema itself
+    na.mm_given = 1;
+    na.x_min = qi.x_min;
+    na.x_max = qi.x_max;
+  }
   if (na.A <= kNormWaveA) {
     if (threadIdx.x < 64) normalize_wave(ctl, na);
   } else if constexpr (NT == kBig) {
@@ -1129,6 +1138,7 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
     for (uint32_t a = threadIdx.x; a < A; a += kWG) hist[a] = 0;
     __syncthreads();
   }
+  uint32_t seen = 0;
   for (uint32_t i = blockIdx.x * kWG + threadIdx.x; i < N; i += gridDim.x * kWG) {
     uint32_t e1 = row_end[i], e0 = i ? row_end[i - 1] : 0;
     uint32_t ri = e1 - e0;
@@ -1137,10 +1147,10 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
     else atomicAdd(&cnt[ri], 1u);
     if (i == N - 1) {
       ctl->nnz = e1;
-      __hip_atomic_store(&ctl->len_d, 2ull * e1 + N, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // an exchange, for its returned value (see below): l_D has to be in place before this work-group's ticket
+      seen |= (uint32_t)__hip_atomic_exchange(&ctl->len_d, 2ull * e1 + N, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
-  uint32_t seen = 0;
   if (LDS_HIST) {
     __syncthreads();
     for (uint32_t a = threadIdx.x; a < A; a += kWG) {

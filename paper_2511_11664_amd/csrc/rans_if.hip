@@ -3122,7 +3122,10 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       LAUNCH_CHECK();
       uint32_t N = (uint32_t)p.rows;
       uint32_t g = (N + kWG - 1) / kWG;
-      g = g > 128 ? 128 : g;  // few work-groups: each ends with additions to the same few addresses and a ticket
+      // few work-groups: each ends with additions to the same few addresses and a ticket; more only when a
+      // lane would otherwise walk very many rows
+      const uint32_t g_cap = N > (1u << 20) ? 512u : 128u;
+      g = g > g_cap ? g_cap : g;
       const int fold = A <= kNormWaveA;  // one wave of the last work-group can build the table
       const NormArgs na = norm_args(p, L, ws, n, d_stream, cap);
       if (lds_hist)

@@ -128,6 +128,11 @@ CSR_CASES = [
     (40000, 1, torch.float32, 8, 12, 64, 640),
     (2, 65535, torch.float32, 8, 15, 64, 0),
     (200000, 5, torch.float32, 8, 12, 64, 256),
+    # the coder's LDS staging of D with an 8-byte-entry table (alphabet between 1024 and 8192), and one chunk of
+    # thousands of rows (many 16-row tiles, ragged first tile, all three parts of D inside one chunk)
+    (50, 3000, torch.float32, 8, 13, 64, 640),
+    (3000, 64, torch.float16, 8, 12, 64, 0),
+    (3000, 64, torch.float32, 6, 12, 128, 128 * 200),
 ]
 
 

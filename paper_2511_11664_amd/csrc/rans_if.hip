@@ -2657,36 +2657,62 @@ __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const u
     return;
   }
   bool bad = false;
-  // a lane per nonzero, eight of them per step with all their loads issued first (the loads of one
-  // nonzero after the other would leave the kernel waiting on memory latency); the row of a nonzero by
-  // bisection of the local offsets
-  constexpr int kU = 8;
-  for (uint32_t j0 = 0; j0 < cnt_here; j0 += kWG * kU) {
-    uint32_t v[kU], c[kU], cp[kU];
+  // A lane takes runs of eight consecutive nonzeros (their values and column indices come with one 16-byte
+  // load each, 2-byte aligned: where c starts inside D depends on the number of nonzeros), two runs per step
+  // with all loads issued first.  The row of a run's first nonzero is found by bisection of the local offsets,
+  // the rows of the others by walking on from there.
+  constexpr int kU = 2;
+  const uint16_t *Dv = D + base, *Dc = D + (uint64_t)nnz + base;
+  for (uint32_t m0 = 0; 8 * m0 < cnt_here; m0 += kWG * kU) {
+    uint32_t vw[kU][4], cw[kU][4], cp[kU];
 #pragma unroll
     for (int u = 0; u < kU; u++) {
-      const uint32_t j = j0 + u * kWG + threadIdx.x;
-      v[u] = c[u] = cp[u] = 0;
-      if (j < cnt_here) {
-        v[u] = D[base + j];
-        c[u] = D[(uint64_t)nnz + base + j];
-        if (j) cp[u] = D[(uint64_t)nnz + base + j - 1];
+      const uint32_t j = 8 * (m0 + u * kWG + threadIdx.x);
+      cp[u] = 0;
+#pragma unroll
+      for (int k = 0; k < 4; k++) vw[u][k] = cw[u][k] = 0;
+      if (j + 8 <= cnt_here) {
+        __builtin_memcpy(vw[u], Dv + j, 16);
+        __builtin_memcpy(cw[u], Dc + j, 16);
+      } else {
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+          if (j + k < cnt_here) {
+            vw[u][k >> 1] |= (uint32_t)Dv[j + k] << (16 * (k & 1));
+            cw[u][k >> 1] |= (uint32_t)Dc[j + k] << (16 * (k & 1));
+          }
+        }
       }
+      if (j && j < cnt_here) cp[u] = Dc[j - 1];
     }
 #pragma unroll
     for (int u = 0; u < kU; u++) {
-      const uint32_t j = j0 + u * kWG + threadIdx.x;
-      if (j < cnt_here) {
-        uint32_t lo = 0, hi = rows;  // largest local row with roff[row] <= j (roff[rows] = cnt_here > j)
+      const uint32_t j0 = 8 * (m0 + u * kWG + threadIdx.x);
+      if (j0 < cnt_here) {
+        uint32_t lo = 0, hi = rows;  // largest local row with roff[row] <= j0 (roff[rows] = cnt_here > j0)
         while (hi - lo > 1) {
           const uint32_t mid = (lo + hi) >> 1;
-          if (roff[mid] <= j) lo = mid;
+          if (roff[mid] <= j0) lo = mid;
           else hi = mid;
         }
-        bool b = v[u] == 0 || v[u] >= (1u << q_bits) || c[u] >= K;
-        if (j > roff[lo] && cp[u] >= c[u]) b = true;
-        if (b) bad = true;
-        else dense[lo * K + c[u]] = (uint8_t)v[u];
+        uint32_t row = lo, row_beg = roff[lo], row_end = roff[lo + 1], prev_c = cp[u];
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+          const uint32_t j = j0 + k;
+          if (j < cnt_here) {
+            while (j >= row_end) {  // ends: row_end of the last row is cnt_here > j
+              row++;
+              row_beg = row_end;
+              row_end = roff[row + 1];
+            }
+            const uint32_t vv = (vw[u][k >> 1] >> (16 * (k & 1))) & 0xffffu, cc = (cw[u][k >> 1] >> (16 * (k & 1))) & 0xffffu;
+            bool b = vv == 0 || vv >= (1u << q_bits) || cc >= K;
+            if (j > row_beg && prev_c >= cc) b = true;
+            if (b) bad = true;
+            else dense[row * K + cc] = (uint8_t)vv;
+            prev_c = cc;
+          }
+        }
       }
     }
   }

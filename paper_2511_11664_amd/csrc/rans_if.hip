@@ -74,6 +74,7 @@ struct Layout {
   size_t dec_lut, dec_tab, dec_F, D, row_off;
   size_t total;
   uint32_t A, nc_max, capw, n_blk;
+  uint32_t cnt_rep;  // partial histograms behind the histogram of D (CSR mode with an LDS-sized alphabet), else 0
   uint32_t n_pub;  // work-groups of the encoder when it also places its words (0: separate gather kernel)
   uint64_t len_max, chunk_len_max;
 };
@@ -105,6 +106,7 @@ int check_params(const rans_params *p, uint64_t n) {
   return RANS_OK;
 }
 
+constexpr uint32_t kCntRep = 8;  // partial histograms the CSR kernels spread their same-address additions over
 constexpr uint32_t kCsrTile = kWG * 16;  // elements per tile in the CSR count / compact kernels
 constexpr uint32_t kDenseTileCells = 16384; // symbols per tile of the CSR-to-dense kernel (one row if a row is larger)
 constexpr uint32_t kCompactBlocks = 1024;  // work-groups of the compact kernel (persistent over tiles)
@@ -126,7 +128,8 @@ Layout make_layout(const rans_params &p, uint64_t n) {
   };
   L.ctl = take(sizeof(Ctl));
   L.mm_part = take(kMaxParts * 16);
-  L.cnt = take((size_t)L.A * 4);
+  L.cnt_rep = (p.mode == RANS_MODE_CSR && L.A <= kLdsHistMaxA) ? kCntRep : 0;
+  L.cnt = take((size_t)L.A * 4 * (1 + L.cnt_rep));
   L.fq = take((size_t)L.A * 4);
   L.enc_tab = take((size_t)L.A * 8);
   L.enc_tab4 = take((size_t)L.A * 16);
@@ -241,6 +244,13 @@ __device__ __forceinline__ uint64_t lane63_64(uint64_t v) {  // the value lane 6
   const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, 63);
   const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), 63);
   return ((uint64_t)hi << 32) | lo;
+}
+
+// Work-group barrier that orders LDS accesses only: outstanding global loads and stores stay in flight.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // Sum / max over a work-group of NT threads; every thread receives the result.
@@ -551,7 +561,9 @@ __device__ __forceinline__ uint64_t ld64(const uint8_t *p) { return (uint64_t)ld
 // largest-f symbols pay a deficit, lowest index on ties), F = exclusive cumulative
 // sum, encoder table {reciprocal, f | F << 16}, container header and table.
 struct NormArgs {
-  const uint32_t *cnt;
+  const uint32_t *cnt;      // histogram of D; n_rep partial histograms of A words each follow it (their sum counts)
+  uint32_t n_rep;
+  const uint32_t *lds_cnt;  // the folded counts in LDS, when the calling kernel has put them there (set inside it)
   uint32_t *fq;
   uint2 *enc_tab;
   uint4 *enc_tab4;
@@ -566,6 +578,14 @@ struct NormArgs {
   int mm_given;
   float x_min, x_max;
 };
+// Count of symbol a: the histogram's entry plus those of the partial histograms behind it.
+__device__ __forceinline__ uint32_t hist_count(const NormArgs &na, uint32_t a) {
+  if (na.lds_cnt) return na.lds_cnt[a];
+  uint32_t c = __hip_atomic_load(na.cnt + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (uint32_t k = 1; k <= na.n_rep; k++)
+    c += __hip_atomic_load(na.cnt + (size_t)k * na.A + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return c;
+}
 // Container header (fixed part) and the geometry the later kernels read from the control block.
 __device__ void write_header(const CtlRef &ctl, const NormArgs &na, uint64_t len_d, uint64_t n_chunks, uint64_t dir_off,
                              uint64_t payload_off) {
@@ -634,7 +654,6 @@ __device__ __forceinline__ int emit_entries(const NormArgs &na, uint32_t a, uint
 }
 
 __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
-  const uint32_t *cnt = na.cnt;
   uint32_t *fq = na.fq;
   uint2 *enc_tab = na.enc_tab;
   uint4 *enc_tab4 = na.enc_tab4;
@@ -651,7 +670,7 @@ __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
   if (get_status(ctl) != 0) return;  // uniform: written by an earlier kernel
   uint64_t len_loc = 0, present_loc = 0;
   for (uint32_t a = threadIdx.x; a < A; a += kBig) {
-    uint32_t c = __hip_atomic_load(cnt + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t c = hist_count(na, a);
     len_loc += c;
     present_loc += c != 0;
   }
@@ -668,7 +687,7 @@ __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
   // first estimate and its sum
   uint64_t sum_loc = 0, best_cnt = 0;
   for (uint32_t a = threadIdx.x; a < A; a += kBig) {
-    uint32_t c = __hip_atomic_load(cnt + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t c = hist_count(na, a);
     uint32_t f = 0;
     if (c) {
       uint64_t q = ((uint64_t)c * total + len / 2) / len;
@@ -759,7 +778,7 @@ __device__ void normalize_wave_per(const CtlRef &ctl, const NormArgs &na) {
 #pragma unroll
   for (int q = 0; q < PER; q++) {
     const uint32_t a = PER * lane + q;
-    c[q] = a < A ? __hip_atomic_load(na.cnt + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+    c[q] = a < A ? hist_count(na, a) : 0;
   }
   uint64_t lp = 0;  // l_D in the low 40 bits, the number of present symbols above
 #pragma unroll
@@ -1050,7 +1069,8 @@ __global__ __launch_bounds__(kBig) void k_scan_u32(uint32_t *a, uint32_t n) {
 template <bool LDS_HIST>
 __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_t n, int aligned, uint32_t K,
                                                      const uint32_t *blk_nnz, uint8_t *v, uint16_t *c,
-                                                     uint32_t *row_end, uint32_t *cnt, uint32_t A, uint32_t n_tiles) {
+                                                     uint32_t *row_end, uint32_t *cnt, uint32_t A, uint32_t n_tiles,
+                                                     uint32_t n_rep) {
   extern __shared__ uint32_t hist[];
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
@@ -1121,9 +1141,12 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
     __syncthreads();  // staging and scan scratch are reused by the next tile
   }
   if (LDS_HIST) {
+    // into one of the partial histograms: a thousand work-groups adding to the same few hundred addresses
+    // would keep the kernel busy long after its last tile
+    uint32_t *dst = cnt + (n_rep ? (size_t)(1 + blockIdx.x % n_rep) * A : 0);
     for (uint32_t a = threadIdx.x; a < A; a += kWG) {
       uint32_t t = hist[a];
-      if (t) atomicAdd(&cnt[a], t);
+      if (t) atomicAdd(&dst[a], t);
     }
   }
 }
@@ -1151,30 +1174,49 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
       seen |= (uint32_t)__hip_atomic_exchange(&ctl->len_d, 2ull * e1 + N, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
+  const bool hand_over = fold_norm || na.n_rep;  // the last work-group reads what the others added
   if (LDS_HIST) {
     __syncthreads();
+    uint32_t *dst = cnt + (na.n_rep ? (size_t)(1 + blockIdx.x % na.n_rep) * A : 0);
     for (uint32_t a = threadIdx.x; a < A; a += kWG) {
       uint32_t t = hist[a];
-      // with the table build folded in, the additions return their old value: a returned value is the only
-      // proof that an addition has been performed before the work-group takes its ticket
+      // before a hand-over the additions return their old value: a returned value is the only proof that an
+      // addition has been performed before the work-group takes its ticket
       if (t) {
-        if (fold_norm) seen |= atomicAdd(&cnt[a], t);
-        else atomicAdd(&cnt[a], t);
+        if (hand_over) seen |= atomicAdd(&dst[a], t);
+        else atomicAdd(&dst[a], t);
       }
     }
   }
-  if (!fold_norm) return;
+  if (!hand_over) return;
   if (seen == 0xffffffffu) set_status(ctl, RANS_ERR_HIP);  // cannot happen (counts are below 2^31); keeps the values in use
-  // D's histogram is complete once every work-group has added its row counts: the last one to do so
-  // builds the frequency table (the same hand-over as at the end of k_quant_hist).  It also reads len_d,
-  // which the work-group holding the last row stored (device-scope atomic) before the barrier ahead of
-  // its ticket.
+  // D's histogram is complete once every work-group has added its row counts: the last one to do so folds
+  // the partial histograms and, if asked to, builds the frequency table (the same hand-over as at the end of
+  // k_quant_hist).  It also reads len_d, which the work-group holding the last row exchanged in before the
+  // barrier ahead of its ticket.
   __shared__ uint32_t s_ticket;
+  __shared__ uint32_t s_cnt[kNormWaveA];
   __syncthreads();
   if (threadIdx.x == 0) s_ticket = __hip_atomic_fetch_add(&ctl->hist_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
   if (s_ticket != gridDim.x - 1) return;
-  if (threadIdx.x < 64) normalize_wave(ctl, na);
+  if (na.n_rep) {  // all loads of a lane in flight together
+    for (uint32_t a0 = threadIdx.x; a0 < A; a0 += kWG) {
+      uint32_t part_c[kCntRep + 1];
+#pragma unroll
+      for (uint32_t k = 0; k <= kCntRep; k++)
+        part_c[k] = k <= na.n_rep ? __hip_atomic_load(cnt + (size_t)k * A + a0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+      uint32_t sum = 0;
+#pragma unroll
+      for (uint32_t k = 0; k <= kCntRep; k++) sum += part_c[k];
+      if (!fold_norm) cnt[a0] = sum;  // for k_normalize
+      if (a0 < kNormWaveA) s_cnt[a0] = sum;
+    }
+    lds_barrier();
+    na.n_rep = 0;
+    if (A <= kNormWaveA) na.lds_cnt = s_cnt;
+  }
+  if (fold_norm && threadIdx.x < 64) normalize_wave(ctl, na);
 }
 
 // ------------------------------------------------------------------ kernels: rANS encode
@@ -1277,12 +1319,6 @@ __device__ __forceinline__ EncEntry load_entry(const uint2 *g_tab, const uint32_
 // published its own (those were dispatched earlier and never wait for a higher index, so the wait ends;
 // it is bounded all the same and turns into RANS_ERR_HIP if the bound is hit), and derives the chunk's
 // byte offset and its own position inside the chunk from those totals.
-// Work-group barrier that orders LDS accesses only: outstanding global loads and stores stay in flight.
-__device__ __forceinline__ void lds_barrier() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-  __builtin_amdgcn_s_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
 constexpr int kSpinMax = 1 << 18;
 constexpr uint32_t kEncTileBytes = 16384;  // LDS tile of the fused placement (overlays ring and table)
 __device__ __forceinline__ uint32_t wait_published(const uint32_t *pub, uint32_t i, const CtlRef &ctl) {
@@ -3070,7 +3106,7 @@ inline uint32_t *tile_counts_of(const Layout &L, uint8_t *ws) {
 }
 
 NormArgs norm_args(const rans_params &p, const Layout &L, uint8_t *ws, uint64_t n, uint8_t *d_stream, size_t cap) {
-  return NormArgs{(const uint32_t *)(ws + L.cnt), (uint32_t *)(ws + L.fq), (uint2 *)(ws + L.enc_tab),
+  return NormArgs{(const uint32_t *)(ws + L.cnt), L.cnt_rep, nullptr, (uint32_t *)(ws + L.fq), (uint2 *)(ws + L.enc_tab),
                   (uint4 *)(ws + L.enc_tab4), L.A, p, n, p.mode == RANS_MODE_CSR ? 0 : 1, d_stream, (uint64_t)cap};
 }
 
@@ -3090,16 +3126,16 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
   if (n) {
     uint32_t g = n_part = grid_for(n, kWG * V * 4, kMaxParts);
     if (f16) {
-      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, part, ctl, cnt, L.A, cw_, ncz_);
-      else PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, part, ctl, cnt, L.A, cw_, ncz_);
+      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, true>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, part, ctl, cnt, L.A * (1 + L.cnt_rep), cw_, ncz_);
+      else PROF_LAUNCH(KID_MINMAX, (k_minmax<__half, false>), dim3(g), dim3(kWG), 0, st, (const __half *)d_x, (uint32_t)n, part, ctl, cnt, L.A * (1 + L.cnt_rep), cw_, ncz_);
     } else {
-      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, part, ctl, cnt, L.A, cw_, ncz_);
-      else PROF_LAUNCH(KID_MINMAX, (k_minmax<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, part, ctl, cnt, L.A, cw_, ncz_);
+      if (vec) PROF_LAUNCH(KID_MINMAX, (k_minmax<float, true>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, part, ctl, cnt, L.A * (1 + L.cnt_rep), cw_, ncz_);
+      else PROF_LAUNCH(KID_MINMAX, (k_minmax<float, false>), dim3(g), dim3(kWG), 0, st, (const float *)d_x, (uint32_t)n, part, ctl, cnt, L.A * (1 + L.cnt_rep), cw_, ncz_);
     }
     LAUNCH_CHECK();
   }
   if (!n) {  // empty tensor: only the bookkeeping and the (zero) quantiser parameters
-    PROF_LAUNCH(KID_QINFO, k_qinfo, dim3(1), dim3(kBig), 0, st, ctl, part, n_part, p.q_bits, d_qinfo, cnt, L.A, cw_, ncz_);
+    PROF_LAUNCH(KID_QINFO, k_qinfo, dim3(1), dim3(kBig), 0, st, ctl, part, n_part, p.q_bits, d_qinfo, cnt, L.A * (1 + L.cnt_rep), cw_, ncz_);
     LAUNCH_CHECK();
   }
   if (n) {
@@ -3141,10 +3177,10 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       const uint32_t g_compact = L.n_blk < kCompactBlocks ? L.n_blk : kCompactBlocks;
       if (lds_hist)
         PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true>), dim3(g_compact), dim3(kWG), A * 4, st, d_sym, (uint32_t)n, al,
-                           (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk);
+                           (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, L.cnt_rep);
       else
         PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<false>), dim3(g_compact), dim3(kWG), 0, st, d_sym, (uint32_t)n, al,
-                           (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk);
+                           (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, L.cnt_rep);
       LAUNCH_CHECK();
       uint32_t N = (uint32_t)p.rows;
       uint32_t g = (N + kWG - 1) / kWG;
@@ -3163,7 +3199,9 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     }
   }
   if (!table_done) {  // else the histogram kernel has built the table
-    PROF_LAUNCH(KID_NORMALIZE, k_normalize, dim3(1), dim3(kBig), 0, st, ctl, norm_args(p, L, ws, n, d_stream, cap));
+    NormArgs na_k = norm_args(p, L, ws, n, d_stream, cap);
+    if (csr && n) na_k.n_rep = 0;  // k_csr_rows has folded the partial histograms
+    PROF_LAUNCH(KID_NORMALIZE, k_normalize, dim3(1), dim3(kBig), 0, st, ctl, na_k);
     LAUNCH_CHECK();
   }
   const uint32_t groups = (S + kWG - 1) / kWG;
@@ -3624,7 +3662,7 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
   const uint32_t seq = next_seq();
   const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   PROF_LAUNCH(KID_QINFO, k_qinfo_from_user, dim3(1), dim3(kBig), 0, st, ctl, d_qinfo, p->q_bits,
-              (uint32_t *)(ws + L.cnt), L.A, (uint32_t *)(ws + L.chunk_words), counter_words(L));
+              (uint32_t *)(ws + L.cnt), L.A * (1 + L.cnt_rep), (uint32_t *)(ws + L.chunk_words), counter_words(L));
   LAUNCH_CHECK();
   if (n_elems) {
     const bool vec = aligned_to(d_sym, 16);

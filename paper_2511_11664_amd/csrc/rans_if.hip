@@ -109,7 +109,7 @@ int check_params(const rans_params *p, uint64_t n) {
 constexpr uint32_t kCntRep = 8;  // partial histograms the CSR kernels spread their same-address additions over
 constexpr uint32_t kCsrTile = kWG * 16;  // elements per tile in the CSR count / compact kernels
 constexpr uint32_t kDenseTileCells = 16384; // symbols per tile of the CSR-to-dense kernel (one row if a row is larger)
-constexpr uint32_t kCompactBlocks = 1024;  // work-groups of the compact kernel (persistent over tiles)
+constexpr uint32_t kCompactBlocks = 2048;  // work-groups of the compact kernel (persistent over tiles)
 
 Layout make_layout(const rans_params &p, uint64_t n) {
   Layout L{};
@@ -917,9 +917,13 @@ __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRe
   fd.init(s);
   const uint32_t rep = threadIdx.x & (kHistRep - 1);
   const uint32_t tile = NT * V * kQIter;
-  // CSR: the nonzeros of each tile of kCsrTile symbols are counted on the way.  A wave's symbols of one step
-  // lie in one tile: the lanes' counts are summed with a wave scan and the last lane adds the sum to the
-  // tile's global counter.
+  // CSR: the nonzeros of each tile of kCsrTile symbols are counted on the way.  A work-group's tile of
+  // NT * V * kQIter elements is V such tiles and a wave's symbols of one step lie in one of them: the lanes'
+  // counts are summed with a wave scan, the last lane adds the sum to the tile's LDS counter, and after the
+  // work-group's tile the counters go out with plain stores (every tile is counted by exactly one work-group).
+  __shared__ uint32_t s_nz[16];
+  static_assert(V <= 16, "one LDS counter per tile of kCsrTile symbols");
+  if (CSR && threadIdx.x < 16) s_nz[threadIdx.x] = 0;  // ordered by the barrier below
   uint32_t lane_nz = 0;
   auto bump = [&](uint32_t a) {
     atomicAdd(&h[a * kHistRep + rep], 1u);
@@ -933,7 +937,7 @@ __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRe
     return (uint32_t)__builtin_amdgcn_fmed3f(r, 0.0f, levels);
   };
   // a work-group walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... and flushes its histogram once
-  for (uint64_t base = (uint64_t)blockIdx.x * tile; base < n; base += (uint64_t)gridDim.x * tile)
+  for (uint64_t base = (uint64_t)blockIdx.x * tile; base < n; base += (uint64_t)gridDim.x * tile) {
 #pragma unroll
   for (int it = 0; it < kQIter; it++) {
     uint64_t e0 = base + ((uint64_t)it * NT + threadIdx.x) * V;
@@ -982,9 +986,20 @@ __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRe
     if constexpr (CSR) {  // every lane of the wave is here; lane 0 holds the wave's lowest element
       const uint32_t wave_nz = wave_incl_sum_scan(lane_nz);
       lane_nz = 0;
-      const uint32_t tile_of_wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(e0 / kCsrTile));
-      if ((threadIdx.x & 63) == 63 && wave_nz) atomicAdd(&blk_nnz[tile_of_wave], wave_nz);
+      const uint32_t slot = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((e0 - base) / kCsrTile));
+      if ((threadIdx.x & 63) == 63 && wave_nz) atomicAdd(&s_nz[slot], wave_nz);
     }
+  }
+  if constexpr (CSR) {
+    __syncthreads();
+    if (threadIdx.x < V) {
+      const uint64_t t_idx = base / kCsrTile + threadIdx.x;
+      const uint32_t c_t = s_nz[threadIdx.x];
+      s_nz[threadIdx.x] = 0;
+      if (t_idx * kCsrTile < n) blk_nnz[t_idx] = c_t;
+    }
+    __syncthreads();
+  }
   }
   };  // run
   if (fast) run(std::true_type{});

@@ -1,0 +1,186 @@
+// rans_csr.h -- modified CSR, encode side (Sec. 3.1 "Modified CSR Encoding"): compaction, row counts
+//
+// Part of the one translation unit rans_if.hip (included there, in this order); not a stand-alone header.
+#pragma once
+
+#include "rans_quant.h"
+
+namespace {
+
+// ------------------------------------------------------------------ kernels: modified CSR
+
+__device__ __forceinline__ void load16(const uint8_t *p, uint64_t e0, uint64_t n, bool aligned, uint8_t out[16]) {
+  if (aligned && e0 + 16 <= n) {
+    uint4 w = *(const uint4 *)(p + e0);
+    uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int k = 0; k < 16; k++) out[k] = (uint8_t)(ww[k >> 2] >> (8 * (k & 3)));
+  } else {
+#pragma unroll
+    for (int k = 0; k < 16; k++) out[k] = (e0 + k < n) ? p[e0 + k] : (uint8_t)0;
+  }
+}
+
+// Stream compaction of the nonzero symbols in flat (= row-major) order: v gets the
+// values, c the column indices, row_end[i] the number of nonzeros up to and
+// including row i.  Column indices are histogrammed into cnt on the way.
+// A work-group walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...: a tile's nonzeros are
+// compacted in LDS first and leave with consecutive lanes on consecutive entries, and the
+// column histogram is added to the global one once at the end (few work-groups: same-address
+// global atomics are what costs here).  blk_nnz[t] is the number of nonzeros of tile t (counted by
+// k_quant_hist); a tile's place in v and c is the sum over the tiles before it, which the work-group
+// adds up itself.
+template <bool LDS_HIST>
+__global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_t n, int aligned, uint32_t K,
+                                                     const uint32_t *blk_nnz, uint8_t *v, uint16_t *c,
+                                                     uint32_t *row_end, uint32_t *cnt, uint32_t A, uint32_t n_tiles,
+                                                     uint32_t n_rep) {
+  extern __shared__ uint32_t hist[];
+  __shared__ uint32_t sh[kWG / 64];
+  __shared__ uint64_t sh64[kWG / 64];
+  __shared__ uint8_t s_v[kCsrTile];
+  __shared__ uint16_t s_c[kCsrTile];
+  if (LDS_HIST) {
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) hist[a] = 0;
+  }
+  // where the work-group's tile starts in v and c: the nonzeros of all tiles before it (k_quant_hist has
+  // counted them), kept up to date from tile to tile with the counts of the tiles in between
+  uint32_t base;
+  {
+    uint64_t part = 0;
+    for (uint32_t u0 = threadIdx.x; u0 < blockIdx.x; u0 += 4 * kWG) {
+      uint32_t x4[4];
+#pragma unroll
+      for (int k = 0; k < 4; k++) x4[k] = u0 + k * kWG < blockIdx.x ? blk_nnz[u0 + k * kWG] : 0u;
+#pragma unroll
+      for (int k = 0; k < 4; k++) part += x4[k];
+    }
+    base = (uint32_t)block_sum64<kWG>(part, sh64);
+  }
+  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const uint64_t e0 = (uint64_t)tile * kCsrTile + threadIdx.x * 16;
+    uint8_t b[16];
+    load16(sym, e0, n, aligned, b);
+    uint32_t cth = 0;
+#pragma unroll
+    for (int k = 0; k < 16; k++) cth += b[k] != 0;
+    uint32_t tot;
+    uint32_t loc = block_excl_scan<kWG>(cth, sh, &tot);  // also orders the hist zeroing and the staging reuse
+    if (e0 < n) {
+      uint32_t row = (uint32_t)(e0 / K), col = (uint32_t)(e0 - (uint64_t)row * K);
+#pragma unroll
+      for (int k = 0; k < 16; k++) {
+        if (e0 + k < n) {
+          if (b[k]) {
+            s_v[loc] = b[k];
+            s_c[loc] = (uint16_t)col;
+            loc++;
+            if (LDS_HIST) atomicAdd(&hist[col], 1u);
+            else atomicAdd(&cnt[col], 1u);
+          }
+          if (++col == K) {
+            row_end[row] = base + loc;
+            col = 0;
+            row++;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < tot; i += kWG) {
+      v[base + i] = s_v[i];
+      c[base + i] = s_c[i];
+    }
+    if (tile + gridDim.x < n_tiles) {  // uniform
+      uint64_t skip = 0;
+      for (uint32_t u0 = tile + threadIdx.x; u0 < tile + gridDim.x; u0 += 4 * kWG) {
+        uint32_t x4[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) x4[k] = u0 + k * kWG < tile + gridDim.x ? blk_nnz[u0 + k * kWG] : 0u;
+#pragma unroll
+        for (int k = 0; k < 4; k++) skip += x4[k];
+      }
+      base += (uint32_t)block_sum64<kWG>(skip, sh64);
+    }
+    __syncthreads();  // staging and scan scratch are reused by the next tile
+  }
+  if (LDS_HIST) {
+    // into one of the partial histograms: a thousand work-groups adding to the same few hundred addresses
+    // would keep the kernel busy long after its last tile
+    uint32_t *dst = cnt + (n_rep ? (size_t)(1 + blockIdx.x % n_rep) * A : 0);
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) {
+      uint32_t t = hist[a];
+      if (t) atomicAdd(&dst[a], t);
+    }
+  }
+}
+
+// r[i] = row_end[i] - row_end[i-1] (the NON-cumulative row count), histogrammed.  Work-groups stride
+// over the rows and add their histogram to the global one once.
+template <bool LDS_HIST>
+__global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint32_t N, uint16_t *r, uint32_t *cnt,
+                                                  uint32_t A, CtlRef ctl, int fold_norm, NormArgs na) {
+  extern __shared__ uint32_t hist[];
+  if (LDS_HIST) {
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) hist[a] = 0;
+    __syncthreads();
+  }
+  uint32_t seen = 0;
+  for (uint32_t i = blockIdx.x * kWG + threadIdx.x; i < N; i += gridDim.x * kWG) {
+    uint32_t e1 = row_end[i], e0 = i ? row_end[i - 1] : 0;
+    uint32_t ri = e1 - e0;
+    r[i] = (uint16_t)ri;
+    if (LDS_HIST) atomicAdd(&hist[ri], 1u);
+    else atomicAdd(&cnt[ri], 1u);
+    if (i == N - 1) {
+      ctl->nnz = e1;
+      // an exchange, for its returned value (see below): l_D has to be in place before this work-group's ticket
+      seen |= (uint32_t)__hip_atomic_exchange(&ctl->len_d, 2ull * e1 + N, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+  const bool hand_over = fold_norm || na.n_rep;  // the last work-group reads what the others added
+  if (LDS_HIST) {
+    __syncthreads();
+    uint32_t *dst = cnt + (na.n_rep ? (size_t)(1 + blockIdx.x % na.n_rep) * A : 0);
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) {
+      uint32_t t = hist[a];
+      // before a hand-over the additions return their old value: a returned value is the only proof that an
+      // addition has been performed before the work-group takes its ticket
+      if (t) {
+        if (hand_over) seen |= atomicAdd(&dst[a], t);
+        else atomicAdd(&dst[a], t);
+      }
+    }
+  }
+  if (!hand_over) return;
+  if (seen == 0xffffffffu) set_status(ctl, RANS_ERR_HIP);  // cannot happen (counts are below 2^31); keeps the values in use
+  // D's histogram is complete once every work-group has added its row counts: the last one to do so folds
+  // the partial histograms and, if asked to, builds the frequency table (the same hand-over as at the end of
+  // k_quant_hist).  It also reads len_d, which the work-group holding the last row exchanged in before the
+  // barrier ahead of its ticket.
+  __shared__ uint32_t s_ticket;
+  __shared__ uint32_t s_cnt[kNormWaveA];
+  __syncthreads();
+  if (threadIdx.x == 0) s_ticket = __hip_atomic_fetch_add(&ctl->hist_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (s_ticket != gridDim.x - 1) return;
+  if (na.n_rep) {  // all loads of a lane in flight together
+    for (uint32_t a0 = threadIdx.x; a0 < A; a0 += kWG) {
+      uint32_t part_c[kCntRep + 1];
+#pragma unroll
+      for (uint32_t k = 0; k <= kCntRep; k++)
+        part_c[k] = k <= na.n_rep ? __hip_atomic_load(cnt + (size_t)k * A + a0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+      uint32_t sum = 0;
+#pragma unroll
+      for (uint32_t k = 0; k <= kCntRep; k++) sum += part_c[k];
+      if (!fold_norm) cnt[a0] = sum;  // for k_normalize
+      if (a0 < kNormWaveA) s_cnt[a0] = sum;
+    }
+    lds_barrier();
+    na.n_rep = 0;
+    if (A <= kNormWaveA) na.lds_cnt = s_cnt;
+  }
+  if (fold_norm && threadIdx.x < 64) normalize_wave(ctl, na);
+}
+
+}  // namespace

@@ -1,0 +1,804 @@
+// rans_decode.h -- rANS decoder (Eq. 3-4), CSR expand, dequantise
+//
+// Part of the one translation unit rans_if.hip (included there, in this order); not a stand-alone header.
+#pragma once
+
+#include "rans_common.h"
+
+namespace {
+
+// ------------------------------------------------------------------ kernels: decode
+
+// One work-group: validate the header against the expected geometry, rebuild F,
+// the slot -> symbol table (Eq. 3) and the decoder table f | F << 16, recompute
+// s and z from the stored extrema.
+__global__ __launch_bounds__(kBig) void k_dec_prepare(const uint8_t *in, uint64_t bytes, CtlRef ctl, rans_header h,
+                                                      uint16_t *lut, uint32_t *tab, uint32_t *Farr,
+                                                      rans_qinfo *qout) {
+  __shared__ uint32_t sh32[kBig / 64];
+  __shared__ int s_ok;
+  const uint32_t A = h.alphabet, M = h.p.freq_bits, total = 1u << M;
+  const uint64_t table_off = kHdrBytes;
+  const uint64_t dir_off = table_off + (((uint64_t)A * 2 + 7) & ~7ull);
+  const uint64_t payload_off = dir_off + 8 * ((uint64_t)h.n_chunks + 1);
+  if (threadIdx.x == 0) {
+    bool ok = bytes >= payload_off;
+    ok = ok && ld32(in) == 0x31464952u;
+    ok = ok && ld32(in + 4) == (1u | (h.p.mode << 16) | (h.p.in_dtype << 24));
+    ok = ok && ld32(in + 8) == (h.p.q_bits | (M << 8));
+    ok = ok && ld64(in + 12) == h.n_elems && ld64(in + 20) == h.p.rows && ld64(in + 28) == h.p.cols;
+    ok = ok && ld64(in + 36) == h.len_d && ld32(in + 44) == A && ld32(in + 48) == h.p.n_streams;
+    ok = ok && ld32(in + 52) == h.p.chunk_syms && ld32(in + 56) == h.n_chunks;
+    ok = ok && ld32(in + 60) == __float_as_uint(h.x_min) && ld32(in + 64) == __float_as_uint(h.x_max);
+    if (ok)
+      for (uint32_t o = 68; o < kHdrBytes; o += 4) ok = ok && ld32(in + o) == 0;
+    if (ok) {
+      ok = ok && ld64(in + dir_off) == 0 && ld64(in + dir_off + 8ull * h.n_chunks) == bytes - payload_off;
+    }
+    s_ok = ok;
+    ctl->last_seq = ctl.seq;
+    if (!ok) set_status(ctl, RANS_ERR_CORRUPT);
+    ctl->len_d = h.len_d;
+    ctl->n_chunks = h.n_chunks;
+    ctl->dir_off = dir_off;
+    ctl->payload_off = payload_off;
+    ctl->nnz = h.p.mode == RANS_MODE_CSR ? (uint32_t)((h.len_d - h.p.rows) / 2) : 0;
+    // Eq. 6 parameters from the stored extrema, same arithmetic as on the encoding side
+    float mn = h.x_min, mx = h.x_max;
+    float range = mx - mn;
+    float s = range / (float)((1u << h.p.q_bits) - 1u);
+    float zf = eq6_zero_point(mn, s);
+    ctl->x_min = mn;
+    ctl->x_max = mx;
+    ctl->scale = s;
+    ctl->zero_point = zf;
+    if (qout) {
+      qout->x_min = mn;
+      qout->x_max = mx;
+      qout->scale = s;
+      qout->zero_point = zf;
+    }
+  }
+  __syncthreads();
+  if (!s_ok) return;
+  // F and the decoder table; marks for the slot table
+  for (uint32_t sl = threadIdx.x; sl < total; sl += kBig) lut[sl] = 0;
+  __syncthreads();
+  uint32_t carry = 0;
+  bool pad_ok = true;
+  for (uint32_t base = 0; base < A; base += kBig) {
+    uint32_t a = base + threadIdx.x;
+    uint32_t f = a < A ? *(const uint16_t *)(in + table_off + 2ull * a) : 0, tot;
+    uint32_t F = carry + block_excl_scan<kBig>(f, sh32, &tot);
+    if (a < A) {
+      tab[a] = f | (F << 16);
+      Farr[a] = F;
+      if (f && F < total) lut[F] = (uint16_t)a;  // symbols with f > 0 start at distinct slots
+    }
+    carry += tot;
+    __syncthreads();
+  }
+  for (uint64_t o = table_off + 2ull * A + 2 * threadIdx.x; o < dir_off; o += 2 * kBig)
+    pad_ok = pad_ok && *(const uint16_t *)(in + o) == 0;
+  if (!pad_ok) set_status(ctl, RANS_ERR_CORRUPT);
+  if (carry != (h.len_d ? total : 0u)) {
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  if (threadIdx.x == 0) Farr[A] = carry;
+  __syncthreads();
+  // slot table = running maximum of the marks: each thread owns a contiguous range of slots
+  const uint32_t per = (total + kBig - 1) / kBig;
+  const uint32_t s0 = threadIdx.x * per;
+  uint32_t loc = 0;
+  for (uint32_t i = 0; i < per && s0 + i < total; i++) {
+    uint32_t m = lut[s0 + i];
+    loc = m > loc ? m : loc;
+  }
+  // exclusive running maximum across threads
+  uint32_t inc = loc;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    uint32_t o = __shfl_up(inc, d);
+    if (lane >= d) inc = o > inc ? o : inc;
+  }
+  uint32_t prev = __shfl_up(inc, 1);
+  if (lane == 0) prev = 0;
+  __syncthreads();
+  if (lane == 63) sh32[w] = inc;
+  __syncthreads();
+  uint32_t run = 0;
+  for (int i = 0; i < w; i++) run = sh32[i] > run ? sh32[i] : run;
+  run = prev > run ? prev : run;
+  for (uint32_t i = 0; i < per && s0 + i < total; i++) {
+    uint32_t m = lut[s0 + i];
+    run = m > run ? m : run;
+    lut[s0 + i] = (uint16_t)run;
+  }
+}
+
+struct SinkSym {
+  uint8_t *out;
+  __device__ __forceinline__ void init(const CtlRef &) {}
+  __device__ __forceinline__ void put(uint64_t i, uint32_t x) const { out[i] = (uint8_t)x; }
+};
+struct SinkU16 {
+  uint16_t *out;
+  __device__ __forceinline__ void init(const CtlRef &) {}
+  __device__ __forceinline__ void put(uint64_t i, uint32_t x) const { out[i] = (uint16_t)x; }
+};
+// Inverse of Eq. 6 fused into the decoder: x = s * (xhat - z).
+template <typename OutT>
+struct SinkFloat {
+  OutT *out;
+  float s, zf, x_min;
+  __device__ __forceinline__ void init(const CtlRef &ctl) {
+    s = ctl->scale;
+    zf = ctl->zero_point;
+    x_min = ctl->x_min;
+  }
+  __device__ __forceinline__ void put(uint64_t i, uint32_t x) const {
+    float y = s == 0.0f ? x_min : s * ((float)x - zf);
+    if constexpr (sizeof(OutT) == 4) out[i] = y;
+    else out[i] = __float2half_rn(y);
+  }
+};
+
+// One lane per stream: slot = s mod 2^M, symbol from the slot table (Eq. 3), state
+// update (Eq. 4), refill of one 16-bit word when the state drops below 2^16.  All
+// sizes and offsets taken from the container are checked before use.
+template <class Sink, bool LDS_TAB>
+__global__ __launch_bounds__(kWG) void k_decode(const uint8_t *in, uint64_t bytes, CtlRef ctl, const uint16_t *g_lut,
+                                                const uint32_t *g_tab, uint32_t A, uint32_t M, uint32_t S,
+                                                uint32_t cs, uint32_t groups, Sink sink) {
+  extern __shared__ __align__(16) uint32_t l_mem[];
+  __shared__ uint32_t sh[kWG / 64];
+  __shared__ uint64_t sh64[kWG / 64];
+  if (get_status(ctl) != 0) return;
+  const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
+  const uint32_t nc = ctl->n_chunks;
+  if (k >= nc) return;
+  sink.init(ctl);
+  const uint32_t total = 1u << M;
+  uint32_t *l_tab = l_mem;
+  uint16_t *l_lut = (uint16_t *)(l_mem + A);
+  if (LDS_TAB) {
+    for (uint32_t a = threadIdx.x; a < A; a += kWG) l_tab[a] = g_tab[a];
+    for (uint32_t i = threadIdx.x; i < total / 2; i += kWG) ((uint32_t *)l_lut)[i] = ((const uint32_t *)g_lut)[i];
+    __syncthreads();
+  }
+  const uint32_t *tab = LDS_TAB ? l_tab : g_tab;
+  const uint16_t *lut = LDS_TAB ? l_lut : g_lut;
+
+  const uint64_t payload_off = ctl->payload_off;
+  const uint64_t payload_bytes = bytes - payload_off;
+  const uint8_t *dir = in + ctl->dir_off;
+  const uint64_t o0 = ld64(dir + 8ull * k), o1 = ld64(dir + 8ull * k + 8);
+  if (o0 > o1 || o1 > payload_bytes || o1 - o0 < 8ull * S || (o0 & 3)) {
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  const uint8_t *ck = in + payload_off + o0;
+  const uint64_t ck_bytes = o1 - o0;
+  const uint64_t len = ctl->len_d;
+  const uint64_t chunk_len = cs ? cs : len;
+  const uint64_t base = (uint64_t)k * chunk_len;
+  const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
+  const uint32_t *nwk = (const uint32_t *)(ck + 4ull * S);
+  uint64_t pre_loc = 0;
+  for (uint32_t i = threadIdx.x; i < g * kWG; i += kWG) pre_loc += nwk[i];
+  const uint64_t pre = block_sum64<kWG>(pre_loc, sh64);
+  const uint32_t j = g * kWG + threadIdx.x;
+  const bool live = j < S;
+  const uint64_t n_j = (live && n_here > j) ? (n_here - j + S - 1) / S : 0;
+  uint32_t nw = live ? nwk[j] : 0;
+  bool bad = false;
+  if (nw > n_j) {
+    bad = true;
+    nw = 0;
+  }
+  uint32_t tot;
+  const uint32_t ex = block_excl_scan<kWG>(nw, sh, &tot);
+  const uint64_t w0 = pre + ex;  // index of this stream's first word inside the chunk
+  if (8ull * S + 2 * (w0 + nw) > ck_bytes) {
+    bad = true;
+    nw = 0;
+  }
+  if (live) {
+    const uint16_t *wp = (const uint16_t *)(ck + 8ull * S) + w0;
+    uint32_t s = ((const uint32_t *)ck)[j];
+    uint32_t used = 0;
+    const uint32_t mask = total - 1;
+    for (uint64_t t = 0; t < n_j; t++) {
+      bad |= s < kL;
+      uint32_t slot = s & mask;
+      uint32_t x = lut[slot];
+      uint32_t e = tab[x];
+      s = (e & 0xffffu) * (s >> M) + slot - (e >> 16);
+      if (s < kL) {
+        uint32_t w = 0;
+        if (used < nw) w = wp[used++];
+        else bad = true;
+        s = (s << 16) | w;
+      }
+      sink.put(base + j + t * S, x);
+    }
+    bad |= (s != kL) || (used != nw);
+    if (j == S - 1) {  // chunk size must be exactly header + words, padded to 4 bytes with zeros
+      uint64_t end = 8ull * S + 2 * (w0 + nw);
+      if (((end + 3) & ~3ull) != ck_bytes) bad = true;
+      else if (end != ck_bytes && *(const uint16_t *)(ck + end) != 0) bad = true;
+    }
+  }
+  if (bad) set_status(ctl, RANS_ERR_CORRUPT);
+}
+
+// ---- fast decoder: tables rebuilt per work-group in LDS, word stream read through an LDS window ----
+
+// The 128-byte header the caller expects, as 32 little-endian words.
+struct HdrImage {
+  uint32_t w[32];
+};
+
+// First wave of work-group 0 of the fast decoder: compare the header and the ends of the
+// directory with what the host expects, check the zero padding after the frequency table,
+// publish the geometry and the quantiser parameters (Eq. 6, recomputed from the stored extrema
+// with the encoder's arithmetic).  The other work-groups do not wait for this: they take the
+// geometry from the kernel arguments and report what they find themselves.
+__device__ void dec_check_header(const uint8_t *in, uint64_t bytes, const CtlRef &ctl, const HdrImage &img,
+                                 const rans_header &h, rans_qinfo *qout) {
+  const uint32_t lane = threadIdx.x;  // called by threads 0..63
+  const uint32_t A = h.alphabet;
+  const uint64_t table_off = kHdrBytes;
+  const uint64_t dir_off = table_off + (((uint64_t)A * 2 + 7) & ~7ull);
+  const uint64_t payload_off = dir_off + 8 * ((uint64_t)h.n_chunks + 1);
+  bool ok = true;
+  if (lane < 32) ok = ld32(in + 4 * lane) == img.w[lane];
+  if (lane == 32) ok = ld64(in + dir_off) == 0;
+  if (lane == 33) ok = ld64(in + dir_off + 8ull * h.n_chunks) == bytes - payload_off;
+  for (uint64_t o = table_off + 2ull * A + 2 * lane; o < dir_off; o += 128) ok = ok && *(const uint16_t *)(in + o) == 0;
+  const bool all_ok = __ballot(!ok) == 0;
+  if (lane != 0) return;
+  ctl->last_seq = ctl.seq;
+  if (!all_ok) set_status(ctl, RANS_ERR_CORRUPT);
+  ctl->len_d = h.len_d;
+  ctl->n_chunks = h.n_chunks;
+  ctl->dir_off = dir_off;
+  ctl->payload_off = payload_off;
+  ctl->nnz = h.p.mode == RANS_MODE_CSR ? (uint32_t)((h.len_d - h.p.rows) / 2) : 0;
+  const float mn = h.x_min, mx = h.x_max;
+  const float sc = (mx - mn) / (float)((1u << h.p.q_bits) - 1u);
+  const float zf = eq6_zero_point(mn, sc);
+  ctl->x_min = mn;
+  ctl->x_max = mx;
+  ctl->scale = sc;
+  ctl->zero_point = zf;
+  if (qout) {
+    qout->x_min = mn;
+    qout->x_max = mx;
+    qout->scale = sc;
+    qout->zero_point = zf;
+  }
+}
+
+// The same as a kernel of its own, for a container without chunks (nothing else to launch).
+__global__ __launch_bounds__(64) void k_dec_begin(const uint8_t *in, uint64_t bytes, CtlRef ctl, HdrImage img,
+                                                  rans_header h, rans_qinfo *qout) {
+  dec_check_header(in, bytes, ctl, img, h, qout);
+}
+
+// Output side of the fast decoder.  bits(x) is evaluated once per symbol value when
+// the tables are built; put() stores the precomputed bits.
+struct FSinkSym {
+  uint8_t *out;
+  __device__ __forceinline__ uint32_t bits(uint32_t x, float, float, float) const { return x; }
+  // byte_off is a byte offset from a wave-uniform base: the store can take the base from scalar
+  // registers; non-temporal because the output is streamed once and must not evict the coded words
+  __device__ __forceinline__ static void put(uint8_t *base, uint32_t byte_off, uint32_t b) {
+    __builtin_nontemporal_store((uint8_t)b, base + byte_off);
+  }
+};
+struct FSinkU16 {
+  uint16_t *out;
+  __device__ __forceinline__ uint32_t bits(uint32_t x, float, float, float) const { return x; }
+  __device__ __forceinline__ static void put(uint16_t *base, uint32_t byte_off, uint32_t b) {
+    __builtin_nontemporal_store((uint16_t)b, (uint16_t *)((uint8_t *)base + byte_off));
+  }
+};
+// Inverse of Eq. 6 fused into the decoder: x = s * (xhat - z), one value per symbol.
+template <typename OutT>
+struct FSinkFloat {
+  OutT *out;
+  __device__ __forceinline__ uint32_t bits(uint32_t x, float sc, float zf, float x_min) const {
+    const float y = sc == 0.0f ? x_min : sc * ((float)x - zf);
+    if constexpr (sizeof(OutT) == 4) return __float_as_uint(y);
+    else return (uint32_t)__half_as_ushort(__float2half_rn(y));
+  }
+  __device__ __forceinline__ static void put(OutT *base, uint32_t byte_off, uint32_t b) {
+    if constexpr (sizeof(OutT) == 4) __builtin_nontemporal_store(b, (uint32_t *)((uint8_t *)base + byte_off));
+    else __builtin_nontemporal_store((uint16_t)b, (uint16_t *)((uint8_t *)base + byte_off));
+  }
+};
+
+
+// 16 bytes of the container at a 16-byte aligned offset; bytes past the end read as zero.
+__device__ __forceinline__ uint4 load_block16(const uint8_t *in, uint64_t bytes, uint64_t off) {
+  if (off + 16 <= bytes) return *(const uint4 *)(in + off);
+  uint32_t w[4] = {0, 0, 0, 0};
+  for (int q = 0; q < 8; q++)
+    if (off + 2 * q + 2 <= bytes) w[q >> 1] |= (uint32_t) * (const uint16_t *)(in + off + 2 * q) << (16 * (q & 1));
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// Interleaved rANS decoder (Eq. 3-4), one stream per lane.
+//
+// Every work-group rebuilds the tables in LDS from the stored frequencies: F by a
+// block scan, {f | F << 16, output bits} per symbol, and the slot -> symbol table
+// (Eq. 3) by marking each present symbol's first slot and taking a running maximum.
+//
+// A stream's words are read through a 16-word window in LDS ([row][stream] layout):
+// the lane loads 16-byte aligned blocks of its segment from global memory and the
+// coder consumes single words from the window, keeping the next word in a register.
+// Refills happen at wave-uniform points, every four steps: the block fetched at one
+// check is written to LDS at the next, and a block is requested as soon as the
+// reader has entered the block before it.  A stream consumes at most one word per
+// step and a block holds eight, so the words are always there in time, while the
+// global loads have at least four steps to complete.
+//
+// Everything taken from the container is checked before use; loads never leave the
+// buffer, and the final state / word count of every stream is verified.
+//
+// WIDE: instead of the two dependent lookups slot -> symbol -> {f, F, output}, one 8-byte entry per slot
+// {f | (slot - F) << 16, output bits} (a 2^M x 8 B table): one LDS access on the state's dependency chain.
+// The byte-per-slot table, the per-symbol table and the scan scratch are then only needed while the tables
+// are built; they live at tmp_off, which may alias the window (not yet in use at that time).
+template <class Sink, typename LutT, bool MUL24, int NT, bool WIDE>
+__global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t bytes, CtlRef ctl, uint32_t A,
+                                                     uint32_t M, uint32_t S, uint32_t cs, uint32_t groups,
+                                                     uint64_t len, uint64_t dir_off, uint64_t payload_off,
+                                                     float x_min, float x_max, uint32_t q_bits, uint32_t tmp_off,
+                                                     HdrImage img, rans_header hdr, rans_qinfo *qout, Sink sink) {
+  extern __shared__ __align__(16) uint32_t l_mem[];
+  constexpr uint32_t kWinRowBytes = 2 * NT;          // one 16-bit word per stream
+  constexpr uint32_t kWinBytes = 16 * kWinRowBytes;   // 16-word window per stream
+  constexpr uint32_t NW = NT / 64;                    // waves per work-group
+  // this is the first kernel of the call: no status to look at yet; work-group 0 checks the header
+  if (blockIdx.x == 0 && threadIdx.x < 64) dec_check_header(in, bytes, ctl, img, hdr, qout);
+  const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
+  const uint32_t total = 1u << M, mask = total - 1;
+  // LDS: [window][lut][misc: 48 words][tab: A x 8 B], or WIDE: [window][wide table] and
+  // [lut][misc][tab] at tmp_off.  The window and the table the coder reads sit at constant offsets, so
+  // their addresses need no base arithmetic.
+  LutT *lut = (LutT *)(l_mem + (WIDE ? tmp_off : kWinBytes) / 4);
+  uint32_t *misc = (uint32_t *)lut + ((total * (uint32_t)sizeof(LutT) + 15) / 16) * 4;
+  uint64_t *misc64 = (uint64_t *)(misc + 16);
+  uint2 *tab = (uint2 *)(misc + 48);
+  uint2 *wide = (uint2 *)(l_mem + kWinBytes / 4);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  // ---- global loads of the stream set-up first: their latency overlaps the table build below
+  const uint32_t f_first = threadIdx.x < A ? *(const uint16_t *)(in + kHdrBytes + 2ull * threadIdx.x) : 0;
+  const uint64_t payload_bytes = bytes - payload_off;
+  const uint8_t *dir = in + dir_off;
+  const uint64_t o0 = ld64(dir + 8ull * k), o1 = ld64(dir + 8ull * k + 8);
+  if (o0 > o1 || o1 > payload_bytes || o1 - o0 < 8ull * S || (o0 & 3)) {
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  const uint64_t ck_off = payload_off + o0;  // chunk start, from the start of the container
+  const uint8_t *ck = in + ck_off;
+  const uint64_t ck_bytes = o1 - o0;
+  const uint64_t chunk_len = cs ? cs : len;
+  const uint64_t base = (uint64_t)k * chunk_len;
+  const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
+  const uint32_t *nwk = (const uint32_t *)(ck + 4ull * S);
+  uint64_t pre_loc = 0;
+  for (uint32_t i = threadIdx.x; i < g * NT; i += NT) pre_loc += nwk[i];
+  const uint32_t j = g * NT + threadIdx.x;
+  const bool live = j < S;
+  const uint32_t nw_stored = live ? nwk[j] : 0;
+  const uint32_t s_stored = live ? ((const uint32_t *)ck)[j] : kL;
+
+  // ---- this work-group's streams
+  const uint64_t pre = block_sum64<NT>(pre_loc, misc64);
+  const uint64_t rows_full = n_here / S;
+  const uint32_t rem_row = (uint32_t)(n_here - rows_full * S);
+  const uint64_t n_j = live ? rows_full + (j < rem_row ? 1 : 0) : 0;
+  uint32_t nw = nw_stored;
+  bool bad = false;
+  if (nw > n_j) {
+    bad = true;
+    nw = 0;
+  }
+  uint32_t tot;
+  const uint32_t ex = block_excl_scan<NT>(nw, misc, &tot);
+  const uint64_t w0 = pre + ex;  // index of this stream's first word inside the chunk
+  if (8ull * S + 2 * (w0 + nw) > ck_bytes) {
+    bad = true;
+    nw = 0;
+  }
+  // where the stream's words are; its first two 16-byte blocks are requested now, so that their latency
+  // overlaps the table build
+  const uint64_t B0 = ck_off + 8ull * S + 2 * w0;  // first byte of the stream's words
+  const uint64_t blk_base = B0 & ~15ull;           // 16-byte blocks are counted from here
+  const uint8_t *sp = in + blk_base;
+  const uint32_t pos0 = (uint32_t)(B0 & 15) >> 1;
+  const uint32_t end16 = (uint32_t)(B0 - blk_base) + 2 * nw;  // stream end, in bytes from blk_base
+  // bytes of the container from blk_base on (saturated): loads stay below this
+  const uint64_t room = bytes > blk_base ? bytes - blk_base : 0;
+  const uint32_t lim16 = room > 0xffffffffull ? 0xffffffffu : (uint32_t)room;
+  auto load_block = [&](uint32_t off16) -> uint4 {  // 16 bytes at sp + off16; bytes past the end read as zero
+    if (off16 <= lim16 && lim16 - off16 >= 16) return *(const uint4 *)(sp + off16);
+    uint32_t w[4] = {0, 0, 0, 0};
+    for (uint32_t q = 0; q < 8; q++)
+      if ((uint64_t)off16 + 2 * q + 2 <= lim16) w[q >> 1] |= (uint32_t) * (const uint16_t *)(sp + off16 + 2 * q) << (16 * (q & 1));
+    return make_uint4(w[0], w[1], w[2], w[3]);
+  };
+  uint4 q_first[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
+  if (live) {
+    q_first[0] = load_block(0);
+    if (16 < end16) q_first[1] = load_block(16);
+  }
+
+  // ---- tables
+  const float sc = (x_max - x_min) / (float)((1u << q_bits) - 1u);
+  const float zf = eq6_zero_point(x_min, sc);
+  for (uint32_t i = threadIdx.x; i < (total * sizeof(LutT) + 3) / 4; i += NT) ((uint32_t *)lut)[i] = 0;
+  uint32_t carry = 0;
+  for (uint32_t a0 = 0; a0 < A; a0 += NT) {  // also orders the zeroing above before the marks below
+    const uint32_t a = a0 + threadIdx.x;
+    const uint32_t f = a0 == 0 ? f_first : (a < A ? *(const uint16_t *)(in + kHdrBytes + 2ull * a) : 0);
+    uint32_t tot;
+    const uint32_t F = carry + block_excl_scan<NT>(f, misc, &tot);
+    if (a < A) {
+      tab[a] = make_uint2(f | (F << 16), sink.bits(a, sc, zf, x_min));
+      if (f && F < total) lut[F] = (LutT)a;  // present symbols start at distinct slots
+    }
+    carry += tot;
+  }
+  if (carry != total) {  // uniform; an empty D never reaches this kernel
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  __syncthreads();
+  {  // running maximum of the marks: each wave owns a contiguous share of the slots
+    constexpr uint32_t V = 4 / sizeof(LutT);  // slots per 32-bit word
+    constexpr uint32_t kIt = 4;               // words of a lane handled together (their scans do not depend on each other)
+    const uint32_t per_wave = ((total + NW * 64 * V - 1) / (NW * 64 * V)) * 64 * V;
+    const uint32_t lo = wave * per_wave;
+    if (lo < total) {
+      const uint32_t hi = lo + per_wave < total ? lo + per_wave : total;
+      // symbol that owns slot lo: the largest a with F[a] <= lo
+      uint32_t a_lo = 0, a_hi = A;
+      while (a_hi - a_lo > 1) {
+        const uint32_t mid = (a_lo + a_hi) >> 1;
+        if ((tab[mid].x >> 16) <= lo) a_lo = mid;
+        else a_hi = mid;
+      }
+      uint32_t run = a_lo;
+      for (uint32_t b0 = lo; b0 < hi; b0 += 64 * V * kIt) {
+        uint32_t e[kIt][V], inc[kIt];
+#pragma unroll
+        for (uint32_t it = 0; it < kIt; it++) {
+          const uint32_t idx = b0 + it * 64 * V + lane * V;
+          const uint32_t w = idx < hi ? ((const uint32_t *)lut)[idx / V] : 0;
+#pragma unroll
+          for (uint32_t q = 0; q < V; q++) e[it][q] = (w >> (8 * sizeof(LutT) * q)) & (sizeof(LutT) == 1 ? 0xffu : 0xffffu);
+#pragma unroll
+          for (uint32_t q = 1; q < V; q++) e[it][q] = e[it][q] > e[it][q - 1] ? e[it][q] : e[it][q - 1];
+          inc[it] = wave_incl_max_scan(e[it][V - 1]);
+        }
+#pragma unroll
+        for (uint32_t it = 0; it < kIt; it++) {
+          const uint32_t idx = b0 + it * 64 * V + lane * V;
+          // largest mark before this lane's word: the lane below's inclusive maximum, or the running one
+          uint32_t prev = (uint32_t)__builtin_amdgcn_update_dpp((int)run, (int)inc[it], 0x138, 0xf, 0xf, false);  // wave_shr:1
+          prev = prev > run ? prev : run;
+          uint32_t sy[V];
+#pragma unroll
+          for (uint32_t q = 0; q < V; q++) sy[q] = e[it][q] > prev ? e[it][q] : prev;
+          if (idx < hi) {
+            if (WIDE) {  // straight to the slot table the coder reads
+              uint2 te[V];
+#pragma unroll
+              for (uint32_t q = 0; q < V; q++) te[q] = tab[sy[q]];
+#pragma unroll
+              for (uint32_t q = 0; q < V; q++)
+                if (idx + q < total) wide[idx + q] = make_uint2((te[q].x & 0xffffu) | ((idx + q - (te[q].x >> 16)) << 16), te[q].y);
+            } else {
+              uint32_t w = 0;
+#pragma unroll
+              for (uint32_t q = 0; q < V; q++) w |= sy[q] << (8 * sizeof(LutT) * q);
+              ((uint32_t *)lut)[idx / V] = w;
+            }
+          }
+          const uint32_t last = (uint32_t)__builtin_amdgcn_readlane((int)inc[it], 63);
+          run = last > run ? last : run;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  if (WIDE) __syncthreads();  // the scan scratch above may alias the window that is filled below
+  if (live) {
+    typedef __attribute__((address_space(3))) uint16_t lds_u16;
+    constexpr uint32_t RB = kWinRowBytes, LOG_RB = NT == 1024 ? 11 : 9;
+    // column of this stream inside a window row; lanes l and l+32 share a 32-bit bank word, so the two
+    // halves of a wave never collide.  The window starts at LDS address 0 (this kernel has no static LDS).
+    if ((uint32_t)(uintptr_t)(lds_u16 *)l_mem != 0) {  // cannot happen without static LDS; the slot arithmetic relies on it
+      set_status(ctl, RANS_ERR_HIP);
+      return;
+    }
+    const uint32_t lane_col = ((uint32_t)lane & 31u) * 2 + ((uint32_t)lane >> 5);
+    const uint32_t colb = 2 * ((uint32_t)wave * 64 + lane_col);
+    auto wread = [&](uint32_t rd_scaled) -> uint32_t {  // word whose number times RB is rd_scaled
+      return *(lds_u16 *)(uintptr_t)((rd_scaled & (kWinBytes - 1)) | colb);
+    };
+    auto store_block = [&](uint32_t b, const uint4 &q) {  // block b -> rows 8(b&1) .. 8(b&1)+7
+      lds_u16 *row0 = (lds_u16 *)(uintptr_t)(((b & 1u) * 8 * RB) | colb);
+      const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+      for (int i = 0; i < 8; i++) row0[i * (RB / 2)] = (uint16_t)(w[i >> 1] >> (16 * (i & 1)));
+    };
+    // the first two blocks, requested before the table build
+    store_block(0, q_first[0]);
+    if (16 < end16) store_block(1, q_first[1]);
+    uint32_t ldb = 2;              // next block to request
+    uint32_t rd9 = pos0 * RB;      // RB times the number of the next unread word (counted from blk_base)
+    uint32_t pend_b = 0;
+    bool pending = false;
+    uint4 pend_q = make_uint4(0, 0, 0, 0);
+    uint32_t wnext = wread(rd9);
+    uint32_t s = s_stored;
+    uint32_t smin = s;
+    auto *ob = sink.out + base + (uint64_t)g * NT;  // uniform base of this work-group's outputs
+    constexpr uint32_t kOutElem = sizeof(*sink.out);
+    uint32_t oi = threadIdx.x * kOutElem;           // byte offset of this stream's next output
+    const uint32_t oi_step = S * kOutElem;
+    // table addresses as plain LDS offsets (the window starts at 0, the slot table right after it)
+    typedef __attribute__((address_space(3))) LutT lds_lut;
+    typedef __attribute__((address_space(3))) uint64_t lds_u64;
+    const uint32_t tab_off = (uint32_t)(uintptr_t)(lds_u64 *)tab;
+    // Called every 8 steps (a step consumes at most one word).  The window holds blocks cur and cur + 1,
+    // cur the block of the next unread word.  A block is requested two blocks ahead and moved into the
+    // window once the block whose rows it takes (two blocks back) is read up.  Reading a block takes at
+    // least 8 steps, so each block sees a call while it is being read: block b is requested during
+    // block b - 2 at the latest and stored during block b - 1.
+    auto refill = [&]() {
+      const uint32_t cur = rd9 >> (LOG_RB + 3);
+      if (pending && pend_b <= cur + 1) {
+        store_block(pend_b, pend_q);
+        pending = false;
+      }
+      if (!pending && ldb <= cur + 2 && ldb * 16 < end16) {
+        pend_q = load_block(ldb * 16);
+        pend_b = ldb;
+        pending = true;
+        ldb++;
+      }
+    };
+    auto step = [&]() {
+      const uint32_t slot = s & mask;
+      uint2 e;
+      uint32_t bias;  // slot - F
+      if constexpr (WIDE) {
+        const uint64_t e64 = *(lds_u64 *)(uintptr_t)(kWinBytes + slot * 8);
+        e = make_uint2((uint32_t)e64, (uint32_t)(e64 >> 32));
+        bias = e.x >> 16;
+      } else {
+        const uint32_t x = *(lds_lut *)(uintptr_t)(kWinBytes + slot * (uint32_t)sizeof(LutT));
+        const uint64_t e64 = *(lds_u64 *)(uintptr_t)(tab_off + x * 8);
+        e = make_uint2((uint32_t)e64, (uint32_t)(e64 >> 32));
+        bias = slot - (e.x >> 16);
+      }
+      // f < 2^16 always; s >> M < 2^24 only when M >= 8
+      s = (MUL24 ? __umul24(e.x & 0xffffu, s >> M) : (e.x & 0xffffu) * (s >> M)) + bias;
+      sink.put(ob, oi, e.y);
+      oi += oi_step;
+      if (s < kL) {
+        s = (s << 16) | wnext;
+        rd9 += RB;
+        wnext = wread(rd9);
+      }
+      smin = s < smin ? s : smin;
+    };
+    uint64_t t = 0;
+    for (; t + 8 <= rows_full; t += 8) {
+      refill();
+#pragma unroll
+      for (int u = 0; u < 8; u++) step();
+    }
+    if (t < rows_full || j < rem_row) {
+      refill();
+      for (; t < rows_full; t++) step();
+      if (j < rem_row) step();
+    }
+    const uint32_t rd = rd9 >> LOG_RB;
+    bad |= smin < kL || s != kL || rd - pos0 != nw;
+    if (j == S - 1) {  // chunk size must be exactly header + words, padded to 4 bytes with zeros
+      const uint64_t end = 8ull * S + 2 * (w0 + nw);
+      if (((end + 3) & ~3ull) != ck_bytes) bad = true;
+      else if (end != ck_bytes && *(const uint16_t *)(ck + end) != 0) bad = true;
+    }
+  }
+  if (bad) set_status(ctl, RANS_ERR_CORRUPT);
+}
+
+// Decoder side of the modified CSR (Sec. 3.1: the cumulative sum of r is taken at decode time, then v is
+// scattered).  Rows are cut into tiles of `tile_rows` rows; k_row_part sums r over each tile (and checks
+// r[i] <= K), a single-work-group scan turns the sums into the index of each tile's first nonzero, and
+// k_csr_to_dense rebuilds one tile per work-group in LDS and writes it out in the output type.
+__global__ __launch_bounds__(kWG) void k_row_part(const uint16_t *r, uint32_t N, uint32_t K, uint32_t tile_rows,
+                                                  uint32_t *part, CtlRef ctl) {
+  __shared__ uint64_t sh64[kWG / 64];
+  if (get_status(ctl) != 0) return;
+  const uint32_t i0 = blockIdx.x * tile_rows;
+  const uint32_t i1 = i0 + tile_rows < N ? i0 + tile_rows : N;
+  uint64_t loc = 0;
+  bool bad = false;
+  for (uint32_t i = i0 + threadIdx.x; i < i1; i += kWG) {
+    const uint32_t v = r[i];
+    bad |= v > K;
+    loc += v;
+  }
+  const uint64_t tot = block_sum64<kWG>(loc, sh64);
+  if (bad || tot > 0xffffffffull) set_status(ctl, RANS_ERR_CORRUPT);
+  if (threadIdx.x == 0) part[blockIdx.x] = (uint32_t)tot;
+}
+
+// One tile of rows: row offsets by a local scan of r, the tile zeroed in LDS, every nonzero of the tile
+// placed (its row found by bisection of the local offsets) and checked (1 <= v < 2^Q, c < K, c strictly
+// increasing inside a row), then the tile written out: as symbols, or dequantised (x = s (xhat - z)).
+// D holds v, c, r as 16-bit symbols; part[] the exclusive scan of the tile sums, part[n_tiles] = their total.
+template <typename OutT>
+__global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const uint32_t *part, uint32_t N, uint32_t K,
+                                                      uint32_t tile_rows, uint32_t q_bits, OutT *out, CtlRef ctl) {
+  extern __shared__ __align__(16) uint32_t l_mem[];
+  __shared__ uint32_t sh[kWG / 64];
+  if (get_status(ctl) != 0) return;
+  const uint32_t nnz = ctl->nnz;
+  const uint32_t i0 = blockIdx.x * tile_rows;
+  const uint32_t rows = i0 + tile_rows < N ? tile_rows : N - i0;
+  uint32_t *roff = l_mem;                                          // rows + 1 local offsets
+  uint8_t *dense = (uint8_t *)(l_mem + ((rows + 1 + 3) & ~3u));   // rows * K symbols
+  const uint32_t base = part[blockIdx.x];
+  const uint32_t n_tiles = gridDim.x;
+  if (blockIdx.x == n_tiles - 1 && part[n_tiles] != nnz) {  // sum of r must be the number of nonzeros
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  const uint16_t *r = D + 2ull * nnz + i0;
+  uint32_t carry = 0;
+  for (uint32_t b0 = 0; b0 < rows; b0 += kWG) {
+    const uint32_t i = b0 + threadIdx.x;
+    const uint32_t v = i < rows ? r[i] : 0;
+    uint32_t tot;
+    const uint32_t ex = block_excl_scan<kWG>(v, sh, &tot);
+    if (i < rows) roff[i] = carry + ex;
+    carry += tot;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) roff[rows] = carry;
+  const uint32_t cells = rows * K;
+  for (uint32_t i = threadIdx.x; i < (cells + 3) / 4; i += kWG) ((uint32_t *)dense)[i] = 0;
+  __syncthreads();
+  const uint32_t cnt_here = carry;
+  if ((uint64_t)base + cnt_here > nnz) {  // uniform: the offsets would run past the stored nonzeros
+    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
+    return;
+  }
+  bool bad = false;
+  // A lane takes runs of eight consecutive nonzeros (their values and column indices come with one 16-byte
+  // load each, 2-byte aligned: where c starts inside D depends on the number of nonzeros), two runs per step
+  // with all loads issued first.  The row of a run's first nonzero is found by bisection of the local offsets,
+  // the rows of the others by walking on from there.
+  constexpr int kU = 2;
+  const uint16_t *Dv = D + base, *Dc = D + (uint64_t)nnz + base;
+  for (uint32_t m0 = 0; 8 * m0 < cnt_here; m0 += kWG * kU) {
+    uint32_t vw[kU][4], cw[kU][4], cp[kU];
+#pragma unroll
+    for (int u = 0; u < kU; u++) {
+      const uint32_t j = 8 * (m0 + u * kWG + threadIdx.x);
+      cp[u] = 0;
+#pragma unroll
+      for (int k = 0; k < 4; k++) vw[u][k] = cw[u][k] = 0;
+      if (j + 8 <= cnt_here) {
+        __builtin_memcpy(vw[u], Dv + j, 16);
+        __builtin_memcpy(cw[u], Dc + j, 16);
+      } else {
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+          if (j + k < cnt_here) {
+            vw[u][k >> 1] |= (uint32_t)Dv[j + k] << (16 * (k & 1));
+            cw[u][k >> 1] |= (uint32_t)Dc[j + k] << (16 * (k & 1));
+          }
+        }
+      }
+      if (j && j < cnt_here) cp[u] = Dc[j - 1];
+    }
+#pragma unroll
+    for (int u = 0; u < kU; u++) {
+      const uint32_t j0 = 8 * (m0 + u * kWG + threadIdx.x);
+      if (j0 < cnt_here) {
+        uint32_t lo = 0, hi = rows;  // largest local row with roff[row] <= j0 (roff[rows] = cnt_here > j0)
+        while (hi - lo > 1) {
+          const uint32_t mid = (lo + hi) >> 1;
+          if (roff[mid] <= j0) lo = mid;
+          else hi = mid;
+        }
+        uint32_t row = lo, row_beg = roff[lo], row_end = roff[lo + 1], prev_c = cp[u];
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+          const uint32_t j = j0 + k;
+          if (j < cnt_here) {
+            while (j >= row_end) {  // ends: row_end of the last row is cnt_here > j
+              row++;
+              row_beg = row_end;
+              row_end = roff[row + 1];
+            }
+            const uint32_t vv = (vw[u][k >> 1] >> (16 * (k & 1))) & 0xffffu, cc = (cw[u][k >> 1] >> (16 * (k & 1))) & 0xffffu;
+            bool b = vv == 0 || vv >= (1u << q_bits) || cc >= K;
+            if (j > row_beg && prev_c >= cc) b = true;
+            if (b) bad = true;
+            else dense[row * K + cc] = (uint8_t)vv;
+            prev_c = cc;
+          }
+        }
+      }
+    }
+  }
+  if (bad) set_status(ctl, RANS_ERR_CORRUPT);
+  __syncthreads();
+  const float s = ctl->scale, zf = ctl->zero_point, x_min = ctl->x_min;
+  OutT *o = out + (uint64_t)i0 * K;
+  auto conv = [&](uint32_t sym) -> OutT {
+    if constexpr (sizeof(OutT) == 1) {
+      return (OutT)sym;
+    } else {
+      const float y = s == 0.0f ? x_min : s * ((float)sym - zf);
+      if constexpr (sizeof(OutT) == 4) return y;
+      else return __float2half_rn(y);
+    }
+  };
+  // four cells per lane and step when the tile starts on a 4-cell boundary of a 16-byte aligned output
+  const bool vec4 = (((uint64_t)i0 * K) & 3) == 0 && ((uintptr_t)out & 15) == 0;
+  const uint32_t cells4 = vec4 ? cells / 4 : 0;
+  for (uint32_t q = threadIdx.x; q < cells4; q += kWG) {
+    const uint32_t w = ((const uint32_t *)dense)[q];
+    struct alignas(4 * sizeof(OutT)) Quad { OutT a, b, c, d; };
+    ((Quad *)o)[q] = Quad{conv(w & 0xffu), conv((w >> 8) & 0xffu), conv((w >> 16) & 0xffu), conv(w >> 24)};
+  }
+  for (uint32_t i = cells4 * 4 + threadIdx.x; i < cells; i += kWG) o[i] = conv(dense[i]);
+}
+
+// Inverse of Eq. 6 over a symbol array.  VEC: sixteen symbols per lane and step (both arrays 16-byte
+// aligned); the tail and unaligned arrays go one symbol at a time.
+template <typename OutT, bool VEC>
+__global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *sym, uint64_t n, const rans_qinfo *qi, CtlRef ctl,
+                                                 OutT *out) {
+  if (ctl && get_status(ctl) != 0) return;
+  const float s = qi->scale, zf = qi->zero_point, x_min = qi->x_min;
+  auto conv = [&](uint32_t a) -> OutT {
+    const float y = s == 0.0f ? x_min : s * ((float)a - zf);
+    if constexpr (sizeof(OutT) == 4) return y;
+    else return __float2half_rn(y);
+  };
+  const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (uint64_t)gridDim.x * blockDim.x;
+  uint64_t done = 0;
+  if constexpr (VEC) {
+    struct alignas(4 * sizeof(OutT)) Quad { OutT a, b, c, d; };
+    const uint64_t nv = n / 16;
+    for (uint64_t i = tid; i < nv; i += stride) {
+      const uint4 w = ((const uint4 *)sym)[i];
+      const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+      for (int k = 0; k < 4; k++)
+        ((Quad *)out)[4 * i + k] = Quad{conv(ww[k] & 0xffu), conv((ww[k] >> 8) & 0xffu), conv((ww[k] >> 16) & 0xffu), conv(ww[k] >> 24)};
+    }
+    done = nv * 16;
+  }
+  for (uint64_t i = done + tid; i < n; i += stride) out[i] = conv(sym[i]);
+}
+
+}  // namespace

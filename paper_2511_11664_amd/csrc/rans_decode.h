@@ -292,6 +292,7 @@ __global__ __launch_bounds__(64) void k_dec_begin(const uint8_t *in, uint64_t by
 // the tables are built; put() stores the precomputed bits.
 struct FSinkSym {
   uint8_t *out;
+  static constexpr bool kNarrow = true;  // the output value has at most 16 bits
   __device__ __forceinline__ uint32_t bits(uint32_t x, float, float, float) const { return x; }
   // byte_off is a byte offset from a wave-uniform base: the store can take the base from scalar
   // registers; non-temporal because the output is streamed once and must not evict the coded words
@@ -301,6 +302,7 @@ struct FSinkSym {
 };
 struct FSinkU16 {
   uint16_t *out;
+  static constexpr bool kNarrow = true;
   __device__ __forceinline__ uint32_t bits(uint32_t x, float, float, float) const { return x; }
   __device__ __forceinline__ static void put(uint16_t *base, uint32_t byte_off, uint32_t b) {
     __builtin_nontemporal_store((uint16_t)b, (uint16_t *)((uint8_t *)base + byte_off));
@@ -310,6 +312,7 @@ struct FSinkU16 {
 template <typename OutT>
 struct FSinkFloat {
   OutT *out;
+  static constexpr bool kNarrow = sizeof(OutT) <= 2;
   __device__ __forceinline__ uint32_t bits(uint32_t x, float sc, float zf, float x_min) const {
     const float y = sc == 0.0f ? x_min : sc * ((float)x - zf);
     if constexpr (sizeof(OutT) == 4) return __float_as_uint(y);
@@ -350,7 +353,8 @@ __device__ __forceinline__ uint4 load_block16(const uint8_t *in, uint64_t bytes,
 // buffer, and the final state / word count of every stream is verified.
 //
 // WIDE: instead of the two dependent lookups slot -> symbol -> {f, F, output}, one 8-byte entry per slot
-// {f | (slot - F) << 16, output bits} (a 2^M x 8 B table): one LDS access on the state's dependency chain.
+// {f | (slot - F) << 16, output bits} - or, for outputs of at most 16 bits, {f, output | (slot - F) << 16}, which
+// saves the unpacking of f - (a 2^M x 8 B table): one LDS access on the state's dependency chain.
 // The byte-per-slot table, the per-symbol table and the scan scratch are then only needed while the tables
 // are built; they live at tmp_off, which may alias the window (not yet in use at that time).
 template <class Sink, typename LutT, bool MUL24, int NT, bool WIDE>
@@ -505,7 +509,10 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
               for (uint32_t q = 0; q < V; q++) te[q] = tab[sy[q]];
 #pragma unroll
               for (uint32_t q = 0; q < V; q++)
-                if (idx + q < total) wide[idx + q] = make_uint2((te[q].x & 0xffffu) | ((idx + q - (te[q].x >> 16)) << 16), te[q].y);
+                if (idx + q < total) {
+                  const uint32_t fq = te[q].x & 0xffffu, bq = idx + q - (te[q].x >> 16);  // f, slot - F
+                  wide[idx + q] = Sink::kNarrow ? make_uint2(fq, (te[q].y & 0xffffu) | (bq << 16)) : make_uint2(fq | (bq << 16), te[q].y);
+                }
             } else {
               uint32_t w = 0;
 #pragma unroll
@@ -582,18 +589,26 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
       const uint32_t slot = s & mask;
       uint2 e;
       uint32_t bias;  // slot - F
+      uint32_t fx;    // f
       if constexpr (WIDE) {
         const uint64_t e64 = *(lds_u64 *)(uintptr_t)(kWinBytes + slot * 8);
         e = make_uint2((uint32_t)e64, (uint32_t)(e64 >> 32));
-        bias = e.x >> 16;
+        if constexpr (Sink::kNarrow) {  // {f, output | (slot - F) << 16}: f needs no unpacking, the store takes the low bits
+          fx = e.x;
+          bias = e.y >> 16;
+        } else {
+          fx = e.x & 0xffffu;
+          bias = e.x >> 16;
+        }
       } else {
         const uint32_t x = *(lds_lut *)(uintptr_t)(kWinBytes + slot * (uint32_t)sizeof(LutT));
         const uint64_t e64 = *(lds_u64 *)(uintptr_t)(tab_off + x * 8);
         e = make_uint2((uint32_t)e64, (uint32_t)(e64 >> 32));
         bias = slot - (e.x >> 16);
+        fx = e.x & 0xffffu;
       }
       // f < 2^16 always; s >> M < 2^24 only when M >= 8
-      s = (MUL24 ? __umul24(e.x & 0xffffu, s >> M) : (e.x & 0xffffu) * (s >> M)) + bias;
+      s = (MUL24 ? __umul24(fx, s >> M) : fx * (s >> M)) + bias;
       sink.put(ob, oi, e.y);
       oi += oi_step;
       if (s < kL) {

@@ -364,8 +364,7 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
                                                      float x_min, float x_max, uint32_t q_bits, uint32_t tmp_off,
                                                      HdrImage img, rans_header hdr, rans_qinfo *qout, Sink sink) {
   extern __shared__ __align__(16) uint32_t l_mem[];
-  constexpr uint32_t kWinRowBytes = 2 * NT;          // one 16-bit word per stream
-  constexpr uint32_t kWinBytes = 16 * kWinRowBytes;   // 16-word window per stream
+  constexpr uint32_t kWinBytes = 32 * NT;             // 16-word window per stream, one 32-byte line each
   constexpr uint32_t NW = NT / 64;                    // waves per work-group
   // this is the first kernel of the call: no status to look at yet; work-group 0 checks the header
   if (blockIdx.x == 0 && threadIdx.x < 64) dec_check_header(in, bytes, ctl, img, hdr, qout);
@@ -530,23 +529,23 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
   if (WIDE) __syncthreads();  // the scan scratch above may alias the window that is filled below
   if (live) {
     typedef __attribute__((address_space(3))) uint16_t lds_u16;
-    constexpr uint32_t RB = kWinRowBytes, LOG_RB = NT == 1024 ? 11 : 9;
-    // column of this stream inside a window row; lanes l and l+32 share a 32-bit bank word, so the two
-    // halves of a wave never collide.  The window starts at LDS address 0 (this kernel has no static LDS).
+    // A stream's 16-word window is one 32-byte line of LDS: a block of eight words arrives with ONE 16-byte
+    // store (the refill code is issued for the whole wave whenever any lane needs it, so its length counts
+    // on every call), single words are read at 2 (n mod 16) inside the line.  rd9 is twice the number of the
+    // next unread word.  The window starts at LDS address 0 (this kernel has no static LDS).
+    constexpr uint32_t RB = 2, LOG_RB = 1;
     if ((uint32_t)(uintptr_t)(lds_u16 *)l_mem != 0) {  // cannot happen without static LDS; the slot arithmetic relies on it
       set_status(ctl, RANS_ERR_HIP);
       return;
     }
-    const uint32_t lane_col = ((uint32_t)lane & 31u) * 2 + ((uint32_t)lane >> 5);
-    const uint32_t colb = 2 * ((uint32_t)wave * 64 + lane_col);
-    auto wread = [&](uint32_t rd_scaled) -> uint32_t {  // word whose number times RB is rd_scaled
-      return *(lds_u16 *)(uintptr_t)((rd_scaled & (kWinBytes - 1)) | colb);
+    const uint32_t colb = 32 * ((uint32_t)wave * 64 + (uint32_t)lane);
+    auto wread = [&](uint32_t rd_scaled) -> uint32_t {  // word whose number times 2 is rd_scaled
+      return *(lds_u16 *)(uintptr_t)((rd_scaled & 31u) | colb);
     };
-    auto store_block = [&](uint32_t b, const uint4 &q) {  // block b -> rows 8(b&1) .. 8(b&1)+7
-      lds_u16 *row0 = (lds_u16 *)(uintptr_t)(((b & 1u) * 8 * RB) | colb);
-      const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-      for (int i = 0; i < 8; i++) row0[i * (RB / 2)] = (uint16_t)(w[i >> 1] >> (16 * (i & 1)));
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) u32x4 lds_u128;
+    auto store_block = [&](uint32_t b, const uint4 &q) {  // block b -> words 8 (b & 1) .. 8 (b & 1) + 7 of the line
+      *(lds_u128 *)(uintptr_t)(((b & 1u) * 16) | colb) = u32x4{q.x, q.y, q.z, q.w};
     };
     // the first two blocks, requested before the table build
     store_block(0, q_first[0]);

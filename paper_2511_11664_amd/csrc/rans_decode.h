@@ -340,14 +340,15 @@ __device__ __forceinline__ uint4 load_block16(const uint8_t *in, uint64_t bytes,
 // block scan, {f | F << 16, output bits} per symbol, and the slot -> symbol table
 // (Eq. 3) by marking each present symbol's first slot and taking a running maximum.
 //
-// A stream's words are read through a 16-word window in LDS ([row][stream] layout):
-// the lane loads 16-byte aligned blocks of its segment from global memory and the
-// coder consumes single words from the window, keeping the next word in a register.
-// Refills happen at wave-uniform points, every four steps: the block fetched at one
-// check is written to LDS at the next, and a block is requested as soon as the
-// reader has entered the block before it.  A stream consumes at most one word per
-// step and a block holds eight, so the words are always there in time, while the
-// global loads have at least four steps to complete.
+// A stream's words are read through a 16-word window in LDS (one 32-byte line per
+// stream): the lane loads 16-byte aligned blocks of its segment from global memory,
+// a block goes into its half of the line with one 16-byte store, and the coder consumes
+// single words from the line, keeping the next word in a register.  Refills happen at
+// wave-uniform points, every eight steps: the block fetched at one check is written to
+// LDS at a later one, and a block is requested as soon as the reader has entered the
+// block before it.  A stream consumes at most one word per step and a block holds
+// eight, so the words are always there in time, while the global loads have at least
+// eight steps to complete.
 //
 // Everything taken from the container is checked before use; loads never leave the
 // buffer, and the final state / word count of every stream is verified.

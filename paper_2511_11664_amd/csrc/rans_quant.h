@@ -525,7 +525,10 @@ __device__ void normalize_wave_per(const CtlRef &ctl, const NormArgs &na) {
 }
 
 __device__ void normalize_wave(const CtlRef &ctl, const NormArgs &na) {
+  // as few symbols per lane as the alphabet allows (CSR with K = 2^Q has 2^Q + 1 symbols)
   if (na.A <= 256) normalize_wave_per<4>(ctl, na);
+  else if (na.A <= 320) normalize_wave_per<5>(ctl, na);
+  else if (na.A <= 384) normalize_wave_per<6>(ctl, na);
   else normalize_wave_per<8>(ctl, na);
 }
 

@@ -129,7 +129,7 @@ Layout make_layout(const rans_params &p, uint64_t n) {
   }
   if (p.mode != RANS_MODE_CSR) L.n_blk = 0;
   // per-chunk word counts, the encoder's published totals, the nonzeros per CSR tile: all zeroed when a call starts
-  L.chunk_words = take(((size_t)L.nc_max + 1 + L.n_pub + L.n_blk) * 4);
+  L.chunk_words = take(((size_t)L.nc_max + 1 + L.n_pub + 2 * (size_t)L.n_blk) * 4);  // tile counts, then group counts
   // word blocks of the encoder, per work-group (kWG streams, absent ones included): see k_encode
   L.scratch = take((size_t)L.nc_max * ((p.n_streams + kWG - 1) / kWG) * kWG * L.capw * 2);
   size_t enc_end = o;

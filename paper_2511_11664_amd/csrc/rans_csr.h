@@ -24,43 +24,52 @@ __device__ __forceinline__ void load16(const uint8_t *p, uint64_t e0, uint64_t n
 // Stream compaction of the nonzero symbols in flat (= row-major) order: v gets the
 // values, c the column indices, row_end[i] the number of nonzeros up to and
 // including row i.  Column indices are histogrammed into cnt on the way.
-// A work-group walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...: a tile's nonzeros are
-// compacted in LDS first and leave with consecutive lanes on consecutive entries, and the
-// column histogram is added to the global one once at the end (few work-groups: same-address
-// global atomics are what costs here).  blk_nnz[t] is the number of nonzeros of tile t (counted by
-// k_quant_hist); a tile's place in v and c is the sum over the tiles before it, which the work-group
-// adds up itself.
+// A work-group takes tiles_per_wg consecutive tiles: a tile's nonzeros are compacted in LDS first
+// and leave with consecutive lanes on consecutive entries, and the column histogram is added to a
+// global one once at the end (few work-groups: same-address global atomics are what costs here).
+// k_quant_hist has counted the nonzeros of every tile (blk_nnz) and of every group of tiles_per_grp
+// tiles (grp_nnz); the place of the work-group's first tile in v and c is the sum over the groups
+// and then the tiles before it, and every further tile follows the one before.
 template <bool LDS_HIST>
 __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_t n, int aligned, uint32_t K,
-                                                     const uint32_t *blk_nnz, uint8_t *v, uint16_t *c,
+                                                     const uint32_t *blk_nnz, const uint32_t *grp_nnz,
+                                                     uint32_t tiles_per_grp, uint8_t *v, uint16_t *c,
                                                      uint32_t *row_end, uint32_t *cnt, uint32_t A, uint32_t n_tiles,
-                                                     uint32_t n_rep) {
+                                                     uint32_t tiles_per_wg, uint32_t n_rep) {
   extern __shared__ uint32_t hist[];
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
   __shared__ uint8_t s_v[kCsrTile];
   __shared__ uint16_t s_c[kCsrTile];
+  // A lane holds 16 consecutive symbols, so at each step the columns of a wave's lanes are 16 apart and
+  // would fall into two LDS banks: the histogram keeps column j in slot j ^ ((j >> 4) & 15) instead (a
+  // permutation within each aligned block of 16 slots; the array is A rounded up to 16).
+  auto slot_of = [](uint32_t j) { return j ^ ((j >> 4) & 15u); };
   if (LDS_HIST) {
-    for (uint32_t a = threadIdx.x; a < A; a += kWG) hist[a] = 0;
+    for (uint32_t a = threadIdx.x; a < ((A + 15u) & ~15u); a += kWG) hist[a] = 0;
   }
-  // where the work-group's tile starts in v and c: the nonzeros of all tiles before it (k_quant_hist has
-  // counted them), kept up to date from tile to tile with the counts of the tiles in between
+  const uint32_t t0 = blockIdx.x * tiles_per_wg;  // < n_tiles by the size of the grid
+  const uint32_t t1 = t0 + tiles_per_wg < n_tiles ? t0 + tiles_per_wg : n_tiles;
+  uint8_t b[16];
+  load16(sym, (uint64_t)t0 * kCsrTile + threadIdx.x * 16, n, aligned, b);
   uint32_t base;
   {
+    const uint32_t g0 = t0 / tiles_per_grp;
     uint64_t part = 0;
-    for (uint32_t u0 = threadIdx.x; u0 < blockIdx.x; u0 += 4 * kWG) {
-      uint32_t x4[4];
+    for (uint32_t u0 = threadIdx.x; u0 < g0; u0 += 8 * kWG) {
+      uint32_t x8[8];
 #pragma unroll
-      for (int k = 0; k < 4; k++) x4[k] = u0 + k * kWG < blockIdx.x ? blk_nnz[u0 + k * kWG] : 0u;
+      for (int k = 0; k < 8; k++) x8[k] = u0 + k * kWG < g0 ? grp_nnz[u0 + k * kWG] : 0u;
 #pragma unroll
-      for (int k = 0; k < 4; k++) part += x4[k];
+      for (int k = 0; k < 8; k++) part += x8[k];
     }
+    for (uint32_t t = g0 * tiles_per_grp + threadIdx.x; t < t0; t += kWG) part += blk_nnz[t];
     base = (uint32_t)block_sum64<kWG>(part, sh64);
   }
-  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+  for (uint32_t tile = t0; tile < t1; tile++) {
     const uint64_t e0 = (uint64_t)tile * kCsrTile + threadIdx.x * 16;
-    uint8_t b[16];
-    load16(sym, e0, n, aligned, b);
+    uint8_t nb[16];  // the next tile's symbols are on their way while this one is placed
+    if (tile + 1 < t1) load16(sym, e0 + kCsrTile, n, aligned, nb);
     uint32_t cth = 0;
 #pragma unroll
     for (int k = 0; k < 16; k++) cth += b[k] != 0;
@@ -75,7 +84,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
             s_v[loc] = b[k];
             s_c[loc] = (uint16_t)col;
             loc++;
-            if (LDS_HIST) atomicAdd(&hist[col], 1u);
+            if (LDS_HIST) atomicAdd(&hist[slot_of(col)], 1u);
             else atomicAdd(&cnt[col], 1u);
           }
           if (++col == K) {
@@ -91,16 +100,10 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
       v[base + i] = s_v[i];
       c[base + i] = s_c[i];
     }
-    if (tile + gridDim.x < n_tiles) {  // uniform
-      uint64_t skip = 0;
-      for (uint32_t u0 = tile + threadIdx.x; u0 < tile + gridDim.x; u0 += 4 * kWG) {
-        uint32_t x4[4];
+    base += tot;
+    if (tile + 1 < t1) {
 #pragma unroll
-        for (int k = 0; k < 4; k++) x4[k] = u0 + k * kWG < tile + gridDim.x ? blk_nnz[u0 + k * kWG] : 0u;
-#pragma unroll
-        for (int k = 0; k < 4; k++) skip += x4[k];
-      }
-      base += (uint32_t)block_sum64<kWG>(skip, sh64);
+      for (int k = 0; k < 16; k++) b[k] = nb[k];
     }
     __syncthreads();  // staging and scan scratch are reused by the next tile
   }
@@ -109,7 +112,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
     // would keep the kernel busy long after its last tile
     uint32_t *dst = cnt + (n_rep ? (size_t)(1 + blockIdx.x % n_rep) * A : 0);
     for (uint32_t a = threadIdx.x; a < A; a += kWG) {
-      uint32_t t = hist[a];
+      uint32_t t = hist[slot_of(a)];
       if (t) atomicAdd(&dst[a], t);
     }
   }

@@ -130,6 +130,10 @@ inline uint32_t *tile_counts_of(const Layout &L, uint8_t *ws) {
   return L.n_blk ? (uint32_t *)(ws + L.chunk_words) + L.nc_max + 1 + L.n_pub : nullptr;
 }
 
+inline uint32_t *grp_counts_of(const Layout &L, uint8_t *ws) {  // nonzeros per group of tiles (one work-group step of k_quant_hist)
+  return L.n_blk ? tile_counts_of(L, ws) + L.n_blk : nullptr;
+}
+
 NormArgs norm_args(const rans_params &p, const Layout &L, uint8_t *ws, uint64_t n, uint8_t *d_stream, size_t cap) {
   return NormArgs{(const uint32_t *)(ws + L.cnt), L.cnt_rep, nullptr, (uint32_t *)(ws + L.fq), (uint2 *)(ws + L.enc_tab),
                   (uint4 *)(ws + L.enc_tab4), L.A, p, n, p.mode == RANS_MODE_CSR ? 0 : 1, d_stream, (uint64_t)cap};
@@ -138,7 +142,8 @@ NormArgs norm_args(const rans_params &p, const Layout &L, uint8_t *ws, uint64_t 
 // Extrema, Eq. 6, symbols and their histogram.  With `na` (dense mode, a container follows) the
 // histogram kernel also builds the frequency table and the container header.
 int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Layout &L, uint8_t *ws, uint8_t *d_sym,
-                    rans_qinfo *d_qinfo, hipStream_t st, uint32_t seq, const NormArgs *na) {
+                    rans_qinfo *d_qinfo, hipStream_t st, uint32_t seq, const NormArgs *na,
+                    uint32_t *tiles_per_grp = nullptr) {
   const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   uint32_t *cnt = (uint32_t *)(ws + L.cnt);
   uint32_t *cw_ = (uint32_t *)(ws + L.chunk_words);
@@ -146,6 +151,8 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
   const bool f16 = p.in_dtype == RANS_F16;
   const bool vec = aligned_to(d_x, 16) && aligned_to(d_sym, 8);
   const uint32_t V = vec ? (f16 ? 8 : 4) : 1;
+  static_assert(QNT * kQIter == kCsrTile, "a work-group step of k_quant_hist is V tiles of the CSR kernels");
+  if (tiles_per_grp) *tiles_per_grp = V;
   MinMaxPart *part = (MinMaxPart *)(ws + L.mm_part);
   uint32_t n_part = 0;
   if (n) {
@@ -171,11 +178,11 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
     auto launch_qh = [&](auto csr_tag) {
       constexpr bool CSRV = decltype(csr_tag)::value;
       if (f16) {
-        if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws));
-        else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws));
+        if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws), grp_counts_of(L, ws));
+        else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws), grp_counts_of(L, ws));
       } else {
-        if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws));
-        else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws));
+        if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws), grp_counts_of(L, ws));
+        else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws), grp_counts_of(L, ws));
       }
     };
     if (skip0) launch_qh(std::true_type{});
@@ -188,7 +195,7 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
 // Everything after the symbol histogram: CSR, table, coder, container.
 int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, const Layout &L, uint8_t *ws,
                        uint8_t *d_stream, size_t cap, uint64_t *d_stream_bytes, hipStream_t st, uint32_t seq,
-                       bool table_done) {
+                       bool table_done, uint32_t tiles_per_grp) {
   const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   uint32_t *cnt = (uint32_t *)(ws + L.cnt);
   const bool csr = p.mode == RANS_MODE_CSR;
@@ -199,13 +206,15 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     const uint32_t *blk = tile_counts_of(L, ws);  // counted by k_quant_hist
     uint32_t *row_end = (uint32_t *)(ws + L.row_end);
     if (n) {
-      const uint32_t g_compact = L.n_blk < kCompactBlocks ? L.n_blk : kCompactBlocks;
+      const uint32_t tpw = (L.n_blk + kCompactBlocks - 1) / kCompactBlocks;  // consecutive tiles per work-group
+      const uint32_t g_compact = (L.n_blk + tpw - 1) / tpw;
+      const uint32_t *grp = grp_counts_of(L, ws);
       if (lds_hist)
-        PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true>), dim3(g_compact), dim3(kWG), A * 4, st, d_sym, (uint32_t)n, al,
-                           (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, L.cnt_rep);
+        PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true>), dim3(g_compact), dim3(kWG), ((A + 15u) & ~15u) * 4, st, d_sym, (uint32_t)n, al,
+                           (uint32_t)p.cols, blk, grp, tiles_per_grp, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, tpw, L.cnt_rep);
       else
         PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<false>), dim3(g_compact), dim3(kWG), 0, st, d_sym, (uint32_t)n, al,
-                           (uint32_t)p.cols, blk, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, L.cnt_rep);
+                           (uint32_t)p.cols, blk, grp, tiles_per_grp, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, tpw, L.cnt_rep);
       LAUNCH_CHECK();
       uint32_t N = (uint32_t)p.rows;
       uint32_t g = (N + kWG - 1) / kWG;
@@ -698,16 +707,16 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
     auto launch_qh = [&](auto csr_tag) {
       constexpr bool CSRV = decltype(csr_tag)::value;
       if (vec)
-        PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, fold, na, tile_counts_of(L, ws));
+        PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, fold, na, tile_counts_of(L, ws), grp_counts_of(L, ws));
       else
-        PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, fold, na, tile_counts_of(L, ws));
+        PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, fold, na, tile_counts_of(L, ws), grp_counts_of(L, ws));
     };
     if (skip0) launch_qh(std::true_type{});
     else launch_qh(std::false_type{});
     LAUNCH_CHECK();
   }
   return launch_encode_tail(d_sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq,
-                            n_elems && p->mode != RANS_MODE_CSR);
+                            n_elems && p->mode != RANS_MODE_CSR, aligned_to(d_sym, 16) ? 16u : 1u);
 }
 
 int rans_compress(const void *d_x, uint64_t n_elems, const rans_params *p, uint8_t *d_stream, size_t stream_cap,
@@ -724,9 +733,10 @@ int rans_compress(const void *d_x, uint64_t n_elems, const rans_params *p, uint8
   const uint32_t seq = next_seq();
   const bool fold = n_elems && p->mode != RANS_MODE_CSR;  // dense: the histogram kernel also builds the table
   const NormArgs na = norm_args(*p, L, ws, n_elems, d_stream, stream_cap);
-  rc = launch_quantize(d_x, n_elems, *p, L, ws, ws + L.sym, nullptr, st, seq, fold ? &na : nullptr);
+  uint32_t tpg = 1;
+  rc = launch_quantize(d_x, n_elems, *p, L, ws, ws + L.sym, nullptr, st, seq, fold ? &na : nullptr, &tpg);
   if (rc) return rc;
-  return launch_encode_tail(ws + L.sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq, fold);
+  return launch_encode_tail(ws + L.sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq, fold, tpg);
 }
 
 int rans_decode(const uint8_t *d_stream, size_t stream_bytes, const rans_header *h_hdr, uint8_t *d_sym,

@@ -555,7 +555,8 @@ template <typename T, bool VEC, int NT, bool CSR>
 __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRef ctl, uint32_t q_bits,
                                                     uint8_t *sym, uint32_t *cnt, int skip_zero_bin,
                                                     const MinMaxPart *part, uint32_t n_part, rans_qinfo *qout,
-                                                    int fold_norm, NormArgs na, uint32_t *blk_nnz) {
+                                                    int fold_norm, NormArgs na, uint32_t *blk_nnz,
+                                                    uint32_t *grp_nnz) {
   constexpr bool IS_SYM = sizeof(T) == 1;
   constexpr int V = VEC ? (int)(16 / sizeof(T)) : 1;
   __shared__ uint32_t h[256 * kHistRep];
@@ -657,11 +658,17 @@ __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRe
   }
   if constexpr (CSR) {
     __syncthreads();
-    if (threadIdx.x < V) {
+    if (threadIdx.x < 64) {  // the first wave; V <= 16 of its lanes hold a tile each
+      const bool mine = threadIdx.x < V;
       const uint64_t t_idx = base / kCsrTile + threadIdx.x;
-      const uint32_t c_t = s_nz[threadIdx.x];
-      s_nz[threadIdx.x] = 0;
-      if (t_idx * kCsrTile < n) blk_nnz[t_idx] = c_t;
+      const uint32_t c_t = mine ? s_nz[threadIdx.x] : 0u;
+      const uint32_t upto = wave_incl_sum_scan(c_t);
+      if (mine) {
+        s_nz[threadIdx.x] = 0;
+        if (t_idx * kCsrTile < n) blk_nnz[t_idx] = c_t;
+      }
+      // and the nonzeros of the whole group of V tiles, which spares k_csr_compact most of its additions
+      if (threadIdx.x == 63) grp_nnz[base / tile] = upto;
     }
     __syncthreads();
   }

@@ -202,6 +202,15 @@ def test_unaligned_buffers():
     cc = B.Codec(pc, n)
     cc.qinfo.copy_(codec.qinfo)
     assert cc.container(cc.encode(sym)) == refc
+    assert cc.container(cc.compress(xd)) == refc  # CSR from the unaligned tensor: element-wise quantise path
+    # fp16 tensor at an odd element offset, CSR with several tiles of symbols per work-group step
+    n2 = 70001
+    b16 = _relu_normal(n2 + 3, 4, torch.float16)
+    x16 = b16[1:1 + n2]
+    p16 = B.make_params(8, 12, n2, 1, B.MODE_CSR, 64, 1280, B.F16)
+    ref16, _ = oracle.compress(x16.numpy().copy(), _oparams(p16))
+    c16 = B.Codec(p16, n2)
+    assert c16.container(c16.compress(b16.cuda()[1:1 + n2])) == ref16
 
 
 def test_edge_cases():

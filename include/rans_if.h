@@ -24,6 +24,13 @@
  *     first such error.  No call aborts or throws.
  *   - Limits: n_elems <= 2^30; 1 <= Q <= 8; 1 <= M <= 15; 1 <= S <= 65536;
  *     CSR mode needs cols <= 65535.
+ *   - Stream capture: every entry point that takes a `stream`, except
+ *     rans_last_status and rans_decode / rans_decompress without a header
+ *     hint (these read a few bytes back and synchronise), only enqueues
+ *     kernels and may be captured into a HIP graph.  A replay writes the same
+ *     bytes as the eager call.  The encoding entry points start every replay
+ *     with a clean status; an error that a replayed decoding call records
+ *     stays in the workspace until another call has run on it.
  */
 #ifndef RANS_IF_H
 #define RANS_IF_H

@@ -16,6 +16,11 @@ namespace {
 __device__ void reset_call_state(const CtlRef &ctl, uint32_t *cnt, uint32_t A, uint32_t *chunk_words, uint32_t nc) {
   if (threadIdx.x == 0) {
     ctl->last_seq = ctl.seq;
+    // A call captured into a graph keeps its number on every replay: an error that the previous replay recorded
+    // is not this one's.  (Nothing else of this call has run yet: the kernel that gets here is its first, and
+    // no other work-group of it touches the status.)
+    if ((uint32_t)(*(volatile unsigned long long *)&ctl.p->status >> 32) == ctl.seq)
+      *(volatile unsigned long long *)&ctl.p->status = 0;
     ctl->len_d = 0;
     ctl->payload_off = ctl->dir_off = ctl->total_bytes = 0;
     ctl->nnz = 0;

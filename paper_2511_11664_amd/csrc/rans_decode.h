@@ -363,7 +363,8 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
                                                      uint32_t M, uint32_t S, uint32_t cs, uint32_t groups,
                                                      uint64_t len, uint64_t dir_off, uint64_t payload_off,
                                                      float x_min, float x_max, uint32_t q_bits, uint32_t tmp_off,
-                                                     HdrImage img, rans_header hdr, rans_qinfo *qout, Sink sink) {
+                                                     uint32_t misc_off, HdrImage img, rans_header hdr,
+                                                     rans_qinfo *qout, Sink sink) {
   extern __shared__ __align__(16) uint32_t l_mem[];
   constexpr uint32_t kWinBytes = 32 * NT;             // 16-word window per stream, one 32-byte line each
   constexpr uint32_t NW = NT / 64;                    // waves per work-group
@@ -371,11 +372,13 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
   if (blockIdx.x == 0 && threadIdx.x < 64) dec_check_header(in, bytes, ctl, img, hdr, qout);
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
   const uint32_t total = 1u << M, mask = total - 1;
-  // LDS: [window][lut][misc: 48 words][tab: A x 8 B], or WIDE: [window][wide table] and
-  // [lut][misc][tab] at tmp_off.  The window and the table the coder reads sit at constant offsets, so
-  // their addresses need no base arithmetic.
+  // LDS: [window][lut][misc: 48 words][tab: A x 8 B], or WIDE: [window][wide table], [lut] at tmp_off and
+  // [misc][tab] behind it or, with misc_off != 0, there (the tables of the build may lie over the window, which
+  // is filled after the build).  The window and the table the coder reads sit at constant offsets, so their
+  // addresses need no base arithmetic.
   LutT *lut = (LutT *)(l_mem + (WIDE ? tmp_off : kWinBytes) / 4);
-  uint32_t *misc = (uint32_t *)lut + ((total * (uint32_t)sizeof(LutT) + 15) / 16) * 4;
+  uint32_t *misc = (WIDE && misc_off) ? l_mem + misc_off / 4
+                                      : (uint32_t *)lut + ((total * (uint32_t)sizeof(LutT) + 15) / 16) * 4;
   uint64_t *misc64 = (uint64_t *)(misc + 16);
   uint2 *tab = (uint2 *)(misc + 48);
   uint2 *wide = (uint2 *)(l_mem + kWinBytes / 4);

@@ -118,6 +118,8 @@ inline uint32_t next_seq() {
   return v;
 }
 
+constexpr uint32_t kDecWideGroupMinChunks = 192;
+
 inline uint32_t grid_for(uint64_t n, uint32_t per_block, uint32_t cap) {
   uint64_t g = (n + per_block - 1) / per_block;
   if (g < 1) g = 1;
@@ -392,19 +394,25 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
   const bool csr = h.p.mode == RANS_MODE_CSR;
   const size_t lut_elem = A <= 256 ? 1 : 2;
   // work-group size of the fast decoder: 1024 lanes share one set of tables when a chunk has that many streams
-  const uint32_t nt = S > 512 ? 1024u : 256u;
+  // ... and there are enough chunks to give every CU one; with fewer, smaller groups spread a chunk over more CUs
+  // (two of 512 lanes where the per-slot table takes most of a CU's LDS and each group has to build its own)
+  const uint32_t nt = S <= 512 ? 256u : (h.n_chunks >= kDecWideGroupMinChunks ? 1024u : (M >= 14 ? 512u : 256u));
   const uint32_t groups_f = (S + nt - 1) / nt;
   const size_t win_b = 32 * (size_t)nt;
   const size_t tmp_b = align_up((size_t)lut_elem << M, 16) + 192 + (size_t)A * 8;  // [lut][misc][tab]
   const size_t lds_two = win_b + tmp_b;
   // wide table: 8 bytes per slot after the window; the build-time tables alias the window if they fit there
   const size_t wide_b = (size_t)8 << M;
+  // (or only the slot -> symbol table does, and the rest follows the wide table)
+  const size_t lut_b = align_up((size_t)lut_elem << M, 16);
   const bool tmp_alias = tmp_b <= win_b;
-  const size_t lds_wide = win_b + wide_b + (tmp_alias ? 0 : tmp_b);
-  const uint32_t tmp_off = (uint32_t)(tmp_alias ? 0 : win_b + wide_b);
+  const bool lut_alias = !tmp_alias && lut_b <= win_b;
+  const size_t lds_wide = win_b + wide_b + (tmp_alias ? 0 : (lut_alias ? tmp_b - lut_b : tmp_b));
+  const uint32_t tmp_off = (uint32_t)((tmp_alias || lut_alias) ? 0 : win_b + wide_b);
+  const uint32_t misc_off = (uint32_t)(lut_alias ? win_b + wide_b : 0);
   const size_t kLdsMax = 160 * 1024;
   // worth it when the table is shared by enough lanes: always up to 2^13 slots, at 2^14 only for 1024-lane groups
-  const bool use_wide = lds_wide <= kLdsMax && (M <= 13 || nt == 1024);
+  const bool use_wide = lds_wide <= kLdsMax && (M <= 13 || nt >= 512);
   const size_t lds_fast = use_wide ? lds_wide : lds_two;
   // the fast decoder indexes a chunk's outputs and words with 32-bit offsets
   const bool small_chunk = L.chunk_len_max < (1ull << 29) && L.capw < (1u << 20);
@@ -436,7 +444,7 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
       const uint64_t dir_off = kHdrBytes + align_up((size_t)A * 2, 8);
 #define FDEC_ARGS                                                                                            \
   d_stream, (uint64_t)stream_bytes, ctl, A, M, S, h.p.chunk_syms, groups_f, h.len_d, dir_off, payload_off, h.x_min, \
-      h.x_max, h.p.q_bits, tmp_off, img, h, d_qinfo
+      h.x_max, h.p.q_bits, tmp_off, misc_off, img, h, d_qinfo
 #define FDEC_ONE(SINKT, LUTT, MULV, NTV, WIDEV, sinkv)                                                              \
   do {                                                                                                             \
     auto kfn = k_decode_fast<SINKT, LUTT, MULV, NTV, WIDEV>;                                                       \
@@ -446,18 +454,20 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
     if (lds_fast > 64 * 1024 && attr_rc != hipSuccess) return RANS_ERR_HIP;                                        \
     PROF_LAUNCH(KID_DECODE, kfn, grid, blk, lds_fast, st, FDEC_ARGS, sinkv);                                       \
   } while (0)
+#define FDEC_NT(SINKT, LUTT, MULV, WIDEV, sinkv)                                                                   \
+  do {                                                                                                             \
+    if (nt == 1024) FDEC_ONE(SINKT, LUTT, MULV, 1024, WIDEV, sinkv);                                               \
+    else if (nt == 512) FDEC_ONE(SINKT, LUTT, MULV, 512, WIDEV, sinkv);                                            \
+    else FDEC_ONE(SINKT, LUTT, MULV, 256, WIDEV, sinkv);                                                           \
+  } while (0)
 #define FDEC_LAUNCH(SINKT, LUTT, sinkv)                                                                            \
   do {                                                                                                             \
     if (use_wide) {                                                                                                \
-      if (M >= 8 && nt == 1024) FDEC_ONE(SINKT, LUTT, true, 1024, true, sinkv);                                    \
-      else if (M >= 8) FDEC_ONE(SINKT, LUTT, true, 256, true, sinkv);                                              \
-      else if (nt == 1024) FDEC_ONE(SINKT, LUTT, false, 1024, true, sinkv);                                        \
-      else FDEC_ONE(SINKT, LUTT, false, 256, true, sinkv);                                                         \
+      if (M >= 8) FDEC_NT(SINKT, LUTT, true, true, sinkv);                                                         \
+      else FDEC_NT(SINKT, LUTT, false, true, sinkv);                                                               \
     } else {                                                                                                       \
-      if (M >= 8 && nt == 1024) FDEC_ONE(SINKT, LUTT, true, 1024, false, sinkv);                                   \
-      else if (M >= 8) FDEC_ONE(SINKT, LUTT, true, 256, false, sinkv);                                             \
-      else if (nt == 1024) FDEC_ONE(SINKT, LUTT, false, 1024, false, sinkv);                                       \
-      else FDEC_ONE(SINKT, LUTT, false, 256, false, sinkv);                                                        \
+      if (M >= 8) FDEC_NT(SINKT, LUTT, true, false, sinkv);                                                        \
+      else FDEC_NT(SINKT, LUTT, false, false, sinkv);                                                              \
     }                                                                                                              \
   } while (0)
       if (csr) {
@@ -475,6 +485,7 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
         FDEC_LAUNCH(FSinkFloat<__half>, uint8_t, sk);
       }
 #undef FDEC_LAUNCH
+#undef FDEC_NT
 #undef FDEC_ONE
 #undef FDEC_ARGS
       LAUNCH_CHECK();

@@ -104,6 +104,11 @@ DENSE_CASES = [
     (2000003, torch.float16, 8, 14, 1024, 1024),
     # more work-groups than the encoder places itself: separate size scan and gather kernels
     (1200007, torch.float32, 8, 12, 32, 64),
+    # few chunks of many streams: the decoder splits a chunk over groups of 512 (M = 14) or 256 lanes, the last
+    # group ragged
+    (200003, torch.float16, 8, 14, 600, 600 * 64),
+    (200003, torch.float32, 8, 12, 1000, 1000 * 40),
+    (150001, torch.float32, 7, 13, 777, 0),
 ]
 
 
@@ -133,6 +138,9 @@ CSR_CASES = [
     (50, 3000, torch.float32, 8, 13, 64, 640),
     (3000, 64, torch.float16, 8, 12, 64, 0),
     (3000, 64, torch.float32, 6, 12, 128, 128 * 200),
+    # few chunks of many streams (ragged last group of the decoder), alphabet of 257 symbols at M = 14 and 12
+    (2000, 256, torch.float16, 8, 14, 600, 600 * 100),
+    (2000, 256, torch.float32, 8, 12, 1000, 0),
 ]
 
 

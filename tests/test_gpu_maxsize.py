@@ -7,7 +7,7 @@ properties that hold at any size.
   * the frequency table in the container against the oracle's normalisation of the histogram of ALL decoded
     symbols (counted by torch, not by the library);
   * sampled streams of sampled chunks (first, inner, last ragged): final state, word count and words against
-    the oracle's single-stream coder run on oracle-quantised symbols (Eq. 2, O10 layout);
+    the oracle's single-stream coder run on oracle-quantised symbols (Eq. 2; the chunk layout of the container: states, word counts, words per stream);
   * the directory: monotone, ends at the container size;
   * CSR: decodes to exactly the symbols of the dense path, l_D = 2 nnz + N, table = normalised counts of
     v, c and r recomputed by torch.

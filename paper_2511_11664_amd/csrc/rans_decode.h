@@ -668,24 +668,44 @@ __global__ __launch_bounds__(kWG) void k_row_part(const uint16_t *r, uint32_t N,
 // One tile of rows: row offsets by a local scan of r, the tile zeroed in LDS, every nonzero of the tile
 // placed (its row found by bisection of the local offsets) and checked (1 <= v < 2^Q, c < K, c strictly
 // increasing inside a row), then the tile written out: as symbols, or dequantised (x = s (xhat - z)).
-// D holds v, c, r as 16-bit symbols; part[] the exclusive scan of the tile sums, part[n_tiles] = their total.
+// D holds v, c, r as 16-bit symbols; part[] the exclusive scan of the tile sums with part[n_tiles] = their total
+// (`scanned`), or - with few enough tiles that every work-group can add up the sums before its own - the tile
+// sums themselves, which spares the scan kernel.
 template <typename OutT>
-__global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const uint32_t *part, uint32_t N, uint32_t K,
-                                                      uint32_t tile_rows, uint32_t q_bits, OutT *out, CtlRef ctl) {
+__global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const uint32_t *part, int scanned, uint32_t N,
+                                                      uint32_t K, uint32_t tile_rows, uint32_t q_bits, OutT *out,
+                                                      CtlRef ctl) {
   extern __shared__ __align__(16) uint32_t l_mem[];
   __shared__ uint32_t sh[kWG / 64];
+  __shared__ uint64_t sh64[kWG / 64];
   if (get_status(ctl) != 0) return;
   const uint32_t nnz = ctl->nnz;
   const uint32_t i0 = blockIdx.x * tile_rows;
   const uint32_t rows = i0 + tile_rows < N ? tile_rows : N - i0;
   uint32_t *roff = l_mem;                                          // rows + 1 local offsets
   uint8_t *dense = (uint8_t *)(l_mem + ((rows + 1 + 3) & ~3u));   // rows * K symbols
-  const uint32_t base = part[blockIdx.x];
   const uint32_t n_tiles = gridDim.x;
-  if (blockIdx.x == n_tiles - 1 && part[n_tiles] != nnz) {  // sum of r must be the number of nonzeros
+  uint64_t base64, total;
+  if (scanned) {
+    base64 = part[blockIdx.x];
+    total = part[n_tiles];
+  } else {
+    uint64_t loc = 0;
+    for (uint32_t u0 = threadIdx.x; u0 < blockIdx.x; u0 += 4 * kWG) {
+      uint32_t x4[4];
+#pragma unroll
+      for (int k = 0; k < 4; k++) x4[k] = u0 + k * kWG < blockIdx.x ? part[u0 + k * kWG] : 0u;
+#pragma unroll
+      for (int k = 0; k < 4; k++) loc += x4[k];
+    }
+    base64 = block_sum64<kWG>(loc, sh64);
+    total = base64 + part[blockIdx.x];  // of interest in the last work-group only
+  }
+  if ((blockIdx.x == n_tiles - 1 && total != nnz) || base64 > nnz) {  // sum of r must be the number of nonzeros
     if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
     return;
   }
+  const uint32_t base = (uint32_t)base64;
   const uint16_t *r = D + 2ull * nnz + i0;
   uint32_t carry = 0;
   for (uint32_t b0 = 0; b0 < rows; b0 += kWG) {

@@ -119,6 +119,7 @@ inline uint32_t next_seq() {
 }
 
 constexpr uint32_t kDecWideGroupMinChunks = 192;
+constexpr uint32_t kExpandOwnSumMaxTiles = 4096;
 
 inline uint32_t grid_for(uint64_t n, uint32_t per_block, uint32_t cap) {
   uint64_t g = (n + per_block - 1) / per_block;
@@ -542,8 +543,12 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
     uint32_t *part = (uint32_t *)(ws + L.row_off);  // n_tiles + 1 entries (n_tiles <= N)
     PROF_LAUNCH(KID_ROW_SCAN, k_row_part, dim3(n_tiles), dim3(kWG), 0, st, D + 2 * nnz, N, K, tile_rows, part, ctl);
     LAUNCH_CHECK();
-    PROF_LAUNCH(KID_SCAN, k_scan_u32, dim3(1), dim3(kBig), 0, st, part, n_tiles);
-    LAUNCH_CHECK();
+    // up to a few thousand tiles every work-group of the expand kernel adds up the sums before its own
+    const int scanned = n_tiles > kExpandOwnSumMaxTiles;
+    if (scanned) {
+      PROF_LAUNCH(KID_SCAN, k_scan_u32, dim3(1), dim3(kBig), 0, st, part, n_tiles);
+      LAUNCH_CHECK();
+    }
     const size_t lds = (((size_t)tile_rows + 1 + 3) & ~(size_t)3) * 4 + (((size_t)tile_rows * K + 3) & ~(size_t)3);
     if (lds > 64 * 1024) {  // a single long row: allow dynamic LDS beyond the default 64 KB (once per instantiation)
       static const hipError_t a0 = hipFuncSetAttribute((const void *)k_csr_to_dense<uint8_t>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
@@ -552,13 +557,13 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
       if (a0 != hipSuccess || a1 != hipSuccess || a2 != hipSuccess) return RANS_ERR_HIP;
     }
     if (out_kind == 0)
-      PROF_LAUNCH(KID_CSR_EXPAND, (k_csr_to_dense<uint8_t>), dim3(n_tiles), dim3(kWG), lds, st, D, part, N, K, tile_rows,
+      PROF_LAUNCH(KID_CSR_EXPAND, (k_csr_to_dense<uint8_t>), dim3(n_tiles), dim3(kWG), lds, st, D, part, scanned, N, K, tile_rows,
                   h.p.q_bits, (uint8_t *)d_out, ctl);
     else if (out_kind == 1)
-      PROF_LAUNCH(KID_CSR_EXPAND, (k_csr_to_dense<float>), dim3(n_tiles), dim3(kWG), lds, st, D, part, N, K, tile_rows,
+      PROF_LAUNCH(KID_CSR_EXPAND, (k_csr_to_dense<float>), dim3(n_tiles), dim3(kWG), lds, st, D, part, scanned, N, K, tile_rows,
                   h.p.q_bits, (float *)d_out, ctl);
     else
-      PROF_LAUNCH(KID_CSR_EXPAND, (k_csr_to_dense<__half>), dim3(n_tiles), dim3(kWG), lds, st, D, part, N, K, tile_rows,
+      PROF_LAUNCH(KID_CSR_EXPAND, (k_csr_to_dense<__half>), dim3(n_tiles), dim3(kWG), lds, st, D, part, scanned, N, K, tile_rows,
                   h.p.q_bits, (__half *)d_out, ctl);
     LAUNCH_CHECK();
   }

@@ -129,17 +129,55 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
     __syncthreads();
   }
   uint32_t seen = 0;
-  for (uint32_t i = blockIdx.x * kWG + threadIdx.x; i < N; i += gridDim.x * kWG) {
-    uint32_t e1 = row_end[i], e0 = i ? row_end[i - 1] : 0;
-    uint32_t ri = e1 - e0;
-    r[i] = (uint16_t)ri;
-    if (LDS_HIST) atomicAdd(&hist[ri], 1u);
-    else atomicAdd(&cnt[ri], 1u);
-    if (i == N - 1) {
+  // a lane takes four consecutive rows: one 16-byte load of their ends, one 8-byte store of their counts;
+  // the loads of four such quads are in flight together
+  const uint32_t n_quads = (N + 3) / 4;
+  constexpr int kU = 4;
+  auto load_quad = [&](uint32_t q, uint32_t (&e)[5]) {
+    const uint32_t i = 4 * q;
+    e[0] = i ? row_end[i - 1] : 0;
+    if (i + 4 <= N) {
+      const uint4 w = *(const uint4 *)(row_end + i);
+      e[1] = w.x; e[2] = w.y; e[3] = w.z; e[4] = w.w;
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; k++) e[k + 1] = i + k < N ? row_end[i + k] : e[k];
+    }
+  };
+  auto do_quad = [&](uint32_t q, const uint32_t (&e)[5]) {
+    const uint32_t i = 4 * q;
+    uint32_t rr[4];
+#pragma unroll
+    for (int k = 0; k < 4; k++) rr[k] = e[k + 1] - e[k];
+    if (i + 4 <= N) {
+      *(uint2 *)(r + i) = make_uint2(rr[0] | (rr[1] << 16), rr[2] | (rr[3] << 16));
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; k++)
+        if (i + k < N) r[i + k] = (uint16_t)rr[k];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+      if (i + k < N) {
+        if (LDS_HIST) atomicAdd(&hist[rr[k]], 1u);
+        else atomicAdd(&cnt[rr[k]], 1u);
+      }
+    }
+    if (i + 4 >= N) {  // the quad with the last row (ends behind it repeat the last row's)
+      const uint32_t e1 = e[4];
       ctl->nnz = e1;
       // an exchange, for its returned value (see below): l_D has to be in place before this work-group's ticket
       seen |= (uint32_t)__hip_atomic_exchange(&ctl->len_d, 2ull * e1 + N, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+  };
+  for (uint32_t q0 = blockIdx.x * (kWG * kU) + threadIdx.x; q0 < n_quads; q0 += gridDim.x * (kWG * kU)) {
+    uint32_t e[kU][5];
+#pragma unroll
+    for (int u = 0; u < kU; u++)
+      if (q0 + u * kWG < n_quads) load_quad(q0 + u * kWG, e[u]);
+#pragma unroll
+    for (int u = 0; u < kU; u++)
+      if (q0 + u * kWG < n_quads) do_quad(q0 + u * kWG, e[u]);
   }
   const bool hand_over = fold_norm || na.n_rep;  // the last work-group reads what the others added
   if (LDS_HIST) {

@@ -708,15 +708,45 @@ __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const u
   const uint32_t base = (uint32_t)base64;
   const uint16_t *r = D + 2ull * nnz + i0;
   uint32_t carry = 0;
-  for (uint32_t b0 = 0; b0 < rows; b0 += kWG) {
-    const uint32_t i = b0 + threadIdx.x;
+  if (rows <= kWG) {
+    const uint32_t i = threadIdx.x;
     const uint32_t v = i < rows ? r[i] : 0;
-    uint32_t tot;
-    const uint32_t ex = block_excl_scan<kWG>(v, sh, &tot);
-    if (i < rows) roff[i] = carry + ex;
-    carry += tot;
-    __syncthreads();
+    const uint32_t ex = block_excl_scan<kWG>(v, sh, &carry);
+    if (i < rows) roff[i] = ex;
+  } else {
+    // many short rows (at most 16 kWG of them, by the host's choice of tile): a lane adds up 16 consecutive
+    // counts by itself, one scan over the lanes' sums
+    constexpr int kRpt = 16;
+    const uint32_t t0 = threadIdx.x * kRpt;
+    uint32_t w[kRpt / 2], loc[kRpt];
+    const bool whole = t0 + kRpt <= rows;
+    if (whole) {
+      __builtin_memcpy(w, r + t0, 2 * kRpt);  // 2-byte aligned
+    } else {
+#pragma unroll
+      for (int k = 0; k < kRpt / 2; k++) {
+        const uint32_t a = t0 + 2 * k < rows ? r[t0 + 2 * k] : 0u, b = t0 + 2 * k + 1 < rows ? r[t0 + 2 * k + 1] : 0u;
+        w[k] = a | (b << 16);
+      }
+    }
+    uint32_t sum = 0;
+#pragma unroll
+    for (int k = 0; k < kRpt; k++) {
+      loc[k] = sum;
+      sum += (w[k >> 1] >> (16 * (k & 1))) & 0xffffu;
+    }
+    const uint32_t ex = block_excl_scan<kWG>(sum, sh, &carry);
+    if (whole) {
+#pragma unroll
+      for (int k = 0; k < kRpt; k += 4)
+        *(uint4 *)(roff + t0 + k) = make_uint4(ex + loc[k], ex + loc[k + 1], ex + loc[k + 2], ex + loc[k + 3]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < kRpt; k++)
+        if (t0 + k < rows) roff[t0 + k] = ex + loc[k];
+    }
   }
+  __syncthreads();
   if (threadIdx.x == 0) roff[rows] = carry;
   const uint32_t cells = rows * K;
   for (uint32_t i = threadIdx.x; i < (cells + 3) / 4; i += kWG) ((uint32_t *)dense)[i] = 0;

@@ -220,10 +220,9 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
                            (uint32_t)p.cols, blk, grp, tiles_per_grp, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, tpw, L.cnt_rep);
       LAUNCH_CHECK();
       uint32_t N = (uint32_t)p.rows;
-      uint32_t g = (N + kWG - 1) / kWG;
-      // few work-groups: each ends with additions to the same few addresses and a ticket; more only when a
-      // lane would otherwise walk very many rows
-      const uint32_t g_cap = N > (1u << 20) ? 512u : 128u;
+      uint32_t g = (N + 16 * kWG - 1) / (16 * kWG);  // a lane takes 16 rows per step
+      // few work-groups: each ends with additions to the same few addresses and a ticket
+      const uint32_t g_cap = N > (1u << 20) ? 256u : 128u;
       g = g > g_cap ? g_cap : g;
       const int fold = A <= kNormWaveA;  // one wave of the last work-group can build the table
       const NormArgs na = norm_args(p, L, ws, n, d_stream, cap);

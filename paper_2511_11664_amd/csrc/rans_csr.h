@@ -39,8 +39,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
   extern __shared__ uint32_t hist[];
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
-  __shared__ uint8_t s_v[kCsrTile];
-  __shared__ uint16_t s_c[kCsrTile];
+  __shared__ uint32_t s_vc[kCsrTile];  // value | column << 8 of the tile's nonzeros, in order (one LDS write each)
   // A lane holds 16 consecutive symbols, so at each step the columns of a wave's lanes are 16 apart and
   // would fall into two LDS banks: the histogram keeps column j in slot j ^ ((j >> 4) & 15) instead (a
   // permutation within each aligned block of 16 slots; the array is A rounded up to 16).
@@ -81,8 +80,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
       for (int k = 0; k < 16; k++) {
         if (e0 + k < n) {
           if (b[k]) {
-            s_v[loc] = b[k];
-            s_c[loc] = (uint16_t)col;
+            s_vc[loc] = b[k] | (col << 8);
             loc++;
             if (LDS_HIST) atomicAdd(&hist[slot_of(col)], 1u);
             else atomicAdd(&cnt[col], 1u);
@@ -97,8 +95,9 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
     }
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < tot; i += kWG) {
-      v[base + i] = s_v[i];
-      c[base + i] = s_c[i];
+      const uint32_t vc = s_vc[i];
+      v[base + i] = (uint8_t)vc;
+      c[base + i] = (uint16_t)(vc >> 8);
     }
     base += tot;
     if (tile + 1 < t1) {

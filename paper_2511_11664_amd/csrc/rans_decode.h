@@ -645,7 +645,8 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
 
 // Decoder side of the modified CSR (Sec. 3.1: the cumulative sum of r is taken at decode time, then v is
 // scattered).  Rows are cut into tiles of `tile_rows` rows; k_row_part sums r over each tile (and checks
-// r[i] <= K), a single-work-group scan turns the sums into the index of each tile's first nonzero, and
+// r[i] <= K); the index of a tile's first nonzero is the sum of the tile sums before it, which the tile's
+// work-group adds up itself (a single-work-group scan kernel does it when there are thousands of tiles), and
 // k_csr_to_dense rebuilds one tile per work-group in LDS and writes it out in the output type.
 __global__ __launch_bounds__(kWG) void k_row_part(const uint16_t *r, uint32_t N, uint32_t K, uint32_t tile_rows,
                                                   uint32_t *part, CtlRef ctl) {

@@ -366,3 +366,41 @@ def test_full_size_csr_config_repeated():
     assert B.rans_last_status(codec.ws) == 0
     sym_ref, _ = oracle.quantize(x.numpy(), 8)
     assert np.array_equal(sym.cpu().numpy(), sym_ref)
+
+
+def _random_cases(seed, count):
+    """Seeded parameter mixes: sizes, dtypes, bit widths, table sizes, stream and chunk counts, both modes."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(count):
+        q = int(rng.integers(1, 9))
+        dtype = torch.float16 if rng.random() < 0.4 else torch.float32
+        s = int(rng.choice([1, 3, 32, 64, 100, 256, 300, 512, 640, 1024, 1500, 2048]))
+        if rng.random() < 0.5:   # dense
+            n = int(rng.integers(1, 250000))
+            m = int(rng.integers(q, 16))
+            rows, cols, mode = n, 1, B.MODE_DENSE
+            length = n
+        else:
+            cols = int(rng.choice([1, 2, 4, 7, 16, 60, 64, 255, 256, 257, 1000, 5000]))
+            rows = int(rng.integers(1, max(2, 250000 // cols)))
+            n = rows * cols
+            need = max(q, int(np.ceil(np.log2(cols + 1))))
+            m = int(rng.integers(need, 16))
+            mode = B.MODE_CSR
+            length = 2 * n + rows
+        per_chunk = int(rng.choice([0, 1, 2, 8, 64, 300]))
+        cs = per_chunk * s
+        if cs and (length + cs - 1) // cs > 20000:   # keeps the grid within what a small test should launch
+            cs = 0
+        cases.append((i, n, rows, cols, mode, dtype, q, m, s, cs, float(rng.choice([0.0, -0.5, 0.8])),
+                      float(rng.choice([1.0, 1e-3, 300.0]))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(2511, 48), ids=lambda c: f"r{c[0]}")
+def test_random_parameter_mixes(case):
+    i, n, rows, cols, mode, dtype, q, m, s, cs, shift, scale = case
+    x = _relu_normal(n, 1000 + i, dtype, shift=shift, scale=scale)
+    p = B.make_params(q, m, rows, cols, mode, s, cs, B.F16 if dtype == torch.float16 else B.F32)
+    _check_all(x, p, f"random {i}")

@@ -656,7 +656,19 @@ __global__ __launch_bounds__(kWG) void k_row_part(const uint16_t *r, uint32_t N,
   const uint32_t i1 = i0 + tile_rows < N ? i0 + tile_rows : N;
   uint64_t loc = 0;
   bool bad = false;
-  for (uint32_t i = i0 + threadIdx.x; i < i1; i += kWG) {
+  // eight counts per lane and step (one 16-byte load, 2-byte aligned: r starts behind v and c), the tail one by one
+  const uint32_t n8 = (i1 - i0) / 8;
+  for (uint32_t q = threadIdx.x; q < n8; q += kWG) {
+    uint32_t w[4];
+    __builtin_memcpy(w, r + i0 + 8 * q, 16);
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+      const uint32_t a = w[k] & 0xffffu, b = w[k] >> 16;
+      bad |= a > K || b > K;
+      loc += a + b;
+    }
+  }
+  for (uint32_t i = i0 + 8 * n8 + threadIdx.x; i < i1; i += kWG) {
     const uint32_t v = r[i];
     bad |= v > K;
     loc += v;

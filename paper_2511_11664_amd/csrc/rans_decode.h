@@ -695,8 +695,9 @@ __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const u
   const uint32_t nnz = ctl->nnz;
   const uint32_t i0 = blockIdx.x * tile_rows;
   const uint32_t rows = i0 + tile_rows < N ? tile_rows : N - i0;
-  uint32_t *roff = l_mem;                                          // rows + 1 local offsets
-  uint8_t *dense = (uint8_t *)(l_mem + ((rows + 1 + 3) & ~3u));   // rows * K symbols
+  // rows + 1 local offsets; 16 bits do: a tile has at most 65535 cells and k_row_part has checked r[i] <= K
+  uint16_t *roff = (uint16_t *)l_mem;
+  uint8_t *dense = (uint8_t *)l_mem + ((2 * (rows + 1) + 15) & ~15u);  // rows * K symbols
   const uint32_t n_tiles = gridDim.x;
   uint64_t base64, total;
   if (scanned) {
@@ -725,7 +726,7 @@ __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const u
     const uint32_t i = threadIdx.x;
     const uint32_t v = i < rows ? r[i] : 0;
     const uint32_t ex = block_excl_scan<kWG>(v, sh, &carry);
-    if (i < rows) roff[i] = ex;
+    if (i < rows) roff[i] = (uint16_t)ex;
   } else {
     // many short rows (at most 16 kWG of them, by the host's choice of tile): a lane adds up 16 consecutive
     // counts by itself, one scan over the lanes' sums
@@ -751,16 +752,17 @@ __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const u
     const uint32_t ex = block_excl_scan<kWG>(sum, sh, &carry);
     if (whole) {
 #pragma unroll
-      for (int k = 0; k < kRpt; k += 4)
-        *(uint4 *)(roff + t0 + k) = make_uint4(ex + loc[k], ex + loc[k + 1], ex + loc[k + 2], ex + loc[k + 3]);
+      for (int k = 0; k < kRpt; k += 8)
+        *(uint4 *)(roff + t0 + k) = make_uint4((ex + loc[k]) | ((ex + loc[k + 1]) << 16), (ex + loc[k + 2]) | ((ex + loc[k + 3]) << 16),
+                                               (ex + loc[k + 4]) | ((ex + loc[k + 5]) << 16), (ex + loc[k + 6]) | ((ex + loc[k + 7]) << 16));
     } else {
 #pragma unroll
       for (int k = 0; k < kRpt; k++)
-        if (t0 + k < rows) roff[t0 + k] = ex + loc[k];
+        if (t0 + k < rows) roff[t0 + k] = (uint16_t)(ex + loc[k]);
     }
   }
   __syncthreads();
-  if (threadIdx.x == 0) roff[rows] = carry;
+  if (threadIdx.x == 0) roff[rows] = (uint16_t)carry;
   const uint32_t cells = rows * K;
   for (uint32_t i = threadIdx.x; i < (cells + 3) / 4; i += kWG) ((uint32_t *)dense)[i] = 0;
   __syncthreads();

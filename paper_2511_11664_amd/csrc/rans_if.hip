@@ -548,7 +548,7 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
       PROF_LAUNCH(KID_SCAN, k_scan_u32, dim3(1), dim3(kBig), 0, st, part, n_tiles);
       LAUNCH_CHECK();
     }
-    const size_t lds = (((size_t)tile_rows + 1 + 3) & ~(size_t)3) * 4 + (((size_t)tile_rows * K + 3) & ~(size_t)3);
+    const size_t lds = ((2 * ((size_t)tile_rows + 1) + 15) & ~(size_t)15) + (((size_t)tile_rows * K + 3) & ~(size_t)3);
     if (lds > 64 * 1024) {  // a single long row: allow dynamic LDS beyond the default 64 KB (once per instantiation)
       static const hipError_t a0 = hipFuncSetAttribute((const void *)k_csr_to_dense<uint8_t>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
       static const hipError_t a1 = hipFuncSetAttribute((const void *)k_csr_to_dense<float>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);

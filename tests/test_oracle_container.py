@@ -226,3 +226,22 @@ def test_whole_path_on_synthetic_workloads(oracle, name, shrink, over):
     err = np.abs(y.astype(np.float64) - x.astype(np.float64)).max()
     assert err <= qi.scale * 1.01 + (abs(float(x.astype(np.float64).max())) * 2 ** -10 if w.in_dtype else 0)
     assert len(buf) < x.nbytes
+
+
+def test_container_digests_of_formula_inputs_are_unchanged():
+    """The oracle's containers for inputs given by closed formulas against the digests stored by
+    tests/golden/make_oracle_digests.py: an unintended change of the arithmetic or the layout changes a digest."""
+    import importlib.util
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_oracle_digests", os.path.join(here, "golden", "make_oracle_digests.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = {}
+    for line in open(os.path.join(here, "golden", "oracle_container_digests.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, n, h = line.split()
+        stored[name] = (int(n), h)
+    got = {name: (n, h) for name, n, h in mod.digests()}
+    assert got == stored

@@ -404,3 +404,27 @@ def test_random_parameter_mixes(case):
     x = _relu_normal(n, 1000 + i, dtype, shift=shift, scale=scale)
     p = B.make_params(q, m, rows, cols, mode, s, cs, B.F16 if dtype == torch.float16 else B.F32)
     _check_all(x, p, f"random {i}")
+
+
+def test_formula_inputs_match_the_stored_oracle_digests():
+    """The containers of the formula-given inputs of tests/golden/make_oracle_digests.py, made by the HIP path,
+    against the digests that script stored from the oracle."""
+    import hashlib
+    import importlib.util
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_oracle_digests", os.path.join(here, "golden", "make_oracle_digests.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = {}
+    for line in open(os.path.join(here, "golden", "oracle_container_digests.txt")):
+        if not line.startswith("#") and line.strip():
+            name, nb, h = line.split()
+            stored[name] = (int(nb), h)
+    for name, x, q, m, rows, cols, mode, s, cs in mod.cases():
+        print(f"[case] formula input {name}", flush=True)
+        p = B.make_params(q, m, rows, cols, mode, s, cs, B.F16 if x.dtype == np.float16 else B.F32)
+        codec = B.Codec(p, x.size)
+        xd = torch.from_numpy(x.copy()).cuda() if x.size else torch.zeros(0, device="cuda")
+        got = codec.container(codec.compress(xd))
+        assert (len(got), hashlib.sha256(got).hexdigest()) == stored[name], name

@@ -10,14 +10,19 @@ from paper_2511_11664_amd import binding as B
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("mode,cols", [(0, 1), (1, 6)])
-def test_mutated_containers_are_rejected_or_decode_cleanly(mode, cols):
+@pytest.mark.parametrize("mode,cols,M,S,cs", [
+    (0, 1, 11, 16, 512),
+    (1, 6, 11, 16, 512),
+    (0, 1, 14, 1024, 4096),   # two chunks of 1024 streams at M = 14: groups of 512 lanes, per-slot table
+    (1, 6, 12, 600, 2400),    # groups of 256 lanes, the last one ragged
+])
+def test_mutated_containers_are_rejected_or_decode_cleanly(mode, cols, M, S, cs):
     rng = np.random.default_rng(9)
     n = 6000
     x = np.maximum(rng.standard_normal(n), 0).astype(np.float32)
-    op = oracle.make_params(8, 11, n // cols, cols, mode, 16, 512, 0)
+    op = oracle.make_params(8, M, n // cols, cols, mode, S, cs, 0)
     buf, sym_ref = oracle.compress(x, op)
-    p = B.make_params(8, 11, n // cols, cols, mode, 16, 512, B.F32)
+    p = B.make_params(8, M, n // cols, cols, mode, S, cs, B.F32)
     codec = B.Codec(p, n)
     out = torch.empty(n, dtype=torch.uint8, device="cuda")
     n_bad = n_ok = 0

@@ -30,7 +30,9 @@ __device__ __forceinline__ void load16(const uint8_t *p, uint64_t e0, uint64_t n
 // k_quant_hist has counted the nonzeros of every tile (blk_nnz) and of every group of tiles_per_grp
 // tiles (grp_nnz); the place of the work-group's first tile in v and c is the sum over the groups
 // and then the tiles before it, and every further tile follows the one before.
-template <bool LDS_HIST>
+// SHORT_ROWS (few columns): a row ends every few symbols; instead of a store behind a branch at every symbol, the
+// lane notes which of its symbols are nonzero and derives its row ends from that mask after the walk.
+template <bool LDS_HIST, bool SHORT_ROWS = false>
 __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_t n, int aligned, uint32_t K,
                                                      const uint32_t *blk_nnz, const uint32_t *grp_nnz,
                                                      uint32_t tiles_per_grp, uint8_t *v, uint16_t *c,
@@ -47,6 +49,9 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
   if (LDS_HIST) {
     for (uint32_t a = threadIdx.x; a < ((A + 15u) & ~15u); a += kWG) hist[a] = 0;
   }
+  // few columns (8 K <= A, which the host has checked for SHORT_ROWS): eight counters per column, one per lane
+  // residue and K slots apart - with K dividing 16 every lane of a wave meets the same column at the same step
+  const uint32_t rep_off = SHORT_ROWS ? (threadIdx.x & 7u) * K : 0u;
   const uint32_t t0 = blockIdx.x * tiles_per_wg;  // < n_tiles by the size of the grid
   const uint32_t t1 = t0 + tiles_per_wg < n_tiles ? t0 + tiles_per_wg : n_tiles;
   uint8_t b[16];
@@ -76,21 +81,30 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
     uint32_t loc = block_excl_scan<kWG>(cth, sh, &tot);  // also orders the hist zeroing and the staging reuse
     if (e0 < n) {
       uint32_t row = (uint32_t)(e0 / K), col = (uint32_t)(e0 - (uint64_t)row * K);
+      const uint32_t col0 = col, loc0 = loc;
+      uint32_t nzmask = 0;
 #pragma unroll
       for (int k = 0; k < 16; k++) {
         if (e0 + k < n) {
           if (b[k]) {
             s_vc[loc] = b[k] | (col << 8);
             loc++;
-            if (LDS_HIST) atomicAdd(&hist[slot_of(col)], 1u);
+            if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : slot_of(col)], 1u);
             else atomicAdd(&cnt[col], 1u);
+            if (SHORT_ROWS) nzmask |= 1u << k;
           }
-          if (++col == K) {
+          if (SHORT_ROWS) {
+            col = col + 1 == K ? 0u : col + 1;
+          } else if (++col == K) {
             row_end[row] = base + loc;
             col = 0;
             row++;
           }
         }
+      }
+      if (SHORT_ROWS) {  // symbol p ends a row when col0 + p + 1 is a multiple of K
+        for (uint32_t p = K - 1 - col0; p < 16 && e0 + p < n; p += K)
+          row_end[row++] = base + loc0 + (uint32_t)__popc(nzmask & ((2u << p) - 1u));
       }
     }
     __syncthreads();
@@ -110,8 +124,14 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
     // into one of the partial histograms: a thousand work-groups adding to the same few hundred addresses
     // would keep the kernel busy long after its last tile
     uint32_t *dst = cnt + (n_rep ? (size_t)(1 + blockIdx.x % n_rep) * A : 0);
-    for (uint32_t a = threadIdx.x; a < A; a += kWG) {
-      uint32_t t = hist[slot_of(a)];
+    for (uint32_t a = threadIdx.x; a < (SHORT_ROWS ? K : A); a += kWG) {
+      uint32_t t = 0;
+      if (SHORT_ROWS) {
+#pragma unroll
+        for (uint32_t k = 0; k < 8; k++) t += hist[a + k * K];
+      } else {
+        t = hist[slot_of(a)];
+      }
       if (t) atomicAdd(&dst[a], t);
     }
   }

@@ -120,6 +120,7 @@ inline uint32_t next_seq() {
 
 constexpr uint32_t kDecWideGroupMinChunks = 192;
 constexpr uint32_t kExpandOwnSumMaxTiles = 4096;
+constexpr uint32_t kShortRowCols = 32;  // rows up to this length: k_csr_compact derives its row ends from a mask
 
 inline uint32_t grid_for(uint64_t n, uint32_t per_block, uint32_t cap) {
   uint64_t g = (n + per_block - 1) / per_block;
@@ -212,7 +213,10 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       const uint32_t tpw = (L.n_blk + kCompactBlocks - 1) / kCompactBlocks;  // consecutive tiles per work-group
       const uint32_t g_compact = (L.n_blk + tpw - 1) / tpw;
       const uint32_t *grp = grp_counts_of(L, ws);
-      if (lds_hist)
+      if (lds_hist && p.cols <= kShortRowCols && 8ull * p.cols <= A)
+        PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true, true>), dim3(g_compact), dim3(kWG), ((A + 15u) & ~15u) * 4, st, d_sym, (uint32_t)n, al,
+                           (uint32_t)p.cols, blk, grp, tiles_per_grp, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, tpw, L.cnt_rep);
+      else if (lds_hist)
         PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true>), dim3(g_compact), dim3(kWG), ((A + 15u) & ~15u) * 4, st, d_sym, (uint32_t)n, al,
                            (uint32_t)p.cols, blk, grp, tiles_per_grp, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, tpw, L.cnt_rep);
       else

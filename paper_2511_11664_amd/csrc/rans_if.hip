@@ -539,9 +539,34 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
     // tiles), at least one row (a row has at most 65535 cells)
     uint64_t cells = n / 1024;
     cells = cells < 2048 ? 2048 : (cells > kDenseTileCells ? kDenseTileCells : cells);
-    uint32_t tile_rows = (uint32_t)(cells / K);
-    tile_rows = tile_rows < 1 ? 1 : (tile_rows > 4096 ? 4096 : tile_rows);
-    if (tile_rows >= 4) tile_rows &= ~3u;  // then every tile starts on a 4-cell boundary (vector stores)
+    auto rows_of = [&](uint64_t c) {
+      uint32_t tr = (uint32_t)(c / K);
+      tr = tr < 1 ? 1 : (tr > 4096 ? 4096 : tr);
+      if (tr >= 4) tr &= ~3u;  // then every tile starts on a 4-cell boundary (vector stores)
+      return tr;
+    };
+    auto lds_of = [&](uint32_t tr) {
+      return ((2 * ((size_t)tr + 1) + 15) & ~(size_t)15) + (((size_t)tr * K + 3) & ~(size_t)3);
+    };
+    uint32_t tile_rows = rows_of(cells);
+    if (cells == kDenseTileCells) {
+      // Large tensors: all tiles should be on the chip at once (256 CUs, each with 160 KB of LDS and room for eight
+      // work-groups of this size).  A tile count just above that runs a second, nearly empty round; somewhat smaller
+      // tiles, of which more fit a CU, avoid it.
+      uint64_t best_cost = ~0ull;
+      for (uint64_t c = kDenseTileCells; c >= kDenseTileCells / 2; c -= kDenseTileCells / 8) {
+        const uint32_t tr = rows_of(c);
+        const uint64_t nt = (N + tr - 1) / tr;
+        uint64_t per_cu = (160 * 1024) / (lds_of(tr) + 256);
+        per_cu = per_cu > 8 ? 8 : (per_cu < 1 ? 1 : per_cu);
+        const uint64_t rounds = (nt + 256 * per_cu - 1) / (256 * per_cu);
+        const uint64_t cost = rounds * tr * K;
+        if (cost < best_cost) {
+          best_cost = cost;
+          tile_rows = tr;
+        }
+      }
+    }
     const uint32_t n_tiles = (N + tile_rows - 1) / tile_rows;
     uint32_t *part = (uint32_t *)(ws + L.row_off);  // n_tiles + 1 entries (n_tiles <= N)
     PROF_LAUNCH(KID_ROW_SCAN, k_row_part, dim3(n_tiles), dim3(kWG), 0, st, D + 2 * nnz, N, K, tile_rows, part, ctl);
@@ -552,7 +577,7 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
       PROF_LAUNCH(KID_SCAN, k_scan_u32, dim3(1), dim3(kBig), 0, st, part, n_tiles);
       LAUNCH_CHECK();
     }
-    const size_t lds = ((2 * ((size_t)tile_rows + 1) + 15) & ~(size_t)15) + (((size_t)tile_rows * K + 3) & ~(size_t)3);
+    const size_t lds = lds_of(tile_rows);
     if (lds > 64 * 1024) {  // a single long row: allow dynamic LDS beyond the default 64 KB (once per instantiation)
       static const hipError_t a0 = hipFuncSetAttribute((const void *)k_csr_to_dense<uint8_t>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
       static const hipError_t a1 = hipFuncSetAttribute((const void *)k_csr_to_dense<float>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);

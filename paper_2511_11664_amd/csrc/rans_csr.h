@@ -139,7 +139,9 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
 
 // r[i] = row_end[i] - row_end[i-1] (the NON-cumulative row count), histogrammed.  Work-groups stride
 // over the rows and add their histogram to the global one once.
-template <bool LDS_HIST>
+// REP (short rows, 8 (K + 1) <= A): a row count is one of K + 1 values, which a wave's lanes would all add to
+// the same few LDS addresses; every value gets eight counters, one per lane residue, K + 1 slots apart.
+template <bool LDS_HIST, bool REP = false>
 __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint32_t N, uint16_t *r, uint32_t *cnt,
                                                   uint32_t A, CtlRef ctl, int fold_norm, NormArgs na) {
   extern __shared__ uint32_t hist[];
@@ -148,6 +150,8 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
     __syncthreads();
   }
   uint32_t seen = 0;
+  const uint32_t n_val = na.p.cols + 1;  // REP: distinct row counts
+  const uint32_t rep_off = REP ? (threadIdx.x & 7u) * n_val : 0u;
   // a lane takes four consecutive rows: one 16-byte load of their ends, one 8-byte store of their counts;
   // the loads of four such quads are in flight together
   const uint32_t n_quads = (N + 3) / 4;
@@ -178,7 +182,7 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
 #pragma unroll
     for (int k = 0; k < 4; k++) {
       if (i + k < N) {
-        if (LDS_HIST) atomicAdd(&hist[rr[k]], 1u);
+        if (LDS_HIST) atomicAdd(&hist[rr[k] + rep_off], 1u);
         else atomicAdd(&cnt[rr[k]], 1u);
       }
     }
@@ -202,8 +206,14 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
   if (LDS_HIST) {
     __syncthreads();
     uint32_t *dst = cnt + (na.n_rep ? (size_t)(1 + blockIdx.x % na.n_rep) * A : 0);
-    for (uint32_t a = threadIdx.x; a < A; a += kWG) {
-      uint32_t t = hist[a];
+    for (uint32_t a = threadIdx.x; a < (REP ? n_val : A); a += kWG) {
+      uint32_t t = 0;
+      if (REP) {
+#pragma unroll
+        for (uint32_t k = 0; k < 8; k++) t += hist[a + k * n_val];
+      } else {
+        t = hist[a];
+      }
       // before a hand-over the additions return their old value: a returned value is the only proof that an
       // addition has been performed before the work-group takes its ticket
       if (t) {

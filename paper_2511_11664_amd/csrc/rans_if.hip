@@ -230,7 +230,9 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       g = g > g_cap ? g_cap : g;
       const int fold = A <= kNormWaveA;  // one wave of the last work-group can build the table
       const NormArgs na = norm_args(p, L, ws, n, d_stream, cap);
-      if (lds_hist)
+      if (lds_hist && 8ull * (p.cols + 1) <= A)  // short rows: eight counters per row count
+        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<true, true>), dim3(g), dim3(kWG), A * 4, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl, fold, na);
+      else if (lds_hist)
         PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<true>), dim3(g), dim3(kWG), A * 4, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl, fold, na);
       else
         PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<false>), dim3(g), dim3(kWG), 0, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl, fold, na);

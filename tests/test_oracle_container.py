@@ -66,6 +66,37 @@ def test_alphabet(oracle):
     assert oracle.alphabet(oracle.MODE_CSR, 4, 3136) == 3137
 
 
+def test_histogram_is_the_count_of_every_symbol_of_D(oracle):
+    """Sec. 3.1 "Concatenation and rANS Encoding": one frequency vector over the whole of D.  Against numpy's
+    bincount on ragged lengths; the last (and the first) symbol of D is unique in some cases, so that a loop
+    which stops one symbol early, starts one late or counts one twice is caught."""
+    rng = np.random.default_rng(3)
+    for length in (0, 1, 2, 3, 7, 64, 65, 1000, 4097, 70001):
+        for A in (2, 5, 256, 257, 3137):
+            D = rng.integers(0, A - 1, length).astype(np.uint16)      # symbol A - 1 stays free
+            if length >= 2:
+                D[-1] = A - 1                                          # occurs once, at the very end
+            got = oracle.histogram(D, A)
+            want = np.bincount(D, minlength=A).astype(np.uint64)
+            assert got.dtype == np.uint64 and got.size == A
+            assert np.array_equal(got, want)
+            assert int(got.sum()) == length
+            if length >= 2:
+                assert got[A - 1] == 1
+                D2 = D.copy()
+                D2[0] = A - 1                                          # and once at the very start
+                assert oracle.histogram(D2, A)[A - 1] == 2
+    # the histograms of v, c and r, padded to a common length and added, are the histogram of D = v (+) c (+) r
+    x = (rng.integers(0, 256, 60 * 37) * (rng.random(60 * 37) < 0.4)).astype(np.uint8)
+    p = oracle.make_params(8, 12, 60, 37, oracle.MODE_CSR, 4, 0, 0)
+    D = oracle.symbols_D(x, p)
+    m = x.reshape(60, 37)
+    ri, ci = np.nonzero(m)
+    parts = (np.bincount(m[ri, ci], minlength=256), np.bincount(ci, minlength=256),
+             np.bincount(np.count_nonzero(m, axis=1), minlength=256))
+    assert np.array_equal(oracle.histogram(D, 256), (parts[0] + parts[1] + parts[2]).astype(np.uint64))
+
+
 def _fields(buf):
     """Re-read every header field straight from the bytes."""
     magic, ver, mode, dt, q, m, rsv = struct.unpack_from("<4sHBBBBH", buf, 0)
@@ -94,7 +125,8 @@ def test_container_layout_and_roundtrip(oracle, mode, S, cs, n):
     assert h == dict(magic=b"RIF1", ver=1, mode=mode, dt=0, q=6, m=10, rsv=0, T=n, N=n // cols, K=cols,
                      lenD=D.size, A=A, S=S, cs=cs, nc=nc, xmin=qi.x_min, xmax=qi.x_max, tail=bytes(60))
     sec = oracle.container_sections(buf)
-    f, _ = oracle.normalize(oracle.histogram(D, A), 10)
+    # the one frequency vector over all of D, counted here without the oracle's histogram routine
+    f, _ = oracle.normalize(np.bincount(D, minlength=A).astype(np.uint64), 10)
     assert np.array_equal(sec["f"], f)
     # directory and chunk sizes
     table_bytes = (2 * A + 7) // 8 * 8

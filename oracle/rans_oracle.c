@@ -694,37 +694,53 @@ static uint64_t isqrt_u64(uint64_t t) {
   return r;
 }
 
+/* Sec. 3.2: the search domain is every reshape [N, K] with K a divisor of T, K <= 2^Q (so that a column
+ * index is no wider than a value) and N = T / K > sqrt(T) (more rows than columns); Algorithm 1 writes the
+ * same set as N_min = max(floor(sqrt T) + 1, ceil(T / 2^Q)) <= N <= T.  It is listed here by ascending K,
+ * which is the order the algorithm visits it in (N descending). */
+static uint32_t reshape_domain(uint64_t T, uint32_t q_bits, uint64_t *dom_N, uint32_t cap) {
+  const uint64_t root = isqrt_u64(T);
+  uint32_t n = 0;
+  for (uint64_t K = 1; K <= (1ull << q_bits) && K <= T; K++) {
+    if (T % K != 0) continue;
+    if (T / K <= root) continue; /* N > sqrt(T) fails, and does so for every larger K too */
+    if (n < cap) dom_N[n] = T / K;
+    n++;
+  }
+  return n;
+}
+
 int orc_search_reshape(const uint8_t *xhat, uint64_t T, uint32_t q_bits, uint64_t *N_best, double *best_cost,
                        uint64_t *cand_N, double *cand_cost, uint32_t cand_cap, uint32_t *n_cand) {
   if (!xhat || !N_best || !best_cost || T == 0 || q_bits < 1 || q_bits > 8) return ORC_ERR_ARG;
-  const uint64_t two_q = 1ull << q_bits;
-  const uint64_t n_sqrt = isqrt_u64(T) + 1;
-  const uint64_t n_q = (T + two_q - 1) / two_q;
-  const uint64_t N_min = n_sqrt > n_q ? n_sqrt : n_q;
-  const uint64_t N_max = T;
-  double best = INFINITY, prev = INFINITY;
-  uint64_t N_tilde = N_max;
-  uint32_t evaluated = 0;
-  for (uint64_t N = N_max; N >= N_min && N >= 1; N--) {
-    if (T % N != 0) continue;
-    double cost;
-    int rc = orc_reshape_cost(xhat, T, N, q_bits, &cost, NULL);
+  enum { DOM_MAX = 256 }; /* K <= 2^Q <= 256 */
+  uint64_t dom_N[DOM_MAX];
+  double dom_cost[DOM_MAX];
+  const uint32_t n_dom = reshape_domain(T, q_bits, dom_N, DOM_MAX);
+  /* the size proxy of every reshape in the domain */
+  for (uint32_t i = 0; i < n_dom; i++) {
+    int rc = orc_reshape_cost(xhat, T, dom_N[i], q_bits, &dom_cost[i], NULL);
     if (rc) return rc;
-    if (evaluated < cand_cap) {
-      if (cand_N) cand_N[evaluated] = N;
-      if (cand_cost) cand_cost[evaluated] = cost;
-    }
-    evaluated++;
-    if (cost < best) {
-      best = cost;
-      N_tilde = N;
-    }
-    if (cost > prev) break;
-    prev = cost;
   }
-  *N_best = N_tilde;
-  *best_cost = best;
-  if (n_cand) *n_cand = evaluated;
+  /* the stop rule: the reshapes are looked at in order until one costs more than the one before it (that one
+   * is still looked at); the cheapest one seen wins, the earliest on equal cost */
+  uint32_t seen = n_dom;
+  for (uint32_t i = 1; i < n_dom; i++) {
+    if (dom_cost[i] > dom_cost[i - 1]) {
+      seen = i + 1;
+      break;
+    }
+  }
+  uint32_t arg = 0;
+  for (uint32_t i = 1; i < seen; i++)
+    if (dom_cost[i] < dom_cost[arg]) arg = i;
+  *N_best = seen ? dom_N[arg] : T;
+  *best_cost = seen ? dom_cost[arg] : INFINITY;
+  for (uint32_t i = 0; i < seen && i < cand_cap; i++) {
+    if (cand_N) cand_N[i] = dom_N[i];
+    if (cand_cost) cand_cost[i] = dom_cost[i];
+  }
+  if (n_cand) *n_cand = seen;
   return ORC_OK;
 }
 

@@ -17,6 +17,7 @@
  * Parity pins (see tests/test_oracle_*.py): quantisation invariants and
  * closed-form values, the hand-computed two-symbol example of Eq. 2 / Eq. 4,
  * exact round trip, a big-integer coder written directly from Eq. 2-4,
+ * the histogram of D against an independent count,
  * exhaustive brute force over tiny alphabets, CSR brute force, size against
  * the entropy bound of Eq. 1; the reshape cost against an independent numpy /
  * scipy construction, a closed form for K = 1 and a planted column structure,
@@ -139,10 +140,12 @@ int orc_decode_container(const uint8_t *buf, size_t bytes, uint16_t *D, uint64_t
  * binary64, symbols summed in ascending order.  N must divide T and T/N must be at most 65535. */
 int orc_reshape_cost(const uint8_t *xhat, uint64_t T, uint64_t N, uint32_t q_bits, double *cost_bits,
                      uint64_t *len_D);
-/* Algorithm 1: N from N_max = T down to N_min = max(floor(sqrt T) + 1, ceil(T / 2^Q)), divisors of T only;
- * the best cost so far and its N are kept; the walk stops after the first N whose cost is larger than the
- * previous one.  cand_N / cand_cost (nullable, cand_cap entries) receive every N evaluated and its cost,
- * *n_cand their number.  No N in the domain: *N_best = T, *best_cost = +inf, *n_cand = 0. */
+/* Algorithm 1.  Domain: the reshapes [N, K = T/N] with K | T, K <= 2^Q and N > sqrt(T) (the algorithm's
+ * N_min = max(floor(sqrt T) + 1, ceil(T / 2^Q)) <= N <= T), in the order of descending N.  Every reshape of the
+ * domain is costed with orc_reshape_cost; the reshapes are then looked at in that order up to and including the
+ * first one that costs more than its predecessor, and the cheapest one looked at wins (the earliest on equal
+ * cost).  cand_N / cand_cost (nullable, cand_cap entries) receive the reshapes looked at and their costs,
+ * *n_cand their number.  Empty domain: *N_best = T, *best_cost = +inf, *n_cand = 0. */
 int orc_search_reshape(const uint8_t *xhat, uint64_t T, uint32_t q_bits, uint64_t *N_best, double *best_cost,
                        uint64_t *cand_N, double *cand_cost, uint32_t cand_cap, uint32_t *n_cand);
 

@@ -33,6 +33,25 @@ def build(force: bool = False) -> str:
     return _SO
 
 
+_SO_MT = os.path.join(_DIR, "librans_oracle_mt.so")
+_SRC_MT = os.path.join(_DIR, "rans_oracle_mt.cpp")
+
+
+def build_mt(force: bool = False) -> str:
+    """Compile the all-cores timing driver (rans_oracle_mt.cpp: std::thread around the oracle's own routines)
+    together with the oracle into one shared library."""
+    srcs = (_SRC, _SRC_MT, os.path.join(_DIR, "rans_oracle.h"))
+    stale = (not os.path.exists(_SO_MT)) or os.path.getmtime(_SO_MT) < max(os.path.getmtime(f) for f in srcs)
+    if force or stale:
+        obj = os.path.join(_DIR, "rans_oracle_mt_c.o")
+        subprocess.run(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra", "-fPIC",
+                        "-c", "-o", obj, _SRC], check=True)
+        subprocess.run(["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra", "-shared",
+                        "-fPIC", "-pthread", "-I", _DIR, "-o", _SO_MT, _SRC_MT, obj, "-lm"], check=True)
+        os.remove(obj)
+    return _SO_MT
+
+
 class Params(C.Structure):
     _fields_ = [("q_bits", C.c_uint32), ("freq_bits", C.c_uint32), ("rows", C.c_uint64),
                 ("cols", C.c_uint64), ("mode", C.c_uint32), ("n_streams", C.c_uint32),
@@ -311,6 +330,43 @@ def decompress(buf, out_dtype=F32):
     _check(lib().orc_decompress(_ptr(a), C.c_size_t(a.size), _ptr(sym), C.c_uint64(sym.size), C.byref(qi),
                                 out_dtype, _ptr(out)))
     return sym[:h.n_elems], qi, out[:h.n_elems]
+
+
+_lib_mt = None
+
+
+def lib_mt():
+    global _lib_mt
+    if _lib_mt is None:
+        _lib_mt = C.CDLL(build_mt())
+        _lib_mt.orc_container_bound.restype = C.c_size_t
+        _lib_mt.orc_container_bound.argtypes = [C.c_uint64, C.POINTER(Params), C.c_uint64]
+    return _lib_mt
+
+
+def compress_mt(x: np.ndarray, p: Params, n_threads: int) -> bytes:
+    """The oracle's container, computed by n_threads threads (timing driver; same bytes as compress)."""
+    x = np.ascontiguousarray(x).reshape(-1)
+    assert _dtype_code(x) == p.in_dtype
+    worst_len = x.size if p.mode == MODE_DENSE else 2 * x.size + p.rows
+    cap = lib_mt().orc_container_bound(C.c_uint64(worst_len), C.byref(p), C.c_uint64(x.size))
+    out = np.empty(cap, np.uint8)
+    nb = C.c_size_t()
+    _check(lib_mt().orc_mt_compress(_ptr(x), C.c_uint64(x.size), C.byref(p), _ptr(out), C.c_size_t(cap), C.byref(nb),
+                                    C.c_uint(n_threads)))
+    return out[:nb.value].tobytes()
+
+
+def decompress_mt(buf, out_dtype, n_threads: int):
+    """container -> (uint8 symbols, dequantised array) by n_threads threads (same values as decompress)."""
+    a = np.frombuffer(bytes(buf), np.uint8) if not isinstance(buf, np.ndarray) else buf
+    hh = Header()
+    _check(lib().orc_parse_header(_ptr(a), C.c_size_t(a.size), C.byref(hh)))
+    sym = np.empty(max(hh.n_elems, 1), np.uint8)
+    out = np.empty(max(hh.n_elems, 1), np.float32 if out_dtype == F32 else np.float16)
+    _check(lib_mt().orc_mt_decompress(_ptr(a), C.c_size_t(a.size), _ptr(sym), C.c_uint64(sym.size), out_dtype, _ptr(out),
+                                      C.c_uint(n_threads)))
+    return sym[:hh.n_elems], out[:hh.n_elems]
 
 
 def reshape_cost(xhat: np.ndarray, n_rows: int, q_bits: int):

@@ -406,6 +406,82 @@ size_t orc_container_bound(uint64_t len, const orc_params *p, uint64_t n_elems) 
   return (size_t)b;
 }
 
+int orc_write_header_and_table(const orc_params *p, uint64_t n_elems, uint64_t len, float x_min, float x_max,
+                               const uint16_t *f, uint8_t *out, size_t out_cap, size_t *dir_off_out,
+                               size_t *payload_off_out) {
+  uint32_t A = orc_alphabet(p->mode, p->q_bits, p->cols), M = p->freq_bits, S = p->n_streams;
+  uint64_t nc64 = n_chunks_of(len, p->chunk_syms);
+  if (nc64 > 0xffffffffull) return ORC_ERR_ARG;
+  uint32_t nc = (uint32_t)nc64;
+  size_t table_off = HDR_BYTES;
+  size_t dir_off = table_off + (((size_t)A * 2 + 7) & ~(size_t)7);
+  size_t payload_off = dir_off + 8 * ((size_t)nc + 1);
+  if (payload_off > out_cap) return ORC_ERR_CAPACITY;
+  memset(out, 0, payload_off);
+  memcpy(out, "RIF1", 4);
+  put16(out + 4, 1);
+  out[6] = (uint8_t)p->mode;
+  out[7] = (uint8_t)p->in_dtype;
+  out[8] = (uint8_t)p->q_bits;
+  out[9] = (uint8_t)M;
+  put64(out + 12, n_elems);
+  put64(out + 20, p->rows);
+  put64(out + 28, p->cols);
+  put64(out + 36, len);
+  put32(out + 44, A);
+  put32(out + 48, S);
+  put32(out + 52, p->chunk_syms);
+  put32(out + 56, nc);
+  uint32_t bits;
+  memcpy(&bits, &x_min, 4);
+  put32(out + 60, bits);
+  memcpy(&bits, &x_max, 4);
+  put32(out + 64, bits);
+  for (uint32_t a = 0; a < A; a++) put16(out + table_off + 2 * (size_t)a, f[a]);
+  *dir_off_out = dir_off;
+  *payload_off_out = payload_off;
+  return ORC_OK;
+}
+
+/* One chunk: state[S] u32, nwords[S] u32, then the streams' words one stream after the other, zero-padded to
+ * a multiple of 4 bytes.  Stream j codes the chunk's local symbols j, j + S, j + 2S, ... */
+int orc_encode_chunk(const uint16_t *D, uint64_t base, uint64_t n_here, uint32_t S, const uint16_t *f,
+                     const uint32_t *F, uint32_t M, uint8_t *out, size_t out_cap, size_t *chunk_bytes) {
+  size_t wpos = 8 * (size_t)S;
+  if (wpos > out_cap) return ORC_ERR_CAPACITY;
+  uint16_t *tmp = NULL;
+  size_t tmp_cap = 0;
+  int rc = ORC_OK;
+  for (uint32_t j = 0; j < S; j++) {
+    uint64_t n_j = n_here > j ? (n_here - j + S - 1) / S : 0;
+    if (n_j > tmp_cap) {
+      free(tmp);
+      tmp_cap = (size_t)n_j;
+      tmp = (uint16_t *)malloc(tmp_cap * sizeof(uint16_t));
+    }
+    uint32_t s;
+    uint64_t e;
+    rc = orc_encode_stream(D, base + j, S, n_j, f, F, M, tmp, &e, &s);
+    if (rc) break;
+    if (wpos + 2 * e > out_cap) {
+      rc = ORC_ERR_CAPACITY;
+      break;
+    }
+    put32(out + 4 * (size_t)j, s);
+    put32(out + 4 * (size_t)S + 4 * (size_t)j, (uint32_t)e);
+    for (uint64_t i = 0; i < e; i++) put16(out + wpos + 2 * i, tmp[i]);
+    wpos += 2 * e;
+  }
+  free(tmp);
+  if (rc) return rc;
+  while (wpos % 4 != 0) {
+    if (wpos >= out_cap) return ORC_ERR_CAPACITY;
+    out[wpos++] = 0;
+  }
+  *chunk_bytes = wpos;
+  return ORC_OK;
+}
+
 /* Format definition.  Little-endian:
  *   0 "RIF1" | 4 version u16 = 1 | 6 mode u8 | 7 in_dtype u8 | 8 Q u8 | 9 M u8 |
  *   10 reserved u16 | 12 T u64 | 20 N u64 | 28 K u64 | 36 len_D u64 | 44 A u32 |
@@ -436,92 +512,27 @@ int orc_encode_container(const uint16_t *D, uint64_t len, const orc_params *p, u
   orc_histogram(D, len, A, cnt);
   rc = orc_normalize(cnt, A, M, f, F);
   free(cnt);
+  size_t dir_off = 0, payload_off = 0;
+  if (rc == ORC_OK) rc = orc_write_header_and_table(p, n_elems, len, x_min, x_max, f, out, out_cap, &dir_off, &payload_off);
   if (rc) {
     free(f);
     free(F);
     return rc;
   }
-
-  size_t table_off = HDR_BYTES;
-  size_t dir_off = table_off + (((size_t)A * 2 + 7) & ~(size_t)7);
-  size_t payload_off = dir_off + 8 * ((size_t)nc + 1);
-  if (payload_off > out_cap) {
-    free(f);
-    free(F);
-    return ORC_ERR_CAPACITY;
-  }
-  memset(out, 0, payload_off);
-  memcpy(out, "RIF1", 4);
-  put16(out + 4, 1);
-  out[6] = (uint8_t)p->mode;
-  out[7] = (uint8_t)p->in_dtype;
-  out[8] = (uint8_t)p->q_bits;
-  out[9] = (uint8_t)M;
-  put64(out + 12, n_elems);
-  put64(out + 20, p->rows);
-  put64(out + 28, p->cols);
-  put64(out + 36, len);
-  put32(out + 44, A);
-  put32(out + 48, S);
-  put32(out + 52, p->chunk_syms);
-  put32(out + 56, nc);
-  uint32_t bits;
-  memcpy(&bits, &x_min, 4);
-  put32(out + 60, bits);
-  memcpy(&bits, &x_max, 4);
-  put32(out + 64, bits);
-  for (uint32_t a = 0; a < A; a++) put16(out + table_off + 2 * (size_t)a, f[a]);
-
   uint64_t chunk_len = p->chunk_syms ? p->chunk_syms : len;
   size_t pos = payload_off; /* absolute write position */
-  uint16_t *tmp = NULL;
-  size_t tmp_cap = 0;
-  rc = ORC_OK;
   for (uint32_t k = 0; k < nc && rc == ORC_OK; k++) {
     put64(out + dir_off + 8 * (size_t)k, (uint64_t)(pos - payload_off));
     uint64_t base = (uint64_t)k * chunk_len;
     uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
-    size_t hdr = pos;
-    size_t wpos = pos + 8 * (size_t)S;
-    if (wpos > out_cap) {
-      rc = ORC_ERR_CAPACITY;
-      break;
-    }
-    for (uint32_t j = 0; j < S; j++) {
-      uint64_t n_j = n_here > j ? (n_here - j + S - 1) / S : 0;
-      if (n_j > tmp_cap) {
-        free(tmp);
-        tmp_cap = (size_t)n_j;
-        tmp = (uint16_t *)malloc(tmp_cap * sizeof(uint16_t));
-      }
-      uint32_t s;
-      uint64_t e;
-      rc = orc_encode_stream(D, base + j, S, n_j, f, F, M, tmp, &e, &s);
-      if (rc) break;
-      if (wpos + 2 * e > out_cap) {
-        rc = ORC_ERR_CAPACITY;
-        break;
-      }
-      put32(out + hdr + 4 * (size_t)j, s);
-      put32(out + hdr + 4 * (size_t)S + 4 * (size_t)j, (uint32_t)e);
-      for (uint64_t i = 0; i < e; i++) put16(out + wpos + 2 * i, tmp[i]);
-      wpos += 2 * e;
-    }
-    if (rc) break;
-    while ((wpos - payload_off) % 4 != 0) {
-      if (wpos >= out_cap) {
-        rc = ORC_ERR_CAPACITY;
-        break;
-      }
-      out[wpos++] = 0;
-    }
-    pos = wpos;
+    size_t ck_bytes = 0;
+    rc = orc_encode_chunk(D, base, n_here, S, f, F, M, out + pos, out_cap - pos, &ck_bytes);
+    if (rc == ORC_OK) pos += ck_bytes;
   }
   if (rc == ORC_OK) {
     put64(out + dir_off + 8 * (size_t)nc, (uint64_t)(pos - payload_off));
     *out_bytes = pos;
   }
-  free(tmp);
   free(f);
   free(F);
   return rc;
@@ -570,16 +581,10 @@ int orc_parse_header(const uint8_t *buf, size_t bytes, orc_header *h) {
   return ORC_OK;
 }
 
-/* Inverse of orc_encode_container: every field is re-read and checked. */
-int orc_decode_container(const uint8_t *buf, size_t bytes, uint16_t *D, uint64_t D_cap,
-                         orc_header *h) {
-  int rc = orc_parse_header(buf, bytes, h);
-  if (rc) return rc;
-  if (h->len_D > D_cap) return ORC_ERR_CAPACITY;
-  if (h->len_D && !D) return ORC_ERR_ARG;
-  uint32_t A = h->A, M = h->p.freq_bits, S = h->p.n_streams, nc = h->n_chunks;
-  uint16_t *f = (uint16_t *)calloc(A, sizeof(uint16_t));
-  uint32_t *F = (uint32_t *)calloc((size_t)A + 1, sizeof(uint32_t));
+/* Reads the stored table back and checks it (sum 2^M, or 0 for an empty D; zero padding) together with the two
+ * ends of the chunk directory.  f: A entries, F: A + 1. */
+int orc_read_table(const uint8_t *buf, size_t bytes, const orc_header *h, uint16_t *f, uint32_t *F) {
+  uint32_t A = h->A, M = h->p.freq_bits, nc = h->n_chunks;
   uint32_t acc = 0;
   for (uint32_t a = 0; a < A; a++) {
     f[a] = (uint16_t)get16(buf + h->table_off + 2 * (size_t)a);
@@ -587,54 +592,71 @@ int orc_decode_container(const uint8_t *buf, size_t bytes, uint16_t *D, uint64_t
     acc += f[a];
   }
   F[A] = acc;
-  rc = ORC_OK;
   for (size_t i = h->table_off + 2 * (size_t)A; i < h->dir_off; i++)
-    if (buf[i] != 0) rc = ORC_ERR_CORRUPT;
-  if (acc != (h->len_D ? (1u << M) : 0u)) rc = ORC_ERR_CORRUPT;
+    if (buf[i] != 0) return ORC_ERR_CORRUPT;
+  if (acc != (h->len_D ? (1u << M) : 0u)) return ORC_ERR_CORRUPT;
   size_t payload_bytes = bytes - h->payload_off;
-  if (rc == ORC_OK && get64(buf + h->dir_off) != 0) rc = ORC_ERR_CORRUPT;
-  if (rc == ORC_OK && get64(buf + h->dir_off + 8 * (size_t)nc) != payload_bytes)
-    rc = ORC_ERR_CORRUPT;
+  if (get64(buf + h->dir_off) != 0) return ORC_ERR_CORRUPT;
+  if (get64(buf + h->dir_off + 8 * (size_t)nc) != payload_bytes) return ORC_ERR_CORRUPT;
+  return ORC_OK;
+}
+
+/* Chunk k of a container whose header and table have been read: every size and offset is checked. */
+int orc_decode_chunk(const uint8_t *buf, size_t bytes, const orc_header *h, uint32_t k, const uint16_t *f,
+                     const uint32_t *F, uint16_t *D) {
+  uint32_t A = h->A, M = h->p.freq_bits, S = h->p.n_streams;
+  size_t payload_bytes = bytes - h->payload_off;
   uint64_t chunk_len = h->p.chunk_syms ? h->p.chunk_syms : h->len_D;
+  uint64_t o0 = get64(buf + h->dir_off + 8 * (size_t)k);
+  uint64_t o1 = get64(buf + h->dir_off + 8 * ((size_t)k + 1));
+  if (o0 > o1 || o1 > payload_bytes || o1 - o0 < 8ull * S) return ORC_ERR_CORRUPT;
+  const uint8_t *ck = buf + h->payload_off + o0;
+  uint64_t ck_bytes = o1 - o0;
+  uint64_t base = (uint64_t)k * chunk_len;
+  uint64_t n_here = h->len_D - base < chunk_len ? h->len_D - base : chunk_len;
+  uint64_t wpos = 8ull * S;
   uint16_t *wtmp = NULL;
   size_t wtmp_cap = 0;
-  for (uint32_t k = 0; k < nc && rc == ORC_OK; k++) {
-    uint64_t o0 = get64(buf + h->dir_off + 8 * (size_t)k);
-    uint64_t o1 = get64(buf + h->dir_off + 8 * ((size_t)k + 1));
-    if (o0 > o1 || o1 > payload_bytes || o1 - o0 < 8ull * S) {
+  int rc = ORC_OK;
+  for (uint32_t j = 0; j < S && rc == ORC_OK; j++) {
+    uint64_t n_j = n_here > j ? (n_here - j + S - 1) / S : 0;
+    uint32_t s = get32(ck + 4 * (size_t)j);
+    uint64_t nw = get32(ck + 4 * (size_t)S + 4 * (size_t)j);
+    if (nw > n_j || wpos + 2 * nw > ck_bytes) {
       rc = ORC_ERR_CORRUPT;
       break;
     }
-    const uint8_t *ck = buf + h->payload_off + o0;
-    uint64_t ck_bytes = o1 - o0;
-    uint64_t base = (uint64_t)k * chunk_len;
-    uint64_t n_here = h->len_D - base < chunk_len ? h->len_D - base : chunk_len;
-    uint64_t wpos = 8ull * S;
-    for (uint32_t j = 0; j < S && rc == ORC_OK; j++) {
-      uint64_t n_j = n_here > j ? (n_here - j + S - 1) / S : 0;
-      uint32_t s = get32(ck + 4 * (size_t)j);
-      uint64_t nw = get32(ck + 4 * (size_t)S + 4 * (size_t)j);
-      if (nw > n_j || wpos + 2 * nw > ck_bytes) {
-        rc = ORC_ERR_CORRUPT;
-        break;
-      }
-      if (nw > wtmp_cap) {
-        free(wtmp);
-        wtmp_cap = (size_t)nw;
-        wtmp = (uint16_t *)malloc(wtmp_cap * sizeof(uint16_t));
-      }
-      for (uint64_t i = 0; i < nw; i++) wtmp[i] = (uint16_t)get16(ck + wpos + 2 * i);
-      rc = orc_decode_stream(s, wtmp, nw, f, F, A, M, D, base + j, S, n_j);
-      if (rc) break;
-      wpos += 2 * nw;
+    if (nw > wtmp_cap) {
+      free(wtmp);
+      wtmp_cap = (size_t)nw;
+      wtmp = (uint16_t *)malloc(wtmp_cap * sizeof(uint16_t));
     }
+    for (uint64_t i = 0; i < nw; i++) wtmp[i] = (uint16_t)get16(ck + wpos + 2 * i);
+    rc = orc_decode_stream(s, wtmp, nw, f, F, A, M, D, base + j, S, n_j);
     if (rc) break;
-    uint64_t padded = (wpos + 3) & ~(uint64_t)3;
-    if (padded != ck_bytes) rc = ORC_ERR_CORRUPT;
-    for (uint64_t i = wpos; i < ck_bytes && rc == ORC_OK; i++)
-      if (ck[i] != 0) rc = ORC_ERR_CORRUPT;
+    wpos += 2 * nw;
   }
   free(wtmp);
+  if (rc) return rc;
+  uint64_t padded = (wpos + 3) & ~(uint64_t)3;
+  if (padded != ck_bytes) return ORC_ERR_CORRUPT;
+  for (uint64_t i = wpos; i < ck_bytes; i++)
+    if (ck[i] != 0) return ORC_ERR_CORRUPT;
+  return ORC_OK;
+}
+
+/* Inverse of orc_encode_container: every field is re-read and checked. */
+int orc_decode_container(const uint8_t *buf, size_t bytes, uint16_t *D, uint64_t D_cap,
+                         orc_header *h) {
+  int rc = orc_parse_header(buf, bytes, h);
+  if (rc) return rc;
+  if (h->len_D > D_cap) return ORC_ERR_CAPACITY;
+  if (h->len_D && !D) return ORC_ERR_ARG;
+  uint32_t A = h->A, nc = h->n_chunks;
+  uint16_t *f = (uint16_t *)calloc(A, sizeof(uint16_t));
+  uint32_t *F = (uint32_t *)calloc((size_t)A + 1, sizeof(uint32_t));
+  rc = orc_read_table(buf, bytes, h, f, F);
+  for (uint32_t k = 0; k < nc && rc == ORC_OK; k++) rc = orc_decode_chunk(buf, bytes, h, k, f, F, D);
   free(f);
   free(F);
   return rc;

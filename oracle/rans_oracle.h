@@ -117,6 +117,14 @@ int orc_decode_stream(uint32_t state, const uint16_t *words, uint64_t n_words, c
 int orc_encode_container(const uint16_t *D, uint64_t len, const orc_params *p, uint64_t n_elems,
                          float x_min, float x_max, uint8_t *out, size_t out_cap,
                          size_t *out_bytes);
+/* The pieces orc_encode_container is made of (also called, chunk by chunk from several threads, by the
+ * all-cores timing driver rans_oracle_mt.cpp): fixed header and frequency table; one chunk's states, word
+ * counts and words into a buffer of its own (out_cap bytes; *chunk_bytes includes the padding to 4 bytes). */
+int orc_write_header_and_table(const orc_params *p, uint64_t n_elems, uint64_t len, float x_min, float x_max,
+                               const uint16_t *f, uint8_t *out, size_t out_cap, size_t *dir_off,
+                               size_t *payload_off);
+int orc_encode_chunk(const uint16_t *D, uint64_t base, uint64_t n_here, uint32_t S, const uint16_t *f,
+                     const uint32_t *F, uint32_t M, uint8_t *out, size_t out_cap, size_t *chunk_bytes);
 /* Upper bound of the container size for len symbols. */
 size_t orc_container_bound(uint64_t len, const orc_params *p, uint64_t n_elems);
 
@@ -130,6 +138,10 @@ typedef struct {
 
 /* Parse and validate the fixed header only. */
 int orc_parse_header(const uint8_t *buf, size_t bytes, orc_header *h);
+/* The pieces orc_decode_container is made of: the stored table (validated), one chunk. */
+int orc_read_table(const uint8_t *buf, size_t bytes, const orc_header *h, uint16_t *f, uint32_t *F);
+int orc_decode_chunk(const uint8_t *buf, size_t bytes, const orc_header *h, uint32_t k, const uint16_t *f,
+                     const uint32_t *F, uint16_t *D);
 /* Decode a container to D (cap >= len_D), validating everything. */
 int orc_decode_container(const uint8_t *buf, size_t bytes, uint16_t *D, uint64_t D_cap,
                          orc_header *h);

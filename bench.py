@@ -108,6 +108,7 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     B.rans_profile_enable(None)
+    # the status is sticky: the first error of any of the 2 K calls would still be there
     assert rc == 0 and B.rans_last_status(codec.ws) == 0
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     prof = B.rans_profile_read()          # launch durations of the dominant kernel inside the timed region
@@ -125,7 +126,9 @@ def main():
 
     reps = max(args.steps, 20)
     enc_p50, enc_p10, enc_p90 = p50_us(lambda: B.rans_compress(x, n, p, codec.stream, codec.nbytes, codec.ws), reps)
+    assert B.rans_last_status(codec.ws) == 0 and int(codec.nbytes.item()) == nbytes
     dec_p50, dec_p10, dec_p90 = p50_us(lambda: B.rans_decompress(codec.stream, nbytes, hdr, w.in_dtype, out, codec.ws), reps)
+    assert B.rans_last_status(codec.ws) == 0
 
     # the four unfused entry points, for the record (symbols through a caller-side buffer)
     sym = torch.empty(n, dtype=torch.uint8, device=dev)

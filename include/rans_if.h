@@ -9,28 +9,39 @@
  *
  * Conventions
  *   - Pointers named d_* are DEVICE pointers owned by the caller; h_* are host
- *     pointers.  The library allocates and frees nothing and keeps no state
- *     between calls: scratch lives in the caller's workspace d_ws, whose size
+ *     pointers.  The entry points with a workspace argument allocate and free
+ *     nothing: scratch lives in the caller's workspace d_ws, whose size
  *     rans_workspace_bytes() returns.  d_ws must be 256-byte aligned, d_stream
- *     16-byte aligned, tensors aligned to their element size.
+ *     16-byte aligned, tensors aligned to their element size.  A workspace
+ *     needs no initialisation and may be reused by any sequence of calls, one
+ *     at a time.  Host-side state of the library: a process-wide call counter
+ *     (calls are numbered so that a kernel can tell its own call's status
+ *     from an older one's) and, only while rans_profile_enable() is on, the
+ *     event pairs of the timing aid.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     All work is enqueued on it; calls return without synchronising unless
  *     stated otherwise.
  *   - Return value: RANS_OK or a negative RANS_ERR_*.  Errors that depend only
  *     on the arguments are detected on the host before any launch.  Errors
  *     that depend on the data (non-finite input, too many distinct symbols,
- *     output capacity, corrupt container) are recorded in the workspace; the
- *     kernels then stop producing output, and rans_last_status() reports the
- *     first such error.  No call aborts or throws.
+ *     a caller-provided symbol outside {0..2^Q-1}, output capacity, corrupt
+ *     container) are recorded in the workspace; the kernels of that call then
+ *     stop producing output, and rans_last_status() reports the first error
+ *     recorded by ANY call on the workspace since the status was last read.
+ *     RANS_ERR_HIP as a recorded status means an internal check failed: a
+ *     histogram that does not add up to the number of symbols, or the
+ *     encoder's bounded wait for the work-groups before it ran out (possible
+ *     when the GPU is time-sliced between processes); the output of that call
+ *     is invalid and the call can simply be repeated.  No call aborts or throws.
  *   - Limits: n_elems <= 2^30; 1 <= Q <= 8; 1 <= M <= 15; 1 <= S <= 65536;
  *     CSR mode needs cols <= 65535.
  *   - Stream capture: every entry point that takes a `stream`, except
  *     rans_last_status and rans_decode / rans_decompress without a header
  *     hint (these read a few bytes back and synchronise), only enqueues
  *     kernels and may be captured into a HIP graph.  A replay writes the same
- *     bytes as the eager call.  The encoding entry points start every replay
- *     with a clean status; an error that a replayed decoding call records
- *     stays in the workspace until another call has run on it.
+ *     bytes as the eager call.  Every replay starts like a fresh call; an
+ *     error that a replay records stays in the workspace until
+ *     rans_last_status() has read it.
  */
 #ifndef RANS_IF_H
 #define RANS_IF_H
@@ -107,7 +118,8 @@ int rans_quantize(const void *d_x, uint64_t n_elems, const rans_params *p, uint8
  * d_sym: n_elems quantised symbols (< 2^Q).  d_qinfo: the extrema that go into
  * the header (device).  d_stream / stream_cap: output buffer; the number of
  * bytes written goes to *d_stream_bytes (device, 8-byte aligned; 0 on a data
- * error).  Data errors: RANS_ERR_ALPHABET, RANS_ERR_CAPACITY. */
+ * error).  Data errors: RANS_ERR_ALPHABET, RANS_ERR_CAPACITY, RANS_ERR_ARG (a
+ * symbol >= 2^Q), RANS_ERR_NONFINITE (extrema in d_qinfo), RANS_ERR_HIP (see above). */
 int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p,
                 const rans_qinfo *d_qinfo, uint8_t *d_stream, size_t stream_cap,
                 uint64_t *d_stream_bytes, void *d_ws, size_t ws_bytes, void *stream);
@@ -170,9 +182,11 @@ int rans_search_reshape(const uint8_t *d_sym, uint64_t n_elems, uint32_t q_bits,
  * RANS_ERR_CORRUPT if the fields are not a valid header. */
 int rans_peek_header(const void *h_bytes, size_t n_bytes, rans_header *out);
 
-/* First data-dependent error recorded in the workspace by the calls enqueued
- * so far (RANS_OK if none).  Synchronises `stream`. */
-int rans_last_status(const void *d_ws, void *stream);
+/* First data-dependent error that any call on this workspace has recorded since
+ * the previous rans_last_status() on it (RANS_OK if none): a failed call is not
+ * hidden by later successful ones.  Reading clears the record.  Synchronises
+ * `stream`, on which the calls to be covered must have been enqueued. */
+int rans_last_status(void *d_ws, void *stream);
 
 const char *rans_strerror(int code);
 

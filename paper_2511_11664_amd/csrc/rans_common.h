@@ -32,9 +32,16 @@ struct Ctl {
   uint64_t total_bytes;
   uint32_t nnz, n_chunks;
   uint32_t hist_done;                    // work-groups of the histogram kernel that have added their counts
-  uint32_t pad[45];
+  uint32_t pad0;
+  // First data-dependent error of ANY call on this workspace since the host last read it (rans_last_status):
+  // kStickyTag in the upper 48 bits, minus the error code in the lower 16 (0 = none).  A word without the tag
+  // is a workspace that has never recorded an error (fresh memory), so nothing has to initialise it.
+  unsigned long long sticky;
+  uint32_t pad[42];
 };
 static_assert(sizeof(Ctl) == 256, "control block is 256 bytes");
+static_assert(offsetof(Ctl, sticky) == 80, "rans_last_status reads the sticky word at this offset");
+constexpr unsigned long long kStickyTag = 0x52414e535354ull;  // "RANSST"
 
 // What kernels receive: the control block and the number of the call they belong to.
 struct CtlRef {
@@ -159,8 +166,20 @@ __device__ __forceinline__ int get_status(const CtlRef &ctl) {
   const unsigned long long v = *(volatile const unsigned long long *)&ctl.p->status;
   return (uint32_t)(v >> 32) == ctl.seq ? (int)(uint32_t)v : 0;
 }
-// Records `code` as the error of call ctl.seq unless that call already has one.
+// Records `code` as the error of call ctl.seq unless that call already has one, and as the workspace's
+// sticky error unless an earlier one is still waiting to be read.
 __device__ __forceinline__ void set_status(const CtlRef &ctl, int code) {
+  {
+    unsigned long long *sw = &ctl.p->sticky;
+    unsigned long long old = *(volatile unsigned long long *)sw;
+    const unsigned long long want = (kStickyTag << 16) | (unsigned long long)(uint16_t)(-code);
+    for (int tries = 0; tries < 64; tries++) {
+      if ((old >> 16) == kStickyTag && (old & 0xffffu) != 0) break;  // an earlier error stays
+      const unsigned long long prev = atomicCAS(sw, old, want);
+      if (prev == old) break;
+      old = prev;
+    }
+  }
   unsigned long long *w = (unsigned long long *)&ctl.p->status;
   unsigned long long old = *(volatile unsigned long long *)w;
   for (int tries = 0; tries < 64; tries++) {  // other writers only ever store an error of this call: one retry suffices
@@ -170,6 +189,23 @@ __device__ __forceinline__ void set_status(const CtlRef &ctl, int code) {
     if (prev == old) return;
     old = prev;
   }
+}
+
+// The same as ONE value for a whole work-group (every thread must call it).  Another work-group of the
+// running kernel may record an error at any moment; lanes that each read the word themselves could then
+// disagree, and the ones that carry on would meet barriers and LDS slots the others never reach.
+__device__ __forceinline__ bool group_has_status(const CtlRef &ctl) {
+  return __syncthreads_or(get_status(ctl) != 0) != 0;
+}
+
+// The same through an LDS word of the caller's (for kernels whose LDS layout must not gain a static variable,
+// which the reduction above may bring in).  The word is free again when the function returns.
+__device__ __forceinline__ bool group_has_status(const CtlRef &ctl, uint32_t *lds_word) {
+  if (threadIdx.x == 0) *lds_word = get_status(ctl) != 0;
+  __syncthreads();
+  const bool any = *lds_word != 0;
+  __syncthreads();
+  return any;
 }
 
 __device__ __forceinline__ uint32_t f2key(float v) {

@@ -49,8 +49,9 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
   if (LDS_HIST) {
     for (uint32_t a = threadIdx.x; a < ((A + 15u) & ~15u); a += kWG) hist[a] = 0;
   }
-  // few columns (8 K <= A, which the host has checked for SHORT_ROWS): eight counters per column, one per lane
-  // residue and K slots apart - with K dividing 16 every lane of a wave meets the same column at the same step
+  // few columns (the host selects SHORT_ROWS for K <= 32 with 8 K <= A, so the counters fit): eight counters per
+  // column, one per lane residue and K slots apart - when K divides 16 every lane of a wave meets the same column
+  // at the same step, and for other small K few distinct ones
   const uint32_t rep_off = SHORT_ROWS ? (threadIdx.x & 7u) * K : 0u;
   const uint32_t t0 = blockIdx.x * tiles_per_wg;  // < n_tiles by the size of the grid
   const uint32_t t1 = t0 + tiles_per_wg < n_tiles ? t0 + tiles_per_wg : n_tiles;

@@ -155,7 +155,7 @@ __global__ __launch_bounds__(kWG) void k_decode(const uint8_t *in, uint64_t byte
   extern __shared__ __align__(16) uint32_t l_mem[];
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
-  if (get_status(ctl) != 0) return;
+  if (group_has_status(ctl)) return;
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
   const uint32_t nc = ctl->n_chunks;
   if (k >= nc) return;
@@ -651,7 +651,7 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
 __global__ __launch_bounds__(kWG) void k_row_part(const uint16_t *r, uint32_t N, uint32_t K, uint32_t tile_rows,
                                                   uint32_t *part, CtlRef ctl) {
   __shared__ uint64_t sh64[kWG / 64];
-  if (get_status(ctl) != 0) return;
+  if (group_has_status(ctl)) return;
   const uint32_t i0 = blockIdx.x * tile_rows;
   const uint32_t i1 = i0 + tile_rows < N ? i0 + tile_rows : N;
   uint64_t loc = 0;
@@ -691,7 +691,7 @@ __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const u
   extern __shared__ __align__(16) uint32_t l_mem[];
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
-  if (get_status(ctl) != 0) return;
+  if (group_has_status(ctl)) return;
   const uint32_t nnz = ctl->nnz;
   const uint32_t i0 = blockIdx.x * tile_rows;
   const uint32_t rows = i0 + tile_rows < N ? tile_rows : N - i0;
@@ -815,10 +815,16 @@ __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const u
         for (int k = 0; k < 8; k++) {
           const uint32_t j = j0 + k;
           if (j < cnt_here) {
-            while (j >= row_end) {  // ends: row_end of the last row is cnt_here > j
+            // ends at the last row at the latest: its end is roff[rows] = cnt_here > j (the bound on `row`
+            // keeps the walk inside roff[] whatever the offsets hold)
+            while (j >= row_end && row + 1 < rows) {
               row++;
               row_beg = row_end;
               row_end = roff[row + 1];
+            }
+            if (j >= row_end) {
+              bad = true;
+              continue;
             }
             const uint32_t vv = (vw[u][k >> 1] >> (16 * (k & 1))) & 0xffffu, cc = (cw[u][k >> 1] >> (16 * (k & 1))) & 0xffffu;
             bool b = vv == 0 || vv >= (1u << q_bits) || cc >= K;
@@ -860,7 +866,7 @@ __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const u
 template <typename OutT, bool VEC>
 __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *sym, uint64_t n, const rans_qinfo *qi, CtlRef ctl,
                                                  OutT *out) {
-  if (ctl && get_status(ctl) != 0) return;
+  if (ctl && group_has_status(ctl)) return;
   const float s = qi->scale, zf = qi->zero_point, x_min = qi->x_min;
   auto conv = [&](uint32_t a) -> OutT {
     const float y = s == 0.0f ? x_min : s * ((float)a - zf);

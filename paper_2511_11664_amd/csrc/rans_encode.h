@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
   auto bail = [&]() {
     if (FUSE && threadIdx.x == 0) __hip_atomic_store(wg_pub + blockIdx.x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   };
-  if (get_status(ctl) != 0) {
+  if (group_has_status(ctl, l_mem)) {  // through the dynamic LDS: this kernel must not have static LDS (see below)
     if (FUSE && blockIdx.x == 0 && threadIdx.x == 0 && d_stream_bytes) *d_stream_bytes = 0;
     bail();
     return;
@@ -646,7 +646,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
 __global__ __launch_bounds__(kBig) void k_chunk_scan(CtlRef ctl, uint32_t *chunk_words, uint32_t S, uint8_t *out,
                                                      uint64_t cap, uint64_t *d_stream_bytes) {
   __shared__ uint64_t sh64[kBig / 64];
-  if (get_status(ctl) != 0) {
+  if (group_has_status(ctl)) {
     if (threadIdx.x == 0 && d_stream_bytes) *d_stream_bytes = 0;
     return;
   }
@@ -713,7 +713,7 @@ __global__ __launch_bounds__(kWG) void k_gather(CtlRef ctl, const uint16_t *scra
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
   __shared__ uint16_t tile[kGatherTile];
-  if (get_status(ctl) != 0) {
+  if (group_has_status(ctl)) {
     if (FUSED_SCAN && blockIdx.x == 0 && threadIdx.x == 0 && d_stream_bytes) *d_stream_bytes = 0;
     return;
   }

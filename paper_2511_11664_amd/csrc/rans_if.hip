@@ -21,6 +21,7 @@
 #include <hip/hip_ext.h>
 
 #include <cmath>
+#include <cstddef>
 #include <cstring>
 #include <atomic>
 #include <mutex>
@@ -844,13 +845,20 @@ int rans_search_reshape(const uint8_t *d_sym, uint64_t n_elems, uint32_t q_bits,
   return launch_search_reshape(d_sym, n_elems, q_bits, d_result, (uint8_t *)d_ws, P, (hipStream_t)stream);
 }
 
-int rans_last_status(const void *d_ws, void *stream) {
+int rans_last_status(void *d_ws, void *stream) {
   if (!d_ws) return RANS_ERR_ARG;
-  uint32_t w[3] = {0, 0, 0};  // status, status_seq, last_seq
   hipStream_t st = (hipStream_t)stream;
-  if (hipMemcpyAsync(w, d_ws, sizeof(w), hipMemcpyDeviceToHost, st) != hipSuccess) return RANS_ERR_HIP;
+  unsigned long long w = 0;  // the control block's sticky word
+  uint8_t *at = (uint8_t *)d_ws + offsetof(Ctl, sticky);
+  if (hipMemcpyAsync(&w, at, sizeof(w), hipMemcpyDeviceToHost, st) != hipSuccess) return RANS_ERR_HIP;
   if (hipStreamSynchronize(st) != hipSuccess) return RANS_ERR_HIP;
-  return w[1] == w[2] ? (int32_t)w[0] : RANS_OK;  // an error of an older call is not this call's
+  // without the tag the workspace has never recorded an error
+  if ((w >> 16) != kStickyTag || (w & 0xffffu) == 0) return RANS_OK;
+  // reading clears it (stream-ordered; the source is copied before the call returns)
+  static const unsigned long long cleared = kStickyTag << 16;
+  if (hipMemcpyAsync(at, &cleared, sizeof(cleared), hipMemcpyHostToDevice, st) != hipSuccess) return RANS_ERR_HIP;
+  if (hipStreamSynchronize(st) != hipSuccess) return RANS_ERR_HIP;
+  return -(int)(uint32_t)(w & 0xffffu);
 }
 
 int rans_profile_enable(uint64_t kernel_mask, uint32_t every) {

@@ -334,7 +334,7 @@ __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
   __shared__ uint32_t sh32[kBig / 64];
   __shared__ int64_t s_d;
   const uint32_t M = p.freq_bits, total = 1u << M;
-  if (get_status(ctl) != 0) return;  // uniform: written by an earlier kernel
+  if (group_has_status(ctl)) return;
   uint64_t len_loc = 0, present_loc = 0;
   for (uint32_t a = threadIdx.x; a < A; a += kBig) {
     uint32_t c = hist_count(na, a);
@@ -343,12 +343,12 @@ __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
   }
   const uint64_t len = block_sum64<kBig>(len_loc, sh64);
   const uint64_t present = block_sum64<kBig>(present_loc, sh64);
-  if (dense) {
-    if (threadIdx.x == 0) ctl->len_d = len;
-  }
-  const uint64_t len_d = dense ? len : ctl->len_d;
-  if (present > total || len != len_d) {  // the second cannot happen; kept as a guard
-    if (threadIdx.x == 0) set_status(ctl, RANS_ERR_ALPHABET);
+  // l_D as the rest of the call knows it: the tensor's size (DENSE), or what the row-count kernel derived from
+  // the row ends.  A histogram that does not add up to it is an incomplete hand-over, never a wrong table.
+  const uint64_t len_d = dense ? n_elems : ctl->len_d;
+  if (dense && threadIdx.x == 0) ctl->len_d = len_d;
+  if (present > total || len != len_d) {
+    if (threadIdx.x == 0) set_status(ctl, len != len_d ? RANS_ERR_HIP : RANS_ERR_ALPHABET);
     return;
   }
   // first estimate and its sum
@@ -438,7 +438,7 @@ __device__ void normalize_wave_per(const CtlRef &ctl, const NormArgs &na) {
   const uint32_t A = na.A;
   const rans_params &p = na.p;
   const uint32_t M = p.freq_bits, total = 1u << M;
-  if (get_status(ctl) != 0) return;  // uniform: written by an earlier kernel
+  if (__ballot(get_status(ctl) != 0) != 0) return;  // one decision for the wave
   auto total64 = [](uint64_t v) { return lane63_64(wave_incl_scan64(v, [](uint64_t a, uint64_t b) { return a + b; })); };
   auto max64 = [](uint64_t v) { return lane63_64(wave_incl_scan64(v, [](uint64_t a, uint64_t b) { return a > b ? a : b; })); };
   uint32_t c[PER];
@@ -452,11 +452,13 @@ __device__ void normalize_wave_per(const CtlRef &ctl, const NormArgs &na) {
   for (int q = 0; q < PER; q++) lp += (uint64_t)c[q] + ((uint64_t)(c[q] != 0) << 40);
   lp = total64(lp);
   const uint64_t len = lp & ((1ull << 40) - 1), present = lp >> 40;
-  if (na.dense && lane == 0) ctl->len_d = len;
-  // CSR mode: len_d was stored with a device-scope atomic by a work-group of the kernel this may run in
-  const uint64_t len_d = na.dense ? len : __hip_atomic_load(&ctl->len_d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (present > total || len != len_d) {  // the second cannot happen; kept as a guard
-    if (lane == 0) set_status(ctl, RANS_ERR_ALPHABET);
+  // l_D as the rest of the call knows it: the tensor's size (DENSE), or - CSR mode - what a work-group of the
+  // kernel this may run in stored with a device-scope atomic.  A histogram that does not add up to it is an
+  // incomplete hand-over between work-groups and becomes an error, never a wrong table.
+  const uint64_t len_d = na.dense ? na.n_elems : __hip_atomic_load(&ctl->len_d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (na.dense && lane == 0) ctl->len_d = len_d;
+  if (present > total || len != len_d) {
+    if (lane == 0) set_status(ctl, len != len_d ? RANS_ERR_HIP : RANS_ERR_ALPHABET);
     return;
   }
   // first estimate, its sum, the symbol with the largest count

@@ -287,6 +287,29 @@ def test_data_errors():
     sym = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
     rc = B.rans_encode(sym, n, p2, c2.qinfo, c2.stream, c2.nbytes, c2.ws)
     assert rc == 0 and B.rans_last_status(c2.ws) == B.ERR_ARG
+    # the status is sticky: a failed call is still reported after later good calls on the same workspace, once
+    xb = _relu_normal(n, 3)
+    xb[5] = float("nan")
+    good = codec.compress(x.cuda())
+    hdr = codec.header(good)
+    out = torch.empty(n, dtype=torch.float32, device="cuda")
+    keep = codec.stream.clone()
+    assert B.rans_compress(xb.cuda(), n, p, codec.stream, codec.nbytes, codec.ws) == 0      # fails on the device
+    assert B.rans_decompress(keep, good, hdr, B.F32, out, codec.ws) == 0                     # succeeds
+    assert B.rans_compress(x.cuda(), n, p, codec.stream, codec.nbytes, codec.ws) == 0        # succeeds
+    assert B.rans_last_status(codec.ws) == B.ERR_NONFINITE
+    assert B.rans_last_status(codec.ws) == 0                                                 # reading cleared it
+    assert codec.container(int(codec.nbytes.item())) == ref
+    # the first of two different errors is the one reported
+    assert B.rans_compress(x.cuda(), n, p, small, codec.nbytes, codec.ws) == 0               # capacity
+    assert B.rans_compress(xb.cuda(), n, p, codec.stream, codec.nbytes, codec.ws) == 0       # non-finite
+    assert B.rans_last_status(codec.ws) == B.ERR_CAPACITY and B.rans_last_status(codec.ws) == 0
+    # a workspace needs no initialisation: whatever bytes it holds, a good call reports no error
+    for fill in (0x00, 0xAB, 0xFF):
+        codec.ws.fill_(fill)
+        assert B.rans_compress(x.cuda(), n, p, codec.stream, codec.nbytes, codec.ws) == 0
+        assert B.rans_last_status(codec.ws) == 0
+        assert codec.container(int(codec.nbytes.item())) == ref
     # host-side argument errors
     assert B.rans_compress(x.cuda(), n, p, codec.stream, codec.nbytes, codec.ws[:1024]) == B.ERR_WORKSPACE
     assert B.rans_compress(x.cuda(), n, p, codec.stream[1:], codec.nbytes, codec.ws) == B.ERR_ARG
@@ -318,25 +341,46 @@ def test_synthetic_workloads(name, shrink, over):
     assert nbytes < x.numel() * x.element_size()
 
 
-def test_full_size_llama_config_in_bench_configuration():
-    """The configuration bench.py times (c5a: fp16 8x2048x4096, Q=8, M=14, S=1024), whole container compared."""
-    w = synth.workload("c5a", 1)
+FULL_SIZE = [
+    # the configurations bench.py reports, at their full size and in its launch configuration
+    ("c5a", {}),
+    ("c5b", {}),                                            # 327 680-symbol chunks, 256 of them
+    ("c2", dict(mode=0, chunk_syms=100352)),                # DENSE
+    ("c2", dict(mode=1, cols=256, chunk_syms=65536)),       # CSR, K = 256
+    ("c2", dict(mode=1, cols=7, chunk_syms=81920)),         # CSR with a reshape of the kind Algorithm 1 picks
+    ("c3", dict(mode=0)),                                   # DENSE, Q = 8: 98 chunks, the decoder splits a chunk
+    ("c3", dict(mode=0, q_bits=6)),
+    ("c3", dict(mode=1, cols=64, q_bits=6, chunk_syms=81920)),
+    ("c4", dict(chunk_syms=18432)),
+    ("c4", {}),
+]
+
+
+@pytest.mark.parametrize("name,over", FULL_SIZE, ids=lambda v: v if isinstance(v, str) else "-".join(f"{k}{x}" for k, x in v.items()) or "default")
+def test_full_size_configs_whole_container(name, over):
+    """Whole container and whole decompressed tensor against the oracle at the full size of every configuration
+    bench.py reports (c5a is the one its headline line is timed on)."""
+    w = synth.workload(name, 1, **over)
     x = synth.make(w)
     p = B.params_of(w)
-    print("[case] c5a full size", flush=True)
+    print(f"[case] {name} full size {over} n={w.numel}", flush=True)
     ref, sym_ref = oracle.compress(x.numpy(), _oparams(p))
     codec = B.Codec(p, w.numel)
-    nbytes = codec.compress(x.cuda())
+    xd = x.cuda()
+    nbytes = codec.compress(xd)
     assert nbytes == len(ref)
     got = codec.stream[:nbytes].cpu().numpy()
     assert np.array_equal(got, np.frombuffer(ref, np.uint8))
+    del got
     hdr = codec.header(nbytes)
-    out = torch.empty(w.numel, dtype=torch.float16, device="cuda")
+    out = torch.empty(w.numel, dtype=x.dtype, device="cuda")
     codec.decompress(nbytes, hdr, out)
-    _, qi = oracle.quantize(x.numpy()[:1], 8)  # placeholder for the struct type
-    qi = oracle.qinfo_from_minmax(hdr.x_min, hdr.x_max, 8)
-    y_ref = oracle.dequantize(sym_ref, qi, oracle.F16)
-    assert np.array_equal(out.cpu().numpy().view(np.uint16), y_ref.view(np.uint16))
+    qi = oracle.qinfo_from_minmax(hdr.x_min, hdr.x_max, w.q_bits)
+    y_ref = oracle.dequantize(sym_ref, qi, w.in_dtype)
+    assert np.array_equal(out.cpu().numpy().view(np.uint8), y_ref.view(np.uint8))
+    sym = torch.empty(w.numel, dtype=torch.uint8, device="cuda")
+    codec.decode(nbytes, hdr, sym)
+    assert np.array_equal(sym.cpu().numpy(), sym_ref)
 
 
 def test_full_size_csr_config_repeated():

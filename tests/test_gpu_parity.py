@@ -321,15 +321,16 @@ def test_data_errors():
 
 
 @pytest.mark.parametrize("name,shrink,over", [
+    ("c1", 1, dict(mode=0)),
     ("c1", 1, {}),
-    ("c1", 1, dict(mode=1)),
-    ("c1", 1, dict(mode=1, cols=7, chunk_syms=32 * 128)),
-    ("c1", 1, dict(chunk_syms=32 * 64)),
+    ("c1", 1, dict(cols=7, chunk_syms=32 * 128)),
+    ("c1", 1, dict(mode=0, chunk_syms=32 * 64)),
+    ("c2", 32, dict(mode=0, chunk_syms=1 << 18)),
+    ("c2", 32, dict(chunk_syms=1 << 18)),
     ("c2", 32, {}),
-    ("c2", 32, dict(mode=1)),
-    ("c3", 64, dict(mode=1)),
-    ("c3", 64, dict(q_bits=6, mode=1, cols=64)),
-    ("c3", 64, dict(q_bits=6)),
+    ("c3", 64, dict(chunk_syms=1 << 18)),
+    ("c3", 64, dict(q_bits=6, cols=64, chunk_syms=1 << 18)),
+    ("c3", 64, dict(q_bits=6, mode=0, chunk_syms=1 << 18)),
     ("c4", 8, {}),
     ("c5a", 32, {}),
     ("c5b", 32, dict(chunk_syms=1 << 20)),
@@ -341,29 +342,18 @@ def test_synthetic_workloads(name, shrink, over):
     assert nbytes < x.numel() * x.element_size()
 
 
-FULL_SIZE = [
-    # the configurations bench.py reports, at their full size and in its launch configuration
-    ("c5a", {}),
-    ("c5b", {}),                                            # 327 680-symbol chunks, 256 of them
-    ("c2", dict(mode=0, chunk_syms=100352)),                # DENSE
-    ("c2", dict(mode=1, cols=256, chunk_syms=65536)),       # CSR, K = 256
-    ("c2", dict(mode=1, cols=7, chunk_syms=81920)),         # CSR with a reshape of the kind Algorithm 1 picks
-    ("c3", dict(mode=0)),                                   # DENSE, Q = 8: 98 chunks, the decoder splits a chunk
-    ("c3", dict(mode=0, q_bits=6)),
-    ("c3", dict(mode=1, cols=64, q_bits=6, chunk_syms=81920)),
-    ("c4", dict(chunk_syms=18432)),
-    ("c4", {}),
-]
+# the configurations bench.py reports, at their full size and in its launch configuration
+FULL_SIZE = [(label, name, over) for label, name, over in synth.BENCH_CONFIGS]
 
 
-@pytest.mark.parametrize("name,over", FULL_SIZE, ids=lambda v: v if isinstance(v, str) else "-".join(f"{k}{x}" for k, x in v.items()) or "default")
-def test_full_size_configs_whole_container(name, over):
+@pytest.mark.parametrize("label,name,over", FULL_SIZE, ids=[c[0] for c in FULL_SIZE])
+def test_full_size_configs_whole_container(label, name, over):
     """Whole container and whole decompressed tensor against the oracle at the full size of every configuration
     bench.py reports (c5a is the one its headline line is timed on)."""
     w = synth.workload(name, 1, **over)
     x = synth.make(w)
     p = B.params_of(w)
-    print(f"[case] {name} full size {over} n={w.numel}", flush=True)
+    print(f"[case] {label}: {name} full size {over} n={w.numel}", flush=True)
     ref, sym_ref = oracle.compress(x.numpy(), _oparams(p))
     codec = B.Codec(p, w.numel)
     xd = x.cuda()
@@ -389,7 +379,7 @@ def test_full_size_csr_config_repeated():
     path is built by whichever work-group adds its part of the histogram last, hundreds of work-groups and a wide
     spread of row counts; a hand-over that starts before every addition has been performed shows up here as an
     error status on some of the calls."""
-    w = synth.workload("c3", 1, mode=1, cols=256, chunk_syms=65536)
+    w = synth.workload("c3", 1, mode=1, cols=256, chunk_syms=65536)  # more chunks than the benchmark's row
     x = synth.make(w)
     p = B.params_of(w)
     print("[case] c3 CSR full size, repeated", flush=True)

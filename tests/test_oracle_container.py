@@ -243,8 +243,8 @@ def test_corruption_is_detected_not_crashing(oracle):
 
 
 @pytest.mark.parametrize("name,shrink,over", [
-    ("c1", 1, {}), ("c1", 1, dict(mode=1)), ("c1", 1, dict(mode=1, cols=7, chunk_syms=32 * 128)),
-    ("c2", 64, {}), ("c2", 64, dict(mode=1)), ("c3", 128, dict(q_bits=6, mode=1, cols=64)),
+    ("c1", 1, dict(mode=0)), ("c1", 1, {}), ("c1", 1, dict(cols=7, chunk_syms=32 * 128)),
+    ("c2", 64, dict(mode=0)), ("c2", 64, {}), ("c3", 128, dict(q_bits=6, cols=64)),
     ("c4", 16, {}), ("c5a", 64, {}), ("c5b", 64, dict(chunk_syms=1 << 20)),
 ])
 def test_whole_path_on_synthetic_workloads(oracle, name, shrink, over):

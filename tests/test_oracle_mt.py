@@ -7,8 +7,8 @@ from paper_2511_11664_amd import synth
 
 
 @pytest.mark.parametrize("name,shrink,over", [
-    ("c1", 1, {}), ("c1", 1, dict(mode=1, cols=7, chunk_syms=32 * 128)), ("c1", 1, dict(mode=1)),
-    ("c2", 64, dict(mode=1)), ("c3", 128, dict(q_bits=6, mode=1, cols=64)), ("c4", 16, {}), ("c5a", 64, {}),
+    ("c1", 1, dict(mode=0)), ("c1", 1, dict(cols=7, chunk_syms=32 * 128)), ("c1", 1, {}),
+    ("c2", 64, {}), ("c3", 128, dict(q_bits=6, cols=64)), ("c4", 16, {}), ("c5a", 64, {}),
 ])
 @pytest.mark.parametrize("threads", [1, 3, 8])
 def test_threaded_driver_equals_the_oracle(oracle, name, shrink, over, threads):

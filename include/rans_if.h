@@ -149,6 +149,21 @@ int rans_compress(const void *d_x, uint64_t n_elems, const rans_params *p, uint8
                   size_t stream_cap, uint64_t *d_stream_bytes, void *d_ws, size_t ws_bytes,
                   void *stream);
 
+/* rans_compress for callers that cannot allocate device memory and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch memory is an array of
+ * RANS_NOALLOC_WS_BYTES bytes inside the library's own device image (every GPU the library runs on holds
+ * its copy until the process ends); the call allocates and frees nothing.  Same container bytes as rans_compress.
+ * Parameters whose workspace (rans_workspace_bytes) exceeds RANS_NOALLOC_WS_BYTES: RANS_ERR_WORKSPACE, nothing
+ * is launched.  *d_ws_used (host pointer, nullable) receives the device address of the array, for
+ * rans_last_status(); a data error also shows as *d_stream_bytes == 0.  All calls on one GPU share the one
+ * array: calls that overlap in time on the same GPU (two streams, two threads) race and must be serialised
+ * by the caller.  Everything a call needs to start from zero it clears itself; a recorded error stays until
+ * rans_last_status() reads it.  The first call on a device looks the array's address up (a host-side step,
+ * not a kernel: make that call outside stream capture). */
+#define RANS_NOALLOC_WS_BYTES (32u << 20)
+int rans_compress_noalloc(const void *d_x, uint64_t n_elems, const rans_params *p, uint8_t *d_stream,
+                          size_t stream_cap, uint64_t *d_stream_bytes, void **d_ws_used, void *stream);
+
 /* container -> tensor of out_dtype (elem_cap elements available at d_x_out).
  * Same values as rans_decode followed by rans_dequantize. */
 int rans_decompress(const uint8_t *d_stream, size_t stream_bytes, const rans_header *h_hdr,

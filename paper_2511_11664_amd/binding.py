@@ -71,8 +71,10 @@ class Header(C.Structure):
                 ("x_min", C.c_float), ("x_max", C.c_float)]
 
 
+NOALLOC_WS_BYTES = 32 << 20
+
 EXPORTS = ("rans_workspace_bytes", "rans_quantize", "rans_encode", "rans_decode", "rans_dequantize",
-           "rans_compress", "rans_decompress", "rans_peek_header", "rans_last_status",
+           "rans_compress", "rans_compress_noalloc", "rans_decompress", "rans_peek_header", "rans_last_status",
            "rans_search_workspace_bytes", "rans_search_reshape",
            "rans_profile_enable", "rans_profile_reset", "rans_profile_read",
            "rans_strerror", "rans_profile_kernel_name")
@@ -95,6 +97,7 @@ def lib() -> C.CDLL:
         L.rans_decode.argtypes = [vp, sz, HP, vp, u64, vp, vp, sz, vp]
         L.rans_dequantize.argtypes = [vp, u64, vp, u32, vp, vp]
         L.rans_compress.argtypes = [vp, u64, PP, vp, sz, vp, vp, sz, vp]
+        L.rans_compress_noalloc.argtypes = [vp, u64, PP, vp, sz, vp, C.POINTER(vp), vp]
         L.rans_decompress.argtypes = [vp, sz, HP, u32, vp, u64, vp, sz, vp]
         L.rans_peek_header.argtypes = [vp, sz, HP]
         L.rans_last_status.argtypes = [vp, vp]
@@ -124,6 +127,9 @@ def _stream():
 
 
 def _p(t):
+    """Device pointer of a tensor (None -> NULL); a plain integer is taken as an address."""
+    if isinstance(t, int):
+        return C.c_void_p(t)
     return C.c_void_p(t.data_ptr() if t is not None else 0)
 
 
@@ -167,6 +173,14 @@ def rans_dequantize(d_sym, n_elems, d_qinfo, out_dtype, d_x_out) -> int:
 def rans_compress(d_x, n_elems, p, d_stream, d_stream_bytes, d_ws) -> int:
     return lib().rans_compress(_p(d_x), n_elems, C.byref(p), _p(d_stream), d_stream.numel(), _p(d_stream_bytes),
                                _p(d_ws), d_ws.numel() * d_ws.element_size(), _stream())
+
+
+def rans_compress_noalloc(d_x, n_elems, p, d_stream, d_stream_bytes):
+    """-> (rc, device address of the library's own workspace, for rans_last_status)."""
+    ws = C.c_void_p()
+    rc = lib().rans_compress_noalloc(_p(d_x), n_elems, C.byref(p), _p(d_stream), d_stream.numel(), _p(d_stream_bytes),
+                                     C.byref(ws), _stream())
+    return rc, ws.value
 
 
 def rans_decompress(d_stream, stream_bytes, hdr, out_dtype, d_x_out, d_ws) -> int:

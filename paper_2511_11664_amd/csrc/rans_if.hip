@@ -37,6 +37,11 @@
 #include "rans_decode.h"
 #include "rans_reshape.h"
 
+// Workspace of rans_compress_noalloc (declared in rans_if.h): device memory that belongs to the library, so
+// that callers which cannot allocate need not bring a workspace.  The rest of this file never uses the name
+// except to look its device address up (static_ws_of_current_device).
+static __device__ __align__(256) uint8_t static_ws[RANS_NOALLOC_WS_BYTES];
+
 namespace {
 
 // ------------------------------------------------------------------ instrumentation
@@ -602,6 +607,55 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
 }
 
 
+// Shared body of rans_compress and rans_compress_noalloc.
+int compress_impl(const void *d_x, uint64_t n_elems, const rans_params *p, uint8_t *d_stream, size_t stream_cap,
+                  uint64_t *d_stream_bytes, void *d_ws, size_t ws_bytes, void *stream) {
+  Layout L;
+  int rc = check_common(p, n_elems, d_ws, ws_bytes, &L);
+  if (rc) return rc;
+  if (!d_stream || !d_stream_bytes || (n_elems && !d_x)) return RANS_ERR_ARG;
+  if (!aligned_to(d_x, p->in_dtype == RANS_F16 ? 2 : 4)) return RANS_ERR_ARG;
+  if (!aligned_to(d_stream, 16) || !aligned_to(d_stream_bytes, 8)) return RANS_ERR_ARG;
+  if (stream_cap < kHdrBytes) return RANS_ERR_CAPACITY;
+  hipStream_t st = (hipStream_t)stream;
+  uint8_t *ws = (uint8_t *)d_ws;
+  const uint32_t seq = next_seq();
+  const bool fold = n_elems && p->mode != RANS_MODE_CSR;  // dense: the histogram kernel also builds the table
+  const NormArgs na = norm_args(*p, L, ws, n_elems, d_stream, stream_cap);
+  uint32_t tpg = 1;
+  rc = launch_quantize(d_x, n_elems, *p, L, ws, ws + L.sym, nullptr, st, seq, fold ? &na : nullptr, &tpg);
+  if (rc) return rc;
+  return launch_encode_tail(ws + L.sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq, fold, tpg);
+}
+
+// ---- the workspace of rans_compress_noalloc: a device array of the library itself
+//
+// Every GPU the library runs on holds its own copy of the array, at its own address, until the process
+// ends.  In host code the array's name is only a handle for the look-up below; what kernels, copies and the
+// status read take is the device address that look-up returns, kept per device.
+constexpr size_t kStaticWsBytes = RANS_NOALLOC_WS_BYTES;
+constexpr int kStaticWsMaxDevices = 64;
+struct StaticWs {
+  std::mutex mu;
+  void *ptr[kStaticWsMaxDevices] = {nullptr};
+};
+StaticWs g_static_ws;
+
+int static_ws_of_current_device(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return RANS_ERR_HIP;
+  if (dev < 0 || dev >= kStaticWsMaxDevices) return RANS_ERR_ARG;
+  std::lock_guard<std::mutex> lk(g_static_ws.mu);
+  if (!g_static_ws.ptr[dev]) {  // once per device, with that device current
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(static_ws)) != hipSuccess || !p) return RANS_ERR_HIP;
+    if (!aligned_to(p, 256)) return RANS_ERR_HIP;
+    g_static_ws.ptr[dev] = p;
+  }
+  *out = g_static_ws.ptr[dev];
+  return RANS_OK;
+}
+
 // ---- reshape search: host side
 
 struct RsPlan {
@@ -768,22 +822,19 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
 
 int rans_compress(const void *d_x, uint64_t n_elems, const rans_params *p, uint8_t *d_stream, size_t stream_cap,
                   uint64_t *d_stream_bytes, void *d_ws, size_t ws_bytes, void *stream) {
-  Layout L;
-  int rc = check_common(p, n_elems, d_ws, ws_bytes, &L);
+  return compress_impl(d_x, n_elems, p, d_stream, stream_cap, d_stream_bytes, d_ws, ws_bytes, stream);
+}
+
+int rans_compress_noalloc(const void *d_x, uint64_t n_elems, const rans_params *p, uint8_t *d_stream,
+                          size_t stream_cap, uint64_t *d_stream_bytes, void **d_ws_used, void *stream) {
+  int rc = check_params(p, n_elems);
   if (rc) return rc;
-  if (!d_stream || !d_stream_bytes || (n_elems && !d_x)) return RANS_ERR_ARG;
-  if (!aligned_to(d_x, p->in_dtype == RANS_F16 ? 2 : 4)) return RANS_ERR_ARG;
-  if (!aligned_to(d_stream, 16) || !aligned_to(d_stream_bytes, 8)) return RANS_ERR_ARG;
-  if (stream_cap < kHdrBytes) return RANS_ERR_CAPACITY;
-  hipStream_t st = (hipStream_t)stream;
-  uint8_t *ws = (uint8_t *)d_ws;
-  const uint32_t seq = next_seq();
-  const bool fold = n_elems && p->mode != RANS_MODE_CSR;  // dense: the histogram kernel also builds the table
-  const NormArgs na = norm_args(*p, L, ws, n_elems, d_stream, stream_cap);
-  uint32_t tpg = 1;
-  rc = launch_quantize(d_x, n_elems, *p, L, ws, ws + L.sym, nullptr, st, seq, fold ? &na : nullptr, &tpg);
+  if (make_layout(*p, n_elems).total > kStaticWsBytes) return RANS_ERR_WORKSPACE;  // beyond the stated maximum
+  void *ws = nullptr;
+  rc = static_ws_of_current_device(&ws);
   if (rc) return rc;
-  return launch_encode_tail(ws + L.sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq, fold, tpg);
+  if (d_ws_used) *d_ws_used = ws;
+  return compress_impl(d_x, n_elems, p, d_stream, stream_cap, d_stream_bytes, ws, kStaticWsBytes, stream);
 }
 
 int rans_decode(const uint8_t *d_stream, size_t stream_bytes, const rans_header *h_hdr, uint8_t *d_sym,

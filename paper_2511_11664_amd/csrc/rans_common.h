@@ -62,6 +62,11 @@ struct Layout {
   uint32_t A, nc_max, capw, n_blk;
   uint32_t cnt_rep;  // partial histograms behind the histogram of D (CSR mode with an LDS-sized alphabet), else 0
   uint32_t n_pub;  // work-groups of the encoder when it also places its words (0: separate gather kernel)
+  // the counters behind `chunk_words` (32-bit words; everything before tc_off is zeroed when a call starts, and so
+  // are the n_blk tile counts there): [0, nc_max] words per chunk, then n_pub published work-group totals, then -
+  // at the even index acc_off - one 64-bit counter per chunk (fused placement only), then at tc_off the nonzeros
+  // per CSR tile and per group of tiles
+  uint32_t acc_off, tc_off;
   uint64_t len_max, chunk_len_max;
 };
 
@@ -136,7 +141,9 @@ Layout make_layout(const rans_params &p, uint64_t n) {
   }
   if (p.mode != RANS_MODE_CSR) L.n_blk = 0;
   // per-chunk word counts, the encoder's published totals, the nonzeros per CSR tile: all zeroed when a call starts
-  L.chunk_words = take(((size_t)L.nc_max + 1 + L.n_pub + 2 * (size_t)L.n_blk) * 4);  // tile counts, then group counts
+  L.acc_off = (L.nc_max + 1 + L.n_pub + 1) & ~1u;
+  L.tc_off = L.acc_off + (L.n_pub ? 2 * L.nc_max : 0);
+  L.chunk_words = take(((size_t)L.tc_off + 2 * (size_t)L.n_blk) * 4);
   // word blocks of the encoder, per work-group (kWG streams, absent ones included): see k_encode
   L.scratch = take((size_t)L.nc_max * ((p.n_streams + kWG - 1) / kWG) * kWG * L.capw * 2);
   size_t enc_end = o;

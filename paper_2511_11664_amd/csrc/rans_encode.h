@@ -56,11 +56,16 @@ struct SrcCsr {
   __device__ __forceinline__ static uint32_t get(uint32_t raw, int q) { return (raw >> (16 * q)) & 0xffffu; }
 };
 
-constexpr int kStageRows = 32;         // rows per tile of the encoder's symbol staging (dense source)
+constexpr int kStageRows = 16;         // rows per register tile of the encoder's symbol staging (dense source); LDS holds as many per wave
 constexpr int kStageRows2 = 16;        // the same for the CSR source (16-bit entries)
-constexpr uint32_t kRingStride = 40;  // bytes between the word rings of adjacent streams: 16 slots + padding against bank conflicts
 constexpr uint32_t kEncTab16MaxA = 1024;  // CSR alphabets up to this size use the 16-byte table entries
-constexpr int kEncAhead = 8;  // rows of symbols fetched ahead of the coder; also the flush period of the word ring
+constexpr int kEncAhead = 8;  // rows of symbols fetched ahead of the coder; also the period of the word area's overflow check
+constexpr uint32_t kEncGuard = 16;     // unused LDS bytes below the first stream's word area
+
+// Words a stream can keep in LDS: rw slots of 16 bits in an area of 2 rw + 4 bytes.  rw is a multiple of 16, so
+// the distance between the areas of adjacent streams is an odd number of 32-bit words and the lanes of a wave
+// that write the same slot number hit 64 different banks.
+__host__ __device__ inline uint32_t enc_area_stride(uint32_t rw) { return 2 * rw + 4; }
 
 // Encoder table entry as the coder uses it.
 struct EncEntry {
@@ -84,31 +89,35 @@ __device__ __forceinline__ EncEntry load_entry(const uint2 *g_tab, const uint32_
   return e;
 }
 
-// Interleaved rANS encoder (Eq. 2 with 16-bit renormalisation).  One work-group codes kWG * SPL
-// streams of one chunk (only SPL = 1 is instantiated: the hardware interleaves waves better than the
-// compiler interleaves several streams inside a lane).
+// Interleaved rANS encoder (Eq. 2 with 16-bit renormalisation).  One work-group codes kWG streams of one
+// chunk, one stream per lane (the hardware interleaves waves better than the compiler interleaves several
+// streams inside a lane).
 //
-// Symbols are taken last to first in batches of kEncAhead rows, fetched a batch ahead (dense source:
-// through a per-wave LDS stage filled with 16-byte loads a whole tile ahead), table entries looked up
-// three rows ahead.  The per-row arithmetic is branch-free (selects only) so that it stays one basic
-// block.  floor(s / f) of Eq. 2 is a multiply-high and a shift with the per-symbol multiplier that
-// k_normalize proved exact (table form 2, when every entry is exact), else a multiply-high with
-// floor(2^32 / f) plus one correction step.
+// Symbols are taken last to first in batches of kEncAhead rows, fetched ahead of the coder (through a
+// per-wave LDS stage filled with 16-byte loads two tiles ahead), table entries looked up three rows ahead.
+// The per-row arithmetic is branch-free (selects only) so that it stays one basic block.  floor(s / f) of
+// Eq. 2 is a multiply-high and a shift with the per-symbol multiplier that k_normalize proved exact (table
+// form 2, when every entry is exact), else a multiply-high with floor(2^32 / f) plus one correction step.
 //
-// Emitted words wait in a 16-slot LDS area per stream, filled from the top: the low half of the state
-// is written to the next slot on every step and the slot pointer moves only when the renormalisation
-// fires, so a slot keeps being rewritten until it is really used.  After every kEncAhead rows (a
-// wave-uniform point) a stream with 8 or more waiting words moves its 8 oldest as one 16-byte block to
-// scratch in global memory (block-major per work-group: lanes that flush the same block number write
-// adjacent memory); inside a block ascending address = descending word number, the decoder's order.
+// Emitted words stay in LDS: every stream has an area of rw 16-bit slots, filled from its top slot downwards
+// (ascending address = descending word number, the order the decoder reads).  The low half of the state is
+// written to the next slot on every step and the slot pointer moves only when the renormalisation fires, so a
+// slot keeps being rewritten until it is really used.  Most streams of a chunk fit their area.  One that
+// does not - checked after every kEncAhead rows, a wave-uniform point - moves its complete 8-word blocks,
+// oldest first, as 16-byte blocks to scratch in global memory (block-major per work-group: lanes that spill
+// the same block number write adjacent memory) and its few remaining words to the top of the area.
 //
-// FUSE: the work-group also moves its streams' words to their place in the container (what k_gather
-// does otherwise).  It publishes its word total, waits until every work-group with a lower index has
-// published its own (those were dispatched earlier and never wait for a higher index, so the wait ends;
-// it is bounded all the same and turns into RANS_ERR_HIP if the bound is hit), and derives the chunk's
-// byte offset and its own position inside the chunk from those totals.
+// FUSE: the work-group also moves its streams' words to their place in the container (what k_gather does
+// otherwise).  It adds its word total to its chunk's counter and publishes it for the later groups of the
+// chunk, waits until every earlier chunk is complete and every earlier group of its own chunk has published
+// (those work-groups were dispatched earlier and never wait for a higher index, so the wait ends; it is bounded
+// all the same and turns into RANS_ERR_HIP if the bound is hit), and derives the chunk's byte offset and its
+// own position inside the chunk from those totals: one load per chunk instead of one per work-group, all of
+// a lane's loads independent of each other.  Its words then go from the areas (and, for the streams that
+// spilled, from scratch) through an LDS tile to the container in aligned 16-byte stores.
+// Without FUSE everything is spilled to scratch at the end, in the block format k_gather reads.
 constexpr int kSpinMax = 1 << 18;
-constexpr uint32_t kEncTileBytes = 16384;  // LDS tile of the fused placement (overlays ring and table)
+constexpr uint64_t kChunkWordsMask = (1ull << 40) - 1;  // chunk counter: words below, finished groups above
 __device__ __forceinline__ uint32_t wait_published(const uint32_t *pub, uint32_t i, const CtlRef &ctl) {
   for (int spins = 0; spins < kSpinMax; spins++) {
     const uint32_t v = __hip_atomic_load(pub + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -118,25 +127,38 @@ __device__ __forceinline__ uint32_t wait_published(const uint32_t *pub, uint32_t
   }
   return 0;
 }
+// Words of chunk c once all of its `groups` work-groups have added theirs; ~0 if the wait gives up.
+__device__ __forceinline__ uint64_t wait_chunk(const unsigned long long *acc, uint32_t c, uint32_t groups, const CtlRef &ctl) {
+  for (int spins = 0; spins < kSpinMax; spins++) {
+    const unsigned long long v = __hip_atomic_load(acc + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((uint32_t)(v >> 40) == groups) return v & kChunkWordsMask;
+    if ((spins & 255) == 255 && get_status(ctl) != 0) return ~0ull;
+    __builtin_amdgcn_s_sleep(4);
+  }
+  return ~0ull;
+}
 
-template <class Src, int SPL, int TAB, bool MUL24, bool FUSE>
-__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k_encode(Src src, const uint2 *g_tab, const uint4 *g_tab4, uint32_t A, uint32_t M,
-                                                uint32_t S,
-                                                uint32_t cs, CtlRef ctl, uint16_t *scratch, uint32_t capw,
-                                                uint32_t *st_out, uint32_t *nw_out, uint32_t *chunk_words,
-                                                uint32_t groups, uint32_t *wg_pub, uint8_t *out, uint64_t cap,
-                                                uint64_t *d_stream_bytes, int wide) {
-  extern __shared__ __align__(16) uint32_t l_mem[];  // the only LDS of this kernel, so the ring starts at offset 0
+template <class Src, int TAB, bool MUL24, bool FUSE>
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k_encode(
+    Src src, const uint2 *g_tab, const uint4 *g_tab4, uint32_t A, uint32_t M, uint32_t S, uint32_t cs, CtlRef ctl,
+    uint16_t *scratch, uint32_t capw, uint32_t *st_out, uint32_t *nw_out, uint32_t *chunk_words, uint32_t groups,
+    uint32_t *wg_pub, unsigned long long *chunk_acc, uint8_t *out, uint64_t cap, uint64_t *d_stream_bytes, int wide,
+    uint32_t rw, uint32_t wgs_per_class, uint32_t n_classes) {
+  extern __shared__ __align__(16) uint32_t l_mem[];  // the only LDS of this kernel, so the word areas start at offset kEncGuard
+  const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
+  const unsigned long long t_begin = (FUSE && n_classes > 1) ? wall_clock64() : 0ull;
   // every exit publishes a total (0 words), or the work-groups behind this one would wait for it
   auto bail = [&]() {
-    if (FUSE && threadIdx.x == 0) __hip_atomic_store(wg_pub + blockIdx.x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (FUSE && threadIdx.x == 0) {
+      __hip_atomic_store(wg_pub + blockIdx.x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_fetch_add(chunk_acc + k, 1ull << 40, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   };
   if (group_has_status(ctl, l_mem)) {  // through the dynamic LDS: this kernel must not have static LDS (see below)
     if (FUSE && blockIdx.x == 0 && threadIdx.x == 0 && d_stream_bytes) *d_stream_bytes = 0;
     bail();
     return;
   }
-  const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
   const uint32_t nc = ctl->n_chunks;
   if (k >= nc) {
     if (FUSE && nc == 0 && blockIdx.x == 0 && threadIdx.x == 0) {  // empty D: only the directory's single entry
@@ -151,11 +173,12 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
   }
   src.init(ctl);
   const uint32_t sh_lim = 32 - M, totalM = 1u << M;
-  // LDS: [ring][table].  The ring comes first (LDS address 0) so that a slot address is the lane's
-  // fixed base plus twice the slot number.
-  constexpr uint32_t G = kWG * SPL;  // streams per work-group
-  constexpr uint32_t kRingBytes = kRingStride * G;
-  uint32_t *l_tab = l_mem + kRingBytes / 4;
+  // LDS: [guard][word areas][table][reduction scratch][symbol stage].  The areas come first so that a slot
+  // address is the lane's fixed base plus twice the slot number; what follows them is reused as the tile of
+  // the fused placement once the coding is over.
+  const uint32_t stride = enc_area_stride(rw);
+  const uint32_t areas_end = kEncGuard + stride * kWG;  // a multiple of 16
+  uint32_t *l_tab = l_mem + areas_end / 4;
   uint32_t *sh = l_tab + (TAB == 2 ? A * 4 : (TAB == 1 ? A * 2 : 0));  // 4 + 8 words for the final reductions
   // TAB == 2 has two forms of the table: the division-free one when every entry of it is exact for
   // this frequency table (the common case), else {floor(2^32/f), f, F, 2^M - f} with a correction step.
@@ -177,43 +200,50 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
   const uint64_t chunk_len = cs ? cs : len;
   const uint64_t base = (uint64_t)k * chunk_len;
   const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
-  const uint32_t j0 = (g * kWG + threadIdx.x) * SPL;
-  const bool live = j0 < S;  // S is a multiple of SPL: a lane's streams are all live or all absent
-  // Emitted words wait in a 16-slot LDS area per stream, filled from its top slot downwards: `wp` is the
-  // LDS address of the slot of the next word.  Once 8 or more words wait, the 8 oldest (the upper half:
-  // ascending address = descending word number, the order the decoder reads) leave as one 16-byte block
-  // and the lower half moves up.
-  uint32_t s[SPL], wp[SPL];
-  // Scratch holds the work-group's 16-byte blocks block-major: block b of the stream in column c at
-  // ((b * G + c) * 8) words from the work-group's base, so that the lanes of a wave that flush the
-  // same block number write adjacent memory.
-  uint16_t *gp[SPL];    // where the stream's next 16-byte block goes
-  uint32_t colb[SPL];   // LDS address of the stream's area; areas are kRingStride bytes apart (conflict-free)
-#pragma unroll
-  for (int i = 0; i < SPL; i++) {
-    s[i] = kL;
-    gp[i] = scratch + (uint64_t)blockIdx.x * (kWG * SPL) * capw + (i * kWG + threadIdx.x) * 8;
-    colb[i] = kRingStride * (i * kWG + threadIdx.x);
-    wp[i] = colb[i] + 30;
-  }
-  // the areas start at LDS address 0, so that `wp` is a plain LDS address
+  const uint32_t j0 = g * kWG + threadIdx.x;
+  const bool live = j0 < S;
+  // the areas are addressed as plain LDS addresses
   typedef __attribute__((address_space(3))) uint16_t lds_u16;
-  typedef __attribute__((address_space(3))) uint64_t lds_u64;
+  typedef __attribute__((address_space(3))) uint32_t lds_u32;
   if ((uint32_t)(uintptr_t)(lds_u16 *)l_mem != 0) {  // cannot happen without static LDS; the slot arithmetic relies on it
     if (threadIdx.x == 0) set_status(ctl, RANS_ERR_HIP);
     bail();
     return;
   }
-  auto flush = [&](int i) {
-    if (wp[i] < colb[i] + 16) {  // 8 or more words wait
-      lds_u64 *r = (lds_u64 *)(uintptr_t)colb[i];
-      const uint64_t lo0 = r[0], lo1 = r[1], hi0 = r[2], hi1 = r[3];
-      *(uint4 *)gp[i] = make_uint4((uint32_t)hi0, (uint32_t)(hi0 >> 32), (uint32_t)hi1, (uint32_t)(hi1 >> 32));
-      gp[i] += kWG * SPL * 8;
-      r[2] = lo0;
-      r[3] = lo1;
-      wp[i] += 16;
+  uint32_t s = kL;
+  const uint32_t colb = kEncGuard + stride * threadIdx.x;  // the lane's area: slots colb, colb + 2, ..., top - 2
+  const uint32_t top = colb + 2 * rw;
+  uint32_t wp = top - 2;                                   // LDS address of the slot of the next word
+  // Scratch holds the work-group's spilled 16-byte blocks block-major: block b of the stream in column c at
+  // ((b * kWG + c) * 8) words from the work-group's base.
+  uint16_t *const g0 = scratch + (uint64_t)blockIdx.x * kWG * capw + threadIdx.x * 8;
+  uint16_t *gp = g0;  // where the stream's next spilled block goes
+  auto words_in_area = [&]() { return (top - 2 - wp) >> 1; };
+  // Moves the area's complete 8-word blocks (oldest first: from the top) to scratch and what is left, fewer
+  // than 8 words, to the top of the area.  `all`: the remainder goes out too, as one more block whose first
+  // 8 - r words are not part of the stream (the format k_gather reads).
+  auto spill = [&](bool all) {
+    const uint32_t n_used = words_in_area();
+    const uint32_t nblk = n_used >> 3, r = n_used & 7;
+    for (uint32_t b = 0; b < nblk; b++) {
+      const lds_u32 *q = (const lds_u32 *)(uintptr_t)(top - 16 * (b + 1));
+      *(uint4 *)gp = make_uint4(q[0], q[1], q[2], q[3]);
+      gp += kWG * 8;
     }
+    if (r && nblk) {  // the remaining words sit at the bottom end of what was used: up to the top
+      for (uint32_t i = 0; i < r; i++)
+        *(lds_u16 *)(uintptr_t)(top - 2 * r + 2 * i) = *(const lds_u16 *)(uintptr_t)(wp + 2 + 2 * i);
+    }
+    wp = top - 2 - 2 * r;
+    if (all && r) {
+      const lds_u32 *q = (const lds_u32 *)(uintptr_t)(top - 16);
+      *(uint4 *)gp = make_uint4(q[0], q[1], q[2], q[3]);
+      gp += kWG * 8;
+    }
+  };
+  // after every batch: a stream with fewer than kEncAhead free slots left makes room
+  auto make_room = [&]() {
+    if (wp < colb + 2 * (kEncAhead - 1)) spill(false);
   };
   // The coding loop, for one of the two table forms (an entry is {m, f, F, cmpl} with the meaning of
   // that form: EXACT {mx, lim1, Fx | sh << 16, 2^M - f}, else {floor(2^32/f), f, F, 2^M - f}).
@@ -221,37 +251,20 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
     constexpr bool EXACT = decltype(exact_tag)::value;
     constexpr int WIDE_KIND = decltype(wide_tag)::value;  // 0: direct loads, 1: dense bytes through LDS, 2: CSR segments through LDS
     constexpr bool WIDE = WIDE_KIND == 1;
-    // Eq. 2 for the lane's SPL streams, phase by phase across the streams so that the
-    // independent chains interleave; selects only, no branches.
-    auto row = [&](const EncEntry (&e)[SPL]) {
-      bool c[SPL];
-      uint32_t q[SPL];
-#pragma unroll
-      for (int i = 0; i < SPL; i++)  // too large for this symbol: emit 16 bits
-        c[i] = EXACT ? s[i] > e[i].f : (s[i] >> sh_lim) >= e[i].f;
-#pragma unroll
-      for (int i = 0; i < SPL; i++) *(lds_u16 *)(uintptr_t)wp[i] = (uint16_t)s[i];  // speculative: the slot counts only if c
-#pragma unroll
-      for (int i = 0; i < SPL; i++) {
-        s[i] = c[i] ? s[i] >> 16 : s[i];
-        wp[i] = c[i] ? wp[i] - 2 : wp[i];
-      }
-#pragma unroll
-      for (int i = 0; i < SPL; i++) q[i] = __umulhi(s[i], e[i].m);
+    // Eq. 2; selects only, no branches.
+    auto row = [&](const EncEntry &e) {
+      const bool c = EXACT ? s > e.f : (s >> sh_lim) >= e.f;  // too large for this symbol: emit 16 bits
+      *(lds_u16 *)(uintptr_t)wp = (uint16_t)s;                // speculative: the slot counts only if c
+      s = c ? s >> 16 : s;
+      wp = c ? wp - 2 : wp;
+      uint32_t q = __umulhi(s, e.m);
       if constexpr (EXACT) {
-#pragma unroll
-        for (int i = 0; i < SPL; i++) q[i] >>= e[i].F >> 16;
-#pragma unroll
-        for (int i = 0; i < SPL; i++)
-          s[i] = (MUL24 ? __umul24(q[i], e[i].cmpl) + s[i] : q[i] * e[i].cmpl + s[i]) + (e[i].F & 0xffffu);
+        q >>= e.F >> 16;
+        s = (MUL24 ? __umul24(q, e.cmpl) + s : q * e.cmpl + s) + (e.F & 0xffffu);
       } else {
-        uint32_t rem[SPL];
-#pragma unroll
-        for (int i = 0; i < SPL; i++) rem[i] = s[i] - (MUL24 ? __umul24(q[i], e[i].f) : q[i] * e[i].f);
-#pragma unroll
-        for (int i = 0; i < SPL; i++) q[i] += rem[i] >= e[i].f ? 1u : 0u;
-#pragma unroll
-        for (int i = 0; i < SPL; i++) s[i] = s[i] + e[i].F + (MUL24 ? __umul24(q[i], e[i].cmpl) : q[i] * e[i].cmpl);
+        const uint32_t rem = s - (MUL24 ? __umul24(q, e.f) : q * e.f);
+        q += rem >= e.f ? 1u : 0u;
+        s = s + e.F + (MUL24 ? __umul24(q, e.cmpl) : q * e.cmpl);
       }
     };
     auto entry = [&](uint32_t x) -> EncEntry {
@@ -262,88 +275,75 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
         return load_entry<TAB>(g_tab, l_tab, x, totalM);
       }
     };
-    auto lookup = [&](EncEntry (&e)[SPL], uint32_t raw) {
-#pragma unroll
-      for (int i = 0; i < SPL; i++) e[i] = entry(Src::get(raw, i));
-    };
     const uint64_t rows_full = n_here / S;
     const uint32_t rem_row = (uint32_t)(n_here - rows_full * S);
-    EncEntry ea[SPL];
     if (rem_row) {  // ragged last row: only streams j < rem_row have a symbol there
-#pragma unroll
-      for (int i = 0; i < SPL; i++) {
-        // an absent stream gets a neutral entry, which leaves the state untouched
-        ea[i] = EXACT ? EncEntry{0u, 0xffffffffu, 0u, 0u} : EncEntry{0u, totalM, 0u, 0u};
-        if (j0 + i < rem_row) ea[i] = entry(src(base + rows_full * S + j0 + i));
-      }
+      // an absent stream gets a neutral entry, which leaves the state untouched
+      EncEntry ea = EXACT ? EncEntry{0u, 0xffffffffu, 0u, 0u} : EncEntry{0u, totalM, 0u, 0u};
+      if (j0 < rem_row) ea = entry(src(base + rows_full * S + j0));
       row(ea);
     }
     // rows beyond a multiple of kEncAhead, one at a time
     uint64_t t = rows_full;
-    for (uint32_t r = (uint32_t)(rows_full % kEncAhead); r > 0; r--, t--) {
-      lookup(ea, src.template fetch<SPL>(base + (t - 1) * S + j0));
-      row(ea);
-    }
-    // at most 1 + 7 words staged so far; from here on every batch ends with a flush, which keeps a
-    // stream's staged words below 8 at the start of a batch and below 16 (the ring size) inside it
-#pragma unroll
-    for (int i = 0; i < SPL; i++) flush(i);
-    // full batches of kEncAhead rows: rows fetched one batch ahead, table entries one row ahead,
-    // alternating between two register sets
+    for (uint32_t r = (uint32_t)(rows_full % kEncAhead); r > 0; r--, t--) row(entry(src(base + (t - 1) * S + j0)));
+    // at most 1 + 7 words so far (rw >= 16): from here on every batch ends with make_room(), which keeps at least
+    // kEncAhead slots free at the start of a batch
+    make_room();
+    // full batches of kEncAhead rows: rows fetched one batch ahead, table entries kLook rows ahead of their use
+    // (an LDS read takes longer than the arithmetic of a row), in a rotation of kLook + 1 register sets
     uint32_t cur[kEncAhead], nxt[kEncAhead];
-    // Table entries are looked up kLook rows ahead of their use (an LDS read takes longer than the
-    // arithmetic of a row), in a rotation of kLook + 1 register sets.
     constexpr int kLook = 3;
-    EncEntry E[kLook + 1][SPL];
+    EncEntry E[kLook + 1];
     auto prime = [&]() {  // entries of the first kLook rows of nxt[]
 #pragma unroll
-      for (int u = 0; u < kLook; u++) lookup(E[u], nxt[u]);
+      for (int u = 0; u < kLook; u++) E[u] = entry(nxt[u]);
     };
     auto batch = [&]() {  // codes the rows in cur[]; leaves the entries of nxt[0 .. kLook-1] in E[0 .. kLook-1]
 #pragma unroll
       for (int u = 0; u < kEncAhead; u++) {
         // past the end of the batch this looks up rows of the next batch; when there is none, nxt[]
         // still holds old, valid symbols and the entries are simply not used
-        lookup(E[(u + kLook) % (kLook + 1)], u + kLook < kEncAhead ? cur[(u + kLook) % kEncAhead] : nxt[(u + kLook) % kEncAhead]);
+        E[(u + kLook) % (kLook + 1)] = entry(u + kLook < kEncAhead ? cur[(u + kLook) % kEncAhead] : nxt[(u + kLook) % kEncAhead]);
         row(E[u % (kLook + 1)]);
       }
-#pragma unroll
-      for (int i = 0; i < SPL; i++) flush(i);
+      make_room();
     };
     if constexpr (WIDE) {
       // Symbols through LDS: single-byte loads keep too few bytes in flight to cover the memory latency.
-      // A wave owns a 64-byte column of the chunk's rows.  It fetches kStageRows rows of it at a time
-      // with 16-byte loads (lane L: row L/4 and row 16 + L/4 of the tile, bytes 16 (L%4) ..), a whole tile
-      // ahead of the coder, and parks them in a private LDS area that holds two tiles, row r in line
-      // r mod 64; the coder reads its byte of each row from there.  No other wave touches the area.
-      static_assert(!WIDE || (SPL == 1 && kEncAhead == 8 && kStageRows == 32), "tile arithmetic below");
+      // A wave owns a 64-byte column of the chunk's rows.  It fetches 16 rows of it at a time with 16-byte loads
+      // (lane L: row L / 4 of the tile, bytes 16 (L % 4) ..; tiles start at multiples of 16 rows) and keeps two such
+      // tiles waiting in registers, so a request has 24 to 32 rows of coding to arrive.  LDS holds two slots of
+      // 8 rows per wave: before a batch, the half tile with its rows is parked in the slot the batch before the
+      // last one has read up (a half tile is what 32 lanes hold, and lane L's 16 bytes go to byte 16 L of the
+      // two slots taken as one area: rows 0-7 of a tile to slot 0, rows 8-15 to slot 1).  No other wave touches the area.
+      static_assert(!WIDE || (kEncAhead == 8 && kStageRows == 16), "tile arithmetic below");
       const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-      uint8_t *stg = (uint8_t *)(sh + 16) + wv * (2 * kStageRows * 64);
+      uint8_t *stg = (uint8_t *)(sh + 16) + wv * (kStageRows * 64);
       const uint8_t *colp = src.bytes() + base + (j0 - lane) + 16 * (lane & 3);  // the lane's 16 bytes of row 0
-      uint4 pend[2];
-      auto request = [&](uint64_t t_lo, uint64_t t_top) {  // rows t_lo .. t_lo+31 (below t_top) of the column
-#pragma unroll
-        for (int h = 0; h < 2; h++) {
-          const uint64_t r = t_lo + 16 * h + (lane >> 2);
-          pend[h] = make_uint4(0, 0, 0, 0);
-          if (r < t_top) pend[h] = *(const uint4 *)(colp + r * S);
-        }
+      auto request = [&](uint64_t t_lo, uint64_t t_top) -> uint4 {  // rows t_lo .. t_lo+15 (below t_top) of the column
+        const uint64_t r = t_lo + (lane >> 2);
+        return r < t_top ? *(const uint4 *)(colp + r * S) : make_uint4(0, 0, 0, 0);
       };
-      auto park = [&](uint64_t t_lo) {
-#pragma unroll
-        for (int h = 0; h < 2; h++)
-          *(uint4 *)(stg + (((uint32_t)t_lo + 16 * h) & 63u) * 64 + 16 * lane) = pend[h];
+      auto park_half = [&](const uint4 &q, uint32_t upper) {  // rows 8 upper .. 8 upper + 7 of the tile in q
+        if ((lane >> 5) == upper) *(uint4 *)(stg + 16 * lane) = q;
       };
       auto read_rows = [&](uint32_t *dst, uint64_t t_hi) {  // rows t_hi-1 .. t_hi-8; t_hi is a multiple of 8
-        const uint8_t *b = stg + (((uint32_t)t_hi - 8) & 63u) * 64 + lane;
+        const uint8_t *b = stg + (((uint32_t)t_hi - 8) & 8u) * 64 + lane;
 #pragma unroll
         for (int u = 0; u < kEncAhead; u++) dst[u] = b[(kEncAhead - 1 - u) * 64];
       };
+      uint4 pend0 = make_uint4(0, 0, 0, 0), pend1 = pend0;  // pend0: the tile the next batch lies in (or the one below, once it is parked whole)
       if (t) {
         const uint64_t t_lo = (t - 1) & ~(uint64_t)(kStageRows - 1);
-        request(t_lo, t);
-        park(t_lo);
-        if (t_lo) request(t_lo - kStageRows, t_lo);
+        pend0 = request(t_lo, t);
+        if (t_lo >= kStageRows) pend1 = request(t_lo - kStageRows, t_lo);
+        if ((t & 15) == 8) {  // the first batch is the tile's lower half, its upper half lies past the end
+          park_half(pend0, 0);
+          pend0 = pend1;
+          if (t_lo >= 2 * kStageRows) pend1 = request(t_lo - 2 * kStageRows, t_lo - kStageRows);
+        } else {
+          park_half(pend0, 1);
+        }
         read_rows(nxt, t);
         prime();
       }
@@ -351,10 +351,13 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
 #pragma unroll
         for (int u = 0; u < kEncAhead; u++) cur[u] = nxt[u];
         t -= kEncAhead;
-        if (t) {
-          if ((t & (kStageRows - 1)) == 0) {  // the next rows belong to the tile below: it has arrived by now
-            park(t - kStageRows);
-            if (t > kStageRows) request(t - 2 * kStageRows, t - kStageRows);
+        if (t) {  // the next batch is rows t-8 .. t-1
+          if ((t & 15) == 0) {
+            park_half(pend0, 1);  // upper half of the tile below the one just finished
+          } else {
+            park_half(pend0, 0);  // lower half of the same tile; with it the tile is parked whole
+            pend0 = pend1;
+            if (t >= 8 + 2 * kStageRows) pend1 = request(t - 8 - 2 * kStageRows, t - 8 - kStageRows);
           }
           read_rows(nxt, t);
         }
@@ -365,7 +368,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
       // kStageRows2 rows of them, lane L fetches the 16 entries 16 (L % 4) .. of row L / 4: one 16-byte load
       // where they all lie in v, two where they all lie in c or in r (2-byte aligned: where c starts inside D
       // depends on the number of nonzeros), entry by entry where they straddle two parts or the end of D.
-      static_assert(WIDE_KIND != 2 || (SPL == 1 && kEncAhead == 8 && kStageRows2 == 16), "tile arithmetic below");
+      static_assert(WIDE_KIND != 2 || (kEncAhead == 8 && kStageRows2 == 16), "tile arithmetic below");
       const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
       // 16-byte aligned whatever the size of the table before it
       uint8_t *stg = (uint8_t *)(((uintptr_t)(sh + 16) + 15) & ~(uintptr_t)15) + wv * (2 * kStageRows2 * 128);
@@ -386,9 +389,9 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
           } else {
             uint32_t w[8];
 #pragma unroll
-            for (int k = 0; k < 8; k++) {
-              const uint32_t lo = i + 2 * k < len ? src(i + 2 * k) : 0u, hi = i + 2 * k + 1 < len ? src(i + 2 * k + 1) : 0u;
-              w[k] = lo | (hi << 16);
+            for (int kk = 0; kk < 8; kk++) {
+              const uint32_t lo = i + 2 * kk < len ? src(i + 2 * kk) : 0u, hi = i + 2 * kk + 1 < len ? src(i + 2 * kk + 1) : 0u;
+              w[kk] = lo | (hi << 16);
             }
             pend[0] = make_uint4(w[0], w[1], w[2], w[3]);
             pend[1] = make_uint4(w[4], w[5], w[6], w[7]);
@@ -403,9 +406,9 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
           const uint32_t ww[4] = {pend[0].x, pend[0].y, pend[0].z, pend[0].w};
           uint32_t e[8];
 #pragma unroll
-          for (int k = 0; k < 8; k++) {
-            const uint32_t two = ww[k >> 1] >> (16 * (k & 1));
-            e[k] = (two & 0xffu) | ((two & 0xff00u) << 8);
+          for (int kk = 0; kk < 8; kk++) {
+            const uint32_t two = ww[kk >> 1] >> (16 * (kk & 1));
+            e[kk] = (two & 0xffu) | ((two & 0xff00u) << 8);
           }
           a = make_uint4(e[0], e[1], e[2], e[3]);
           b = make_uint4(e[4], e[5], e[6], e[7]);
@@ -450,7 +453,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
     } else {
       auto fetch_rows = [&](uint32_t *dst, uint64_t t_hi) {  // rows t_hi-1 .. t_hi-kEncAhead
 #pragma unroll
-        for (int u = 0; u < kEncAhead; u++) dst[u] = src.template fetch<SPL>(base + (t_hi - 1 - u) * S + j0);
+        for (int u = 0; u < kEncAhead; u++) dst[u] = src(base + (t_hi - 1 - u) * S + j0);
       };
       if (t) {
         fetch_rows(nxt, t);
@@ -466,7 +469,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
     }
   };
   if (live) {
-    if constexpr (std::is_same<Src, SrcDense>::value && SPL == 1) {
+    if constexpr (std::is_same<Src, SrcDense>::value) {
       if (wide) {
         if (exact) run(std::true_type{}, std::integral_constant<int, 1>{});
         else run(std::false_type{}, std::integral_constant<int, 1>{});
@@ -474,7 +477,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
         if (exact) run(std::true_type{}, std::integral_constant<int, 0>{});
         else run(std::false_type{}, std::integral_constant<int, 0>{});
       }
-    } else if constexpr (std::is_same<Src, SrcCsr>::value && SPL == 1) {
+    } else {
       if (wide) {
         if (exact) run(std::true_type{}, std::integral_constant<int, 2>{});
         else run(std::false_type{}, std::integral_constant<int, 2>{});
@@ -482,73 +485,106 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
         if (exact) run(std::true_type{}, std::integral_constant<int, 0>{});
         else run(std::false_type{}, std::integral_constant<int, 0>{});
       }
-    } else {
-      if (exact) run(std::true_type{}, std::integral_constant<int, 0>{});
-      else run(std::false_type{}, std::integral_constant<int, 0>{});
     }
   }
-  uint32_t nw[SPL];
-#pragma unroll
-  for (int i = 0; i < SPL; i++) {
-    const uint16_t *g0 = scratch + (uint64_t)blockIdx.x * (kWG * SPL) * capw + (i * kWG + threadIdx.x) * 8;
-    const uint32_t n_rem = (colb[i] + 30 - wp[i]) >> 1;  // fewer than 8
-    nw[i] = live ? (uint32_t)((gp[i] - g0) / (kWG * SPL)) + n_rem : 0;
-    if (live) {
-      // the remaining words sit at the top of the area's upper half: it leaves as one more block, whose
-      // first 8 - n_rem words are not part of the stream
-      if (n_rem) {
-        const lds_u64 *r = (const lds_u64 *)(uintptr_t)colb[i];
-        const uint64_t hi0 = r[2], hi1 = r[3];
-        *(uint4 *)gp[i] = make_uint4((uint32_t)hi0, (uint32_t)(hi0 >> 32), (uint32_t)hi1, (uint32_t)(hi1 >> 32));
-      }
-      if (!FUSE) {
-        st_out[(uint64_t)k * S + j0 + i] = s[i];
-        nw_out[(uint64_t)k * S + j0 + i] = nw[i];
-      }
-    }
+  if (!FUSE && live) spill(true);  // k_gather finds every word in scratch
+  const uint32_t n_lds = (FUSE && live) ? words_in_area() : 0;                     // words still in the area
+  const uint32_t nbg = live ? (uint32_t)((gp - g0) / (kWG * 8)) : 0;               // blocks in scratch
+  // without FUSE the last block may be partial: spill(true) has left wp at the top minus the r words it holds
+  const uint32_t nw = !live ? 0 : (FUSE ? 8 * nbg + n_lds : ((top - 2 - wp) >> 1 ? 8 * (nbg - 1) + ((top - 2 - wp) >> 1) : 8 * nbg));
+  if (!FUSE && live) {
+    st_out[(uint64_t)k * S + j0] = s;
+    nw_out[(uint64_t)k * S + j0] = nw;
   }
-  uint32_t mine = 0;
-#pragma unroll
-  for (int i = 0; i < SPL; i++) mine += nw[i];
   uint32_t tot;
-  const uint32_t ex = block_excl_scan<kWG>(mine, sh, &tot);
+  const uint32_t ex = block_excl_scan<kWG>(nw, sh, &tot);
   if (!FUSE) {
     if (threadIdx.x == 0 && tot) atomicAdd(&chunk_words[k], tot);
     return;
   }
   if constexpr (FUSE) {
-    static_assert(!FUSE || SPL == 1, "the fused placement assumes one stream per lane");
-    if (threadIdx.x == 0) __hip_atomic_store(wg_pub + blockIdx.x, tot + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    // The lane's own words come back from scratch in the aligned 16-byte blocks written above (block 0
-    // is the lowest one; it starts with `skip` words that are not part of the stream).
-    constexpr int kInFlight = 4;
-    const uint32_t nw1 = live ? nw[0] : 0;
-    // block bi of the stream in read order (bi = 0: the newest, partial one) is block nb - 1 - bi as written
-    const uint16_t *g0 = scratch + (uint64_t)blockIdx.x * kWG * capw + threadIdx.x * 8;
-    const uint32_t nb = (nw1 + 7) / 8, skip = nb * 8 - nw1;
-    // totals of the work-groups before this one: whole chunks give the chunk's byte offset, the groups
-    // of this chunk before g give the position inside the chunk
-    uint64_t off_loc = 0, pre_loc = 0;
-    uint32_t failed = 0;
-    for (uint32_t c = threadIdx.x; c < k; c += kWG) {
-      uint64_t words = 0;
-      for (uint32_t g2 = 0; g2 < groups; g2++) {
-        const uint32_t v = wait_published(wg_pub, c * groups + g2, ctl);
-        failed |= v == 0;
-        words += v - 1;
+    if (threadIdx.x == 0) {
+      __hip_atomic_store(wg_pub + blockIdx.x, tot + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_fetch_add(chunk_acc + k, (1ull << 40) | tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // The spilled blocks of the whole work-group, taken as one list in stream order and, inside a stream, in
+    // read order (the last written first): thread i moves blocks i, i + kWG, ...  Their owners and places come
+    // from three small tables in LDS (the stage is no longer needed).  Every thread requests its first kPre
+    // blocks now, so that they arrive while the work-group waits for the totals of the others.
+    uint32_t *t_bex = sh + 16, *t_dst = t_bex + kWG, *t_nbg = t_dst + kWG;
+    uint32_t n_spilled;
+    const uint32_t bex = block_excl_scan<kWG>(nbg, sh, &n_spilled);
+    constexpr int kPre = 2;
+    uint4 pre_q[kPre];
+    uint32_t pre_dst[kPre];  // word offset from the work-group's first word; ~0: no block
+    auto owner_of = [&](uint32_t i) {  // the last stream whose first block is at or before i
+      uint32_t lo = 0, hi = kWG;
+      while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (t_bex[mid] <= i) lo = mid;
+        else hi = mid;
       }
-      off_loc += (8ull * S + 2 * words + 3) & ~3ull;
+      return lo;
+    };
+    auto block_src = [&](uint32_t i, uint32_t *dst_off) -> const uint4 * {
+      const uint32_t o = owner_of(i), bi = i - t_bex[o];
+      *dst_off = t_dst[o] + 8 * bi;
+      return (const uint4 *)(scratch + (uint64_t)blockIdx.x * kWG * capw + ((uint64_t)(t_nbg[o] - 1 - bi) * kWG + o) * 8);
+    };
+    if (n_spilled) {  // uniform
+      t_bex[threadIdx.x] = bex;
+      t_dst[threadIdx.x] = ex + n_lds;
+      t_nbg[threadIdx.x] = nbg;
+      lds_barrier();
+#pragma unroll
+      for (int u = 0; u < kPre; u++) {
+        const uint32_t i = threadIdx.x + u * kWG;
+        pre_dst[u] = ~0u;
+        if (i < n_spilled) pre_q[u] = *block_src(i, &pre_dst[u]);
+      }
     }
-    for (uint32_t g2 = threadIdx.x; g2 < g; g2 += kWG) {
-      const uint32_t v = wait_published(wg_pub, k * groups + g2, ctl);
-      failed |= v == 0;
-      pre_loc += v - 1;
+    // Polling for the totals of the others delays every vector load of the compute unit that is issued behind
+    // it, i.e. the symbols of the work-groups that still code there.  Work-groups are placed round robin and the
+    // hardware favours a unit's oldest waves, so with several work-groups per unit the first ones finish well
+    // before the last: such a work-group first sleeps, without a single load, for about as long as the later
+    // ones still need (a share of its own coding time per work-group behind it - an estimate that only decides
+    // when the polling starts, not what is computed).
+    if (n_classes > 1 && threadIdx.x < 64) {
+      const uint32_t cls = blockIdx.x / wgs_per_class;  // < n_classes by the host's choice of wgs_per_class
+      const unsigned long long now = wall_clock64();
+      const unsigned long long until = now + ((now - t_begin) * (n_classes - 1 - cls) * 12) / 100;
+      while (wall_clock64() < until) __builtin_amdgcn_s_sleep(32);
     }
-    uint64_t *sh64 = (uint64_t *)(sh + 4);
-    const uint64_t off = block_sum64<kWG>(off_loc, sh64);
-    const uint64_t pre = block_sum64<kWG>(pre_loc, sh64);
-    const uint64_t any_failed = block_sum64<kWG>(failed, sh64);
-    if (any_failed) {  // uniform: a wait ran into its bound, or another work-group reported an error
+    // Totals of what lies before this work-group's words: every earlier chunk (its size gives the chunk's
+    // byte offset) and the earlier groups of this chunk (the position inside the chunk).  The first wave
+    // collects them - a lane's loads are independent of each other - and hands the sums over through LDS.
+    uint64_t *sh64 = (uint64_t *)(sh + 4);  // [0] chunk offset, [1] words before this group, [2] a wait failed
+    const uint32_t lane = threadIdx.x & 63;
+    if (threadIdx.x < 64) {
+      uint64_t off_loc = 0, pre_loc = 0, failed = 0;
+      for (uint32_t c = lane; c < k; c += 64) {
+        const uint64_t words = wait_chunk(chunk_acc, c, groups, ctl);
+        failed |= words == ~0ull;
+        off_loc += (8ull * S + 2 * words + 3) & ~3ull;
+      }
+      for (uint32_t g2 = lane; g2 < g; g2 += 64) {
+        const uint32_t v = wait_published(wg_pub, k * groups + g2, ctl);
+        failed |= v == 0;
+        pre_loc += v - 1;
+      }
+      auto add64 = [](uint64_t x, uint64_t y) { return x + y; };
+      off_loc = lane63_64(wave_incl_scan64(off_loc, add64));
+      pre_loc = lane63_64(wave_incl_scan64(pre_loc, add64));
+      failed = lane63_64(wave_incl_scan64(failed, add64));
+      if (lane == 0) {
+        sh64[0] = off_loc;
+        sh64[1] = pre_loc;
+        sh64[2] = failed;
+      }
+    }
+    __syncthreads();
+    const uint64_t off = sh64[0], pre = sh64[1];
+    if (sh64[2]) {  // uniform: a wait ran into its bound, or another work-group reported an error
       if (threadIdx.x == 0) {
         if (get_status(ctl) == 0) set_status(ctl, RANS_ERR_HIP);
         if (k == nc - 1 && g == groups - 1 && d_stream_bytes) *d_stream_bytes = 0;
@@ -576,69 +612,65 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
     }
     if (!fits) return;  // uniform
     uint8_t *ck = out + ctl->payload_off + off;
-    const uint32_t j = j0;
     if (live) {
-      st32(ck + 4ull * j, s[0]);
-      st32(ck + 4ull * S + 4ull * j, nw1);
+      st32(ck + 4ull * j0, s);
+      st32(ck + 4ull * S + 4ull * j0, nw);
     }
-    // words: registers / scratch -> LDS tile -> container.  A lane stages its own stream's words in LDS
-    // at their position in the chunk; the work-group then writes the staged tile out in aligned
-    // 16-byte vectors (single words only at the two ends of its range).  The tile reuses the ring and
-    // the table, which are no longer needed.  Tile positions are shifted by the destination's offset
-    // inside a 16-byte vector, so LDS vectors and output vectors coincide.
-    uint16_t *tile = (uint16_t *)l_mem;
-    constexpr uint32_t kTile = kEncTileBytes / 2;
-    uint16_t *dst = (uint16_t *)(ck + 8ull * S) + pre;
-    const uint32_t shift = (uint32_t)(((uintptr_t)dst >> 1) & 7);
-    uint16_t *vbase = dst - shift;  // 16-byte aligned; tile word p' (over all tiles) goes to vbase[p']
-    const uint32_t exs = ex + shift;
-    lds_barrier();  // everyone is done with the ring, the table and the reduction scratch
-    for (uint32_t t0 = 0; t0 < shift + tot; t0 += kTile) {
-      const uint32_t lo = exs > t0 ? exs : t0;
-      const uint32_t hi = exs + nw1 < t0 + kTile ? exs + nw1 : t0 + kTile;
-      auto stage = [&](const uint4 &q, uint32_t bi) {
-        const uint32_t w0 = bi * 8 - skip;  // read-order number of the block's first word (wraps in block 0)
-        const uint32_t pos0 = exs + w0;
-        if (bi * 8 >= skip && pos0 >= lo && pos0 + 8 <= hi) {
-          // the whole block belongs to the stream and to this tile: one 16-byte LDS store at a 2-byte
-          // aligned address (the target allows unaligned LDS access)
-          __builtin_memcpy(tile + (pos0 - t0), &q, 16);
-        } else {
-          const uint32_t ww[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-          for (int i = 0; i < 8; i++) {
-            const uint32_t pos = pos0 + i;
-            if (w0 + i < nw1 && pos >= lo && pos < hi) tile[pos - t0] = (uint16_t)(ww[i >> 1] >> (16 * (i & 1)));
+    // Words.  In read order a stream's words are the area's, lowest address first, then its spilled blocks, the
+    // last written first.  The areas: eight lanes share a stream, each moving eight of its words (and eight more
+    // 64 words on, where an area holds that many) as one 16-byte piece - both ends are only 2-byte aligned, which the target allows - so a
+    // wave moves eight streams per step and their pieces are adjacent in the container.
+    uint16_t *dst = (uint16_t *)(ck + 8ull * S) + pre;  // first word of this group
+    for (uint32_t L0 = 0; L0 < 64; L0 += 8) {
+      const int from = (int)(L0 + (lane >> 3));
+      const uint32_t nL = (uint32_t)__shfl((int)n_lds, from), eL = (uint32_t)__shfl((int)ex, from);
+      const uint32_t aL = (uint32_t)__shfl((int)wp, from) + 2;
+      for (uint32_t w0 = 8 * (lane & 7); w0 < nL; w0 += 64) {
+        const uint16_t *sp = (const uint16_t *)l_mem + (aL >> 1) + w0;
+        uint16_t *dp = dst + eL + w0;
+        if (w0 + 8 <= nL) {
+          uint4 q;
+          __builtin_memcpy(&q, sp, 16);
+          __builtin_memcpy(dp, &q, 16);
+        } else {  // the stream's last piece, 1 to 7 words: four, two, one
+          const uint32_t rem = nL - w0;
+          uint32_t o = 0;
+          if (rem & 4) {
+            uint2 q;
+            __builtin_memcpy(&q, sp, 8);
+            __builtin_memcpy(dp, &q, 8);
+            o = 4;
           }
-        }
-      };
-      if (lo < hi) {
-        const uint32_t b_lo = (lo - exs + skip) / 8, b_hi = (hi - 1 - exs + skip) / 8;
-        for (uint32_t b0 = b_lo; b0 <= b_hi; b0 += kInFlight) {
-          uint4 q[kInFlight];
-#pragma unroll
-          for (int u = 0; u < kInFlight; u++)
-            if (b0 + u <= b_hi) q[u] = *(const uint4 *)(g0 + (uint64_t)(nb - 1 - (b0 + u)) * (kWG * 8));
-#pragma unroll
-          for (int u = 0; u < kInFlight; u++)
-            if (b0 + u <= b_hi) stage(q[u], b0 + u);
+          if (rem & 2) {
+            uint32_t q;
+            __builtin_memcpy(&q, sp + o, 4);
+            __builtin_memcpy(dp + o, &q, 4);
+            o += 2;
+          }
+          if (rem & 1) dp[o] = sp[o];
         }
       }
-      lds_barrier();
-      const uint32_t a = t0 == 0 ? shift : 0;                                      // first valid tile word
-      const uint32_t e = shift + tot - t0 < kTile ? shift + tot - t0 : kTile;      // end of the valid tile words
-      const uint32_t head_end = a ? (e < 8u ? e : 8u) : 0;
-      const uint32_t v_lo = a ? 1 : 0, v_hi = e / 8;
-      const uint32_t tail_beg = v_hi >= v_lo ? 8 * v_hi : e;
-      for (uint32_t v = v_lo + threadIdx.x; v < v_hi; v += kWG) ((uint4 *)(vbase + t0))[v] = ((const uint4 *)tile)[v];
-      if (threadIdx.x < 8) {
-        const uint32_t h = a + threadIdx.x, t = tail_beg + threadIdx.x;
-        if (h < head_end) vbase[t0 + h] = tile[h];
-        if (t < e) vbase[t0 + t] = tile[t];
-      }
-      lds_barrier();
     }
-    if (last_group && live && j == S - 1 && ((pre + tot) & 1)) dst[tot] = 0;  // pad the chunk to 4 bytes
+    // a spilled block to its place: 16 bytes to a 2-byte aligned address
+    auto put_block = [&](const uint4 &q, uint32_t dst_off) { __builtin_memcpy(dst + dst_off, &q, 16); };
+    if (n_spilled) {
+#pragma unroll
+      for (int u = 0; u < kPre; u++)
+        if (pre_dst[u] != ~0u) put_block(pre_q[u], pre_dst[u]);
+      for (uint32_t i0 = threadIdx.x + kPre * kWG; i0 < n_spilled; i0 += 4 * kWG) {  // the rest, four in flight per thread
+        uint4 q[4];
+        uint32_t d_off[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+          d_off[u] = ~0u;
+          if (i0 + u * kWG < n_spilled) q[u] = *block_src(i0 + u * kWG, &d_off[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++)
+          if (d_off[u] != ~0u) put_block(q[u], d_off[u]);
+      }
+    }
+    if (last_group && live && j0 == S - 1 && ((pre + tot) & 1)) dst[tot] = 0;  // pad the chunk to 4 bytes
   }
 }
 

@@ -124,6 +124,19 @@ inline uint32_t next_seq() {
   return v;
 }
 
+// Compute units of the current device (0 if the query fails); asked once per device.
+inline uint32_t compute_units() {
+  static std::atomic<int> cached[64];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  int v = cached[dev].load(std::memory_order_relaxed);
+  if (v == 0) {
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 0;
+    cached[dev].store(v, std::memory_order_relaxed);
+  }
+  return (uint32_t)v;
+}
+
 constexpr uint32_t kDecWideGroupMinChunks = 192;
 constexpr uint32_t kExpandOwnSumMaxTiles = 4096;
 constexpr uint32_t kShortRowCols = 32;  // rows up to this length: k_csr_compact derives its row ends from a mask
@@ -135,9 +148,9 @@ inline uint32_t grid_for(uint64_t n, uint32_t per_block, uint32_t cap) {
 }
 
 // Index of the last of the counters behind L.chunk_words that a call starts from zero, and the tile counts among them.
-inline uint32_t counter_words(const Layout &L) { return L.nc_max + L.n_pub + L.n_blk; }
+inline uint32_t counter_words(const Layout &L) { return L.tc_off + L.n_blk - 1; }
 inline uint32_t *tile_counts_of(const Layout &L, uint8_t *ws) {
-  return L.n_blk ? (uint32_t *)(ws + L.chunk_words) + L.nc_max + 1 + L.n_pub : nullptr;
+  return L.n_blk ? (uint32_t *)(ws + L.chunk_words) + L.tc_off : nullptr;
 }
 
 inline uint32_t *grp_counts_of(const Layout &L, uint8_t *ws) {  // nonzeros per group of tiles (one work-group step of k_quant_hist)
@@ -262,35 +275,58 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     const uint4 *tab4 = (const uint4 *)(ws + L.enc_tab4);
     const bool lds_tab = lds_hist;
     const bool mul24 = p.freq_bits >= 8;  // then floor(s/f) < 2^24 and both products fit the 24-bit multiplier
-#define ENC_LAUNCH2(SRCT, SPLV, TABV, M24, FUSEV)                                                                 \
-  PROF_LAUNCH(KID_ENCODE, (k_encode<SRCT, SPLV, TABV, M24, FUSEV>), dim3(L.nc_max * groups_e), dim3(kWG), lds_e, st, \
-              src, tab, tab4, A, p.freq_bits, S, p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups_e,      \
-              cw + L.nc_max + 1, d_stream, (uint64_t)cap, d_stream_bytes, wide_e)
-#define ENC_LAUNCH(SRCT, SPLV, TABV)                                                                              \
-  do {                                                                                                            \
-    const uint32_t groups_e = (S + kWG * SPLV - 1) / (kWG * SPLV);                                                \
-    size_t lds_e = (TABV == 2 ? A * 16 : (TABV == 1 ? A * 8 : 0)) + kRingStride * kWG * SPLV + 64;                         \
-    const int wide_e = SPLV == 1 && S % 64 == 0 && (csr || aligned_to(d_sym, 16));                                \
-    if (wide_e) lds_e += csr ? (kWG / 64) * 2 * kStageRows2 * 128 + 16 : (kWG / 64) * 2 * kStageRows * 64;        \
-    if (fused_gather && lds_e < kEncTileBytes) lds_e = kEncTileBytes;                                             \
-    if (mul24) {                                                                                                  \
-      if (fused_gather) ENC_LAUNCH2(SRCT, SPLV, TABV, true, true);                                                \
-      else ENC_LAUNCH2(SRCT, SPLV, TABV, true, false);                                                            \
-    } else {                                                                                                      \
-      if (fused_gather) ENC_LAUNCH2(SRCT, SPLV, TABV, false, true);                                               \
-      else ENC_LAUNCH2(SRCT, SPLV, TABV, false, false);                                                           \
-    }                                                                                                             \
+#define ENC_LAUNCH2(SRCT, TABV, M24, FUSEV)                                                                        \
+  do {                                                                                                              \
+    auto kfn = k_encode<SRCT, TABV, M24, FUSEV>;                                                                    \
+    /* once per instantiation: allow dynamic LDS beyond the default 64 KB (large alphabets) */                     \
+    static const hipError_t attr_rc =                                                                               \
+        hipFuncSetAttribute((const void *)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);             \
+    if (lds_e > 64 * 1024 && attr_rc != hipSuccess) return RANS_ERR_HIP;                                            \
+    PROF_LAUNCH(KID_ENCODE, kfn, dim3(n_wg_e), dim3(kWG), lds_e, st, src, tab, tab4, A, p.freq_bits, S,             \
+                p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups, cw + L.nc_max + 1,                  \
+                (unsigned long long *)(cw + L.acc_off), d_stream, (uint64_t)cap, d_stream_bytes, wide_e, rw_e,      \
+                wgs_per_class_e, n_classes_e);                                                                      \
   } while (0)
-    // One stream per lane: the hardware interleaves waves better than the compiler interleaves
-    // several streams inside a lane, and the stream count rarely exceeds what the chip can hold.
+#define ENC_LAUNCH(SRCT, TABV)                                                                                      \
+  do {                                                                                                              \
+    const int wide_e = S % 64 == 0 && (csr || aligned_to(d_sym, 16));                                               \
+    /* LDS behind the word areas: table, reduction scratch, then the symbol stage, which the placement reuses   */ \
+    /* for three tables of kWG words                                                                             */ \
+    size_t stage_e = wide_e ? (csr ? (kWG / 64) * 2 * kStageRows2 * 128 + 16 : (kWG / 64) * kStageRows * 64) : 0;   \
+    if (stage_e < 3 * kWG * 4) stage_e = 3 * kWG * 4;                                                               \
+    const size_t rest_e = (TABV == 2 ? A * 16 : (TABV == 1 ? A * 8 : 0)) + 64 + stage_e;                            \
+    /* slots per stream: what a stream can need (capw), as far as the LDS goes when every work-group of the grid */ \
+    /* (up to four per compute unit) is to be resident at once                                                  */ \
+    const uint32_t n_wg_e = L.nc_max * groups;                                                                      \
+    const uint32_t n_cu_e = compute_units();                                                                        \
+    uint32_t want_cu_e = n_cu_e ? (n_wg_e + n_cu_e - 1) / n_cu_e : 4;                                               \
+    want_cu_e = want_cu_e < 1 ? 1 : (want_cu_e > 4 ? 4 : want_cu_e);                                                \
+    const size_t budget_e = (160 * 1024) / want_cu_e;                                                               \
+    uint32_t rw_e = L.capw < 16 ? 16 : (L.capw > 252 ? 252 : (L.capw + 3) & ~3u);                                   \
+    while (rw_e > 16 && kEncGuard + enc_area_stride(rw_e) * kWG + rest_e > budget_e) rw_e -= 4;                     \
+    const size_t lds_e = kEncGuard + enc_area_stride(rw_e) * kWG + rest_e;                                          \
+    /* work-groups per compute unit when the whole grid is resident at once (see the kernel's timed wait) */       \
+    size_t per_cu_e = (160 * 1024) / lds_e;                                                                         \
+    per_cu_e = per_cu_e > 8 ? 8 : per_cu_e;                                                                         \
+    const bool resident_e = n_cu_e && per_cu_e && n_wg_e <= n_cu_e * per_cu_e;                                      \
+    const uint32_t wgs_per_class_e = resident_e ? n_cu_e : n_wg_e;                                                  \
+    const uint32_t n_classes_e = resident_e ? (n_wg_e + n_cu_e - 1) / n_cu_e : 1;                                   \
+    if (mul24) {                                                                                                    \
+      if (fused_gather) ENC_LAUNCH2(SRCT, TABV, true, true);                                                        \
+      else ENC_LAUNCH2(SRCT, TABV, true, false);                                                                    \
+    } else {                                                                                                        \
+      if (fused_gather) ENC_LAUNCH2(SRCT, TABV, false, true);                                                       \
+      else ENC_LAUNCH2(SRCT, TABV, false, false);                                                                   \
+    }                                                                                                               \
+  } while (0)
     if (csr) {
       SrcCsr src{ws + L.v, (const uint16_t *)(ws + L.c), (const uint16_t *)(ws + L.r), 0};
-      if (A <= kEncTab16MaxA) ENC_LAUNCH(SrcCsr, 1, 2);
-      else if (lds_tab) ENC_LAUNCH(SrcCsr, 1, 1);
-      else ENC_LAUNCH(SrcCsr, 1, 0);
+      if (A <= kEncTab16MaxA) ENC_LAUNCH(SrcCsr, 2);
+      else if (lds_tab) ENC_LAUNCH(SrcCsr, 1);
+      else ENC_LAUNCH(SrcCsr, 0);
     } else {
       SrcDense src{d_sym};
-      ENC_LAUNCH(SrcDense, 1, 2);
+      ENC_LAUNCH(SrcDense, 2);
     }
 #undef ENC_LAUNCH
 #undef ENC_LAUNCH2

@@ -146,7 +146,6 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
     uint32_t rw, uint32_t wgs_per_class, uint32_t n_classes) {
   extern __shared__ __align__(16) uint32_t l_mem[];  // the only LDS of this kernel, so the word areas start at offset kEncGuard
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
-  const unsigned long long t_begin = (FUSE && n_classes > 1) ? wall_clock64() : 0ull;
   // every exit publishes a total (0 words), or the work-groups behind this one would wait for it
   auto bail = [&]() {
     if (FUSE && threadIdx.x == 0) {
@@ -245,6 +244,30 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
   auto make_room = [&]() {
     if (wp < colb + 2 * (kEncAhead - 1)) spill(false);
   };
+  // The hardware issues a compute unit's oldest waves first: of several work-groups on a unit the first finishes
+  // well before the last, which then runs alone and cannot fill the unit; and a work-group that polls for the
+  // others' totals while its neighbours still code delays every vector load of the unit that is issued behind
+  // the poll, i.e. their symbols.  Work-groups are placed round robin, so blockIdx.x / wgs_per_class tells the
+  // work-groups of a unit apart.  With four of them per unit and long streams each takes every wave priority in
+  // turn, sixteen rows at a time, and all finish at about the same time.  Otherwise (two or three per unit, or
+  // streams of fewer than 128 rows, where the priorities did not even the progress out) an early one instead
+  // sleeps before its first poll, without a single load, for about as long as the later ones still need: a
+  // share of its own coding time per work-group behind it - an estimate that only decides when the polling
+  // starts, not what is computed.  (Measured on c5a, 256 rows: 48 us with the sleep, 45 us with the priorities;
+  // c2 DENSE, 98 rows: 24.5 us with the sleep, 30 us with the priorities.)
+  const uint32_t prio_class = n_classes > 1 ? blockIdx.x / wgs_per_class : 0;  // < n_classes by the host's choice
+  const bool prio_rotate = n_classes == 4 && chunk_len / S >= 128;
+  const bool timed_wait = n_classes > 1 && !prio_rotate;
+  const unsigned long long t_begin = (FUSE && timed_wait) ? wall_clock64() : 0ull;
+  auto rotate_prio = [&](uint64_t t) {
+    if (prio_rotate) {
+      const uint32_t pr = (prio_class + ((uint32_t)t >> 4)) & 3u;
+      if (pr == 0) __builtin_amdgcn_s_setprio(0);
+      else if (pr == 1) __builtin_amdgcn_s_setprio(1);
+      else if (pr == 2) __builtin_amdgcn_s_setprio(2);
+      else __builtin_amdgcn_s_setprio(3);
+    }
+  };
   // The coding loop, for one of the two table forms (an entry is {m, f, F, cmpl} with the meaning of
   // that form: EXACT {mx, lim1, Fx | sh << 16, 2^M - f}, else {floor(2^32/f), f, F, 2^M - f}).
   auto run = [&](auto exact_tag, auto wide_tag) {
@@ -332,17 +355,28 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
 #pragma unroll
         for (int u = 0; u < kEncAhead; u++) dst[u] = b[(kEncAhead - 1 - u) * 64];
       };
-      uint4 pend0 = make_uint4(0, 0, 0, 0), pend1 = pend0;  // pend0: the tile the next batch lies in (or the one below, once it is parked whole)
+      // pend[0]: the tile the next batch lies in (or the one below, once it is parked whole); pend[i]: i tiles below
+      constexpr int kPend = 2;
+      uint4 pend[kPend];
+#pragma unroll
+      for (int i = 0; i < kPend; i++) pend[i] = make_uint4(0, 0, 0, 0);
+      auto advance = [&](uint64_t lowest_lo_plus16) {  // pend[0] is used up: the others move up, a new tile is requested below them
+#pragma unroll
+        for (int i = 0; i + 1 < kPend; i++) pend[i] = pend[i + 1];
+        pend[kPend - 1] = make_uint4(0, 0, 0, 0);
+        if (lowest_lo_plus16 >= kStageRows) pend[kPend - 1] = request(lowest_lo_plus16 - kStageRows, lowest_lo_plus16);
+      };
       if (t) {
         const uint64_t t_lo = (t - 1) & ~(uint64_t)(kStageRows - 1);
-        pend0 = request(t_lo, t);
-        if (t_lo >= kStageRows) pend1 = request(t_lo - kStageRows, t_lo);
+        pend[0] = request(t_lo, t);
+#pragma unroll
+        for (int i = 1; i < kPend; i++)
+          if (t_lo >= (uint64_t)i * kStageRows) pend[i] = request(t_lo - (uint64_t)i * kStageRows, t_lo - (uint64_t)(i - 1) * kStageRows);
         if ((t & 15) == 8) {  // the first batch is the tile's lower half, its upper half lies past the end
-          park_half(pend0, 0);
-          pend0 = pend1;
-          if (t_lo >= 2 * kStageRows) pend1 = request(t_lo - 2 * kStageRows, t_lo - kStageRows);
+          park_half(pend[0], 0);
+          advance(t_lo >= (uint64_t)(kPend - 1) * kStageRows ? t_lo - (uint64_t)(kPend - 1) * kStageRows : 0);
         } else {
-          park_half(pend0, 1);
+          park_half(pend[0], 1);
         }
         read_rows(nxt, t);
         prime();
@@ -351,13 +385,15 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
 #pragma unroll
         for (int u = 0; u < kEncAhead; u++) cur[u] = nxt[u];
         t -= kEncAhead;
+        rotate_prio(t);
         if (t) {  // the next batch is rows t-8 .. t-1
           if ((t & 15) == 0) {
-            park_half(pend0, 1);  // upper half of the tile below the one just finished
+            park_half(pend[0], 1);  // upper half of the tile below the one just finished
           } else {
-            park_half(pend0, 0);  // lower half of the same tile; with it the tile is parked whole
-            pend0 = pend1;
-            if (t >= 8 + 2 * kStageRows) pend1 = request(t - 8 - 2 * kStageRows, t - 8 - kStageRows);
+            park_half(pend[0], 0);  // lower half of the same tile; with it the tile is parked whole
+            // pend[0] was the tile [t-8, t+8); the lowest pending one is kPend - 1 tiles below it
+            const uint64_t low = t - 8;  // start of the used-up tile
+            advance(low >= (uint64_t)(kPend - 1) * kStageRows ? low - (uint64_t)(kPend - 1) * kStageRows : 0);
           }
           read_rows(nxt, t);
         }
@@ -438,6 +474,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
 #pragma unroll
         for (int u = 0; u < kEncAhead; u++) cur[u] = nxt[u];
         t -= kEncAhead;
+        rotate_prio(t);
         if (t) {
           if ((t & (kStageRows2 - 1)) == 0) {  // the next rows belong to the tile below: it has arrived by now
             park(t - kStageRows2, t_req_top);
@@ -463,6 +500,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
 #pragma unroll
         for (int u = 0; u < kEncAhead; u++) cur[u] = nxt[u];
         t -= kEncAhead;
+        rotate_prio(t);
         if (t) fetch_rows(nxt, t);
         batch();
       }
@@ -487,6 +525,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
       }
     }
   }
+  if (prio_rotate) __builtin_amdgcn_s_setprio(0);
   if (!FUSE && live) spill(true);  // k_gather finds every word in scratch
   const uint32_t n_lds = (FUSE && live) ? words_in_area() : 0;                     // words still in the area
   const uint32_t nbg = live ? (uint32_t)((gp - g0) / (kWG * 8)) : 0;               // blocks in scratch
@@ -543,16 +582,9 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
         if (i < n_spilled) pre_q[u] = *block_src(i, &pre_dst[u]);
       }
     }
-    // Polling for the totals of the others delays every vector load of the compute unit that is issued behind
-    // it, i.e. the symbols of the work-groups that still code there.  Work-groups are placed round robin and the
-    // hardware favours a unit's oldest waves, so with several work-groups per unit the first ones finish well
-    // before the last: such a work-group first sleeps, without a single load, for about as long as the later
-    // ones still need (a share of its own coding time per work-group behind it - an estimate that only decides
-    // when the polling starts, not what is computed).
-    if (n_classes > 1 && threadIdx.x < 64) {
-      const uint32_t cls = blockIdx.x / wgs_per_class;  // < n_classes by the host's choice of wgs_per_class
+    if (timed_wait && threadIdx.x < 64) {  // the sleep before the first poll (see above)
       const unsigned long long now = wall_clock64();
-      const unsigned long long until = now + ((now - t_begin) * (n_classes - 1 - cls) * 12) / 100;
+      const unsigned long long until = now + ((now - t_begin) * (n_classes - 1 - prio_class) * 12) / 100;
       while (wall_clock64() < until) __builtin_amdgcn_s_sleep(32);
     }
     // Totals of what lies before this work-group's words: every earlier chunk (its size gives the chunk's

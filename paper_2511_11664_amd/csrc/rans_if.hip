@@ -305,12 +305,13 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     uint32_t rw_e = L.capw < 16 ? 16 : (L.capw > 252 ? 252 : (L.capw + 3) & ~3u);                                   \
     while (rw_e > 16 && kEncGuard + enc_area_stride(rw_e) * kWG + rest_e > budget_e) rw_e -= 4;                     \
     const size_t lds_e = kEncGuard + enc_area_stride(rw_e) * kWG + rest_e;                                          \
-    /* work-groups per compute unit when the whole grid is resident at once (see the kernel's timed wait) */       \
+    /* work-groups per compute unit when the whole grid is resident at once (see the kernel on wave priorities) */ \
     size_t per_cu_e = (160 * 1024) / lds_e;                                                                         \
     per_cu_e = per_cu_e > 8 ? 8 : per_cu_e;                                                                         \
     const bool resident_e = n_cu_e && per_cu_e && n_wg_e <= n_cu_e * per_cu_e;                                      \
     const uint32_t wgs_per_class_e = resident_e ? n_cu_e : n_wg_e;                                                  \
-    const uint32_t n_classes_e = resident_e ? (n_wg_e + n_cu_e - 1) / n_cu_e : 1;                                   \
+    uint32_t n_classes_e = resident_e ? (n_wg_e + n_cu_e - 1) / n_cu_e : 1;                                         \
+    if (n_classes_e > 4) n_classes_e = 1; /* there are four wave priorities */                                      \
     if (mul24) {                                                                                                    \
       if (fused_gather) ENC_LAUNCH2(SRCT, TABV, true, true);                                                        \
       else ENC_LAUNCH2(SRCT, TABV, true, false);                                                                    \

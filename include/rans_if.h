@@ -205,6 +205,16 @@ int rans_last_status(void *d_ws, void *stream);
 
 const char *rans_strerror(int code);
 
+/* Diagnostic (not part of the paper's method): runs, on the device, the two
+ * division routines with which the frequency-table kernels replace integer
+ * division (Sec. 3.2's normalisation and the encoder's reciprocal multipliers of
+ * Eq. 2) against the integer division they stand for: floor(2^(32+k) / d) for
+ * every d in 1 .. 65535 with 2^k <= d < 2^(k+1), and floor(n / d) for n_random
+ * pseudo-random pairs with a quotient below 2^17.  *d_mismatches (device, 4
+ * bytes, written by the call) receives the number of disagreements: 0 on a
+ * correct build.  Enqueued on `stream`. */
+int rans_selftest_divide(uint32_t *d_mismatches, uint64_t n_random, void *stream);
+
 /* Measurement aid for benchmarks (not part of the paper's method): per-kernel
  * launch durations.  rans_profile_enable(mask) makes every later launch of the
  * kernels whose bit (1 << kernel_id) is set record a pair of HIP events on its

@@ -75,7 +75,7 @@ NOALLOC_WS_BYTES = 32 << 20
 
 EXPORTS = ("rans_workspace_bytes", "rans_quantize", "rans_encode", "rans_decode", "rans_dequantize",
            "rans_compress", "rans_compress_noalloc", "rans_decompress", "rans_peek_header", "rans_last_status",
-           "rans_search_workspace_bytes", "rans_search_reshape",
+           "rans_search_workspace_bytes", "rans_search_reshape", "rans_selftest_divide",
            "rans_profile_enable", "rans_profile_reset", "rans_profile_read",
            "rans_strerror", "rans_profile_kernel_name")
 
@@ -103,6 +103,7 @@ def lib() -> C.CDLL:
         L.rans_last_status.argtypes = [vp, vp]
         L.rans_search_workspace_bytes.argtypes = [u64, u32, C.POINTER(sz)]
         L.rans_search_reshape.argtypes = [vp, u64, u32, vp, vp, sz, vp]
+        L.rans_selftest_divide.argtypes = [vp, u64, vp]
         L.rans_strerror.argtypes = [C.c_int]
         L.rans_strerror.restype = C.c_char_p
         L.rans_profile_enable.argtypes = [u64, u32]
@@ -198,6 +199,11 @@ def rans_peek_header(h_bytes: bytes):
 
 def rans_last_status(d_ws) -> int:
     return lib().rans_last_status(_p(d_ws), _stream())
+
+
+def rans_selftest_divide(d_mismatches, n_random: int) -> int:
+    """d_mismatches: a device tensor of one 32-bit word."""
+    return lib().rans_selftest_divide(_p(d_mismatches), n_random, _stream())
 
 
 def rans_search_workspace_bytes(n_elems: int, q_bits: int):

@@ -25,13 +25,13 @@ struct Ctl {
   int32_t status;
   uint32_t status_seq;
   uint32_t last_seq;                     // number of the latest call enqueued on this workspace
-  uint32_t enc_exact;                    // every entry of the division-free encoder table is exact (see k_normalize)
+  uint32_t enc_exact;                    // every entry of the division-free encoder table is exact (see emit_entries)
   float x_min, x_max, scale, zero_point; // Eq. 6
   uint64_t len_d;                        // l_D of Eq. 7
   uint64_t payload_off, dir_off;         // container section offsets
   uint64_t total_bytes;
   uint32_t nnz, n_chunks;
-  uint32_t hist_done;                    // work-groups of the histogram kernel that have added their counts
+  uint32_t hist_done;                    // not used (kept for the layout)
   uint32_t pad0;
   // First data-dependent error of ANY call on this workspace since the host last read it (rans_last_status):
   // kStickyTag in the upper 48 bits, minus the error code in the lower 16 (0 = none).  A word without the tag
@@ -173,6 +173,13 @@ __device__ __forceinline__ int get_status(const CtlRef &ctl) {
   const unsigned long long v = *(volatile const unsigned long long *)&ctl.p->status;
   return (uint32_t)(v >> 32) == ctl.seq ? (int)(uint32_t)v : 0;
 }
+// The same at the start of a kernel, where the errors of interest are those of the kernels before it: they
+// ended before this one began, so an ordinary cached load sees them, and it returns several times sooner than
+// the load above, which goes past the caches.
+__device__ __forceinline__ int status_at_entry(const CtlRef &ctl) {
+  const unsigned long long v = *(const unsigned long long *)&ctl.p->status;  // {status, status_seq}
+  return (uint32_t)(v >> 32) == ctl.seq ? (int)(uint32_t)v : 0;
+}
 // Records `code` as the error of call ctl.seq unless that call already has one, and as the workspace's
 // sticky error unless an earlier one is still waiting to be read.
 __device__ __forceinline__ void set_status(const CtlRef &ctl, int code) {
@@ -198,17 +205,17 @@ __device__ __forceinline__ void set_status(const CtlRef &ctl, int code) {
   }
 }
 
-// The same as ONE value for a whole work-group (every thread must call it).  Another work-group of the
-// running kernel may record an error at any moment; lanes that each read the word themselves could then
-// disagree, and the ones that carry on would meet barriers and LDS slots the others never reach.
+// The status at entry as ONE value for a whole work-group (every thread must call it).  Another work-group
+// of the running kernel may record an error at any moment; lanes that each read the word themselves could
+// then disagree, and the ones that carry on would meet barriers and LDS slots the others never reach.
 __device__ __forceinline__ bool group_has_status(const CtlRef &ctl) {
-  return __syncthreads_or(get_status(ctl) != 0) != 0;
+  return __syncthreads_or(status_at_entry(ctl) != 0) != 0;
 }
 
 // The same through an LDS word of the caller's (for kernels whose LDS layout must not gain a static variable,
 // which the reduction above may bring in).  The word is free again when the function returns.
 __device__ __forceinline__ bool group_has_status(const CtlRef &ctl, uint32_t *lds_word) {
-  if (threadIdx.x == 0) *lds_word = get_status(ctl) != 0;
+  if (threadIdx.x == 0) *lds_word = status_at_entry(ctl) != 0;
   __syncthreads();
   const bool any = *lds_word != 0;
   __syncthreads();
@@ -277,7 +284,7 @@ __device__ __forceinline__ void lds_barrier() {
 
 // Sum / max over a work-group of NT threads; every thread receives the result.
 template <int NT>
-__device__ uint64_t block_sum64(uint64_t v, uint64_t *sh /* NT/64 entries */) {
+__device__ __forceinline__ uint64_t block_sum64(uint64_t v, uint64_t *sh /* NT/64 entries */) {
   v = lane63_64(wave_incl_scan64(v, [](uint64_t a, uint64_t b) { return a + b; }));
   __syncthreads();
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
@@ -288,7 +295,7 @@ __device__ uint64_t block_sum64(uint64_t v, uint64_t *sh /* NT/64 entries */) {
   return t;
 }
 template <int NT>
-__device__ uint64_t block_max64(uint64_t v, uint64_t *sh) {
+__device__ __forceinline__ uint64_t block_max64(uint64_t v, uint64_t *sh) {
   v = lane63_64(wave_incl_scan64(v, [](uint64_t a, uint64_t b) { return a > b ? a : b; }));
   __syncthreads();
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
@@ -301,7 +308,7 @@ __device__ uint64_t block_max64(uint64_t v, uint64_t *sh) {
 
 // Exclusive prefix sum over a work-group of NT threads; *total receives the sum.
 template <int NT>
-__device__ uint32_t block_excl_scan(uint32_t v, uint32_t *sh /* NT/64 entries */, uint32_t *total) {
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *sh /* NT/64 entries */, uint32_t *total) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const uint32_t inc = wave_incl_sum_scan(v);
   __syncthreads();

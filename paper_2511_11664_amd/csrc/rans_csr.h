@@ -144,14 +144,13 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
 // the same few LDS addresses; every value gets eight counters, one per lane residue, K + 1 slots apart.
 template <bool LDS_HIST, bool REP = false>
 __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint32_t N, uint16_t *r, uint32_t *cnt,
-                                                  uint32_t A, CtlRef ctl, int fold_norm, NormArgs na) {
+                                                  uint32_t A, CtlRef ctl, uint32_t n_cols, uint32_t n_rep) {
   extern __shared__ uint32_t hist[];
   if (LDS_HIST) {
     for (uint32_t a = threadIdx.x; a < A; a += kWG) hist[a] = 0;
     __syncthreads();
   }
-  uint32_t seen = 0;
-  const uint32_t n_val = na.p.cols + 1;  // REP: distinct row counts
+  const uint32_t n_val = n_cols + 1;  // REP: distinct row counts
   const uint32_t rep_off = REP ? (threadIdx.x & 7u) * n_val : 0u;
   // a lane takes four consecutive rows: one 16-byte load of their ends, one 8-byte store of their counts;
   // the loads of four such quads are in flight together
@@ -190,8 +189,7 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
     if (i + 4 >= N) {  // the quad with the last row (ends behind it repeat the last row's)
       const uint32_t e1 = e[4];
       ctl->nnz = e1;
-      // an exchange, for its returned value (see below): l_D has to be in place before this work-group's ticket
-      seen |= (uint32_t)__hip_atomic_exchange(&ctl->len_d, 2ull * e1 + N, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      ctl->len_d = 2ull * e1 + N;
     }
   };
   for (uint32_t q0 = blockIdx.x * (kWG * kU) + threadIdx.x; q0 < n_quads; q0 += gridDim.x * (kWG * kU)) {
@@ -203,10 +201,11 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
     for (int u = 0; u < kU; u++)
       if (q0 + u * kWG < n_quads) do_quad(q0 + u * kWG, e[u]);
   }
-  const bool hand_over = fold_norm || na.n_rep;  // the last work-group reads what the others added
+  // The partial histograms (one of n_rep, by work-group) are summed by the kernel that builds the table, which
+  // starts after this one has ended.
   if (LDS_HIST) {
     __syncthreads();
-    uint32_t *dst = cnt + (na.n_rep ? (size_t)(1 + blockIdx.x % na.n_rep) * A : 0);
+    uint32_t *dst = cnt + (n_rep ? (size_t)(1 + blockIdx.x % n_rep) * A : 0);
     for (uint32_t a = threadIdx.x; a < (REP ? n_val : A); a += kWG) {
       uint32_t t = 0;
       if (REP) {
@@ -215,43 +214,9 @@ __global__ __launch_bounds__(kWG) void k_csr_rows(const uint32_t *row_end, uint3
       } else {
         t = hist[a];
       }
-      // before a hand-over the additions return their old value: a returned value is the only proof that an
-      // addition has been performed before the work-group takes its ticket
-      if (t) {
-        if (hand_over) seen |= atomicAdd(&dst[a], t);
-        else atomicAdd(&dst[a], t);
-      }
+      if (t) atomicAdd(&dst[a], t);
     }
   }
-  if (!hand_over) return;
-  if (seen == 0xffffffffu) set_status(ctl, RANS_ERR_HIP);  // cannot happen (counts are below 2^31); keeps the values in use
-  // D's histogram is complete once every work-group has added its row counts: the last one to do so folds
-  // the partial histograms and, if asked to, builds the frequency table (the same hand-over as at the end of
-  // k_quant_hist).  It also reads len_d, which the work-group holding the last row exchanged in before the
-  // barrier ahead of its ticket.
-  __shared__ uint32_t s_ticket;
-  __shared__ uint32_t s_cnt[kNormWaveA];
-  __syncthreads();
-  if (threadIdx.x == 0) s_ticket = __hip_atomic_fetch_add(&ctl->hist_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __syncthreads();
-  if (s_ticket != gridDim.x - 1) return;
-  if (na.n_rep) {  // all loads of a lane in flight together
-    for (uint32_t a0 = threadIdx.x; a0 < A; a0 += kWG) {
-      uint32_t part_c[kCntRep + 1];
-#pragma unroll
-      for (uint32_t k = 0; k <= kCntRep; k++)
-        part_c[k] = k <= na.n_rep ? __hip_atomic_load(cnt + (size_t)k * A + a0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
-      uint32_t sum = 0;
-#pragma unroll
-      for (uint32_t k = 0; k <= kCntRep; k++) sum += part_c[k];
-      if (!fold_norm) cnt[a0] = sum;  // for k_normalize
-      if (a0 < kNormWaveA) s_cnt[a0] = sum;
-    }
-    lds_barrier();
-    na.n_rep = 0;
-    if (A <= kNormWaveA) na.lds_cnt = s_cnt;
-  }
-  if (fold_norm && threadIdx.x < 64) normalize_wave(ctl, na);
 }
 
 }  // namespace

@@ -138,12 +138,15 @@ __device__ __forceinline__ uint64_t wait_chunk(const unsigned long long *acc, ui
   return ~0ull;
 }
 
+// Sixteen bytes at an address that is only 2-byte aligned, moved to or from registers in one access.
+struct __attribute__((packed, aligned(2))) Block16 { uint32_t x, y, z, w; };
+
 template <class Src, int TAB, bool MUL24, bool FUSE>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k_encode(
     Src src, const uint2 *g_tab, const uint4 *g_tab4, uint32_t A, uint32_t M, uint32_t S, uint32_t cs, CtlRef ctl,
     uint16_t *scratch, uint32_t capw, uint32_t *st_out, uint32_t *nw_out, uint32_t *chunk_words, uint32_t groups,
     uint32_t *wg_pub, unsigned long long *chunk_acc, uint8_t *out, uint64_t cap, uint64_t *d_stream_bytes, int wide,
-    uint32_t rw, uint32_t wgs_per_class, uint32_t n_classes) {
+    uint32_t rw, uint32_t wgs_per_class, uint32_t n_classes, int build_tab, NormArgs na) {
   extern __shared__ __align__(16) uint32_t l_mem[];  // the only LDS of this kernel, so the word areas start at offset kEncGuard
   const uint32_t k = blockIdx.x / groups, g = blockIdx.x % groups;
   // every exit publishes a total (0 words), or the work-groups behind this one would wait for it
@@ -158,19 +161,6 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
     bail();
     return;
   }
-  const uint32_t nc = ctl->n_chunks;
-  if (k >= nc) {
-    if (FUSE && nc == 0 && blockIdx.x == 0 && threadIdx.x == 0) {  // empty D: only the directory's single entry
-      uint8_t *dir0 = out + ctl->dir_off;
-      st32(dir0, 0u);
-      st32(dir0 + 4, 0u);
-      ctl->total_bytes = ctl->payload_off;
-      if (d_stream_bytes) *d_stream_bytes = ctl->payload_off;
-    }
-    bail();
-    return;
-  }
-  src.init(ctl);
   const uint32_t sh_lim = 32 - M, totalM = 1u << M;
   // LDS: [guard][word areas][table][reduction scratch][symbol stage].  The areas come first so that a slot
   // address is the lane's fixed base plus twice the slot number; what follows them is reused as the tile of
@@ -179,23 +169,92 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
   const uint32_t areas_end = kEncGuard + stride * kWG;  // a multiple of 16
   uint32_t *l_tab = l_mem + areas_end / 4;
   uint32_t *sh = l_tab + (TAB == 2 ? A * 4 : (TAB == 1 ? A * 2 : 0));  // 4 + 8 words for the final reductions
-  // TAB == 2 has two forms of the table: the division-free one when every entry of it is exact for
-  // this frequency table (the common case), else {floor(2^32/f), f, F, 2^M - f} with a correction step.
-  const bool exact = TAB == 2 && ctl->enc_exact != 0;
-  if (TAB == 1) {
-    for (uint32_t a = threadIdx.x; a < A; a += kWG) ((uint2 *)l_tab)[a] = g_tab[a];
-  } else if (TAB == 2) {
-    if (exact) {
-      for (uint32_t a = threadIdx.x; a < A; a += kWG) ((uint4 *)l_tab)[a] = g_tab4[a];
-    } else {
+  // Frequency table (Sec. 3.2's normalisation) and container geometry.  build_tab (alphabets that one wave
+  // can normalise): D's histogram is complete, because the kernels that counted have ended, and every
+  // work-group derives the same table from it for itself, straight into its LDS.  That is about three
+  // microseconds of one wave per work-group; a hand-over from the last counting work-group, or a launch of
+  // its own for the table, costs the call as much or more and needs ordering between work-groups that this
+  // does not.  The first work-group also writes the header and the table of the container.  Otherwise
+  // k_normalize has left tables and geometry in memory.
+  uint32_t nc, exact_tab;
+  uint64_t len, dir_off, payload_off;
+  if (TAB == 2 && build_tab) {
+    uint2 *const l_tab8 = (uint2 *)(sh + 16);  // {floor(2^32/f), f | F << 16}: in the stage, which is free until the coding
+    uint32_t *const l_cnt = (uint32_t *)(l_tab8 + A);
+    {  // the counts, partial histograms summed, with all of a lane's loads in flight together
+      constexpr uint32_t kParts = kCntRep + 1;  // n_rep is 0 or kCntRep
       for (uint32_t a = threadIdx.x; a < A; a += kWG) {
-        uint2 q = g_tab[a];
+        uint32_t c[kParts];
+#pragma unroll
+        for (uint32_t q = 0; q < kParts; q++) c[q] = q <= na.n_rep ? na.cnt[(size_t)q * A + a] : 0u;
+        uint32_t t = 0;
+#pragma unroll
+        for (uint32_t q = 0; q < kParts; q++) t += c[q];
+        l_cnt[a] = t;
+      }
+      __syncthreads();
+    }
+    if (threadIdx.x < 64) {
+      NormArgs nl = na;  // a copy in registers: the argument itself cannot be changed in place
+      nl.lds_cnt = l_cnt;
+      nl.enc_tab = l_tab8;
+      nl.enc_tab4 = (uint4 *)l_tab;
+      nl.quiet = blockIdx.x != 0;
+      nl.entry_checked = 1;
+      const NormResult r = normalize_wave(ctl, nl);
+      if (threadIdx.x == 0) {
+        sh[0] = r.ok; sh[1] = r.exact; sh[2] = r.n_chunks;
+        *(uint64_t *)(sh + 4) = r.len_d; *(uint64_t *)(sh + 6) = r.dir_off; *(uint64_t *)(sh + 8) = r.payload_off;
+      }
+    }
+    __syncthreads();
+    const uint32_t ok = sh[0];
+    exact_tab = sh[1]; nc = sh[2];
+    len = *(const uint64_t *)(sh + 4); dir_off = *(const uint64_t *)(sh + 6); payload_off = *(const uint64_t *)(sh + 8);
+    if (!ok) {
+      if (FUSE && blockIdx.x == 0 && threadIdx.x == 0 && d_stream_bytes) *d_stream_bytes = 0;
+      bail();
+      return;
+    }
+    if (!exact_tab) {
+      for (uint32_t a = threadIdx.x; a < A; a += kWG) {
+        const uint2 q = l_tab8[a];
         ((uint4 *)l_tab)[a] = make_uint4(q.x, q.y & 0xffffu, q.y >> 16, totalM - (q.y & 0xffffu));
       }
     }
+    __syncthreads();  // the table is complete; sh and the stage may be written again
+  } else {
+    nc = ctl->n_chunks; len = ctl->len_d; dir_off = ctl->dir_off; payload_off = ctl->payload_off;
+    exact_tab = TAB == 2 && ctl->enc_exact != 0;
+    // TAB == 2 has two forms of the table: the division-free one when every entry of it is exact for
+    // this frequency table (the common case), else {floor(2^32/f), f, F, 2^M - f} with a correction step.
+    if (TAB == 1) {
+      for (uint32_t a = threadIdx.x; a < A; a += kWG) ((uint2 *)l_tab)[a] = g_tab[a];
+    } else if (TAB == 2) {
+      if (exact_tab) {
+        for (uint32_t a = threadIdx.x; a < A; a += kWG) ((uint4 *)l_tab)[a] = g_tab4[a];
+      } else {
+        for (uint32_t a = threadIdx.x; a < A; a += kWG) {
+          uint2 q = g_tab[a];
+          ((uint4 *)l_tab)[a] = make_uint4(q.x, q.y & 0xffffu, q.y >> 16, totalM - (q.y & 0xffffu));
+        }
+      }
+    }
+    if (TAB != 0) __syncthreads();
   }
-  if (TAB != 0) __syncthreads();
-  const uint64_t len = ctl->len_d;
+  const bool exact = exact_tab != 0;
+  if (k >= nc) {
+    if (FUSE && nc == 0 && blockIdx.x == 0 && threadIdx.x == 0) {  // empty D: only the directory's single entry
+      uint8_t *dir0 = out + dir_off;
+      st32(dir0, 0u);
+      st32(dir0 + 4, 0u);
+      ctl->total_bytes = payload_off;
+      if (d_stream_bytes) *d_stream_bytes = payload_off;
+    }
+    bail();
+    return;
+  }
+  src.init(ctl);
   const uint64_t chunk_len = cs ? cs : len;
   const uint64_t base = (uint64_t)k * chunk_len;
   const uint64_t n_here = len - base < chunk_len ? len - base : chunk_len;
@@ -420,8 +479,9 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
             pend[0] = *(const uint4 *)(src.v_ptr() + i);
           } else if (i >= nnz && (i + 16 <= 2 * nnz || (i >= 2 * nnz && i + 16 <= len))) {
             const uint16_t *q = i < 2 * nnz ? src.c_ptr() + (i - nnz) : src.r_ptr() + (i - 2 * nnz);
-            __builtin_memcpy(&pend[0], q, 16);
-            __builtin_memcpy(&pend[1], q + 8, 16);
+            const Block16 b0 = *(const Block16 *)q, b1 = *(const Block16 *)(q + 8);
+            pend[0] = make_uint4(b0.x, b0.y, b0.z, b0.w);
+            pend[1] = make_uint4(b1.x, b1.y, b1.z, b1.w);
           } else {
             uint32_t w[8];
 #pragma unroll
@@ -623,8 +683,8 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
       }
       return;
     }
-    uint8_t *dir = out + ctl->dir_off;
-    const uint64_t my_end = ctl->payload_off + off + 8ull * S + 2 * (pre + tot);  // end of this group's words
+    uint8_t *dir = out + dir_off;
+    const uint64_t my_end = payload_off + off + 8ull * S + 2 * (pre + tot);  // end of this group's words
     const bool last_group = g == groups - 1;
     const uint64_t chunk_end = (my_end + 3) & ~3ull;  // meaningful for the chunk's last group
     const bool fits = (last_group ? chunk_end : my_end) <= cap;
@@ -634,7 +694,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
         st32(dir + 8ull * k + 4, (uint32_t)(off >> 32));
       }
       if (k == nc - 1 && last_group) {
-        const uint64_t pay = chunk_end - ctl->payload_off;
+        const uint64_t pay = chunk_end - payload_off;
         st32(dir + 8ull * nc, (uint32_t)pay);
         st32(dir + 8ull * nc + 4, (uint32_t)(pay >> 32));
         ctl->total_bytes = chunk_end;
@@ -643,7 +703,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
       if (!fits) set_status(ctl, RANS_ERR_CAPACITY);
     }
     if (!fits) return;  // uniform
-    uint8_t *ck = out + ctl->payload_off + off;
+    uint8_t *ck = out + payload_off + off;
     if (live) {
       st32(ck + 4ull * j0, s);
       st32(ck + 4ull * S + 4ull * j0, nw);
@@ -684,7 +744,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
       }
     }
     // a spilled block to its place: 16 bytes to a 2-byte aligned address
-    auto put_block = [&](const uint4 &q, uint32_t dst_off) { __builtin_memcpy(dst + dst_off, &q, 16); };
+    auto put_block = [&](const uint4 &q, uint32_t dst_off) { *(Block16 *)(dst + dst_off) = Block16{q.x, q.y, q.z, q.w}; };
     if (n_spilled) {
 #pragma unroll
       for (int u = 0; u < kPre; u++)

@@ -162,11 +162,9 @@ NormArgs norm_args(const rans_params &p, const Layout &L, uint8_t *ws, uint64_t 
                   (uint4 *)(ws + L.enc_tab4), L.A, p, n, p.mode == RANS_MODE_CSR ? 0 : 1, d_stream, (uint64_t)cap};
 }
 
-// Extrema, Eq. 6, symbols and their histogram.  With `na` (dense mode, a container follows) the
-// histogram kernel also builds the frequency table and the container header.
+// Extrema, Eq. 6, symbols and their histogram.
 int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Layout &L, uint8_t *ws, uint8_t *d_sym,
-                    rans_qinfo *d_qinfo, hipStream_t st, uint32_t seq, const NormArgs *na,
-                    uint32_t *tiles_per_grp = nullptr) {
+                    rans_qinfo *d_qinfo, hipStream_t st, uint32_t seq, uint32_t *tiles_per_grp = nullptr) {
   const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   uint32_t *cnt = (uint32_t *)(ws + L.cnt);
   uint32_t *cw_ = (uint32_t *)(ws + L.chunk_words);
@@ -196,16 +194,14 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
   if (n) {
     uint32_t g = grid_for(n, QNT * V * kQIter, kQuantBlocks);
     int skip0 = p.mode == RANS_MODE_CSR;
-    const int fold = na != nullptr;
-    const NormArgs nav = na ? *na : NormArgs{};
     auto launch_qh = [&](auto csr_tag) {
       constexpr bool CSRV = decltype(csr_tag)::value;
       if (f16) {
-        if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws), grp_counts_of(L, ws));
-        else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws), grp_counts_of(L, ws));
+        if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, tile_counts_of(L, ws), grp_counts_of(L, ws));
+        else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<__half, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const __half *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, tile_counts_of(L, ws), grp_counts_of(L, ws));
       } else {
-        if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws), grp_counts_of(L, ws));
-        else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, fold, nav, tile_counts_of(L, ws), grp_counts_of(L, ws));
+        if (vec) PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, tile_counts_of(L, ws), grp_counts_of(L, ws));
+        else PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<float, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, (const float *)d_x, (uint32_t)n, ctl, p.q_bits, d_sym, cnt, skip0, part, n_part, d_qinfo, tile_counts_of(L, ws), grp_counts_of(L, ws));
       }
     };
     if (skip0) launch_qh(std::true_type{});
@@ -218,7 +214,7 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
 // Everything after the symbol histogram: CSR, table, coder, container.
 int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, const Layout &L, uint8_t *ws,
                        uint8_t *d_stream, size_t cap, uint64_t *d_stream_bytes, hipStream_t st, uint32_t seq,
-                       bool table_done, uint32_t tiles_per_grp) {
+                       uint32_t tiles_per_grp) {
   const CtlRef ctl{(Ctl *)(ws + L.ctl), seq};
   uint32_t *cnt = (uint32_t *)(ws + L.cnt);
   const bool csr = p.mode == RANS_MODE_CSR;
@@ -244,24 +240,25 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       LAUNCH_CHECK();
       uint32_t N = (uint32_t)p.rows;
       uint32_t g = (N + 16 * kWG - 1) / (16 * kWG);  // a lane takes 16 rows per step
-      // few work-groups: each ends with additions to the same few addresses and a ticket
+      // few work-groups: each ends with additions to the same few addresses
       const uint32_t g_cap = N > (1u << 20) ? 256u : 128u;
       g = g > g_cap ? g_cap : g;
-      const int fold = A <= kNormWaveA;  // one wave of the last work-group can build the table
-      const NormArgs na = norm_args(p, L, ws, n, d_stream, cap);
       if (lds_hist && 8ull * (p.cols + 1) <= A)  // short rows: eight counters per row count
-        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<true, true>), dim3(g), dim3(kWG), A * 4, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl, fold, na);
+        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<true, true>), dim3(g), dim3(kWG), A * 4, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl, (uint32_t)p.cols, L.cnt_rep);
       else if (lds_hist)
-        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<true>), dim3(g), dim3(kWG), A * 4, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl, fold, na);
+        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<true>), dim3(g), dim3(kWG), A * 4, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl, (uint32_t)p.cols, L.cnt_rep);
       else
-        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<false>), dim3(g), dim3(kWG), 0, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl, fold, na);
+        PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<false>), dim3(g), dim3(kWG), 0, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl, (uint32_t)p.cols, L.cnt_rep);
       LAUNCH_CHECK();
-      table_done = fold != 0;
     }
   }
-  if (!table_done) {  // else the histogram kernel has built the table
-    NormArgs na_k = norm_args(p, L, ws, n, d_stream, cap);
-    if (csr && n) na_k.n_rep = 0;  // k_csr_rows has folded the partial histograms
+  // D's histogram is complete here (the kernels that counted end before the next one starts).  Alphabets
+  // that one wave can normalise: every work-group of the encoder builds the table for itself; otherwise, and
+  // when there is nothing to encode, a kernel of its own does.
+  NormArgs na_k = norm_args(p, L, ws, n, d_stream, cap);
+  if (!(csr && n)) na_k.n_rep = 0;  // only k_csr_rows spreads its counts over partial histograms
+  const int enc_builds = A <= kNormWaveA && L.nc_max != 0;
+  if (!enc_builds) {
     PROF_LAUNCH(KID_NORMALIZE, k_normalize, dim3(1), dim3(kBig), 0, st, ctl, na_k);
     LAUNCH_CHECK();
   }
@@ -285,7 +282,7 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     PROF_LAUNCH(KID_ENCODE, kfn, dim3(n_wg_e), dim3(kWG), lds_e, st, src, tab, tab4, A, p.freq_bits, S,             \
                 p.chunk_syms, ctl, scratch, L.capw, st_arr, nw_arr, cw, groups, cw + L.nc_max + 1,                  \
                 (unsigned long long *)(cw + L.acc_off), d_stream, (uint64_t)cap, d_stream_bytes, wide_e, rw_e,      \
-                wgs_per_class_e, n_classes_e);                                                                      \
+                wgs_per_class_e, n_classes_e, (TABV == 2 && enc_builds) ? 1 : 0, na_k);                             \
   } while (0)
 #define ENC_LAUNCH(SRCT, TABV)                                                                                      \
   do {                                                                                                              \
@@ -294,6 +291,7 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
     /* for three tables of kWG words                                                                             */ \
     size_t stage_e = wide_e ? (csr ? (kWG / 64) * 2 * kStageRows2 * 128 + 16 : (kWG / 64) * kStageRows * 64) : 0;   \
     if (stage_e < 3 * kWG * 4) stage_e = 3 * kWG * 4;                                                               \
+    if (enc_builds && stage_e < A * 12) stage_e = A * 12; /* counts and the table's other form, while it is built */ \
     const size_t rest_e = (TABV == 2 ? A * 16 : (TABV == 1 ? A * 8 : 0)) + 64 + stage_e;                            \
     /* slots per stream: what a stream can need (capw), as far as the LDS goes when every work-group of the grid */ \
     /* (up to four per compute unit) is to be resident at once                                                  */ \
@@ -657,12 +655,10 @@ int compress_impl(const void *d_x, uint64_t n_elems, const rans_params *p, uint8
   hipStream_t st = (hipStream_t)stream;
   uint8_t *ws = (uint8_t *)d_ws;
   const uint32_t seq = next_seq();
-  const bool fold = n_elems && p->mode != RANS_MODE_CSR;  // dense: the histogram kernel also builds the table
-  const NormArgs na = norm_args(*p, L, ws, n_elems, d_stream, stream_cap);
   uint32_t tpg = 1;
-  rc = launch_quantize(d_x, n_elems, *p, L, ws, ws + L.sym, nullptr, st, seq, fold ? &na : nullptr, &tpg);
+  rc = launch_quantize(d_x, n_elems, *p, L, ws, ws + L.sym, nullptr, st, seq, &tpg);
   if (rc) return rc;
-  return launch_encode_tail(ws + L.sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq, fold, tpg);
+  return launch_encode_tail(ws + L.sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq, tpg);
 }
 
 // ---- the workspace of rans_compress_noalloc: a device array of the library itself
@@ -840,21 +836,19 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
     const bool vec = aligned_to(d_sym, 16);
     const uint32_t g = grid_for(n_elems, QNT * (vec ? 16 : 1) * kQIter, kQuantBlocks);
     const int skip0 = p->mode == RANS_MODE_CSR;
-    const int fold = !skip0;  // dense: the histogram is complete after this kernel, which then builds the table
-    const NormArgs na = norm_args(*p, L, ws, n_elems, d_stream, stream_cap);
     auto launch_qh = [&](auto csr_tag) {
       constexpr bool CSRV = decltype(csr_tag)::value;
       if (vec)
-        PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, fold, na, tile_counts_of(L, ws), grp_counts_of(L, ws));
+        PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, true, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, tile_counts_of(L, ws), grp_counts_of(L, ws));
       else
-        PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, fold, na, tile_counts_of(L, ws), grp_counts_of(L, ws));
+        PROF_LAUNCH(KID_QUANT_HIST, (k_quant_hist<uint8_t, false, QNT, CSRV>), dim3(g), dim3(QNT), 0, st, d_sym, (uint32_t)n_elems, ctl, p->q_bits, (uint8_t *)nullptr, (uint32_t *)(ws + L.cnt), skip0, (const MinMaxPart *)nullptr, 0u, (rans_qinfo *)nullptr, tile_counts_of(L, ws), grp_counts_of(L, ws));
     };
     if (skip0) launch_qh(std::true_type{});
     else launch_qh(std::false_type{});
     LAUNCH_CHECK();
   }
   return launch_encode_tail(d_sym, n_elems, *p, L, ws, d_stream, stream_cap, d_stream_bytes, st, seq,
-                            n_elems && p->mode != RANS_MODE_CSR, aligned_to(d_sym, 16) ? 16u : 1u);
+                            aligned_to(d_sym, 16) ? 16u : 1u);
 }
 
 int rans_compress(const void *d_x, uint64_t n_elems, const rans_params *p, uint8_t *d_stream, size_t stream_cap,
@@ -931,6 +925,18 @@ int rans_search_reshape(const uint8_t *d_sym, uint64_t n_elems, uint32_t q_bits,
   if (P.too_many) return RANS_ERR_ARG;
   if (ws_bytes < P.total) return RANS_ERR_WORKSPACE;
   return launch_search_reshape(d_sym, n_elems, q_bits, d_result, (uint8_t *)d_ws, P, (hipStream_t)stream);
+}
+
+int rans_selftest_divide(uint32_t *d_mismatches, uint64_t n_random, void *stream) {
+  if (!d_mismatches || !aligned_to(d_mismatches, 4)) return RANS_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  hipLaunchKernelGGL(k_selftest_clear, dim3(1), dim3(1), 0, st, d_mismatches);
+  LAUNCH_CHECK();
+  uint64_t g = (n_random + kWG - 1) / kWG;
+  g = g < 256 ? 256 : (g > 4096 ? 4096 : g);  // at least the 65536 divisors of the first check
+  hipLaunchKernelGGL(k_selftest_divide, dim3((uint32_t)g), dim3(kWG), 0, st, d_mismatches, n_random);
+  LAUNCH_CHECK();
+  return RANS_OK;
 }
 
 int rans_last_status(void *d_ws, void *stream) {

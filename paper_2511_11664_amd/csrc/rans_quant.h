@@ -244,17 +244,29 @@ struct NormArgs {
   // the control block's copy was then written by another of its work-groups and is not read).
   int mm_given;
   float x_min, x_max;
+  // Set by a kernel in which every work-group builds the table for itself (the encoder): only the first one
+  // writes the container's header and table and the control block's geometry; the others keep what they
+  // compute to themselves.  0: the caller is the table's only builder and writes everything.
+  int quiet;
+  int entry_checked;  // the caller has looked at the call's status already (set inside the calling kernel)
 };
-// Count of symbol a: the histogram's entry plus those of the partial histograms behind it.
+// What the table build leaves in the registers of the wave or work-group that ran it.
+struct NormResult {
+  uint32_t ok;  // 0: an error has been recorded, nothing below is valid
+  uint32_t exact;
+  uint32_t n_chunks;
+  uint64_t len_d, dir_off, payload_off;
+};
+// Count of symbol a: the histogram's entry plus those of the partial histograms behind it.  Plain loads: the
+// histogram was completed by kernels that ended before the one that reads it began.
 __device__ __forceinline__ uint32_t hist_count(const NormArgs &na, uint32_t a) {
   if (na.lds_cnt) return na.lds_cnt[a];
-  uint32_t c = __hip_atomic_load(na.cnt + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  for (uint32_t k = 1; k <= na.n_rep; k++)
-    c += __hip_atomic_load(na.cnt + (size_t)k * na.A + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  uint32_t c = na.cnt[a];
+  for (uint32_t k = 1; k <= na.n_rep; k++) c += na.cnt[(size_t)k * na.A + a];
   return c;
 }
 // Container header (fixed part) and the geometry the later kernels read from the control block.
-__device__ void write_header(const CtlRef &ctl, const NormArgs &na, uint64_t len_d, uint64_t n_chunks, uint64_t dir_off,
+__device__ __forceinline__ void write_header(const CtlRef &ctl, const NormArgs &na, uint64_t len_d, uint64_t n_chunks, uint64_t dir_off,
                              uint64_t payload_off) {
   const rans_params &p = na.p;
   uint8_t *out = na.out;
@@ -277,9 +289,56 @@ __device__ void write_header(const CtlRef &ctl, const NormArgs &na, uint64_t len
   for (uint32_t o = 68; o < kHdrBytes; o += 4) st32(out + o, 0u);
 }
 
-// Everything stored per symbol: f in the container, the encoder's two table entries.  m_floor is
-// floor(2^32 / f) (any value for f <= 1), div(two) returns floor(two / f) for two = 2^(32+k).  Returns
-// whether the division-free entry is inexact.
+// floor(n / d) for n < 2^48 and 1 <= d < 2^32 when that quotient is below 2^17, without an integer or
+// binary64 division (each a long dependent instruction sequence here).  The binary32 estimate n * (1 / d)
+// carries a relative error below 2^-21 (two conversions, a reciprocal good to one unit in the last place, a
+// product), that is less than 1/16 absolute for such quotients, so its truncation is the quotient or one
+// off; the exact remainder then says which.
+__device__ __forceinline__ uint32_t div_small_quot(uint64_t n, uint32_t d) {
+  const float nf = __builtin_fmaf((float)(uint32_t)(n >> 32), 4294967296.0f, (float)(uint32_t)n);
+  uint32_t q = (uint32_t)(nf * __builtin_amdgcn_rcpf((float)d));
+  const int64_t r = (int64_t)n - (int64_t)((uint64_t)q * d);
+  q = r < 0 ? q - 1 : (r >= (int64_t)d ? q + 1 : q);
+  return q;
+}
+// floor(2^(32+k) / d) for 2^k <= d < 2^(k+1), d < 2^16: long division in base 2^16, whose two digits
+// are quotients of the kind above (the first lies in (2^15, 2^16], the second below 2^16).
+__device__ __forceinline__ uint64_t div_pow2_by(uint32_t k, uint32_t d) {
+  const uint32_t n1 = 1u << (16 + k);
+  const uint32_t q1 = div_small_quot(n1, d);
+  const uint32_t r1 = n1 - q1 * d;  // < d
+  const uint32_t q2 = div_small_quot((uint64_t)r1 << 16, d);
+  return ((uint64_t)q1 << 16) + q2;
+}
+
+// Checks the two routines above against integer division (see rans_selftest_divide).
+__global__ void k_selftest_clear(uint32_t *mismatches) { *mismatches = 0; }
+__global__ __launch_bounds__(kWG) void k_selftest_divide(uint32_t *mismatches, uint64_t n_random) {
+  const uint64_t i = (uint64_t)blockIdx.x * kWG + threadIdx.x;
+  uint32_t bad = 0;
+  if (i >= 1 && i < 65536) {
+    const uint32_t d = (uint32_t)i, k = 31u - (uint32_t)__clz((int)d);
+    bad += div_pow2_by(k, d) != (1ull << (32 + k)) / d;
+  }
+  for (uint64_t t = i; t < n_random; t += (uint64_t)gridDim.x * kWG) {
+    // a divisor of 1 .. 32 bits, a quotient below 2^17 and a remainder, from a mixing function of t
+    uint64_t h = (t + 1) * 0x9e3779b97f4a7c15ull;
+    h ^= h >> 29; h *= 0xbf58476d1ce4e5b9ull; h ^= h >> 32;
+    const uint32_t bits = 1 + (uint32_t)(h % 32);
+    uint64_t h2 = h * 0x94d049bb133111ebull; h2 ^= h2 >> 31;
+    uint32_t d = (uint32_t)(h2 >> 32) >> (32 - bits);
+    d = d ? d : 1u;
+    const uint32_t q = (uint32_t)(h2 & 0x1ffffu);
+    uint64_t h3 = h2 * 0xd6e8feb86659fd93ull; h3 ^= h3 >> 32;
+    const uint32_t r = t % 3 == 0 ? 0u : (t % 3 == 1 ? d - 1 : (uint32_t)(h3 % d));  // both ends of the remainder's range
+    const uint64_t n = (uint64_t)q * d + r;
+    if (n < (1ull << 48)) bad += div_small_quot(n, d) != q;
+  }
+  if (bad) atomicAdd(mismatches, bad);
+}
+
+// Everything stored per symbol: f in the container, the encoder's two table entries.  div(k, d) returns
+// floor(2^(32+k) / d) for 2^k <= d < 2^(k+1), d < 2^16.  Returns whether the division-free entry is inexact.
 //
 // Division-free entry {lim1, mx, Fx | sh << 16, 2^M - f}: the coder renormalises when s > lim1 and
 // then takes q = mulhi(s, mx) >> sh for floor(s / f) in Eq. 2.  At that point s <= lim1 =
@@ -288,36 +347,42 @@ __device__ void write_header(const CtlRef &ctl, const NormArgs &na, uint64_t len
 // for f > 2^(M-1)).  Powers of two take mx = 2^31, sh = k - 1.  f = 1 cannot have its multiplier
 // 2^32: it takes mx = 2^32 - 1, which gives q = s - 1 (s >= 1 there), and the missing 2^M - f is
 // added to Fx instead.  f = 0 (absent symbol) is never looked up.
+//
+// The one division is made for every symbol, whatever its case, and the cases select afterwards: the
+// divisions of a lane's symbols are then independent instruction streams that overlap, where branches
+// around them would run them one after the other.  The fallback entry's floor(2^32 / f) is the same
+// quotient shifted down by k (floors of successive integer divisions compose).
 template <class Div>
-__device__ __forceinline__ int emit_entries(const NormArgs &na, uint32_t a, uint32_t f, uint32_t F, uint32_t m_floor,
-                                            Div div) {
+__device__ __forceinline__ int emit_entries(const NormArgs &na, uint32_t a, uint32_t f, uint32_t F, Div div,
+                                            bool store = true) {
   const uint32_t M = na.p.freq_bits, total = 1u << M;
-  int inexact = 0;
+  const uint32_t fd = f ? f : 1u;
+  const uint32_t k = 31u - (uint32_t)__clz((int)fd);
+  const uint64_t two = 1ull << (32 + k);
+  const uint64_t quo = div(k, fd);  // 2^32 for a power of two, else below 2^32 (f > 2^k)
   // floor(2^32 / f) for f >= 2, 2^32 - 1 for f = 1: with it mulhi(s, m) is floor(s / f) or one less
-  const uint32_t m = f <= 1 ? 0xffffffffu : m_floor;
-  na.enc_tab[a] = make_uint2(m, f | (F << 16));
-  *(uint16_t *)(na.out + kHdrBytes + 2ull * a) = (uint16_t)f;
+  const uint32_t m = f <= 1 ? 0xffffffffu : (uint32_t)(quo >> k);
   const uint32_t cmpl = total - f;
-  uint32_t lim1 = (f << (32 - M)) - 1u, mx = 0, sh = 0, Fx = F;
+  const uint32_t lim1 = (f << (32 - M)) - 1u;
+  const bool pow2 = (f & (f - 1)) == 0;  // also f = 0, 1
+  const uint64_t mq = quo + 1;
+  const uint64_t e = mq * fd - two;
+  const int inexact = !pow2 && (uint64_t)lim1 * e >= two;
+  uint32_t mx = pow2 ? 0x80000000u : (uint32_t)mq, sh = pow2 ? k - 1 : k, Fx = F;
   if (f == 1) {
     mx = 0xffffffffu;
+    sh = 0;
     Fx = F + cmpl;
-  } else if (f > 1) {
-    const uint32_t k = 31u - (uint32_t)__clz((int)f);
-    if ((f & (f - 1)) == 0) {
-      mx = 0x80000000u;
-      sh = k - 1;
-    } else {
-      const uint64_t two = 1ull << (32 + k);
-      const uint64_t mq = div(two) + 1;  // < 2^32 because f > 2^k
-      const uint64_t e = mq * f - two;
-      if ((uint64_t)lim1 * e >= two) inexact = 1;
-      mx = (uint32_t)mq;
-      sh = k;
-    }
+  } else if (f == 0) {
+    mx = 0;
+    sh = 0;
   }
-  na.enc_tab4[a] = make_uint4(lim1, mx, Fx | (sh << 16), cmpl);
-  return inexact;
+  if (store) {  // a symbol of the alphabet (the caller may pass lanes beyond it, with f = 0)
+    na.enc_tab[a] = make_uint2(m, f | (F << 16));
+    if (!na.quiet) *(uint16_t *)(na.out + kHdrBytes + 2ull * a) = (uint16_t)f;
+    na.enc_tab4[a] = make_uint4(lim1, mx, Fx | (sh << 16), cmpl);
+  }
+  return store && inexact;
 }
 
 __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
@@ -344,7 +409,7 @@ __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
   const uint64_t len = block_sum64<kBig>(len_loc, sh64);
   const uint64_t present = block_sum64<kBig>(present_loc, sh64);
   // l_D as the rest of the call knows it: the tensor's size (DENSE), or what the row-count kernel derived from
-  // the row ends.  A histogram that does not add up to it is an incomplete hand-over, never a wrong table.
+  // the row ends.  A histogram that does not add up to it becomes an error, never a wrong table.
   const uint64_t len_d = dense ? n_elems : ctl->len_d;
   if (dense && threadIdx.x == 0) ctl->len_d = len_d;
   if (present > total || len != len_d) {
@@ -409,7 +474,7 @@ __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
     uint32_t f = a < A ? fq[a] : 0, tot;
     uint32_t F = carry + block_excl_scan<kBig>(f, sh32, &tot);
     if (a < A) {
-      inexact |= emit_entries(na, a, f, F, (uint32_t)(0x100000000ull / (f ? f : 1)), [&](uint64_t two) { return two / f; });
+      inexact |= emit_entries(na, a, f, F, [](uint32_t k, uint32_t d) { return (1ull << (32 + k)) / d; });
     }
     carry += tot;
     __syncthreads();
@@ -419,26 +484,20 @@ __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
   for (uint64_t o = table_off + 2ull * A + 2 * threadIdx.x; o < dir_off; o += 2 * kBig) *(uint16_t *)(out + o) = 0;
 }
 
-// floor(a / b) for 0 <= a < 2^52, 1 <= b < 2^32 through one binary64 division instead of the much
-// longer 64-bit integer division.  Both operands are exact in binary64.  If b divides a the division is
-// exact.  Otherwise a / b lies at least 1 / b away from the integers next to it, and the correctly
-// rounded quotient differs from a / b by at most (a / b) * 2^-53 < 1 / b (because a < 2^53), so it
-// stays strictly between the same two integers and its floor is the floor of a / b.
-__device__ __forceinline__ uint64_t floor_div_f64(uint64_t a, uint32_t b) {
-  return (uint64_t)((double)a / (double)b);
-}
-
 // The same as normalize_body for alphabets of up to 64 PER symbols, by ONE wave without a barrier: lane l
 // owns the symbols PER l .. PER l + PER - 1, sums and maxima are wave scans.  Called by the first wave of a
-// work-group; the single work-group version spends most of its time in barriers between 16 waves.
+// work-group (of the encoder, where every work-group builds the table for itself, or of k_normalize).  About
+// a thousand instructions of one wave; sharing the symbols out over the four waves of an encoder work-group
+// was measured and is no faster, since the barriers and the four-fold instruction issue eat the gain.
 constexpr uint32_t kNormWaveA = 512;
 template <int PER>
-__device__ void normalize_wave_per(const CtlRef &ctl, const NormArgs &na) {
+__device__ __forceinline__ NormResult normalize_wave_per(const CtlRef &ctl, const NormArgs &na) {
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t A = na.A;
   const rans_params &p = na.p;
   const uint32_t M = p.freq_bits, total = 1u << M;
-  if (__ballot(get_status(ctl) != 0) != 0) return;  // one decision for the wave
+  NormResult res{};
+  if (!na.entry_checked && __ballot(status_at_entry(ctl) != 0) != 0) return res;  // one decision for the wave
   auto total64 = [](uint64_t v) { return lane63_64(wave_incl_scan64(v, [](uint64_t a, uint64_t b) { return a + b; })); };
   auto max64 = [](uint64_t v) { return lane63_64(wave_incl_scan64(v, [](uint64_t a, uint64_t b) { return a > b ? a : b; })); };
   uint32_t c[PER];
@@ -452,27 +511,24 @@ __device__ void normalize_wave_per(const CtlRef &ctl, const NormArgs &na) {
   for (int q = 0; q < PER; q++) lp += (uint64_t)c[q] + ((uint64_t)(c[q] != 0) << 40);
   lp = total64(lp);
   const uint64_t len = lp & ((1ull << 40) - 1), present = lp >> 40;
-  // l_D as the rest of the call knows it: the tensor's size (DENSE), or - CSR mode - what a work-group of the
-  // kernel this may run in stored with a device-scope atomic.  A histogram that does not add up to it is an
-  // incomplete hand-over between work-groups and becomes an error, never a wrong table.
-  const uint64_t len_d = na.dense ? na.n_elems : __hip_atomic_load(&ctl->len_d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  if (na.dense && lane == 0) ctl->len_d = len_d;
+  // l_D as the rest of the call knows it: the tensor's size (DENSE), or - CSR mode - what the row-count kernel
+  // derived from the row ends.  A histogram that does not add up to it becomes an error, never a wrong table.
+  const uint64_t len_d = na.dense ? na.n_elems : ctl->len_d;
+  if (na.dense && !na.quiet && lane == 0) ctl->len_d = len_d;
   if (present > total || len != len_d) {
     if (lane == 0) set_status(ctl, len != len_d ? RANS_ERR_HIP : RANS_ERR_ALPHABET);
-    return;
+    return res;
   }
   // first estimate, its sum, the symbol with the largest count
   uint32_t f[PER];
   uint64_t sum = 0, best = 0;
 #pragma unroll
   for (int q = 0; q < PER; q++) {
-    f[q] = 0;
-    if (c[q]) {
-      const uint64_t e = floor_div_f64((uint64_t)c[q] * total + len / 2, (uint32_t)len);  // < 2^46 over < 2^32
-      f[q] = e < 1 ? 1u : (uint32_t)e;
-      const uint64_t key = ((uint64_t)c[q] << 32) | (0xffffffffu - (PER * lane + q));  // max count, lowest index
-      best = key > best ? key : best;
-    }
+    // the division is made for absent symbols too (and for an empty D, by 1): see emit_entries on branches
+    const uint32_t e = div_small_quot((uint64_t)c[q] * total + len / 2, len ? (uint32_t)len : 1u);  // at most 2^M
+    f[q] = c[q] ? (e < 1 ? 1u : e) : 0u;
+    const uint64_t key = ((uint64_t)c[q] << 32) | (0xffffffffu - (PER * lane + q));  // max count, lowest index
+    best = c[q] && key > best ? key : best;
     sum += f[q];
   }
   sum = total64(sum);
@@ -507,9 +563,9 @@ __device__ void normalize_wave_per(const CtlRef &ctl, const NormArgs &na) {
   const uint64_t payload_off = dir_off + 8 * (n_chunks + 1);
   if (payload_off > na.cap) {
     if (lane == 0) set_status(ctl, RANS_ERR_CAPACITY);
-    return;
+    return res;
   }
-  if (lane == 0) write_header(ctl, na, len_d, n_chunks, dir_off, payload_off);
+  if (!na.quiet && lane == 0) write_header(ctl, na, len_d, n_chunks, dir_off, payload_off);
   // cumulative sum, encoder tables, stored table
   uint32_t mine = 0;
 #pragma unroll
@@ -519,24 +575,29 @@ __device__ void normalize_wave_per(const CtlRef &ctl, const NormArgs &na) {
 #pragma unroll
   for (int q = 0; q < PER; q++) {
     const uint32_t a = PER * lane + q;
-    if (a < A) {
-      const uint32_t fa = f[q];
-      inexact |= emit_entries(na, a, fa, F, (uint32_t)floor_div_f64(0x100000000ull, fa ? fa : 1),
-                              [&](uint64_t two) { return floor_div_f64(two, fa); });  // two <= 2^46, fa < 2^16
-    }
+    inexact |= emit_entries(na, a, f[q], F, [](uint32_t k, uint32_t d) { return div_pow2_by(k, d); }, a < A);
     F += f[q];
   }
   const bool any_inexact = __ballot(inexact) != 0;
-  if (lane == 0) ctl->enc_exact = any_inexact ? 0u : 1u;
-  for (uint64_t o = table_off + 2ull * A + 2 * lane; o < dir_off; o += 2 * 64) *(uint16_t *)(na.out + o) = 0;
+  if (!na.quiet) {
+    if (lane == 0) ctl->enc_exact = any_inexact ? 0u : 1u;
+    for (uint64_t o = table_off + 2ull * A + 2 * lane; o < dir_off; o += 2 * 64) *(uint16_t *)(na.out + o) = 0;
+  }
+  res.ok = 1;
+  res.exact = any_inexact ? 0u : 1u;
+  res.n_chunks = (uint32_t)n_chunks;
+  res.len_d = len_d;
+  res.dir_off = dir_off;
+  res.payload_off = payload_off;
+  return res;
 }
 
-__device__ void normalize_wave(const CtlRef &ctl, const NormArgs &na) {
+__device__ __forceinline__ NormResult normalize_wave(const CtlRef &ctl, const NormArgs &na) {
   // as few symbols per lane as the alphabet allows (CSR with K = 2^Q has 2^Q + 1 symbols)
-  if (na.A <= 256) normalize_wave_per<4>(ctl, na);
-  else if (na.A <= 320) normalize_wave_per<5>(ctl, na);
-  else if (na.A <= 384) normalize_wave_per<6>(ctl, na);
-  else normalize_wave_per<8>(ctl, na);
+  if (na.A <= 256) return normalize_wave_per<4>(ctl, na);
+  if (na.A <= 320) return normalize_wave_per<5>(ctl, na);
+  if (na.A <= 384) return normalize_wave_per<6>(ctl, na);
+  return normalize_wave_per<8>(ctl, na);
 }
 
 __global__ __launch_bounds__(kBig) void k_normalize(CtlRef ctl, NormArgs na) {
@@ -562,8 +623,7 @@ template <typename T, bool VEC, int NT, bool CSR>
 __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRef ctl, uint32_t q_bits,
                                                     uint8_t *sym, uint32_t *cnt, int skip_zero_bin,
                                                     const MinMaxPart *part, uint32_t n_part, rans_qinfo *qout,
-                                                    int fold_norm, NormArgs na, uint32_t *blk_nnz,
-                                                    uint32_t *grp_nnz) {
+                                                    uint32_t *blk_nnz, uint32_t *grp_nnz) {
   constexpr bool IS_SYM = sizeof(T) == 1;
   constexpr int V = VEC ? (int)(16 / sizeof(T)) : 1;
   __shared__ uint32_t h[256 * kHistRep];
@@ -684,41 +744,15 @@ __global__ __launch_bounds__(NT) void k_quant_hist(const T *x, uint32_t n, CtlRe
   if (fast) run(std::true_type{});
   else run(std::false_type{});
   __syncthreads();
-  uint32_t seen = 0;
+  // The counts go to the global histogram with additions that return nothing: the kernel that reads them
+  // starts after this one has ended, which is all the ordering the histogram needs.
   for (int a = threadIdx.x; a < 256; a += NT) {
     uint32_t t = 0;
 #pragma unroll
     for (int r = 0; r < kHistRep; r++) t += h[a * kHistRep + r];
     if (!t) continue;
     if (a >= (1 << q_bits)) set_status(ctl, RANS_ERR_ARG);  // caller-provided symbol outside {0..2^Q-1}
-    else if (!(skip_zero_bin && a == 0)) {
-      // with the table build folded in, the additions return their old value: a returned value is the only
-      // proof that an addition has been performed before the work-group takes its ticket (one without a
-      // result is acknowledged earlier than that)
-      if (fold_norm) seen |= atomicAdd(&cnt[a], t);
-      else atomicAdd(&cnt[a], t);
-    }
-  }
-  if (!fold_norm) return;
-  if (seen == 0xffffffffu) set_status(ctl, RANS_ERR_HIP);  // cannot happen (counts are below 2^31); keeps the values in use
-  // The work-group that adds its counts last also builds the frequency table (saves a launch).  The
-  // additions above are device-scope atomics that return a value; the barrier waits for the values, so
-  // this work-group's additions have been performed when it takes its ticket.  The last one reads the
-  // histogram with device-scope atomic loads, so no cache has to be written back or invalidated in between.
-  __shared__ uint32_t s_ticket;
-  __syncthreads();
-  if (threadIdx.x == 0) s_ticket = __hip_atomic_fetch_add(&ctl->hist_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __syncthreads();
-  if (s_ticket != gridDim.x - 1) return;
-  if (part) {  // every work-group has computed the extrema itself
-    na.mm_given = 1;
-    na.x_min = qi.x_min;
-    na.x_max = qi.x_max;
-  }
-  if (na.A <= kNormWaveA) {
-    if (threadIdx.x < 64) normalize_wave(ctl, na);
-  } else if constexpr (NT == kBig) {
-    normalize_body(ctl, na);
+    else if (!(skip_zero_bin && a == 0)) atomicAdd(&cnt[a], t);
   }
 }
 

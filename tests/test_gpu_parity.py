@@ -249,6 +249,17 @@ def test_edge_cases():
     _check_all(x, B.make_params(2, 12, rows, cols, B.MODE_CSR, 32, 0, B.F32), "deficit")
 
 
+def test_table_divisions_equal_integer_division():
+    """The frequency-table kernels divide through a reciprocal estimate and an exact remainder check; on the device
+    that runs them: every divisor of the encoder's multipliers (Eq. 2), and 2^24 quotients of the kind Sec. 3.2's
+    normalisation takes, against integer division."""
+    bad = torch.full((1,), 123, dtype=torch.int32, device="cuda")
+    print("[case] division self-test", flush=True)
+    assert B.rans_selftest_divide(bad, 1 << 24) == 0
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
+
+
 def test_data_errors():
     n = 4096
     p = B.make_params(8, 12, n, 1, B.MODE_DENSE, 32, 0, B.F32)

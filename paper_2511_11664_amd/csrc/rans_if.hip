@@ -52,12 +52,12 @@ namespace {
 enum KernelId {
   KID_MINMAX = 0, KID_QINFO, KID_QUANT_HIST, KID_SCAN, KID_CSR_COMPACT, KID_CSR_ROWS,
   KID_NORMALIZE, KID_ENCODE, KID_CHUNK_SCAN, KID_GATHER, KID_DEC_PREPARE, KID_DECODE, KID_ROW_SCAN,
-  KID_CSR_EXPAND, KID_DEQUANT, KID_COUNT
+  KID_CSR_EXPAND, KID_DEQUANT, KID_RS_MASK, KID_RS_COLS, KID_RS_ROWS, KID_RS_COST, KID_COUNT
 };
 const char *const kKernelNames[KID_COUNT] = {
     "k_minmax", "k_qinfo", "k_quant_hist", "k_scan_u32", "k_csr_compact", "k_csr_rows",
     "k_normalize", "k_encode", "k_chunk_scan", "k_gather", "k_dec_prepare", "k_decode", "k_row_part",
-    "k_csr_to_dense", "k_dequant"};
+    "k_csr_to_dense", "k_dequant", "k_rs_mask", "k_rs_cols", "k_rs_rows", "k_rs_cost"};
 
 struct ProfRecord {
   int kid;
@@ -694,8 +694,9 @@ int static_ws_of_current_device(void **out) {
 struct RsPlan {
   RsCands cands;
   RsOffsets offs;
+  RsGroups grps;
   uint32_t n_entries, n_tiles;
-  size_t mask16, lp, tile_cnt, zero0, hv, hc, hr, bad, costs, ticket, total;  // byte offsets in the workspace
+  size_t mask16, lp, tile_cnt, zero0, hv, hl, hr, bad, costs, ticket, total;  // byte offsets in the workspace
   uint32_t zero_words;
   bool too_many;
 };
@@ -722,15 +723,60 @@ RsPlan rs_plan(uint64_t n, uint32_t q_bits) {
     }
     P.cands.K[P.cands.n++] = (uint16_t)K;
   }
-  uint32_t oc = 0, orr = 0;
+  uint32_t orr = 0;
   for (uint32_t k = 0; k < P.cands.n; k++) {
-    P.offs.hc[k] = oc;
     P.offs.hr[k] = orr;
-    oc += P.cands.K[k];
     orr += P.cands.K[k] + 1u;
   }
-  P.offs.hc[P.cands.n] = oc;
   P.offs.hr[P.cands.n] = orr;
+  {  // work-groups of k_rs_rows: about kRowsGrid in all, shared out by the number of rows (K = 1 needs one)
+    constexpr uint64_t kRowsGrid = 4096;
+    uint64_t rows_all = 0;
+    for (uint32_t k = 0; k < P.cands.n; k++) rows_all += P.cands.K[k] > 1 ? n / P.cands.K[k] : 0;
+    uint32_t w = 0;
+    for (uint32_t k = 0; k < P.cands.n; k++) {
+      P.offs.wg0[k] = w;
+      const uint64_t rows = P.cands.K[k] > 1 ? n / P.cands.K[k] : 0;
+      const uint64_t need = (rows + 4 * 63 - 1) / (4 * 63);  // work-groups that have a row at all
+      uint64_t share = rows_all ? (rows * kRowsGrid + rows_all - 1) / rows_all : 1;
+      share = share > need ? need : share;
+      w += (uint32_t)(share < 1 ? 1 : share);
+    }
+    P.offs.wg0[P.cands.n] = w;
+  }
+  // groups of consecutive candidates with a common multiple of at most kRsLcmMax (see RsGroups)
+  uint32_t ol = 0;
+  {
+    auto gcd = [](uint32_t a, uint32_t b) {
+      while (b) {
+        const uint32_t t = a % b;
+        a = b;
+        b = t;
+      }
+      return a;
+    };
+    uint32_t cur = 0;  // common multiple of the open group, 0: none open
+    for (uint32_t k = 0; k < P.cands.n; k++) {
+      const uint32_t K = P.cands.K[k];
+      const uint64_t l2 = cur ? (uint64_t)cur / gcd(cur, K) * K : 0;
+      if (cur && l2 <= kRsLcmMax) {
+        cur = (uint32_t)l2;
+      } else {
+        if (cur) P.grps.n++;
+        cur = K;
+      }
+      P.grps.of[k] = (uint8_t)P.grps.n;
+      P.grps.L[P.grps.n] = cur;
+    }
+    if (cur) P.grps.n++;
+    for (uint32_t g = 0; g < P.grps.n; g++) {
+      uint32_t &L = P.grps.L[g];
+      if (L < 32) L *= (32 + L - 1) / L;  // the kernel's wrap-around assumes at least 32 residues
+      P.grps.off[g] = ol;
+      ol += L;
+    }
+    P.grps.off[P.grps.n] = ol;
+  }
   P.n_entries = (uint32_t)((n + 15) / 16);
   P.n_tiles = (uint32_t)((n + kRsTile - 1) / kRsTile);
   size_t o = 0;
@@ -744,7 +790,7 @@ RsPlan rs_plan(uint64_t n, uint32_t q_bits) {
   P.tile_cnt = take(((size_t)P.n_tiles + 1) * 4);
   P.zero0 = o;
   P.hv = take(256 * 4);
-  P.hc = take((size_t)oc * 4 + 4);
+  P.hl = take((size_t)ol * 4 + 4);
   P.hr = take((size_t)orr * 4 + 4);
   P.bad = take(4);
   P.costs = take(RANS_RESHAPE_MAX_CAND * 8);
@@ -758,31 +804,35 @@ int launch_search_reshape(const uint8_t *d_sym, uint64_t n, uint32_t q_bits, ran
                           const RsPlan &P, hipStream_t st) {
   uint16_t *mask16 = (uint16_t *)(ws + P.mask16), *lp = (uint16_t *)(ws + P.lp);
   uint32_t *tile_cnt = (uint32_t *)(ws + P.tile_cnt);
-  uint32_t *hv = (uint32_t *)(ws + P.hv), *hc = (uint32_t *)(ws + P.hc), *hr = (uint32_t *)(ws + P.hr);
+  uint32_t *hv = (uint32_t *)(ws + P.hv), *hl = (uint32_t *)(ws + P.hl), *hr = (uint32_t *)(ws + P.hr);
   uint32_t *bad = (uint32_t *)(ws + P.bad);
   hipLaunchKernelGGL(k_rs_zero, dim3(8), dim3(256), 0, st, (uint32_t *)(ws + P.zero0), P.zero_words);
   LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_rs_mask, dim3(P.n_tiles < 1024 ? P.n_tiles : 1024), dim3(kWG), 0, st, d_sym, (uint32_t)n,
-                     (int)aligned_to(d_sym, 16), P.n_tiles, mask16, lp, tile_cnt, hv, q_bits, bad);
+  PROF_LAUNCH(KID_RS_MASK, k_rs_mask, dim3(P.n_tiles < 512 ? P.n_tiles : 512), dim3(kWG), 0, st, d_sym, (uint32_t)n,
+              (int)aligned_to(d_sym, 16), P.n_tiles, mask16, lp, tile_cnt, hv, q_bits, bad);
   LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(kBig), 0, st, tile_cnt, P.n_tiles);
+  PROF_LAUNCH(KID_SCAN, k_scan_u32, dim3(1), dim3(kBig), 0, st, tile_cnt, P.n_tiles);
   LAUNCH_CHECK();
-  const uint32_t g_e = grid_for(P.n_entries, kWG, 1024);
-  for (uint32_t k0 = 0; k0 < P.cands.n;) {  // groups of candidates whose column bins fit in LDS together
-    uint32_t k1 = k0 + 1;
-    while (k1 < P.cands.n && P.offs.hc[k1 + 1] - P.offs.hc[k0] <= kRsColBins) k1++;
-    hipLaunchKernelGGL(k_rs_cols, dim3(g_e), dim3(kWG), 0, st, mask16, P.n_entries, P.cands, k0, k1, P.offs, hc);
-    LAUNCH_CHECK();
-    k0 = k1;
+  {
+    static const hipError_t attr_rc = hipFuncSetAttribute((const void *)k_rs_cols, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                          kRsLcmMax * 4);
+    if (attr_rc != hipSuccess) return RANS_ERR_HIP;
+    const uint32_t n_cu = compute_units();
+    const uint32_t g_e = grid_for((P.n_entries + 7) / 8, kWG, n_cu ? n_cu : 256);  // one work-group per compute unit
+    for (uint32_t g = 0; g < P.grps.n; g++) {
+      PROF_LAUNCH(KID_RS_COLS, k_rs_cols, dim3(g_e), dim3(kWG), P.grps.L[g] * 4, st, mask16, P.n_entries, P.grps.L[g],
+                  hl + P.grps.off[g]);
+      LAUNCH_CHECK();
+    }
   }
   if (P.cands.n) {
-    hipLaunchKernelGGL(k_rs_rows, dim3(grid_for(n, kWG, 512), P.cands.n), dim3(kWG), 0, st, mask16, lp, tile_cnt,
-                       (uint32_t)n, P.n_tiles, P.cands, P.offs, hr);
+    PROF_LAUNCH(KID_RS_ROWS, k_rs_rows, dim3(P.offs.wg0[P.cands.n]), dim3(kWG), 0, st, mask16, lp, tile_cnt,
+                (uint32_t)n, P.n_tiles, P.cands, P.offs, hr);
     LAUNCH_CHECK();
   }
   if (P.cands.n)
-    hipLaunchKernelGGL(k_rs_cost, dim3(P.cands.n), dim3(kWG), 0, st, P.cands, (uint32_t)n, P.n_tiles, q_bits, tile_cnt, hv, hc,
-                       hr, P.offs, bad, (double *)(ws + P.costs), (uint32_t *)(ws + P.ticket), d_res);
+    PROF_LAUNCH(KID_RS_COST, k_rs_cost, dim3(P.cands.n), dim3(kWG), 0, st, P.cands, (uint32_t)n, P.n_tiles, q_bits, tile_cnt, hv, hl,
+                hr, P.offs, P.grps, bad, (double *)(ws + P.costs), (uint32_t *)(ws + P.ticket), d_res);
   else
     hipLaunchKernelGGL(k_rs_empty, dim3(1), dim3(1), 0, st, (uint32_t)n, bad, d_res);
   LAUNCH_CHECK();

@@ -19,28 +19,47 @@ struct RsCands {
   uint32_t n;
   uint16_t K[RANS_RESHAPE_MAX_CAND];
 };
-struct RsOffsets {  // first bin of each candidate's column / row-count histogram; entry n = total
-  uint32_t hc[RANS_RESHAPE_MAX_CAND + 1], hr[RANS_RESHAPE_MAX_CAND + 1];
+struct RsOffsets {  // first bin of each candidate's row-count histogram; entry n = total
+  uint32_t hr[RANS_RESHAPE_MAX_CAND + 1];
+  // first work-group of each candidate in the grid of k_rs_rows (shares in proportion to the number of rows, so
+  // that the candidates with the shortest rows do not run on alone at the end); entry n = the grid
+  uint32_t wg0[RANS_RESHAPE_MAX_CAND + 1];
+};
+// Candidates are grouped so that the members of a group have a common multiple L of at most kRsLcmMax: one
+// histogram of the nonzero positions modulo L then serves every member, whose own column histogram
+// (positions modulo K) is that one folded K-periodically.
+constexpr uint32_t kRsLcmMax = 32768;  // LDS words of k_rs_cols
+struct RsGroups {
+  uint32_t n;
+  uint32_t L[RANS_RESHAPE_MAX_CAND];        // residues of group g: a multiple of every K in it, at least 16
+  uint32_t off[RANS_RESHAPE_MAX_CAND + 1];  // first word of its histogram in hl; entry n = total
+  uint8_t of[RANS_RESHAPE_MAX_CAND];        // group of candidate k
 };
 
 __global__ __launch_bounds__(kWG) void k_rs_mask(const uint8_t *sym, uint32_t n, int aligned, uint32_t n_tiles,
                                                  uint16_t *mask16, uint16_t *lp, uint32_t *tile_cnt, uint32_t *hv,
                                                  uint32_t q_bits, uint32_t *bad_flag) {
   __shared__ uint32_t sh[kWG / 64];
-  __shared__ uint32_t h[256];
-  h[threadIdx.x] = 0;  // kWG == 256
+  // eight counters per value, one per lane residue: activations have a few very frequent values, and a wave's
+  // additions to one LDS address are performed one after the other
+  __shared__ uint32_t h[256 * 8];
+  for (uint32_t i = threadIdx.x; i < 256 * 8; i += kWG) h[i] = 0;
+  const uint32_t rep = threadIdx.x & 7u;
   __syncthreads();
+  uint8_t b[16];
+  if (blockIdx.x < n_tiles) load16(sym, (uint64_t)blockIdx.x * kRsTile + threadIdx.x * 16, n, aligned, b);
   for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const uint64_t e0 = (uint64_t)tile * kRsTile + threadIdx.x * 16;
-    uint8_t b[16];
-    load16(sym, e0, n, aligned, b);
+    uint8_t nb[16];  // the next tile's symbols are on their way while this one is looked at
+    const bool more = tile + gridDim.x < n_tiles;
+    if (more) load16(sym, e0 + (uint64_t)gridDim.x * kRsTile, n, aligned, nb);
     uint32_t m = 0;
 #pragma unroll
     for (int k = 0; k < 16; k++) {
       if (b[k]) {
         m |= 1u << k;
         if (b[k] >> q_bits) atomicOr(bad_flag, 1u);  // not a symbol of this bit width
-        atomicAdd(&h[b[k]], 1u);
+        atomicAdd(&h[b[k] * 8u + rep], 1u);
       }
     }
     uint32_t tot;
@@ -50,9 +69,15 @@ __global__ __launch_bounds__(kWG) void k_rs_mask(const uint8_t *sym, uint32_t n,
       lp[e0 >> 4] = (uint16_t)ex;
     }
     if (threadIdx.x == 0) tile_cnt[tile] = tot;
+    if (more) {
+#pragma unroll
+      for (int k = 0; k < 16; k++) b[k] = nb[k];
+    }
     __syncthreads();
   }
-  const uint32_t t = h[threadIdx.x];
+  uint32_t t = 0;  // kWG == 256: a thread per value
+#pragma unroll
+  for (int r = 0; r < 8; r++) t += h[threadIdx.x * 8 + r];
   if (t) atomicAdd(&hv[threadIdx.x], t);
 }
 
@@ -61,35 +86,49 @@ __global__ void k_rs_zero(uint32_t *p, uint32_t words) {
   for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < words; i += gridDim.x * blockDim.x) p[i] = 0;
 }
 
-// Histograms of c = position mod K over the nonzero positions, for the candidates [k0, k1): their bins
-// sit one after the other in LDS (at most kRsColBins in total) and in hc (at hc_off[k]).
-constexpr uint32_t kRsColBins = 8192;
-__global__ __launch_bounds__(kWG) void k_rs_cols(const uint16_t *mask16, uint32_t n_entries, RsCands cands, uint32_t k0,
-                                                 uint32_t k1, RsOffsets offs, uint32_t *hc) {
-  __shared__ uint32_t h[kRsColBins];
-  const uint32_t *hc_off = offs.hc;
-  const uint32_t base0 = hc_off[k0], bins = hc_off[k1] - base0;
-  for (uint32_t i = threadIdx.x; i < bins; i += kWG) h[i] = 0;
+// Histogram of the nonzero positions modulo L (one group of candidates; see RsGroups), in LDS and then added
+// to hl.  A thread takes eight consecutive mask entries (128 positions) with one load and walks their set bits.
+__global__ __launch_bounds__(kWG) void k_rs_cols(const uint16_t *mask16, uint32_t n_entries, uint32_t L, uint32_t *hl) {
+  extern __shared__ uint32_t h_l[];
+  for (uint32_t i = threadIdx.x; i < L; i += kWG) h_l[i] = 0;
   __syncthreads();
-  for (uint32_t e = blockIdx.x * kWG + threadIdx.x; e < n_entries; e += gridDim.x * kWG) {
-    const uint32_t m = mask16[e];
-    if (!m) continue;
-    const uint32_t g0 = e * 16;  // n <= 2^30: fits
-    for (uint32_t k = k0; k < k1; k++) {
-      const uint32_t K = cands.K[k];
-      uint32_t *hk = h + (hc_off[k] - base0);
-      uint32_t c = g0 % K;
+  const uint32_t n_oct = (n_entries + 7) / 8;
+  const uint32_t stride = gridDim.x * kWG;
+  const uint32_t step = (uint32_t)(((uint64_t)stride * 128) % L);  // positions between a thread's octets, modulo L
+  uint32_t c = (uint32_t)(((uint64_t)(blockIdx.x * kWG + threadIdx.x) * 128) % L);
+  for (uint32_t o = blockIdx.x * kWG + threadIdx.x; o < n_oct; o += stride) {
+    uint32_t w[4];
+    if (8 * o + 8 <= n_entries) {  // the mask array starts 256-byte aligned
+      const uint4 q = *(const uint4 *)(mask16 + 8 * (size_t)o);
+      w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+    } else {
 #pragma unroll
-      for (int bit = 0; bit < 16; bit++) {
-        if (m & (1u << bit)) atomicAdd(&hk[c], 1u);
-        c = c + 1 == K ? 0 : c + 1;
+      for (int j = 0; j < 4; j++) {
+        const uint32_t e = 8 * o + 2 * j;
+        w[j] = (e < n_entries ? mask16[e] : 0u) | ((e + 1 < n_entries ? (uint32_t)mask16[e + 1] : 0u) << 16);
       }
     }
+    uint32_t cj = c;  // residue of the first position of the word at hand
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      uint32_t m = w[j];
+      while (m) {
+        const uint32_t bit = (uint32_t)__ffs((int)m) - 1u;
+        m &= m - 1u;
+        uint32_t pos = cj + bit;  // < 2 L as L >= 32
+        pos = pos >= L ? pos - L : pos;
+        atomicAdd(&h_l[pos], 1u);
+      }
+      cj += 32;
+      cj = cj >= L ? cj - L : cj;
+    }
+    c += step;
+    c = c >= L ? c - L : c;
   }
   __syncthreads();
-  for (uint32_t i = threadIdx.x; i < bins; i += kWG) {
-    const uint32_t t = h[i];
-    if (t) atomicAdd(&hc[base0 + i], t);
+  for (uint32_t i = threadIdx.x; i < L; i += kWG) {
+    const uint32_t t = h_l[i];
+    if (t) atomicAdd(&hl[i], t);
   }
 }
 
@@ -101,17 +140,22 @@ __device__ __forceinline__ uint32_t rs_prefix(uint32_t g, uint32_t n, uint32_t n
   return tile_off[g / kRsTile] + lp[e] + __popc((uint32_t)mask16[e] & ((1u << (g & 15)) - 1u));
 }
 
-// Histogram of the row counts r for candidate blockIdx.y: r[i] = prefix((i + 1) K) - prefix(i K).
+// Histogram of the row counts r of one candidate (the work-group's, see RsOffsets): r[i] = prefix((i + 1) K) - prefix(i K).  A wave
+// takes 63 consecutive rows: lane l looks up the prefix at the start of row l of them (lane 63: the end of the
+// last), and a row's count is the neighbouring lane's prefix minus the lane's own - one look-up per row.
 __global__ __launch_bounds__(kWG) void k_rs_rows(const uint16_t *mask16, const uint16_t *lp, const uint32_t *tile_off,
                                                  uint32_t n, uint32_t n_tiles, RsCands cands, RsOffsets offs,
                                                  uint32_t *hr) {
   __shared__ uint32_t h[257];
   const uint32_t *hr_off = offs.hr;
-  const uint32_t k = blockIdx.y, K = cands.K[k];
+  uint32_t k = 0;
+  while (k + 1 < cands.n && offs.wg0[k + 1] <= blockIdx.x) k++;  // uniform; at most a hundred steps
+  const uint32_t K = cands.K[k];
+  const uint32_t bx = blockIdx.x - offs.wg0[k], gx = offs.wg0[k + 1] - offs.wg0[k];
   const uint32_t nnz = tile_off[n_tiles];
   uint32_t *out = hr + hr_off[k];
   if (K == 1) {  // the row counts are the zero mask itself
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (bx == 0 && threadIdx.x == 0) {
       out[0] = n - nnz;
       out[1] = nnz;
     }
@@ -120,10 +164,23 @@ __global__ __launch_bounds__(kWG) void k_rs_rows(const uint16_t *mask16, const u
   for (uint32_t i = threadIdx.x; i <= K; i += kWG) h[i] = 0;
   __syncthreads();
   const uint32_t N = n / K;
-  for (uint32_t i = blockIdx.x * kWG + threadIdx.x; i < N; i += gridDim.x * kWG) {
-    const uint32_t a = rs_prefix(i * K, n, nnz, mask16, lp, tile_off);
-    const uint32_t b = rs_prefix(i * K + K, n, nnz, mask16, lp, tile_off);
-    atomicAdd(&h[b - a], 1u);
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t waves = gx * (kWG / 64);
+  // four groups of 63 rows per step, their look-ups in flight together
+  constexpr uint32_t kU = 4;
+  for (uint32_t i0 = (bx * (kWG / 64) + (threadIdx.x >> 6)) * 63; i0 < N; i0 += kU * waves * 63) {
+    uint32_t a[kU];
+#pragma unroll
+    for (uint32_t u = 0; u < kU; u++) {
+      const uint32_t i = i0 + u * waves * 63 + lane;  // i K stays below 2^32 (n <= 2^30, K <= 2^8) when i <= N
+      a[u] = rs_prefix(i <= N ? i * K : n, n, nnz, mask16, lp, tile_off);
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < kU; u++) {
+      const uint32_t i = i0 + u * waves * 63 + lane;
+      const uint32_t b = (uint32_t)__shfl_down((int)a[u], 1);
+      if (lane < 63 && i < N) atomicAdd(&h[b - a[u]], 1u);
+    }
   }
   __syncthreads();
   for (uint32_t i = threadIdx.x; i <= K; i += kWG) {
@@ -136,16 +193,34 @@ __global__ __launch_bounds__(kWG) void k_rs_rows(const uint16_t *mask16, const u
 // (a fixed tree: lanes, then waves); the work-group that finishes last walks the candidates from the
 // largest N down.  costs[] and the ticket live in the zeroed part of the workspace.
 __global__ __launch_bounds__(kWG) void k_rs_cost(RsCands cands, uint32_t n, uint32_t n_tiles, uint32_t q_bits,
-                                                 const uint32_t *tile_off, const uint32_t *hv, const uint32_t *hc,
-                                                 const uint32_t *hr, RsOffsets offs, const uint32_t *bad_flag,
-                                                 double *costs, uint32_t *ticket, rans_reshape_result *res) {
+                                                 const uint32_t *tile_off, const uint32_t *hv, const uint32_t *hl,
+                                                 const uint32_t *hr, RsOffsets offs, RsGroups grps,
+                                                 const uint32_t *bad_flag, double *costs, uint32_t *ticket,
+                                                 rans_reshape_result *res) {
   __shared__ double s_part[kWG / 64];
   __shared__ uint32_t s_ticket;
-  const uint32_t *hc_off = offs.hc, *hr_off = offs.hr;
+  __shared__ uint32_t s_col[256];  // this candidate's column histogram (K <= 2^8)
+  const uint32_t *hr_off = offs.hr;
   const uint32_t k = blockIdx.x;
   const uint32_t nnz = tile_off[n_tiles];
   {
     const uint32_t K = cands.K[k], N = n / K;
+    // the group's histogram of positions modulo L, folded K-periodically (K divides L)
+    s_col[threadIdx.x] = 0;  // kWG == 256
+    __syncthreads();
+    {
+      const uint32_t g = grps.of[k], L = grps.L[g];
+      const uint32_t *hg = hl + grps.off[g];
+      for (uint32_t i0 = threadIdx.x; i0 < L; i0 += 8 * kWG) {  // a thread's eight loads in flight together
+        uint32_t t[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) t[u] = i0 + u * kWG < L ? hg[i0 + u * kWG] : 0u;
+#pragma unroll
+        for (int u = 0; u < 8; u++)
+          if (t[u]) atomicAdd(&s_col[(i0 + u * kWG) % K], t[u]);
+      }
+    }
+    __syncthreads();
     const uint32_t two_q = 1u << q_bits;
     const uint32_t A = K + 1 > two_q ? K + 1 : two_q;
     const uint64_t len = 2ull * nnz + N;
@@ -153,7 +228,7 @@ __global__ __launch_bounds__(kWG) void k_rs_cost(RsCands cands, uint32_t n, uint
     for (uint32_t a = threadIdx.x; a < A; a += kWG) {
       uint64_t c = 0;
       if (a < two_q) c += hv[a];
-      if (a < K) c += hc[hc_off[k] + a];
+      if (a < K) c += s_col[a];
       if (a <= K) c += hr[hr_off[k] + a];
       if (c) {
         const double p = (double)c / (double)len;

@@ -422,8 +422,8 @@ __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
     uint32_t c = hist_count(na, a);
     uint32_t f = 0;
     if (c) {
-      uint64_t q = ((uint64_t)c * total + len / 2) / len;
-      f = q < 1 ? 1u : (uint32_t)q;
+      const uint32_t q = div_small_quot((uint64_t)c * total + len / 2, (uint32_t)len);  // at most 2^M
+      f = q < 1 ? 1u : q;
       uint64_t key = ((uint64_t)c << 32) | (0xffffffffu - a);  // max count, lowest index
       best_cnt = key > best_cnt ? key : best_cnt;
     }
@@ -474,7 +474,7 @@ __device__ void normalize_body(const CtlRef &ctl, const NormArgs &na) {
     uint32_t f = a < A ? fq[a] : 0, tot;
     uint32_t F = carry + block_excl_scan<kBig>(f, sh32, &tot);
     if (a < A) {
-      inexact |= emit_entries(na, a, f, F, [](uint32_t k, uint32_t d) { return (1ull << (32 + k)) / d; });
+      inexact |= emit_entries(na, a, f, F, [](uint32_t k, uint32_t d) { return div_pow2_by(k, d); });
     }
     carry += tot;
     __syncthreads();

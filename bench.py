@@ -277,11 +277,15 @@ def main():
     traffic, traffic_source = None, None
     tfile = os.path.join(ROOT, "profiles", f"{w.name}_{'csr' if w.mode else 'dense'}_pmc_traffic.txt")
     if dom and os.path.exists(tfile) and not over:
-        for line in open(tfile):
-            if line.startswith(dom + " "):
-                traffic = int(line.split()[-1])
-                traffic_source = (os.path.relpath(tfile, ROOT)
-                                  + " (rocprofv3 --pmc runs of this command, recorded earlier; not measured in this run)")
+        # the summary has one line per template instantiation; the timed loop runs the fused encoder and the
+        # decoder that writes the caller's dtype, the other instantiations belong to the unfused entry points
+        want = {"k_encode": f"k_encode<{'SrcCsr' if w.mode else 'SrcDense'},2,{'true' if w.freq_bits >= 8 else 'false'},true>",
+                "k_decode": "k_decode_fast<FSink" + ("U16" if w.mode else "Float")}.get(dom, dom + "<")
+        hits = [line.split() for line in open(tfile) if line.startswith(want)]
+        if len(hits) == 1:
+            traffic = int(hits[0][-1])
+            traffic_source = (os.path.relpath(tfile, ROOT) + f" line {hits[0][0]}"
+                              + " (rocprofv3 --pmc runs of this command, recorded earlier; not measured in this run)")
     roof = None
     if dom:
         avg_ms = prof[dom]["total_ms"] / prof[dom]["count"]

@@ -212,28 +212,45 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
         }
       }
     }
-    if (threadIdx.x < 64) {
-      NormArgs nl = na;  // a copy in registers: the argument itself cannot be changed in place
-      nl.lds_cnt = l_cnt;
-      nl.enc_tab = l_tab8;
-      nl.enc_tab4 = (uint4 *)l_tab;
-      nl.quiet = blockIdx.x != 0;
-      nl.entry_checked = 1;
+    NormArgs nl = na;  // a copy in registers: the argument itself cannot be changed in place
+    nl.lds_cnt = l_cnt;
+    nl.enc_tab = l_tab8;
+    nl.enc_tab4 = (uint4 *)l_tab;
+    nl.quiet = blockIdx.x != 0;
+    nl.entry_checked = 1;
+    // Alphabets above 256 symbols (CSR): the wave would make five to eight symbols' entries per lane, so it stops at
+    // the frequencies and the whole work-group makes the entries, a lane per symbol (c2 as CSR: 2 us less).  With
+    // a byte alphabet the wave does it all: the second step's barriers and its instructions on all sixteen waves
+    // of a compute unit cost more than they save there (c5a: 0.8 us more).
+    const bool split = A > 256;
+    nl.fF = split ? (uint2 *)l_tab : nullptr;
+    if (threadIdx.x < 64) {  // frequencies and their running sums: one wave
       const NormResult r = normalize_wave(ctl, nl);
       if (threadIdx.x == 0) {
-        sh[0] = r.ok; sh[1] = r.exact; sh[2] = r.n_chunks;
+        sh[0] = r.ok; sh[1] = split ? 0u : (r.exact ? 0u : 1u); sh[2] = r.n_chunks;
         *(uint64_t *)(sh + 4) = r.len_d; *(uint64_t *)(sh + 6) = r.dir_off; *(uint64_t *)(sh + 8) = r.payload_off;
       }
     }
     __syncthreads();
     const uint32_t ok = sh[0];
-    exact_tab = sh[1]; nc = sh[2];
+    nc = sh[2];
     len = *(const uint64_t *)(sh + 4); dir_off = *(const uint64_t *)(sh + 6); payload_off = *(const uint64_t *)(sh + 8);
     if (!ok) {
       if (FUSE && blockIdx.x == 0 && threadIdx.x == 0 && d_stream_bytes) *d_stream_bytes = 0;
       bail();
       return;
     }
+    if (split) {  // the table entries: every lane its symbol's (a division each), which overwrite {f, F} in the slot
+      int inexact = 0;
+      for (uint32_t a = threadIdx.x; a < A; a += kWG) {
+        const uint2 e = nl.fF[2 * a];
+        inexact |= emit_entries(nl, a, e.x, e.y, [](uint32_t kk, uint32_t d) { return div_pow2_by(kk, d); });
+      }
+      if (inexact) atomicOr(&sh[1], 1u);
+      __syncthreads();
+      if (blockIdx.x == 0 && threadIdx.x == 0) ctl->enc_exact = sh[1] == 0;
+    }
+    exact_tab = sh[1] == 0;
     if (!exact_tab) {
       for (uint32_t a = threadIdx.x; a < A; a += kWG) {
         const uint2 q = l_tab8[a];

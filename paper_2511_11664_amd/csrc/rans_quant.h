@@ -249,6 +249,9 @@ struct NormArgs {
   // compute to themselves.  0: the caller is the table's only builder and writes everything.
   int quiet;
   int entry_checked;  // the caller has looked at the call's status already (set inside the calling kernel)
+  // Set by a kernel whose whole work-group makes the table entries (emit_entries) after one wave has normalised:
+  // the wave then only leaves {f, F} of symbol a in fF[2 a] (the first half of the symbol's 16-byte table slot).
+  uint2 *fF;
 };
 // What the table build leaves in the registers of the wave or work-group that ran it.
 struct NormResult {
@@ -557,7 +560,12 @@ __device__ __forceinline__ NormResult normalize_wave_per(const CtlRef &ctl, cons
     d += take;
   }
   // container geometry
-  const uint64_t n_chunks = len_d == 0 ? 0 : (p.chunk_syms == 0 ? 1 : (len_d + p.chunk_syms - 1) / p.chunk_syms);
+  // l_D < 2^32 (at most 3 * 2^30): a 32-bit division, far shorter than the 64-bit one
+  uint64_t n_chunks = len_d == 0 ? 0 : 1;
+  if (len_d && p.chunk_syms) {
+    const uint32_t qc = (uint32_t)len_d / p.chunk_syms;
+    n_chunks = qc + ((uint32_t)len_d - qc * p.chunk_syms != 0);
+  }
   const uint64_t table_off = kHdrBytes;
   const uint64_t dir_off = table_off + (((uint64_t)A * 2 + 7) & ~7ull);
   const uint64_t payload_off = dir_off + 8 * (n_chunks + 1);
@@ -571,6 +579,22 @@ __device__ __forceinline__ NormResult normalize_wave_per(const CtlRef &ctl, cons
 #pragma unroll
   for (int q = 0; q < PER; q++) mine += f[q];
   uint32_t F = wave_incl_sum_scan(mine) - mine;
+  if (na.fF) {  // the entries are made by the caller's whole work-group
+#pragma unroll
+    for (int q = 0; q < PER; q++) {
+      const uint32_t a = PER * lane + q;
+      if (a < A) na.fF[2 * a] = make_uint2(f[q], F);
+      F += f[q];
+    }
+    if (!na.quiet)
+      for (uint64_t o = table_off + 2ull * A + 2 * lane; o < dir_off; o += 2 * 64) *(uint16_t *)(na.out + o) = 0;
+    res.ok = 1;
+    res.n_chunks = (uint32_t)n_chunks;
+    res.len_d = len_d;
+    res.dir_off = dir_off;
+    res.payload_off = payload_off;
+    return res;
+  }
   int inexact = 0;
 #pragma unroll
   for (int q = 0; q < PER; q++) {

@@ -124,7 +124,7 @@ BENCH_CONFIGS = (
     ("t1_csr4", "t1", dict(mode=MODE_CSR, cols=4)),
     ("c2_csr256", "c2", {}),
     ("c2_csr7", "c2", dict(cols=7, chunk_syms=80 * 1024)),
-    ("c2_csr4", "c2", dict(cols=4, chunk_syms=80 * 1024)),
+    ("c2_csr4", "c2", dict(cols=4, chunk_syms=96 * 1024)),  # l_D = 21.8 M: 223 chunks, one round of the decoder
     ("c2_dense", "c2", dict(mode=MODE_DENSE, chunk_syms=100352)),
     ("c3_csr256_q8", "c3", {}),
     ("c3_csr64_q6", "c3", dict(q_bits=6, cols=64)),

@@ -21,6 +21,27 @@ __device__ __forceinline__ void load16(const uint8_t *p, uint64_t e0, uint64_t n
   }
 }
 
+// The same 16 symbols as four words (symbol k in byte k % 4 of word k / 4).
+__device__ __forceinline__ void load16w(const uint8_t *p, uint64_t e0, uint64_t n, bool aligned, uint32_t out[4]) {
+  if (aligned && e0 + 16 <= n) {
+    const uint4 w = *(const uint4 *)(p + e0);
+    out[0] = w.x; out[1] = w.y; out[2] = w.z; out[3] = w.w;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      uint32_t t = 0;
+#pragma unroll
+      for (int q = 0; q < 4; q++) t |= (e0 + 4 * j + q < n ? (uint32_t)p[e0 + 4 * j + q] : 0u) << (8 * q);
+      out[j] = t;
+    }
+  }
+}
+// Bit q of the result is set when byte q of w is not zero.
+__device__ __forceinline__ uint32_t nonzero_bytes(uint32_t w) {
+  const uint32_t t = (((w & 0x7f7f7f7fu) + 0x7f7f7f7fu) | w) & 0x80808080u;  // bit 7 of every nonzero byte
+  return ((t >> 7) * 0x01020408u) >> 24;  // the four bits gathered: no carries, each partial sum is below 16
+}
+
 // Stream compaction of the nonzero symbols in flat (= row-major) order: v gets the
 // values, c the column indices, row_end[i] the number of nonzeros up to and
 // including row i.  Column indices are histogrammed into cnt on the way.
@@ -30,8 +51,11 @@ __device__ __forceinline__ void load16(const uint8_t *p, uint64_t e0, uint64_t n
 // k_quant_hist has counted the nonzeros of every tile (blk_nnz) and of every group of tiles_per_grp
 // tiles (grp_nnz); the place of the work-group's first tile in v and c is the sum over the groups
 // and then the tiles before it, and every further tile follows the one before.
-// SHORT_ROWS (few columns): a row ends every few symbols; instead of a store behind a branch at every symbol, the
-// lane notes which of its symbols are nonzero and derives its row ends from that mask after the walk.
+// A lane takes 16 consecutive symbols as four words, derives the mask of its nonzero ones with a few word
+// operations and then visits only the set bits (about a third of the symbols of a post-ReLU tensor; a wave
+// runs as many steps as its fullest lane has nonzeros, nine or ten of 16).  Row ends come from the mask
+// afterwards: symbol p ends a row when the lane's first column plus p + 1 is a multiple of K.
+// SHORT_ROWS (few columns): eight counters per column, see below.
 template <bool LDS_HIST, bool SHORT_ROWS = false>
 __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_t n, int aligned, uint32_t K,
                                                      const uint32_t *blk_nnz, const uint32_t *grp_nnz,
@@ -55,8 +79,8 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
   const uint32_t rep_off = SHORT_ROWS ? (threadIdx.x & 7u) * K : 0u;
   const uint32_t t0 = blockIdx.x * tiles_per_wg;  // < n_tiles by the size of the grid
   const uint32_t t1 = t0 + tiles_per_wg < n_tiles ? t0 + tiles_per_wg : n_tiles;
-  uint8_t b[16];
-  load16(sym, (uint64_t)t0 * kCsrTile + threadIdx.x * 16, n, aligned, b);
+  uint32_t w[4];
+  load16w(sym, (uint64_t)t0 * kCsrTile + threadIdx.x * 16, n, aligned, w);
   uint32_t base;
   {
     const uint32_t g0 = t0 / tiles_per_grp;
@@ -71,42 +95,33 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
     for (uint32_t t = g0 * tiles_per_grp + threadIdx.x; t < t0; t += kWG) part += blk_nnz[t];
     base = (uint32_t)block_sum64<kWG>(part, sh64);
   }
+  // (x * inv16) >> 16 = x / K for the x < 32 that occur when K < 16
+  const uint32_t inv16 = 65536u / K + 1u;
   for (uint32_t tile = t0; tile < t1; tile++) {
     const uint64_t e0 = (uint64_t)tile * kCsrTile + threadIdx.x * 16;
-    uint8_t nb[16];  // the next tile's symbols are on their way while this one is placed
-    if (tile + 1 < t1) load16(sym, e0 + kCsrTile, n, aligned, nb);
-    uint32_t cth = 0;
-#pragma unroll
-    for (int k = 0; k < 16; k++) cth += b[k] != 0;
+    uint32_t nw[4];  // the next tile's symbols are on their way while this one is placed
+    if (tile + 1 < t1) load16w(sym, e0 + kCsrTile, n, aligned, nw);
+    // symbols past the end of the tensor read as zero
+    const uint32_t mask = nonzero_bytes(w[0]) | (nonzero_bytes(w[1]) << 4) | (nonzero_bytes(w[2]) << 8) | (nonzero_bytes(w[3]) << 12);
     uint32_t tot;
-    uint32_t loc = block_excl_scan<kWG>(cth, sh, &tot);  // also orders the hist zeroing and the staging reuse
+    const uint32_t loc0 = block_excl_scan<kWG>((uint32_t)__popc(mask), sh, &tot);  // also orders the hist zeroing and the staging reuse
     if (e0 < n) {
-      uint32_t row = (uint32_t)(e0 / K), col = (uint32_t)(e0 - (uint64_t)row * K);
-      const uint32_t col0 = col, loc0 = loc;
-      uint32_t nzmask = 0;
-#pragma unroll
-      for (int k = 0; k < 16; k++) {
-        if (e0 + k < n) {
-          if (b[k]) {
-            s_vc[loc] = b[k] | (col << 8);
-            loc++;
-            if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : slot_of(col)], 1u);
-            else atomicAdd(&cnt[col], 1u);
-            if (SHORT_ROWS) nzmask |= 1u << k;
-          }
-          if (SHORT_ROWS) {
-            col = col + 1 == K ? 0u : col + 1;
-          } else if (++col == K) {
-            row_end[row] = base + loc;
-            col = 0;
-            row++;
-          }
-        }
+      const uint32_t row0 = (uint32_t)(e0 / K), col0 = (uint32_t)(e0 - (uint64_t)row0 * K);
+      uint32_t loc = loc0;
+      for (uint32_t mk = mask; mk; mk &= mk - 1u) {
+        const uint32_t k = (uint32_t)__ffs((int)mk) - 1u;
+        const uint32_t wk = k < 8 ? (k < 4 ? w[0] : w[1]) : (k < 12 ? w[2] : w[3]);
+        const uint32_t val = (wk >> (8 * (k & 3u))) & 0xffu;
+        uint32_t col = col0 + k;
+        if (K >= 16) col -= col >= K ? K : 0u;
+        else col -= K * ((col * inv16) >> 16);
+        s_vc[loc++] = val | (col << 8);
+        if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : slot_of(col)], 1u);
+        else atomicAdd(&cnt[col], 1u);
       }
-      if (SHORT_ROWS) {  // symbol p ends a row when col0 + p + 1 is a multiple of K
-        for (uint32_t p = K - 1 - col0; p < 16 && e0 + p < n; p += K)
-          row_end[row++] = base + loc0 + (uint32_t)__popc(nzmask & ((2u << p) - 1u));
-      }
+      uint32_t row = row0;
+      for (uint32_t p = K - 1 - col0; p < 16 && e0 + p < n; p += K)
+        row_end[row++] = base + loc0 + (uint32_t)__popc(mask & ((2u << p) - 1u));
     }
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < tot; i += kWG) {
@@ -117,7 +132,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
     base += tot;
     if (tile + 1 < t1) {
 #pragma unroll
-      for (int k = 0; k < 16; k++) b[k] = nb[k];
+      for (int k = 0; k < 4; k++) w[k] = nw[k];
     }
     __syncthreads();  // staging and scan scratch are reused by the next tile
   }

@@ -249,6 +249,52 @@ def test_edge_cases():
     _check_all(x, B.make_params(2, 12, rows, cols, B.MODE_CSR, 32, 0, B.F32), "deficit")
 
 
+def _inexact_entries(container: bytes, A: int, M: int) -> int:
+    """Symbols whose division-free multiplier (Eq. 2 as multiply-high and shift) is not exact for every state the
+    coder can meet: computed from the stored frequency table, with the condition the table kernels state."""
+    f = np.frombuffer(container[128:128 + 2 * A], dtype="<u2").astype(np.int64)
+    bad = 0
+    for fa in f:
+        fa = int(fa)
+        if fa < 2 or fa & (fa - 1) == 0:
+            continue
+        k = fa.bit_length() - 1
+        two = 1 << (32 + k)
+        e = (two // fa + 1) * fa - two
+        bad += ((fa << (32 - M)) - 1) * e >= two
+    return bad
+
+
+def test_both_table_forms_and_the_alphabet_switches():
+    """The encoder builds its table itself for alphabets up to 512 symbols (one wave up to 256, wave plus work-group
+    above), k_normalize above that; a frequency table with a multiplier that is not exact makes the coder use its other
+    table form.  Every combination has to give the oracle's bytes."""
+    n = 60000
+    forms = set()
+    for seed, dens in ((1, 0.004), (2, 0.01), (3, 0.02), (4, 0.03), (5, 0.05), (6, 0.08)):
+        g = torch.Generator().manual_seed(100 + seed)
+        x = torch.relu(torch.randn(n, generator=g)) * (torch.rand(n, generator=g) < dens)
+        p = B.make_params(8, 12, n, 1, B.MODE_DENSE, 64, 4096, B.F32)
+        ref, _ = oracle.compress(x.numpy(), _oparams(p))
+        forms.add((256, _inexact_entries(ref, 256, 12) > 0))
+        _check_all(x, p, f"dominant symbol d={dens} A=256")
+    # the same for a 301-symbol alphabet: 2000 rows of 300 columns, nearly all of them empty (r = 0 dominates D)
+    N, K = 2000, 300
+    for seed, dens in ((1, 0.0001), (3, 0.0001), (4, 0.0002), (5, 0.00005), (6, 0.0002)):
+        g = torch.Generator().manual_seed(200 + seed)
+        x = torch.relu(torch.randn(N * K, generator=g)) * (torch.rand(N * K, generator=g) < dens)
+        p = B.make_params(8, 12, N, K, B.MODE_CSR, 64, 4096, B.F32)
+        ref, _ = oracle.compress(x.numpy(), _oparams(p))
+        forms.add((301, _inexact_entries(ref, 301, 12) > 0))
+        _check_all(x, p, f"dominant symbol d={dens} A=301")
+    assert {(256, True), (256, False), (301, True), (301, False)} <= forms, forms
+    # alphabet sizes on both sides of the switches (CSR: A = K + 1 for K >= 2^Q)
+    for K in (255, 256, 511, 512, 1023, 1024, 1500):
+        rows = 40
+        x = _relu_normal(rows * K, 7 + K)
+        _check_all(x, B.make_params(8, 12, rows, K, B.MODE_CSR, 32, 2048, B.F32), f"alphabet {K + 1}")
+
+
 def test_table_divisions_equal_integer_division():
     """The frequency-table kernels divide through a reciprocal estimate and an exact remainder check; on the device
     that runs them: every divisor of the encoder's multipliers (Eq. 2), and 2^24 quotients of the kind Sec. 3.2's

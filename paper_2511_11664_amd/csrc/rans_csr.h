@@ -42,6 +42,44 @@ __device__ __forceinline__ uint32_t nonzero_bytes(uint32_t w) {
   return ((t >> 7) * 0x01020408u) >> 24;  // the four bits gathered: no carries, each partial sum is below 16
 }
 
+// Rows of KK columns with KK dividing 16 lie inside a lane's 16 symbols: their counts r (Sec. 3.1, the
+// non-cumulative row counts) are the population counts of KK-bit fields of the lane's nonzero mask.  The lane
+// stores them (consecutive lanes, consecutive rows: one store of up to 16 bytes each) and counts them in an LDS
+// histogram of eight counters per value, one per lane residue.
+template <uint32_t KK>
+__device__ __forceinline__ void rows_inside_lane(uint32_t mask, uint64_t e0, uint32_t n, uint16_t *r, uint32_t *s_r,
+                                                 uint32_t lane_rep) {
+  constexpr uint32_t NF = 16 / KK;
+  const uint32_t row0 = (uint32_t)(e0 / KK);
+  uint32_t v[NF];
+#pragma unroll
+  for (uint32_t f = 0; f < NF; f++) v[f] = (uint32_t)__popc((mask >> (f * KK)) & ((1u << KK) - 1u));
+  const bool full = e0 + 16 <= n;  // n is a multiple of KK: otherwise whole rows are missing at the end
+  if (full) {
+    if constexpr (NF == 1) {
+      r[row0] = (uint16_t)v[0];
+    } else {
+      uint32_t w[NF / 2];
+#pragma unroll
+      for (uint32_t q = 0; q < NF / 2; q++) w[q] = v[2 * q] | (v[2 * q + 1] << 16);
+      if constexpr (NF == 2) *(uint32_t *)(r + row0) = w[0];
+      else if constexpr (NF == 4) *(uint2 *)(r + row0) = make_uint2(w[0], w[1]);
+      else if constexpr (NF == 8) *(uint4 *)(r + row0) = make_uint4(w[0], w[1], w[2], w[3]);
+      else {
+        *(uint4 *)(r + row0) = make_uint4(w[0], w[1], w[2], w[3]);
+        *(uint4 *)(r + row0 + 8) = make_uint4(w[4], w[5], w[6], w[7]);
+      }
+    }
+  }
+#pragma unroll
+  for (uint32_t f = 0; f < NF; f++) {
+    if (full || e0 + f * KK < n) {
+      if (!full) r[row0 + f] = (uint16_t)v[f];
+      atomicAdd(&s_r[v[f] + lane_rep * (KK + 1)], 1u);
+    }
+  }
+}
+
 // Stream compaction of the nonzero symbols in flat (= row-major) order: v gets the
 // values, c the column indices, row_end[i] the number of nonzeros up to and
 // including row i.  Column indices are histogrammed into cnt on the way.
@@ -61,8 +99,13 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
                                                      const uint32_t *blk_nnz, const uint32_t *grp_nnz,
                                                      uint32_t tiles_per_grp, uint8_t *v, uint16_t *c,
                                                      uint32_t *row_end, uint32_t *cnt, uint32_t A, uint32_t n_tiles,
-                                                     uint32_t tiles_per_wg, uint32_t n_rep) {
+                                                     uint32_t tiles_per_wg, uint32_t n_rep, int rows_in_lane,
+                                                     uint16_t *r, uint32_t N, CtlRef ctl) {
   extern __shared__ uint32_t hist[];
+  // rows_in_lane (K divides 16): the row counts, their histogram and l_D come from this kernel, and neither the
+  // row ends nor k_csr_rows are needed
+  __shared__ uint32_t s_r[17 * 8];
+  if (threadIdx.x < 17 * 8) s_r[threadIdx.x] = 0;  // ordered before its use by the barriers of the first tile
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
   __shared__ uint32_t s_vc[kCsrTile];  // value | column << 8 of the tile's nonzeros, in order (one LDS write each)
@@ -119,9 +162,18 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
         if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : slot_of(col)], 1u);
         else atomicAdd(&cnt[col], 1u);
       }
-      uint32_t row = row0;
-      for (uint32_t p = K - 1 - col0; p < 16 && e0 + p < n; p += K)
-        row_end[row++] = base + loc0 + (uint32_t)__popc(mask & ((2u << p) - 1u));
+      if (rows_in_lane) {  // uniform
+        const uint32_t lr = threadIdx.x & 7u;
+        if (K == 4) rows_inside_lane<4>(mask, e0, n, r, s_r, lr);
+        else if (K == 2) rows_inside_lane<2>(mask, e0, n, r, s_r, lr);
+        else if (K == 8) rows_inside_lane<8>(mask, e0, n, r, s_r, lr);
+        else if (K == 16) rows_inside_lane<16>(mask, e0, n, r, s_r, lr);
+        else rows_inside_lane<1>(mask, e0, n, r, s_r, lr);
+      } else {
+        uint32_t row = row0;
+        for (uint32_t p = K - 1 - col0; p < 16 && e0 + p < n; p += K)
+          row_end[row++] = base + loc0 + (uint32_t)__popc(mask & ((2u << p) - 1u));
+      }
     }
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < tot; i += kWG) {
@@ -135,6 +187,20 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
       for (int k = 0; k < 4; k++) w[k] = nw[k];
     }
     __syncthreads();  // staging and scan scratch are reused by the next tile
+  }
+  if (rows_in_lane) {
+    __syncthreads();
+    uint32_t *dst_r = cnt + (n_rep ? (size_t)(1 + blockIdx.x % n_rep) * A : 0);
+    if (threadIdx.x <= K) {
+      uint32_t t = 0;
+#pragma unroll
+      for (uint32_t q = 0; q < 8; q++) t += s_r[threadIdx.x + q * (K + 1)];
+      if (t) atomicAdd(&dst_r[threadIdx.x], t);
+    }
+    if (t1 == n_tiles && threadIdx.x == 0) {  // the work-group with the last tile knows the number of nonzeros
+      ctl->nnz = base;
+      ctl->len_d = 2ull * base + N;
+    }
   }
   if (LDS_HIST) {
     // into one of the partial histograms: a thousand work-groups adding to the same few hundred addresses

@@ -228,16 +228,19 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       const uint32_t tpw = (L.n_blk + kCompactBlocks - 1) / kCompactBlocks;  // consecutive tiles per work-group
       const uint32_t g_compact = (L.n_blk + tpw - 1) / tpw;
       const uint32_t *grp = grp_counts_of(L, ws);
+      // rows that lie inside a lane's 16 symbols: the compaction also produces the row counts (see rows_inside_lane)
+      const int rows_in_lane = p.cols <= 16 && 16 % p.cols == 0;
       if (lds_hist && p.cols <= kShortRowCols && 8ull * p.cols <= A)
         PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true, true>), dim3(g_compact), dim3(kWG), ((A + 15u) & ~15u) * 4, st, d_sym, (uint32_t)n, al,
-                           (uint32_t)p.cols, blk, grp, tiles_per_grp, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, tpw, L.cnt_rep);
+                           (uint32_t)p.cols, blk, grp, tiles_per_grp, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, tpw, L.cnt_rep, rows_in_lane, (uint16_t *)(ws + L.r), (uint32_t)p.rows, ctl);
       else if (lds_hist)
         PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true>), dim3(g_compact), dim3(kWG), ((A + 15u) & ~15u) * 4, st, d_sym, (uint32_t)n, al,
-                           (uint32_t)p.cols, blk, grp, tiles_per_grp, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, tpw, L.cnt_rep);
+                           (uint32_t)p.cols, blk, grp, tiles_per_grp, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, tpw, L.cnt_rep, rows_in_lane, (uint16_t *)(ws + L.r), (uint32_t)p.rows, ctl);
       else
         PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<false>), dim3(g_compact), dim3(kWG), 0, st, d_sym, (uint32_t)n, al,
-                           (uint32_t)p.cols, blk, grp, tiles_per_grp, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, tpw, L.cnt_rep);
+                           (uint32_t)p.cols, blk, grp, tiles_per_grp, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, tpw, L.cnt_rep, rows_in_lane, (uint16_t *)(ws + L.r), (uint32_t)p.rows, ctl);
       LAUNCH_CHECK();
+      if (!rows_in_lane) {
       uint32_t N = (uint32_t)p.rows;
       uint32_t g = (N + 16 * kWG - 1) / (16 * kWG);  // a lane takes 16 rows per step
       // few work-groups: each ends with additions to the same few addresses
@@ -250,6 +253,7 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       else
         PROF_LAUNCH(KID_CSR_ROWS, (k_csr_rows<false>), dim3(g), dim3(kWG), 0, st, row_end, N, (uint16_t *)(ws + L.r), cnt, A, ctl, (uint32_t)p.cols, L.cnt_rep);
       LAUNCH_CHECK();
+      }
     }
   }
   // D's histogram is complete here (the kernels that counted end before the next one starts).  Alphabets

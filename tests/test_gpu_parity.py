@@ -141,6 +141,11 @@ CSR_CASES = [
     # few chunks of many streams (ragged last group of the decoder), alphabet of 257 symbols at M = 14 and 12
     (2000, 256, torch.float16, 8, 14, 600, 600 * 100),
     (2000, 256, torch.float32, 8, 12, 1000, 0),
+    # rows inside a lane's 16 symbols (K divides 16: the compaction kernel also makes the row counts), ragged ends
+    (4099, 2, torch.float32, 8, 12, 64, 1024),
+    (1237, 8, torch.float16, 8, 12, 32, 0),
+    (20001, 4, torch.float32, 3, 11, 128, 4096),
+    (333, 16, torch.float32, 8, 12, 64, 2048),
 ]
 
 

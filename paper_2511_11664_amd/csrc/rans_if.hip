@@ -192,8 +192,8 @@ int launch_quantize(const void *d_x, uint64_t n, const rans_params &p, const Lay
     LAUNCH_CHECK();
   }
   if (n) {
-    uint32_t g = grid_for(n, QNT * V * kQIter, kQuantBlocks);
     int skip0 = p.mode == RANS_MODE_CSR;
+    uint32_t g = grid_for(n, QNT * V * kQIter, skip0 ? kQuantBlocksCsr : kQuantBlocks);
     auto launch_qh = [&](auto csr_tag) {
       constexpr bool CSRV = decltype(csr_tag)::value;
       if (f16) {
@@ -888,8 +888,8 @@ int rans_encode(const uint8_t *d_sym, uint64_t n_elems, const rans_params *p, co
   LAUNCH_CHECK();
   if (n_elems) {
     const bool vec = aligned_to(d_sym, 16);
-    const uint32_t g = grid_for(n_elems, QNT * (vec ? 16 : 1) * kQIter, kQuantBlocks);
     const int skip0 = p->mode == RANS_MODE_CSR;
+    const uint32_t g = grid_for(n_elems, QNT * (vec ? 16 : 1) * kQIter, skip0 ? kQuantBlocksCsr : kQuantBlocks);
     auto launch_qh = [&](auto csr_tag) {
       constexpr bool CSRV = decltype(csr_tag)::value;
       if (vec)

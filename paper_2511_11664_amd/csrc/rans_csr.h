@@ -102,9 +102,12 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
                                                      uint32_t tiles_per_wg, uint32_t n_rep, int rows_in_lane,
                                                      uint16_t *r, uint32_t N, CtlRef ctl) {
   extern __shared__ uint32_t hist[];
-  // rows_in_lane (K divides 16): the row counts, their histogram and l_D come from this kernel, and neither the
-  // row ends nor k_csr_rows are needed
+  // rows_in_lane: 1 (K divides 16) or 2 (K divides the tile of 4096 symbols, 64 <= K, so that every tile starts a
+  // row and holds at most 64 of them): the row counts, their histogram and l_D come from this kernel, and neither
+  // the row ends nor k_csr_rows are needed.  2: the lane that holds a row's last symbol leaves the number of the
+  // tile's nonzeros up to there in LDS, and after the tile's barrier a thread per row takes the difference.
   __shared__ uint32_t s_r[17 * 8];
+  __shared__ uint32_t s_rowend[64];
   if (threadIdx.x < 17 * 8) s_r[threadIdx.x] = 0;  // ordered before its use by the barriers of the first tile
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
@@ -162,7 +165,10 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
         if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : slot_of(col)], 1u);
         else atomicAdd(&cnt[col], 1u);
       }
-      if (rows_in_lane) {  // uniform
+      if (rows_in_lane == 2) {  // uniform; one row end per lane at most
+        const uint32_t p = K - 1 - col0;
+        if (p < 16) s_rowend[row0 - (uint32_t)((uint64_t)tile * kCsrTile / K)] = loc0 + (uint32_t)__popc(mask & ((2u << p) - 1u));
+      } else if (rows_in_lane) {
         const uint32_t lr = threadIdx.x & 7u;
         if (K == 4) rows_inside_lane<4>(mask, e0, n, r, s_r, lr);
         else if (K == 2) rows_inside_lane<2>(mask, e0, n, r, s_r, lr);
@@ -176,6 +182,14 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
       }
     }
     __syncthreads();
+    if (rows_in_lane == 2) {
+      const uint32_t row_t0 = (uint32_t)((uint64_t)tile * kCsrTile / K), row = row_t0 + threadIdx.x;
+      if (threadIdx.x < kCsrTile / K && row < N) {
+        const uint32_t rj = s_rowend[threadIdx.x] - (threadIdx.x ? s_rowend[threadIdx.x - 1] : 0u);
+        r[row] = (uint16_t)rj;
+        atomicAdd(&hist[slot_of(rj)], 1u);  // the same alphabet as the columns: one histogram for all of D
+      }
+    }
     for (uint32_t i = threadIdx.x; i < tot; i += kWG) {
       const uint32_t vc = s_vc[i];
       v[base + i] = (uint8_t)vc;
@@ -191,7 +205,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
   if (rows_in_lane) {
     __syncthreads();
     uint32_t *dst_r = cnt + (n_rep ? (size_t)(1 + blockIdx.x % n_rep) * A : 0);
-    if (threadIdx.x <= K) {
+    if (rows_in_lane == 1 && threadIdx.x <= K) {
       uint32_t t = 0;
 #pragma unroll
       for (uint32_t q = 0; q < 8; q++) t += s_r[threadIdx.x + q * (K + 1)];

@@ -229,7 +229,11 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       const uint32_t g_compact = (L.n_blk + tpw - 1) / tpw;
       const uint32_t *grp = grp_counts_of(L, ws);
       // rows that lie inside a lane's 16 symbols: the compaction also produces the row counts (see rows_inside_lane)
-      const int rows_in_lane = p.cols <= 16 && 16 % p.cols == 0;
+      // or inside a tile whose every start is a row start (the LDS column histogram in its plain layout also takes
+      // the row counts then): see k_csr_compact
+      const bool short_rows = lds_hist && p.cols <= kShortRowCols && 8ull * p.cols <= A;
+      const int rows_in_lane = (p.cols <= 16 && 16 % p.cols == 0) ? 1
+                               : (lds_hist && !short_rows && p.cols >= 64 && kCsrTile % p.cols == 0) ? 2 : 0;
       if (lds_hist && p.cols <= kShortRowCols && 8ull * p.cols <= A)
         PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true, true>), dim3(g_compact), dim3(kWG), ((A + 15u) & ~15u) * 4, st, d_sym, (uint32_t)n, al,
                            (uint32_t)p.cols, blk, grp, tiles_per_grp, ws + L.v, (uint16_t *)(ws + L.c), row_end, cnt, A, L.n_blk, tpw, L.cnt_rep, rows_in_lane, (uint16_t *)(ws + L.r), (uint32_t)p.rows, ctl);

@@ -106,7 +106,7 @@ _RECIPES = {
     "t1": ((1, 128, 28, 28), torch.float32, 6, _c1, 8, 12, 64, 64 * 64, MODE_DENSE, 784),
     # c2: the configured "rows = 256" would need 100 352 column symbols (more than the 65 535 a 16-bit symbol
     # allows, and than any 2^12 table holds); it is run as N x 256 instead
-    "c2": ((32, 256, 56, 56), torch.float32, 1, _c2, 8, 12, 1024, 1 << 16, MODE_CSR, 256),
+    "c2": ((32, 256, 56, 56), torch.float32, 1, _c2, 8, 12, 1024, 80 * 1024, MODE_CSR, 256),
     "c3": ((64, 512, 28, 28), torch.float32, 2, _c3, 8, 14, 1024, 80 * 1024, MODE_CSR, 256),
     "c4": ((16, 3136, 96), torch.float32, 3, _c4, 8, 12, 1024, 1 << 18, MODE_DENSE, 96),
     "c5a": ((8, 2048, 4096), torch.float16, 4, _c5, 8, 14, 1024, 1 << 18, MODE_DENSE, 4096),

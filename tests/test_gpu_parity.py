@@ -146,6 +146,10 @@ CSR_CASES = [
     (1237, 8, torch.float16, 8, 12, 32, 0),
     (20001, 4, torch.float32, 3, 11, 128, 4096),
     (333, 16, torch.float32, 8, 12, 64, 2048),
+    # rows that start with a tile of 4096 symbols (K divides 4096, K >= 64): row counts from the tile's own prefix
+    (37, 4096, torch.float32, 8, 13, 64, 4096),
+    (5, 2048, torch.float16, 8, 12, 32, 0),
+    (129, 128, torch.float32, 8, 12, 64, 1024),
 ]
 
 

@@ -52,12 +52,12 @@ namespace {
 enum KernelId {
   KID_MINMAX = 0, KID_QINFO, KID_QUANT_HIST, KID_SCAN, KID_CSR_COMPACT, KID_CSR_ROWS,
   KID_NORMALIZE, KID_ENCODE, KID_CHUNK_SCAN, KID_GATHER, KID_DEC_PREPARE, KID_DECODE, KID_ROW_SCAN,
-  KID_CSR_EXPAND, KID_DEQUANT, KID_RS_MASK, KID_RS_COLS, KID_RS_ROWS, KID_RS_COST, KID_COUNT
+  KID_CSR_EXPAND, KID_DEQUANT, KID_RS_MASK, KID_RS_COLS, KID_RS_ROWS, KID_RS_COST, KID_RS_ROWS_POW2, KID_COUNT
 };
 const char *const kKernelNames[KID_COUNT] = {
     "k_minmax", "k_qinfo", "k_quant_hist", "k_scan_u32", "k_csr_compact", "k_csr_rows",
     "k_normalize", "k_encode", "k_chunk_scan", "k_gather", "k_dec_prepare", "k_decode", "k_row_part",
-    "k_csr_to_dense", "k_dequant", "k_rs_mask", "k_rs_cols", "k_rs_rows", "k_rs_cost"};
+    "k_csr_to_dense", "k_dequant", "k_rs_mask", "k_rs_cols", "k_rs_rows", "k_rs_cost", "k_rs_rows_pow2"};
 
 struct ProfRecord {
   int kid;
@@ -703,6 +703,8 @@ struct RsPlan {
   RsCands cands;
   RsOffsets offs;
   RsGroups grps;
+  RsPow2 pow2;    // candidates whose row counts k_rs_rows_pow2 takes from the mask
+  bool any_pow2;
   uint32_t n_entries, n_tiles;
   size_t mask16, lp, tile_cnt, zero0, hv, hl, hr, bad, costs, ticket, total;  // byte offsets in the workspace
   uint32_t zero_words;
@@ -739,16 +741,25 @@ RsPlan rs_plan(uint64_t n, uint32_t q_bits) {
   P.offs.hr[P.cands.n] = orr;
   {  // work-groups of k_rs_rows: about kRowsGrid in all, shared out by the number of rows (K = 1 needs one)
     constexpr uint64_t kRowsGrid = 4096;
+    // K = 1 has a closed form and K = 2, 4, 8, 16 a kernel of their own: no rows for k_rs_rows
+    auto rows_of = [&](uint32_t K) -> uint64_t { return (K == 1 || K == 2 || K == 4 || K == 8 || K == 16) ? 0 : n / K; };
+    for (uint32_t i = 0; i < 4; i++) P.pow2.hr_at[i] = ~0u;
+    for (uint32_t k = 0; k < P.cands.n; k++)
+      for (uint32_t i = 0; i < 4; i++)
+        if (P.cands.K[k] == (2u << i)) {
+          P.pow2.hr_at[i] = P.offs.hr[k];
+          P.any_pow2 = true;
+        }
     uint64_t rows_all = 0;
-    for (uint32_t k = 0; k < P.cands.n; k++) rows_all += P.cands.K[k] > 1 ? n / P.cands.K[k] : 0;
+    for (uint32_t k = 0; k < P.cands.n; k++) rows_all += rows_of(P.cands.K[k]);
     uint32_t w = 0;
     for (uint32_t k = 0; k < P.cands.n; k++) {
       P.offs.wg0[k] = w;
-      const uint64_t rows = P.cands.K[k] > 1 ? n / P.cands.K[k] : 0;
+      const uint64_t rows = rows_of(P.cands.K[k]);
       const uint64_t need = (rows + 4 * 63 - 1) / (4 * 63);  // work-groups that have a row at all
       uint64_t share = rows_all ? (rows * kRowsGrid + rows_all - 1) / rows_all : 1;
       share = share > need ? need : share;
-      w += (uint32_t)(share < 1 ? 1 : share);
+      w += (uint32_t)((share < 1 && (rows || P.cands.K[k] == 1)) ? 1 : share);  // K = 1 keeps one work-group for its closed form
     }
     P.offs.wg0[P.cands.n] = w;
   }
@@ -833,7 +844,13 @@ int launch_search_reshape(const uint8_t *d_sym, uint64_t n, uint32_t q_bits, ran
       LAUNCH_CHECK();
     }
   }
-  if (P.cands.n) {
+  if (P.any_pow2) {
+    const uint32_t n_cu = compute_units();
+    PROF_LAUNCH(KID_RS_ROWS_POW2, k_rs_rows_pow2, dim3(grid_for((P.n_entries + 7) / 8, kWG, n_cu ? n_cu : 256)), dim3(kWG), 0, st,
+                mask16, P.n_entries, (uint32_t)n, P.pow2, hr);
+    LAUNCH_CHECK();
+  }
+  if (P.cands.n && P.offs.wg0[P.cands.n]) {
     PROF_LAUNCH(KID_RS_ROWS, k_rs_rows, dim3(P.offs.wg0[P.cands.n]), dim3(kWG), 0, st, mask16, lp, tile_cnt,
                 (uint32_t)n, P.n_tiles, P.cands, P.offs, hr);
     LAUNCH_CHECK();

@@ -132,6 +132,96 @@ __global__ __launch_bounds__(kWG) void k_rs_cols(const uint16_t *mask16, uint32_
   }
 }
 
+// Row-count histograms of the candidates K = 2, 4, 8, 16 (those of them in the domain: hr_at[i] is the first bin of
+// K = 2 << i, ~0 for none), straight from the zero mask: such rows are K-bit fields of a mask word, and their
+// counts are population counts of the fields - taken for all fields of a 32-position word at once, with word
+// operations for K = 2 and 4 (how many fields hold 1, 2, ... set bits) and per field for K = 8 and 16.  These
+// candidates have the most rows; k_rs_rows, which looks up two prefix counts per row, is left with the others.
+struct RsPow2 {
+  uint32_t hr_at[4];
+};
+__global__ __launch_bounds__(kWG) void k_rs_rows_pow2(const uint16_t *mask16, uint32_t n_entries, uint32_t n, RsPow2 at,
+                                                      uint32_t *hr) {
+  __shared__ uint32_t s_h[4][17 * 8];  // eight counters per value, one per lane residue
+  for (uint32_t i = threadIdx.x; i < 4 * 17 * 8; i += kWG) (&s_h[0][0])[i] = 0;
+  __syncthreads();
+  const uint32_t rp = threadIdx.x & 7u;
+  const uint32_t n_oct = (n_entries + 7) / 8;
+  uint32_t c2[3] = {0, 0, 0}, c4[5] = {0, 0, 0, 0, 0};
+  for (uint32_t o = blockIdx.x * kWG + threadIdx.x; o < n_oct; o += gridDim.x * kWG) {
+    uint32_t w[4];
+    if (8 * o + 8 <= n_entries) {
+      const uint4 q = *(const uint4 *)(mask16 + 8 * (size_t)o);
+      w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        const uint32_t e = 8 * o + 2 * j;
+        w[j] = (e < n_entries ? mask16[e] : 0u) | ((e + 1 < n_entries ? (uint32_t)mask16[e + 1] : 0u) << 16);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const uint64_t p0 = ((uint64_t)o * 4 + j) * 32;  // first position of the word
+      const uint32_t m = w[j];
+      if (p0 + 32 <= n) {  // all of the word's rows exist (n is a multiple of every K here)
+        if (at.hr_at[0] != ~0u) {
+          const uint32_t x = m & 0x55555555u, y = (m >> 1) & 0x55555555u;
+          const uint32_t two = (uint32_t)__popc(x & y), one = (uint32_t)__popc(x ^ y);
+          c2[2] += two; c2[1] += one; c2[0] += 16u - two - one;
+        }
+        uint32_t t = m - ((m >> 1) & 0x55555555u);
+        t = (t & 0x33333333u) + ((t >> 2) & 0x33333333u);  // eight fields of four bits: their population counts (0 .. 4)
+        if (at.hr_at[1] != ~0u) {
+          uint32_t rest = 8;
+#pragma unroll
+          for (uint32_t v = 1; v <= 4; v++) {
+            const uint32_t z = t ^ (v * 0x11111111u);
+            const uint32_t ne = (z | (z >> 1) | (z >> 2)) & 0x11111111u;  // bit 3 of a field is never set
+            const uint32_t eq = 8u - (uint32_t)__popc(ne);
+            c4[v] += eq;
+            rest -= eq;
+          }
+          c4[0] += rest;
+        }
+        if (at.hr_at[2] != ~0u) {
+          const uint32_t b = (t + (t >> 4)) & 0x0f0f0f0fu;  // four fields of eight bits
+#pragma unroll
+          for (int f = 0; f < 4; f++) atomicAdd(&s_h[2][((b >> (8 * f)) & 0xffu) * 8 + rp], 1u);
+        }
+        if (at.hr_at[3] != ~0u) {
+          atomicAdd(&s_h[3][(uint32_t)__popc(m & 0xffffu) * 8 + rp], 1u);
+          atomicAdd(&s_h[3][(uint32_t)__popc(m >> 16) * 8 + rp], 1u);
+        }
+      } else if (p0 < n) {  // the word with the end of the tensor: row by row
+#pragma unroll
+        for (uint32_t i = 0; i < 4; i++) {
+          if (at.hr_at[i] == ~0u) continue;
+          const uint32_t K = 2u << i;
+          for (uint32_t q = 0; q < 32 && p0 + q < n; q += K)
+            atomicAdd(&s_h[i][(uint32_t)__popc((m >> q) & ((1u << K) - 1u)) * 8 + rp], 1u);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (uint32_t v = 0; v < 3; v++)
+    if (c2[v]) atomicAdd(&s_h[0][v * 8 + rp], c2[v]);
+#pragma unroll
+  for (uint32_t v = 0; v < 5; v++)
+    if (c4[v]) atomicAdd(&s_h[1][v * 8 + rp], c4[v]);
+  __syncthreads();
+  if (threadIdx.x < 4 * 17) {
+    const uint32_t i = threadIdx.x / 17, v = threadIdx.x % 17;
+    if (at.hr_at[i] != ~0u && v <= (2u << i)) {
+      uint32_t t = 0;
+#pragma unroll
+      for (int q = 0; q < 8; q++) t += s_h[i][v * 8 + q];
+      if (t) atomicAdd(&hr[at.hr_at[i] + v], t);
+    }
+  }
+}
+
 // nonzeros before position g (g <= n)
 __device__ __forceinline__ uint32_t rs_prefix(uint32_t g, uint32_t n, uint32_t nnz, const uint16_t *mask16,
                                               const uint16_t *lp, const uint32_t *tile_off) {
@@ -165,6 +255,42 @@ __global__ __launch_bounds__(kWG) void k_rs_rows(const uint16_t *mask16, const u
   __syncthreads();
   const uint32_t N = n / K;
   const uint32_t lane = threadIdx.x & 63;
+  if (K < 16) {
+    // Short rows that are not aligned fields of a mask word (K = 7, 14, ...): a row's count is the population
+    // count of K bits of a 32-bit window over two mask entries.  A wave's additions to the few bins of such a
+    // histogram are performed one after the other in LDS, so every lane counts in registers instead - one byte
+    // per value in two 64-bit words - and the wave adds its lanes' bytes up every 255 rows at the latest.
+    uint64_t pk0 = 0, pk1 = 0;
+    auto flush = [&]() {
+      for (uint32_t v = 0; v <= K; v++) {  // uniform
+        const uint32_t mine = (uint32_t)((v < 8 ? pk0 : pk1) >> (8 * (v & 7u))) & 0xffu;
+        const uint32_t tot = wave_incl_sum_scan(mine);
+        if (lane == 63 && tot) atomicAdd(&h[v], tot);
+      }
+      pk0 = pk1 = 0;
+    };
+    const uint32_t n_entries = (n + 15) / 16;
+    const uint32_t stride = gx * kWG;
+    const uint32_t n_it = (N + stride - 1) / stride;  // the same for every thread
+    for (uint32_t it = 0; it < n_it; it++) {
+      const uint32_t i = bx * kWG + threadIdx.x + it * stride;
+      if (i < N) {
+        const uint32_t g = i * K, e = g >> 4;  // i K < n <= 2^30
+        const uint32_t win = (uint32_t)mask16[e] | (e + 1 < n_entries ? (uint32_t)mask16[e + 1] << 16 : 0u);
+        const uint32_t r = (uint32_t)__popc((win >> (g & 15u)) & ((1u << K) - 1u));
+        if (r < 8) pk0 += 1ull << (8 * r);
+        else pk1 += 1ull << (8 * (r - 8));
+      }
+      if ((it & 255u) == 254u) flush();
+    }
+    flush();
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i <= K; i += kWG) {
+      const uint32_t t = h[i];
+      if (t) atomicAdd(&out[i], t);
+    }
+    return;
+  }
   const uint32_t waves = gx * (kWG / 64);
   // four groups of 63 rows per step, their look-ups in flight together
   constexpr uint32_t kU = 4;

@@ -13,7 +13,7 @@ constexpr uint32_t kHdrBytes = 128;
 constexpr uint32_t kLdsHistMaxA = 8192; // alphabets up to this size keep histograms / tables in LDS
 constexpr uint64_t kMaxElems = 1ull << 30;
 constexpr uint32_t kFusedGatherMax = 16384;  // encoder work-groups up to which the encoder places its words itself
-constexpr uint32_t kMaxParts = 1024;    // work-groups (partial results) of the min/max kernel
+constexpr uint32_t kMaxParts = 512;     // work-groups (partial results) of the min/max kernel: two per compute unit read fastest
 
 // ------------------------------------------------------------------ workspace
 

@@ -161,6 +161,22 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4))) void k
     bail();
     return;
   }
+  // The grid is sized for the longest D the tensor could have (in CSR mode the host does not know the number of
+  // nonzeros): a work-group whose chunk does not exist leaves before the table build, not after it.  l_D is
+  // known here - the CSR kernels stored it - and with it the number of chunks.
+  // (A dense grid has exactly one work-group per part of a chunk: nothing to leave, and no load to wait for.)
+  if (!std::is_same<Src, SrcDense>::value) {
+    const uint64_t len_pre = ctl->len_d;
+    uint32_t nc_pre = len_pre ? 1u : 0u;
+    if (len_pre && cs) {
+      const uint32_t qc = (uint32_t)len_pre / cs;  // l_D < 2^32
+      nc_pre = qc + ((uint32_t)len_pre - qc * cs != 0);
+    }
+    if (k >= nc_pre && blockIdx.x != 0) {  // the first work-group stays: it writes the header whatever l_D is
+      bail();
+      return;
+    }
+  }
   const uint32_t sh_lim = 32 - M, totalM = 1u << M;
   // LDS: [guard][word areas][table][reduction scratch][symbol stage].  The areas come first so that a slot
   // address is the lane's fixed base plus twice the slot number; what follows them is reused as the tile of

@@ -102,9 +102,9 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
                                                      uint32_t tiles_per_wg, uint32_t n_rep, int rows_in_lane,
                                                      uint16_t *r, uint32_t N, CtlRef ctl) {
   extern __shared__ uint32_t hist[];
-  // rows_in_lane: 1 (K divides 16) or 2 (K divides the tile of 4096 symbols, 64 <= K, so that every tile starts a
-  // row and holds at most 64 of them): the row counts, their histogram and l_D come from this kernel, and neither
-  // the row ends nor k_csr_rows are needed.  2: the lane that holds a row's last symbol leaves the number of the
+  // rows_in_lane: 1 (K divides 16), 3 (any other K < 16) or 2 (K divides the tile of 4096 symbols, 64 <= K, so that
+  // every tile starts a row and holds at most 64 of them): the row counts, their histogram and l_D come from this
+  // kernel, and neither the row ends nor k_csr_rows are needed.  2: the lane that holds a row's last symbol leaves the number of the
   // tile's nonzeros up to there in LDS, and after the tile's barrier a thread per row takes the difference.
   __shared__ uint32_t s_r[17 * 8];
   __shared__ uint32_t s_rowend[64];
@@ -165,7 +165,21 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
         if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : slot_of(col)], 1u);
         else atomicAdd(&cnt[col], 1u);
       }
-      if (rows_in_lane == 2) {  // uniform; one row end per lane at most
+      if (rows_in_lane == 3) {
+        // short rows that straddle lanes (K < 16, not a divisor of 16): the lane takes the rows that start inside
+        // its 16 symbols and looks at the nonzero flags of the 16 symbols behind them for the ends
+        uint32_t ext[4];
+        load16w(sym, e0 + 16, n, aligned, ext);
+        const uint32_t m32 = mask | ((nonzero_bytes(ext[0]) | (nonzero_bytes(ext[1]) << 4) | (nonzero_bytes(ext[2]) << 8) |
+                                      (nonzero_bytes(ext[3]) << 12)) << 16);
+        const uint32_t lr = threadIdx.x & 7u;
+        uint32_t row = row0 + (col0 ? 1u : 0u);
+        for (uint32_t p = col0 ? K - col0 : 0u; p < 16 && e0 + p < n; p += K, row++) {
+          const uint32_t rj = (uint32_t)__popc((m32 >> p) & ((1u << K) - 1u));
+          r[row] = (uint16_t)rj;
+          atomicAdd(&s_r[rj + lr * (K + 1)], 1u);
+        }
+      } else if (rows_in_lane == 2) {  // uniform; one row end per lane at most
         const uint32_t p = K - 1 - col0;
         if (p < 16) s_rowend[row0 - (uint32_t)((uint64_t)tile * kCsrTile / K)] = loc0 + (uint32_t)__popc(mask & ((2u << p) - 1u));
       } else if (rows_in_lane) {
@@ -205,7 +219,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
   if (rows_in_lane) {
     __syncthreads();
     uint32_t *dst_r = cnt + (n_rep ? (size_t)(1 + blockIdx.x % n_rep) * A : 0);
-    if (rows_in_lane == 1 && threadIdx.x <= K) {
+    if (rows_in_lane != 2 && threadIdx.x <= K) {
       uint32_t t = 0;
 #pragma unroll
       for (uint32_t q = 0; q < 8; q++) t += s_r[threadIdx.x + q * (K + 1)];

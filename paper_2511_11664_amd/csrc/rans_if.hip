@@ -233,6 +233,7 @@ int launch_encode_tail(const uint8_t *d_sym, uint64_t n, const rans_params &p, c
       // the row counts then): see k_csr_compact
       const bool short_rows = lds_hist && p.cols <= kShortRowCols && 8ull * p.cols <= A;
       const int rows_in_lane = (p.cols <= 16 && 16 % p.cols == 0) ? 1
+                               : p.cols < 16 ? 3
                                : (lds_hist && !short_rows && p.cols >= 64 && kCsrTile % p.cols == 0) ? 2 : 0;
       if (lds_hist && p.cols <= kShortRowCols && 8ull * p.cols <= A)
         PROF_LAUNCH(KID_CSR_COMPACT, (k_csr_compact<true, true>), dim3(g_compact), dim3(kWG), ((A + 15u) & ~15u) * 4, st, d_sym, (uint32_t)n, al,

@@ -96,7 +96,7 @@ __device__ __forceinline__ EncEntry load_entry(const uint2 *g_tab, const uint32_
 // Symbols are taken last to first in batches of kEncAhead rows, fetched ahead of the coder (through a
 // per-wave LDS stage filled with 16-byte loads two tiles ahead), table entries looked up three rows ahead.
 // The per-row arithmetic is branch-free (selects only) so that it stays one basic block.  floor(s / f) of
-// Eq. 2 is a multiply-high and a shift with the per-symbol multiplier that k_normalize proved exact (table
+// Eq. 2 is a multiply-high and a shift with the per-symbol multiplier that the table build proved exact (table
 // form 2, when every entry is exact), else a multiply-high with floor(2^32 / f) plus one correction step.
 //
 // Emitted words stay in LDS: every stream has an area of rw 16-bit slots, filled from its top slot downwards
@@ -113,8 +113,9 @@ __device__ __forceinline__ EncEntry load_entry(const uint2 *g_tab, const uint32_
 // (those work-groups were dispatched earlier and never wait for a higher index, so the wait ends; it is bounded
 // all the same and turns into RANS_ERR_HIP if the bound is hit), and derives the chunk's byte offset and its
 // own position inside the chunk from those totals: one load per chunk instead of one per work-group, all of
-// a lane's loads independent of each other.  Its words then go from the areas (and, for the streams that
-// spilled, from scratch) through an LDS tile to the container in aligned 16-byte stores.
+// a lane's loads independent of each other.  Its words then go straight from the areas to their place in the
+// container (eight lanes per stream, 16-byte pieces to addresses that are only 2-byte aligned, a tail of 4-, 2-
+// and 1-word stores), and the blocks of the streams that spilled from scratch, 16 bytes at a time.
 // Without FUSE everything is spilled to scratch at the end, in the block format k_gather reads.
 constexpr int kSpinMax = 1 << 18;
 constexpr uint64_t kChunkWordsMask = (1ull << 40) - 1;  // chunk counter: words below, finished groups above

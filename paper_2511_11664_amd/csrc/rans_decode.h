@@ -561,7 +561,10 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
     uint4 pend_q = make_uint4(0, 0, 0, 0);
     uint32_t wnext = wread(rd9);
     uint32_t s = s_stored;
-    uint32_t smin = s;
+    // The state is at least 2^16 before every symbol if it is at the start: a step leaves f (s >> M) + (slot - F)
+    // with f >= 1 (every slot of a table that sums to 2^M belongs to a present symbol) and s >> M >= 1, that is at
+    // least 1, and a value below 2^16 is then shifted up by 16 bits.  So only the stored state needs the check.
+    const bool s_low = s < kL;
     auto *ob = sink.out + base + (uint64_t)g * NT;  // uniform base of this work-group's outputs
     constexpr uint32_t kOutElem = sizeof(*sink.out);
     uint32_t oi = threadIdx.x * kOutElem;           // byte offset of this stream's next output
@@ -619,7 +622,6 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
         rd9 += RB;
         wnext = wread(rd9);
       }
-      smin = s < smin ? s : smin;
     };
     uint64_t t = 0;
     for (; t + 8 <= rows_full; t += 8) {
@@ -633,7 +635,7 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
       if (j < rem_row) step();
     }
     const uint32_t rd = rd9 >> LOG_RB;
-    bad |= smin < kL || s != kL || rd - pos0 != nw;
+    bad |= s_low || s != kL || rd - pos0 != nw;
     if (j == S - 1) {  // chunk size must be exactly header + words, padded to 4 bytes with zeros
       const uint64_t end = 8ull * S + 2 * (w0 + nw);
       if (((end + 3) & ~3ull) != ck_bytes) bad = true;

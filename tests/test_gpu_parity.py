@@ -439,12 +439,34 @@ def test_full_size_configs_whole_container(label, name, over):
     assert np.array_equal(sym.cpu().numpy(), sym_ref)
 
 
+@pytest.mark.parametrize("name,over", [("c5a", {}), ("c2", dict(mode=0, chunk_syms=100352)), ("c4", dict(chunk_syms=18432))])
+def test_full_size_dense_configs_repeated(name, over):
+    """The dense encoder's three ways of sharing a compute unit among its work-groups (wave priorities in turn:
+    c5a; a timed sleep before the look-back: c2 with 98 rows per stream; neither: c4 in small chunks) give the
+    same container on every one of many calls in a row (the first one is compared with the oracle's by
+    test_full_size_configs_whole_container)."""
+    w = synth.workload(name, 1, **over)
+    xd = synth.make(w).cuda()
+    p = B.params_of(w)
+    print(f"[case] {name} {over} full size, repeated", flush=True)
+    codec = B.Codec(p, w.numel)
+    first = None
+    for it in range(30):
+        assert B.rans_compress(xd, w.numel, p, codec.stream, codec.nbytes, codec.ws) == 0
+        assert B.rans_last_status(codec.ws) == 0, f"call {it}"
+        nbytes = int(codec.nbytes.item())
+        got = codec.stream[:nbytes].clone()
+        if first is None:
+            first = got
+        assert got.numel() == first.numel() and torch.equal(got, first), f"call {it}"
+
+
 def test_full_size_csr_config_repeated():
     """c3 in CSR form at full size (fp32 64x512x28x28, N x 256, Q=8, M=14, S=1024, 2^16-symbol chunks): the whole
-    container against the oracle's, and the same bytes on every one of many calls in a row.  The table of this
-    path is built by whichever work-group adds its part of the histogram last, hundreds of work-groups and a wide
-    spread of row counts; a hand-over that starts before every addition has been performed shows up here as an
-    error status on some of the calls."""
+    container against the oracle's, and the same bytes on every one of many calls in a row.  Thousands of
+    work-groups add to the histogram of D, the encoder's work-groups each build the table from it and place their
+    words by looking at the totals of the ones before them; anything that depends on how the work-groups happen to
+    be timed shows up here as an error status or as different bytes on some of the calls."""
     w = synth.workload("c3", 1, mode=1, cols=256, chunk_syms=65536)  # more chunks than the benchmark's row
     x = synth.make(w)
     p = B.params_of(w)

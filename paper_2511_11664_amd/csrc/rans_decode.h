@@ -653,7 +653,9 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
 __global__ __launch_bounds__(kWG) void k_row_part(const uint16_t *r, uint32_t N, uint32_t K, uint32_t tile_rows,
                                                   uint32_t *part, CtlRef ctl) {
   __shared__ uint64_t sh64[kWG / 64];
-  if (group_has_status(ctl)) return;
+  // the status word is read first and looked at after the counts: the two trips to memory overlap (r lies inside
+  // D whatever an earlier kernel has found)
+  const bool failed = status_at_entry(ctl) != 0;
   const uint32_t i0 = blockIdx.x * tile_rows;
   const uint32_t i1 = i0 + tile_rows < N ? i0 + tile_rows : N;
   uint64_t loc = 0;
@@ -675,32 +677,93 @@ __global__ __launch_bounds__(kWG) void k_row_part(const uint16_t *r, uint32_t N,
     bad |= v > K;
     loc += v;
   }
+  if (__syncthreads_or(failed)) return;
   const uint64_t tot = block_sum64<kWG>(loc, sh64);
   if (bad || tot > 0xffffffffull) set_status(ctl, RANS_ERR_CORRUPT);
   if (threadIdx.x == 0) part[blockIdx.x] = (uint32_t)tot;
 }
 
-// One tile of rows: row offsets by a local scan of r, the tile zeroed in LDS, every nonzero of the tile
-// placed (its row found by bisection of the local offsets) and checked (1 <= v < 2^Q, c < K, c strictly
-// increasing inside a row), then the tile written out: as symbols, or dequantised (x = s (xhat - z)).
+// LDS of one tile of k_csr_to_dense, in bytes from the start of the dynamic allocation (the host sizes the
+// launch with the same figures): the tile's non-empty rows in order, one bit per nonzero of the tile (set where
+// a row begins), the number of set bits before each 32-bit word of that map, and the tile itself.
+struct ExpandLds {
+  uint32_t nerow, heads, wrank, dense, total;
+};
+__host__ __device__ inline ExpandLds expand_lds(uint32_t tile_rows, uint32_t K) {
+  const uint32_t cells = tile_rows * K;                 // at most 65535 (checked by the host)
+  const uint32_t nw = ((cells + 31) / 32 + 7) & ~7u;  // words of the map, a multiple of eight
+  ExpandLds l;
+  l.nerow = 0;
+  l.heads = (2 * tile_rows + 15) & ~15u;
+  l.wrank = l.heads + 4 * nw;
+  l.dense = l.wrank + 2 * nw;
+  l.total = l.dense + ((cells + 3) & ~3u);
+  return l;
+}
+
+// One tile of rows, rebuilt in LDS and written out as symbols or dequantised (x = s (xhat - z)).
 // D holds v, c, r as 16-bit symbols; part[] the exclusive scan of the tile sums with part[n_tiles] = their total
 // (`scanned`), or - with few enough tiles that every work-group can add up the sums before its own - the tile
-// sums themselves, which spares the scan kernel.
+// sums themselves, which spares the scan kernel.  nnz is the number of nonzeros the header implies.
+//
+// The tile's nonzeros are j = 0 .. cnt-1 (cnt = sum of the tile's r).  A scan of r gives every non-empty row the
+// index of its first nonzero and its rank among the non-empty rows; the row writes its number to nerow[rank] and
+// sets bit j_first of `heads`.  The row of nonzero j is then nerow[(set bits of heads at or below j) - 1]: a
+// lane that takes eight consecutive nonzeros needs the count of set bits before its byte of the map (wrank of the
+// word plus a population count) and eight independent LDS reads - no search through row offsets and no walk from
+// row to row, whose dependent LDS reads dominated an earlier form of this kernel.
+// Checked here: 1 <= v < 2^Q, c < K, c strictly increasing inside a row (a nonzero that is not the first of its
+// row must have a larger column than its predecessor), the tile sums against nnz.  r[i] <= K was checked by
+// k_row_part, which is what keeps a tile's sum below 2^16.
+// The loads of r, of the tile sums and - once the tile's first nonzero is known - of the first 16 kWG values and
+// column indices are all issued before the scans that say how many of them the tile really has (reads past the
+// tile's own nonzeros stay inside v and c: they are bounded by nnz).
 template <typename OutT>
 __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const uint32_t *part, int scanned, uint32_t N,
-                                                      uint32_t K, uint32_t tile_rows, uint32_t q_bits, OutT *out,
-                                                      CtlRef ctl) {
+                                                      uint32_t K, uint32_t tile_rows, uint32_t q_bits, uint32_t nnz,
+                                                      OutT *out, CtlRef ctl) {
   extern __shared__ __align__(16) uint32_t l_mem[];
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
-  if (group_has_status(ctl)) return;
-  const uint32_t nnz = ctl->nnz;
-  const uint32_t i0 = blockIdx.x * tile_rows;
+  // Work-groups are handed to the compute units in the order of their numbers, and (almost) all of them are on
+  // the chip at once.  The earlier ones of a unit get the higher wave priority: they reach their stores sooner,
+  // so that writing starts while the later ones still place their nonzeros.
+  {
+    const uint32_t turn = blockIdx.x >> 9;  // two work-groups per unit and level, with 256 units
+    if (turn == 0) __builtin_amdgcn_s_setprio(3);
+    else if (turn == 1) __builtin_amdgcn_s_setprio(2);
+    else if (turn == 2) __builtin_amdgcn_s_setprio(1);
+  }
+  const ExpandLds lay = expand_lds(tile_rows, K);
+  uint16_t *nerow = (uint16_t *)((uint8_t *)l_mem + lay.nerow);
+  uint32_t *heads = (uint32_t *)((uint8_t *)l_mem + lay.heads);
+  uint16_t *wrank = (uint16_t *)((uint8_t *)l_mem + lay.wrank);
+  uint8_t *dense = (uint8_t *)l_mem + lay.dense;
+  const uint32_t i0 = blockIdx.x * tile_rows;  // below N: the grid has ceil(N / tile_rows) work-groups
   const uint32_t rows = i0 + tile_rows < N ? tile_rows : N - i0;
-  // rows + 1 local offsets; 16 bits do: a tile has at most 65535 cells and k_row_part has checked r[i] <= K
-  uint16_t *roff = (uint16_t *)l_mem;
-  uint8_t *dense = (uint8_t *)l_mem + ((2 * (rows + 1) + 15) & ~15u);  // rows * K symbols
+  const uint32_t cells = rows * K;
   const uint32_t n_tiles = gridDim.x;
+  // the counts of the tile's rows: one per lane, or (more than kWG rows: at most 16 kWG, by the host's choice of
+  // tile) sixteen consecutive ones per lane, two to a word
+  constexpr int kRpt = 16;
+  const uint16_t *r = D + 2ull * nnz + i0;
+  const bool one_row = rows <= kWG;
+  const uint32_t t0 = threadIdx.x * kRpt;
+  uint32_t rw[kRpt / 2];
+#pragma unroll
+  for (int k = 0; k < kRpt / 2; k++) rw[k] = 0;
+  if (one_row) {
+    if (threadIdx.x < rows) rw[0] = r[threadIdx.x];
+  } else if (t0 + kRpt <= rows) {
+    __builtin_memcpy(rw, r + t0, 2 * kRpt);  // 2-byte aligned: r starts behind v and c
+  } else {
+#pragma unroll
+    for (int k = 0; k < kRpt; k++)
+      if (t0 + k < rows) rw[k >> 1] |= (uint32_t)r[t0 + k] << (16 * (k & 1));
+  }
+  // the map and the tile start at zero
+  for (uint32_t i = threadIdx.x; i < (lay.wrank - lay.heads) / 4; i += kWG) heads[i] = 0;
+  for (uint32_t i = threadIdx.x; i < (cells + 3) / 4; i += kWG) ((uint32_t *)dense)[i] = 0;
   uint64_t base64, total;
   if (scanned) {
     base64 = part[blockIdx.x];
@@ -714,84 +777,119 @@ __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const u
 #pragma unroll
       for (int k = 0; k < 4; k++) loc += x4[k];
     }
-    base64 = block_sum64<kWG>(loc, sh64);
-    total = base64 + part[blockIdx.x];  // of interest in the last work-group only
+    base64 = loc;
+    total = part[blockIdx.x];
+  }
+  if (group_has_status(ctl)) return;
+  if (!scanned) {
+    base64 = block_sum64<kWG>(base64, sh64);
+    total += base64;  // of interest in the last work-group only
   }
   if ((blockIdx.x == n_tiles - 1 && total != nnz) || base64 > nnz) {  // sum of r must be the number of nonzeros
     if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
     return;
   }
   const uint32_t base = (uint32_t)base64;
-  const uint16_t *r = D + 2ull * nnz + i0;
-  uint32_t carry = 0;
-  if (rows <= kWG) {
-    const uint32_t i = threadIdx.x;
-    const uint32_t v = i < rows ? r[i] : 0;
-    const uint32_t ex = block_excl_scan<kWG>(v, sh, &carry);
-    if (i < rows) roff[i] = (uint16_t)ex;
-  } else {
-    // many short rows (at most 16 kWG of them, by the host's choice of tile): a lane adds up 16 consecutive
-    // counts by itself, one scan over the lanes' sums
-    constexpr int kRpt = 16;
-    const uint32_t t0 = threadIdx.x * kRpt;
-    uint32_t w[kRpt / 2], loc[kRpt];
-    const bool whole = t0 + kRpt <= rows;
-    if (whole) {
-      __builtin_memcpy(w, r + t0, 2 * kRpt);  // 2-byte aligned
-    } else {
+  const uint32_t cap = nnz - base;  // nonzeros stored from the tile's first one on
+  // A lane takes runs of eight consecutive nonzeros (their values and column indices come with one 16-byte
+  // load each, 2-byte aligned: where c starts inside D depends on the number of nonzeros), two runs per step.
+  // The first step's loads go out now.
+  constexpr int kU = 2;
+  const uint16_t *Dv = D + base, *Dc = D + (uint64_t)nnz + base;
+  uint32_t vw[kU][4], cw[kU][4], cp[kU];
 #pragma unroll
-      for (int k = 0; k < kRpt / 2; k++) {
-        const uint32_t a = t0 + 2 * k < rows ? r[t0 + 2 * k] : 0u, b = t0 + 2 * k + 1 < rows ? r[t0 + 2 * k + 1] : 0u;
-        w[k] = a | (b << 16);
-      }
+  for (int u = 0; u < kU; u++) {
+    const uint32_t j = 8 * (u * kWG + threadIdx.x);
+    cp[u] = 0;
+#pragma unroll
+    for (int k = 0; k < 4; k++) vw[u][k] = cw[u][k] = 0;
+    if (j < cells && j + 8 <= cap) {
+      __builtin_memcpy(vw[u], Dv + j, 16);
+      __builtin_memcpy(cw[u], Dc + j, 16);
     }
-    uint32_t sum = 0;
+    if (j && j < cells && j < cap) cp[u] = Dc[j - 1];
+  }
+  // scan of the counts, packed: nonzeros in the low half, non-empty rows in the high half (a tile has at most
+  // 65535 cells, so neither sum leaves its half)
+  uint32_t carry = 0;
+  if (one_row) {
+    const uint32_t v = rw[0];
+    const uint32_t ex = block_excl_scan<kWG>(v | (v ? 0x10000u : 0u), sh, &carry);
+    if (v) {
+      nerow[ex >> 16] = (uint16_t)threadIdx.x;
+      atomicOr(&heads[(ex & 0xffffu) >> 5], 1u << (ex & 31));
+    }
+  } else {
+    uint32_t loc[kRpt], sum = 0;
 #pragma unroll
     for (int k = 0; k < kRpt; k++) {
+      const uint32_t v = (rw[k >> 1] >> (16 * (k & 1))) & 0xffffu;
       loc[k] = sum;
-      sum += (w[k >> 1] >> (16 * (k & 1))) & 0xffffu;
+      sum += v | (v ? 0x10000u : 0u);
     }
     const uint32_t ex = block_excl_scan<kWG>(sum, sh, &carry);
-    if (whole) {
+    // consecutive rows mostly begin inside the same word of the map: one atomic per word
+    uint32_t cur = 0, acc = 0;
 #pragma unroll
-      for (int k = 0; k < kRpt; k += 8)
-        *(uint4 *)(roff + t0 + k) = make_uint4((ex + loc[k]) | ((ex + loc[k + 1]) << 16), (ex + loc[k + 2]) | ((ex + loc[k + 3]) << 16),
-                                               (ex + loc[k + 4]) | ((ex + loc[k + 5]) << 16), (ex + loc[k + 6]) | ((ex + loc[k + 7]) << 16));
-    } else {
-#pragma unroll
-      for (int k = 0; k < kRpt; k++)
-        if (t0 + k < rows) roff[t0 + k] = (uint16_t)(ex + loc[k]);
+    for (int k = 0; k < kRpt; k++) {
+      const uint32_t v = (rw[k >> 1] >> (16 * (k & 1))) & 0xffffu;
+      if (v) {
+        const uint32_t q = ex + loc[k], wd = (q & 0xffffu) >> 5;
+        nerow[q >> 16] = (uint16_t)(t0 + k);
+        if (wd != cur) {
+          if (acc) atomicOr(&heads[cur], acc);
+          cur = wd;
+          acc = 0;
+        }
+        acc |= 1u << (q & 31);
+      }
     }
+    if (acc) atomicOr(&heads[cur], acc);
   }
-  __syncthreads();
-  if (threadIdx.x == 0) roff[rows] = (uint16_t)carry;
-  const uint32_t cells = rows * K;
-  for (uint32_t i = threadIdx.x; i < (cells + 3) / 4; i += kWG) ((uint32_t *)dense)[i] = 0;
-  __syncthreads();
-  const uint32_t cnt_here = carry;
-  if ((uint64_t)base + cnt_here > nnz) {  // uniform: the offsets would run past the stored nonzeros
+  const uint32_t cnt_here = carry & 0xffffu;
+  if (cnt_here > cap) {  // uniform: the tile's nonzeros would run past the stored ones
     if (threadIdx.x == 0) set_status(ctl, RANS_ERR_CORRUPT);
     return;
   }
+  __syncthreads();
+  {
+    // set bits of the map before each of its words: eight words per lane, one scan over the lanes
+    const uint32_t nw = (cnt_here + 31) >> 5, w0 = threadIdx.x * 8;
+    uint32_t pc[8], sum = 0;
+#pragma unroll
+    for (int k = 0; k < 8; k++) pc[k] = 0;
+    if (w0 < nw) {
+      const uint4 a = *(const uint4 *)(heads + w0), b = *(const uint4 *)(heads + w0 + 4);
+      const uint32_t hw[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int k = 0; k < 8; k++) {
+        pc[k] = sum;
+        sum += __popc(hw[k]);
+      }
+    }
+    uint32_t tot;
+    const uint32_t ex = block_excl_scan<kWG>(sum, sh, &tot);
+    if (w0 < nw)
+      *(uint4 *)(wrank + w0) = make_uint4((ex + pc[0]) | ((ex + pc[1]) << 16), (ex + pc[2]) | ((ex + pc[3]) << 16),
+                                          (ex + pc[4]) | ((ex + pc[5]) << 16), (ex + pc[6]) | ((ex + pc[7]) << 16));
+  }
+  __syncthreads();
   bool bad = false;
-  // A lane takes runs of eight consecutive nonzeros (their values and column indices come with one 16-byte
-  // load each, 2-byte aligned: where c starts inside D depends on the number of nonzeros), two runs per step
-  // with all loads issued first.  The row of a run's first nonzero is found by bisection of the local offsets,
-  // the rows of the others by walking on from there.
-  constexpr int kU = 2;
-  const uint16_t *Dv = D + base, *Dc = D + (uint64_t)nnz + base;
   for (uint32_t m0 = 0; 8 * m0 < cnt_here; m0 += kWG * kU) {
-    uint32_t vw[kU][4], cw[kU][4], cp[kU];
 #pragma unroll
     for (int u = 0; u < kU; u++) {
       const uint32_t j = 8 * (m0 + u * kWG + threadIdx.x);
-      cp[u] = 0;
+      if (m0) {  // later steps (a tile with more than 16 kWG nonzeros) load here
+        cp[u] = 0;
 #pragma unroll
-      for (int k = 0; k < 4; k++) vw[u][k] = cw[u][k] = 0;
-      if (j + 8 <= cnt_here) {
-        __builtin_memcpy(vw[u], Dv + j, 16);
-        __builtin_memcpy(cw[u], Dc + j, 16);
-      } else {
+        for (int k = 0; k < 4; k++) vw[u][k] = cw[u][k] = 0;
+        if (j < cnt_here && j + 8 <= cap) {
+          __builtin_memcpy(vw[u], Dv + j, 16);
+          __builtin_memcpy(cw[u], Dc + j, 16);
+        }
+        if (j < cnt_here) cp[u] = Dc[j - 1];
+      }
+      if (j < cnt_here && j + 8 > cap) {  // the last few nonzeros of all: one by one
 #pragma unroll
         for (int k = 0; k < 8; k++) {
           if (j + k < cnt_here) {
@@ -800,37 +898,25 @@ __global__ __launch_bounds__(kWG) void k_csr_to_dense(const uint16_t *D, const u
           }
         }
       }
-      if (j && j < cnt_here) cp[u] = Dc[j - 1];
     }
 #pragma unroll
     for (int u = 0; u < kU; u++) {
       const uint32_t j0 = 8 * (m0 + u * kWG + threadIdx.x);
       if (j0 < cnt_here) {
-        uint32_t lo = 0, hi = rows;  // largest local row with roff[row] <= j0 (roff[rows] = cnt_here > j0)
-        while (hi - lo > 1) {
-          const uint32_t mid = (lo + hi) >> 1;
-          if (roff[mid] <= j0) lo = mid;
-          else hi = mid;
-        }
-        uint32_t row = lo, row_beg = roff[lo], row_end = roff[lo + 1], prev_c = cp[u];
+        const uint32_t word = heads[j0 >> 5], sft = j0 & 31;
+        const uint32_t first8 = (word >> sft) & 0xffu;
+        uint32_t rank = wrank[j0 >> 5] + __popc(word & ((1u << sft) - 1u));  // rows begun before j0
+        uint32_t prev_c = cp[u];
 #pragma unroll
         for (int k = 0; k < 8; k++) {
-          const uint32_t j = j0 + k;
-          if (j < cnt_here) {
-            // ends at the last row at the latest: its end is roff[rows] = cnt_here > j (the bound on `row`
-            // keeps the walk inside roff[] whatever the offsets hold)
-            while (j >= row_end && row + 1 < rows) {
-              row++;
-              row_beg = row_end;
-              row_end = roff[row + 1];
-            }
-            if (j >= row_end) {
-              bad = true;
-              continue;
-            }
+          if (j0 + k < cnt_here) {
+            const bool head = (first8 >> k) & 1u;
+            rank += head;
+            // rank >= 1: the tile's first nonzero begins a row (the guard only keeps the read inside nerow)
+            const uint32_t row = nerow[(rank ? rank : 1u) - 1u];
             const uint32_t vv = (vw[u][k >> 1] >> (16 * (k & 1))) & 0xffffu, cc = (cw[u][k >> 1] >> (16 * (k & 1))) & 0xffffu;
-            bool b = vv == 0 || vv >= (1u << q_bits) || cc >= K;
-            if (j > row_beg && prev_c >= cc) b = true;
+            bool b = vv == 0 || vv >= (1u << q_bits) || cc >= K || row >= rows;
+            if (!head && prev_c >= cc) b = true;
             if (b) bad = true;
             else dense[row * K + cc] = (uint8_t)vv;
             prev_c = cc;

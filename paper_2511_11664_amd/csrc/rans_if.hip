@@ -597,25 +597,40 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
       if (tr >= 4) tr &= ~3u;  // then every tile starts on a 4-cell boundary (vector stores)
       return tr;
     };
-    auto lds_of = [&](uint32_t tr) {
-      return ((2 * ((size_t)tr + 1) + 15) & ~(size_t)15) + (((size_t)tr * K + 3) & ~(size_t)3);
-    };
+    auto lds_of = [&](uint32_t tr) { return (size_t)expand_lds(tr, K).total; };
     uint32_t tile_rows = rows_of(cells);
     if (cells == kDenseTileCells) {
-      // Large tensors: all tiles should be on the chip at once (256 CUs, each with 160 KB of LDS and room for eight
-      // work-groups of this size).  A tile count just above that runs a second, nearly empty round; somewhat smaller
-      // tiles, of which more fit a CU, avoid it.
-      uint64_t best_cost = ~0ull;
-      for (uint64_t c = kDenseTileCells; c >= kDenseTileCells / 2; c -= kDenseTileCells / 8) {
-        const uint32_t tr = rows_of(c);
-        const uint64_t nt = (N + tr - 1) / tr;
-        uint64_t per_cu = (160 * 1024) / (lds_of(tr) + 256);
-        per_cu = per_cu > 8 ? 8 : (per_cu < 1 ? 1 : per_cu);
-        const uint64_t rounds = (nt + 256 * per_cu - 1) / (256 * per_cu);
-        const uint64_t cost = rounds * tr * K;
-        if (cost < best_cost) {
-          best_cost = cost;
-          tile_rows = tr;
+      // Large tensors.  The kernel is fastest with every tile on the chip at once (256 CUs; a CU holds eight
+      // work-groups of this size, fewer if their LDS does not fit) and the tiles spread evenly: its time follows
+      // the most loaded CU, which has m = ceil(tiles / 256) tiles.  For every m that tile sizes from half to 9/8
+      // of the nominal one allow, the smallest tile with that m is a candidate.  The cost is m tiles (each with a
+      // fixed part worth about 2048 cells), with a surcharge of the share of the tiles that does not fit the chip
+      // at once, and another eighth beyond 2048 tiles (the row-sum kernel then needs a second turn as well).
+      // Tiles of which fewer than seven fit a CU are taken only if there is no other: measured, the loss of
+      // resident waves costs more than the larger tile saves.
+      const uint32_t lo = rows_of(kDenseTileCells / 2), hi = rows_of(kDenseTileCells + kDenseTileCells / 8);
+      const uint32_t unit = (K & 3) == 0 ? 1 : 4;  // keeps every tile's first cell on a 4-cell boundary
+      bool found = false;
+      for (int pass = 0; pass < 2 && !found; pass++) {
+        const uint64_t min_per_cu = pass ? 1 : 7;
+        uint64_t best_cost = ~0ull;
+        for (uint64_t m = ((uint64_t)N + 256ull * hi - 1) / (256ull * hi); m <= 64; m++) {
+          uint64_t tr = ((uint64_t)N + 256 * m - 1) / (256 * m);
+          tr = (tr + unit - 1) / unit * unit;
+          if (tr < lo) break;
+          if (tr > hi || tr * K > 65535) continue;
+          const uint64_t nt = (N + tr - 1) / tr;
+          uint64_t per_cu = (160 * 1024) / (lds_of((uint32_t)tr) + 256);
+          per_cu = per_cu > 8 ? 8 : per_cu;
+          if (per_cu < min_per_cu) continue;
+          uint64_t cost = m * (tr * K + 2048) * 64;
+          if (nt > 256 * per_cu) cost += cost * (nt - 256 * per_cu) / nt;
+          if (nt > 2048) cost += cost / 8;
+          if (cost < best_cost) {
+            best_cost = cost;
+            tile_rows = (uint32_t)tr;
+            found = true;
+          }
         }
       }
     }
@@ -638,13 +653,13 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
     }
     if (out_kind == 0)
       PROF_LAUNCH(KID_CSR_EXPAND, (k_csr_to_dense<uint8_t>), dim3(n_tiles), dim3(kWG), lds, st, D, part, scanned, N, K, tile_rows,
-                  h.p.q_bits, (uint8_t *)d_out, ctl);
+                  h.p.q_bits, (uint32_t)nnz, (uint8_t *)d_out, ctl);
     else if (out_kind == 1)
       PROF_LAUNCH(KID_CSR_EXPAND, (k_csr_to_dense<float>), dim3(n_tiles), dim3(kWG), lds, st, D, part, scanned, N, K, tile_rows,
-                  h.p.q_bits, (float *)d_out, ctl);
+                  h.p.q_bits, (uint32_t)nnz, (float *)d_out, ctl);
     else
       PROF_LAUNCH(KID_CSR_EXPAND, (k_csr_to_dense<__half>), dim3(n_tiles), dim3(kWG), lds, st, D, part, scanned, N, K, tile_rows,
-                  h.p.q_bits, (__half *)d_out, ctl);
+                  h.p.q_bits, (uint32_t)nnz, (__half *)d_out, ctl);
     LAUNCH_CHECK();
   }
   return RANS_OK;

@@ -651,36 +651,46 @@ __global__ __launch_bounds__(NT) void k_decode_fast(const uint8_t *in, uint64_t 
 // work-group adds up itself (a single-work-group scan kernel does it when there are thousands of tiles), and
 // k_csr_to_dense rebuilds one tile per work-group in LDS and writes it out in the output type.
 __global__ __launch_bounds__(kWG) void k_row_part(const uint16_t *r, uint32_t N, uint32_t K, uint32_t tile_rows,
-                                                  uint32_t *part, CtlRef ctl) {
-  __shared__ uint64_t sh64[kWG / 64];
-  // the status word is read first and looked at after the counts: the two trips to memory overlap (r lies inside
-  // D whatever an earlier kernel has found)
+                                                  uint32_t n_tiles, uint32_t *part, CtlRef ctl) {
+  // A wave per tile (a tile has at most 4096 rows): no barrier and no LDS, and a quarter of the work-groups.
+  // The status word is read first and looked at after the counts: the two trips to memory overlap (r lies inside
+  // D whatever an earlier kernel has found).
   const bool failed = status_at_entry(ctl) != 0;
-  const uint32_t i0 = blockIdx.x * tile_rows;
+  const uint32_t lane = threadIdx.x & 63u, tile = blockIdx.x * (kWG / 64) + (threadIdx.x >> 6);
+  if (tile >= n_tiles) return;  // whole waves
+  const uint32_t i0 = tile * tile_rows;
   const uint32_t i1 = i0 + tile_rows < N ? i0 + tile_rows : N;
-  uint64_t loc = 0;
+  uint32_t loc = 0;  // at most 4096 counts below 2^16
   bool bad = false;
   // eight counts per lane and step (one 16-byte load, 2-byte aligned: r starts behind v and c), the tail one by one
   const uint32_t n8 = (i1 - i0) / 8;
-  for (uint32_t q = threadIdx.x; q < n8; q += kWG) {
-    uint32_t w[4];
-    __builtin_memcpy(w, r + i0 + 8 * q, 16);
+  for (uint32_t q0 = lane; q0 < n8; q0 += 64 * 4) {  // four loads in flight
+    uint32_t w[4][4];
 #pragma unroll
-    for (int k = 0; k < 4; k++) {
-      const uint32_t a = w[k] & 0xffffu, b = w[k] >> 16;
-      bad |= a > K || b > K;
-      loc += a + b;
+    for (int u = 0; u < 4; u++) {
+#pragma unroll
+      for (int k = 0; k < 4; k++) w[u][k] = 0;
+      if (q0 + 64 * u < n8) __builtin_memcpy(w[u], r + i0 + 8 * (q0 + 64 * u), 16);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+#pragma unroll
+      for (int k = 0; k < 4; k++) {
+        const uint32_t a = w[u][k] & 0xffffu, b = w[u][k] >> 16;
+        bad |= a > K || b > K;
+        loc += a + b;
+      }
     }
   }
-  for (uint32_t i = i0 + 8 * n8 + threadIdx.x; i < i1; i += kWG) {
+  for (uint32_t i = i0 + 8 * n8 + lane; i < i1; i += 64) {
     const uint32_t v = r[i];
     bad |= v > K;
     loc += v;
   }
-  if (__syncthreads_or(failed)) return;
-  const uint64_t tot = block_sum64<kWG>(loc, sh64);
-  if (bad || tot > 0xffffffffull) set_status(ctl, RANS_ERR_CORRUPT);
-  if (threadIdx.x == 0) part[blockIdx.x] = (uint32_t)tot;
+  if (__ballot(failed) != 0) return;  // one decision for the wave
+  const uint32_t tot = wave_incl_sum_scan(loc);
+  if (bad) set_status(ctl, RANS_ERR_CORRUPT);
+  if (lane == 63) part[tile] = tot;
 }
 
 // LDS of one tile of k_csr_to_dense, in bytes from the start of the dynamic allocation (the host sizes the

@@ -636,7 +636,8 @@ int decode_common(const uint8_t *d_stream, size_t stream_bytes, const rans_heade
     }
     const uint32_t n_tiles = (N + tile_rows - 1) / tile_rows;
     uint32_t *part = (uint32_t *)(ws + L.row_off);  // n_tiles + 1 entries (n_tiles <= N)
-    PROF_LAUNCH(KID_ROW_SCAN, k_row_part, dim3(n_tiles), dim3(kWG), 0, st, D + 2 * nnz, N, K, tile_rows, part, ctl);
+    PROF_LAUNCH(KID_ROW_SCAN, k_row_part, dim3((n_tiles + kWG / 64 - 1) / (kWG / 64)), dim3(kWG), 0, st, D + 2 * nnz, N, K, tile_rows,
+                n_tiles, part, ctl);
     LAUNCH_CHECK();
     // up to a few thousand tiles every work-group of the expand kernel adds up the sums before its own
     const int scanned = n_tiles > kExpandOwnSumMaxTiles;

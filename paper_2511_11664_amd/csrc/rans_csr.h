@@ -153,18 +153,25 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
     const uint32_t loc0 = block_excl_scan<kWG>((uint32_t)__popc(mask), sh, &tot);  // also orders the hist zeroing and the staging reuse
     if (e0 < n) {
       const uint32_t row0 = (uint32_t)(e0 / K), col0 = (uint32_t)(e0 - (uint64_t)row0 * K);
-      uint32_t loc = loc0;
-      for (uint32_t mk = mask; mk; mk &= mk - 1u) {
-        const uint32_t k = (uint32_t)__ffs((int)mk) - 1u;
-        const uint32_t wk = k < 8 ? (k < 4 ? w[0] : w[1]) : (k < 12 ? w[2] : w[3]);
-        const uint32_t val = (wk >> (8 * (k & 3u))) & 0xffu;
-        uint32_t col = col0 + k;
-        if (K >= 16) col -= col >= K ? K : 0u;
-        else col -= K * ((col * inv16) >> 16);
-        s_vc[loc++] = val | (col << 8);
-        if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : slot_of(col)], 1u);
-        else atomicAdd(&cnt[col], 1u);
-      }
+      // the walk, once for each way of wrapping the column (decided outside the loop: K is uniform)
+      auto walk = [&](auto wide_rows) {
+        uint32_t loc = loc0;
+        for (uint32_t mk = mask; mk; mk &= mk - 1u) {
+          const uint32_t k = (uint32_t)__ffs((int)mk) - 1u;
+          // byte k of the lane's 16: a byte permute of each half (selector byte 0 = k mod 8, the others give
+          // zero), and the half that holds it
+          const uint32_t sel = 0x0c0c0c00u | (k & 7u);
+          const uint32_t val = k < 8 ? __builtin_amdgcn_perm(w[1], w[0], sel) : __builtin_amdgcn_perm(w[3], w[2], sel);
+          uint32_t col = col0 + k;
+          if (decltype(wide_rows)::value) col -= col >= K ? K : 0u;  // K >= 16: at most one wrap
+          else col -= K * ((col * inv16) >> 16);
+          s_vc[loc++] = val | (col << 8);
+          if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : slot_of(col)], 1u);
+          else atomicAdd(&cnt[col], 1u);
+        }
+      };
+      if (K >= 16) walk(std::true_type{});
+      else walk(std::false_type{});
       if (rows_in_lane == 3) {
         // short rows that straddle lanes (K < 16, not a divisor of 16): the lane takes the rows that start inside
         // its 16 symbols and looks at the nonzero flags of the 16 symbols behind them for the ends

@@ -112,10 +112,11 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
   __shared__ uint32_t s_vc[kCsrTile];  // value | column << 8 of the tile's nonzeros, in order (one LDS write each)
-  // A lane holds 16 consecutive symbols, so at each step the columns of a wave's lanes are 16 apart and
-  // would fall into two LDS banks: the histogram keeps column j in slot j ^ ((j >> 4) & 15) instead (a
-  // permutation within each aligned block of 16 slots; the array is A rounded up to 16).
-  auto slot_of = [](uint32_t j) { return j ^ ((j >> 4) & 15u); };
+  // The column histogram in its plain layout.  A lane holds 16 consecutive symbols, so the first columns of a
+  // wave's lanes are 16 apart, but a lane's j-th nonzero sits at a different place in each lane: the low bits of
+  // the columns met at one step are spread as they are, and a permutation of the slots (which an earlier walk
+  // over all 16 positions in lockstep needed) only costs two instructions per nonzero.
+  auto slot_of = [](uint32_t j) { return j; };
   if (LDS_HIST) {
     for (uint32_t a = threadIdx.x; a < ((A + 15u) & ~15u); a += kWG) hist[a] = 0;
   }
@@ -163,15 +164,17 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
           const uint32_t sel = 0x0c0c0c00u | (k & 7u);
           const uint32_t val = k < 8 ? __builtin_amdgcn_perm(w[1], w[0], sel) : __builtin_amdgcn_perm(w[3], w[2], sel);
           uint32_t col = col0 + k;
-          if (decltype(wide_rows)::value) col -= col >= K ? K : 0u;  // K >= 16: at most one wrap
+          if (decltype(wide_rows)::value == 2) col &= K - 1u;             // K a power of two
+          else if (decltype(wide_rows)::value == 1) col -= col >= K ? K : 0u;  // K >= 16: at most one wrap
           else col -= K * ((col * inv16) >> 16);
           s_vc[loc++] = val | (col << 8);
           if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : slot_of(col)], 1u);
           else atomicAdd(&cnt[col], 1u);
         }
       };
-      if (K >= 16) walk(std::true_type{});
-      else walk(std::false_type{});
+      if ((K & (K - 1u)) == 0) walk(std::integral_constant<int, 2>{});
+      else if (K >= 16) walk(std::integral_constant<int, 1>{});
+      else walk(std::integral_constant<int, 0>{});
       if (rows_in_lane == 3) {
         // short rows that straddle lanes (K < 16, not a divisor of 16): the lane takes the rows that start inside
         // its 16 symbols and looks at the nonzero flags of the 16 symbols behind them for the ends

@@ -168,8 +168,6 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
           else if (decltype(wide_rows)::value == 1) col -= col >= K ? K : 0u;  // K >= 16: at most one wrap
           else col -= K * ((col * inv16) >> 16);
           s_vc[loc++] = val | (col << 8);
-          if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : slot_of(col)], 1u);
-          else atomicAdd(&cnt[col], 1u);
         }
       };
       if ((K & (K - 1u)) == 0) walk(std::integral_constant<int, 2>{});
@@ -214,10 +212,14 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
         atomicAdd(&hist[slot_of(rj)], 1u);  // the same alphabet as the columns: one histogram for all of D
       }
     }
+    // the tile's nonzeros to their place, and their columns into the histogram: here every lane has work at
+    // every step (in the walk a wave runs as long as its fullest lane)
     for (uint32_t i = threadIdx.x; i < tot; i += kWG) {
-      const uint32_t vc = s_vc[i];
+      const uint32_t vc = s_vc[i], col = vc >> 8;
       v[base + i] = (uint8_t)vc;
-      c[base + i] = (uint16_t)(vc >> 8);
+      c[base + i] = (uint16_t)col;
+      if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : slot_of(col)], 1u);
+      else atomicAdd(&cnt[col], 1u);
     }
     base += tot;
     if (tile + 1 < t1) {

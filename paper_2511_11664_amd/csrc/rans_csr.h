@@ -144,6 +144,17 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
   }
   // (x * inv16) >> 16 = x / K for the x < 32 that occur when K < 16
   const uint32_t inv16 = 65536u / K + 1u;
+  // Row and column of the lane's first symbol, and the first row of the tile: one division before the loop, then
+  // from tile to tile by the quotient and remainder of the tile size (a 64-bit division per lane and tile cost
+  // as many instructions as a third of the walk).
+  const uint32_t tile_q = kCsrTile / K, tile_r = kCsrTile % K;
+  uint32_t row0, col0, tile_row0;
+  {
+    const uint64_t e_first = (uint64_t)t0 * kCsrTile + threadIdx.x * 16;
+    row0 = (uint32_t)(e_first / K);
+    col0 = (uint32_t)(e_first - (uint64_t)row0 * K);
+    tile_row0 = (uint32_t)((uint64_t)t0 * kCsrTile / K);  // of use where K divides the tile
+  }
   for (uint32_t tile = t0; tile < t1; tile++) {
     const uint64_t e0 = (uint64_t)tile * kCsrTile + threadIdx.x * 16;
     uint32_t nw[4];  // the next tile's symbols are on their way while this one is placed
@@ -153,7 +164,6 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
     uint32_t tot;
     const uint32_t loc0 = block_excl_scan<kWG>((uint32_t)__popc(mask), sh, &tot);  // also orders the hist zeroing and the staging reuse
     if (e0 < n) {
-      const uint32_t row0 = (uint32_t)(e0 / K), col0 = (uint32_t)(e0 - (uint64_t)row0 * K);
       // the walk, once for each way of wrapping the column (decided outside the loop: K is uniform)
       auto walk = [&](auto wide_rows) {
         uint32_t loc = loc0;
@@ -189,7 +199,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
         }
       } else if (rows_in_lane == 2) {  // uniform; one row end per lane at most
         const uint32_t p = K - 1 - col0;
-        if (p < 16) s_rowend[row0 - (uint32_t)((uint64_t)tile * kCsrTile / K)] = loc0 + (uint32_t)__popc(mask & ((2u << p) - 1u));
+        if (p < 16) s_rowend[row0 - tile_row0] = loc0 + (uint32_t)__popc(mask & ((2u << p) - 1u));
       } else if (rows_in_lane) {
         const uint32_t lr = threadIdx.x & 7u;
         if (K == 4) rows_inside_lane<4>(mask, e0, n, r, s_r, lr);
@@ -205,7 +215,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
     }
     __syncthreads();
     if (rows_in_lane == 2) {
-      const uint32_t row_t0 = (uint32_t)((uint64_t)tile * kCsrTile / K), row = row_t0 + threadIdx.x;
+      const uint32_t row = tile_row0 + threadIdx.x;
       if (threadIdx.x < kCsrTile / K && row < N) {
         const uint32_t rj = s_rowend[threadIdx.x] - (threadIdx.x ? s_rowend[threadIdx.x - 1] : 0u);
         r[row] = (uint16_t)rj;
@@ -222,6 +232,13 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
       else atomicAdd(&cnt[col], 1u);
     }
     base += tot;
+    row0 += tile_q;
+    col0 += tile_r;
+    if (col0 >= K) {
+      col0 -= K;
+      row0++;
+    }
+    tile_row0 += tile_q;  // exact where it is used (K divides the tile)
     if (tile + 1 < t1) {
 #pragma unroll
       for (int k = 0; k < 4; k++) w[k] = nw[k];

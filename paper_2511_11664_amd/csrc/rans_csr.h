@@ -88,14 +88,16 @@ __device__ __forceinline__ void rows_inside_lane(uint32_t mask, uint64_t e0, uin
 // values, c the column indices, row_end[i] the number of nonzeros up to and
 // including row i.  Column indices are histogrammed into cnt on the way.
 // A work-group takes tiles_per_wg consecutive tiles: a tile's nonzeros are compacted in LDS first
-// and leave with consecutive lanes on consecutive entries, and the column histogram is added to a
+// and leave with consecutive lanes on consecutive entries (that loop also counts their columns in an LDS
+// histogram: every lane has work at every step there), and the column histogram is added to a
 // global one once at the end (few work-groups: same-address global atomics are what costs here).
 // k_quant_hist has counted the nonzeros of every tile (blk_nnz) and of every group of tiles_per_grp
 // tiles (grp_nnz); the place of the work-group's first tile in v and c is the sum over the groups
 // and then the tiles before it, and every further tile follows the one before.
 // A lane takes 16 consecutive symbols as four words, derives the mask of its nonzero ones with a few word
 // operations and then visits only the set bits (about a third of the symbols of a post-ReLU tensor; a wave
-// runs as many steps as its fullest lane has nonzeros, nine or ten of 16).  Row ends come from the mask
+// runs as many steps as its fullest lane has nonzeros, nine or ten of 16; the step is kept to a dozen vector
+// instructions, which is what bounds the walk).  Row ends come from the mask
 // afterwards: symbol p ends a row when the lane's first column plus p + 1 is a multiple of K.
 // SHORT_ROWS (few columns): eight counters per column, see below.
 template <bool LDS_HIST, bool SHORT_ROWS = false>
@@ -116,17 +118,11 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
   __shared__ uint32_t sh[kWG / 64];
   __shared__ uint64_t sh64[kWG / 64];
   __shared__ uint32_t s_vc[kCsrTile];  // value | column << 8 of the tile's nonzeros, in order (one LDS write each)
-  // The column histogram in its plain layout.  A lane holds 16 consecutive symbols, so the first columns of a
-  // wave's lanes are 16 apart, but a lane's j-th nonzero sits at a different place in each lane: the low bits of
-  // the columns met at one step are spread as they are, and a permutation of the slots (which an earlier walk
-  // over all 16 positions in lockstep needed) only costs two instructions per nonzero.
-  auto slot_of = [](uint32_t j) { return j; };
   if (LDS_HIST) {
     for (uint32_t a = threadIdx.x; a < ((A + 15u) & ~15u); a += kWG) hist[a] = 0;
   }
   // few columns (the host selects SHORT_ROWS for K <= 32 with 8 K <= A, so the counters fit): eight counters per
-  // column, one per lane residue and K slots apart - when K divides 16 every lane of a wave meets the same column
-  // at the same step, and for other small K few distinct ones
+  // column, one per lane residue and K slots apart - a wave's 64 consecutive nonzeros meet only K distinct columns
   const uint32_t rep_off = SHORT_ROWS ? (threadIdx.x & 7u) * K : 0u;
   const uint32_t t0 = blockIdx.x * tiles_per_wg;  // < n_tiles by the size of the grid
   const uint32_t t1 = t0 + tiles_per_wg < n_tiles ? t0 + tiles_per_wg : n_tiles;
@@ -222,7 +218,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
       if (threadIdx.x < kCsrTile / K && row < N) {
         const uint32_t rj = s_rowend[threadIdx.x] - (threadIdx.x ? s_rowend[threadIdx.x - 1] : 0u);
         r[row] = (uint16_t)rj;
-        atomicAdd(&hist[slot_of(rj)], 1u);  // the same alphabet as the columns: one histogram for all of D
+        atomicAdd(&hist[rj], 1u);  // the same alphabet as the columns: one histogram for all of D
       }
     }
     // the tile's nonzeros to their place, and their columns into the histogram: here every lane has work at
@@ -231,7 +227,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
       const uint32_t vc = s_vc[i], col = vc >> 8;
       v[base + i] = (uint8_t)vc;
       c[base + i] = (uint16_t)col;
-      if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : slot_of(col)], 1u);
+      if (LDS_HIST) atomicAdd(&hist[SHORT_ROWS ? col + rep_off : col], 1u);
       else atomicAdd(&cnt[col], 1u);
     }
     base += tot;
@@ -272,7 +268,7 @@ __global__ __launch_bounds__(kWG) void k_csr_compact(const uint8_t *sym, uint32_
 #pragma unroll
         for (uint32_t k = 0; k < 8; k++) t += hist[a + k * K];
       } else {
-        t = hist[slot_of(a)];
+        t = hist[a];
       }
       if (t) atomicAdd(&dst[a], t);
     }

@@ -439,6 +439,38 @@ def test_full_size_configs_whole_container(label, name, over):
     assert np.array_equal(sym.cpu().numpy(), sym_ref)
 
 
+@pytest.mark.parametrize("N,K,Q,M,density", [
+    (5_600_001, 3, 8, 12, 0.30),     # K below 16, not a divisor of 16: rows that straddle lanes; 4096-row tiles
+    (1_400_003, 12, 8, 12, 0.45),
+    (168_011, 100, 6, 13, 0.30),     # K >= 16 that does not divide the tile: row ends through memory
+    (50_503, 333, 8, 13, 0.15),      # alphabet of K + 1 symbols
+    (3_407, 5000, 8, 14, 0.05),      # a few rows per tile
+])
+def test_large_csr_odd_shapes(N, K, Q, M, density):
+    """Tensors above 16.7 M elements (where the expand kernel sizes its tiles by the load of the fullest compute
+    unit, and every kernel runs in the launch shape of the large configurations) with row and column counts that
+    divide nothing: container, decoded symbols and dequantised values against the oracle."""
+    n = N * K
+    g = torch.Generator().manual_seed(N % 1000 + K)
+    x = torch.rand(n, generator=g)
+    x = torch.where(x < density, x + 0.01, torch.zeros(()))
+    p = B.make_params(Q, M, N, K, B.MODE_CSR, 1024, 80 * 1024, B.F32)
+    print(f"[case] large CSR N={N} K={K} Q={Q} M={M} n={n}", flush=True)
+    ref, sym_ref = oracle.compress(x.numpy(), _oparams(p))
+    codec = B.Codec(p, n)
+    nbytes = codec.compress(x.cuda())
+    assert nbytes == len(ref)
+    assert np.array_equal(codec.stream[:nbytes].cpu().numpy(), np.frombuffer(ref, np.uint8))
+    hdr = codec.header(nbytes)
+    sym = torch.empty(n, dtype=torch.uint8, device="cuda")
+    codec.decode(nbytes, hdr, sym)
+    assert np.array_equal(sym.cpu().numpy(), sym_ref)
+    out = torch.empty(n, dtype=torch.float32, device="cuda")
+    codec.decompress(nbytes, hdr, out)
+    qi = oracle.qinfo_from_minmax(hdr.x_min, hdr.x_max, Q)
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), oracle.dequantize(sym_ref, qi, oracle.F32).view(np.uint32))
+
+
 @pytest.mark.parametrize("name,over", [("c5a", {}), ("c2", dict(mode=0, chunk_syms=100352)), ("c4", dict(chunk_syms=18432))])
 def test_full_size_dense_configs_repeated(name, over):
     """The dense encoder's three ways of sharing a compute unit among its work-groups (wave priorities in turn:
